@@ -1,0 +1,233 @@
+"""Float64 CPU oracle for the LoRDO per-matrix optimizer path.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+HIP library must compute; it is imported by tests/, by the smoke check and by
+the benchmark's cpu_baseline leg and by nothing else.  It shares no code with
+the HIP path and never sees a value produced by it, except where a test hands
+it a basis on purpose (teacher forcing of the sign/rotation-ambiguous basis).
+
+Every function is the paper's formula written out with numpy in float64, one
+statement per line of the formula, no blocking, fusion or reordering.  Library
+primitives used as steps: `@` (matmul), `numpy.linalg.qr`, `numpy.linalg.svd`.
+
+Notation is the paper's: W in R^{p x q} (weights x), Q in R^{p x r} (projection,
+orthonormal columns), g = Q^T G in R^{r x q} (low-rank gradient), u, v in
+R^{r x q} (first and second moment), E in R^{p x q} (error buffer), t (count of
+local steps taken so far), Delta (pseudo-gradient), b (outer momentum).
+
+Readings of points the paper leaves open (each is stated again at its use):
+  * bias correction (omitted "for ease of notation" in Alg. 1 and 2 but present
+    in Sec. 2 and in the second-moment rotation) is ON by default:
+    u_hat = u / (1 - beta1^t), v_hat = v / (1 - beta2^t), t never reset;
+  * the squares in the second-moment rotation (Alg. 1, "rotate the second
+    moment locally") are elementwise;
+  * pseudo-gradient sign follows App. A.1 / A.2: Delta = anchor - x and the
+    outer step is x <- anchor - eta_s * step(Delta);
+  * Nesterov outer optimizer (App. D.4, D.5 name it, give no formula):
+    b <- mu b + Delta ; x <- anchor - eta_s (Delta + mu b);
+  * mu(z) of the full-rank QHM term (Sec. 3.2) is the mean over the rank index,
+    one scale per column.
+
+Parity pins live in tests/test_oracle_*.py.  Unpinned: nothing in the default
+path; the full-rank QHM form is pinned only by its reductions (omega = 1, and
+r = p with Q = I) -- "parity unpinned" beyond those for that optional variant.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+F64 = np.float64
+
+
+# ----------------------------------------------------------------------------
+# hyper-parameters (Alg. 1, "Require")
+# ----------------------------------------------------------------------------
+@dataclass
+class Hyper:
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    bias_correction: bool = True
+    qhm_mode: str = "none"          # "none" | "low" | "full"   (Alg. 1, three cases of the update)
+    omega: float = 1.0
+    error_feedback: bool = False    # Alg. 1, error-feedback lines
+    outer_lr: float = 1.0           # OuterOpt: averaging by default (Alg. 1, Require)
+    outer_momentum: float = 0.0
+    outer_nesterov: bool = False
+    power_iters: int = 2
+
+
+@dataclass
+class MatrixState:
+    """Optimizer state of one weight matrix."""
+    Q: np.ndarray                   # p x r
+    u: np.ndarray                   # r x q
+    v: np.ndarray                   # r x q
+    anchor: np.ndarray              # p x q : x_{t-K_x}
+    E: np.ndarray | None = None     # p x q
+    b: np.ndarray | None = None     # p x q
+    t: int = 0
+    last_g: np.ndarray | None = field(default=None, repr=False)
+    last_N: np.ndarray | None = field(default=None, repr=False)
+
+
+def identity_projection(p: int, r: int) -> np.ndarray:
+    """Q_0 = first r columns of the identity (Alg. 2, Require)."""
+    Q = np.zeros((p, r), dtype=F64)
+    Q[np.arange(r), np.arange(r)] = 1.0
+    return Q
+
+
+def init_state(W0: np.ndarray, r: int, Q0: np.ndarray | None = None) -> MatrixState:
+    """u_{-1} = v_{-1} = 0, E_{-1} = 0 (Alg. 1, Require); anchor = x_0; b_0 = 0."""
+    W0 = np.asarray(W0, dtype=F64)
+    p, q = W0.shape
+    Q = identity_projection(p, r) if Q0 is None else np.array(Q0, dtype=F64)
+    assert Q.shape == (p, r)
+    return MatrixState(Q=Q, u=np.zeros((r, q)), v=np.zeros((r, q)), anchor=W0.copy(),
+                       E=np.zeros((p, q)), b=np.zeros((p, q)), t=0)
+
+
+# ----------------------------------------------------------------------------
+# local step (Sec. 2, low-rank update equations; Alg. 1 inner loop)
+# ----------------------------------------------------------------------------
+def project_down(Q: np.ndarray, A: np.ndarray) -> np.ndarray:
+    """g = Q^T A, r x q (Sec. 2; Alg. 1 low-rank gradient signal)."""
+    return Q.T @ A
+
+
+def update_moments(u, v, g, beta1, beta2):
+    """u <- beta1 u + (1-beta1) g ; v <- beta2 v + (1-beta2) g*g (Sec. 2; Alg. 1)."""
+    u_new = beta1 * u + (1.0 - beta1) * g
+    v_new = beta2 * v + (1.0 - beta2) * (g * g)
+    return u_new, v_new
+
+
+def bias_factors(t: int, hp: Hyper):
+    """c1 = 1 - beta1^t, c2 = 1 - beta2^t; both 1 when bias correction is off."""
+    if not hp.bias_correction:
+        return 1.0, 1.0
+    return 1.0 - hp.beta1 ** t, 1.0 - hp.beta2 ** t
+
+
+def low_rank_direction(u, v, g, t: int, hp: Hyper) -> np.ndarray:
+    """Bracketed r x q term of the update (Alg. 1, cases "No QHM" and "Low-Rank QHM";
+    the full-rank case uses the "No QHM" bracket).  eps sits outside the root (Sec. 2)."""
+    c1, c2 = bias_factors(t, hp)
+    u_hat = u / c1
+    v_hat = v / c2
+    denom = np.sqrt(v_hat) + hp.eps
+    if hp.qhm_mode == "low":
+        return (hp.omega * u_hat + (1.0 - hp.omega) * g) / denom
+    return u_hat / denom
+
+
+def project_up(Q: np.ndarray, N: np.ndarray) -> np.ndarray:
+    """Q N, p x q (Sec. 2; Alg. 1 parameter update)."""
+    return Q @ N
+
+
+def local_step(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyper,
+               grad_scale: float = 1.0) -> np.ndarray:
+    """One local step of Alg. 1 for one matrix.  Returns the new W; updates st."""
+    W = np.asarray(W, dtype=F64)
+    G_hat = grad_scale * np.asarray(G, dtype=F64)      # clipped gradient: caller's scale
+    st.t += 1
+    A = G_hat + st.E if hp.error_feedback else G_hat
+    g = project_down(st.Q, A)
+    if hp.error_feedback:
+        st.E = A - project_up(st.Q, g)                 # E_t = G + E_{t-1} - Q g
+    st.u, st.v = update_moments(st.u, st.v, g, hp.beta1, hp.beta2)
+    N = low_rank_direction(st.u, st.v, g, st.t, hp)
+    st.last_g, st.last_N = g, N
+    if hp.qhm_mode == "full":
+        _, c2 = bias_factors(st.t, hp)
+        col_scale = np.mean(np.sqrt(st.v / c2) + hp.eps, axis=0)      # mu(.) over the rank index
+        step = (1.0 - hp.omega) * (G_hat / col_scale[None, :]) + hp.omega * project_up(st.Q, N)
+    else:
+        step = project_up(st.Q, N)
+    return W - lr * step
+
+
+# ----------------------------------------------------------------------------
+# subspace refresh (Sec. 2 "ComputeProjection"; Alg. 1 sync branch)
+# ----------------------------------------------------------------------------
+def svd_projection(A: np.ndarray, r: int) -> np.ndarray:
+    """The paper's default: U, S, V = SVD(A); Q = U[:, :r] (Sec. 2)."""
+    U, _, _ = np.linalg.svd(np.asarray(A, dtype=F64), full_matrices=False)
+    return U[:, :r]
+
+
+def orth(Y: np.ndarray) -> np.ndarray:
+    """Thin QR (Householder), columns signed so that diag(R) > 0."""
+    Qf, R = np.linalg.qr(Y)
+    s = np.sign(np.diag(R))
+    s[s == 0] = 1.0
+    return Qf * s[None, :]
+
+
+def range_finder(A: np.ndarray, Omega: np.ndarray, power_iters: int) -> np.ndarray:
+    """Block power iteration with a Gaussian start, orthonormalised after every product:
+    Y = orth(A Omega); repeat: Z = orth(A^T Y); Y = orth(A Z)."""
+    A = np.asarray(A, dtype=F64)
+    Y = orth(A @ np.asarray(Omega, dtype=F64))
+    for _ in range(power_iters):
+        Z = orth(A.T @ Y)
+        Y = orth(A @ Z)
+    return Y
+
+
+def rotate_moments(Q_new, Q_old, u, v, t: int, hp: Hyper):
+    """Alg. 1, "rotate the first / second moment locally" (same lines in Alg. 2):
+    R = Q_new^T Q_old;  u <- R u;
+    v <- (1 - beta2^t) | (R o R)(v_hat - u_hat o u_hat) + (R u_hat) o (R u_hat) |."""
+    R = Q_new.T @ Q_old
+    c1, c2 = bias_factors(t, hp)
+    u_hat = u / c1
+    v_hat = v / c2
+    u_new = R @ u
+    Ru = R @ u_hat
+    v_new = c2 * np.abs((R * R) @ (v_hat - u_hat * u_hat) + Ru * Ru)
+    return u_new, v_new
+
+
+def refresh_subspace(st: MatrixState, A_src: np.ndarray, Omega: np.ndarray, hp: Hyper,
+                     Q_forced: np.ndarray | None = None) -> np.ndarray:
+    """New projection from A_src, then rotation of both moments into it.
+    `Q_forced` replaces the computed basis (tests use it to teacher-force the
+    basis the other implementation found; the rotation is basis dependent)."""
+    Q_new = range_finder(A_src, Omega, hp.power_iters) if Q_forced is None \
+        else np.asarray(Q_forced, dtype=F64)
+    if st.t > 0:                                        # before any step both moments are zero
+        st.u, st.v = rotate_moments(Q_new, st.Q, st.u, st.v, st.t, hp)
+    st.Q = Q_new
+    return Q_new
+
+
+def mssv(Q_new: np.ndarray, Q_old: np.ndarray) -> float:
+    """Mean squared singular value of R = Q_new^T Q_old (Sec. 5.1, Metrics):
+    (1/r) sum sigma_i^2 = ||R||_F^2 / r."""
+    R = Q_new.T @ Q_old
+    return float(np.sum(R * R) / R.shape[0])
+
+
+# ----------------------------------------------------------------------------
+# outer step (Alg. 1 sync branch; App. A.1, A.2; App. D.4, D.5)
+# ----------------------------------------------------------------------------
+def pseudo_gradient(st: MatrixState, W: np.ndarray) -> np.ndarray:
+    """Delta^m = x_{t-K_x} - x_t  (App. A.1 sign convention)."""
+    return st.anchor - np.asarray(W, dtype=F64)
+
+
+def outer_step(st: MatrixState, avg_delta: np.ndarray, hp: Hyper) -> np.ndarray:
+    """x <- OuterOpt(Delta, x_{t-K_x}).  Plain: x = anchor - eta_s Delta (eta_s = 1 is
+    averaging).  With momentum mu: b <- mu b + Delta; step = Delta + mu b (Nesterov)
+    or b (heavy ball).  The new x becomes the anchor of the next window."""
+    D = np.asarray(avg_delta, dtype=F64)
+    st.b = hp.outer_momentum * st.b + D
+    step = D + hp.outer_momentum * st.b if hp.outer_nesterov else st.b
+    W_new = st.anchor - hp.outer_lr * step
+    st.anchor = W_new.copy()
+    return W_new

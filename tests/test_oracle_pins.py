@@ -1,0 +1,500 @@
+"""Pins of the float64 oracle to things other than itself: library optimizers the
+method reduces to, closed forms, invariants, brute force on tiny inputs and a
+library SVD.  Each test names the passage of the paper that fixes the value."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lordo_oracle as orc
+from paper_2602_04396_amd import synth
+
+TOL = 1e-12
+
+
+def rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def rng_of(i):
+    return np.random.default_rng(synth.seed_for(0, i))
+
+
+# ---------------------------------------------------------------------------
+# local step
+# ---------------------------------------------------------------------------
+def test_reduces_to_library_adam_when_Q_is_identity():
+    """Sec. 2: with r = p and Q = I the low-rank update is the full-rank Adam update.
+    Library routine: torch.optim.Adam in float64 (eps outside the root, bias corrected)."""
+    rng = rng_of(1)
+    p, q = 12, 9
+    W0 = rng.standard_normal((p, q))
+    hp = orc.Hyper(beta1=0.9, beta2=0.999, eps=1e-8)
+    st = orc.init_state(W0, p, np.eye(p))
+    Wt = torch.tensor(W0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([Wt], lr=1e-3, betas=(0.9, 0.999), eps=1e-8)
+    W = W0.copy()
+    for t in range(7):
+        G = rng.standard_normal((p, q))
+        W = orc.local_step(st, W, G, 1e-3, hp)
+        Wt.grad = torch.tensor(G, dtype=torch.float64)
+        opt.step()
+    assert rel(W, Wt.detach().numpy()) < 1e-13
+    s = opt.state[Wt]
+    assert rel(st.u, s["exp_avg"].numpy()) < 1e-13
+    assert rel(st.v, s["exp_avg_sq"].numpy()) < 1e-13
+
+
+def test_projections_against_triple_loops():
+    """Sec. 2: g = Q^T G is r x q with g[i][j] = sum_k Q[k][i] G[k][j];
+    Q N is p x q with (QN)[k][j] = sum_i Q[k][i] N[i][j].  Brute force, tiny."""
+    rng = rng_of(2)
+    p, q, r = 5, 4, 3
+    Q = rng.standard_normal((p, r))
+    G = rng.standard_normal((p, q))
+    N = rng.standard_normal((r, q))
+    g = np.zeros((r, q))
+    for i in range(r):
+        for j in range(q):
+            for k in range(p):
+                g[i, j] += Q[k, i] * G[k, j]
+    up = np.zeros((p, q))
+    for k in range(p):
+        for j in range(q):
+            for i in range(r):
+                up[k, j] += Q[k, i] * N[i, j]
+    assert rel(orc.project_down(Q, G), g) < 1e-14
+    assert rel(orc.project_up(Q, N), up) < 1e-14
+
+
+def test_first_step_closed_form():
+    """Sec. 2 with bias correction: from zero state u_hat = g and v_hat = g*g, so the
+    first update is W_1 = W_0 - eta Q [g / (|g| + eps)]."""
+    rng = rng_of(3)
+    p, q, r = 20, 14, 5
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    G = rng.standard_normal((p, q))
+    hp = orc.Hyper()
+    st = orc.init_state(W0, r, Q)
+    W1 = orc.local_step(st, W0, G, 0.01, hp)
+    g = Q.T @ G
+    expect = W0 - 0.01 * Q @ (g / (np.abs(g) + 1e-8))
+    assert rel(W1, expect) < 1e-13
+
+
+def test_constant_gradient_closed_form_and_rank():
+    """A constant gradient keeps u_hat = g and v_hat = g*g at every t, so after T steps
+    W_T = W_0 - (sum eta_t) Q [g/(|g|+eps)]; and with a fixed Q the change W_T - W_0 has
+    rank at most r (App. A.2, pseudo-gradient with a fixed projection)."""
+    rng = rng_of(4)
+    p, q, r = 24, 18, 4
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    G = rng.standard_normal((p, q))
+    hp = orc.Hyper()
+    st = orc.init_state(W0, r, Q)
+    W = W0.copy()
+    etas = [1e-3 * (1 + 0.1 * k) for k in range(10)]
+    for eta in etas:
+        W = orc.local_step(st, W, G, eta, hp)
+    g = Q.T @ G
+    expect = W0 - sum(etas) * Q @ (g / (np.abs(g) + 1e-8))
+    assert rel(W - W0, expect - W0) < 1e-9
+    sv = np.linalg.svd(W - W0, compute_uv=False)
+    assert sv[r] < 1e-12 * sv[0]
+
+
+def test_varying_gradient_change_has_rank_at_most_r():
+    rng = rng_of(5)
+    p, q, r = 16, 20, 3
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    st = orc.init_state(W0, r, Q)
+    W = W0.copy()
+    for _ in range(6):
+        W = orc.local_step(st, W, rng.standard_normal((p, q)), 1e-2, orc.Hyper())
+    sv = np.linalg.svd(W - W0, compute_uv=False)
+    assert sv[r] < 1e-12 * sv[0] and sv[r - 1] > 1e-6 * sv[0]
+
+
+def test_no_bias_correction_flag():
+    """Alg. 1 as printed (bias correction omitted): first step is
+    u = (1-b1) g, v = (1-b2) g^2, N = u / (sqrt v + eps)."""
+    rng = rng_of(6)
+    p, q, r = 10, 8, 4
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    G = rng.standard_normal((p, q))
+    hp = orc.Hyper(bias_correction=False)
+    st = orc.init_state(W0, r, Q)
+    W1 = orc.local_step(st, W0, G, 0.5, hp)
+    g = Q.T @ G
+    N = (0.1 * g) / (np.sqrt(0.001 * g * g) + 1e-8)
+    assert rel(W1, W0 - 0.5 * Q @ N) < 1e-13
+
+
+def test_grad_scale_is_a_plain_prefactor():
+    rng = rng_of(7)
+    p, q, r = 10, 8, 4
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    G = rng.standard_normal((p, q))
+    a = orc.init_state(W0, r, Q)
+    b = orc.init_state(W0, r, Q)
+    Wa = orc.local_step(a, W0, G, 0.1, orc.Hyper(), grad_scale=0.25)
+    Wb = orc.local_step(b, W0, 0.25 * G, 0.1, orc.Hyper())
+    assert rel(Wa, Wb) < 1e-14 and rel(a.v, b.v) < 1e-14
+
+
+def test_exact_reconstruction_when_rank_le_r():
+    """rank(G) <= r and range(G) inside span(Q)  =>  Q Q^T G = G."""
+    rng = rng_of(8)
+    p, q, r = 30, 22, 6
+    G = rng.standard_normal((p, r)) @ rng.standard_normal((r, q))
+    Q = orc.range_finder(G, rng.standard_normal((q, r)), 1)
+    assert rel(orc.project_up(Q, orc.project_down(Q, G)), G) < 1e-12
+
+
+# ---------------------------------------------------------------------------
+# optional variants: error feedback and quasi-hyperbolic momentum
+# ---------------------------------------------------------------------------
+def test_error_feedback_telescopes_and_is_orthogonal_to_Q():
+    """Alg. 1 error-feedback lines: E_t = G_t + E_{t-1} - Q g_t with g_t = Q^T(G_t + E_{t-1})
+    gives sum_t G_t = sum_t Q g_t + E_T and, for orthonormal Q, Q^T E_t = 0."""
+    rng = rng_of(9)
+    p, q, r = 18, 12, 4
+    Q = synth.orthonormal(rng, p, r)
+    W = rng.standard_normal((p, q))
+    hp = orc.Hyper(error_feedback=True)
+    st = orc.init_state(W, r, Q)
+    sumG = np.zeros((p, q))
+    sumQg = np.zeros((p, q))
+    for _ in range(5):
+        G = rng.standard_normal((p, q))
+        W = orc.local_step(st, W, G, 1e-3, hp)
+        sumG += G
+        sumQg += Q @ st.last_g
+        assert np.abs(Q.T @ st.E).max() < 1e-13
+    assert rel(sumQg + st.E, sumG) < 1e-13
+
+
+@pytest.mark.parametrize("mode", ["low", "full"])
+def test_qhm_omega_one_is_no_qhm(mode):
+    """Alg. 1: at omega = 1 both QHM cases are the "No QHM" case."""
+    rng = rng_of(10)
+    p, q, r = 14, 10, 3
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    a = orc.init_state(W0, r, Q)
+    b = orc.init_state(W0, r, Q)
+    Wa, Wb = W0.copy(), W0.copy()
+    for _ in range(4):
+        G = rng.standard_normal((p, q))
+        Wa = orc.local_step(a, Wa, G, 1e-2, orc.Hyper())
+        Wb = orc.local_step(b, Wb, G, 1e-2, orc.Hyper(qhm_mode=mode, omega=1.0))
+    assert rel(Wa, Wb) < 1e-14
+
+
+def test_full_rank_qhm_omega_zero_is_column_scaled_sgd():
+    """Sec. 3.2: at omega = 0 the full-rank form is G_hat / mu(sqrt(v_hat) + eps), with mu the mean
+    over the r rank indices of a column; at step one v_hat = g*g, so the scale of column j
+    is mean_i |g_ij| + eps."""
+    rng = rng_of(11)
+    p, q, r = 9, 7, 3
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    G = rng.standard_normal((p, q))
+    st = orc.init_state(W0, r, Q)
+    W1 = orc.local_step(st, W0, G, 0.1, orc.Hyper(qhm_mode="full", omega=0.0))
+    g = Q.T @ G
+    scale = np.abs(g).mean(axis=0) + 1e-8
+    assert rel(W1, W0 - 0.1 * G / scale[None, :]) < 1e-13
+
+
+def test_low_rank_qhm_stays_in_span_full_rank_qhm_leaves_it():
+    """App. A.4: the low-rank QHM update stays in span(Q); the full-rank one does not."""
+    rng = rng_of(12)
+    p, q, r = 16, 12, 3
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    G = rng.standard_normal((p, q))
+    P_perp = np.eye(p) - Q @ Q.T
+    lo = orc.local_step(orc.init_state(W0, r, Q), W0, G, 0.1, orc.Hyper(qhm_mode="low", omega=0.7))
+    fu = orc.local_step(orc.init_state(W0, r, Q), W0, G, 0.1, orc.Hyper(qhm_mode="full", omega=0.7))
+    assert np.linalg.norm(P_perp @ (lo - W0)) < 1e-13
+    assert np.linalg.norm(P_perp @ (fu - W0)) > 1e-3
+
+
+# ---------------------------------------------------------------------------
+# subspace refresh
+# ---------------------------------------------------------------------------
+def test_orth_is_orthonormal_same_span_positive_diagonal():
+    rng = rng_of(13)
+    Y = rng.standard_normal((40, 7)) @ np.diag(np.logspace(0, -3, 7))
+    Qo = orc.orth(Y)
+    assert np.abs(Qo.T @ Qo - np.eye(7)).max() < 1e-13
+    R = Qo.T @ Y
+    assert np.abs(np.tril(R, -1)).max() < 1e-12 * np.abs(R).max()
+    assert (np.diag(R) > 0).all()
+    assert rel(Qo @ R, Y) < 1e-13
+
+
+def test_svd_projection_is_top_left_singular_subspace():
+    """Sec. 2 default ComputeProjection: Q = U[:, :r].  Checked through the variational
+    property it must have: ||Q^T A||_F^2 = sum of the r largest eigenvalues of A A^T
+    (a different library routine: symmetric eigensolver)."""
+    rng = rng_of(14)
+    A = rng.standard_normal((15, 11))
+    r = 4
+    Q = orc.svd_projection(A, r)
+    assert np.abs(Q.T @ Q - np.eye(r)).max() < 1e-13
+    ev = np.sort(np.linalg.eigvalsh(A @ A.T))[::-1]
+    assert abs(np.sum((Q.T @ A) ** 2) - ev[:r].sum()) < 1e-10
+    # and no other r-dimensional subspace captures more (random trials)
+    for _ in range(20):
+        B = synth.orthonormal(rng, 15, r)
+        assert np.sum((B.T @ A) ** 2) <= ev[:r].sum() + 1e-10
+
+
+def _c1_source(seed_idx=0):
+    rng = np.random.default_rng(synth.seed_for(1, seed_idx))
+    S = synth.c1_signal(rng)
+    G = synth.c1_gradient(S, rng).astype(np.float64)
+    Om = synth.omega(rng, 256, 16).astype(np.float64)
+    return S, G, Om
+
+
+def test_range_finder_converges_to_svd_subspace_on_config1():
+    """Config 1 (rank-8 signal, sigma 10..1, noise 0.01, r = 16): the range finder's span must
+    close in on the top-8 left singular subspace of G, the residual shrinking per power iteration
+    at least as fast as the textbook rate of block power iteration, (sigma_9 / sigma_8)^2."""
+    _, G, Om = _c1_source()
+    U, sv, _ = np.linalg.svd(G, full_matrices=False)
+    U8 = U[:, :8]
+    rate = (sv[8] / sv[7]) ** 2
+    res = []
+    for it in range(5):
+        Q = orc.range_finder(G, Om, it)
+        assert np.abs(Q.T @ Q - np.eye(16)).max() < 1e-12
+        res.append(np.linalg.norm(U8 - Q @ (Q.T @ U8)))
+    for k in range(4):
+        assert res[k + 1] < 1.05 * rate * res[k]
+    assert res[2] < 1e-2 and res[4] < 1e-4
+
+
+def test_range_finder_reaches_svd_projector_with_a_gap():
+    """With a spectral gap at r, enough power iterations give the projector U_r U_r^T
+    of the paper's default SVD projection."""
+    rng = rng_of(15)
+    p, q, r = 48, 40, 5
+    A = (synth.orthonormal(rng, p, p)[:, :q] * np.concatenate([np.linspace(9, 5, r), 0.5 * rng.random(q - r)])) \
+        @ synth.orthonormal(rng, q, q).T
+    Q = orc.range_finder(A, rng.standard_normal((q, r)), 12)
+    Qs = orc.svd_projection(A, r)
+    assert np.linalg.norm(Q @ Q.T - Qs @ Qs.T) < 1e-9
+
+
+def test_range_finder_rank_deficient_source_still_reconstructs():
+    """rank(A) < r: the basis is completed arbitrarily; only Q^T Q = I and Q Q^T A = A are fixed."""
+    rng = rng_of(16)
+    p, q, r = 30, 25, 8
+    A = rng.standard_normal((p, 3)) @ rng.standard_normal((3, q))
+    Q = orc.range_finder(A, rng.standard_normal((q, r)), 1)
+    assert np.abs(Q.T @ Q - np.eye(r)).max() < 1e-12
+    assert rel(Q @ (Q.T @ A), A) < 1e-12
+
+
+# ---------------------------------------------------------------------------
+# moment rotation
+# ---------------------------------------------------------------------------
+def _moments(rng, r, q, t, hp):
+    """Moments as t steps of EMA on random low-rank gradients would leave them."""
+    u = np.zeros((r, q))
+    v = np.zeros((r, q))
+    for _ in range(t):
+        g = rng.standard_normal((r, q))
+        u, v = orc.update_moments(u, v, g, hp.beta1, hp.beta2)
+    return u, v
+
+
+def test_rotation_identity_when_basis_unchanged():
+    """Alg. 1 rotation lines with Q_new = Q_old: R = I, u unchanged and
+    v = c2 |v_hat - u_hat^2 + u_hat^2| = v."""
+    rng = rng_of(17)
+    hp = orc.Hyper()
+    Q = synth.orthonormal(rng, 20, 5)
+    u, v = _moments(rng, 5, 9, 6, hp)
+    un, vn = orc.rotate_moments(Q, Q, u, v, 6, hp)
+    assert rel(un, u) < TOL and rel(vn, v) < TOL
+
+
+def test_rotation_permutation_and_sign_flip():
+    """Q_new = Q_old Pi permutes the rows of u and v; Q_new = Q_old diag(+-1) flips the
+    signs of rows of u and leaves v alone."""
+    rng = rng_of(18)
+    hp = orc.Hyper()
+    r, q = 5, 8
+    Q = synth.orthonormal(rng, 17, r)
+    u, v = _moments(rng, r, q, 4, hp)
+    perm = np.array([2, 0, 4, 1, 3])
+    un, vn = orc.rotate_moments(Q[:, perm], Q, u, v, 4, hp)
+    assert rel(un, u[perm]) < TOL and rel(vn, v[perm]) < TOL
+    s = np.array([1, -1, -1, 1, -1.0])
+    un, vn = orc.rotate_moments(Q * s, Q, u, v, 4, hp)
+    assert rel(un, u * s[:, None]) < TOL and rel(vn, v) < TOL
+
+
+def test_rotation_within_span_keeps_full_space_momentum():
+    """Q_new = Q_old O with O orthogonal: Q_new u_new = Q_old u (the momentum seen in the
+    full space does not move)."""
+    rng = rng_of(19)
+    hp = orc.Hyper()
+    r, q = 6, 7
+    Q = synth.orthonormal(rng, 25, r)
+    O = synth.orthonormal(rng, r, r)
+    u, v = _moments(rng, r, q, 3, hp)
+    un, vn = orc.rotate_moments(Q @ O, Q, u, v, 3, hp)
+    assert rel((Q @ O) @ un, Q @ u) < TOL
+    assert (vn >= 0).all()
+
+
+def test_rotation_to_orthogonal_subspace_clears_moments():
+    rng = rng_of(20)
+    hp = orc.Hyper()
+    B = synth.orthonormal(rng, 30, 8)
+    u, v = _moments(rng, 4, 6, 5, hp)
+    un, vn = orc.rotate_moments(B[:, 4:], B[:, :4], u, v, 5, hp)
+    assert np.abs(un).max() < 1e-14 and np.abs(vn).max() < 1e-14
+
+
+def test_second_moment_rotation_hadamard_reading_brute_force():
+    """Reading of the squares in the second-moment rotation as elementwise: for one column,
+    new_v_i = c2 | sum_j R_ij^2 (v_hat_j - u_hat_j^2) + (sum_j R_ij u_hat_j)^2 |, i.e. a
+    variance pushed through the linear map R plus the squared rotated mean."""
+    rng = rng_of(21)
+    hp = orc.Hyper()
+    r, q, t = 4, 3, 5
+    Qo = synth.orthonormal(rng, 12, r)
+    Qn = synth.orthonormal(rng, 12, r)
+    u, v = _moments(rng, r, q, t, hp)
+    un, vn = orc.rotate_moments(Qn, Qo, u, v, t, hp)
+    c1, c2 = 1 - 0.9 ** t, 1 - 0.999 ** t
+    R = np.zeros((r, r))
+    for i in range(r):
+        for j in range(r):
+            for k in range(12):
+                R[i, j] += Qn[k, i] * Qo[k, j]
+    for col in range(q):
+        for i in range(r):
+            var = sum(R[i, j] ** 2 * (v[j, col] / c2 - (u[j, col] / c1) ** 2) for j in range(r))
+            mean = sum(R[i, j] * u[j, col] / c1 for j in range(r))
+            assert abs(vn[i, col] - c2 * abs(var + mean ** 2)) < 1e-14
+            assert abs(un[i, col] - sum(R[i, j] * u[j, col] for j in range(r))) < 1e-14
+
+
+def test_refresh_before_first_step_keeps_zero_moments():
+    _, G, Om = _c1_source()
+    st = orc.init_state(np.zeros((256, 256)), 16)
+    orc.refresh_subspace(st, G, Om, orc.Hyper())
+    assert st.t == 0 and not st.u.any() and not st.v.any()
+    assert np.abs(st.Q.T @ st.Q - np.eye(16)).max() < 1e-12
+
+
+def test_mssv_limits():
+    """Sec. 5.1 Metrics: same basis -> 1, orthogonal bases -> 0."""
+    rng = rng_of(22)
+    B = synth.orthonormal(rng, 20, 8)
+    assert abs(orc.mssv(B[:, :4], B[:, :4]) - 1) < 1e-13
+    assert orc.mssv(B[:, :4], B[:, 4:]) < 1e-26
+    sv = np.linalg.svd(B[:, 2:6].T @ B[:, :4], compute_uv=False)
+    assert abs(orc.mssv(B[:, 2:6], B[:, :4]) - np.mean(sv ** 2)) < 1e-13
+
+
+# ---------------------------------------------------------------------------
+# outer step
+# ---------------------------------------------------------------------------
+def test_outer_default_is_worker_average():
+    """Alg. 1: OuterOpt is averaging by default: with eta_s = 1 and no momentum the new model
+    is the mean of the workers' models."""
+    rng = rng_of(23)
+    anchor = rng.standard_normal((6, 5))
+    workers = [anchor + 0.1 * rng.standard_normal((6, 5)) for _ in range(4)]
+    st = orc.init_state(anchor, 2)
+    deltas = [orc.pseudo_gradient(st, w) for w in workers]
+    x = orc.outer_step(st, np.mean(deltas, axis=0), orc.Hyper())
+    assert rel(x, np.mean(workers, axis=0)) < 1e-14
+    assert rel(st.anchor, x) < 1e-15
+
+
+@pytest.mark.parametrize("nesterov", [True, False])
+def test_outer_momentum_matches_library_sgd(nesterov):
+    """App. D.4/D.5: Nesterov outer optimizer as in DiLoCo = SGD with (Nesterov) momentum fed the
+    pseudo-gradient.  Library routine: torch.optim.SGD in float64."""
+    rng = rng_of(24)
+    x0 = rng.standard_normal((7, 4))
+    hp = orc.Hyper(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=nesterov)
+    st = orc.init_state(x0, 2)
+    xt = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([xt], lr=0.7, momentum=0.9, nesterov=nesterov)
+    for _ in range(5):
+        D = rng.standard_normal((7, 4))
+        x = orc.outer_step(st, D, hp)
+        xt.grad = torch.tensor(D)
+        opt.step()
+        assert rel(x, xt.detach().numpy()) < 1e-13
+
+
+def test_outer_nesterov_closed_form_two_steps():
+    """From b = 0: first step is eta_s (1 + mu) Delta; a second step with the same Delta is
+    eta_s (1 + mu + mu^2) Delta."""
+    rng = rng_of(25)
+    x0 = rng.standard_normal((5, 5))
+    D = rng.standard_normal((5, 5))
+    hp = orc.Hyper(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True)
+    st = orc.init_state(x0, 2)
+    x1 = orc.outer_step(st, D, hp)
+    assert rel(x1, x0 - 0.7 * 1.9 * D) < 1e-14
+    x2 = orc.outer_step(st, D, hp)
+    assert rel(x2, x1 - 0.7 * (1 + 0.9 + 0.81) * D) < 1e-14
+
+
+def test_config1_chain_closed_form():
+    """Config 1 with a constant gradient: 10 local steps at eta = 1e-3 then one Nesterov outer step
+    (eta_s 0.7, mu 0.9) on the worker's own pseudo-gradient: W = W_0 - 0.7 * 1.9 * 1e-2 * Q N,
+    N = g / (|g| + eps)."""
+    S, G, Om = _c1_source()
+    rng = np.random.default_rng(synth.seed_for(1, 99))
+    W0 = synth.weights(rng, 256, 256).astype(np.float64)
+    hp = orc.Hyper(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=2)
+    st = orc.init_state(W0, 16)
+    orc.refresh_subspace(st, G, Om, hp)
+    W = W0.copy()
+    for _ in range(10):
+        W = orc.local_step(st, W, G, 1e-3, hp)
+    D = orc.pseudo_gradient(st, W)
+    W = orc.outer_step(st, D, hp)
+    g = st.Q.T @ G
+    expect = W0 - 0.7 * 1.9 * 1e-2 * st.Q @ (g / (np.abs(g) + 1e-8))
+    assert rel(W - W0, expect - W0) < 1e-9
+
+
+# ---------------------------------------------------------------------------
+# Sec. 3.3 communication ratios (used by the sharding note only)
+# ---------------------------------------------------------------------------
+def test_comm_ratios_golden():
+    here = os.path.dirname(__file__)
+    quoted = {}
+    with open(os.path.join(here, "golden", "comm_ratios.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, val, tol = line.split()
+                quoted[name] = (float(val), float(tol))
+    K, r, p, q = 32, 256, 2048, 2048
+    lowrank = 1.0 / ((1 + r / q) / K + 1 / K + 1 / K)
+    fullrank = 1.0 / ((1 + r / q) / K + r / (K * p) + r / (K * p))
+    val, tol = quoted["vs_lowrank_ddp"]
+    assert abs(lowrank - val) / val < tol
+    val, tol = quoted["vs_fullrank_ddp"]
+    assert abs(fullrank - val) / val < tol
