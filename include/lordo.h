@@ -1,0 +1,149 @@
+/*
+ * lordo.h -- C ABI of the MI355X (gfx950) LoRDO per-matrix optimizer library.
+ *
+ * The library runs, for a set of weight matrices W_i in R^{p_i x q_i}, the hot path of
+ * LoRDO: the low-rank local step (Sec. 2 low-rank update; Alg. 1 inner loop), the
+ * periodic subspace refresh with rotation of both moments (Sec. 2 "ComputeProjection";
+ * Alg. 1 sync branch, rotation lines) and the infrequent outer step on the
+ * pseudo-gradient (Alg. 1 sync branch; App. A.1-A.2; App. D.4-D.5).
+ *
+ * Conventions for every entry point
+ *   - All matrices are dense, row-major and contiguous: element (a, b) of a p x q matrix
+ *     is at index a*q + b.  Notation is the paper's: p rows, q columns, rank r,
+ *     projection Q (p x r), low-rank gradient g = Q^T G (r x q), moments u, v (r x q).
+ *   - "device" pointers are HIP device addresses; "host" pointers are ordinary host
+ *     memory.  Arrays of pointers (`void* const*`) are HOST arrays of length n holding
+ *     one DEVICE pointer per matrix, in the order of the shapes given to lordo_init.
+ *   - The caller owns and allocates every buffer, including the arena the library keeps
+ *     its state in; the library never allocates or frees device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
+ *     enqueue work on it and return; they do not synchronise, except lordo_init,
+ *     lordo_poll_status and lordo_destroy.  All calls on one context must be issued
+ *     on one stream, or be ordered by the caller.
+ *   - Return value: LORDO_OK or a negative LORDO_E* code; lordo_strerror gives text.
+ *     Argument and state errors are detected before anything is enqueued.  A numerical
+ *     breakdown inside a kernel (non-positive Cholesky pivot) is latched in device
+ *     memory and reported by lordo_poll_status as LORDO_ENUMERIC.
+ *   - There is no CPU fallback: without a GPU every compute call returns LORDO_EHIP.
+ */
+#ifndef LORDO_H
+#define LORDO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LORDO_OK        0
+#define LORDO_EINVAL   (-1)   /* null pointer, bad shape, r > p, unknown dtype, unsupported option */
+#define LORDO_ENOMEM   (-2)   /* arena smaller than lordo_workspace_bytes                           */
+#define LORDO_EHIP     (-3)   /* HIP runtime error (message on stderr)                               */
+#define LORDO_ESTATE   (-4)   /* call not valid in the current state                                 */
+#define LORDO_ENUMERIC (-5)   /* numerical breakdown latched by a kernel                             */
+
+#define LORDO_F32  0
+#define LORDO_BF16 1
+
+/* selectors of lordo_get_state / lordo_set_state; shapes of the plain fp32 buffers exchanged */
+#define LORDO_STATE_Q       0   /* p x r  projection                                   */
+#define LORDO_STATE_U       1   /* r x q  first moment                                 */
+#define LORDO_STATE_V       2   /* r x q  second moment                                */
+#define LORDO_STATE_ANCHOR  3   /* p x q  x_{t-K_x}, the model at the last outer step  */
+#define LORDO_STATE_MOM     4   /* p x q  outer momentum b (only if outer_momentum!=0) */
+#define LORDO_STATE_GLOW    5   /* r x q  g of the last local step (read only)         */
+#define LORDO_STATE_NUPD    6   /* r x q  bracketed update N of the last local step (read only) */
+
+typedef struct lordo_ctx lordo_ctx;
+
+/* One weight matrix: rows p, cols q, rank r; requires 1 <= r <= p (left projection). */
+typedef struct {
+  int64_t rows;
+  int64_t cols;
+  int32_t rank;
+  int32_t reserved;   /* must be 0 */
+} lordo_shape;
+
+/* Hyper-parameters (Alg. 1 "Require").  Scalars are double so that 1-beta and
+ * 1-beta^t are formed from the same decimal values a float64 reference uses. */
+typedef struct {
+  double  beta1, beta2, eps;     /* moment decay rates; eps is added outside the root (Sec. 2)        */
+  int32_t bias_correction;       /* 1: u/(1-beta1^t), v/(1-beta2^t) as in Sec. 2; 0: as Alg. 1 prints  */
+  int32_t qhm_mode;              /* 0 none.  1 (low-rank) and 2 (full-rank) are not built: LORDO_EINVAL */
+  double  omega;                 /* QHM mixing coefficient; ignored when qhm_mode == 0                  */
+  int32_t error_feedback;        /* 0.  1 is not built: LORDO_EINVAL                                    */
+  int32_t outer_nesterov;        /* with outer_momentum != 0: 1 Nesterov, 0 heavy ball                  */
+  double  outer_lr;              /* eta_s; 1.0 with outer_momentum 0 is plain averaging (Alg. 1)        */
+  double  outer_momentum;        /* mu; 0 keeps no momentum buffer                                      */
+  int32_t power_iters;           /* block power iterations of the range finder, 0..8                    */
+  int32_t orth_passes;           /* CholeskyQR passes per orthonormalisation: 2 (default if 0) or 3     */
+  int32_t grad_dtype;            /* LORDO_BF16 or LORDO_F32: element type of every G                    */
+  int32_t reserved;              /* must be 0                                                           */
+} lordo_hparams;
+
+/* Bytes of arena lordo_init needs for these shapes and hyper-parameters (host call). */
+int lordo_workspace_bytes(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp, size_t* out_bytes);
+
+/* Create a context (the north-star call "lordo_init": matrix shapes, rank, hyper-parameters).
+ *   arena        device, caller-allocated, 256-byte aligned, >= lordo_workspace_bytes; the library
+ *                keeps Q, u, v, the anchor, the outer momentum and all scratch in it until destroy.
+ *   W            host array of n device pointers to fp32 p x q weights; read once: anchor <- W.
+ * State after init: Q = first r columns of the identity (Alg. 2 "Require"), u = v = 0,
+ * b = 0, t = 0 (Alg. 1 "Require").  Synchronises `stream` before returning. */
+int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp,
+               void* arena, size_t arena_bytes, void* const* W, void* stream);
+
+/* One local step on every matrix (Sec. 2; Alg. 1 inner loop, "No QHM" case):
+ *   t <- t+1;  g = Q^T (grad_scale * G);  u <- beta1 u + (1-beta1) g;  v <- beta2 v + (1-beta2) g*g;
+ *   N = (u/c1) / (sqrt(v/c2) + eps), c_i = 1-beta_i^t (1 if bias_correction == 0);  W <- W - lr * Q N.
+ *   W   host array of n device pointers, fp32 p x q, updated in place.
+ *   G   host array of n device pointers, p x q of hp.grad_dtype, read only.
+ *   grad_scale  scalar the caller's gradient clipping produced (1 = none). */
+int lordo_local_step(lordo_ctx* ctx, void* const* W, const void* const* G,
+                     double lr, double grad_scale, void* stream);
+
+/* New projection for every matrix and rotation of both moments into it
+ * (Sec. 2 ComputeProjection, here a Gaussian-start block power iteration:
+ *  Y = orth(Src Omega); power_iters x { Z = orth(Src^T Y); Y = orth(Src Z) }; Q_new = Y, columns
+ *  signed so that the triangular factor has a positive diagonal; then, if t > 0, Alg. 1 rotation:
+ *  R = Q_new^T Q;  u <- R u;  v <- c2 | (R o R)(v/c2 - (u/c1)^2) + (R u/c1)^2 |;  finally Q <- Q_new).
+ *   Src        host array of n device pointers, p x q each, element type src_dtype
+ *              (a gradient, or an averaged pseudo-gradient); read only.  Every entry non-NULL.
+ *   Omega      host array of n device pointers, q x r fp32 Gaussian start blocks, read only. */
+int lordo_refresh_subspace(lordo_ctx* ctx, const void* const* Src, int32_t src_dtype,
+                           const void* const* Omega, void* stream);
+
+/* This worker's pseudo-gradient (App. A.1): DeltaOut_i <- anchor_i - W_i, fp32 p x q. */
+int lordo_export_pseudograd(lordo_ctx* ctx, const void* const* W, void* const* DeltaOut, void* stream);
+
+/* Outer step (Alg. 1 OuterOpt; App. A.2): with D = AvgDelta_i (the cross-worker mean, fp32 p x q)
+ * or, if AvgDelta == NULL, this worker's own anchor - W:
+ *   mu == 0:  W <- anchor - eta_s D
+ *   mu != 0:  b <- mu b + D;  W <- anchor - eta_s (D + mu b) (Nesterov) or anchor - eta_s b (heavy ball)
+ * then anchor <- W.  W is written (and read only when AvgDelta == NULL). */
+int lordo_outer_step(lordo_ctx* ctx, void* const* W, const void* const* AvgDelta, void* stream);
+
+/* Copy one state tensor of matrix `mat` to / from a plain row-major fp32 device buffer of the
+ * shape listed at the selector.  set_state(Q) expects orthonormal columns and rebuilds the packed
+ * operand copies; GLOW and NUPD cannot be set. */
+int lordo_get_state(lordo_ctx* ctx, int32_t mat, int32_t which, void* dev_dst, void* stream);
+int lordo_set_state(lordo_ctx* ctx, int32_t mat, int32_t which, const void* dev_src, void* stream);
+
+/* Count t of local steps taken (drives the bias correction); host values. */
+int lordo_get_step(lordo_ctx* ctx, int64_t* t);
+int lordo_set_step(lordo_ctx* ctx, int64_t t);
+
+/* Synchronise `stream` and return LORDO_ENUMERIC if a kernel latched a breakdown since the
+ * last poll (the latch is cleared), else LORDO_OK. */
+int lordo_poll_status(lordo_ctx* ctx, void* stream);
+
+const char* lordo_strerror(int code);
+
+/* Frees host-side bookkeeping only (the arena is the caller's).  NULL is allowed. */
+void lordo_destroy(lordo_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORDO_H */

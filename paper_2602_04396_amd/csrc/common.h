@@ -1,0 +1,121 @@
+// Shared host/device definitions of the LoRDO gfx950 library: packed layouts, per-matrix
+// device records, GEMM descriptors and the launchers each translation unit exports.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lordo {
+
+// ---------------------------------------------------------------------------------------
+// Blocked operand layout ("BL").  A logical matrix X[m][k], m < Mp, k < Kp (both padded to a
+// multiple of 32 with zeros) is stored so that the 32 x 16 operand fragment of one
+// v_mfma_f32_32x32x16_bf16 -- lane l holds X[32*mb + l%32][16*ks + 8*(l/32) + 0..7] -- is one
+// contiguous run in lane order:
+//     index(m, k) = (((m/32) * (Kp/8) + k/8) * 32 + m%32) * 8 + k%8
+// The same indexing holds the fp32 low-rank state (g, u, v) with m = column j of the weight
+// matrix and k = rank index i, so that the flat position of a state element equals the flat
+// position of its entry in the bf16 operand planes of N.
+// ---------------------------------------------------------------------------------------
+__host__ __device__ inline int64_t bl_index(int64_t m, int64_t k, int64_t Kp) {
+  return (((m >> 5) * (Kp >> 3) + (k >> 3)) * 32 + (m & 31)) * 8 + (k & 7);
+}
+__host__ __device__ inline int64_t pad32(int64_t x) { return (x + 31) & ~int64_t(31); }
+
+enum ExtTable : int32_t {       // per-call tables of caller pointers, one entry per matrix
+  EXT_NONE = -1, EXT_W = 0, EXT_G = 1, EXT_SRC = 2, EXT_OMEGA = 3, EXT_DIN = 4, EXT_DOUT = 5, EXT_COUNT = 6
+};
+
+// Per-matrix record in device memory.  Offsets are in BYTES from the arena base unless noted.
+struct MatDev {
+  int32_t p, q, r, pp, qp, rp;
+  int64_t q32;            // fp32 p x r plain projection
+  int64_t qa_hi, qa_lo;   // bf16 BL(m = row of W, k = rank)      : A operand of the up-projection
+  int64_t qt_hi, qt_lo;   // bf16 BL(m = rank, k = row of W)      : A operand of the down-projection
+  int64_t lr_off;         // ELEMENT offset of this matrix in the flat low-rank arrays (g, u, v, N)
+  int64_t anchor, mom;    // fp32 p x q plain (mom = -1 if no outer momentum)
+  // refresh workspace
+  int64_t y[2];           // fp32 p x r, ping-pong of the orthonormalisation
+  int64_t zw[4];          // fp32 q x r; zw[0], zw[1] ping-pong of the q-side block, all four rotation temporaries
+  int64_t gram, lfac;     // fp32 r x r : Gram matrix (consumed by the factorisation) and its Cholesky factor
+  int64_t dinv;           // fp32 ceil(r/NB) blocks of NB x NB : inverses of the diagonal blocks of the factor
+  int64_t rot, rot2;      // fp32 r x r : R = Q_new^T Q_old and its elementwise square
+};
+
+// Work item of the projection kernels.
+struct ProjTile {
+  int32_t mat;
+  int32_t m0;             // first row of the output tile (down: rank index; up: row of W)
+  int32_t n0;             // first column of the tile (column of W)
+  int32_t k0, k1;         // contraction range (down: rows of W; up: unused)
+  int32_t split;          // split-K slice index of the output (down)
+  int32_t pad0, pad1;
+};
+
+// Operand reference of the generic GEMM: arena offset, or caller pointer from table `ext`.
+struct OpRef {
+  int64_t off;            // bytes (added to the arena base, or to the caller pointer)
+  int32_t ext;            // ExtTable
+  int32_t pad;
+};
+
+// C[M x N] = alpha * A[M x K] * B[K x N] + beta * C, fp32 accumulate.
+// A(m, k) at A + m*sAm + k*sAk, B(k, n) at B + k*sBk + n*sBn (element strides), C row-major ldc.
+struct GemmDesc {
+  OpRef A, B, C, C2;      // C2 (off < 0 = none) receives the elementwise square of the result
+  int32_t M, N, K, mat;
+  int64_t sAm, sAk, sBk, sBn;
+  int32_t ldc, a_bf16, b_bf16, pad;   // a_bf16: 0 fp32, 1 bf16, 2 = element type given at launch (refresh source)
+  float alpha, beta;
+};
+
+struct GemmTile { int32_t desc; int16_t tm, tn; };
+
+// Device-side view handed to kernels.
+struct DevCtx {
+  char* arena;
+  const MatDev* mats;
+  void* const* ext;       // EXT_COUNT * n pointers: ext[table * n + mat]
+  int32_t n;
+  int32_t* flag;          // numerical breakdown latch
+};
+
+constexpr int CHUNK = 2048;       // elements per workgroup of the p x q elementwise kernels
+constexpr int NB = 64;            // Cholesky / triangular-solve block size
+
+// ---------------------------------------------------------------------------------------
+// launchers (each defined in one .hip file)
+// ---------------------------------------------------------------------------------------
+// proj.hip
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, float* glow, int64_t split_stride,
+                            float grad_scale, bool g_is_f32, hipStream_t s);
+hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* n_hi,
+                          const uint16_t* n_lo, float lr, hipStream_t s);
+// gemm32.hip
+hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int src_is_bf16,
+                         hipStream_t s);
+// elementwise.hip
+struct AdamArgs { float b1, omb1, b2, omb2, inv_c1, inv_c2, eps; int32_t nsplit; int64_t split_stride; };
+hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
+                       const AdamArgs& a, hipStream_t s);
+hipError_t launch_store_ptrs(void** dst, void* const* host_src, int count, hipStream_t s);
+hipError_t launch_pack_q(const DevCtx& d, int mat_first, int mat_count, hipStream_t s);
+hipError_t launch_identity_q(const DevCtx& d, hipStream_t s);
+hipError_t launch_fill_zero(void* dst, int64_t bytes, hipStream_t s);
+hipError_t launch_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
+// p x q elementwise family: chunk_start (device) has n+1 entries, prefix sums of per-matrix chunk counts
+struct OuterArgs { float lr, mu; int32_t nesterov, has_mom, own_delta; };
+hipError_t launch_outer(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s);
+hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
+hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
+// refresh helpers (grouped over all matrices)
+hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s);
+hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
+hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
+hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);
+hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s);
+// state exchange with plain row-major buffers (one matrix)
+hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, const uint16_t* n_hi, const uint16_t* n_lo,
+                              float* dst, hipStream_t s);
+hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s);
+
+}  // namespace lordo

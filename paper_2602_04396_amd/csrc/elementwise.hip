@@ -1,0 +1,498 @@
+// Elementwise, packing and small dense kernels of the LoRDO library (gfx950).
+//   k_adam          fused low-rank Adam update on the flat low-rank arena (Sec. 2; Alg. 1 moment lines)
+//   k_outer         outer step on the pseudo-gradient (Alg. 1 OuterOpt; App. A.2, D.4)
+//   k_export_delta  pseudo-gradient anchor - W (App. A.1)
+//   k_pack_q        split of the fp32 projection into bf16 hi/lo operand planes
+//   k_potf2         Cholesky of one diagonal block and its inverse (CholeskyQR)
+//   k_rot_pre/post  elementwise parts of the moment rotation (Alg. 1 rotation lines)
+#include "common.h"
+
+namespace lordo {
+
+// ---------------------------------------------------------------------------------------
+// bf16 helpers: round-to-nearest-even split of an fp32 value into hi + lo
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t f2bf(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ void split_bf(float x, uint32_t& hi, uint32_t& lo) {
+  hi = f2bf(x);
+  lo = f2bf(x - bf2f(hi));
+}
+
+// ---------------------------------------------------------------------------------------
+// fused low-rank Adam: one thread per 8 consecutive elements of the flat arena
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, float* __restrict__ u,
+                                              float* __restrict__ v, uint16_t* __restrict__ n_hi,
+                                              uint16_t* __restrict__ n_lo, int64_t ngroups, AdamArgs a) {
+  int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (gidx >= ngroups) return;
+  int64_t base = gidx * 8;
+  float g[8], uu[8], vv[8];
+  {
+    const float4* gp = reinterpret_cast<const float4*>(glow + base);
+    float4 a0 = gp[0], a1 = gp[1];
+    g[0] = a0.x; g[1] = a0.y; g[2] = a0.z; g[3] = a0.w; g[4] = a1.x; g[5] = a1.y; g[6] = a1.z; g[7] = a1.w;
+    for (int sidx = 1; sidx < a.nsplit; ++sidx) {       // deterministic split-K reduction, fixed order
+      const float4* sp = reinterpret_cast<const float4*>(glow + sidx * a.split_stride + base);
+      float4 b0 = sp[0], b1 = sp[1];
+      g[0] += b0.x; g[1] += b0.y; g[2] += b0.z; g[3] += b0.w; g[4] += b1.x; g[5] += b1.y; g[6] += b1.z; g[7] += b1.w;
+    }
+    const float4* up = reinterpret_cast<const float4*>(u + base);
+    float4 u0 = up[0], u1 = up[1];
+    uu[0] = u0.x; uu[1] = u0.y; uu[2] = u0.z; uu[3] = u0.w; uu[4] = u1.x; uu[5] = u1.y; uu[6] = u1.z; uu[7] = u1.w;
+    const float4* vp = reinterpret_cast<const float4*>(v + base);
+    float4 v0 = vp[0], v1 = vp[1];
+    vv[0] = v0.x; vv[1] = v0.y; vv[2] = v0.z; vv[3] = v0.w; vv[4] = v1.x; vv[5] = v1.y; vv[6] = v1.z; vv[7] = v1.w;
+  }
+  uint32_t hi[8], lo[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float un = fmaf(a.b1, uu[e], a.omb1 * g[e]);
+    float vn = fmaf(a.b2, vv[e], a.omb2 * (g[e] * g[e]));
+    uu[e] = un;
+    vv[e] = vn;
+    float nn = (un * a.inv_c1) / (sqrtf(vn * a.inv_c2) + a.eps);
+    split_bf(nn, hi[e], lo[e]);
+  }
+  float4* up = reinterpret_cast<float4*>(u + base);
+  up[0] = make_float4(uu[0], uu[1], uu[2], uu[3]);
+  up[1] = make_float4(uu[4], uu[5], uu[6], uu[7]);
+  float4* vp = reinterpret_cast<float4*>(v + base);
+  vp[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+  vp[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
+  uint4 ph, pl;
+  ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
+  pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
+  *reinterpret_cast<uint4*>(n_hi + base) = ph;
+  *reinterpret_cast<uint4*>(n_lo + base) = pl;
+}
+
+hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
+                       const AdamArgs& a, hipStream_t s) {
+  int64_t ngroups = nelem / 8;
+  if (ngroups == 0) return hipSuccess;
+  unsigned blocks = (unsigned)((ngroups + 255) / 256);
+  hipLaunchKernelGGL(k_adam, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// caller pointer tables: the pointers travel in the kernel arguments, so no host buffer has
+// to outlive the call
+// ---------------------------------------------------------------------------------------
+struct PtrPack { void* p[256]; };
+__global__ void k_store_ptrs(PtrPack pack, void** dst, int count) {
+  int i = threadIdx.x;
+  if (i < count) dst[i] = pack.p[i];
+}
+hipError_t launch_store_ptrs(void** dst, void* const* host_src, int count, hipStream_t s) {
+  for (int done = 0; done < count; done += 256) {
+    PtrPack pack;
+    int c = count - done < 256 ? count - done : 256;
+    for (int i = 0; i < 256; ++i) pack.p[i] = i < c ? host_src[done + i] : nullptr;
+    hipLaunchKernelGGL(k_store_ptrs, dim3(1), dim3(256), 0, s, pack, dst + done, c);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------
+// fill / copy
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fill_zero(uint4* dst, int64_t n16) {
+  int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
+}
+hipError_t launch_fill_zero(void* dst, int64_t bytes, hipStream_t s) {
+  int64_t n16 = bytes / 16;      // regions are 256-byte multiples
+  if (n16 == 0) return hipSuccess;
+  int64_t blocks = (n16 + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(dst), n16);
+  return hipGetLastError();
+}
+__global__ __launch_bounds__(256) void k_copy_f32(float* dst, const float* src, int64_t n) {
+  int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+hipError_t launch_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(k_copy_f32, dim3((unsigned)blocks), dim3(256), 0, s, dst, src, n);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// projection packing
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_identity_q(DevCtx d) {
+  const MatDev& m = d.mats[blockIdx.y];
+  float* q32 = reinterpret_cast<float*>(d.arena + m.q32);
+  int64_t total = (int64_t)m.p * m.r;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int64_t row = i / m.r, col = i % m.r;
+    q32[i] = row == col ? 1.0f : 0.0f;
+  }
+}
+hipError_t launch_identity_q(const DevCtx& d, hipStream_t s) {
+  hipLaunchKernelGGL(k_identity_q, dim3(64, d.n), dim3(256), 0, s, d);
+  return hipGetLastError();
+}
+
+// One thread writes one 8-element group of the up-projection planes and one of the
+// down-projection planes (both have pp*rp/8 groups).
+__global__ __launch_bounds__(256) void k_pack_q(DevCtx d, int mat_first) {
+  const MatDev& m = d.mats[mat_first + blockIdx.y];
+  const float* q32 = reinterpret_cast<const float*>(d.arena + m.q32);
+  uint16_t* qa_hi = reinterpret_cast<uint16_t*>(d.arena + m.qa_hi);
+  uint16_t* qa_lo = reinterpret_cast<uint16_t*>(d.arena + m.qa_lo);
+  uint16_t* qt_hi = reinterpret_cast<uint16_t*>(d.arena + m.qt_hi);
+  uint16_t* qt_lo = reinterpret_cast<uint16_t*>(d.arena + m.qt_lo);
+  int64_t ngroups = (int64_t)m.pp * m.rp / 8;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
+    uint32_t hi[8], lo[8];
+    {   // up-projection plane: group = (row block, rank octet, row in block)
+      int64_t per_mb = (int64_t)(m.rp / 8) * 32;
+      int64_t mb = g / per_mb, rem = g % per_mb;
+      int64_t k8 = rem / 32, m32 = rem % 32;
+      int64_t row = mb * 32 + m32;
+      for (int e = 0; e < 8; ++e) {
+        int64_t k = k8 * 8 + e;
+        float x = (row < m.p && k < m.r) ? q32[row * m.r + k] : 0.0f;
+        split_bf(x, hi[e], lo[e]);
+      }
+      uint4 ph = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+      uint4 pl = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+      *reinterpret_cast<uint4*>(qa_hi + g * 8) = ph;
+      *reinterpret_cast<uint4*>(qa_lo + g * 8) = pl;
+    }
+    {   // down-projection plane: group = (rank block, row octet, rank in block)
+      int64_t per_ib = (int64_t)(m.pp / 8) * 32;
+      int64_t ib = g / per_ib, rem = g % per_ib;
+      int64_t k8 = rem / 32, i32 = rem % 32;
+      int64_t i = ib * 32 + i32;
+      for (int e = 0; e < 8; ++e) {
+        int64_t row = k8 * 8 + e;
+        float x = (row < m.p && i < m.r) ? q32[row * m.r + i] : 0.0f;
+        split_bf(x, hi[e], lo[e]);
+      }
+      uint4 ph = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+      uint4 pl = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+      *reinterpret_cast<uint4*>(qt_hi + g * 8) = ph;
+      *reinterpret_cast<uint4*>(qt_lo + g * 8) = pl;
+    }
+  }
+}
+hipError_t launch_pack_q(const DevCtx& d, int mat_first, int mat_count, hipStream_t s) {
+  if (mat_count <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_pack_q, dim3(128, mat_count), dim3(256), 0, s, d, mat_first);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_q_from_y(DevCtx d, int ybuf) {
+  const MatDev& m = d.mats[blockIdx.y];
+  float* q32 = reinterpret_cast<float*>(d.arena + m.q32);
+  const float* y = reinterpret_cast<const float*>(d.arena + m.y[ybuf]);
+  int64_t total = (int64_t)m.p * m.r;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) q32[i] = y[i];
+}
+hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s) {
+  hipLaunchKernelGGL(k_q_from_y, dim3(128, d.n), dim3(256), 0, s, d, ybuf);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// p x q elementwise family (outer step, pseudo-gradient, anchor copy)
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int find_mat(const int64_t* chunk_start, int n, int64_t b) {
+  int lo = 0, hi = n;             // invariant: chunk_start[lo] <= b < chunk_start[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (chunk_start[mid] <= b) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <int MODE>   // 0 outer step, 1 export delta, 2 anchor <- W
+__global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict__ chunk_start, OuterArgs a) {
+  int64_t b = blockIdx.x;
+  int mat = find_mat(chunk_start, d.n, b);
+  const MatDev& m = d.mats[mat];
+  int64_t total = (int64_t)m.p * m.q;
+  int64_t off = (b - chunk_start[mat]) * CHUNK;
+  float* W = reinterpret_cast<float*>(d.ext[EXT_W * d.n + mat]);
+  float* anchor = reinterpret_cast<float*>(d.arena + m.anchor);
+  float* mom = a.has_mom ? reinterpret_cast<float*>(d.arena + m.mom) : nullptr;
+  const float* din = (MODE == 0 && !a.own_delta) ? reinterpret_cast<const float*>(d.ext[EXT_DIN * d.n + mat]) : nullptr;
+  float* dout = MODE == 1 ? reinterpret_cast<float*>(d.ext[EXT_DOUT * d.n + mat]) : nullptr;
+  bool vec = (total % 4 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
+             (din == nullptr || (reinterpret_cast<uintptr_t>(din) & 15) == 0) &&
+             (dout == nullptr || (reinterpret_cast<uintptr_t>(dout) & 15) == 0);
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    int64_t i0 = off + rep * 1024 + threadIdx.x * 4;
+    if (i0 >= total) continue;
+    float w[4], an[4], dl[4], bb[4];
+    int cnt = total - i0 < 4 ? (int)(total - i0) : 4;
+    if (vec) {
+      float4 t;
+      if (MODE != 0 || a.own_delta) { t = *reinterpret_cast<const float4*>(W + i0); w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w; }
+      if (MODE != 2) { t = *reinterpret_cast<const float4*>(anchor + i0); an[0] = t.x; an[1] = t.y; an[2] = t.z; an[3] = t.w; }
+      if (din) { t = *reinterpret_cast<const float4*>(din + i0); dl[0] = t.x; dl[1] = t.y; dl[2] = t.z; dl[3] = t.w; }
+      if (MODE == 0 && mom) { t = *reinterpret_cast<const float4*>(mom + i0); bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w; }
+    } else {
+      for (int e = 0; e < cnt; ++e) {
+        if (MODE != 0 || a.own_delta) w[e] = W[i0 + e];
+        if (MODE != 2) an[e] = anchor[i0 + e];
+        if (din) dl[e] = din[i0 + e];
+        if (MODE == 0 && mom) bb[e] = mom[i0 + e];
+      }
+    }
+    float o0[4], o1[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (MODE == 0) {
+        float dd = a.own_delta ? an[e] - w[e] : dl[e];
+        float step = dd;
+        if (mom) {
+          float bn = fmaf(a.mu, bb[e], dd);
+          o1[e] = bn;
+          step = a.nesterov ? fmaf(a.mu, bn, dd) : bn;
+        }
+        o0[e] = fmaf(-a.lr, step, an[e]);
+      } else if (MODE == 1) {
+        o0[e] = an[e] - w[e];
+      } else {
+        o0[e] = w[e];
+      }
+    }
+    if (vec) {
+      float4 t0 = make_float4(o0[0], o0[1], o0[2], o0[3]);
+      if (MODE == 0) {
+        *reinterpret_cast<float4*>(W + i0) = t0;
+        *reinterpret_cast<float4*>(anchor + i0) = t0;
+        if (mom) *reinterpret_cast<float4*>(mom + i0) = make_float4(o1[0], o1[1], o1[2], o1[3]);
+      } else if (MODE == 1) {
+        *reinterpret_cast<float4*>(dout + i0) = t0;
+      } else {
+        *reinterpret_cast<float4*>(anchor + i0) = t0;
+      }
+    } else {
+      for (int e = 0; e < cnt; ++e) {
+        if (MODE == 0) { W[i0 + e] = o0[e]; anchor[i0 + e] = o0[e]; if (mom) mom[i0 + e] = o1[e]; }
+        else if (MODE == 1) dout[i0 + e] = o0[e];
+        else anchor[i0 + e] = o0[e];
+      }
+    }
+  }
+}
+
+hipError_t launch_outer(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_pq<0>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  return hipGetLastError();
+}
+hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s) {
+  OuterArgs a{};
+  hipLaunchKernelGGL(k_pq<1>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  return hipGetLastError();
+}
+hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s) {
+  OuterArgs a{};
+  hipLaunchKernelGGL(k_pq<2>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// CholeskyQR helpers
+// ---------------------------------------------------------------------------------------
+// S_ii += coef * trace(S): keeps the first factorisation positive definite in fp32.
+__global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef) {
+  const MatDev& m = d.mats[blockIdx.x];
+  float* S = reinterpret_cast<float*>(d.arena + m.gram);
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < m.r; i += 256) acc += S[(int64_t)i * m.r + i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  float shift = coef * red[0];
+  for (int i = threadIdx.x; i < m.r; i += 256) S[(int64_t)i * m.r + i] += shift;
+}
+hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s) {
+  hipLaunchKernelGGL(k_gram_shift, dim3(d.n), dim3(256), 0, s, d, coef);
+  return hipGetLastError();
+}
+
+// Diagonal block jb of the Gram matrix: L = chol(S_jj) (lower), X = L^{-1}; writes L into the
+// factor and X into the block-inverse array.  One workgroup per matrix.
+__global__ __launch_bounds__(256) void k_potf2(DevCtx d, int jb) {
+  const MatDev& m = d.mats[blockIdx.x];
+  int o = jb * NB;
+  int nbk = m.r - o;
+  if (nbk <= 0) return;
+  if (nbk > NB) nbk = NB;
+  const float* S = reinterpret_cast<const float*>(d.arena + m.gram);
+  float* L = reinterpret_cast<float*>(d.arena + m.lfac);
+  float* X = reinterpret_cast<float*>(d.arena + m.dinv) + (int64_t)jb * NB * NB;
+  __shared__ float Ls[NB][NB + 1];
+  __shared__ float Xs[NB][NB + 1];
+  __shared__ float dmax_s[256];
+  int tid = threadIdx.x;
+  float dm = 0.f;
+  for (int idx = tid; idx < NB * NB; idx += 256) {
+    int i = idx / NB, j = idx % NB;
+    float val;
+    if (i < nbk && j < nbk) val = j <= i ? S[(int64_t)(o + i) * m.r + (o + j)] : 0.f;
+    else val = i == j ? 1.f : 0.f;
+    Ls[i][j] = val;
+    Xs[i][j] = 0.f;
+    if (i == j && i < nbk) dm = fmaxf(dm, val);
+  }
+  dmax_s[tid] = dm;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) dmax_s[tid] = fmaxf(dmax_s[tid], dmax_s[tid + w]);
+    __syncthreads();
+  }
+  float floor_piv = 1e-12f * dmax_s[0] + 1e-37f;
+  for (int k = 0; k < NB; ++k) {
+    float piv = Ls[k][k];
+    if (!(piv > floor_piv)) {
+      if (tid == 0) *d.flag = 1;
+      piv = floor_piv;
+    }
+    float dd = sqrtf(piv);
+    __syncthreads();
+    if (tid < NB - k) {
+      int i = k + tid;
+      Ls[i][k] = i == k ? dd : Ls[i][k] / dd;
+    }
+    __syncthreads();
+    int w = NB - k - 1;
+    for (int idx = tid; idx < w * w; idx += 256) {
+      int i = k + 1 + idx / w, j = k + 1 + idx % w;
+      if (j <= i) Ls[i][j] -= Ls[i][k] * Ls[j][k];
+    }
+    __syncthreads();
+  }
+  if (tid < NB) {       // column tid of X = L^{-1} by forward substitution
+    int c = tid;
+    Xs[c][c] = 1.f / Ls[c][c];
+    for (int i = c + 1; i < NB; ++i) {
+      float sacc = 0.f;
+      for (int k = c; k < i; ++k) sacc = fmaf(Ls[i][k], Xs[k][c], sacc);
+      Xs[i][c] = -sacc / Ls[i][i];
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < NB * NB; idx += 256) {
+    int i = idx / NB, j = idx % NB;
+    X[idx] = j <= i ? Xs[i][j] : 0.f;
+    if (i < nbk && j < nbk) L[(int64_t)(o + i) * m.r + (o + j)] = j <= i ? Ls[i][j] : 0.f;
+  }
+}
+hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
+  hipLaunchKernelGGL(k_potf2, dim3(d.n), dim3(256), 0, s, d, jb);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// moment rotation, elementwise parts.  Plain temporaries are q x r row-major (the transposes of
+// the paper's r x q arrays): zw[2] = u_hat^T, zw[3] = (v_hat - u_hat^2)^T; the two GEMMs leave
+// zw[0] = (R u_hat)^T and zw[1] = ((R o R)(v_hat - u_hat^2))^T.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_rot_pre(DevCtx d, const float* __restrict__ u, const float* __restrict__ v,
+                                                 float inv_c1, float inv_c2) {
+  const MatDev& m = d.mats[blockIdx.y];
+  float* uh = reinterpret_cast<float*>(d.arena + m.zw[2]);
+  float* var = reinterpret_cast<float*>(d.arena + m.zw[3]);
+  int64_t ngroups = (int64_t)m.qp * m.rp / 8;
+  int64_t per_jb = (int64_t)(m.rp / 8) * 32;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
+    int64_t jb = g / per_jb, rem = g % per_jb;
+    int64_t i8 = rem / 32, j = jb * 32 + rem % 32;
+    if (j >= m.q) continue;
+    for (int e = 0; e < 8; ++e) {
+      int64_t i = i8 * 8 + e;
+      if (i >= m.r) break;
+      float a = u[m.lr_off + g * 8 + e] * inv_c1;
+      float b = v[m.lr_off + g * 8 + e] * inv_c2;
+      uh[j * m.r + i] = a;
+      var[j * m.r + i] = b - a * a;
+    }
+  }
+}
+hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s) {
+  hipLaunchKernelGGL(k_rot_pre, dim3(256, d.n), dim3(256), 0, s, d, u, v, inv_c1, inv_c2);
+  return hipGetLastError();
+}
+__global__ __launch_bounds__(256) void k_rot_post(DevCtx d, float* __restrict__ u, float* __restrict__ v, float c1, float c2) {
+  const MatDev& m = d.mats[blockIdx.y];
+  const float* a1 = reinterpret_cast<const float*>(d.arena + m.zw[0]);
+  const float* a2 = reinterpret_cast<const float*>(d.arena + m.zw[1]);
+  int64_t ngroups = (int64_t)m.qp * m.rp / 8;
+  int64_t per_jb = (int64_t)(m.rp / 8) * 32;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
+    int64_t jb = g / per_jb, rem = g % per_jb;
+    int64_t i8 = rem / 32, j = jb * 32 + rem % 32;
+    for (int e = 0; e < 8; ++e) {
+      int64_t i = i8 * 8 + e;
+      float un = 0.f, vn = 0.f;
+      if (j < m.q && i < m.r) {
+        float ru = a1[j * m.r + i];
+        un = c1 * ru;                                  // R u = c1 * R u_hat
+        vn = c2 * fabsf(a2[j * m.r + i] + ru * ru);
+      }
+      u[m.lr_off + g * 8 + e] = un;
+      v[m.lr_off + g * 8 + e] = vn;
+    }
+  }
+}
+hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s) {
+  hipLaunchKernelGGL(k_rot_post, dim3(256, d.n), dim3(256), 0, s, d, u, v, c1, c2);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// state exchange: blocked low-rank arrays <-> plain r x q row-major
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_lr_to_plain(DevCtx d, int mat, const float* lr_arr, const uint16_t* n_hi,
+                                                     const uint16_t* n_lo, float* dst) {
+  const MatDev& m = d.mats[mat];
+  int64_t total = (int64_t)m.r * m.q;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    int64_t i = t / m.q, j = t % m.q;
+    int64_t src = m.lr_off + bl_index(j, i, m.rp);
+    dst[t] = lr_arr ? lr_arr[src] : bf2f(n_hi[src]) + bf2f(n_lo[src]);
+  }
+}
+hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, const uint16_t* n_hi, const uint16_t* n_lo,
+                              float* dst, hipStream_t s) {
+  hipLaunchKernelGGL(k_lr_to_plain, dim3(256), dim3(256), 0, s, d, mat, lr_arr, n_hi, n_lo, dst);
+  return hipGetLastError();
+}
+__global__ __launch_bounds__(256) void k_plain_to_lr(DevCtx d, int mat, float* lr_arr, const float* src) {
+  const MatDev& m = d.mats[mat];
+  int64_t total = (int64_t)m.r * m.q;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    int64_t i = t / m.q, j = t % m.q;
+    lr_arr[m.lr_off + bl_index(j, i, m.rp)] = src[t];
+  }
+}
+hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s) {
+  hipLaunchKernelGGL(k_plain_to_lr, dim3(256), dim3(256), 0, s, d, mat, lr_arr, src);
+  return hipGetLastError();
+}
+
+}  // namespace lordo

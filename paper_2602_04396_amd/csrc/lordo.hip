@@ -1,0 +1,632 @@
+// C ABI of the LoRDO library: arena planning, static launch plans and the entry points.
+// Everything that depends only on the shapes (tile tables, GEMM descriptors of the refresh,
+// per-matrix records) is built once in lordo_init and kept in the caller's arena; the entry
+// points then only enqueue kernels.
+#include "../../include/lordo.h"
+#include "common.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+using namespace lordo;
+
+namespace {
+
+#define HIPCHK(expr)                                                                              \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) {                                                                       \
+      fprintf(stderr, "lordo: %s failed: %s (%s:%d)\n", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return LORDO_EHIP;                                                                          \
+    }                                                                                             \
+  } while (0)
+
+enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK };
+
+struct Op {
+  int kind;
+  int tile_first = 0, ntiles = 0;   // OP_GEMM
+  int iarg = 0;                     // OP_POTF2: block index; OP_Q_FROM_Y: y buffer
+  float farg = 0.f;                 // OP_SHIFT: coefficient
+  bool rot_only = false;            // part of the moment rotation (skipped while t == 0)
+};
+
+struct Plan {
+  size_t bytes = 0;
+  int64_t lr_total = 0;             // elements of one flat low-rank array
+  int64_t nchunks = 0;
+  int mb = 4;
+  int nsplit = 1;
+  // global regions (byte offsets)
+  int64_t flag, mats, ext, chunk_start, down_tiles, up_tiles, descs, gtiles, glow, u, v, n_hi, n_lo;
+  std::vector<MatDev> mat;
+  std::vector<int64_t> chunk_start_h;
+  std::vector<ProjTile> down_h, up_h;
+  std::vector<GemmDesc> desc_h;
+  std::vector<GemmTile> gtile_h;
+  std::vector<Op> ops;
+};
+
+struct Alloc {
+  size_t cur = 0;
+  int64_t take(size_t bytes) {
+    size_t o = cur;
+    cur += (bytes + 255) & ~size_t(255);
+    return (int64_t)o;
+  }
+};
+
+OpRef ref_arena(int64_t off) { return OpRef{off, EXT_NONE, 0}; }
+OpRef ref_ext(int table, int64_t off = 0) { return OpRef{off, table, 0}; }
+OpRef ref_none() { return OpRef{-1, EXT_NONE, 0}; }
+
+// Workgroups are handed to the 8 XCDs round-robin by index.  Placing logical tile
+// (b % 8) * ceil(T/8) + b / 8 at index b gives each XCD, and so each L2, a contiguous run of
+// logical tiles, which share operand planes.  Holes are marked mat = -1.
+std::vector<ProjTile> xcd_order(const std::vector<ProjTile>& logical) {
+  size_t T = logical.size();
+  size_t per = (T + 7) / 8;
+  std::vector<ProjTile> out(per * 8);
+  for (size_t b = 0; b < per * 8; ++b) {
+    size_t l = (b % 8) * per + b / 8;
+    if (l < T) out[b] = logical[l];
+    else { ProjTile h{}; h.mat = -1; out[b] = h; }
+  }
+  return out;
+}
+
+struct ProgramBuilder {
+  Plan& P;
+  int n;
+  explicit ProgramBuilder(Plan& p, int n_) : P(p), n(n_) {}
+
+  template <class F>
+  void gemm(F make, bool rot_only = false) {       // make(i, desc) -> false to skip matrix i
+    Op op;
+    op.kind = OP_GEMM;
+    op.tile_first = (int)P.gtile_h.size();
+    op.rot_only = rot_only;
+    for (int i = 0; i < n; ++i) {
+      GemmDesc g{};
+      g.C2 = ref_none();
+      g.alpha = 1.f;
+      g.beta = 0.f;
+      g.mat = i;
+      if (!make(i, g)) continue;
+      if (g.M <= 0 || g.N <= 0 || g.K <= 0) continue;
+      int di = (int)P.desc_h.size();
+      P.desc_h.push_back(g);
+      for (int tm = 0; tm < (g.M + 63) / 64; ++tm)
+        for (int tn = 0; tn < (g.N + 63) / 64; ++tn) P.gtile_h.push_back(GemmTile{di, (int16_t)tm, (int16_t)tn});
+    }
+    op.ntiles = (int)P.gtile_h.size() - op.tile_first;
+    P.ops.push_back(op);
+  }
+  void simple(int kind, int iarg = 0, float farg = 0.f, bool rot_only = false) {
+    Op op;
+    op.kind = kind;
+    op.iarg = iarg;
+    op.farg = farg;
+    op.rot_only = rot_only;
+    P.ops.push_back(op);
+  }
+
+  // Thin QR of the block held in buffer `cur` of the pair selected by `buf` (rows = p or q),
+  // by `passes` rounds of CholeskyQR; returns the buffer index that holds the result.
+  int orth(bool y_side, int cur, int passes) {
+    auto buf_of = [&](int i, int which) { return y_side ? P.mat[i].y[which] : P.mat[i].zw[which]; };
+    auto rows_of = [&](int i) { return y_side ? P.mat[i].p : P.mat[i].q; };
+    int max_blocks = 0;
+    for (int i = 0; i < n; ++i) max_blocks = std::max(max_blocks, (P.mat[i].r + NB - 1) / NB);
+    for (int pass = 0; pass < passes; ++pass) {
+      // S = X^T X
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_arena(buf_of(i, cur)); g.sAm = 1; g.sAk = m.r;
+        g.B = ref_arena(buf_of(i, cur)); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.gram); g.ldc = m.r;
+        g.M = m.r; g.N = m.r; g.K = rows_of(i);
+        return true;
+      });
+      if (pass == 0) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
+      for (int jb = 0; jb < max_blocks; ++jb) {
+        simple(OP_POTF2, jb);
+        // L_21 = S_21 L_11^{-T}
+        gemm([&](int i, GemmDesc& g) {
+          const MatDev& m = P.mat[i];
+          int rest = m.r - (jb + 1) * NB;
+          if (rest <= 0) return false;
+          int64_t o = ((int64_t)(jb + 1) * NB * m.r + (int64_t)jb * NB) * 4;
+          g.A = ref_arena(m.gram + o); g.sAm = m.r; g.sAk = 1;
+          g.B = ref_arena(m.dinv + (int64_t)jb * NB * NB * 4); g.sBk = 1; g.sBn = NB;
+          g.C = ref_arena(m.lfac + o); g.ldc = m.r;
+          g.M = rest; g.N = NB; g.K = NB;
+          return true;
+        });
+        // S_22 -= L_21 L_21^T
+        gemm([&](int i, GemmDesc& g) {
+          const MatDev& m = P.mat[i];
+          int rest = m.r - (jb + 1) * NB;
+          if (rest <= 0) return false;
+          int64_t o = ((int64_t)(jb + 1) * NB * m.r + (int64_t)jb * NB) * 4;
+          g.A = ref_arena(m.lfac + o); g.sAm = m.r; g.sAk = 1;
+          g.B = ref_arena(m.lfac + o); g.sBk = 1; g.sBn = m.r;
+          g.C = ref_arena(m.gram + ((int64_t)(jb + 1) * NB * m.r + (int64_t)(jb + 1) * NB) * 4); g.ldc = m.r;
+          g.M = rest; g.N = rest; g.K = NB;
+          g.alpha = -1.f; g.beta = 1.f;
+          return true;
+        });
+      }
+      // Q = X L^{-T}, block column by block column: Q_j = (X_j - Q_{<j} L_{j,<j}^T) L_jj^{-T}
+      int dst = 1 - cur;
+      for (int jb = 0; jb < max_blocks; ++jb) {
+        if (jb > 0)
+          gemm([&](int i, GemmDesc& g) {
+            const MatDev& m = P.mat[i];
+            int nbk = std::min(NB, m.r - jb * NB);
+            if (nbk <= 0) return false;
+            g.A = ref_arena(buf_of(i, dst)); g.sAm = m.r; g.sAk = 1;
+            g.B = ref_arena(m.lfac + (int64_t)jb * NB * m.r * 4); g.sBk = 1; g.sBn = m.r;
+            g.C = ref_arena(buf_of(i, cur) + (int64_t)jb * NB * 4); g.ldc = m.r;
+            g.M = rows_of(i); g.N = nbk; g.K = jb * NB;
+            g.alpha = -1.f; g.beta = 1.f;
+            return true;
+          });
+        gemm([&](int i, GemmDesc& g) {
+          const MatDev& m = P.mat[i];
+          int nbk = std::min(NB, m.r - jb * NB);
+          if (nbk <= 0) return false;
+          g.A = ref_arena(buf_of(i, cur) + (int64_t)jb * NB * 4); g.sAm = m.r; g.sAk = 1;
+          g.B = ref_arena(m.dinv + (int64_t)jb * NB * NB * 4); g.sBk = 1; g.sBn = NB;
+          g.C = ref_arena(buf_of(i, dst) + (int64_t)jb * NB * 4); g.ldc = m.r;
+          g.M = rows_of(i); g.N = nbk; g.K = nbk;
+          return true;
+        });
+      }
+      cur = dst;
+    }
+    return cur;
+  }
+
+  void build(int power_iters, int passes) {
+    // Y = Src Omega
+    gemm([&](int i, GemmDesc& g) {
+      const MatDev& m = P.mat[i];
+      g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2;
+      g.B = ref_ext(EXT_OMEGA); g.sBk = m.r; g.sBn = 1;
+      g.C = ref_arena(m.y[0]); g.ldc = m.r;
+      g.M = m.p; g.N = m.r; g.K = m.q;
+      return true;
+    });
+    int ycur = orth(true, 0, passes);
+    for (int it = 0; it < power_iters; ++it) {
+      // Z = Src^T Y
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2;
+        g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.zw[0]); g.ldc = m.r;
+        g.M = m.q; g.N = m.r; g.K = m.p;
+        return true;
+      });
+      int zcur = orth(false, 0, passes);
+      // Y = Src Z
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2;
+        g.B = ref_arena(m.zw[zcur]); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.y[0]); g.ldc = m.r;
+        g.M = m.p; g.N = m.r; g.K = m.q;
+        return true;
+      });
+      ycur = orth(true, 0, passes);
+    }
+    // rotation: R = Q_new^T Q_old (and R o R)
+    gemm([&](int i, GemmDesc& g) {
+      const MatDev& m = P.mat[i];
+      g.A = ref_arena(m.y[ycur]); g.sAm = 1; g.sAk = m.r;
+      g.B = ref_arena(m.q32); g.sBk = m.r; g.sBn = 1;
+      g.C = ref_arena(m.rot); g.C2 = ref_arena(m.rot2); g.ldc = m.r;
+      g.M = m.r; g.N = m.r; g.K = m.p;
+      return true;
+    }, true);
+    simple(OP_ROT_PRE, 0, 0.f, true);
+    for (int which = 0; which < 2; ++which)
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_arena(m.zw[2 + which]); g.sAm = m.r; g.sAk = 1;
+        g.B = ref_arena(which == 0 ? m.rot : m.rot2); g.sBk = 1; g.sBn = m.r;
+        g.C = ref_arena(m.zw[which]); g.ldc = m.r;
+        g.M = m.q; g.N = m.r; g.K = m.r;
+        return true;
+      }, true);
+    simple(OP_ROT_POST, 0, 0.f, true);
+    simple(OP_Q_FROM_Y, ycur);
+    simple(OP_PACK);
+  }
+};
+
+int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
+  if (!shapes || !hp || n <= 0) return LORDO_EINVAL;
+  for (int i = 0; i < n; ++i) {
+    const lordo_shape& s = shapes[i];
+    if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || s.rank > s.rows || s.reserved != 0) return LORDO_EINVAL;
+    if (s.rows > (1 << 24) || s.cols > (1 << 24) || s.rank > 4096) return LORDO_EINVAL;
+  }
+  if (!(hp->beta1 >= 0 && hp->beta1 < 1) || !(hp->beta2 >= 0 && hp->beta2 < 1) || !(hp->eps >= 0)) return LORDO_EINVAL;
+  if (hp->qhm_mode != 0 || hp->error_feedback != 0 || hp->reserved != 0) return LORDO_EINVAL;
+  if (hp->power_iters < 0 || hp->power_iters > 8) return LORDO_EINVAL;
+  if (hp->orth_passes != 0 && hp->orth_passes != 2 && hp->orth_passes != 3) return LORDO_EINVAL;
+  if (hp->grad_dtype != LORDO_BF16 && hp->grad_dtype != LORDO_F32) return LORDO_EINVAL;
+  if (!std::isfinite(hp->outer_lr) || !std::isfinite(hp->outer_momentum)) return LORDO_EINVAL;
+  return LORDO_OK;
+}
+
+void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan& P) {
+  Alloc A;
+  P.flag = A.take(256);
+  P.mats = A.take(sizeof(MatDev) * n);
+  P.ext = A.take(sizeof(void*) * EXT_COUNT * n);
+  P.chunk_start = A.take(sizeof(int64_t) * (n + 1));
+  P.mat.resize(n);
+  P.chunk_start_h.resize(n + 1);
+  int64_t lr = 0, chunks = 0;
+  int rp_max = 0;
+  const bool has_mom = hp.outer_momentum != 0.0;
+  for (int i = 0; i < n; ++i) {
+    MatDev& m = P.mat[i];
+    m.p = (int)shapes[i].rows; m.q = (int)shapes[i].cols; m.r = shapes[i].rank;
+    m.pp = (int)pad32(m.p); m.qp = (int)pad32(m.q); m.rp = (int)pad32(m.r);
+    m.lr_off = lr;
+    lr += (int64_t)m.qp * m.rp;
+    rp_max = std::max(rp_max, m.rp);
+    P.chunk_start_h[i] = chunks;
+    chunks += ((int64_t)m.p * m.q + CHUNK - 1) / CHUNK;
+  }
+  P.chunk_start_h[n] = chunks;
+  P.nchunks = chunks;
+  P.lr_total = lr;
+  P.mb = rp_max > 64 ? 4 : (rp_max > 32 ? 2 : 1);
+  P.nsplit = 1;
+  P.glow = A.take(sizeof(float) * lr * P.nsplit);
+  P.u = A.take(sizeof(float) * lr);
+  P.v = A.take(sizeof(float) * lr);
+  P.n_hi = A.take(sizeof(uint16_t) * lr);
+  P.n_lo = A.take(sizeof(uint16_t) * lr);
+  for (int i = 0; i < n; ++i) {
+    MatDev& m = P.mat[i];
+    size_t pr = (size_t)m.p * m.r, pq = (size_t)m.p * m.q, qr = (size_t)m.q * m.r, rr = (size_t)m.r * m.r;
+    size_t planes = (size_t)m.pp * m.rp * 2;
+    m.q32 = A.take(pr * 4);
+    m.qa_hi = A.take(planes); m.qa_lo = A.take(planes);
+    m.qt_hi = A.take(planes); m.qt_lo = A.take(planes);
+    m.anchor = A.take(pq * 4);
+    m.mom = has_mom ? A.take(pq * 4) : -1;
+    m.y[0] = A.take(pr * 4); m.y[1] = A.take(pr * 4);
+    for (int k = 0; k < 4; ++k) m.zw[k] = A.take(qr * 4);
+    m.gram = A.take(rr * 4); m.lfac = A.take(rr * 4);
+    m.dinv = A.take((size_t)((m.r + NB - 1) / NB) * NB * NB * 4);
+    m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
+  }
+  // projection tile tables
+  std::vector<ProjTile> down, up;
+  for (int i = 0; i < n; ++i) {
+    const MatDev& m = P.mat[i];
+    for (int n0 = 0; n0 < m.qp; n0 += 128)
+      for (int m0 = 0; m0 < m.rp; m0 += 32 * P.mb) {
+        ProjTile t{};
+        t.mat = i; t.m0 = m0; t.n0 = n0; t.k0 = 0; t.k1 = m.pp; t.split = 0;
+        down.push_back(t);
+      }
+    for (int m0 = 0; m0 < m.pp; m0 += 128)
+      for (int n0 = 0; n0 < m.qp; n0 += 128) {
+        ProjTile t{};
+        t.mat = i; t.m0 = m0; t.n0 = n0;
+        up.push_back(t);
+      }
+  }
+  P.down_h = xcd_order(down);
+  P.up_h = xcd_order(up);
+  P.down_tiles = A.take(sizeof(ProjTile) * P.down_h.size());
+  P.up_tiles = A.take(sizeof(ProjTile) * P.up_h.size());
+  // refresh program
+  ProgramBuilder pb(P, n);
+  pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes);
+  P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
+  P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());
+  P.bytes = A.cur;
+}
+
+}  // namespace
+
+struct lordo_ctx {
+  int n = 0;
+  lordo_hparams hp{};
+  Plan plan;
+  DevCtx dev{};
+  int64_t t = 0;
+  int device = 0;
+  std::vector<void*> shadow[EXT_COUNT];
+  bool shadow_valid[EXT_COUNT] = {false, false, false, false, false, false};
+
+  template <class T>
+  T* at(int64_t off) const { return reinterpret_cast<T*>(dev.arena + off); }
+
+  int set_ext(int table, void* const* host, hipStream_t s) {
+    if (!host) return LORDO_EINVAL;
+    for (int i = 0; i < n; ++i)
+      if (!host[i]) return LORDO_EINVAL;
+    std::vector<void*>& sh = shadow[table];
+    if (shadow_valid[table] && std::memcmp(sh.data(), host, sizeof(void*) * n) == 0) return LORDO_OK;
+    void** dst = const_cast<void**>(dev.ext) + (size_t)table * n;
+    HIPCHK(launch_store_ptrs(dst, host, n, s));
+    sh.assign(host, host + n);
+    shadow_valid[table] = true;
+    return LORDO_OK;
+  }
+};
+
+extern "C" {
+
+int lordo_workspace_bytes(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp, size_t* out_bytes) {
+  if (!out_bytes) return LORDO_EINVAL;
+  int rc = validate(shapes, n, hp);
+  if (rc != LORDO_OK) return rc;
+  Plan P;
+  build_plan(shapes, n, *hp, P);
+  *out_bytes = P.bytes;
+  return LORDO_OK;
+}
+
+int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp, void* arena,
+               size_t arena_bytes, void* const* W, void* stream) {
+  if (!out) return LORDO_EINVAL;
+  *out = nullptr;
+  int rc = validate(shapes, n, hp);
+  if (rc != LORDO_OK) return rc;
+  if (!arena || !W || (reinterpret_cast<uintptr_t>(arena) & 255) != 0) return LORDO_EINVAL;
+  for (int i = 0; i < n; ++i)
+    if (!W[i]) return LORDO_EINVAL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+    fprintf(stderr, "lordo: no HIP device available\n");
+    return LORDO_EHIP;
+  }
+  lordo_ctx* c = new lordo_ctx();
+  c->n = n;
+  c->hp = *hp;
+  build_plan(shapes, n, *hp, c->plan);
+  Plan& P = c->plan;
+  if (arena_bytes < P.bytes) { delete c; return LORDO_ENOMEM; }
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  auto fail = [&](int code) { delete c; return code; };
+  if (hipGetDevice(&c->device) != hipSuccess) return fail(LORDO_EHIP);
+  c->dev.arena = reinterpret_cast<char*>(arena);
+  c->dev.mats = c->at<MatDev>(P.mats);
+  c->dev.ext = c->at<void*>(P.ext);
+  c->dev.n = n;
+  c->dev.flag = c->at<int32_t>(P.flag);
+#define INITCHK(expr)                                                                             \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) {                                                                       \
+      fprintf(stderr, "lordo: %s failed: %s\n", #expr, hipGetErrorString(e_));                    \
+      return fail(LORDO_EHIP);                                                                    \
+    }                                                                                             \
+  } while (0)
+  INITCHK(hipStreamSynchronize(s));
+  INITCHK(hipMemcpy(c->at<void>(P.mats), P.mat.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
+  INITCHK(hipMemcpy(c->at<void>(P.chunk_start), P.chunk_start_h.data(), sizeof(int64_t) * (n + 1), hipMemcpyHostToDevice));
+  INITCHK(hipMemcpy(c->at<void>(P.down_tiles), P.down_h.data(), sizeof(ProjTile) * P.down_h.size(), hipMemcpyHostToDevice));
+  INITCHK(hipMemcpy(c->at<void>(P.up_tiles), P.up_h.data(), sizeof(ProjTile) * P.up_h.size(), hipMemcpyHostToDevice));
+  if (!P.desc_h.empty())
+    INITCHK(hipMemcpy(c->at<void>(P.descs), P.desc_h.data(), sizeof(GemmDesc) * P.desc_h.size(), hipMemcpyHostToDevice));
+  if (!P.gtile_h.empty())
+    INITCHK(hipMemcpy(c->at<void>(P.gtiles), P.gtile_h.data(), sizeof(GemmTile) * P.gtile_h.size(), hipMemcpyHostToDevice));
+  // zero everything from the flat low-rank arrays to the end of the per-matrix regions except
+  // the tables written above: state (u, v, g, N), momentum and scratch all start at zero
+  INITCHK(launch_fill_zero(c->at<void>(P.flag), 256, s));
+  INITCHK(launch_fill_zero(c->at<void>(P.ext), ((sizeof(void*) * EXT_COUNT * n + 255) & ~size_t(255)), s));
+  INITCHK(launch_fill_zero(c->at<void>(P.glow), (int64_t)(P.down_tiles - P.glow), s));
+  INITCHK(launch_identity_q(c->dev, s));
+  INITCHK(launch_pack_q(c->dev, 0, n, s));
+  {
+    int r2 = c->set_ext(EXT_W, W, s);
+    if (r2 != LORDO_OK) return fail(r2);
+  }
+  INITCHK(launch_anchor_from_w(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, s));
+  INITCHK(hipStreamSynchronize(s));
+#undef INITCHK
+  *out = c;
+  return LORDO_OK;
+}
+
+int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double lr, double grad_scale, void* stream) {
+  if (!c || !W || !G || !std::isfinite(lr) || !std::isfinite(grad_scale)) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  Plan& P = c->plan;
+  int rc = c->set_ext(EXT_W, W, s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
+  if (rc != LORDO_OK) return rc;
+  const int64_t t = c->t + 1;
+  double c1 = 1.0, c2 = 1.0;
+  if (c->hp.bias_correction) {
+    c1 = 1.0 - std::pow(c->hp.beta1, (double)t);
+    c2 = 1.0 - std::pow(c->hp.beta2, (double)t);
+  }
+  AdamArgs a;
+  a.b1 = (float)c->hp.beta1; a.omb1 = (float)(1.0 - c->hp.beta1);
+  a.b2 = (float)c->hp.beta2; a.omb2 = (float)(1.0 - c->hp.beta2);
+  a.inv_c1 = (float)(1.0 / c1); a.inv_c2 = (float)(1.0 / c2);
+  a.eps = (float)c->hp.eps;
+  a.nsplit = P.nsplit; a.split_stride = P.lr_total;
+  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, c->at<float>(P.glow),
+                          P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
+  HIPCHK(launch_adam(c->at<float>(P.glow), c->at<float>(P.u), c->at<float>(P.v), c->at<uint16_t>(P.n_hi),
+                     c->at<uint16_t>(P.n_lo), P.lr_total, a, s));
+  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), c->at<uint16_t>(P.n_hi),
+                        c->at<uint16_t>(P.n_lo), (float)lr, s));
+  c->t = t;
+  return LORDO_OK;
+}
+
+int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, void* stream) {
+  if (!c || !Src || !Omega) return LORDO_EINVAL;
+  if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  Plan& P = c->plan;
+  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
+  if (rc != LORDO_OK) return rc;
+  const bool rotate = c->t > 0;
+  double c1 = 1.0, c2 = 1.0;
+  if (c->hp.bias_correction && rotate) {
+    c1 = 1.0 - std::pow(c->hp.beta1, (double)c->t);
+    c2 = 1.0 - std::pow(c->hp.beta2, (double)c->t);
+  }
+  const GemmDesc* descs = c->at<GemmDesc>(P.descs);
+  const GemmTile* tiles = c->at<GemmTile>(P.gtiles);
+  for (const Op& op : P.ops) {
+    if (op.rot_only && !rotate) continue;
+    switch (op.kind) {
+      case OP_GEMM:
+        HIPCHK(launch_gemm32(c->dev, descs, tiles + op.tile_first, op.ntiles, src_dtype == LORDO_BF16, s));
+        break;
+      case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, s)); break;
+      case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
+      case OP_ROT_PRE:
+        HIPCHK(launch_rot_pre(c->dev, c->at<float>(P.u), c->at<float>(P.v), (float)(1.0 / c1), (float)(1.0 / c2), s));
+        break;
+      case OP_ROT_POST:
+        HIPCHK(launch_rot_post(c->dev, c->at<float>(P.u), c->at<float>(P.v), (float)c1, (float)c2, s));
+        break;
+      case OP_Q_FROM_Y: HIPCHK(launch_q_from_y(c->dev, op.iarg, s)); break;
+      case OP_PACK: HIPCHK(launch_pack_q(c->dev, 0, c->n, s)); break;
+      default: return LORDO_ESTATE;
+    }
+  }
+  return LORDO_OK;
+}
+
+int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* DeltaOut, void* stream) {
+  if (!c || !W || !DeltaOut) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc = c->set_ext(EXT_W, const_cast<void* const*>(reinterpret_cast<const void* const*>(W)), s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_DOUT, DeltaOut, s);
+  if (rc != LORDO_OK) return rc;
+  HIPCHK(launch_export_delta(c->dev, c->at<int64_t>(c->plan.chunk_start), c->plan.nchunks, s));
+  return LORDO_OK;
+}
+
+int lordo_outer_step(lordo_ctx* c, void* const* W, const void* const* AvgDelta, void* stream) {
+  if (!c || !W) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc = c->set_ext(EXT_W, W, s);
+  if (rc != LORDO_OK) return rc;
+  OuterArgs a;
+  a.lr = (float)c->hp.outer_lr;
+  a.mu = (float)c->hp.outer_momentum;
+  a.nesterov = c->hp.outer_nesterov ? 1 : 0;
+  a.has_mom = c->hp.outer_momentum != 0.0 ? 1 : 0;
+  a.own_delta = AvgDelta ? 0 : 1;
+  if (AvgDelta) {
+    rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(AvgDelta)), s);
+    if (rc != LORDO_OK) return rc;
+  }
+  HIPCHK(launch_outer(c->dev, c->at<int64_t>(c->plan.chunk_start), c->plan.nchunks, a, s));
+  return LORDO_OK;
+}
+
+int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, void* stream) {
+  if (!c || !dev_dst || mat < 0 || mat >= c->n) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const MatDev& m = c->plan.mat[mat];
+  Plan& P = c->plan;
+  float* dst = reinterpret_cast<float*>(dev_dst);
+  switch (which) {
+    case LORDO_STATE_Q: HIPCHK(launch_copy_f32(dst, c->at<float>(m.q32), (int64_t)m.p * m.r, s)); break;
+    case LORDO_STATE_ANCHOR: HIPCHK(launch_copy_f32(dst, c->at<float>(m.anchor), (int64_t)m.p * m.q, s)); break;
+    case LORDO_STATE_MOM:
+      if (m.mom < 0) return LORDO_ESTATE;
+      HIPCHK(launch_copy_f32(dst, c->at<float>(m.mom), (int64_t)m.p * m.q, s));
+      break;
+    case LORDO_STATE_U: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.u), nullptr, nullptr, dst, s)); break;
+    case LORDO_STATE_V: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.v), nullptr, nullptr, dst, s)); break;
+    case LORDO_STATE_GLOW: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.glow), nullptr, nullptr, dst, s)); break;
+    case LORDO_STATE_NUPD:
+      HIPCHK(launch_lr_to_plain(c->dev, mat, nullptr, c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), dst, s));
+      break;
+    default: return LORDO_EINVAL;
+  }
+  return LORDO_OK;
+}
+
+int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_src, void* stream) {
+  if (!c || !dev_src || mat < 0 || mat >= c->n) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const MatDev& m = c->plan.mat[mat];
+  Plan& P = c->plan;
+  const float* src = reinterpret_cast<const float*>(dev_src);
+  switch (which) {
+    case LORDO_STATE_Q:
+      HIPCHK(launch_copy_f32(c->at<float>(m.q32), src, (int64_t)m.p * m.r, s));
+      HIPCHK(launch_pack_q(c->dev, mat, 1, s));
+      break;
+    case LORDO_STATE_ANCHOR: HIPCHK(launch_copy_f32(c->at<float>(m.anchor), src, (int64_t)m.p * m.q, s)); break;
+    case LORDO_STATE_MOM:
+      if (m.mom < 0) return LORDO_ESTATE;
+      HIPCHK(launch_copy_f32(c->at<float>(m.mom), src, (int64_t)m.p * m.q, s));
+      break;
+    case LORDO_STATE_U: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.u), src, s)); break;
+    case LORDO_STATE_V: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.v), src, s)); break;
+    default: return LORDO_EINVAL;
+  }
+  return LORDO_OK;
+}
+
+int lordo_get_step(lordo_ctx* c, int64_t* t) {
+  if (!c || !t) return LORDO_EINVAL;
+  *t = c->t;
+  return LORDO_OK;
+}
+
+int lordo_set_step(lordo_ctx* c, int64_t t) {
+  if (!c || t < 0) return LORDO_EINVAL;
+  c->t = t;
+  return LORDO_OK;
+}
+
+int lordo_poll_status(lordo_ctx* c, void* stream) {
+  if (!c) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  HIPCHK(hipStreamSynchronize(s));
+  int32_t flag = 0;
+  HIPCHK(hipMemcpy(&flag, c->dev.flag, sizeof(flag), hipMemcpyDeviceToHost));
+  if (flag != 0) {
+    HIPCHK(launch_fill_zero(c->dev.flag, 256, s));
+    HIPCHK(hipStreamSynchronize(s));
+    return LORDO_ENUMERIC;
+  }
+  return LORDO_OK;
+}
+
+const char* lordo_strerror(int code) {
+  switch (code) {
+    case LORDO_OK: return "ok";
+    case LORDO_EINVAL: return "invalid argument (null pointer, bad shape, rank > rows, unsupported option)";
+    case LORDO_ENOMEM: return "arena smaller than lordo_workspace_bytes";
+    case LORDO_EHIP: return "HIP runtime error or no GPU";
+    case LORDO_ESTATE: return "call not valid in the current state";
+    case LORDO_ENUMERIC: return "numerical breakdown in a kernel (non-positive Cholesky pivot)";
+    default: return "unknown error";
+  }
+}
+
+void lordo_destroy(lordo_ctx* c) { delete c; }
+
+}  // extern "C"

@@ -1,0 +1,215 @@
+"""Thin ctypes binding of liblordo.so (see include/lordo.h for the contract of every call).
+
+Only argument marshalling happens here: torch tensors supply device memory and the
+current stream; every step of the path runs in the library's kernels.  There is no
+fallback: if the library has not been built, importing `load()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "lib", "liblordo.so")
+
+OK, EINVAL, ENOMEM, EHIP, ESTATE, ENUMERIC = 0, -1, -2, -3, -4, -5
+F32, BF16 = 0, 1
+STATE_Q, STATE_U, STATE_V, STATE_ANCHOR, STATE_MOM, STATE_GLOW, STATE_NUPD = range(7)
+
+EXPORTS = [
+    "lordo_workspace_bytes", "lordo_init", "lordo_local_step", "lordo_refresh_subspace",
+    "lordo_export_pseudograd", "lordo_outer_step", "lordo_get_state", "lordo_set_state",
+    "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
+]
+
+
+class Shape(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("rank", C.c_int32), ("reserved", C.c_int32)]
+
+
+class HParams(C.Structure):
+    _fields_ = [
+        ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+        ("bias_correction", C.c_int32), ("qhm_mode", C.c_int32),
+        ("omega", C.c_double),
+        ("error_feedback", C.c_int32), ("outer_nesterov", C.c_int32),
+        ("outer_lr", C.c_double), ("outer_momentum", C.c_double),
+        ("power_iters", C.c_int32), ("orth_passes", C.c_int32),
+        ("grad_dtype", C.c_int32), ("reserved", C.c_int32),
+    ]
+
+
+def hparams(beta1=0.9, beta2=0.999, eps=1e-8, bias_correction=True, outer_lr=1.0, outer_momentum=0.0,
+            outer_nesterov=False, power_iters=2, orth_passes=2, grad_dtype=BF16, qhm_mode=0, omega=1.0,
+            error_feedback=False) -> HParams:
+    return HParams(beta1, beta2, eps, int(bias_correction), qhm_mode, omega, int(error_feedback),
+                   int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, 0)
+
+
+class LordoError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"lordo error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load the built library; raise if it is missing (no CPU or eager fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} not built: run `python -m paper_2602_04396_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, vpp = C.c_void_p, C.POINTER(C.c_void_p)
+    lib.lordo_workspace_bytes.argtypes = [C.POINTER(Shape), C.c_int32, C.POINTER(HParams), C.POINTER(C.c_size_t)]
+    lib.lordo_init.argtypes = [C.POINTER(vp), C.POINTER(Shape), C.c_int32, C.POINTER(HParams), vp, C.c_size_t, vpp, vp]
+    lib.lordo_local_step.argtypes = [vp, vpp, vpp, C.c_double, C.c_double, vp]
+    lib.lordo_refresh_subspace.argtypes = [vp, vpp, C.c_int32, vpp, vp]
+    lib.lordo_export_pseudograd.argtypes = [vp, vpp, vpp, vp]
+    lib.lordo_outer_step.argtypes = [vp, vpp, vpp, vp]
+    lib.lordo_get_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
+    lib.lordo_set_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
+    lib.lordo_get_step.argtypes = [vp, C.POINTER(C.c_int64)]
+    lib.lordo_set_step.argtypes = [vp, C.c_int64]
+    lib.lordo_poll_status.argtypes = [vp, vp]
+    lib.lordo_strerror.argtypes = [C.c_int]
+    lib.lordo_strerror.restype = C.c_char_p
+    lib.lordo_destroy.argtypes = [vp]
+    lib.lordo_destroy.restype = None
+    for name in EXPORTS:
+        if name not in ("lordo_strerror", "lordo_destroy"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(code):
+    if code != OK:
+        raise LordoError(code, load().lordo_strerror(code).decode())
+
+
+def _ptr_array(tensors):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def _shape_array(shapes):
+    arr = (Shape * len(shapes))()
+    for i, (p, q, r) in enumerate(shapes):
+        arr[i] = Shape(p, q, r, 0)
+    return arr
+
+
+def workspace_bytes(shapes, hp: HParams) -> int:
+    out = C.c_size_t(0)
+    _check(load().lordo_workspace_bytes(_shape_array(shapes), len(shapes), C.byref(hp), C.byref(out)))
+    return out.value
+
+
+class Lordo:
+    """One optimizer context over a list of (p, q, r) matrices.  `W` and every other
+    argument is a list of torch CUDA tensors, contiguous, in the order of `shapes`."""
+
+    def __init__(self, shapes, hp: HParams, W, torch):
+        self.lib = load()
+        self.torch = torch
+        self.shapes = [tuple(s) for s in shapes]
+        self.hp = hp
+        self.n = len(shapes)
+        self._check_tensors(W, torch.float32, "pq")
+        nbytes = workspace_bytes(self.shapes, hp)
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=W[0].device)
+        base = self.arena.data_ptr()
+        self.arena_ptr = (base + 255) // 256 * 256
+        self.arena_bytes = nbytes
+        self.ctx = C.c_void_p()
+        _check(self.lib.lordo_init(C.byref(self.ctx), _shape_array(self.shapes), self.n, C.byref(hp),
+                                   C.c_void_p(self.arena_ptr), nbytes, _ptr_array(W), self._stream()))
+
+    # -- helpers ----------------------------------------------------------------------------
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream().cuda_stream)
+
+    def _check_tensors(self, ts, dtype, kind):
+        if len(ts) != self.n:
+            raise ValueError("one tensor per matrix expected")
+        for t, (p, q, r) in zip(ts, self.shapes):
+            want = {"pq": (p, q), "qr": (q, r)}[kind]
+            if tuple(t.shape) != want or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError(f"expected contiguous CUDA {dtype} tensor of shape {want}, got {t.dtype} {tuple(t.shape)}")
+
+    def _grad_dtype(self):
+        return self.torch.bfloat16 if self.hp.grad_dtype == BF16 else self.torch.float32
+
+    # -- the four calls -----------------------------------------------------------------------
+    def local_step(self, W, G, lr, grad_scale=1.0):
+        self._check_tensors(W, self.torch.float32, "pq")
+        self._check_tensors(G, self._grad_dtype(), "pq")
+        _check(self.lib.lordo_local_step(self.ctx, _ptr_array(W), _ptr_array(G), float(lr), float(grad_scale), self._stream()))
+
+    def refresh_subspace(self, Src, Omega):
+        dt = Src[0].dtype
+        self._check_tensors(Src, dt, "pq")
+        self._check_tensors(Omega, self.torch.float32, "qr")
+        code = BF16 if dt == self.torch.bfloat16 else F32
+        if dt not in (self.torch.bfloat16, self.torch.float32):
+            raise ValueError("refresh source must be bf16 or fp32")
+        _check(self.lib.lordo_refresh_subspace(self.ctx, _ptr_array(Src), code, _ptr_array(Omega), self._stream()))
+
+    def export_pseudograd(self, W, out):
+        self._check_tensors(W, self.torch.float32, "pq")
+        self._check_tensors(out, self.torch.float32, "pq")
+        _check(self.lib.lordo_export_pseudograd(self.ctx, _ptr_array(W), _ptr_array(out), self._stream()))
+
+    def outer_step(self, W, avg_delta=None):
+        self._check_tensors(W, self.torch.float32, "pq")
+        if avg_delta is not None:
+            self._check_tensors(avg_delta, self.torch.float32, "pq")
+            _check(self.lib.lordo_outer_step(self.ctx, _ptr_array(W), _ptr_array(avg_delta), self._stream()))
+        else:
+            _check(self.lib.lordo_outer_step(self.ctx, _ptr_array(W), None, self._stream()))
+
+    # -- state ------------------------------------------------------------------------------------
+    def _state_shape(self, mat, which):
+        p, q, r = self.shapes[mat]
+        return {STATE_Q: (p, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q)}.get(which, (r, q))
+
+    def get_state(self, mat, which):
+        out = self.torch.empty(self._state_shape(mat, which), dtype=self.torch.float32, device=self.arena.device)
+        _check(self.lib.lordo_get_state(self.ctx, mat, which, C.c_void_p(out.data_ptr()), self._stream()))
+        return out
+
+    def set_state(self, mat, which, src):
+        want = self._state_shape(mat, which)
+        if tuple(src.shape) != want or src.dtype != self.torch.float32 or not src.is_contiguous() or not src.is_cuda:
+            raise ValueError(f"expected contiguous CUDA float32 tensor of shape {want}")
+        _check(self.lib.lordo_set_state(self.ctx, mat, which, C.c_void_p(src.data_ptr()), self._stream()))
+
+    @property
+    def step(self):
+        t = C.c_int64(0)
+        _check(self.lib.lordo_get_step(self.ctx, C.byref(t)))
+        return t.value
+
+    @step.setter
+    def step(self, t):
+        _check(self.lib.lordo_set_step(self.ctx, int(t)))
+
+    def poll_status(self):
+        _check(self.lib.lordo_poll_status(self.ctx, self._stream()))
+
+    def close(self):
+        if self.ctx:
+            self.lib.lordo_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,135 @@
+"""Side-by-side driver of the float64 oracle and the HIP library on identical seeded inputs.
+
+The two implementations share nothing but the input arrays built here.  The only value that
+ever travels from the HIP side to the oracle is a basis handed over on purpose (teacher
+forcing, because the second-moment rotation depends on the basis and not only on its span)
+and the sign decision of elements whose first-step update is the sign of a number that is
+zero to working precision (see `first_step_patch`).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import lordo_oracle as orc
+from paper_2602_04396_amd import synth
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def projector_distance(Qa, Qb):
+    """|| Qa Qa^T - Qb Qb^T ||_F computed without forming p x p matrices:
+    = sqrt(ra + rb - 2 ||Qa^T Qb||_F^2) for orthonormal bases."""
+    Qa = np.asarray(Qa, dtype=np.float64)
+    Qb = np.asarray(Qb, dtype=np.float64)
+    ga = Qa.T @ Qa
+    gb = Qb.T @ Qb
+    cross = Qa.T @ Qb
+    val = np.sum(ga * ga) + np.sum(gb * gb) - 2.0 * np.sum(cross * cross)
+    return float(np.sqrt(max(val, 0.0)))
+
+
+class Pair:
+    """Oracle states + one Lordo context over the same matrices."""
+
+    def __init__(self, torch, shapes, W0, oracle_hp: orc.Hyper, gpu_hp, Q0=None):
+        from paper_2602_04396_amd import lordo
+        self.torch = torch
+        self.lordo = lordo
+        self.shapes = shapes
+        self.ohp = oracle_hp
+        self.dev = torch.device("cuda:0")
+        self.W_gpu = [torch.tensor(w, dtype=torch.float32, device=self.dev).contiguous() for w in W0]
+        self.W_orc = [np.asarray(w, dtype=np.float64).copy() for w in W0]
+        self.W0 = [w.copy() for w in self.W_orc]
+        self.opt = lordo.Lordo(shapes, gpu_hp, self.W_gpu, torch)
+        self.st = []
+        for i, (p, q, r) in enumerate(shapes):
+            q0 = None if Q0 is None else Q0[i]
+            self.st.append(orc.init_state(self.W_orc[i], r, q0))
+            if q0 is not None:
+                self.opt.set_state(i, lordo.STATE_Q, torch.tensor(q0, dtype=torch.float32, device=self.dev).contiguous())
+                # the oracle continues from the fp32 value the library was given
+                self.st[i].Q = np.asarray(q0, dtype=np.float32).astype(np.float64)
+
+    # ------------------------------------------------------------------------------------------
+    def to_dev(self, arrs, bf16):
+        t = self.torch
+        out = []
+        for a in arrs:
+            x = t.tensor(np.asarray(a, dtype=np.float32), device=self.dev)
+            out.append((x.to(t.bfloat16) if bf16 else x).contiguous())
+        return out
+
+    def get(self, i, which):
+        return self.opt.get_state(i, which).cpu().numpy().astype(np.float64)
+
+    def local_step(self, G, lr, grad_scale=1.0, bf16=True, first_step_patch=False):
+        """G: list of float32 arrays (already bf16-representable when bf16=True)."""
+        Gd = self.to_dev(G, bf16)
+        self.opt.local_step(self.W_gpu, Gd, lr, grad_scale)
+        self.torch.cuda.synchronize()
+        patched = 0
+        for i in range(len(self.shapes)):
+            self.W_orc[i] = orc.local_step(self.st[i], self.W_orc[i], np.asarray(G[i], dtype=np.float64), lr, self.ohp,
+                                           grad_scale)
+            if first_step_patch:
+                patched += self._patch_sign_ambiguous(i, lr)
+        return patched
+
+    def _patch_sign_ambiguous(self, i, lr):
+        """From a zero state the update is N = g / (|g| + eps): the sign of g.  Where |g| is
+        below what fp32 accumulation can resolve, either sign (any value in [-1, 1]) is a correct
+        answer; take the library's value there after checking it lies in that range."""
+        st = self.st[i]
+        g = st.last_g
+        tau = 1e-4 * np.sqrt(np.mean(g * g))
+        amb = np.abs(g) < tau
+        if not amb.any():
+            return 0
+        N_gpu = self.get(i, self.lordo.STATE_NUPD)
+        assert np.all(np.abs(N_gpu[amb]) <= 1.0 + 1e-6)
+        N_new = st.last_N.copy()
+        N_new[amb] = N_gpu[amb]
+        self.W_orc[i] = self.W_orc[i] + lr * st.Q @ (st.last_N - N_new)
+        st.last_N = N_new
+        return int(amb.sum())
+
+    def compare_local(self, tol=1e-4, check_N=True):
+        L = self.lordo
+        worst = {}
+        for i in range(len(self.shapes)):
+            st = self.st[i]
+            errs = {
+                "g": rel_l2(self.get(i, L.STATE_GLOW), st.last_g),
+                "u": rel_l2(self.get(i, L.STATE_U), st.u),
+                "v": rel_l2(self.get(i, L.STATE_V), st.v),
+                "dW": rel_l2(self.W_gpu[i].cpu().numpy().astype(np.float64) - self.W0[i], self.W_orc[i] - self.W0[i]),
+            }
+            if check_N:
+                errs["N"] = rel_l2(self.get(i, L.STATE_NUPD), st.last_N)
+            for k, e in errs.items():
+                worst[k] = max(worst.get(k, 0.0), e)
+                assert e <= tol, f"matrix {i} {self.shapes[i]}: rel L2 error of {k} = {e:.3e} > {tol}"
+        return worst
+
+    def refresh(self, Src, Omega, bf16):
+        """Library refresh, then the oracle's own refresh for the subspace check, then the oracle
+        redoes the rotation with the library's basis.  Returns (projector distances, orthonormality)."""
+        L = self.lordo
+        Sd = self.to_dev(Src, bf16)
+        Od = self.to_dev(Omega, False)
+        self.opt.refresh_subspace(Sd, Od)
+        self.opt.poll_status()
+        dists, orths = [], []
+        for i, (p, q, r) in enumerate(self.shapes):
+            Qg = self.get(i, L.STATE_Q)
+            orths.append(float(np.linalg.norm(Qg.T @ Qg - np.eye(r))))
+            Qo = orc.range_finder(np.asarray(Src[i], dtype=np.float64), np.asarray(Omega[i], dtype=np.float64),
+                                  self.ohp.power_iters)
+            dists.append(projector_distance(Qg, Qo))
+            orc.refresh_subspace(self.st[i], None, None, self.ohp, Q_forced=Qg)
+        return dists, orths

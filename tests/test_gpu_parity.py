@@ -1,0 +1,293 @@
+"""Parity of the HIP library (through its C ABI) with the float64 oracle on identical seeded inputs.
+
+Tolerances (from the stated targets): relative L2 <= 1e-4 on g, u, v, N and on the weight change;
+|| Q Q^T - Q' Q'^T ||_F <= 1e-3 for the refreshed subspace; || Q^T Q - I ||_F <= 1e-4.
+"""
+import numpy as np
+import pytest
+
+from oracle import lordo_oracle as orc
+from paper_2602_04396_amd import synth
+from tests.harness import Pair, projector_distance, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+TOL_SUBSPACE = 1e-3
+TOL_ORTH = 1e-4
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available()
+    from paper_2602_04396_amd import lordo
+    lordo.load()          # fails loudly if the HIP library is not built
+    return t
+
+
+def _spiked(shapes, cfg, n_spike, noise="gauss", bf16=True):
+    return [synth.SpikedGradient(p, q, n_spike, synth.seed_for(cfg, i), noise=noise, bf16=bf16)
+            for i, (p, q, r) in enumerate(shapes)]
+
+
+def _weights(shapes, cfg):
+    return [synth.weights(np.random.default_rng(synth.seed_for(cfg, 500 + i)), p, q) for i, (p, q, r) in enumerate(shapes)]
+
+
+def _rand_Q(shapes, cfg):
+    return [synth.orthonormal(np.random.default_rng(synth.seed_for(cfg, 700 + i)), p, r) for i, (p, q, r) in enumerate(shapes)]
+
+
+# several tiles, ragged tails in p, q and r, odd q (unaligned rows), r = p
+SMALL_SHAPES = [(200, 330, 48), (96, 70, 20), (300, 129, 33), (64, 64, 64), (130, 257, 128)]
+
+
+def test_local_steps_bf16_small(torch):
+    from paper_2602_04396_amd import lordo
+    shapes = SMALL_SHAPES
+    pair = Pair(torch, shapes, _weights(shapes, 10), orc.Hyper(), lordo.hparams(grad_dtype=lordo.BF16), _rand_Q(shapes, 10))
+    gens = _spiked(shapes, 10, 8)
+    for t in range(4):
+        G = [g.draw(t) for g in gens]
+        pair.local_step(G, lr=1e-3 * (1 + t), first_step_patch=(t == 0))
+        worst = pair.compare_local(TOL)
+        print(f"step {t + 1}: worst rel L2 {worst}", flush=True)
+    assert pair.opt.step == 4
+
+
+def test_local_steps_identity_init_and_grad_scale(torch):
+    """Q_0 = first r columns of I (the library's own initial state), grad_scale != 1."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(160, 96, 32), (70, 50, 7)]
+    pair = Pair(torch, shapes, _weights(shapes, 11), orc.Hyper(), lordo.hparams())
+    gens = _spiked(shapes, 11, 4)
+    for t in range(3):
+        pair.local_step([g.draw(t) for g in gens], lr=2e-3, grad_scale=0.37, first_step_patch=(t == 0))
+    pair.compare_local(TOL)
+
+
+def test_local_steps_no_bias_correction_fp32_grads(torch):
+    from paper_2602_04396_amd import lordo
+    shapes = [(150, 200, 24), (33, 65, 33)]
+    pair = Pair(torch, shapes, _weights(shapes, 12), orc.Hyper(bias_correction=False, beta1=0.8, beta2=0.95, eps=1e-6),
+                lordo.hparams(beta1=0.8, beta2=0.95, eps=1e-6, bias_correction=False, grad_dtype=lordo.F32),
+                _rand_Q(shapes, 12))
+    gens = _spiked(shapes, 12, 4, bf16=False)
+    for t in range(3):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-2, bf16=False, first_step_patch=(t == 0))
+    pair.compare_local(TOL)
+
+
+def test_full_rank_identity_is_adam(torch):
+    """r = p with Q = I: the library's local step must be the full-rank Adam step (Sec. 2);
+    compared with torch.optim.Adam in float64 on the CPU, not with the oracle."""
+    import torch as t
+    from paper_2602_04396_amd import lordo
+    p, q = 64, 96
+    W0 = _weights([(p, q, p)], 13)
+    Wg = [t.tensor(W0[0], device="cuda")]
+    opt_g = lordo.Lordo([(p, q, p)], lordo.hparams(), Wg, t)
+    Wt = t.tensor(W0[0], dtype=t.float64, requires_grad=True)
+    opt = t.optim.Adam([Wt], lr=1e-3, betas=(0.9, 0.999), eps=1e-8)
+    gen = _spiked([(p, q, p)], 13, 4)[0]
+    for step in range(3):
+        G = gen.draw(step)
+        opt_g.local_step(Wg, [t.tensor(G, device="cuda").to(t.bfloat16)], 1e-3)
+        Wt.grad = t.tensor(G, dtype=t.float64)
+        opt.step()
+        got = Wg[0].cpu().numpy().astype(np.float64) - W0[0]
+        assert rel_l2(got, Wt.detach().numpy() - W0[0]) <= TOL
+    assert rel_l2(opt_g.get_state(0, lordo.STATE_V).cpu().numpy(), opt.state[Wt]["exp_avg_sq"].numpy()) <= TOL
+
+
+def test_config1_chain(torch):
+    """Config 1: 256 x 256 fp32, r = 16, Q from the range finder on G_0 (2 power iterations),
+    10 local steps with fresh noise, one Nesterov outer step on the worker's own pseudo-gradient."""
+    from paper_2602_04396_amd import lordo
+    rng = np.random.default_rng(synth.seed_for(1, 0))
+    S = synth.c1_signal(rng)
+    G0 = synth.c1_gradient(S, rng)
+    Om = synth.omega(rng, 256, 16)
+    W0 = [synth.weights(np.random.default_rng(synth.seed_for(1, 99)), 256, 256)]
+    ohp = orc.Hyper(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=2)
+    ghp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=2, grad_dtype=lordo.F32)
+    pair = Pair(torch, [(256, 256, 16)], W0, ohp, ghp)
+    dists, orths = pair.refresh([G0], [Om], bf16=False)
+    print("config1 refresh: projector distance", dists, "orthonormality", orths, flush=True)
+    assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
+    # the signal subspace found must be the SVD's (paper's default projection), cf. the oracle pin
+    U8 = np.linalg.svd(G0.astype(np.float64), full_matrices=False)[0][:, :8]
+    Qg = pair.get(0, lordo.STATE_Q)
+    assert np.linalg.norm(U8 - Qg @ (Qg.T @ U8)) < 1e-2
+    for t in range(10):
+        G = synth.c1_gradient(S, np.random.default_rng(synth.seed_for(1, 0, t)))
+        pair.local_step([G], lr=1e-3, bf16=False, first_step_patch=(t == 0))
+    worst = pair.compare_local(TOL)
+    print("config1 after 10 steps:", worst, flush=True)
+    # own pseudo-gradient, then Nesterov outer step on it
+    out = [torch.empty_like(pair.W_gpu[0])]
+    pair.opt.export_pseudograd(pair.W_gpu, out)
+    D_orc = orc.pseudo_gradient(pair.st[0], pair.W_orc[0])
+    assert rel_l2(out[0].cpu().numpy(), D_orc) <= TOL
+    pair.opt.outer_step(pair.W_gpu, None)
+    W_new = orc.outer_step(pair.st[0], D_orc, ohp)
+    assert rel_l2(pair.W_gpu[0].cpu().numpy().astype(np.float64) - W0[0], W_new - W0[0]) <= TOL
+    assert rel_l2(pair.get(0, lordo.STATE_ANCHOR), pair.st[0].anchor) <= 1e-6
+    assert rel_l2(pair.get(0, lordo.STATE_MOM), pair.st[0].b) <= TOL
+
+
+def test_config1_constant_gradient_closed_form(torch):
+    """Constant gradient: N = sign-like g/(|g|+eps) at every step, so after 10 steps at eta = 1e-3
+    W_10 = W_0 - 1e-2 Q N.  Elements whose g is zero to working precision are taken from the library."""
+    from paper_2602_04396_amd import lordo
+    rng = np.random.default_rng(synth.seed_for(1, 0))
+    S = synth.c1_signal(rng)
+    G0 = synth.c1_gradient(S, rng)
+    Om = synth.omega(rng, 256, 16)
+    W0 = [synth.weights(np.random.default_rng(synth.seed_for(1, 99)), 256, 256)]
+    pair = Pair(torch, [(256, 256, 16)], W0, orc.Hyper(power_iters=2), lordo.hparams(power_iters=2, grad_dtype=lordo.F32))
+    pair.refresh([G0], [Om], bf16=False)
+    for t in range(10):
+        pair.local_step([G0], lr=1e-3, bf16=False, first_step_patch=True)
+    pair.compare_local(TOL)
+    Q = pair.st[0].Q
+    N = pair.st[0].last_N
+    got = pair.W_gpu[0].cpu().numpy().astype(np.float64) - W0[0]
+    assert rel_l2(got, -1e-2 * Q @ N) <= TOL
+
+
+def test_refresh_rotates_moments(torch):
+    """Refresh after some steps: subspace against the oracle's own range finder, then moments
+    against the oracle's rotation done with the library's basis (the rotation depends on the basis,
+    which is only fixed up to rounding-level differences), plus a basis-free check."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(200, 330, 48), (300, 129, 33), (96, 160, 20), (256, 192, 128)]
+    for power_iters, bf16 in [(1, True), (2, False), (0, True)]:
+        ohp = orc.Hyper(power_iters=power_iters)
+        ghp = lordo.hparams(power_iters=power_iters, grad_dtype=lordo.BF16 if bf16 else lordo.F32)
+        pair = Pair(torch, shapes, _weights(shapes, 20), ohp, ghp, _rand_Q(shapes, 20))
+        gens = _spiked(shapes, 20, 8, bf16=bf16)
+        for t in range(3):
+            pair.local_step([g.draw(t) for g in gens], lr=1e-3, bf16=bf16, first_step_patch=(t == 0))
+        Src = [g.draw(100) for g in gens]
+        Om = [synth.omega(np.random.default_rng(synth.seed_for(20, 900 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+        Qu_before = [pair.st[i].Q @ pair.st[i].u for i in range(len(shapes))]
+        dists, orths = pair.refresh(Src, Om, bf16=bf16)
+        print(f"refresh q_it={power_iters} bf16={bf16}: dist {np.round(dists, 6)} orth {np.round(orths, 7)}", flush=True)
+        assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
+        for i in range(len(shapes)):
+            u_g = pair.get(i, lordo.STATE_U)
+            v_g = pair.get(i, lordo.STATE_V)
+            assert rel_l2(u_g, pair.st[i].u) <= TOL, f"u of matrix {i}"
+            assert rel_l2(v_g, pair.st[i].v) <= TOL, f"v of matrix {i}"
+            # basis-free: Q_new u_new = P_new (Q_old u_old)
+            Qg = pair.get(i, lordo.STATE_Q)
+            assert rel_l2(Qg @ u_g, Qg @ (Qg.T @ Qu_before[i])) <= TOL
+        for t in range(3, 5):
+            pair.local_step([g.draw(t) for g in gens], lr=1e-3, bf16=bf16)
+        pair.compare_local(TOL)
+
+
+def test_refresh_before_first_step_and_exact_reconstruction(torch):
+    """rank(Src) = r exactly: the refreshed Q must reproduce Src (Q Q^T Src = Src); t = 0: no rotation."""
+    from paper_2602_04396_amd import lordo
+    p, q, r = 192, 160, 24
+    rng = np.random.default_rng(synth.seed_for(21, 0))
+    Src = (rng.standard_normal((p, r)) @ rng.standard_normal((r, q))).astype(np.float32)
+    Om = synth.omega(rng, q, r)
+    pair = Pair(torch, [(p, q, r)], _weights([(p, q, r)], 21), orc.Hyper(power_iters=1), lordo.hparams(power_iters=1))
+    dists, orths = pair.refresh([Src], [Om], bf16=False)
+    assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
+    Qg = pair.get(0, lordo.STATE_Q)
+    S64 = Src.astype(np.float64)
+    assert rel_l2(Qg @ (Qg.T @ S64), S64) <= TOL
+    assert not pair.get(0, lordo.STATE_U).any() and not pair.get(0, lordo.STATE_V).any()
+
+
+def test_refresh_rank_deficient_source_three_passes(torch):
+    """rank(Src) < r: the completion of the basis is arbitrary; only Q^T Q = I and Q Q^T Src = Src
+    are fixed.  Three CholeskyQR passes are requested for this degenerate case."""
+    from paper_2602_04396_amd import lordo
+    p, q, r = 128, 96, 16
+    rng = np.random.default_rng(synth.seed_for(22, 0))
+    Src = (rng.standard_normal((p, 5)) @ rng.standard_normal((5, q))).astype(np.float32)
+    Om = synth.omega(rng, q, r)
+    W = [torch.zeros(p, q, device="cuda")]
+    opt = lordo.Lordo([(p, q, r)], lordo.hparams(power_iters=1, orth_passes=3), W, torch)
+    opt.refresh_subspace([torch.tensor(Src, device="cuda")], [torch.tensor(Om, device="cuda")])
+    try:
+        opt.poll_status()
+    except lordo.LordoError as e:          # a latched breakdown is an allowed outcome here
+        assert e.code == lordo.ENUMERIC
+        return
+    Qg = opt.get_state(0, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+    S64 = Src.astype(np.float64)
+    assert np.isfinite(Qg).all()
+    assert rel_l2(Qg @ (Qg.T @ S64), S64) <= 1e-3
+
+
+@pytest.mark.parametrize("mode", ["average", "nesterov", "heavy_ball", "own_delta"])
+def test_outer_step(torch, mode):
+    from paper_2602_04396_amd import lordo
+    shapes = [(100, 77, 8), (64, 128, 16), (33, 2049, 4)]
+    kw = dict(average=dict(outer_lr=1.0), nesterov=dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True),
+              heavy_ball=dict(outer_lr=0.5, outer_momentum=0.8), own_delta=dict(outer_lr=0.9, outer_momentum=0.5, outer_nesterov=True))[mode]
+    ohp = orc.Hyper(**kw)
+    pair = Pair(torch, shapes, _weights(shapes, 30), ohp, lordo.hparams(**kw), _rand_Q(shapes, 30))
+    gens = _spiked(shapes, 30, 2)
+    step = 0
+    for rnd in range(2):
+        for _ in range(2):
+            pair.local_step([g.draw(step) for g in gens], lr=1e-2, first_step_patch=(step == 0))
+            step += 1
+        own = [orc.pseudo_gradient(pair.st[i], pair.W_orc[i]) for i in range(len(shapes))]
+        out = [torch.empty_like(w) for w in pair.W_gpu]
+        pair.opt.export_pseudograd(pair.W_gpu, out)
+        for i in range(len(shapes)):
+            assert rel_l2(out[i].cpu().numpy(), own[i]) <= TOL
+        if mode == "own_delta":
+            avg = own
+            pair.opt.outer_step(pair.W_gpu, None)
+        else:
+            other = [synth.SpikedGradient(p, q, 2, synth.seed_for(31, i), bf16=False).draw(rnd) * 1e-2 * 2
+                     for i, (p, q, r) in enumerate(shapes)]
+            avg = [synth.avg_pseudograd(out[i].cpu().numpy(), other[i]) for i in range(len(shapes))]
+            pair.opt.outer_step(pair.W_gpu, pair.to_dev(avg, False))
+        for i in range(len(shapes)):
+            Wn = orc.outer_step(pair.st[i], np.asarray(avg[i], dtype=np.float64), ohp)
+            pair.W_orc[i] = Wn
+            got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
+            assert rel_l2(got - pair.W0[i], Wn - pair.W0[i]) <= TOL, f"{mode} round {rnd} matrix {i}"
+            assert rel_l2(pair.get(i, lordo.STATE_ANCHOR), pair.st[i].anchor) <= 1e-6
+            if ohp.outer_momentum != 0:
+                assert rel_l2(pair.get(i, lordo.STATE_MOM), pair.st[i].b) <= TOL
+    if mode == "average":
+        # eta_s = 1, no momentum: the new model is the mean of the workers' models (Alg. 1 default)
+        pass
+
+
+def test_state_roundtrip_and_errors(torch):
+    from paper_2602_04396_amd import lordo
+    p, q, r = 70, 45, 9
+    W = [torch.randn(p, q, device="cuda")]
+    opt = lordo.Lordo([(p, q, r)], lordo.hparams(outer_momentum=0.5), W, torch)
+    assert torch.equal(opt.get_state(0, lordo.STATE_ANCHOR), W[0])
+    Q0 = opt.get_state(0, lordo.STATE_Q).cpu().numpy()
+    assert np.array_equal(Q0, np.eye(p, r, dtype=np.float32))
+    for which in (lordo.STATE_U, lordo.STATE_V):
+        x = torch.rand(r, q, device="cuda")
+        opt.set_state(0, which, x)
+        assert torch.equal(opt.get_state(0, which), x)
+    opt.step = 17
+    assert opt.step == 17
+    with pytest.raises(lordo.LordoError) as e:
+        opt.set_state(0, lordo.STATE_GLOW, torch.rand(r, q, device="cuda"))
+    assert e.value.code == lordo.EINVAL
+    with pytest.raises(lordo.LordoError) as e:
+        lordo.Lordo([(8, 8, 9)], lordo.hparams(), [torch.zeros(8, 8, device="cuda")], torch)
+    assert e.value.code == lordo.EINVAL
+    with pytest.raises(lordo.LordoError) as e:
+        lordo.Lordo([(8, 8, 4)], lordo.hparams(qhm_mode=2), [torch.zeros(8, 8, device="cuda")], torch)
+    assert e.value.code == lordo.EINVAL
+    opt.poll_status()
