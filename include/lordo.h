@@ -138,6 +138,19 @@ int lordo_set_step(lordo_ctx* ctx, int64_t t);
  * last poll (the latch is cleared), else LORDO_OK. */
 int lordo_poll_status(lordo_ctx* ctx, void* stream);
 
+/* Measurement aid: with profiling on, every kernel class below is bracketed by a pair of HIP events
+ * on the caller's stream (a few microseconds of overhead per launch).  lordo_profile_read
+ * synchronises `stream` and returns the summed event time and the number of spans of one class
+ * since profiling was last enabled.  Enabling again, or disabling, discards the record. */
+#define LORDO_K_DOWN    0   /* down-projection GEMM,   one span per lordo_local_step            */
+#define LORDO_K_ADAM    1   /* fused low-rank Adam,    one span per lordo_local_step            */
+#define LORDO_K_UP      2   /* up-projection + apply,  one span per lordo_local_step            */
+#define LORDO_K_OUTER   3   /* outer-step kernel,      one span per lordo_outer_step            */
+#define LORDO_K_EXPORT  4   /* pseudo-gradient kernel, one span per lordo_export_pseudograd     */
+#define LORDO_K_REFRESH 5   /* every kernel of one lordo_refresh_subspace call, as one span     */
+int lordo_profile_enable(lordo_ctx* ctx, int32_t on);
+int lordo_profile_read(lordo_ctx* ctx, int32_t kernel_class, double* total_ms, int64_t* launches, void* stream);
+
 const char* lordo_strerror(int code);
 
 /* Frees host-side bookkeeping only (the arena is the caller's).  NULL is allowed. */

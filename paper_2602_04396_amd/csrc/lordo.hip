@@ -341,7 +341,43 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
 
 }  // namespace
 
+constexpr int NUM_KCLASS = 8;
+
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> pool;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> spans[NUM_KCLASS];
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  void begin(int k, hipStream_t s) {
+    if (!on) return;
+    hipEvent_t a = get(), b = get();
+    if (!a || !b) return;
+    (void)hipEventRecord(a, s);
+    spans[k].push_back({a, b});
+  }
+  void end(int k, hipStream_t s) {
+    if (!on || spans[k].empty()) return;
+    (void)hipEventRecord(spans[k].back().second, s);
+  }
+  void clear() {
+    for (auto& v : spans) {
+      for (auto& pr : v) { pool.push_back(pr.first); pool.push_back(pr.second); }
+      v.clear();
+    }
+  }
+  ~Profiler() {
+    clear();
+    for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+  }
+};
+
 struct lordo_ctx {
+  Profiler prof;
   int n = 0;
   lordo_hparams hp{};
   Plan plan;
@@ -463,12 +499,18 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   a.inv_c1 = (float)(1.0 / c1); a.inv_c2 = (float)(1.0 / c2);
   a.eps = (float)c->hp.eps;
   a.nsplit = P.nsplit; a.split_stride = P.lr_total;
+  c->prof.begin(LORDO_K_DOWN, s);
   HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, c->at<float>(P.glow),
                           P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
+  c->prof.end(LORDO_K_DOWN, s);
+  c->prof.begin(LORDO_K_ADAM, s);
   HIPCHK(launch_adam(c->at<float>(P.glow), c->at<float>(P.u), c->at<float>(P.v), c->at<uint16_t>(P.n_hi),
                      c->at<uint16_t>(P.n_lo), P.lr_total, a, s));
+  c->prof.end(LORDO_K_ADAM, s);
+  c->prof.begin(LORDO_K_UP, s);
   HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), c->at<uint16_t>(P.n_hi),
                         c->at<uint16_t>(P.n_lo), (float)lr, s));
+  c->prof.end(LORDO_K_UP, s);
   c->t = t;
   return LORDO_OK;
 }
@@ -490,6 +532,7 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   }
   const GemmDesc* descs = c->at<GemmDesc>(P.descs);
   const GemmTile* tiles = c->at<GemmTile>(P.gtiles);
+  c->prof.begin(LORDO_K_REFRESH, s);
   for (const Op& op : P.ops) {
     if (op.rot_only && !rotate) continue;
     switch (op.kind) {
@@ -509,6 +552,7 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
       default: return LORDO_ESTATE;
     }
   }
+  c->prof.end(LORDO_K_REFRESH, s);
   return LORDO_OK;
 }
 
@@ -519,7 +563,9 @@ int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* Del
   if (rc != LORDO_OK) return rc;
   rc = c->set_ext(EXT_DOUT, DeltaOut, s);
   if (rc != LORDO_OK) return rc;
+  c->prof.begin(LORDO_K_EXPORT, s);
   HIPCHK(launch_export_delta(c->dev, c->at<int64_t>(c->plan.chunk_start), c->plan.nchunks, s));
+  c->prof.end(LORDO_K_EXPORT, s);
   return LORDO_OK;
 }
 
@@ -538,7 +584,9 @@ int lordo_outer_step(lordo_ctx* c, void* const* W, const void* const* AvgDelta, 
     rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(AvgDelta)), s);
     if (rc != LORDO_OK) return rc;
   }
+  c->prof.begin(LORDO_K_OUTER, s);
   HIPCHK(launch_outer(c->dev, c->at<int64_t>(c->plan.chunk_start), c->plan.nchunks, a, s));
+  c->prof.end(LORDO_K_OUTER, s);
   return LORDO_OK;
 }
 
@@ -612,6 +660,28 @@ int lordo_poll_status(lordo_ctx* c, void* stream) {
     HIPCHK(hipStreamSynchronize(s));
     return LORDO_ENUMERIC;
   }
+  return LORDO_OK;
+}
+
+int lordo_profile_enable(lordo_ctx* c, int32_t on) {
+  if (!c) return LORDO_EINVAL;
+  c->prof.clear();
+  c->prof.on = on != 0;
+  return LORDO_OK;
+}
+
+int lordo_profile_read(lordo_ctx* c, int32_t kernel_class, double* total_ms, int64_t* launches, void* stream) {
+  if (!c || !total_ms || !launches || kernel_class < 0 || kernel_class >= NUM_KCLASS) return LORDO_EINVAL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  HIPCHK(hipStreamSynchronize(s));
+  double sum = 0.0;
+  for (auto& pr : c->prof.spans[kernel_class]) {
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, pr.first, pr.second));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)c->prof.spans[kernel_class].size();
   return LORDO_OK;
 }
 

@@ -20,7 +20,9 @@ EXPORTS = [
     "lordo_workspace_bytes", "lordo_init", "lordo_local_step", "lordo_refresh_subspace",
     "lordo_export_pseudograd", "lordo_outer_step", "lordo_get_state", "lordo_set_state",
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
+    "lordo_profile_enable", "lordo_profile_read",
 ]
+K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
 
 class Shape(C.Structure):
@@ -75,6 +77,8 @@ def load() -> C.CDLL:
     lib.lordo_get_step.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.lordo_set_step.argtypes = [vp, C.c_int64]
     lib.lordo_poll_status.argtypes = [vp, vp]
+    lib.lordo_profile_enable.argtypes = [vp, C.c_int32]
+    lib.lordo_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     lib.lordo_strerror.argtypes = [C.c_int]
     lib.lordo_strerror.restype = C.c_char_p
     lib.lordo_destroy.argtypes = [vp]
@@ -91,7 +95,18 @@ def _check(code):
         raise LordoError(code, load().lordo_strerror(code).decode())
 
 
+class PtrList:
+    """Pointer array of an already validated tensor list, reusable across calls (keeps the
+    tensors alive).  Built by Lordo.ptrs(); lets a tight loop skip per-call validation."""
+
+    def __init__(self, tensors, arr):
+        self.tensors = tensors
+        self.arr = arr
+
+
 def _ptr_array(tensors):
+    if isinstance(tensors, PtrList):
+        return tensors.arr
     arr = (C.c_void_p * len(tensors))()
     for i, t in enumerate(tensors):
         arr[i] = t.data_ptr()
@@ -135,7 +150,14 @@ class Lordo:
     def _stream(self):
         return C.c_void_p(self.torch.cuda.current_stream().cuda_stream)
 
+    def ptrs(self, tensors, dtype=None, kind="pq") -> PtrList:
+        """Validate a tensor list once and freeze its device pointers for repeated calls."""
+        self._check_tensors(tensors, dtype or self.torch.float32, kind)
+        return PtrList(list(tensors), _ptr_array(tensors))
+
     def _check_tensors(self, ts, dtype, kind):
+        if isinstance(ts, PtrList):
+            return
         if len(ts) != self.n:
             raise ValueError("one tensor per matrix expected")
         for t, (p, q, r) in zip(ts, self.shapes):
@@ -153,7 +175,7 @@ class Lordo:
         _check(self.lib.lordo_local_step(self.ctx, _ptr_array(W), _ptr_array(G), float(lr), float(grad_scale), self._stream()))
 
     def refresh_subspace(self, Src, Omega):
-        dt = Src[0].dtype
+        dt = (Src.tensors if isinstance(Src, PtrList) else Src)[0].dtype
         self._check_tensors(Src, dt, "pq")
         self._check_tensors(Omega, self.torch.float32, "qr")
         code = BF16 if dt == self.torch.bfloat16 else F32
@@ -202,6 +224,15 @@ class Lordo:
 
     def poll_status(self):
         _check(self.lib.lordo_poll_status(self.ctx, self._stream()))
+
+    def profile_enable(self, on=True):
+        _check(self.lib.lordo_profile_enable(self.ctx, int(on)))
+
+    def profile_read(self, kernel_class):
+        """(total milliseconds, number of spans) of one kernel class since profiling was enabled."""
+        ms, cnt = C.c_double(0), C.c_int64(0)
+        _check(self.lib.lordo_profile_read(self.ctx, kernel_class, C.byref(ms), C.byref(cnt), self._stream()))
+        return ms.value, cnt.value
 
     def close(self):
         if self.ctx:
