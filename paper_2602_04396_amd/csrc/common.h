@@ -71,13 +71,20 @@ struct GemmDesc {
 struct GemmTile { int32_t desc; int16_t tm, tn; };
 
 // Device-side view handed to kernels.
+constexpr int EXT_SLOTS = 8;     // cached pointer tables per kind (e.g. alternating gradient buffers)
+
 struct DevCtx {
   char* arena;
   const MatDev* mats;
-  void* const* ext;       // EXT_COUNT * n pointers: ext[table * n + mat]
+  void* const* ext;       // EXT_COUNT * EXT_SLOTS tables of n pointers each
   int32_t n;
   int32_t* flag;          // numerical breakdown latch
+  int32_t slot[EXT_COUNT];  // table (absolute index) each kind uses in this launch
 };
+
+__device__ __forceinline__ void* ext_ptr(const DevCtx& d, int table, int mat) {
+  return d.ext[(int64_t)d.slot[table] * d.n + mat];
+}
 
 constexpr int CHUNK = 2048;       // elements per workgroup of the p x q elementwise kernels
 constexpr int NB = 64;            // Cholesky / triangular-solve block size
@@ -94,7 +101,13 @@ hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, co
 hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int src_is_bf16,
                          hipStream_t s);
 // elementwise.hip
-struct AdamArgs { float b1, omb1, b2, omb2, inv_c1, inv_c2, eps; int32_t nsplit; int64_t split_stride; };
+// Elements at flat position >= grp_start[i] are the sum of grp_nsplit[i] split-K slices of g.
+struct AdamArgs {
+  float b1, omb1, b2, omb2, inv_c1, inv_c2, eps;
+  int32_t grp_nsplit[4];
+  int64_t grp_start[4];
+  int64_t split_stride;
+};
 hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
                        const AdamArgs& a, hipStream_t s);
 hipError_t launch_store_ptrs(void** dst, void* const* host_src, int count, hipStream_t s);
@@ -115,7 +128,7 @@ hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float 
 hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s);
 // state exchange with plain row-major buffers (one matrix)
 hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, const uint16_t* n_hi, const uint16_t* n_lo,
-                              float* dst, hipStream_t s);
+                              float* dst, int nsplit, int64_t stride, hipStream_t s);
 hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s);
 
 }  // namespace lordo

@@ -38,7 +38,11 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
     const float4* gp = reinterpret_cast<const float4*>(glow + base);
     float4 a0 = gp[0], a1 = gp[1];
     g[0] = a0.x; g[1] = a0.y; g[2] = a0.z; g[3] = a0.w; g[4] = a1.x; g[5] = a1.y; g[6] = a1.z; g[7] = a1.w;
-    for (int sidx = 1; sidx < a.nsplit; ++sidx) {       // deterministic split-K reduction, fixed order
+    int nsplit = a.grp_nsplit[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+      if (base >= a.grp_start[i]) nsplit = a.grp_nsplit[i];
+    for (int sidx = 1; sidx < nsplit; ++sidx) {         // deterministic split-K reduction, fixed order
       const float4* sp = reinterpret_cast<const float4*>(glow + sidx * a.split_stride + base);
       float4 b0 = sp[0], b1 = sp[1];
       g[0] += b0.x; g[1] += b0.y; g[2] += b0.z; g[3] += b0.w; g[4] += b1.x; g[5] += b1.y; g[6] += b1.z; g[7] += b1.w;
@@ -228,11 +232,11 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
   const MatDev& m = d.mats[mat];
   int64_t total = (int64_t)m.p * m.q;
   int64_t off = (b - chunk_start[mat]) * CHUNK;
-  float* W = reinterpret_cast<float*>(d.ext[EXT_W * d.n + mat]);
+  float* W = reinterpret_cast<float*>(ext_ptr(d, EXT_W, mat));
   float* anchor = reinterpret_cast<float*>(d.arena + m.anchor);
   float* mom = a.has_mom ? reinterpret_cast<float*>(d.arena + m.mom) : nullptr;
-  const float* din = (MODE == 0 && !a.own_delta) ? reinterpret_cast<const float*>(d.ext[EXT_DIN * d.n + mat]) : nullptr;
-  float* dout = MODE == 1 ? reinterpret_cast<float*>(d.ext[EXT_DOUT * d.n + mat]) : nullptr;
+  const float* din = (MODE == 0 && !a.own_delta) ? reinterpret_cast<const float*>(ext_ptr(d, EXT_DIN, mat)) : nullptr;
+  float* dout = MODE == 1 ? reinterpret_cast<float*>(ext_ptr(d, EXT_DOUT, mat)) : nullptr;
   bool vec = (total % 4 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
              (din == nullptr || (reinterpret_cast<uintptr_t>(din) & 15) == 0) &&
              (dout == nullptr || (reinterpret_cast<uintptr_t>(dout) & 15) == 0);
@@ -468,18 +472,24 @@ hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float 
 // state exchange: blocked low-rank arrays <-> plain r x q row-major
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_lr_to_plain(DevCtx d, int mat, const float* lr_arr, const uint16_t* n_hi,
-                                                     const uint16_t* n_lo, float* dst) {
+                                                     const uint16_t* n_lo, float* dst, int nsplit, int64_t stride) {
   const MatDev& m = d.mats[mat];
   int64_t total = (int64_t)m.r * m.q;
   for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
     int64_t i = t / m.q, j = t % m.q;
     int64_t src = m.lr_off + bl_index(j, i, m.rp);
-    dst[t] = lr_arr ? lr_arr[src] : bf2f(n_hi[src]) + bf2f(n_lo[src]);
+    if (lr_arr) {
+      float acc = lr_arr[src];
+      for (int sp = 1; sp < nsplit; ++sp) acc += lr_arr[src + sp * stride];   // same order as the Adam kernel
+      dst[t] = acc;
+    } else {
+      dst[t] = bf2f(n_hi[src]) + bf2f(n_lo[src]);
+    }
   }
 }
 hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, const uint16_t* n_hi, const uint16_t* n_lo,
-                              float* dst, hipStream_t s) {
-  hipLaunchKernelGGL(k_lr_to_plain, dim3(256), dim3(256), 0, s, d, mat, lr_arr, n_hi, n_lo, dst);
+                              float* dst, int nsplit, int64_t stride, hipStream_t s) {
+  hipLaunchKernelGGL(k_lr_to_plain, dim3(256), dim3(256), 0, s, d, mat, lr_arr, n_hi, n_lo, dst, nsplit, stride);
   return hipGetLastError();
 }
 __global__ __launch_bounds__(256) void k_plain_to_lr(DevCtx d, int mat, float* lr_arr, const float* src) {

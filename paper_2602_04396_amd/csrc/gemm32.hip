@@ -21,7 +21,7 @@ __device__ __forceinline__ float load_elem(const char* base, int64_t idx, int is
 }
 
 __device__ __forceinline__ const char* resolve(const DevCtx& d, const OpRef& r, int mat) {
-  if (r.ext >= 0) return reinterpret_cast<const char*>(d.ext[r.ext * d.n + mat]) + r.off;
+  if (r.ext >= 0) return reinterpret_cast<const char*>(ext_ptr(d, r.ext, mat)) + r.off;
   return d.arena + r.off;
 }
 

@@ -38,7 +38,10 @@ struct Plan {
   int64_t lr_total = 0;             // elements of one flat low-rank array
   int64_t nchunks = 0;
   int mb = 4;
-  int nsplit = 1;
+  int nsplit = 1;                   // largest split-K factor of the down-projection
+  std::vector<int> splits;          // split-K factor per matrix (1, 2, 4 or 8)
+  int32_t grp_nsplit[4] = {1, 1, 1, 1};
+  int64_t grp_start[4] = {0, INT64_MAX, INT64_MAX, INT64_MAX};
   // global regions (byte offsets)
   int64_t flag, mats, ext, chunk_start, down_tiles, up_tiles, descs, gtiles, glow, u, v, n_hi, n_lo;
   std::vector<MatDev> mat;
@@ -268,28 +271,64 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   Alloc A;
   P.flag = A.take(256);
   P.mats = A.take(sizeof(MatDev) * n);
-  P.ext = A.take(sizeof(void*) * EXT_COUNT * n);
+  P.ext = A.take(sizeof(void*) * EXT_COUNT * EXT_SLOTS * n);
   P.chunk_start = A.take(sizeof(int64_t) * (n + 1));
   P.mat.resize(n);
   P.chunk_start_h.resize(n + 1);
   int64_t lr = 0, chunks = 0;
-  int rp_max = 0;
+  int rp_max = 0, pp_min = 1 << 30;
   const bool has_mom = hp.outer_momentum != 0.0;
   for (int i = 0; i < n; ++i) {
     MatDev& m = P.mat[i];
     m.p = (int)shapes[i].rows; m.q = (int)shapes[i].cols; m.r = shapes[i].rank;
     m.pp = (int)pad32(m.p); m.qp = (int)pad32(m.q); m.rp = (int)pad32(m.r);
-    m.lr_off = lr;
-    lr += (int64_t)m.qp * m.rp;
     rp_max = std::max(rp_max, m.rp);
+    pp_min = std::min(pp_min, m.pp);
     P.chunk_start_h[i] = chunks;
     chunks += ((int64_t)m.p * m.q + CHUNK - 1) / CHUNK;
   }
   P.chunk_start_h[n] = chunks;
   P.nchunks = chunks;
-  P.lr_total = lr;
   P.mb = rp_max > 64 ? 4 : (rp_max > 32 ? 2 : 1);
+  // Split-K of the down-projection.  With few output tiles (small models) the long contraction
+  // over p is cut into slices of about the shortest matrix's height, so that every workgroup
+  // has the same amount of work and the chip is filled; slices are summed, in fixed order, by
+  // the Adam kernel.  Factors are powers of two up to 8.
+  int64_t tiles0 = 0;
+  for (int i = 0; i < n; ++i)
+    tiles0 += (int64_t)((P.mat[i].qp + 127) / 128) * ((P.mat[i].rp + 32 * P.mb - 1) / (32 * P.mb));
+  P.splits.assign(n, 1);
   P.nsplit = 1;
+  if (tiles0 < 1536) {
+    int chunk = std::max(256, pp_min);
+    for (int i = 0; i < n; ++i) {
+      int want = (P.mat[i].pp + chunk - 1) / chunk;
+      int f = 1;
+      while (f * 2 <= want && f < 8) f *= 2;
+      P.splits[i] = f;
+      P.nsplit = std::max(P.nsplit, f);
+    }
+  }
+  // flat low-rank layout: matrices ordered by split factor, so that the Adam kernel knows the
+  // number of slices to sum from the flat position alone
+  {
+    int g = 0;
+    for (int f = 1; f <= 8; f *= 2) {
+      bool any = false;
+      for (int i = 0; i < n; ++i) {
+        if (P.splits[i] != f) continue;
+        if (!any) {
+          any = true;
+          P.grp_nsplit[g] = f;
+          P.grp_start[g] = g == 0 ? 0 : lr;
+        }
+        P.mat[i].lr_off = lr;
+        lr += (int64_t)P.mat[i].qp * P.mat[i].rp;
+      }
+      if (any) ++g;
+    }
+  }
+  P.lr_total = lr;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);
   P.v = A.take(sizeof(float) * lr);
@@ -314,12 +353,16 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   std::vector<ProjTile> down, up;
   for (int i = 0; i < n; ++i) {
     const MatDev& m = P.mat[i];
+    const int f = P.splits[i];
+    const int klen = ((m.pp + f - 1) / f + 31) / 32 * 32;
     for (int n0 = 0; n0 < m.qp; n0 += 128)
-      for (int m0 = 0; m0 < m.rp; m0 += 32 * P.mb) {
-        ProjTile t{};
-        t.mat = i; t.m0 = m0; t.n0 = n0; t.k0 = 0; t.k1 = m.pp; t.split = 0;
-        down.push_back(t);
-      }
+      for (int m0 = 0; m0 < m.rp; m0 += 32 * P.mb)
+        for (int sp = 0; sp < f; ++sp) {
+          ProjTile t{};
+          t.mat = i; t.m0 = m0; t.n0 = n0; t.split = sp;
+          t.k0 = std::min(sp * klen, m.pp); t.k1 = std::min(t.k0 + klen, m.pp);
+          down.push_back(t);
+        }
     for (int m0 = 0; m0 < m.pp; m0 += 128)
       for (int n0 = 0; n0 < m.qp; n0 += 128) {
         ProjTile t{};
@@ -384,8 +427,9 @@ struct lordo_ctx {
   DevCtx dev{};
   int64_t t = 0;
   int device = 0;
-  std::vector<void*> shadow[EXT_COUNT];
-  bool shadow_valid[EXT_COUNT] = {false, false, false, false, false, false};
+  // cached caller pointer tables: EXT_SLOTS per kind, replaced round-robin
+  std::vector<void*> shadow[EXT_COUNT][EXT_SLOTS];
+  int next_slot[EXT_COUNT] = {0, 0, 0, 0, 0, 0};
 
   template <class T>
   T* at(int64_t off) const { return reinterpret_cast<T*>(dev.arena + off); }
@@ -394,12 +438,19 @@ struct lordo_ctx {
     if (!host) return LORDO_EINVAL;
     for (int i = 0; i < n; ++i)
       if (!host[i]) return LORDO_EINVAL;
-    std::vector<void*>& sh = shadow[table];
-    if (shadow_valid[table] && std::memcmp(sh.data(), host, sizeof(void*) * n) == 0) return LORDO_OK;
-    void** dst = const_cast<void**>(dev.ext) + (size_t)table * n;
+    for (int k = 0; k < EXT_SLOTS; ++k) {
+      const std::vector<void*>& sh = shadow[table][k];
+      if (!sh.empty() && std::memcmp(sh.data(), host, sizeof(void*) * n) == 0) {
+        dev.slot[table] = table * EXT_SLOTS + k;
+        return LORDO_OK;
+      }
+    }
+    int k = next_slot[table];
+    next_slot[table] = (k + 1) % EXT_SLOTS;
+    void** dst = const_cast<void**>(dev.ext) + (size_t)(table * EXT_SLOTS + k) * n;
     HIPCHK(launch_store_ptrs(dst, host, n, s));
-    sh.assign(host, host + n);
-    shadow_valid[table] = true;
+    shadow[table][k].assign(host, host + n);
+    dev.slot[table] = table * EXT_SLOTS + k;
     return LORDO_OK;
   }
 };
@@ -444,6 +495,7 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
   c->dev.ext = c->at<void*>(P.ext);
   c->dev.n = n;
   c->dev.flag = c->at<int32_t>(P.flag);
+  for (int k = 0; k < EXT_COUNT; ++k) c->dev.slot[k] = k * EXT_SLOTS;
 #define INITCHK(expr)                                                                             \
   do {                                                                                            \
     hipError_t e_ = (expr);                                                                       \
@@ -464,7 +516,7 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
   // zero everything from the flat low-rank arrays to the end of the per-matrix regions except
   // the tables written above: state (u, v, g, N), momentum and scratch all start at zero
   INITCHK(launch_fill_zero(c->at<void>(P.flag), 256, s));
-  INITCHK(launch_fill_zero(c->at<void>(P.ext), ((sizeof(void*) * EXT_COUNT * n + 255) & ~size_t(255)), s));
+  INITCHK(launch_fill_zero(c->at<void>(P.ext), ((sizeof(void*) * EXT_COUNT * EXT_SLOTS * n + 255) & ~size_t(255)), s));
   INITCHK(launch_fill_zero(c->at<void>(P.glow), (int64_t)(P.down_tiles - P.glow), s));
   INITCHK(launch_identity_q(c->dev, s));
   INITCHK(launch_pack_q(c->dev, 0, n, s));
@@ -498,7 +550,8 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   a.b2 = (float)c->hp.beta2; a.omb2 = (float)(1.0 - c->hp.beta2);
   a.inv_c1 = (float)(1.0 / c1); a.inv_c2 = (float)(1.0 / c2);
   a.eps = (float)c->hp.eps;
-  a.nsplit = P.nsplit; a.split_stride = P.lr_total;
+  for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
+  a.split_stride = P.lr_total;
   c->prof.begin(LORDO_K_DOWN, s);
   HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, c->at<float>(P.glow),
                           P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
@@ -603,11 +656,13 @@ int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, voi
       if (m.mom < 0) return LORDO_ESTATE;
       HIPCHK(launch_copy_f32(dst, c->at<float>(m.mom), (int64_t)m.p * m.q, s));
       break;
-    case LORDO_STATE_U: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.u), nullptr, nullptr, dst, s)); break;
-    case LORDO_STATE_V: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.v), nullptr, nullptr, dst, s)); break;
-    case LORDO_STATE_GLOW: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.glow), nullptr, nullptr, dst, s)); break;
+    case LORDO_STATE_U: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.u), nullptr, nullptr, dst, 1, 0, s)); break;
+    case LORDO_STATE_V: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.v), nullptr, nullptr, dst, 1, 0, s)); break;
+    case LORDO_STATE_GLOW:
+      HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.glow), nullptr, nullptr, dst, P.splits[mat], P.lr_total, s));
+      break;
     case LORDO_STATE_NUPD:
-      HIPCHK(launch_lr_to_plain(c->dev, mat, nullptr, c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), dst, s));
+      HIPCHK(launch_lr_to_plain(c->dev, mat, nullptr, c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), dst, 1, 0, s));
       break;
     default: return LORDO_EINVAL;
   }

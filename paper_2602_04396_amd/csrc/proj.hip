@@ -9,14 +9,33 @@
 //   down:  acc += Qhi^T G + Qlo^T G                      (+ Qhi^T Glo for fp32 G)
 //   up:    acc += Qhi Nhi + Qhi Nlo + Qlo Nhi
 // Accumulation is fp32 in the matrix core.
+//
+// Caller matrices (G, W) are reached through buffer resources: the hardware range check returns
+// zero for reads past the end (rows beyond the matrix or beyond this workgroup's slice of the
+// contraction) and drops such writes, and a lane whose column is outside the matrix is given an
+// offset beyond the range.  No access is guarded by a branch.  Pointers into the arena are cast
+// to the global address space so that no access is a flat one.
 #include "common.h"
 
 namespace lordo {
 
+#define GAS __attribute__((address_space(1)))
+// generic -> global address space (a C-style cast; reinterpret_cast may not change address spaces)
+#define TO_GLOBAL(T, ptr) ((GAS T*)(ptr))
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// native vectors: the only vector types that can be read through address-space pointers
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ bf16x8 as_bf(uint4 x) { return __builtin_bit_cast(bf16x8, x); }
+__device__ __forceinline__ bf16x8 as_bf(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
+__device__ __forceinline__ u32x4 mk4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  u32x4 r;
+  r.x = a; r.y = b; r.z = c; r.w = d;
+  return r;
+}
 
 __device__ __forceinline__ uint32_t f2bf_rne(float x) {
   uint32_t u = __float_as_uint(x);
@@ -26,59 +45,69 @@ __device__ __forceinline__ uint32_t f2bf_rne(float x) {
 }
 
 constexpr int DBK = 32;        // rows of G per pipeline stage
-constexpr int DBN = 128;       // columns of G per workgroup
+
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+constexpr uint32_t OOB = 0x80000000u;        // byte offset beyond any resource (sizes are < 2 GiB)
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
 
 // ---------------------------------------------------------------------------------------
 // Down-projection.  Workgroup = 4 waves; output tile = (32*MB rank indices) x 128 columns.
 // Wave w owns rank block w % MB and MB column blocks starting at (w / MB) * MB.
 // The G tile (32 rows x 128 columns) is transposed in registers and staged in LDS in fragment
 // order: slot (nblk, kgrp, n) is the 16-byte vector G[k0 + 8*kgrp + 0..7][n0 + 32*nblk + n].
+// Each lane stages two adjacent columns of 8 consecutive rows.
 // ---------------------------------------------------------------------------------------
 template <bool GF32>
 struct GStage {
   uint32_t x[GF32 ? 16 : 8];   // bf16: row i -> two columns packed; fp32: row i -> two floats
 };
 
+// Column handling of one lane, fixed for the whole kernel: byte offsets of its two columns
+// inside a row (OOB if the column is outside the matrix).
+struct GCol {
+  uint32_t off0, off1;
+  bool vec;           // both columns with one aligned access
+};
+
+// Rows krow .. krow+7 (krow uniform over the wave) of the lane's two columns.
 template <bool GF32>
-__device__ __forceinline__ void load_gstage(GStage<GF32>& st, const void* Gp, int q, int krow, int klim, int col,
-                                            bool vec_ok) {
+__device__ __forceinline__ void load_gstage(GStage<GF32>& st, rsrc_t rs, uint32_t row_bytes, int krow, const GCol& gc) {
+  if (gc.vec) {                     // uniform branch, taken once per stage
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    int row = krow + i;
-    if constexpr (!GF32) {
-      const uint16_t* G = reinterpret_cast<const uint16_t*>(Gp);
-      uint32_t val = 0;
-      if (row < klim) {
-        int64_t o = (int64_t)row * q + col;
-        if (vec_ok && col + 1 < q) val = *reinterpret_cast<const uint32_t*>(G + o);
-        else {
-          if (col < q) val = G[o];
-          if (col + 1 < q) val |= (uint32_t)G[o + 1] << 16;
-        }
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t soff = (uint32_t)(krow + i) * row_bytes;       // scalar
+      if constexpr (!GF32) {
+        st.x[i] = __builtin_amdgcn_raw_buffer_load_b32(rs, gc.off0, soff, 0);
+      } else {
+        u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, gc.off0, soff, 0);
+        st.x[2 * i] = t.x;
+        st.x[2 * i + 1] = t.y;
       }
-      st.x[i] = val;
-    } else {
-      const float* G = reinterpret_cast<const float*>(Gp);
-      float a = 0.f, b = 0.f;
-      if (row < klim) {
-        int64_t o = (int64_t)row * q + col;
-        if (vec_ok && col + 1 < q) { float2 t = *reinterpret_cast<const float2*>(G + o); a = t.x; b = t.y; }
-        else {
-          if (col < q) a = G[o];
-          if (col + 1 < q) b = G[o + 1];
-        }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t soff = (uint32_t)(krow + i) * row_bytes;
+      if constexpr (!GF32) {
+        uint32_t lo = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, gc.off0, soff, 0);
+        uint32_t hi = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, gc.off1, soff, 0);
+        st.x[i] = lo | (hi << 16);
+      } else {
+        st.x[2 * i] = __builtin_amdgcn_raw_buffer_load_b32(rs, gc.off0, soff, 0);
+        st.x[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b32(rs, gc.off1, soff, 0);
       }
-      st.x[2 * i] = __float_as_uint(a);
-      st.x[2 * i + 1] = __float_as_uint(b);
     }
   }
 }
 
 // 8 rows x 2 columns -> two 16-byte vectors (one per column, 8 consecutive k each)
 template <bool GF32>
-__device__ __forceinline__ void store_gstage(const GStage<GF32>& st, uint4* lds_hi, uint4* lds_lo, int slot) {
+__device__ __forceinline__ void store_gstage(const GStage<GF32>& st, u32x4* lds_hi, u32x4* lds_lo, int slot) {
   if constexpr (!GF32) {
-    uint4 c0, c1;
+    u32x4 c0, c1;
     c0.x = (st.x[0] & 0xffffu) | (st.x[1] << 16);  c1.x = (st.x[0] >> 16) | (st.x[1] & 0xffff0000u);
     c0.y = (st.x[2] & 0xffffu) | (st.x[3] << 16);  c1.y = (st.x[2] >> 16) | (st.x[3] & 0xffff0000u);
     c0.z = (st.x[4] & 0xffffu) | (st.x[5] << 16);  c1.z = (st.x[4] >> 16) | (st.x[5] & 0xffff0000u);
@@ -93,10 +122,10 @@ __device__ __forceinline__ void store_gstage(const GStage<GF32>& st, uint4* lds_
       h0[i] = f2bf_rne(a); l0[i] = f2bf_rne(a - __uint_as_float(h0[i] << 16));
       h1[i] = f2bf_rne(b); l1[i] = f2bf_rne(b - __uint_as_float(h1[i] << 16));
     }
-    lds_hi[slot] = make_uint4(h0[0] | (h0[1] << 16), h0[2] | (h0[3] << 16), h0[4] | (h0[5] << 16), h0[6] | (h0[7] << 16));
-    lds_hi[slot + 1] = make_uint4(h1[0] | (h1[1] << 16), h1[2] | (h1[3] << 16), h1[4] | (h1[5] << 16), h1[6] | (h1[7] << 16));
-    lds_lo[slot] = make_uint4(l0[0] | (l0[1] << 16), l0[2] | (l0[3] << 16), l0[4] | (l0[5] << 16), l0[6] | (l0[7] << 16));
-    lds_lo[slot + 1] = make_uint4(l1[0] | (l1[1] << 16), l1[2] | (l1[3] << 16), l1[4] | (l1[5] << 16), l1[6] | (l1[7] << 16));
+    lds_hi[slot] = mk4(h0[0] | (h0[1] << 16), h0[2] | (h0[3] << 16), h0[4] | (h0[5] << 16), h0[6] | (h0[7] << 16));
+    lds_hi[slot + 1] = mk4(h1[0] | (h1[1] << 16), h1[2] | (h1[3] << 16), h1[4] | (h1[5] << 16), h1[6] | (h1[7] << 16));
+    lds_lo[slot] = mk4(l0[0] | (l0[1] << 16), l0[2] | (l0[3] << 16), l0[4] | (l0[5] << 16), l0[6] | (l0[7] << 16));
+    lds_lo[slot + 1] = mk4(l1[0] | (l1[1] << 16), l1[2] | (l1[3] << 16), l1[4] | (l1[5] << 16), l1[6] | (l1[7] << 16));
   }
 }
 
@@ -105,25 +134,31 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
                                                    int64_t split_stride, float grad_scale) {
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
-  const MatDev& m = d.mats[t.mat];
-  const void* Gp = d.ext[EXT_G * d.n + t.mat];
-  const uint4* qt_hi = reinterpret_cast<const uint4*>(d.arena + m.qt_hi);
-  const uint4* qt_lo = reinterpret_cast<const uint4*>(d.arena + m.qt_lo);
+  const MatDev m = d.mats[t.mat];
+  const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
+  const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
 
   constexpr int STAGE_SLOTS = 4 * 4 * 32;                    // (nblk, kgrp, n) 16-byte slots
-  __shared__ uint4 lds_hi[2 * STAGE_SLOTS];
-  __shared__ uint4 lds_lo[GF32 ? 2 * STAGE_SLOTS : 1];
+  __shared__ u32x4 lds_hi[2 * STAGE_SLOTS];
+  __shared__ u32x4 lds_lo[GF32 ? 2 * STAGE_SLOTS : 1];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps row offsets scalar
   const int mbg = t.m0 / 32 + wave % MB;                      // global rank block of this wave
   const int nb_first = (wave / MB) * MB;                      // first column block (0..3) of this wave
   const bool active = mbg < m.rp / 32;
 
-  const int q = m.q;
-  const int col = t.n0 + 2 * lane;                            // first of the two columns this lane stages
-  const bool vec_ok = GF32 ? ((q & 1) == 0 && (reinterpret_cast<uintptr_t>(Gp) & 7) == 0)
-                           : ((q & 1) == 0 && (reinterpret_cast<uintptr_t>(Gp) & 3) == 0);
+  // G as a buffer that ends after the last row of this workgroup's slice: rows past it read as zero
+  constexpr uint32_t ES = GF32 ? 4 : 2;
   const int klim = t.k1 < m.p ? t.k1 : m.p;
+  const void* Gbase = ext_ptr(d, EXT_G, t.mat);
+  const uint32_t row_bytes = (uint32_t)m.q * ES;
+  const rsrc_t rs = make_rsrc(Gbase, (uint32_t)klim * row_bytes);
+  const int col = t.n0 + 2 * lane;                            // first of the two columns this lane stages
+  GCol gc;
+  gc.vec = (m.q & 1) == 0 && (reinterpret_cast<uintptr_t>(Gbase) & (2 * ES - 1)) == 0;
+  gc.off0 = col < m.q ? (uint32_t)col * ES : OOB;
+  gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * ES : OOB;
   const int wslot = ((lane >> 4) * 4 + wave) * 32 + 2 * (lane & 15);   // nblk = lane/16, kgrp = wave
 
   f32x16 acc[MB];
@@ -133,23 +168,38 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
     for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
 
   const int nstages = (t.k1 - t.k0 + DBK - 1) / DBK;
+  const int64_t kgroups = m.pp / 8;
+  // A fragments of one stage: [k-step][hi, lo]; index of the 16-byte group this lane reads
+  const GAS u32x4* pa_hi = qt_hi + (int64_t)(active ? mbg : 0) * kgroups * 32;     // uniform over the wave
+  const GAS u32x4* pa_lo = qt_lo + (int64_t)(active ? mbg : 0) * kgroups * 32;
+  u32x4 a_cur[4], a_nxt[4];
+  auto load_a = [&](u32x4* dst, int kr) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const uint32_t ag = (uint32_t)(kr / 8 + 2 * ks) * 32u + (uint32_t)lane;   // lane = (lane/32)*32 + lane%32
+      dst[2 * ks] = pa_hi[ag];
+      dst[2 * ks + 1] = pa_lo[ag];
+    }
+  };
   GStage<GF32> st;
-  load_gstage<GF32>(st, Gp, q, t.k0 + 8 * wave, klim, col, vec_ok);
+  load_gstage<GF32>(st, rs, row_bytes, t.k0 + 8 * wave, gc);
+  load_a(a_cur, t.k0);
   store_gstage<GF32>(st, lds_hi, lds_lo, wslot);
   __syncthreads();
 
-  const int64_t kgroups = m.pp / 8;
   for (int s = 0; s < nstages; ++s) {
     const int kr = t.k0 + s * DBK;
-    if (s + 1 < nstages) load_gstage<GF32>(st, Gp, q, kr + DBK + 8 * wave, klim, col, vec_ok);
+    if (s + 1 < nstages) {
+      load_gstage<GF32>(st, rs, row_bytes, kr + DBK + 8 * wave, gc);
+      load_a(a_nxt, kr + DBK);
+    }
     if (active) {
-      const uint4* bh = lds_hi + (s & 1) * STAGE_SLOTS;
-      const uint4* bl = lds_lo + (GF32 ? (s & 1) * STAGE_SLOTS : 0);
+      const u32x4* bh = lds_hi + (s & 1) * STAGE_SLOTS;
+      const u32x4* bl = lds_lo + (GF32 ? (s & 1) * STAGE_SLOTS : 0);
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        int64_t ag = ((int64_t)mbg * kgroups + (kr / 8 + 2 * ks + (lane >> 5))) * 32 + (lane & 31);
-        bf16x8 a_hi = as_bf(qt_hi[ag]);
-        bf16x8 a_lo = as_bf(qt_lo[ag]);
+        bf16x8 a_hi = as_bf(a_cur[2 * ks]);
+        bf16x8 a_lo = as_bf(a_cur[2 * ks + 1]);
 #pragma unroll
         for (int a = 0; a < MB; ++a) {
           int bslot = ((nb_first + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31);
@@ -163,14 +213,17 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
         }
       }
     }
-    if (s + 1 < nstages) store_gstage<GF32>(st, lds_hi + ((s + 1) & 1) * STAGE_SLOTS,
-                                            lds_lo + (GF32 ? ((s + 1) & 1) * STAGE_SLOTS : 0), wslot);
+    if (s + 1 < nstages) {
+      store_gstage<GF32>(st, lds_hi + ((s + 1) & 1) * STAGE_SLOTS, lds_lo + (GF32 ? ((s + 1) & 1) * STAGE_SLOTS : 0), wslot);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a_cur[i] = a_nxt[i];
+    }
     __syncthreads();
   }
 
   if (!active) return;
   // accumulator register v of lane l: rank index 32*mbg + 8*(v/4) + 4*(l/32) + v%4, column 32*nbg + l%32
-  float* out = glow + (int64_t)t.split * split_stride + m.lr_off;
+  GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + m.lr_off;
   const int64_t rgroups = m.rp / 8;
 #pragma unroll
   for (int a = 0; a < MB; ++a) {
@@ -179,9 +232,10 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
 #pragma unroll
     for (int vq = 0; vq < 4; ++vq) {
       int64_t o = (((int64_t)nbg * rgroups + 4 * mbg + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
-      float4 val = make_float4(grad_scale * acc[a][4 * vq], grad_scale * acc[a][4 * vq + 1],
-                               grad_scale * acc[a][4 * vq + 2], grad_scale * acc[a][4 * vq + 3]);
-      *reinterpret_cast<float4*>(out + o) = val;
+      f32x4 val;
+      val.x = grad_scale * acc[a][4 * vq];     val.y = grad_scale * acc[a][4 * vq + 1];
+      val.z = grad_scale * acc[a][4 * vq + 2]; val.w = grad_scale * acc[a][4 * vq + 3];
+      *reinterpret_cast<GAS f32x4*>(out + o) = val;
     }
   }
 }
@@ -201,28 +255,53 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 // ---------------------------------------------------------------------------------------
 // Up-projection with the weight update fused.  Workgroup tile 128 x 128 of W, 4 waves in a
 // 2 x 2 grid, each wave 64 x 64 = 2 x 2 accumulator blocks.  Operand fragments come straight
-// from the packed planes (one coalesced 1 KiB read per wave and fragment).
+// from the packed planes (one coalesced 1 KiB read per wave and fragment), double-buffered in
+// registers; the W tile is fetched before the contraction so its latency hides behind it.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __restrict__ tiles,
                                                  const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
-  const MatDev& m = d.mats[t.mat];
-  float* W = reinterpret_cast<float*>(d.ext[EXT_W * d.n + t.mat]);
-  const uint4* qa_hi = reinterpret_cast<const uint4*>(d.arena + m.qa_hi);
-  const uint4* qa_lo = reinterpret_cast<const uint4*>(d.arena + m.qa_lo);
-  const uint4* nh = reinterpret_cast<const uint4*>(n_hi + m.lr_off);
-  const uint4* nl = reinterpret_cast<const uint4*>(n_lo + m.lr_off);
+  const MatDev m = d.mats[t.mat];
+  const GAS u32x4* qa_hi = TO_GLOBAL(const u32x4, d.arena + m.qa_hi);
+  const GAS u32x4* qa_lo = TO_GLOBAL(const u32x4, d.arena + m.qa_lo);
+  const GAS u32x4* nh = TO_GLOBAL(const u32x4, n_hi + m.lr_off);
+  const GAS u32x4* nl = TO_GLOBAL(const u32x4, n_lo + m.lr_off);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps row offsets scalar
   const int mb0 = t.m0 / 32 + 2 * (wave & 1);
   const int nb0 = t.n0 / 32 + 2 * (wave >> 1);
   const int mblocks = m.pp / 32, nblocks = m.qp / 32;
   if (mb0 >= mblocks || nb0 >= nblocks) return;
+  const int p = m.p, q = m.q;
   const int64_t rgroups = m.rp / 8;
   int mbc[2], nbc[2];          // clamped block indices: loads stay inside the planes, stores are masked
   mbc[0] = mb0; mbc[1] = mb0 + 1 < mblocks ? mb0 + 1 : mb0;
   nbc[0] = nb0; nbc[1] = nb0 + 1 < nblocks ? nb0 + 1 : nb0;
+
+  // accumulator register v of block (a, b): row 32*(mb0+a) + 8*(v/4) + 4*(lane/32) + v%4,
+  // column 32*(nb0+b) + lane%32.  W is a buffer of p*q floats: the lane supplies the byte offset
+  // of (row 4*(lane/32), its column) or an out-of-range offset if the column is outside the
+  // matrix; the row of (a, v) is a scalar offset; rows past p fall outside the buffer.
+  const uint32_t row_bytes = (uint32_t)q * 4u;
+  const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
+  uint32_t voff[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    int colw = 32 * (nb0 + b) + (lane & 31);
+    voff[b] = colw < q ? (uint32_t)(4 * (lane >> 5)) * row_bytes + (uint32_t)colw * 4u : OOB;
+  }
+  float wv[2][2][16];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const uint32_t soff = (uint32_t)(32 * (mb0 + a) + 8 * (v >> 2) + (v & 3)) * row_bytes;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], soff, 0));
+    }
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -232,50 +311,52 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  const int ksteps = m.rp / 16;
-  const int sub = (lane >> 5) * 32 + (lane & 31);
-  for (int ks = 0; ks < ksteps; ++ks) {
-    bf16x8 ah[2], al[2], bh[2], bl[2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-      int64_t g = ((int64_t)mbc[a] * rgroups + 2 * ks) * 32 + sub;
-      ah[a] = as_bf(qa_hi[g]);
-      al[a] = as_bf(qa_lo[g]);
-    }
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      int64_t g = ((int64_t)nbc[b] * rgroups + 2 * ks) * 32 + sub;
-      bh[b] = as_bf(nh[g]);
-      bl[b] = as_bf(nl[g]);
-    }
+  const int ksteps = m.rp / 16;                    // even: rp is a multiple of 32
+  // uniform plane pointers of the two row blocks and two column blocks; the lane adds its index
+  const GAS u32x4* pah0 = qa_hi + (int64_t)mbc[0] * rgroups * 32;
+  const GAS u32x4* pah1 = qa_hi + (int64_t)mbc[1] * rgroups * 32;
+  const GAS u32x4* pal0 = qa_lo + (int64_t)mbc[0] * rgroups * 32;
+  const GAS u32x4* pal1 = qa_lo + (int64_t)mbc[1] * rgroups * 32;
+  const GAS u32x4* pbh0 = nh + (int64_t)nbc[0] * rgroups * 32;
+  const GAS u32x4* pbh1 = nh + (int64_t)nbc[1] * rgroups * 32;
+  const GAS u32x4* pbl0 = nl + (int64_t)nbc[0] * rgroups * 32;
+  const GAS u32x4* pbl1 = nl + (int64_t)nbc[1] * rgroups * 32;
+  struct Frags { u32x4 ah[2], al[2], bh[2], bl[2]; };
+  auto load_frags = [&](Frags& f, int ks) {
+    const uint32_t o = (uint32_t)ks * 64u + (uint32_t)lane;
+    f.ah[0] = pah0[o]; f.al[0] = pal0[o];
+    f.ah[1] = pah1[o]; f.al[1] = pal1[o];
+    f.bh[0] = pbh0[o]; f.bl[0] = pbl0[o];
+    f.bh[1] = pbh1[o]; f.bl[1] = pbl1[o];
+  };
+  auto compute = [&](const Frags& f) {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[a], bh[b], acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ah[a]), as_bf(f.bh[b]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ah[a]), as_bf(f.bl[b]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.al[a]), as_bf(f.bh[b]), acc[a][b], 0, 0, 0);
       }
+  };
+  Frags f0, f1;
+  load_frags(f0, 0);
+  for (int ks = 0; ks < ksteps; ks += 2) {
+    load_frags(f1, ks + 1);
+    compute(f0);
+    if (ks + 2 < ksteps) load_frags(f0, ks + 2);
+    compute(f1);
   }
 
 #pragma unroll
-  for (int a = 0; a < 2; ++a) {
-    if (mb0 + a >= mblocks) continue;
+  for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      if (nb0 + b >= nblocks) continue;
-      int colw = 32 * (nb0 + b) + (lane & 31);
-      if (colw >= m.q) continue;
+    for (int v = 0; v < 16; ++v) {
+      const uint32_t soff = (uint32_t)(32 * (mb0 + a) + 8 * (v >> 2) + (v & 3)) * row_bytes;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        int row = 32 * (mb0 + a) + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row < m.p) {
-          int64_t o = (int64_t)row * m.q + colw;
-          W[o] = fmaf(-lr, acc[a][b][v], W[o]);
-        }
-      }
+      for (int b = 0; b < 2; ++b)
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(fmaf(-lr, acc[a][b][v], wv[a][b][v])), rw, voff[b], soff, 0);
     }
-  }
 }
 
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* n_hi,
