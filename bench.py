@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-events", action="store_true", help="skip the event-timed second pass")
     ap.add_argument("--refresh-every", type=int, default=None)
     ap.add_argument("--outer-every", type=int, default=None)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain 1 GiB device copies (known traffic) to scale the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -177,6 +179,14 @@ def main():
     import torch
     from paper_2602_04396_amd import lordo, synth
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")        # 1 GiB, far beyond every cache
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 device copies of 1 GiB: 1048576 KiB read and 1048576 KiB written each"}))
+        return
     lordo.load()
     cfg = args.config.lower()
     d = synth.CONFIG_DEFAULTS[cfg]
@@ -211,6 +221,10 @@ def main():
     if not args.no_events:
         opt.profile_enable(True)
         run_steps(opt, Wp, Gp, Dp, Op, args.steps, outer_every, refresh_every, lr, start=0)
+        if not outer_every:          # workloads that time the outer step and the refresh on their own
+            opt.outer_step(Wp, Dp)
+        if not refresh_every:
+            opt.refresh_subspace(Gp[0], Op)
         torch.cuda.synchronize()
         total_by = {}
         for name, kc in (("down", lordo.K_DOWN), ("adam", lordo.K_ADAM), ("up", lordo.K_UP), ("outer", lordo.K_OUTER),

@@ -370,6 +370,7 @@ __global__ __launch_bounds__(256) void k_potf2(DevCtx d, int jb) {
     __syncthreads();
   }
   float floor_piv = 1e-12f * dmax_s[0] + 1e-37f;
+  const int tx = tid & 63, ty = tid >> 6;          // column, row phase
   for (int k = 0; k < NB; ++k) {
     float piv = Ls[k][k];
     if (!(piv > floor_piv)) {
@@ -383,23 +384,28 @@ __global__ __launch_bounds__(256) void k_potf2(DevCtx d, int jb) {
       Ls[i][k] = i == k ? dd : Ls[i][k] / dd;
     }
     __syncthreads();
-    int w = NB - k - 1;
-    for (int idx = tid; idx < w * w; idx += 256) {
-      int i = k + 1 + idx / w, j = k + 1 + idx % w;
-      if (j <= i) Ls[i][j] -= Ls[i][k] * Ls[j][k];
+    {   // trailing update of the lower triangle: L[i][j] -= L[i][k] L[j][k], k < j <= i
+      int j = k + 1 + tx;
+      if (j < NB) {
+        float ljk = Ls[j][k];
+        for (int i = j + ty; i < NB; i += 4) Ls[i][j] -= Ls[i][k] * ljk;
+      }
     }
     __syncthreads();
   }
-  if (tid < NB) {       // column tid of X = L^{-1} by forward substitution
-    int c = tid;
-    Xs[c][c] = 1.f / Ls[c][c];
-    for (int i = c + 1; i < NB; ++i) {
-      float sacc = 0.f;
-      for (int k = c; k < i; ++k) sacc = fmaf(Ls[i][k], Xs[k][c], sacc);
-      Xs[i][c] = -sacc / Ls[i][i];
-    }
-  }
+  // X = L^{-1} by elimination on the identity: after step k row k of X is final
+  for (int idx = tid; idx < NB * NB; idx += 256) Xs[idx / NB][idx % NB] = (idx / NB == idx % NB) ? 1.f : 0.f;
   __syncthreads();
+  for (int k = 0; k < NB; ++k) {
+    float inv = 1.f / Ls[k][k];
+    if (tid <= k) Xs[k][tid] *= inv;               // row k, columns 0..k
+    __syncthreads();
+    if (tx <= k) {
+      float xk = Xs[k][tx];
+      for (int i = k + 1 + ty; i < NB; i += 4) Xs[i][tx] -= Ls[i][k] * xk;
+    }
+    __syncthreads();
+  }
   for (int idx = tid; idx < NB * NB; idx += 256) {
     int i = idx / NB, j = idx % NB;
     X[idx] = j <= i ? Xs[i][j] : 0.f;

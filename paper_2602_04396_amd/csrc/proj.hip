@@ -44,10 +44,12 @@ __device__ __forceinline__ uint32_t f2bf_rne(float x) {
   return u >> 16;
 }
 
-constexpr int DBK = 32;        // rows of G per pipeline stage
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// Compiler-level fence: keeps the loads issued before it from being sunk to their first use
+// (prefetches must be in flight while the matrix cores work); it emits no instruction.
+#define ISSUE_FENCE() asm volatile("" ::: "memory")
 constexpr uint32_t OOB = 0x80000000u;        // byte offset beyond any resource (sizes are < 2 GiB)
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
@@ -129,16 +131,18 @@ __device__ __forceinline__ void store_gstage(const GStage<GF32>& st, u32x4* lds_
   }
 }
 
-template <int MB, bool GF32>
+template <int MB, bool GF32, int KG>
 __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
                                                    int64_t split_stride, float grad_scale) {
+  constexpr int BK = 32 * KG;                                 // rows of G per pipeline stage
+  constexpr int KGRPS = 4 * KG;                               // 8-row groups per stage
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
   const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
 
-  constexpr int STAGE_SLOTS = 4 * 4 * 32;                    // (nblk, kgrp, n) 16-byte slots
+  constexpr int STAGE_SLOTS = 4 * KGRPS * 32;                 // (nblk, kgrp, n) 16-byte slots
   __shared__ u32x4 lds_hi[2 * STAGE_SLOTS];
   __shared__ u32x4 lds_lo[GF32 ? 2 * STAGE_SLOTS : 1];
 
@@ -159,7 +163,8 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
   gc.vec = (m.q & 1) == 0 && (reinterpret_cast<uintptr_t>(Gbase) & (2 * ES - 1)) == 0;
   gc.off0 = col < m.q ? (uint32_t)col * ES : OOB;
   gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * ES : OOB;
-  const int wslot = ((lane >> 4) * 4 + wave) * 32 + 2 * (lane & 15);   // nblk = lane/16, kgrp = wave
+  // this wave stages the 8-row groups h*4 + wave, h < KG; nblk = lane/16
+  const int wslot = ((lane >> 4) * KGRPS + wave) * 32 + 2 * (lane & 15);
 
   f32x16 acc[MB];
 #pragma unroll
@@ -167,42 +172,48 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
 
-  const int nstages = (t.k1 - t.k0 + DBK - 1) / DBK;
+  const int nstages = (t.k1 - t.k0 + BK - 1) / BK;
   const int64_t kgroups = m.pp / 8;
-  // A fragments of one stage: [k-step][hi, lo]; index of the 16-byte group this lane reads
+  // A fragments of one stage: [k-step][hi, lo]
   const GAS u32x4* pa_hi = qt_hi + (int64_t)(active ? mbg : 0) * kgroups * 32;     // uniform over the wave
   const GAS u32x4* pa_lo = qt_lo + (int64_t)(active ? mbg : 0) * kgroups * 32;
-  u32x4 a_cur[4], a_nxt[4];
+  const uint32_t agmax = (uint32_t)kgroups * 32u - 64u;                           // last k-step of the plane row block
+  u32x4 a_cur[4 * KG], a_nxt[4 * KG];
   auto load_a = [&](u32x4* dst, int kr) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const uint32_t ag = (uint32_t)(kr / 8 + 2 * ks) * 32u + (uint32_t)lane;   // lane = (lane/32)*32 + lane%32
+    for (int ks = 0; ks < 2 * KG; ++ks) {
+      uint32_t ag = (uint32_t)(kr / 8 + 2 * ks) * 32u;
+      ag = (ag < agmax ? ag : agmax) + (uint32_t)lane;        // a stage may reach past the padded height
       dst[2 * ks] = pa_hi[ag];
       dst[2 * ks + 1] = pa_lo[ag];
     }
   };
-  GStage<GF32> st;
-  load_gstage<GF32>(st, rs, row_bytes, t.k0 + 8 * wave, gc);
+  GStage<GF32> st[KG];
+#pragma unroll
+  for (int h = 0; h < KG; ++h) load_gstage<GF32>(st[h], rs, row_bytes, t.k0 + 8 * (h * 4 + wave), gc);
   load_a(a_cur, t.k0);
-  store_gstage<GF32>(st, lds_hi, lds_lo, wslot);
+#pragma unroll
+  for (int h = 0; h < KG; ++h) store_gstage<GF32>(st[h], lds_hi, lds_lo, wslot + h * 4 * 32);
   __syncthreads();
 
   for (int s = 0; s < nstages; ++s) {
-    const int kr = t.k0 + s * DBK;
+    const int kr = t.k0 + s * BK;
     if (s + 1 < nstages) {
-      load_gstage<GF32>(st, rs, row_bytes, kr + DBK + 8 * wave, gc);
-      load_a(a_nxt, kr + DBK);
+#pragma unroll
+      for (int h = 0; h < KG; ++h) load_gstage<GF32>(st[h], rs, row_bytes, kr + BK + 8 * (h * 4 + wave), gc);
+      load_a(a_nxt, kr + BK);
     }
+    ISSUE_FENCE();
     if (active) {
       const u32x4* bh = lds_hi + (s & 1) * STAGE_SLOTS;
       const u32x4* bl = lds_lo + (GF32 ? (s & 1) * STAGE_SLOTS : 0);
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+      for (int ks = 0; ks < 2 * KG; ++ks) {
         bf16x8 a_hi = as_bf(a_cur[2 * ks]);
         bf16x8 a_lo = as_bf(a_cur[2 * ks + 1]);
 #pragma unroll
         for (int a = 0; a < MB; ++a) {
-          int bslot = ((nb_first + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31);
+          int bslot = ((nb_first + a) * KGRPS + 2 * ks + (lane >> 5)) * 32 + (lane & 31);
           bf16x8 b = as_bf(bh[bslot]);
           acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[a], 0, 0, 0);
           acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[a], 0, 0, 0);
@@ -213,10 +224,14 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
         }
       }
     }
+    ISSUE_FENCE();
     if (s + 1 < nstages) {
-      store_gstage<GF32>(st, lds_hi + ((s + 1) & 1) * STAGE_SLOTS, lds_lo + (GF32 ? ((s + 1) & 1) * STAGE_SLOTS : 0), wslot);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a_cur[i] = a_nxt[i];
+      for (int h = 0; h < KG; ++h)
+        store_gstage<GF32>(st[h], lds_hi + ((s + 1) & 1) * STAGE_SLOTS, lds_lo + (GF32 ? ((s + 1) & 1) * STAGE_SLOTS : 0),
+                           wslot + h * 4 * 32);
+#pragma unroll
+      for (int i = 0; i < 4 * KG; ++i) a_cur[i] = a_nxt[i];
     }
     __syncthreads();
   }
@@ -245,8 +260,8 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
 #define LORDO_DOWN(MBV)                                                                                            \
-  if (g_is_f32) hipLaunchKernelGGL((k_proj_down<MBV, true>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
-  else hipLaunchKernelGGL((k_proj_down<MBV, false>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale);
+  if (g_is_f32) hipLaunchKernelGGL((k_proj_down<MBV, true, 1>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
+  else hipLaunchKernelGGL((k_proj_down<MBV, false, 2>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale);
   if (mb == 4) { LORDO_DOWN(4) } else if (mb == 2) { LORDO_DOWN(2) } else { LORDO_DOWN(1) }
 #undef LORDO_DOWN
   return hipGetLastError();
@@ -302,6 +317,7 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
       for (int b = 0; b < 2; ++b)
         wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], soff, 0));
     }
+  ISSUE_FENCE();
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -343,10 +359,13 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   load_frags(f0, 0);
   for (int ks = 0; ks < ksteps; ks += 2) {
     load_frags(f1, ks + 1);
+    ISSUE_FENCE();
     compute(f0);
     if (ks + 2 < ksteps) load_frags(f0, ks + 2);
+    ISSUE_FENCE();
     compute(f1);
   }
+  ISSUE_FENCE();
 
 #pragma unroll
   for (int a = 0; a < 2; ++a)

@@ -165,11 +165,10 @@ def device_spiked_gradient(torch, p, q, n_spike, seed, noise="gauss", sigma=1e-3
                            dtype=None, device="cuda"):
     """Returns (draw(step) -> tensor of `dtype`, spike factors) on `device`."""
     dtype = dtype or torch.bfloat16
-    gen = torch.Generator(device=device)
-    gen.manual_seed(seed)
     k = min(n_spike, p, q)
-    a, _ = torch.linalg.qr(torch.randn(p, k, generator=gen, device=device))
-    b, _ = torch.linalg.qr(torch.randn(q, k, generator=gen, device=device))
+    rng = np.random.default_rng(seed)          # the thin spike factors are built on the host
+    a = torch.tensor(orthonormal(rng, p, k), dtype=torch.float32, device=device)
+    b = torch.tensor(orthonormal(rng, q, k), dtype=torch.float32, device=device)
     edge = sigma * (p ** 0.5 + q ** 0.5)
     expo = torch.arange(k, device=device, dtype=torch.float32) / max(k - 1, 1)
     s = edge * 20.0 * 10.0 ** (-expo)
