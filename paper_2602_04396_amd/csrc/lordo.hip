@@ -7,6 +7,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -290,6 +291,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.chunk_start_h[n] = chunks;
   P.nchunks = chunks;
   P.mb = rp_max > 64 ? 4 : (rp_max > 32 ? 2 : 1);
+
   // Split-K of the down-projection.  With few output tiles (small models) the long contraction
   // over p is cut into slices of about the shortest matrix's height, so that every workgroup
   // has the same amount of work and the chip is filled; slices are summed, in fixed order, by
@@ -561,7 +563,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
                      c->at<uint16_t>(P.n_lo), P.lr_total, a, s));
   c->prof.end(LORDO_K_ADAM, s);
   c->prof.begin(LORDO_K_UP, s);
-  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), c->at<uint16_t>(P.n_hi),
+  bool w_vec = true;            // 16-byte accesses to W need q % 4 == 0 and 16-byte aligned pointers
+  for (int i = 0; i < c->n; ++i)
+    if ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
+  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
                         c->at<uint16_t>(P.n_lo), (float)lr, s));
   c->prof.end(LORDO_K_UP, s);
   c->t = t;

@@ -269,10 +269,21 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 
 // ---------------------------------------------------------------------------------------
 // Up-projection with the weight update fused.  Workgroup tile 128 x 128 of W, 4 waves in a
-// 2 x 2 grid, each wave 64 x 64 = 2 x 2 accumulator blocks.  Operand fragments come straight
-// from the packed planes (one coalesced 1 KiB read per wave and fragment), double-buffered in
-// registers; the W tile is fetched before the contraction so its latency hides behind it.
+// 2 x 2 grid, each wave 64 x 64 = 2 x 2 accumulator blocks.  Operand fragments come straight from
+// the packed planes (one coalesced 1 KiB read per wave and fragment), double-buffered in registers;
+// the W tile is fetched through a buffer resource before the contraction so its latency hides
+// behind it.
+//
+// The vector-memory front end costs about 16 cycles per instruction whatever its width and one
+// tag look-up per cache line touched, so W is best moved with 16-byte accesses that cover whole
+// 128-byte lines.  VEC = true (q % 4 == 0, W 16-byte aligned): the matrix core computes the
+// transposed block (Q N)^T = N^T Q^T, which puts four consecutive COLUMNS of a row in a lane's
+// four consecutive accumulator registers; each 32 x 32 block then goes through a per-wave LDS
+// buffer (16-byte writes, 16-byte reads) into row order, where 8 lanes cover one 128-byte line of
+// a row, and is combined with the W values that were fetched in that same order.
+// VEC = false: plain orientation, one dword per access, any q and alignment.
 // ---------------------------------------------------------------------------------------
+template <bool VEC>
 __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __restrict__ tiles,
                                                  const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
   const ProjTile t = tiles[blockIdx.x];
@@ -283,6 +294,9 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   const GAS u32x4* nh = TO_GLOBAL(const u32x4, n_hi + m.lr_off);
   const GAS u32x4* nl = TO_GLOBAL(const u32x4, n_lo + m.lr_off);
 
+  constexpr int TP = 36;                                   // LDS pitch (floats) of the 32 x 32 staging block
+  __shared__ float stage[VEC ? 4 * 32 * TP : 1];
+
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps row offsets scalar
   const int mb0 = t.m0 / 32 + 2 * (wave & 1);
@@ -291,31 +305,47 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   if (mb0 >= mblocks || nb0 >= nblocks) return;
   const int p = m.p, q = m.q;
   const int64_t rgroups = m.rp / 8;
-  int mbc[2], nbc[2];          // clamped block indices: loads stay inside the planes, stores are masked
-  mbc[0] = mb0; mbc[1] = mb0 + 1 < mblocks ? mb0 + 1 : mb0;
-  nbc[0] = nb0; nbc[1] = nb0 + 1 < nblocks ? nb0 + 1 : nb0;
 
-  // accumulator register v of block (a, b): row 32*(mb0+a) + 8*(v/4) + 4*(lane/32) + v%4,
-  // column 32*(nb0+b) + lane%32.  W is a buffer of p*q floats: the lane supplies the byte offset
-  // of (row 4*(lane/32), its column) or an out-of-range offset if the column is outside the
-  // matrix; the row of (a, v) is a scalar offset; rows past p fall outside the buffer.
+  // W is a buffer of p*q floats: rows past p fall outside it (reads give 0, writes are dropped); a
+  // lane whose columns are outside the matrix gets an offset outside the buffer.  The lane supplies
+  // its part of the offset, the block / register part is scalar.
   const uint32_t row_bytes = (uint32_t)q * 4u;
   const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
+  // VEC: lane = (rr, c4): row rr + 8j of a block, columns 4*c4 .. 4*c4+3
+  // else: register v of block (a, b) is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+  const int rr = lane >> 3, c4 = lane & 7;
   uint32_t voff[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
-    int colw = 32 * (nb0 + b) + (lane & 31);
-    voff[b] = colw < q ? (uint32_t)(4 * (lane >> 5)) * row_bytes + (uint32_t)colw * 4u : OOB;
+    if constexpr (VEC) {
+      int col = 32 * (nb0 + b) + 4 * c4;
+      voff[b] = col < q ? (uint32_t)rr * row_bytes + (uint32_t)c4 * 16u : OOB;
+    } else {
+      int col = 32 * (nb0 + b) + (lane & 31);
+      voff[b] = col < q ? (uint32_t)(4 * (lane >> 5)) * row_bytes + (uint32_t)(lane & 31) * 4u : OOB;
+    }
   }
+  auto w_soff = [&](int a, int b, int v) -> uint32_t {      // v: register (scalar path) or 4*j (vector path, rows 8j)
+    int row = VEC ? 32 * (mb0 + a) + 8 * (v >> 2) : 32 * (mb0 + a) + 8 * (v >> 2) + (v & 3);
+    return (uint32_t)row * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u;
+  };
   float wv[2][2][16];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const uint32_t soff = (uint32_t)(32 * (mb0 + a) + 8 * (v >> 2) + (v & 3)) * row_bytes;
+    for (int b = 0; b < 2; ++b) {
+      if constexpr (VEC) {
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-        wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], soff, 0));
+        for (int j = 0; j < 4; ++j) {
+          u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rw, voff[b], w_soff(a, b, 4 * j), 0);
+          wv[a][b][4 * j] = __uint_as_float(x.x); wv[a][b][4 * j + 1] = __uint_as_float(x.y);
+          wv[a][b][4 * j + 2] = __uint_as_float(x.z); wv[a][b][4 * j + 3] = __uint_as_float(x.w);
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], w_soff(a, b, v), 0));
+      }
     }
   ISSUE_FENCE();
 
@@ -328,31 +358,44 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
   const int ksteps = m.rp / 16;                    // even: rp is a multiple of 32
-  // uniform plane pointers of the two row blocks and two column blocks; the lane adds its index
-  const GAS u32x4* pah0 = qa_hi + (int64_t)mbc[0] * rgroups * 32;
-  const GAS u32x4* pah1 = qa_hi + (int64_t)mbc[1] * rgroups * 32;
-  const GAS u32x4* pal0 = qa_lo + (int64_t)mbc[0] * rgroups * 32;
-  const GAS u32x4* pal1 = qa_lo + (int64_t)mbc[1] * rgroups * 32;
-  const GAS u32x4* pbh0 = nh + (int64_t)nbc[0] * rgroups * 32;
-  const GAS u32x4* pbh1 = nh + (int64_t)nbc[1] * rgroups * 32;
-  const GAS u32x4* pbl0 = nl + (int64_t)nbc[0] * rgroups * 32;
-  const GAS u32x4* pbl1 = nl + (int64_t)nbc[1] * rgroups * 32;
-  struct Frags { u32x4 ah[2], al[2], bh[2], bl[2]; };
+  // uniform plane pointers of the row blocks and column blocks (clamped into the planes: loads of
+  // blocks past the edge stay inside, their stores fall outside the buffer); the lane adds its index
+  const GAS u32x4* pqh[2]; const GAS u32x4* pql[2];
+  const GAS u32x4* pnh[2]; const GAS u32x4* pnl[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    int mbc = mb0 + a < mblocks ? mb0 + a : mblocks - 1;
+    pqh[a] = qa_hi + (int64_t)mbc * rgroups * 32;
+    pql[a] = qa_lo + (int64_t)mbc * rgroups * 32;
+  }
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    int nbc = nb0 + b < nblocks ? nb0 + b : nblocks - 1;
+    pnh[b] = nh + (int64_t)nbc * rgroups * 32;
+    pnl[b] = nl + (int64_t)nbc * rgroups * 32;
+  }
+  struct Frags { u32x4 qh[2], ql[2], nh[2], nl[2]; };
   auto load_frags = [&](Frags& f, int ks) {
     const uint32_t o = (uint32_t)ks * 64u + (uint32_t)lane;
-    f.ah[0] = pah0[o]; f.al[0] = pal0[o];
-    f.ah[1] = pah1[o]; f.al[1] = pal1[o];
-    f.bh[0] = pbh0[o]; f.bl[0] = pbl0[o];
-    f.bh[1] = pbh1[o]; f.bl[1] = pbl1[o];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) { f.qh[a] = pqh[a][o]; f.ql[a] = pql[a][o]; }
+#pragma unroll
+    for (int b = 0; b < 2; ++b) { f.nh[b] = pnh[b][o]; f.nl[b] = pnl[b][o]; }
   };
   auto compute = [&](const Frags& f) {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ah[a]), as_bf(f.bh[b]), acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ah[a]), as_bf(f.bl[b]), acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.al[a]), as_bf(f.bh[b]), acc[a][b], 0, 0, 0);
+        if constexpr (VEC) {         // transposed block: N fragment first
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.nh[b]), as_bf(f.qh[a]), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.nl[b]), as_bf(f.qh[a]), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.nh[b]), as_bf(f.ql[a]), acc[a][b], 0, 0, 0);
+        } else {
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.qh[a]), as_bf(f.nh[b]), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.qh[a]), as_bf(f.nl[b]), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ql[a]), as_bf(f.nh[b]), acc[a][b], 0, 0, 0);
+        }
       }
   };
   Frags f0, f1;
@@ -367,21 +410,198 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   }
   ISSUE_FENCE();
 
+  if constexpr (VEC) {
+    // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e
+    float* T = stage + wave * 32 * TP;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          f32x4 x;
+          x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
+          *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
+        }
+        // LDS operations of one wave complete in order: the reads below see the writes above
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
+          u32x4 o;
+          o.x = __float_as_uint(fmaf(-lr, x.x, wv[a][b][4 * j]));
+          o.y = __float_as_uint(fmaf(-lr, x.y, wv[a][b][4 * j + 1]));
+          o.z = __float_as_uint(fmaf(-lr, x.z, wv[a][b][4 * j + 2]));
+          o.w = __float_as_uint(fmaf(-lr, x.w, wv[a][b][4 * j + 3]));
+          __builtin_amdgcn_raw_buffer_store_b128(o, rw, voff[b], w_soff(a, b, 4 * j), 0);
+        }
+      }
+  } else {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(fmaf(-lr, acc[a][b][v], wv[a][b][v])), rw, voff[b],
+                                                w_soff(a, b, v), 0);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Up-projection, main path (q % 4 == 0, W 16-byte aligned).  Same tile and wave layout, transposed
+// accumulators and LDS-transposed epilogue as k_proj_up<true>, but the operand fragments are
+// brought in ONCE per workgroup by direct global-to-LDS loads (each 1 KiB fragment is one
+// 16-byte-per-lane load that lands in lane order, so no registers and no transposition are
+// involved) and every wave then reads its fragments from LDS.  This halves the bytes that pass
+// through the vector L1 (each fragment is needed by two of the four waves), which is what bounds
+// the register-fed variant.  Chunks of 32 of the contraction (2 MFMA k-steps, 32 KiB of
+// fragments) are double-buffered; one barrier per chunk.
+// ---------------------------------------------------------------------------------------
+#define LDS_AS __attribute__((address_space(3)))
+__device__ __forceinline__ void dma16(const GAS u32x4* src, u32x4* lds_dst_wave_base) {
+  // lane i's 16 bytes land at lds_dst_wave_base + i; the LDS address must be uniform over the wave
+  __builtin_amdgcn_global_load_lds((const GAS void*)src, (LDS_AS void*)lds_dst_wave_base, 16, 0, 0);
+}
+
+__global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
+                                                     const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
+  const ProjTile t = tiles[blockIdx.x];
+  if (t.mat < 0) return;
+  const MatDev m = d.mats[t.mat];
+  const GAS u32x4* qa_hi = TO_GLOBAL(const u32x4, d.arena + m.qa_hi);
+  const GAS u32x4* qa_lo = TO_GLOBAL(const u32x4, d.arena + m.qa_lo);
+  const GAS u32x4* nh = TO_GLOBAL(const u32x4, n_hi + m.lr_off);
+  const GAS u32x4* nl = TO_GLOBAL(const u32x4, n_lo + m.lr_off);
+
+  // fragment slot (64 x 16 bytes) of chunk buffer s: ((s*2 + kind)*4 + blk)*4 + ks*2 + plane,
+  // kind 0 = Q rows, 1 = N columns; the epilogue staging blocks reuse the same memory
+  constexpr int TP = 36;
+  constexpr int SLOTS = 2 * 2 * 4 * 4;
+  __shared__ u32x4 frag[SLOTS * 64];                       // 64 KiB
+  static_assert(sizeof(u32x4) * SLOTS * 64 >= sizeof(float) * 4 * 32 * TP, "staging blocks must fit");
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave & 1, wn = wave >> 1;
+  const int mblocks = m.pp / 32, nblocks = m.qp / 32;
+  const int mb0 = t.m0 / 32 + 2 * wm, nb0 = t.n0 / 32 + 2 * wn;     // this wave's first row / column block
+  const int p = m.p, q = m.q;
+  const int64_t rgroups = m.rp / 8;
+  const int nchunks = m.rp / 32;
+
+  // this wave feeds block `wave` of both operands (clamped into the planes at the edges)
+  const int mbf = t.m0 / 32 + wave < mblocks ? t.m0 / 32 + wave : mblocks - 1;
+  const int nbf = t.n0 / 32 + wave < nblocks ? t.n0 / 32 + wave : nblocks - 1;
+  const GAS u32x4* src[4] = {qa_hi + (int64_t)mbf * rgroups * 32 + lane, qa_lo + (int64_t)mbf * rgroups * 32 + lane,
+                             nh + (int64_t)nbf * rgroups * 32 + lane, nl + (int64_t)nbf * rgroups * 32 + lane};
+  auto issue_chunk = [&](int c, int s) {
+#pragma unroll
+    for (int kind = 0; kind < 2; ++kind)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl)
+          dma16(src[kind * 2 + pl] + (int64_t)(2 * c + ks) * 64, frag + ((((s * 2 + kind) * 4 + wave) * 4) + ks * 2 + pl) * 64);
+  };
+
+  // W tile in row order: lane = (rr, c4): row rr + 8j of a block, columns 4*c4 .. 4*c4+3
+  const uint32_t row_bytes = (uint32_t)q * 4u;
+  const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
+  const int rr = lane >> 3, c4 = lane & 7;
+  uint32_t voff[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    int col = 32 * (nb0 + b) + 4 * c4;
+    voff[b] = col < q ? (uint32_t)rr * row_bytes + (uint32_t)c4 * 16u : OOB;
+  }
+  auto w_soff = [&](int a, int b, int j) -> uint32_t {
+    return (uint32_t)(32 * (mb0 + a) + 8 * j) * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u;
+  };
+
+  issue_chunk(0, 0);
+  u32x4 wv[2][2][4];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const uint32_t soff = (uint32_t)(32 * (mb0 + a) + 8 * (v >> 2) + (v & 3)) * row_bytes;
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(fmaf(-lr, acc[a][b][v], wv[a][b][v])), rw, voff[b], soff, 0);
+      for (int j = 0; j < 4; ++j) wv[a][b][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff[b], w_soff(a, b, j), 0);
+  ISSUE_FENCE();
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  for (int c = 0; c < nchunks; ++c) {
+    // chunk c was issued before everything that is still in flight except, for c == 0, the 16 W loads
+    if (c == 0) __builtin_amdgcn_s_waitcnt(0x0f70 | 0x4000);       // vmcnt(16): bits [3:0]=0, [15:14]=1
+    else __builtin_amdgcn_s_waitcnt(0x0f70);                       // vmcnt(0)
+    __syncthreads();              // chunk c visible to all waves; every wave is done with chunk c-1
+    if (c + 1 < nchunks) issue_chunk(c + 1, (c + 1) & 1);
+    ISSUE_FENCE();
+    const u32x4* fb = frag + (c & 1) * (2 * 4 * 4 * 64);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      u32x4 qh[2], ql[2], xh[2], xl[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        qh[a] = fb[((0 * 4 + 2 * wm + a) * 4 + ks * 2 + 0) * 64 + lane];
+        ql[a] = fb[((0 * 4 + 2 * wm + a) * 4 + ks * 2 + 1) * 64 + lane];
+      }
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        xh[b] = fb[((1 * 4 + 2 * wn + b) * 4 + ks * 2 + 0) * 64 + lane];
+        xl[b] = fb[((1 * 4 + 2 * wn + b) * 4 + ks * 2 + 1) * 64 + lane];
+      }
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {      // transposed block: N fragment first
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xh[b]), as_bf(qh[a]), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xl[b]), as_bf(qh[a]), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xh[b]), as_bf(ql[a]), acc[a][b], 0, 0, 0);
+        }
+    }
+  }
+  __syncthreads();                // all waves are done reading fragments: reuse the memory for staging
+
+  if (mb0 >= mblocks || nb0 >= nblocks) return;
+  // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e
+  float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        f32x4 x;
+        x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
+        *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
+      }
+      // LDS operations of one wave complete in order: the reads below see the writes above
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
+        u32x4 o;
+        o.x = __float_as_uint(fmaf(-lr, x.x, __uint_as_float(wv[a][b][j].x)));
+        o.y = __float_as_uint(fmaf(-lr, x.y, __uint_as_float(wv[a][b][j].y)));
+        o.z = __float_as_uint(fmaf(-lr, x.z, __uint_as_float(wv[a][b][j].z)));
+        o.w = __float_as_uint(fmaf(-lr, x.w, __uint_as_float(wv[a][b][j].w)));
+        __builtin_amdgcn_raw_buffer_store_b128(o, rw, voff[b], w_soff(a, b, j), 0);
+      }
     }
 }
 
-hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* n_hi,
+hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* n_hi,
                           const uint16_t* n_lo, float lr, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_proj_up, dim3(ntiles), dim3(256), 0, s, d, tiles, n_hi, n_lo, lr);
+  dim3 grid(ntiles), block(256);
+  if (vec) hipLaunchKernelGGL(k_proj_up_dma, grid, block, 0, s, d, tiles, n_hi, n_lo, lr);
+  else hipLaunchKernelGGL((k_proj_up<false>), grid, block, 0, s, d, tiles, n_hi, n_lo, lr);
   return hipGetLastError();
 }
 
