@@ -39,6 +39,7 @@ struct Plan {
   int64_t lr_total = 0;             // elements of one flat low-rank array
   int64_t nchunks = 0;
   int mb = 4;
+  bool down_wide = false;           // 8-wave, 256-column tiles of the down-projection (rank tile 128, bf16 G)
   int nsplit = 1;                   // largest split-K factor of the down-projection
   std::vector<int> splits;          // split-K factor per matrix (1, 2, 4 or 8)
   int32_t grp_nsplit[4] = {1, 1, 1, 1};
@@ -291,6 +292,9 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.chunk_start_h[n] = chunks;
   P.nchunks = chunks;
   P.mb = rp_max > 64 ? 4 : (rp_max > 32 ? 2 : 1);
+  P.down_wide = P.mb == 4 && hp.grad_dtype == LORDO_BF16;
+  if (const char* e = getenv("LORDO_DOWN_WIDE")) P.down_wide = P.down_wide && atoi(e) != 0;   // tuning aid
+  const int down_bn = P.down_wide ? 256 : 128;
 
   // Split-K of the down-projection.  With few output tiles (small models) the long contraction
   // over p is cut into slices of about the shortest matrix's height, so that every workgroup
@@ -298,7 +302,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the Adam kernel.  Factors are powers of two up to 8.
   int64_t tiles0 = 0;
   for (int i = 0; i < n; ++i)
-    tiles0 += (int64_t)((P.mat[i].qp + 127) / 128) * ((P.mat[i].rp + 32 * P.mb - 1) / (32 * P.mb));
+    tiles0 += (int64_t)((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + 32 * P.mb - 1) / (32 * P.mb));
   P.splits.assign(n, 1);
   P.nsplit = 1;
   if (tiles0 < 1536) {
@@ -357,7 +361,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     const MatDev& m = P.mat[i];
     const int f = P.splits[i];
     const int klen = ((m.pp + f - 1) / f + 31) / 32 * 32;
-    for (int n0 = 0; n0 < m.qp; n0 += 128)
+    for (int n0 = 0; n0 < m.qp; n0 += down_bn)
       for (int m0 = 0; m0 < m.rp; m0 += 32 * P.mb)
         for (int sp = 0; sp < f; ++sp) {
           ProjTile t{};
@@ -555,7 +559,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
   a.split_stride = P.lr_total;
   c->prof.begin(LORDO_K_DOWN, s);
-  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, c->at<float>(P.glow),
+  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_wide, c->at<float>(P.glow),
                           P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);

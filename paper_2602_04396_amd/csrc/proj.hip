@@ -55,6 +55,13 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
+// Direct global-to-LDS load of one 1 KiB operand fragment: lane i's 16 bytes land at
+// lds_dst_wave_base + i (checked on the hardware); the LDS address must be uniform over the wave.
+#define LDS_AS __attribute__((address_space(3)))
+__device__ __forceinline__ void dma16(const GAS u32x4* src, u32x4* lds_dst_wave_base) {
+  __builtin_amdgcn_global_load_lds((const GAS void*)src, (LDS_AS void*)lds_dst_wave_base, 16, 0, 0);
+}
+
 // ---------------------------------------------------------------------------------------
 // Down-projection.  Workgroup = 4 waves; output tile = (32*MB rank indices) x 128 columns.
 // Wave w owns rank block w % MB and MB column blocks starting at (w / MB) * MB.
@@ -255,10 +262,130 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
   }
 }
 
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, float* glow, int64_t split_stride,
-                            float grad_scale, bool g_is_f32, hipStream_t s) {
+// ---------------------------------------------------------------------------------------
+// Down-projection, main path (rank tile of 128, bf16 G): 8 waves, output tile 128 rank indices x
+// 256 columns.  Wave w owns rank block w % 4 and the four column blocks of half w / 4.
+// Per stage of 32 rows of G: the G tile (32 x 256) is read once, transposed in registers and staged
+// in LDS in fragment order (wave w stages the 8-row group w / 2 of column half w % 2); the Q
+// fragments of the stage (16 KiB) come in ONCE per workgroup by direct global-to-LDS loads.  Per byte
+// of G the vector L1 sees one byte of Q, against two in the 128-column kernel, and it is that
+// traffic, not HBM, which bounds the narrow kernel.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
+                                                        int64_t split_stride, float grad_scale) {
+  constexpr int BK = 32;
+  const ProjTile t = tiles[blockIdx.x];
+  if (t.mat < 0) return;
+  const MatDev m = d.mats[t.mat];
+  const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
+  const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
+
+  constexpr int GSLOTS = 8 * 4 * 32;                           // (nblk, kgrp, n) 16-byte slots of one stage
+  constexpr int ASLOTS = 4 * 2 * 2 * 64;                       // (mblk, kstep, plane, lane)
+  __shared__ u32x4 gfrag[2 * GSLOTS];                          // 32 KiB
+  __shared__ u32x4 afrag[2 * ASLOTS];                          // 32 KiB
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mb = wave & 3, nh = wave >> 2;                     // compute role
+  const int kgrp = wave >> 1, half = wave & 1;                 // G staging role
+  const int mbg = t.m0 / 32 + mb;
+  const bool active = mbg < m.rp / 32;
+
+  const int klim = t.k1 < m.p ? t.k1 : m.p;
+  const void* Gbase = ext_ptr(d, EXT_G, t.mat);
+  const uint32_t row_bytes = (uint32_t)m.q * 2u;
+  const rsrc_t rs = make_rsrc(Gbase, (uint32_t)klim * row_bytes);
+  const int col = t.n0 + 128 * half + 2 * lane;
+  GCol gc;
+  gc.vec = (m.q & 1) == 0 && (reinterpret_cast<uintptr_t>(Gbase) & 3) == 0;
+  gc.off0 = col < m.q ? (uint32_t)col * 2u : OOB;
+  gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 2u : OOB;
+  const int wslot = ((4 * half + (lane >> 4)) * 4 + kgrp) * 32 + 2 * (lane & 15);
+
+  // Q fragments of a stage: f = mblk*4 + ks*2 + plane; this wave brings in f = 2*wave and 2*wave + 1
+  const int64_t kgroups = m.pp / 8;
+  const int fmb = wave >> 1, fks = wave & 1;                   // both planes of (mblk, kstep)
+  const int fmbg = t.m0 / 32 + fmb < m.rp / 32 ? t.m0 / 32 + fmb : m.rp / 32 - 1;
+  const GAS u32x4* asrc_hi = qt_hi + (int64_t)fmbg * kgroups * 32 + lane;
+  const GAS u32x4* asrc_lo = qt_lo + (int64_t)fmbg * kgroups * 32 + lane;
+  const int kgmax = (int)kgroups - 2;
+  auto issue_a = [&](int kr, int sbuf) {
+    int kg = kr / 8 + 2 * fks;
+    kg = kg < kgmax ? kg : kgmax;                              // a stage may reach past the padded height
+    u32x4* dst = afrag + sbuf * ASLOTS + ((fmb * 2 + fks) * 2) * 64;
+    dma16(asrc_hi + (int64_t)kg * 32, dst);
+    dma16(asrc_lo + (int64_t)kg * 32, dst + 64);
+  };
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+
+  const int nstages = (t.k1 - t.k0 + BK - 1) / BK;
+  GStage<false> st;
+  load_gstage<false>(st, rs, row_bytes, t.k0 + 8 * kgrp, gc);
+  issue_a(t.k0, 0);
+  store_gstage<false>(st, gfrag, nullptr, wslot);
+  __builtin_amdgcn_s_waitcnt(0x0f70);                          // vmcnt(0): the fragments of stage 0 have landed
+  __syncthreads();
+
+  for (int s = 0; s < nstages; ++s) {
+    const int kr = t.k0 + s * BK;
+    if (s + 1 < nstages) {
+      load_gstage<false>(st, rs, row_bytes, kr + BK + 8 * kgrp, gc);
+      issue_a(kr + BK, (s + 1) & 1);
+    }
+    ISSUE_FENCE();
+    if (active) {
+      const u32x4* gb = gfrag + (s & 1) * GSLOTS;
+      const u32x4* ab = afrag + (s & 1) * ASLOTS + mb * 4 * 64;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 a_hi = as_bf(ab[(ks * 2 + 0) * 64 + lane]);
+        bf16x8 a_lo = as_bf(ab[(ks * 2 + 1) * 64 + lane]);
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          bf16x8 b = as_bf(gb[((4 * nh + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31)]);
+          acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[a], 0, 0, 0);
+          acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[a], 0, 0, 0);
+        }
+      }
+    }
+    ISSUE_FENCE();
+    if (s + 1 < nstages) store_gstage<false>(st, gfrag + ((s + 1) & 1) * GSLOTS, nullptr, wslot);
+    __builtin_amdgcn_s_waitcnt(0x0f70);                        // vmcnt(0): next stage's Q fragments have landed
+    __syncthreads();
+  }
+
+  if (!active) return;
+  GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + m.lr_off;
+  const int64_t rgroups = m.rp / 8;
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    int nbg = t.n0 / 32 + 4 * nh + a;
+    if (nbg >= m.qp / 32) continue;
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq) {
+      int64_t o = (((int64_t)nbg * rgroups + 4 * mbg + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+      f32x4 val;
+      val.x = grad_scale * acc[a][4 * vq];     val.y = grad_scale * acc[a][4 * vq + 1];
+      val.z = grad_scale * acc[a][4 * vq + 2]; val.w = grad_scale * acc[a][4 * vq + 3];
+      *reinterpret_cast<GAS f32x4*>(out + o) = val;
+    }
+  }
+}
+
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, float* glow,
+                            int64_t split_stride, float grad_scale, bool g_is_f32, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
+  if (wide) {
+    hipLaunchKernelGGL(k_proj_down_wide, grid, dim3(512), 0, s, d, tiles, glow, split_stride, grad_scale);
+    return hipGetLastError();
+  }
 #define LORDO_DOWN(MBV)                                                                                            \
   if (g_is_f32) hipLaunchKernelGGL((k_proj_down<MBV, true, 1>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
   else hipLaunchKernelGGL((k_proj_down<MBV, false, 2>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale);
@@ -457,11 +584,6 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 // the register-fed variant.  Chunks of 32 of the contraction (2 MFMA k-steps, 32 KiB of
 // fragments) are double-buffered; one barrier per chunk.
 // ---------------------------------------------------------------------------------------
-#define LDS_AS __attribute__((address_space(3)))
-__device__ __forceinline__ void dma16(const GAS u32x4* src, u32x4* lds_dst_wave_base) {
-  // lane i's 16 bytes land at lds_dst_wave_base + i; the LDS address must be uniform over the wave
-  __builtin_amdgcn_global_load_lds((const GAS void*)src, (LDS_AS void*)lds_dst_wave_base, 16, 0, 0);
-}
 
 __global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
                                                      const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
