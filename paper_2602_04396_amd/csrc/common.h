@@ -95,7 +95,7 @@ constexpr int NB = 64;            // Cholesky / triangular-solve block size
 // proj.hip
 hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, float* glow,
                             int64_t split_stride, float grad_scale, bool g_is_f32, hipStream_t s);
-hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* n_hi,
+hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
                           const uint16_t* n_lo, float lr, hipStream_t s);
 // gemm32.hip
 hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int src_is_bf16,

@@ -39,6 +39,7 @@ struct Plan {
   int64_t lr_total = 0;             // elements of one flat low-rank array
   int64_t nchunks = 0;
   int mb = 4;
+  int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
   bool down_wide = false;           // 8-wave, 256-column tiles of the down-projection (rank tile 128, bf16 G)
   int nsplit = 1;                   // largest split-K factor of the down-projection
   std::vector<int> splits;          // split-K factor per matrix (1, 2, 4 or 8)
@@ -293,8 +294,8 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.nchunks = chunks;
   P.mb = rp_max > 64 ? 4 : (rp_max > 32 ? 2 : 1);
   P.down_wide = P.mb == 4 && hp.grad_dtype == LORDO_BF16;
-  if (const char* e = getenv("LORDO_DOWN_WIDE")) P.down_wide = P.down_wide && atoi(e) != 0;   // tuning aid
   const int down_bn = P.down_wide ? 256 : 128;
+  P.up_waves = 4;
 
   // Split-K of the down-projection.  With few output tiles (small models) the long contraction
   // over p is cut into slices of about the shortest matrix's height, so that every workgroup
@@ -570,7 +571,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   bool w_vec = true;            // 16-byte accesses to W need q % 4 == 0 and 16-byte aligned pointers
   for (int i = 0; i < c->n; ++i)
     if ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
-  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
+  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, P.up_waves, c->at<uint16_t>(P.n_hi),
                         c->at<uint16_t>(P.n_lo), (float)lr, s));
   c->prof.end(LORDO_K_UP, s);
   c->t = t;

@@ -585,8 +585,11 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 // fragments) are double-buffered; one barrier per chunk.
 // ---------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
-                                                     const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
+template <int NW>           // waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64)
+__global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
+                                                         const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
+  constexpr int AM = NW == 4 ? 2 : 1;                      // row blocks per wave
+  constexpr int WM = 4 / AM;                               // wave rows
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
   const MatDev m = d.mats[t.mat];
@@ -600,30 +603,34 @@ __global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* _
   constexpr int TP = 36;
   constexpr int SLOTS = 2 * 2 * 4 * 4;
   __shared__ u32x4 frag[SLOTS * 64];                       // 64 KiB
-  static_assert(sizeof(u32x4) * SLOTS * 64 >= sizeof(float) * 4 * 32 * TP, "staging blocks must fit");
+  static_assert(sizeof(u32x4) * SLOTS * 64 >= sizeof(float) * NW * 32 * TP, "staging blocks must fit");
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave & 1, wn = wave >> 1;
+  const int wm = wave % WM, wn = wave / WM;
   const int mblocks = m.pp / 32, nblocks = m.qp / 32;
-  const int mb0 = t.m0 / 32 + 2 * wm, nb0 = t.n0 / 32 + 2 * wn;     // this wave's first row / column block
+  const int mb0 = t.m0 / 32 + AM * wm, nb0 = t.n0 / 32 + 2 * wn;    // this wave's first row / column block
   const int p = m.p, q = m.q;
   const int64_t rgroups = m.rp / 8;
   const int nchunks = m.rp / 32;
 
-  // this wave feeds block `wave` of both operands (clamped into the planes at the edges)
-  const int mbf = t.m0 / 32 + wave < mblocks ? t.m0 / 32 + wave : mblocks - 1;
-  const int nbf = t.n0 / 32 + wave < nblocks ? t.n0 / 32 + wave : nblocks - 1;
+  // feeding role: 32 fragments per chunk = (kind, blk) x (k-step, plane); NW = 4: wave w feeds block w of
+  // both kinds; NW = 8: wave w feeds block w % 4 of kind w / 4
+  const int fblk = wave & 3;
+  const int mbf = t.m0 / 32 + fblk < mblocks ? t.m0 / 32 + fblk : mblocks - 1;
+  const int nbf = t.n0 / 32 + fblk < nblocks ? t.n0 / 32 + fblk : nblocks - 1;
   const GAS u32x4* src[4] = {qa_hi + (int64_t)mbf * rgroups * 32 + lane, qa_lo + (int64_t)mbf * rgroups * 32 + lane,
                              nh + (int64_t)nbf * rgroups * 32 + lane, nl + (int64_t)nbf * rgroups * 32 + lane};
   auto issue_chunk = [&](int c, int s) {
 #pragma unroll
-    for (int kind = 0; kind < 2; ++kind)
+    for (int kind = 0; kind < 2; ++kind) {
+      if (NW == 8 && kind != (wave >> 2)) continue;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int pl = 0; pl < 2; ++pl)
-          dma16(src[kind * 2 + pl] + (int64_t)(2 * c + ks) * 64, frag + ((((s * 2 + kind) * 4 + wave) * 4) + ks * 2 + pl) * 64);
+          dma16(src[kind * 2 + pl] + (int64_t)(2 * c + ks) * 64, frag + ((((s * 2 + kind) * 4 + fblk) * 4) + ks * 2 + pl) * 64);
+    }
   };
 
   // W tile in row order: lane = (rr, c4): row rr + 8j of a block, columns 4*c4 .. 4*c4+3
@@ -641,38 +648,36 @@ __global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* _
   };
 
   issue_chunk(0, 0);
-  u32x4 wv[2][2][4];
+  u32x4 wv[AM][2][4];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < AM; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int j = 0; j < 4; ++j) wv[a][b][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff[b], w_soff(a, b, j), 0);
   ISSUE_FENCE();
 
-  f32x16 acc[2][2];
+  f32x16 acc[AM][2];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < AM; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
   for (int c = 0; c < nchunks; ++c) {
-    // chunk c was issued before everything that is still in flight except, for c == 0, the 16 W loads
-    if (c == 0) __builtin_amdgcn_s_waitcnt(0x0f70 | 0x4000);       // vmcnt(16): bits [3:0]=0, [15:14]=1
-    else __builtin_amdgcn_s_waitcnt(0x0f70);                       // vmcnt(0)
+    __builtin_amdgcn_s_waitcnt(0x0f70);                            // vmcnt(0): this wave's part of chunk c has landed
     __syncthreads();              // chunk c visible to all waves; every wave is done with chunk c-1
     if (c + 1 < nchunks) issue_chunk(c + 1, (c + 1) & 1);
     ISSUE_FENCE();
     const u32x4* fb = frag + (c & 1) * (2 * 4 * 4 * 64);
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      u32x4 qh[2], ql[2], xh[2], xl[2];
+      u32x4 qh[AM], ql[AM], xh[2], xl[2];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        qh[a] = fb[((0 * 4 + 2 * wm + a) * 4 + ks * 2 + 0) * 64 + lane];
-        ql[a] = fb[((0 * 4 + 2 * wm + a) * 4 + ks * 2 + 1) * 64 + lane];
+      for (int a = 0; a < AM; ++a) {
+        qh[a] = fb[((0 * 4 + AM * wm + a) * 4 + ks * 2 + 0) * 64 + lane];
+        ql[a] = fb[((0 * 4 + AM * wm + a) * 4 + ks * 2 + 1) * 64 + lane];
       }
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
@@ -680,7 +685,7 @@ __global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* _
         xl[b] = fb[((1 * 4 + 2 * wn + b) * 4 + ks * 2 + 1) * 64 + lane];
       }
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < AM; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {      // transposed block: N fragment first
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xh[b]), as_bf(qh[a]), acc[a][b], 0, 0, 0);
@@ -695,7 +700,7 @@ __global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* _
   // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e
   float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < AM; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
 #pragma unroll
@@ -718,11 +723,12 @@ __global__ __launch_bounds__(256) void k_proj_up_dma(DevCtx d, const ProjTile* _
     }
 }
 
-hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* n_hi,
+hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
                           const uint16_t* n_lo, float lr, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
-  if (vec) hipLaunchKernelGGL(k_proj_up_dma, grid, block, 0, s, d, tiles, n_hi, n_lo, lr);
+  if (vec && nwaves == 8) hipLaunchKernelGGL((k_proj_up_dma<8>), grid, dim3(512), 0, s, d, tiles, n_hi, n_lo, lr);
+  else if (vec) hipLaunchKernelGGL((k_proj_up_dma<4>), grid, block, 0, s, d, tiles, n_hi, n_lo, lr);
   else hipLaunchKernelGGL((k_proj_up<false>), grid, block, 0, s, d, tiles, n_hi, n_lo, lr);
   return hipGetLastError();
 }

@@ -56,6 +56,19 @@ def test_local_steps_bf16_small(torch):
     assert pair.opt.step == 4
 
 
+def test_local_steps_bf16_aligned_shapes(torch):
+    """Every q a multiple of 8 and every pointer 16-byte aligned: the 16-byte / direct-to-LDS kernels run
+    (the odd shapes above take the dword fallbacks); ragged p, q and r, r up to 256 (two rank tiles)."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (130, 264, 128), (520, 392, 256)]
+    pair = Pair(torch, shapes, _weights(shapes, 14), orc.Hyper(), lordo.hparams(grad_dtype=lordo.BF16), _rand_Q(shapes, 14))
+    gens = _spiked(shapes, 14, 8)
+    for t in range(3):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3, first_step_patch=(t == 0))
+        worst = pair.compare_local(TOL)
+    print("aligned shapes: worst rel L2", worst, flush=True)
+
+
 def test_local_steps_identity_init_and_grad_scale(torch):
     """Q_0 = first r columns of I (the library's own initial state), grad_scale != 1."""
     from paper_2602_04396_amd import lordo
