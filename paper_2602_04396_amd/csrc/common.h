@@ -39,6 +39,7 @@ struct MatDev {
   int64_t gram, lfac;     // fp32 r x r : Gram matrix (consumed by the factorisation) and its Cholesky factor
   int64_t dinv;           // fp32 ceil(r/NB) blocks of NB x NB : inverses of the diagonal blocks of the factor
   int64_t rot, rot2;      // fp32 r x r : R = Q_new^T Q_old and its elementwise square
+  int64_t part;           // fp32 split-K partial sums of the r x r products (Gram, R): slices x r x r
 };
 
 // Work item of the projection kernels.
@@ -66,9 +67,13 @@ struct GemmDesc {
   int64_t sAm, sAk, sBk, sBn;
   int32_t ldc, a_bf16, b_bf16, pad;   // a_bf16: 0 fp32, 1 bf16, 2 = element type given at launch (refresh source)
   float alpha, beta;
+  // split-K (ksplit > 1): slice s covers k in [s*klen, (s+1)*klen) and writes its raw M x N sum to
+  // P + s*M*N; a reduction kernel then adds the slices in order and applies alpha, beta, C2
+  int32_t ksplit, klen;
+  OpRef P;
 };
 
-struct GemmTile { int32_t desc; int16_t tm, tn; };
+struct GemmTile { int32_t desc; int16_t tm, tn; int16_t ks, pad; };
 
 // Device-side view handed to kernels.
 constexpr int EXT_SLOTS = 8;     // cached pointer tables per kind (e.g. alternating gradient buffers)
@@ -98,8 +103,9 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
                           const uint16_t* n_lo, float lr, hipStream_t s);
 // gemm32.hip
-hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int src_is_bf16,
+hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int tile, int src_is_bf16,
                          hipStream_t s);
+hipError_t launch_gemm_reduce(const DevCtx& d, const GemmDesc* descs, int ndescs, hipStream_t s);
 // elementwise.hip
 // Elements at flat position >= grp_start[i] are the sum of grp_nsplit[i] split-K slices of g.
 struct AdamArgs {

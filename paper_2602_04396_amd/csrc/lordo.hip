@@ -29,12 +29,16 @@ enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_ROT_PRE, OP_ROT_POST, OP_Q_F
 struct Op {
   int kind;
   int tile_first = 0, ntiles = 0;   // OP_GEMM
+  int tile = 64;                    // OP_GEMM: workgroup tile edge (64 or 128)
+  int desc_first = 0, ndescs = 0;   // OP_GEMM: descriptors of this launch
+  bool split = false;               // OP_GEMM: split-K launch, followed by the slice reduction
   int iarg = 0;                     // OP_POTF2: block index; OP_Q_FROM_Y: y buffer
   float farg = 0.f;                 // OP_SHIFT: coefficient
   bool rot_only = false;            // part of the moment rotation (skipped while t == 0)
 };
 
 struct Plan {
+  int part_slices = 1;              // K slices the split-K partial buffers are sized for
   size_t bytes = 0;
   int64_t lr_total = 0;             // elements of one flat low-rank array
   int64_t nchunks = 0;
@@ -54,6 +58,26 @@ struct Plan {
   std::vector<GemmTile> gtile_h;
   std::vector<Op> ops;
 };
+
+constexpr int MAX_KSPLIT = 16;
+
+// Launch shape of the r x r products with a long contraction, taken over all matrices: workgroup
+// tile edge and the number of K slices that brings the launch to about 1024 workgroups.
+static int small_out_split(const MatDev* mats, int n, int* tile_out) {
+  int64_t t128 = 0, t64 = 0;
+  bool big_ok = true;
+  for (int i = 0; i < n; ++i) {
+    const int r = mats[i].r;
+    if (r < 128) big_ok = false;
+    t128 += (int64_t)((r + 127) / 128) * ((r + 127) / 128);
+    t64 += (int64_t)((r + 63) / 64) * ((r + 63) / 64);
+  }
+  const bool big = big_ok && t128 >= 512;
+  if (tile_out) *tile_out = big ? 128 : 64;
+  const int64_t tiles = big ? t128 : t64;
+  if (tiles <= 0 || tiles >= 1024) return 1;
+  return (int)std::min<int64_t>(MAX_KSPLIT, (1024 + tiles - 1) / tiles);
+}
 
 struct Alloc {
   size_t cur = 0;
@@ -88,25 +112,56 @@ struct ProgramBuilder {
   int n;
   explicit ProgramBuilder(Plan& p, int n_) : P(p), n(n_) {}
 
+  // One grouped GEMM launch.  `small_out` marks r x r products with a long contraction (Gram matrix,
+  // rotation matrix): with few output tiles they are split along K so that the chip is filled.
   template <class F>
-  void gemm(F make, bool rot_only = false) {       // make(i, desc) -> false to skip matrix i
+  void gemm(F make, bool rot_only = false, bool small_out = false) {       // make(i, desc) -> false to skip matrix i
     Op op;
     op.kind = OP_GEMM;
     op.tile_first = (int)P.gtile_h.size();
     op.rot_only = rot_only;
+    std::vector<GemmDesc> made;
+    int64_t tiles128 = 0, tiles64 = 0;
+    bool big_ok = true;
     for (int i = 0; i < n; ++i) {
       GemmDesc g{};
       g.C2 = ref_none();
+      g.P = ref_none();
       g.alpha = 1.f;
       g.beta = 0.f;
       g.mat = i;
+      g.ksplit = 1;
       if (!make(i, g)) continue;
       if (g.M <= 0 || g.N <= 0 || g.K <= 0) continue;
+      if (g.M < 128 || g.N < 128) big_ok = false;
+      tiles128 += (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
+      tiles64 += (int64_t)((g.M + 63) / 64) * ((g.N + 63) / 64);
+      made.push_back(g);
+    }
+    op.tile = (big_ok && tiles128 >= 512) ? 128 : 64;
+    const int64_t tiles = op.tile == 128 ? tiles128 : tiles64;
+    int ksplit = 1;
+    if (small_out && tiles > 0 && tiles < 1024)
+      ksplit = (int)std::min<int64_t>(P.part_slices, (1024 + tiles - 1) / tiles);     // never more slices than allocated
+    op.desc_first = (int)P.desc_h.size();
+    for (GemmDesc g : made) {
+      int ks = ksplit;
+      int klen = ((g.K + ks - 1) / ks + 15) / 16 * 16;
+      ks = (g.K + klen - 1) / klen;
+      if (ks > 1) {
+        g.ksplit = ks;
+        g.klen = klen;
+        g.P = ref_arena(P.mat[g.mat].part);
+        op.split = true;
+      }
       int di = (int)P.desc_h.size();
       P.desc_h.push_back(g);
-      for (int tm = 0; tm < (g.M + 63) / 64; ++tm)
-        for (int tn = 0; tn < (g.N + 63) / 64; ++tn) P.gtile_h.push_back(GemmTile{di, (int16_t)tm, (int16_t)tn});
+      for (int sl = 0; sl < g.ksplit; ++sl)
+        for (int tm = 0; tm < (g.M + op.tile - 1) / op.tile; ++tm)
+          for (int tn = 0; tn < (g.N + op.tile - 1) / op.tile; ++tn)
+            P.gtile_h.push_back(GemmTile{di, (int16_t)tm, (int16_t)tn, (int16_t)sl, 0});
     }
+    op.ndescs = (int)P.desc_h.size() - op.desc_first;
     op.ntiles = (int)P.gtile_h.size() - op.tile_first;
     P.ops.push_back(op);
   }
@@ -135,7 +190,7 @@ struct ProgramBuilder {
         g.C = ref_arena(m.gram); g.ldc = m.r;
         g.M = m.r; g.N = m.r; g.K = rows_of(i);
         return true;
-      });
+      }, false, true);
       if (pass == 0) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
       for (int jb = 0; jb < max_blocks; ++jb) {
         simple(OP_POTF2, jb);
@@ -237,7 +292,7 @@ struct ProgramBuilder {
       g.C = ref_arena(m.rot); g.C2 = ref_arena(m.rot2); g.ldc = m.r;
       g.M = m.r; g.N = m.r; g.K = m.p;
       return true;
-    }, true);
+    }, true, true);
     simple(OP_ROT_PRE, 0, 0.f, true);
     for (int which = 0; which < 2; ++which)
       gemm([&](int i, GemmDesc& g) {
@@ -341,6 +396,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.v = A.take(sizeof(float) * lr);
   P.n_hi = A.take(sizeof(uint16_t) * lr);
   P.n_lo = A.take(sizeof(uint16_t) * lr);
+  P.part_slices = small_out_split(P.mat.data(), n, nullptr);
   for (int i = 0; i < n; ++i) {
     MatDev& m = P.mat[i];
     size_t pr = (size_t)m.p * m.r, pq = (size_t)m.p * m.q, qr = (size_t)m.q * m.r, rr = (size_t)m.r * m.r;
@@ -355,6 +411,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.gram = A.take(rr * 4); m.lfac = A.take(rr * 4);
     m.dinv = A.take((size_t)((m.r + NB - 1) / NB) * NB * NB * 4);
     m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
+    m.part = A.take(rr * 4 * P.part_slices);
   }
   // projection tile tables
   std::vector<ProjTile> down, up;
@@ -600,7 +657,8 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
     if (op.rot_only && !rotate) continue;
     switch (op.kind) {
       case OP_GEMM:
-        HIPCHK(launch_gemm32(c->dev, descs, tiles + op.tile_first, op.ntiles, src_dtype == LORDO_BF16, s));
+        HIPCHK(launch_gemm32(c->dev, descs, tiles + op.tile_first, op.ntiles, op.tile, src_dtype == LORDO_BF16, s));
+        if (op.split) HIPCHK(launch_gemm_reduce(c->dev, descs + op.desc_first, op.ndescs, s));
         break;
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
