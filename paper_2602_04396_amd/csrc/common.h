@@ -98,7 +98,7 @@ constexpr int NB = 64;            // Cholesky / triangular-solve block size
 // launchers (each defined in one .hip file)
 // ---------------------------------------------------------------------------------------
 // proj.hip
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, float* glow,
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, bool g_vec, float* glow,
                             int64_t split_stride, float grad_scale, bool g_is_f32, hipStream_t s);
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
                           const uint16_t* n_lo, float lr, hipStream_t s);

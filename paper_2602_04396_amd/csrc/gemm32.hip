@@ -8,87 +8,122 @@
 namespace lordo {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TK = 16;
+constexpr int TK = 32;
 
-__device__ __forceinline__ float load_elem(const char* base, int64_t idx, int is_bf16) {
-  if (is_bf16) {
-    uint32_t h = reinterpret_cast<const uint16_t*>(base)[idx];
-    return __uint_as_float(h << 16);
-  }
-  return reinterpret_cast<const float*>(base)[idx];
-}
+#define GAS __attribute__((address_space(1)))
 
 __device__ __forceinline__ const char* resolve(const DevCtx& d, const OpRef& r, int mat) {
   if (r.ext >= 0) return reinterpret_cast<const char*>(ext_ptr(d, r.ext, mat)) + r.off;
   return d.arena + r.off;
 }
 
-// 256 threads = 4 waves in a 2 x 2 grid; each wave WB x WB accumulator blocks of 32 x 32, so the
-// workgroup tile is 64*WB square (64 for small problems, 128 where both output sides reach 128).
-template <int WB>
-__global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __restrict__ descs,
-                                                const GemmTile* __restrict__ tiles, int src_is_bf16) {
-  constexpr int TM = 64 * WB, TN = 64 * WB;
-  constexpr int PITCH = TM + 4;
-  constexpr int PER_THREAD = TM * TK / 256;
-  const GemmTile t = tiles[blockIdx.x];
-  const GemmDesc g = descs[t.desc];
-  const int M = g.M, N = g.N;
-  const int kbeg = g.ksplit > 1 ? t.ks * g.klen : 0;
-  const int K = g.ksplit > 1 ? (kbeg + g.klen < g.K ? kbeg + g.klen : g.K) : g.K;     // end of this slice
-  const int m0 = t.tm * TM, n0 = t.tn * TN;
-  const int a_bf16 = g.a_bf16 == 2 ? src_is_bf16 : g.a_bf16;
-  const char* A = resolve(d, g.A, g.mat);
-  const char* B = resolve(d, g.B, g.mat);
-  float* C = reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C, g.mat)));
-  float* C2 = g.C2.off >= 0 ? reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C2, g.mat))) : nullptr;
+// One operand of a workgroup tile: X(i, k), i < LIM (the M or N side), k < kend, at base + i*s_i + k*s_k.
+// The tile is TMN x TK; a thread fetches NV vectors of four elements along the unit-stride direction
+// (scalar accesses at ragged edges and for unaligned operands) and later writes them to LDS as
+// S[k][i], the order the matrix-core operands are read in.
+template <int TMN, int NV>
+struct Operand {
+  const char* base;
+  int64_t s_i, s_k;
+  int is_bf16, lim, kend, i0;
+  bool kfast, vec_ok;
 
-  __shared__ float As[TK][PITCH];
-  __shared__ float Bs[TK][PITCH];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave & 1) * 32 * WB, wn = (wave >> 1) * 32 * WB;
-
-  // loader mapping: the unit-stride direction of each operand varies fastest across threads
-  const bool a_kfast = g.sAk == 1 && g.sAm != 1;
-  const bool b_kfast = g.sBk == 1 && g.sBn != 1;
-
-  f32x16 acc[WB][WB];
+  __device__ __forceinline__ void setup(const char* b, int64_t si, int64_t sk, int bf, int lim_, int kend_, int i0_, int kbeg) {
+    base = b; s_i = si; s_k = sk; is_bf16 = bf; lim = lim_; kend = kend_; i0 = i0_;
+    kfast = sk == 1 && si != 1;
+    const int64_t s_fast = kfast ? sk : si, s_slow = kfast ? si : sk;
+    const int n_fast = kfast ? kend_ : lim_;
+    const uintptr_t align = is_bf16 ? 7 : 15;
+    // whole vectors only: every vector then lies entirely inside or entirely outside the operand
+    vec_ok = s_fast == 1 && (s_slow & 3) == 0 && (n_fast & 3) == 0 && (reinterpret_cast<uintptr_t>(b) & align) == 0 && (kbeg & 3) == 0;
+  }
+  __device__ __forceinline__ void coords(int v, int& ii, int& kk) const {
+    if (kfast) { kk = (v % (TK / 4)) * 4; ii = v / (TK / 4); }
+    else { ii = (v % (TMN / 4)) * 4; kk = v / (TMN / 4); }
+  }
+  // Branch-free: an element outside the operand is read from element 0 (always valid) and replaced
+  // by zero when the tile is written to LDS.  fetch_raw only issues the loads and leaves the loaded
+  // bits untouched, so nothing waits for them until stash() runs one K step later.
+  template <bool BF16, bool VEC>
+  __device__ __forceinline__ void fetch_raw(u32x4 (&raw)[NV], int k0, int tid) const {
+    const int64_t e_step = kfast ? s_k : s_i;                        // from one element of a vector to the next
+    const int d_i = kfast ? 0 : 1, d_k = kfast ? 1 : 0;
 #pragma unroll
-  for (int a = 0; a < WB; ++a)
+    for (int n = 0; n < NV; ++n) {
+      int ii, kk;
+      coords(tid + n * 256, ii, kk);
+      const int gi = i0 + ii, gk = k0 + kk;
+      const int64_t idx = (int64_t)gi * s_i + (int64_t)gk * s_k;
+      if constexpr (VEC) {
+        const int64_t at = (gi < lim && gk < kend) ? idx : 0;
+        if constexpr (BF16) {
+          u32x2 w = *reinterpret_cast<const GAS u32x2*>((const GAS char*)base + at * 2);
+          raw[n].x = w.x; raw[n].y = w.y;
+        } else {
+          raw[n] = *reinterpret_cast<const GAS u32x4*>((const GAS char*)base + at * 4);
+        }
+      } else {
 #pragma unroll
-    for (int b = 0; b < WB; ++b)
+        for (int e = 0; e < 4; ++e) {
+          const bool ok = gi + e * d_i < lim && gk + e * d_k < kend;
+          const int64_t at = ok ? idx + e * e_step : 0;
+          if constexpr (BF16) raw[n][e] = *reinterpret_cast<const GAS uint16_t*>((const GAS char*)base + at * 2);
+          else raw[n][e] = *reinterpret_cast<const GAS uint32_t*>((const GAS char*)base + at * 4);
+        }
+      }
+    }
+  }
+  // Converts the raw bits of the tile starting at k0, zeroes what lies outside the operand and writes S[k][i].
+  template <bool BF16, bool VEC>
+  __device__ __forceinline__ void stash(const u32x4 (&raw)[NV], float (*S)[TMN + 4], int k0, int tid) const {
+    const int d_i = kfast ? 0 : 1, d_k = kfast ? 1 : 0;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    for (int n = 0; n < NV; ++n) {
+      int ii, kk;
+      coords(tid + n * 256, ii, kk);
+      const int gi = i0 + ii, gk = k0 + kk;
+      f32x4 r;
+      if constexpr (VEC && BF16) {
+        r.x = __uint_as_float(raw[n].x << 16); r.y = __uint_as_float(raw[n].x & 0xffff0000u);
+        r.z = __uint_as_float(raw[n].y << 16); r.w = __uint_as_float(raw[n].y & 0xffff0000u);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = __uint_as_float(BF16 ? raw[n][e] << 16 : raw[n][e]);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (!(gi + e * d_i < lim && gk + e * d_k < kend)) r[e] = 0.f;
+      if (kfast) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) S[kk + e][ii] = r[e];
+      } else {
+        *reinterpret_cast<f32x4*>(&S[kk][ii]) = r;
+      }
+    }
+  }
+};
 
+// K loop of one workgroup tile, specialised on the element type of A and on whole-vector access.
+template <int WB, bool A_BF16, bool VEC, int TM, int NV>
+__device__ __forceinline__ void gemm_loop(f32x16 (&acc)[WB][WB], const Operand<TM, NV>& opA, const Operand<TM, NV>& opB,
+                                          float (*As)[TM + 4], float (*Bs)[TM + 4], int kbeg, int K, int tid, int lane, int wm, int wn) {
+  u32x4 ra[NV], rb[NV];
+  opA.template fetch_raw<A_BF16, VEC>(ra, kbeg, tid);
+  opB.template fetch_raw<false, VEC>(rb, kbeg, tid);
   for (int k0 = kbeg; k0 < K; k0 += TK) {
-    float ra[PER_THREAD], rb[PER_THREAD];
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-      int idx = tid + i * 256;                 // 0 .. TM*TK-1
-      int mm, kk;
-      if (a_kfast) { kk = idx % TK; mm = idx / TK; } else { mm = idx % TM; kk = idx / TM; }
-      int gm = m0 + mm, gk = k0 + kk;
-      ra[i] = (gm < M && gk < K) ? load_elem(A, (int64_t)gm * g.sAm + (int64_t)gk * g.sAk, a_bf16) : 0.f;
-      int nn, kb;
-      if (b_kfast) { kb = idx % TK; nn = idx / TK; } else { nn = idx % TN; kb = idx / TN; }
-      int gn = n0 + nn, gkb = k0 + kb;
-      rb[i] = (gn < N && gkb < K) ? load_elem(B, (int64_t)gkb * g.sBk + (int64_t)gn * g.sBn, g.b_bf16) : 0.f;
-    }
     __syncthreads();                           // previous tile fully consumed
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-      int idx = tid + i * 256;
-      int mm, kk;
-      if (a_kfast) { kk = idx % TK; mm = idx / TK; } else { mm = idx % TM; kk = idx / TM; }
-      As[kk][mm] = ra[i];
-      int nn, kb;
-      if (b_kfast) { kb = idx % TK; nn = idx / TK; } else { nn = idx % TN; kb = idx / TN; }
-      Bs[kb][nn] = rb[i];
-    }
+    opA.template stash<A_BF16, VEC>(ra, As, k0, tid);
+    opB.template stash<false, VEC>(rb, Bs, k0, tid);
     __syncthreads();
+    if (k0 + TK < K) {
+      opA.template fetch_raw<A_BF16, VEC>(ra, k0 + TK, tid);
+      opB.template fetch_raw<false, VEC>(rb, k0 + TK, tid);
+    }
+    asm volatile("" ::: "memory");             // keep the loads above the arithmetic: they must be in flight during it
 #pragma unroll
     for (int kk = 0; kk < TK; kk += 2) {
       float av[WB], bv[WB];
@@ -100,6 +135,56 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
       for (int a = 0; a < WB; ++a)
 #pragma unroll
         for (int b = 0; b < WB; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+    }
+  }
+}
+
+// 256 threads = 4 waves in a 2 x 2 grid; each wave WB x WB accumulator blocks of 32 x 32, so the
+// workgroup tile is 64*WB square (64 for small problems, 128 for large launches).  The next K tile
+// is fetched into registers while the matrix cores work on the one in LDS.
+template <int WB>
+__global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __restrict__ descs,
+                                                const GemmTile* __restrict__ tiles, int src_is_bf16) {
+  constexpr int TM = 64 * WB, TN = 64 * WB;
+  constexpr int PITCH = TM + 4;
+  constexpr int NV = TM * TK / 4 / 256;
+  const GemmTile t = tiles[blockIdx.x];
+  const GemmDesc g = descs[t.desc];
+  const int M = g.M, N = g.N;
+  const int kbeg = g.ksplit > 1 ? t.ks * g.klen : 0;
+  const int K = g.ksplit > 1 ? (kbeg + g.klen < g.K ? kbeg + g.klen : g.K) : g.K;     // end of this slice
+  const int m0 = t.tm * TM, n0 = t.tn * TN;
+  const int a_bf16 = g.a_bf16 == 2 ? src_is_bf16 : g.a_bf16;
+  float* C = reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C, g.mat)));
+  float* C2 = g.C2.off >= 0 ? reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C2, g.mat))) : nullptr;
+
+  __shared__ __attribute__((aligned(16))) float As[TK][PITCH];
+  __shared__ __attribute__((aligned(16))) float Bs[TK][PITCH];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave & 1) * 32 * WB, wn = (wave >> 1) * 32 * WB;
+
+  Operand<TM, NV> opA, opB;
+  opA.setup(resolve(d, g.A, g.mat), g.sAm, g.sAk, a_bf16, M, K, m0, kbeg);
+  opB.setup(resolve(d, g.B, g.mat), g.sBn, g.sBk, 0, N, K, n0, kbeg);
+
+  f32x16 acc[WB][WB];
+#pragma unroll
+  for (int a = 0; a < WB; ++a)
+#pragma unroll
+    for (int b = 0; b < WB; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  if (kbeg < K) {
+    const bool vec = opA.vec_ok && opB.vec_ok;
+    if (a_bf16) {
+      if (vec) gemm_loop<WB, true, true>(acc, opA, opB, As, Bs, kbeg, K, tid, lane, wm, wn);
+      else gemm_loop<WB, true, false>(acc, opA, opB, As, Bs, kbeg, K, tid, lane, wm, wn);
+    } else {
+      if (vec) gemm_loop<WB, false, true>(acc, opA, opB, As, Bs, kbeg, K, tid, lane, wm, wn);
+      else gemm_loop<WB, false, false>(acc, opA, opB, As, Bs, kbeg, K, tid, lane, wm, wn);
     }
   }
 

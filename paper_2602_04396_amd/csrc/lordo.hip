@@ -146,7 +146,7 @@ struct ProgramBuilder {
     op.desc_first = (int)P.desc_h.size();
     for (GemmDesc g : made) {
       int ks = ksplit;
-      int klen = ((g.K + ks - 1) / ks + 15) / 16 * 16;
+      int klen = ((g.K + ks - 1) / ks + 31) / 32 * 32;
       ks = (g.K + klen - 1) / klen;
       if (ks > 1) {
         g.ksplit = ks;
@@ -616,8 +616,11 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   a.eps = (float)c->hp.eps;
   for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
   a.split_stride = P.lr_total;
+  bool g_vec = true;            // 4-byte accesses to a bf16 G need an even q and 4-byte aligned pointers
+  for (int i = 0; i < c->n; ++i)
+    if ((P.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 3) != 0) { g_vec = false; break; }
   c->prof.begin(LORDO_K_DOWN, s);
-  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_wide, c->at<float>(P.glow),
+  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_wide, g_vec, c->at<float>(P.glow),
                           P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);

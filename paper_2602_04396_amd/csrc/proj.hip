@@ -81,13 +81,15 @@ struct GCol {
   bool vec;           // both columns with one aligned access
 };
 
-// Rows krow .. krow+7 (krow uniform over the wave) of the lane's two columns.
+// Rows krow .. krow+7 (krow uniform over the wave) of the lane's two columns.  The resource ends
+// after row `rows`; a row at or beyond it is clamped to `rows`, which puts the scalar offset exactly
+// at the end of the resource, so every lane of that access is out of range and reads zero.
 template <bool GF32>
-__device__ __forceinline__ void load_gstage(GStage<GF32>& st, rsrc_t rs, uint32_t row_bytes, int krow, const GCol& gc) {
+__device__ __forceinline__ void load_gstage(GStage<GF32>& st, rsrc_t rs, uint32_t row_bytes, int krow, int rows, const GCol& gc) {
   if (gc.vec) {                     // uniform branch, taken once per stage
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const uint32_t soff = (uint32_t)(krow + i) * row_bytes;       // scalar
+      const uint32_t soff = (uint32_t)(krow + i < rows ? krow + i : rows) * row_bytes;       // scalar
       if constexpr (!GF32) {
         st.x[i] = __builtin_amdgcn_raw_buffer_load_b32(rs, gc.off0, soff, 0);
       } else {
@@ -99,7 +101,7 @@ __device__ __forceinline__ void load_gstage(GStage<GF32>& st, rsrc_t rs, uint32_
   } else {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const uint32_t soff = (uint32_t)(krow + i) * row_bytes;
+      const uint32_t soff = (uint32_t)(krow + i < rows ? krow + i : rows) * row_bytes;
       if constexpr (!GF32) {
         uint32_t lo = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, gc.off0, soff, 0);
         uint32_t hi = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, gc.off1, soff, 0);
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
   };
   GStage<GF32> st[KG];
 #pragma unroll
-  for (int h = 0; h < KG; ++h) load_gstage<GF32>(st[h], rs, row_bytes, t.k0 + 8 * (h * 4 + wave), gc);
+  for (int h = 0; h < KG; ++h) load_gstage<GF32>(st[h], rs, row_bytes, t.k0 + 8 * (h * 4 + wave), klim, gc);
   load_a(a_cur, t.k0);
 #pragma unroll
   for (int h = 0; h < KG; ++h) store_gstage<GF32>(st[h], lds_hi, lds_lo, wslot + h * 4 * 32);
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
     const int kr = t.k0 + s * BK;
     if (s + 1 < nstages) {
 #pragma unroll
-      for (int h = 0; h < KG; ++h) load_gstage<GF32>(st[h], rs, row_bytes, kr + BK + 8 * (h * 4 + wave), gc);
+      for (int h = 0; h < KG; ++h) load_gstage<GF32>(st[h], rs, row_bytes, kr + BK + 8 * (h * 4 + wave), klim, gc);
       load_a(a_nxt, kr + BK);
     }
     ISSUE_FENCE();
@@ -267,10 +269,32 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
 // 256 columns.  Wave w owns rank block w % 4 and the four column blocks of half w / 4.
 // Per stage of 32 rows of G: the G tile (32 x 256) is read once, transposed in registers and staged
 // in LDS in fragment order (wave w stages the 8-row group w / 2 of column half w % 2); the Q
-// fragments of the stage (16 KiB) come in ONCE per workgroup by direct global-to-LDS loads.  Per byte
-// of G the vector L1 sees one byte of Q, against two in the 128-column kernel, and it is that
-// traffic, not HBM, which bounds the narrow kernel.
+// fragments of the stage (16 KiB) come in ONCE per workgroup by direct global-to-LDS loads.
+//
+// Software pipeline.  In iteration s the workgroup multiplies stage s (in LDS) while the Q
+// fragments of stage s+1 and the G rows of stage s+2 are in flight; the G rows of stage s+1, read
+// one iteration earlier, wait in registers and go to LDS at the end of the iteration.  The
+// global-to-LDS loads are issued from inline assembly: the compiler would otherwise make every LDS
+// access that follows such a load wait for it, which serialises memory latency and arithmetic.
+// The waits are therefore explicit: vector-memory operations complete in issue order, the
+// Q fragments of stage s+1 are issued BEFORE the G loads of stage s+2, so "at most one stage of G
+// loads outstanding" implies that the fragments have landed.
 // ---------------------------------------------------------------------------------------
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+// Lane i's 16 bytes land at lds_dst_wave_base + i.  M0 carries the LDS address; one wait state is
+// required between the write of M0 and the load that uses it.
+__device__ __forceinline__ void dma16_async(const GAS u32x4* src, u32x4* lds_dst_wave_base) {
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(LDS_AS void*)lds_dst_wave_base;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+// Wait until at most N vector-memory operations are outstanding and all LDS operations are done,
+// then the workgroup barrier (no wait for the N youngest loads, unlike __syncthreads()).
+#define WAIT_VM_BARRIER(N) asm volatile("s_waitcnt vmcnt(" #N ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+template <bool VEC>      // VEC: every G row is read with aligned 4-byte accesses (8 loads per stage, else 16)
 __global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
                                                         int64_t split_stride, float grad_scale) {
   constexpr int BK = 32;
@@ -298,14 +322,14 @@ __global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile
   const rsrc_t rs = make_rsrc(Gbase, (uint32_t)klim * row_bytes);
   const int col = t.n0 + 128 * half + 2 * lane;
   GCol gc;
-  gc.vec = (m.q & 1) == 0 && (reinterpret_cast<uintptr_t>(Gbase) & 3) == 0;
+  gc.vec = VEC;
   gc.off0 = col < m.q ? (uint32_t)col * 2u : OOB;
   gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 2u : OOB;
   const int wslot = ((4 * half + (lane >> 4)) * 4 + kgrp) * 32 + 2 * (lane & 15);
 
-  // Q fragments of a stage: f = mblk*4 + ks*2 + plane; this wave brings in f = 2*wave and 2*wave + 1
+  // Q fragments of a stage: f = mblk*4 + ks*2 + plane; this wave brings in both planes of (mblk, kstep)
   const int64_t kgroups = m.pp / 8;
-  const int fmb = wave >> 1, fks = wave & 1;                   // both planes of (mblk, kstep)
+  const int fmb = wave >> 1, fks = wave & 1;
   const int fmbg = t.m0 / 32 + fmb < m.rp / 32 ? t.m0 / 32 + fmb : m.rp / 32 - 1;
   const GAS u32x4* asrc_hi = qt_hi + (int64_t)fmbg * kgroups * 32 + lane;
   const GAS u32x4* asrc_lo = qt_lo + (int64_t)fmbg * kgroups * 32 + lane;
@@ -314,8 +338,8 @@ __global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile
     int kg = kr / 8 + 2 * fks;
     kg = kg < kgmax ? kg : kgmax;                              // a stage may reach past the padded height
     u32x4* dst = afrag + sbuf * ASLOTS + ((fmb * 2 + fks) * 2) * 64;
-    dma16(asrc_hi + (int64_t)kg * 32, dst);
-    dma16(asrc_lo + (int64_t)kg * 32, dst + 64);
+    dma16_async(asrc_hi + (int64_t)kg * 32, dst);
+    dma16_async(asrc_lo + (int64_t)kg * 32, dst + 64);
   };
 
   f32x16 acc[4];
@@ -324,41 +348,57 @@ __global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
 
-  const int nstages = (t.k1 - t.k0 + BK - 1) / BK;
-  GStage<false> st;
-  load_gstage<false>(st, rs, row_bytes, t.k0 + 8 * kgrp, gc);
-  issue_a(t.k0, 0);
-  store_gstage<false>(st, gfrag, nullptr, wslot);
-  __builtin_amdgcn_s_waitcnt(0x0f70);                          // vmcnt(0): the fragments of stage 0 have landed
-  __syncthreads();
-
-  for (int s = 0; s < nstages; ++s) {
-    const int kr = t.k0 + s * BK;
-    if (s + 1 < nstages) {
-      load_gstage<false>(st, rs, row_bytes, kr + BK + 8 * kgrp, gc);
-      issue_a(kr + BK, (s + 1) & 1);
-    }
-    ISSUE_FENCE();
-    if (active) {
-      const u32x4* gb = gfrag + (s & 1) * GSLOTS;
-      const u32x4* ab = afrag + (s & 1) * ASLOTS + mb * 4 * 64;
+  auto compute = [&](int sbuf) {
+    if (!active) return;
+    const u32x4* gb = gfrag + sbuf * GSLOTS;
+    const u32x4* ab = afrag + sbuf * ASLOTS + mb * 4 * 64;
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        bf16x8 a_hi = as_bf(ab[(ks * 2 + 0) * 64 + lane]);
-        bf16x8 a_lo = as_bf(ab[(ks * 2 + 1) * 64 + lane]);
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 a_hi = as_bf(ab[(ks * 2 + 0) * 64 + lane]);
+      bf16x8 a_lo = as_bf(ab[(ks * 2 + 1) * 64 + lane]);
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          bf16x8 b = as_bf(gb[((4 * nh + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31)]);
-          acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[a], 0, 0, 0);
-          acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[a], 0, 0, 0);
-        }
+      for (int a = 0; a < 4; ++a) {
+        bf16x8 b = as_bf(gb[((4 * nh + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31)]);
+        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[a], 0, 0, 0);
+        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[a], 0, 0, 0);
       }
     }
-    ISSUE_FENCE();
-    if (s + 1 < nstages) store_gstage<false>(st, gfrag + ((s + 1) & 1) * GSLOTS, nullptr, wslot);
-    __builtin_amdgcn_s_waitcnt(0x0f70);                        // vmcnt(0): next stage's Q fragments have landed
-    __syncthreads();
+  };
+
+  const int nstages = (t.k1 - t.k0 + BK - 1) / BK;
+  const int krow0 = t.k0 + 8 * kgrp;
+  // Rows at or beyond the end of the slice are read as zero (the loader clamps the row to the size of
+  // the resource), so the loads of stages past the last one are issued unconditionally: the number of
+  // outstanding loads is then the same in every iteration, which the explicit waits rely on.
+  GStage<false> st0, st1;
+  issue_a(t.k0, 0);
+  load_gstage<false>(st0, rs, row_bytes, krow0, klim, gc);                  // stage 0
+  load_gstage<false>(st1, rs, row_bytes, krow0 + BK, klim, gc);             // stage 1
+  store_gstage<false>(st0, gfrag, nullptr, wslot);
+  if constexpr (VEC) WAIT_VM_BARRIER(8); else WAIT_VM_BARRIER(16);
+
+  // one iteration; NEXT holds stage s+1 (read one iteration ago), LOAD receives stage s+2
+#define LORDO_DOWN_ITER(S, NEXT, LOAD)                                                            \
+  {                                                                                               \
+    const int kr = t.k0 + (S) * BK;                                                               \
+    if ((S) + 1 < nstages) issue_a(kr + BK, ((S) + 1) & 1);                                       \
+    load_gstage<false>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc);                    \
+    ISSUE_FENCE();                                                                                \
+    compute((S) & 1);                                                                             \
+    ISSUE_FENCE();                                                                                \
+    store_gstage<false>(NEXT, gfrag + (((S) + 1) & 1) * GSLOTS, nullptr, wslot);                  \
+    if constexpr (VEC) WAIT_VM_BARRIER(8); else WAIT_VM_BARRIER(16);                              \
   }
+  // two stages per trip so that the two register sets alternate statically; the odd last stage is
+  // peeled (an exit in the middle of the trip would make the compiler treat loads as outstanding
+  // at the loop head that are not)
+  int s = 0;
+  for (; s + 1 < nstages; s += 2) {
+    LORDO_DOWN_ITER(s, st1, st0)
+    LORDO_DOWN_ITER(s + 1, st0, st1)
+  }
+  if (s < nstages) LORDO_DOWN_ITER(s, st1, st0)
+#undef LORDO_DOWN_ITER
 
   if (!active) return;
   GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + m.lr_off;
@@ -378,12 +418,13 @@ __global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile
   }
 }
 
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, float* glow,
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, bool g_vec, float* glow,
                             int64_t split_stride, float grad_scale, bool g_is_f32, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
   if (wide) {
-    hipLaunchKernelGGL(k_proj_down_wide, grid, dim3(512), 0, s, d, tiles, glow, split_stride, grad_scale);
+    if (g_vec) hipLaunchKernelGGL(k_proj_down_wide<true>, grid, dim3(512), 0, s, d, tiles, glow, split_stride, grad_scale);
+    else hipLaunchKernelGGL(k_proj_down_wide<false>, grid, dim3(512), 0, s, d, tiles, glow, split_stride, grad_scale);
     return hipGetLastError();
   }
 #define LORDO_DOWN(MBV)                                                                                            \
