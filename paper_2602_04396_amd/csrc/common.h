@@ -49,7 +49,8 @@ struct ProjTile {
   int32_t n0;             // first column of the tile (column of W)
   int32_t k0, k1;         // contraction range (down: rows of W; up: unused)
   int32_t split;          // split-K slice index of the output (down)
-  int32_t pad0, pad1;
+  int32_t fuse;           // down: the tile holds the whole contraction and applies Adam to its state elements
+  int32_t pad1;
 };
 
 // Operand reference of the generic GEMM: arena offset, or caller pointer from table `ext`.
@@ -98,8 +99,9 @@ constexpr int NB = 64;            // Cholesky / triangular-solve block size
 // launchers (each defined in one .hip file)
 // ---------------------------------------------------------------------------------------
 // proj.hip
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, bool g_vec, float* glow,
-                            int64_t split_stride, float grad_scale, bool g_is_f32, hipStream_t s);
+struct DownFuse;     // below: state arrays and coefficients of the Adam update fused into the down-projection
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_waves, bool g_vec, float* glow,
+                            int64_t split_stride, float grad_scale, bool g_is_f32, const DownFuse* fuse, hipStream_t s);
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
                           const uint16_t* n_lo, float lr, hipStream_t s);
 // gemm32.hip
@@ -113,6 +115,14 @@ struct AdamArgs {
   int32_t grp_nsplit[4];
   int64_t grp_start[4];
   int64_t split_stride;
+  int64_t first;          // flat position of the first element the stand-alone kernel updates
+};
+struct DownFuse {
+  float* u;
+  float* v;
+  uint16_t* n_hi;
+  uint16_t* n_lo;
+  AdamArgs a;
 };
 hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
                        const AdamArgs& a, hipStream_t s);

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
                                               uint16_t* __restrict__ n_lo, int64_t ngroups, AdamArgs a) {
   int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (gidx >= ngroups) return;
-  int64_t base = gidx * 8;
+  int64_t base = a.first + gidx * 8;
   float g[8], uu[8], vv[8];
   {
     const float4* gp = reinterpret_cast<const float4*>(glow + base);
@@ -79,8 +79,8 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
 
 hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
                        const AdamArgs& a, hipStream_t s) {
-  int64_t ngroups = nelem / 8;
-  if (ngroups == 0) return hipSuccess;
+  int64_t ngroups = (nelem - a.first) / 8;            // a.first and nelem are multiples of 8
+  if (ngroups <= 0) return hipSuccess;
   unsigned blocks = (unsigned)((ngroups + 255) / 256);
   hipLaunchKernelGGL(k_adam, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
   return hipGetLastError();

@@ -44,7 +44,8 @@ struct Plan {
   int64_t nchunks = 0;
   int mb = 4;
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
-  bool down_wide = false;           // 8-wave, 256-column tiles of the down-projection (rank tile 128, bf16 G)
+  int down_pipe = 0;                // waves of the pipelined down-projection (8: 256-column tiles, 4: 128-column; 0: plain kernel)
+  int64_t adam_first = 0;           // flat position from which the stand-alone Adam kernel runs (elements before it are fused)
   int nsplit = 1;                   // largest split-K factor of the down-projection
   std::vector<int> splits;          // split-K factor per matrix (1, 2, 4 or 8)
   int32_t grp_nsplit[4] = {1, 1, 1, 1};
@@ -348,8 +349,10 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.chunk_start_h[n] = chunks;
   P.nchunks = chunks;
   P.mb = rp_max > 64 ? 4 : (rp_max > 32 ? 2 : 1);
-  P.down_wide = P.mb == 4 && hp.grad_dtype == LORDO_BF16;
-  const int down_bn = P.down_wide ? 256 : 128;
+  // Down-projection launch shape: the pipelined kernel (rank tiles of 128, bf16 G, 256-column
+  // tiles) where it applies, else the plain kernel with 128-column tiles.
+  P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16) ? 8 : 0;
+  const int down_bn = P.down_pipe == 8 ? 256 : 128;
   P.up_waves = 4;
 
   // Split-K of the down-projection.  With few output tiles (small models) the long contraction
@@ -391,6 +394,11 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     }
   }
   P.lr_total = lr;
+  // Adam rides in the epilogue of the pipelined down-projection when no matrix is split, i.e. when
+  // the launch has several rounds of workgroups and the epilogue of one overlaps the main loop of
+  // another; a launch that needs split-K is a single round of workgroups in lock step, where the
+  // stand-alone kernel is as fast and leaves the down-projection shorter.
+  P.adam_first = (P.down_pipe && P.nsplit == 1) ? lr : 0;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);
   P.v = A.take(sizeof(float) * lr);
@@ -425,6 +433,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
           ProjTile t{};
           t.mat = i; t.m0 = m0; t.n0 = n0; t.split = sp;
           t.k0 = std::min(sp * klen, m.pp); t.k1 = std::min(t.k0 + klen, m.pp);
+          t.fuse = (P.down_pipe && P.nsplit == 1) ? 1 : 0;
           down.push_back(t);
         }
     for (int m0 = 0; m0 < m.pp; m0 += 128)
@@ -616,16 +625,22 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   a.eps = (float)c->hp.eps;
   for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
   a.split_stride = P.lr_total;
+  a.first = P.adam_first;
   bool g_vec = true;            // 4-byte accesses to a bf16 G need an even q and 4-byte aligned pointers
   for (int i = 0; i < c->n; ++i)
     if ((P.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 3) != 0) { g_vec = false; break; }
+  DownFuse fuse;
+  fuse.u = c->at<float>(P.u); fuse.v = c->at<float>(P.v);
+  fuse.n_hi = c->at<uint16_t>(P.n_hi); fuse.n_lo = c->at<uint16_t>(P.n_lo);
+  fuse.a = a;
   c->prof.begin(LORDO_K_DOWN, s);
-  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_wide, g_vec, c->at<float>(P.glow),
-                          P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
+  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, c->at<float>(P.glow),
+                          P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, &fuse, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
-  HIPCHK(launch_adam(c->at<float>(P.glow), c->at<float>(P.u), c->at<float>(P.v), c->at<uint16_t>(P.n_hi),
-                     c->at<uint16_t>(P.n_lo), P.lr_total, a, s));
+  if (P.adam_first < P.lr_total)
+    HIPCHK(launch_adam(c->at<float>(P.glow), c->at<float>(P.u), c->at<float>(P.v), c->at<uint16_t>(P.n_hi),
+                       c->at<uint16_t>(P.n_lo), P.lr_total, a, s));
   c->prof.end(LORDO_K_ADAM, s);
   c->prof.begin(LORDO_K_UP, s);
   bool w_vec = true;            // 16-byte accesses to W need q % 4 == 0 and 16-byte aligned pointers

@@ -294,25 +294,61 @@ __device__ __forceinline__ void dma16_async(const GAS u32x4* src, u32x4* lds_dst
 // then the workgroup barrier (no wait for the N youngest loads, unlike __syncthreads()).
 #define WAIT_VM_BARRIER(N) asm volatile("s_waitcnt vmcnt(" #N ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
-template <bool VEC>      // VEC: every G row is read with aligned 4-byte accesses (8 loads per stage, else 16)
-__global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
-                                                        int64_t split_stride, float grad_scale) {
+// Low-rank Adam on four consecutive state elements (Alg. 1, moment and direction lines; the same
+// arithmetic, in the same order, as the stand-alone Adam kernel).
+struct FusedAdam {
+  float* u;
+  float* v;
+  uint16_t* n_hi;
+  uint16_t* n_lo;
+  float b1, omb1, b2, omb2, inv_c1, inv_c2, eps;
+};
+
+__device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f32x4 uu, f32x4 vv) {
+  uint32_t hi[4], lo[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float un = fmaf(f.b1, uu[e], f.omb1 * g[e]);
+    const float vn = fmaf(f.b2, vv[e], f.omb2 * (g[e] * g[e]));
+    uu[e] = un;
+    vv[e] = vn;
+    const float nn = (un * f.inv_c1) / (sqrtf(vn * f.inv_c2) + f.eps);
+    hi[e] = f2bf_rne(nn);
+    lo[e] = f2bf_rne(nn - __uint_as_float(hi[e] << 16));
+  }
+  *TO_GLOBAL(f32x4, f.u + at) = uu;
+  *TO_GLOBAL(f32x4, f.v + at) = vv;
+  u32x2 ph, pl;
+  ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16);
+  pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
+  *TO_GLOBAL(u32x2, f.n_hi + at) = ph;
+  *TO_GLOBAL(u32x2, f.n_lo + at) = pl;
+}
+
+// NW = 8: 256-column tiles (wave w: rank block w % 4, column half w / 4); NW = 4: 128-column tiles.
+// VEC: every G row is read with aligned 4-byte accesses (8 loads per stage, else 16).
+// A tile marked `fuse` holds the whole contraction (no split-K): its epilogue applies Adam to its
+// elements of the low-rank state instead of leaving that to a separate pass over g.
+template <int NW, bool VEC>
+__global__ __launch_bounds__(64 * NW) void k_proj_down_pipe(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
+                                                            int64_t split_stride, float grad_scale, FusedAdam fa) {
   constexpr int BK = 32;
+  constexpr int NH = NW / 4;                                   // column halves of 128
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
   const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
 
-  constexpr int GSLOTS = 8 * 4 * 32;                           // (nblk, kgrp, n) 16-byte slots of one stage
+  constexpr int GSLOTS = 4 * NH * 4 * 32;                      // (nblk, kgrp, n) 16-byte slots of one stage
   constexpr int ASLOTS = 4 * 2 * 2 * 64;                       // (mblk, kstep, plane, lane)
-  __shared__ u32x4 gfrag[2 * GSLOTS];                          // 32 KiB
+  __shared__ u32x4 gfrag[2 * GSLOTS];                          // 16 KiB per 128 columns
   __shared__ u32x4 afrag[2 * ASLOTS];                          // 32 KiB
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mb = wave & 3, nh = wave >> 2;                     // compute role
-  const int kgrp = wave >> 1, half = wave & 1;                 // G staging role
+  const int kgrp = wave / NH, half = wave % NH;                // G staging role: 8-row group, column half
   const int mbg = t.m0 / 32 + mb;
   const bool active = mbg < m.rp / 32;
 
@@ -327,19 +363,24 @@ __global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile
   gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 2u : OOB;
   const int wslot = ((4 * half + (lane >> 4)) * 4 + kgrp) * 32 + 2 * (lane & 15);
 
-  // Q fragments of a stage: f = mblk*4 + ks*2 + plane; this wave brings in both planes of (mblk, kstep)
+  // Q fragments of a stage: f = (mblk*2 + kstep)*2 + plane, 16 of them; a wave brings in 16 / NW
+  // (mblk, kstep) pairs, both planes each
   const int64_t kgroups = m.pp / 8;
-  const int fmb = wave >> 1, fks = wave & 1;
-  const int fmbg = t.m0 / 32 + fmb < m.rp / 32 ? t.m0 / 32 + fmb : m.rp / 32 - 1;
-  const GAS u32x4* asrc_hi = qt_hi + (int64_t)fmbg * kgroups * 32 + lane;
-  const GAS u32x4* asrc_lo = qt_lo + (int64_t)fmbg * kgroups * 32 + lane;
   const int kgmax = (int)kgroups - 2;
+  const int rblocks = m.rp / 32;
   auto issue_a = [&](int kr, int sbuf) {
-    int kg = kr / 8 + 2 * fks;
-    kg = kg < kgmax ? kg : kgmax;                              // a stage may reach past the padded height
-    u32x4* dst = afrag + sbuf * ASLOTS + ((fmb * 2 + fks) * 2) * 64;
-    dma16_async(asrc_hi + (int64_t)kg * 32, dst);
-    dma16_async(asrc_lo + (int64_t)kg * 32, dst + 64);
+#pragma unroll
+    for (int j = 0; j < 8 / NW; ++j) {
+      const int pair = wave * (8 / NW) + j;                    // 0..7
+      const int fmb = pair >> 1, fks = pair & 1;
+      const int fmbg = t.m0 / 32 + fmb < rblocks ? t.m0 / 32 + fmb : rblocks - 1;
+      int kg = kr / 8 + 2 * fks;
+      kg = kg < kgmax ? kg : kgmax;                            // a stage may reach past the padded height
+      const int64_t src = ((int64_t)fmbg * kgroups + kg) * 32 + lane;
+      u32x4* dst = afrag + sbuf * ASLOTS + pair * 2 * 64;
+      dma16_async(qt_hi + src, dst);
+      dma16_async(qt_lo + src, dst + 64);
+    }
   };
 
   f32x16 acc[4];
@@ -401,30 +442,70 @@ __global__ __launch_bounds__(512) void k_proj_down_wide(DevCtx d, const ProjTile
 #undef LORDO_DOWN_ITER
 
   if (!active) return;
-  GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + m.lr_off;
+  const int64_t base = m.lr_off;
+  GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + base;
+  const bool fuse = t.fuse != 0;                                // uniform over the workgroup
   const int64_t rgroups = m.rp / 8;
+  // offset of the lane's four consecutive rank indices of column block nbg, rank group 4*mbg + vq
+  auto offset_of = [&](int nbg, int vq) {
+    return (((int64_t)nbg * rgroups + 4 * mbg + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+  };
+  if (!fuse) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int nbg = t.n0 / 32 + 4 * nh + a;
+      if (nbg >= m.qp / 32) continue;
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        f32x4 val;
+        val.x = grad_scale * acc[a][4 * vq];     val.y = grad_scale * acc[a][4 * vq + 1];
+        val.z = grad_scale * acc[a][4 * vq + 2]; val.w = grad_scale * acc[a][4 * vq + 3];
+        *reinterpret_cast<GAS f32x4*>(out + offset_of(nbg, vq)) = val;
+      }
+    }
+    return;
+  }
+  // fused Adam: the moments of a whole column block are requested before any of them is used
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
-    int nbg = t.n0 / 32 + 4 * nh + a;
+    const int nbg = t.n0 / 32 + 4 * nh + a;
     if (nbg >= m.qp / 32) continue;
+    f32x4 uu[4], vv[4];
 #pragma unroll
     for (int vq = 0; vq < 4; ++vq) {
-      int64_t o = (((int64_t)nbg * rgroups + 4 * mbg + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+      const int64_t at = base + offset_of(nbg, vq);
+      uu[vq] = *TO_GLOBAL(const f32x4, fa.u + at);
+      vv[vq] = *TO_GLOBAL(const f32x4, fa.v + at);
+    }
+    ISSUE_FENCE();
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq) {
+      const int64_t o = offset_of(nbg, vq);
       f32x4 val;
       val.x = grad_scale * acc[a][4 * vq];     val.y = grad_scale * acc[a][4 * vq + 1];
       val.z = grad_scale * acc[a][4 * vq + 2]; val.w = grad_scale * acc[a][4 * vq + 3];
       *reinterpret_cast<GAS f32x4*>(out + o) = val;
+      adam4(fa, base + o, val, uu[vq], vv[vq]);
     }
   }
 }
 
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, bool wide, bool g_vec, float* glow,
-                            int64_t split_stride, float grad_scale, bool g_is_f32, hipStream_t s) {
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_waves, bool g_vec, float* glow,
+                            int64_t split_stride, float grad_scale, bool g_is_f32, const DownFuse* fuse, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
-  if (wide) {
-    if (g_vec) hipLaunchKernelGGL(k_proj_down_wide<true>, grid, dim3(512), 0, s, d, tiles, glow, split_stride, grad_scale);
-    else hipLaunchKernelGGL(k_proj_down_wide<false>, grid, dim3(512), 0, s, d, tiles, glow, split_stride, grad_scale);
+  if (pipe_waves) {
+    FusedAdam fa{};
+    if (fuse) {
+      fa.u = fuse->u; fa.v = fuse->v; fa.n_hi = fuse->n_hi; fa.n_lo = fuse->n_lo;
+      fa.b1 = fuse->a.b1; fa.omb1 = fuse->a.omb1; fa.b2 = fuse->a.b2; fa.omb2 = fuse->a.omb2;
+      fa.inv_c1 = fuse->a.inv_c1; fa.inv_c2 = fuse->a.inv_c2; fa.eps = fuse->a.eps;
+    }
+#define LORDO_PIPE(NWV, VECV)                                                                                     \
+  hipLaunchKernelGGL((k_proj_down_pipe<NWV, VECV>), grid, dim3(64 * NWV), 0, s, d, tiles, glow, split_stride, grad_scale, fa)
+    if (pipe_waves == 8) { if (g_vec) LORDO_PIPE(8, true); else LORDO_PIPE(8, false); }
+    else { if (g_vec) LORDO_PIPE(4, true); else LORDO_PIPE(4, false); }
+#undef LORDO_PIPE
     return hipGetLastError();
   }
 #define LORDO_DOWN(MBV)                                                                                            \

@@ -72,3 +72,48 @@ def test_c2_full_size_sampled_columns():
     for i in picked:
         assert torch.equal(opt.get_state(i, lordo.STATE_ANCHOR), W[i])
         assert torch.isfinite(W[i]).all()
+
+
+def test_many_tiles_fused_adam_sampled_columns():
+    """A launch with so many down-projection tiles that no matrix is split: the Adam update then runs
+    in the epilogue of the down-projection.  One short, very wide matrix (160 x 393216, r = 128) keeps
+    the float64 oracle cheap per sampled column; basis given, two local steps."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    p, q, r = 160, 393216, 128
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.seed_for(6, 1))
+    W = [(0.02 * torch.randn(p, q, generator=gen, device=dev)).contiguous()]
+    G = [[(1e-3 * torch.randn(p, q, generator=gen, device=dev)).to(torch.bfloat16).contiguous()] for _ in range(2)]
+    rng = np.random.default_rng(synth.seed_for(6, 2))
+    Q = synth.orthonormal(rng, p, r).astype(np.float32)
+    hp = lordo.hparams()
+    opt = lordo.Lordo([(p, q, r)], hp, W, torch)
+    opt.set_state(0, lordo.STATE_Q, torch.tensor(Q, device=dev).contiguous())
+    Q64 = opt.get_state(0, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+    cols = np.unique(np.concatenate([[0, 1, 255, 256, 257, q - 257, q - 256, q - 1], rng.integers(0, q, 24)]))
+    st = orc.init_state(W[0][:, cols].cpu().numpy().astype(np.float64), r, Q64)
+    Wo = st.anchor.copy()
+    ohp = orc.Hyper()
+    Wp = opt.ptrs(W)
+    for step, lr in enumerate([1e-3, 2e-3]):
+        W_before = W[0][:, cols].cpu().numpy().astype(np.float64)
+        opt.local_step(Wp, opt.ptrs(G[step], torch.bfloat16), lr)
+        torch.cuda.synchronize()
+        Gc = G[step][0][:, cols].float().cpu().numpy().astype(np.float64)
+        Wo = orc.local_step(st, Wo, Gc, lr, ohp)
+        get = lambda which: opt.get_state(0, which).cpu().numpy().astype(np.float64)[:, cols]
+        assert rel_l2(get(lordo.STATE_GLOW), st.last_g) <= TOL, f"g, step {step}"
+        assert rel_l2(get(lordo.STATE_U), st.u) <= TOL, f"u, step {step}"
+        assert rel_l2(get(lordo.STATE_V), st.v) <= TOL, f"v, step {step}"
+        n_gpu = get(lordo.STATE_NUPD)
+        dW_gpu = W[0][:, cols].cpu().numpy().astype(np.float64) - W_before
+        if step == 0:
+            amb = np.abs(st.last_g) < 1e-4 * np.sqrt(np.mean(st.last_g ** 2))
+            assert rel_l2(np.where(amb, 0, n_gpu), np.where(amb, 0, st.last_N)) <= TOL, "N, step 0"
+            assert rel_l2(dW_gpu, -lr * Q64 @ n_gpu) <= TOL, "weight change, step 0"
+        else:
+            assert rel_l2(n_gpu, st.last_N) <= TOL, f"N, step {step}"
+            assert rel_l2(dW_gpu, -lr * Q64 @ st.last_N) <= TOL, f"weight change, step {step}"
+    opt.poll_status()
