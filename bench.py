@@ -54,6 +54,34 @@ def parse():
     return ap.parse_args()
 
 
+KERNEL_OF_CLASS = {"down": "k_proj_down", "adam": "k_adam", "up": "k_proj_up", "outer": "k_pq<0>"}
+
+
+def measured_traffic(cfg, rank, kernel_class):
+    """HBM bytes per launch of a kernel class from the committed rocprofv3 counter summary of this
+    workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy), or None if there is none."""
+    if rank is not None:
+        return None
+    path = os.path.join(ROOT, "profiles", f"{cfg}_hbm_traffic_pmc.txt")
+    prefix = KERNEL_OF_CLASS.get(kernel_class)
+    if prefix is None or not os.path.exists(path):
+        return None
+    best = None
+    with open(path) as f:
+        for line in f:
+            if line.startswith("#") or line.startswith("kernel,"):
+                continue
+            parts = line.strip().rsplit(",", 4)          # kernel names may hold commas
+            if len(parts) == 5 and parts[0].startswith(prefix):
+                try:
+                    n, tb = int(parts[1]), float(parts[4])
+                except ValueError:
+                    continue
+                if best is None or n > best[0]:
+                    best = (n, tb)
+    return best[1] if best else None
+
+
 def algorithmic_work(shapes, grad_bytes=2):
     """Algorithmic bytes and flops per launch of each kernel class (unpadded sizes)."""
     spq = sum(p * q for p, q, r in shapes)
@@ -249,11 +277,11 @@ def main():
         if t_mfma > t_hbm:
             ach = w["flops"] / avg_s / 1e12
             roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(cfg, args.rank, dom)}
         else:
             ach = w["bytes"] / avg_s / 1e9
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": ach / HBM_PEAK_GBS, "traffic": None}
+                        "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, args.rank, dom)}
 
     cpu = None
     if not args.no_cpu_baseline:
