@@ -100,7 +100,7 @@ constexpr int NB = 64;            // Cholesky / triangular-solve block size
 // ---------------------------------------------------------------------------------------
 // proj.hip
 struct DownFuse;     // below: state arrays and coefficients of the Adam update fused into the down-projection
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_waves, bool g_vec, float* glow,
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_waves, bool g_vec, bool g_once, float* glow,
                             int64_t split_stride, float grad_scale, bool g_is_f32, const DownFuse* fuse, hipStream_t s);
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
                           const uint16_t* n_lo, float lr, hipStream_t s);

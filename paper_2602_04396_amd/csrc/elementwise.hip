@@ -27,6 +27,14 @@ __device__ __forceinline__ void split_bf(float x, uint32_t& hi, uint32_t& lo) {
 // ---------------------------------------------------------------------------------------
 // fused low-rank Adam: one thread per 8 consecutive elements of the flat arena
 // ---------------------------------------------------------------------------------------
+typedef float f32x4n __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4n __attribute__((ext_vector_type(4)));
+
+// g is read for the last time here and the moments are not touched again before the next step, a
+// gigabyte of traffic later: their accesses are non-temporal (streaming lines in L2 and the
+// last-level cache).  N is consumed by the up-projection right away and stays cacheable.
+__device__ __forceinline__ f32x4n ld_stream(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4n*>(p)); }
+__device__ __forceinline__ void st_stream(float* p, f32x4n x) { __builtin_nontemporal_store(x, reinterpret_cast<f32x4n*>(p)); }
 __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, float* __restrict__ u,
                                               float* __restrict__ v, uint16_t* __restrict__ n_hi,
                                               uint16_t* __restrict__ n_lo, int64_t ngroups, AdamArgs a) {
@@ -35,23 +43,21 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
   int64_t base = a.first + gidx * 8;
   float g[8], uu[8], vv[8];
   {
-    const float4* gp = reinterpret_cast<const float4*>(glow + base);
-    float4 a0 = gp[0], a1 = gp[1];
+    const f32x4n* gp = reinterpret_cast<const f32x4n*>(glow + base);
+    f32x4n a0 = __builtin_nontemporal_load(gp), a1 = __builtin_nontemporal_load(gp + 1);
     g[0] = a0.x; g[1] = a0.y; g[2] = a0.z; g[3] = a0.w; g[4] = a1.x; g[5] = a1.y; g[6] = a1.z; g[7] = a1.w;
     int nsplit = a.grp_nsplit[0];
 #pragma unroll
     for (int i = 1; i < 4; ++i)
       if (base >= a.grp_start[i]) nsplit = a.grp_nsplit[i];
     for (int sidx = 1; sidx < nsplit; ++sidx) {         // deterministic split-K reduction, fixed order
-      const float4* sp = reinterpret_cast<const float4*>(glow + sidx * a.split_stride + base);
-      float4 b0 = sp[0], b1 = sp[1];
+      const f32x4n* sp = reinterpret_cast<const f32x4n*>(glow + sidx * a.split_stride + base);
+      f32x4n b0 = __builtin_nontemporal_load(sp), b1 = __builtin_nontemporal_load(sp + 1);
       g[0] += b0.x; g[1] += b0.y; g[2] += b0.z; g[3] += b0.w; g[4] += b1.x; g[5] += b1.y; g[6] += b1.z; g[7] += b1.w;
     }
-    const float4* up = reinterpret_cast<const float4*>(u + base);
-    float4 u0 = up[0], u1 = up[1];
+    f32x4n u0 = ld_stream(u + base), u1 = ld_stream(u + base + 4);
     uu[0] = u0.x; uu[1] = u0.y; uu[2] = u0.z; uu[3] = u0.w; uu[4] = u1.x; uu[5] = u1.y; uu[6] = u1.z; uu[7] = u1.w;
-    const float4* vp = reinterpret_cast<const float4*>(v + base);
-    float4 v0 = vp[0], v1 = vp[1];
+    f32x4n v0 = ld_stream(v + base), v1 = ld_stream(v + base + 4);
     vv[0] = v0.x; vv[1] = v0.y; vv[2] = v0.z; vv[3] = v0.w; vv[4] = v1.x; vv[5] = v1.y; vv[6] = v1.z; vv[7] = v1.w;
   }
   uint32_t hi[8], lo[8];
@@ -64,17 +70,15 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
     float nn = (un * a.inv_c1) / (sqrtf(vn * a.inv_c2) + a.eps);
     split_bf(nn, hi[e], lo[e]);
   }
-  float4* up = reinterpret_cast<float4*>(u + base);
-  up[0] = make_float4(uu[0], uu[1], uu[2], uu[3]);
-  up[1] = make_float4(uu[4], uu[5], uu[6], uu[7]);
-  float4* vp = reinterpret_cast<float4*>(v + base);
-  vp[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
-  vp[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
-  uint4 ph, pl;
+  st_stream(u + base, f32x4n{uu[0], uu[1], uu[2], uu[3]});
+  st_stream(u + base + 4, f32x4n{uu[4], uu[5], uu[6], uu[7]});
+  st_stream(v + base, f32x4n{vv[0], vv[1], vv[2], vv[3]});
+  st_stream(v + base + 4, f32x4n{vv[4], vv[5], vv[6], vv[7]});
+  u32x4n ph, pl;
   ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
   pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
-  *reinterpret_cast<uint4*>(n_hi + base) = ph;
-  *reinterpret_cast<uint4*>(n_lo + base) = pl;
+  *reinterpret_cast<u32x4n*>(n_hi + base) = ph;
+  *reinterpret_cast<u32x4n*>(n_lo + base) = pl;
 }
 
 hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
@@ -246,12 +250,12 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
     if (i0 >= total) continue;
     float w[4], an[4], dl[4], bb[4];
     int cnt = total - i0 < 4 ? (int)(total - i0) : 4;
-    if (vec) {
-      float4 t;
-      if (MODE != 0 || a.own_delta) { t = *reinterpret_cast<const float4*>(W + i0); w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w; }
-      if (MODE != 2) { t = *reinterpret_cast<const float4*>(anchor + i0); an[0] = t.x; an[1] = t.y; an[2] = t.z; an[3] = t.w; }
-      if (din) { t = *reinterpret_cast<const float4*>(din + i0); dl[0] = t.x; dl[1] = t.y; dl[2] = t.z; dl[3] = t.w; }
-      if (MODE == 0 && mom) { t = *reinterpret_cast<const float4*>(mom + i0); bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w; }
+    if (vec) {       // every array here is touched once per call and is far larger than the caches: streaming accesses
+      f32x4n t;
+      if (MODE != 0 || a.own_delta) { t = ld_stream(W + i0); w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w; }
+      if (MODE != 2) { t = ld_stream(anchor + i0); an[0] = t.x; an[1] = t.y; an[2] = t.z; an[3] = t.w; }
+      if (din) { t = ld_stream(din + i0); dl[0] = t.x; dl[1] = t.y; dl[2] = t.z; dl[3] = t.w; }
+      if (MODE == 0 && mom) { t = ld_stream(mom + i0); bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w; }
     } else {
       for (int e = 0; e < cnt; ++e) {
         if (MODE != 0 || a.own_delta) w[e] = W[i0 + e];
@@ -279,15 +283,15 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
       }
     }
     if (vec) {
-      float4 t0 = make_float4(o0[0], o0[1], o0[2], o0[3]);
+      f32x4n t0 = {o0[0], o0[1], o0[2], o0[3]};
       if (MODE == 0) {
-        *reinterpret_cast<float4*>(W + i0) = t0;
-        *reinterpret_cast<float4*>(anchor + i0) = t0;
-        if (mom) *reinterpret_cast<float4*>(mom + i0) = make_float4(o1[0], o1[1], o1[2], o1[3]);
+        st_stream(W + i0, t0);
+        st_stream(anchor + i0, t0);
+        if (mom) st_stream(mom + i0, f32x4n{o1[0], o1[1], o1[2], o1[3]});
       } else if (MODE == 1) {
-        *reinterpret_cast<float4*>(dout + i0) = t0;
+        st_stream(dout + i0, t0);
       } else {
-        *reinterpret_cast<float4*>(anchor + i0) = t0;
+        st_stream(anchor + i0, t0);
       }
     } else {
       for (int e = 0; e < cnt; ++e) {

@@ -45,6 +45,7 @@ struct Plan {
   int mb = 4;
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
   int down_pipe = 0;                // waves of the pipelined down-projection (8: 256-column tiles, 4: 128-column; 0: plain kernel)
+  bool g_once = true;               // every matrix has one rank tile of the down-projection: G is read exactly once
   int64_t adam_first = 0;           // flat position from which the stand-alone Adam kernel runs (elements before it are fused)
   int nsplit = 1;                   // largest split-K factor of the down-projection
   std::vector<int> splits;          // split-K factor per matrix (1, 2, 4 or 8)
@@ -352,6 +353,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // Down-projection launch shape: the pipelined kernel (rank tiles of 128, bf16 G, 256-column
   // tiles) where it applies, else the plain kernel with 128-column tiles.
   P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16) ? 8 : 0;
+  P.g_once = rp_max <= 32 * P.mb;
   const int down_bn = P.down_pipe == 8 ? 256 : 128;
   P.up_waves = 4;
 
@@ -634,7 +636,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   fuse.n_hi = c->at<uint16_t>(P.n_hi); fuse.n_lo = c->at<uint16_t>(P.n_lo);
   fuse.a = a;
   c->prof.begin(LORDO_K_DOWN, s);
-  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, c->at<float>(P.glow),
+  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, P.g_once, c->at<float>(P.glow),
                           P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, &fuse, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
