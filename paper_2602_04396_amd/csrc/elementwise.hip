@@ -344,80 +344,113 @@ hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s) {
 
 // Diagonal block jb of the Gram matrix: L = chol(S_jj) (lower), X = L^{-1}; writes L into the
 // factor and X into the block-inverse array.  One workgroup per matrix.
-__global__ __launch_bounds__(256) void k_potf2(DevCtx d, int jb) {
+__device__ __forceinline__ float lane_value(float x, int lane) {      // value of x in lane `lane` (a constant), as a scalar
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
+}
+
+// One wave per matrix; lane i keeps row i of the 64 x 64 block in 64 registers, so the 64 column
+// steps of the factorisation and of the inversion need no barrier and no LDS round trip: a column
+// is broadcast lane by lane through scalar registers (v_readlane) and applied with one FMA per
+// element.  Everything is unrolled, every register index is a constant.
+__global__ __launch_bounds__(64) void k_potf2(DevCtx d, int jb) {
   const MatDev& m = d.mats[blockIdx.x];
-  int o = jb * NB;
+  const int o = jb * NB;
   int nbk = m.r - o;
   if (nbk <= 0) return;
   if (nbk > NB) nbk = NB;
   const float* S = reinterpret_cast<const float*>(d.arena + m.gram);
   float* L = reinterpret_cast<float*>(d.arena + m.lfac);
   float* X = reinterpret_cast<float*>(d.arena + m.dinv) + (int64_t)jb * NB * NB;
-  __shared__ float Ls[NB][NB + 1];
-  __shared__ float Xs[NB][NB + 1];
-  __shared__ float dmax_s[256];
-  int tid = threadIdx.x;
-  float dm = 0.f;
-  for (int idx = tid; idx < NB * NB; idx += 256) {
-    int i = idx / NB, j = idx % NB;
+  __shared__ float tile[NB][NB + 1];
+  const int lane = threadIdx.x;
+  // rows are read coalesced and handed to their lanes through LDS; identity outside the block
+  for (int rr = 0; rr < NB; ++rr) {
     float val;
-    if (i < nbk && j < nbk) val = j <= i ? S[(int64_t)(o + i) * m.r + (o + j)] : 0.f;
-    else val = i == j ? 1.f : 0.f;
-    Ls[i][j] = val;
-    Xs[i][j] = 0.f;
-    if (i == j && i < nbk) dm = fmaxf(dm, val);
+    if (rr < nbk && lane < nbk) val = lane <= rr ? S[(int64_t)(o + rr) * m.r + (o + lane)] : 0.f;
+    else val = rr == lane ? 1.f : 0.f;
+    tile[rr][lane] = val;
   }
-  dmax_s[tid] = dm;
   __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if (tid < w) dmax_s[tid] = fmaxf(dmax_s[tid], dmax_s[tid + w]);
-    __syncthreads();
-  }
-  float floor_piv = 1e-12f * dmax_s[0] + 1e-37f;
-  const int tx = tid & 63, ty = tid >> 6;          // column, row phase
+  float a[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) a[j] = tile[lane][j];
+  float dmax = lane < nbk ? tile[lane][lane] : 0.f;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) dmax = fmaxf(dmax, __shfl_xor(dmax, off));
+  const float floor_piv = 1e-12f * dmax + 1e-37f;
+  bool bad = false;
+  // right-looking Cholesky: after step k register k holds column k of L
+#pragma clang loop unroll(full)
   for (int k = 0; k < NB; ++k) {
-    float piv = Ls[k][k];
+    // an opaque copy of the lane index per step: otherwise all 64 lane masks are computed up front
+    // and, with those of the inversion, crowd the scalar registers out
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    float piv = lane_value(a[k], k);
     if (!(piv > floor_piv)) {
-      if (tid == 0) *d.flag = 1;
+      bad = true;
       piv = floor_piv;
     }
-    float dd = sqrtf(piv);
-    __syncthreads();
-    if (tid < NB - k) {
-      int i = k + tid;
-      Ls[i][k] = i == k ? dd : Ls[i][k] / dd;
-    }
-    __syncthreads();
-    {   // trailing update of the lower triangle: L[i][j] -= L[i][k] L[j][k], k < j <= i
-      int j = k + 1 + tx;
-      if (j < NB) {
-        float ljk = Ls[j][k];
-        for (int i = j + ty; i < NB; i += 4) Ls[i][j] -= Ls[i][k] * ljk;
+    const float dd = sqrtf(piv);
+    const float lk = ln == k ? dd : (ln > k ? a[k] / dd : 0.f);
+    a[k] = lk;
+    // L[i][j] -= L[i][k] L[j][k] in groups of eight columns; the empty asm pins a group's FMAs
+    // right after its broadcasts (otherwise the compiler issues all broadcasts of a step first and
+    // runs out of scalar registers), while the eight pairs inside a group overlap
+#pragma clang loop unroll(full)
+    for (int jc = 0; jc < NB / 8; ++jc) {
+      if (8 * jc + 7 > k) {
+#pragma clang loop unroll(full)
+        for (int e = 0; e < 8; ++e) {
+          const int j = 8 * jc + e;
+          if (j > k) a[j] = fmaf(-lk, lane_value(lk, j), a[j]);
+        }
+        asm volatile("" : "+v"(a[8 * jc]), "+v"(a[8 * jc + 1]), "+v"(a[8 * jc + 2]), "+v"(a[8 * jc + 3]),
+                          "+v"(a[8 * jc + 4]), "+v"(a[8 * jc + 5]), "+v"(a[8 * jc + 6]), "+v"(a[8 * jc + 7]));
       }
     }
-    __syncthreads();
   }
-  // X = L^{-1} by elimination on the identity: after step k row k of X is final
-  for (int idx = tid; idx < NB * NB; idx += 256) Xs[idx / NB][idx % NB] = (idx / NB == idx % NB) ? 1.f : 0.f;
-  __syncthreads();
-  for (int k = 0; k < NB; ++k) {
-    float inv = 1.f / Ls[k][k];
-    if (tid <= k) Xs[k][tid] *= inv;               // row k, columns 0..k
-    __syncthreads();
-    if (tx <= k) {
-      float xk = Xs[k][tx];
-      for (int i = k + 1 + ty; i < NB; i += 4) Xs[i][tx] -= Ls[i][k] * xk;
+  // X = L^{-1} by forward substitution: lane j builds column j, x[i] = X[i][j]
+  float x[NB];
+#pragma clang loop unroll(full)
+  for (int i = 0; i < NB; ++i) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    // four partial sums: the FMA chain of a row is split so that consecutive pairs overlap
+    float acc[4] = {ln == i ? 1.f : 0.f, 0.f, 0.f, 0.f};
+#pragma clang loop unroll(full)
+    for (int mc = 0; mc < NB / 8; ++mc) {
+      if (8 * mc < i) {
+#pragma clang loop unroll(full)
+        for (int e = 0; e < 8; ++e) {
+          const int mm = 8 * mc + e;
+          if (mm < i) acc[e & 3] = fmaf(-lane_value(a[mm], i), x[mm], acc[e & 3]);    // L[i][mm] is register mm of lane i
+        }
+        asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
+      }
     }
-    __syncthreads();
+    x[i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / lane_value(a[i], i);
   }
-  for (int idx = tid; idx < NB * NB; idx += 256) {
-    int i = idx / NB, j = idx % NB;
-    X[idx] = j <= i ? Xs[i][j] : 0.f;
-    if (i < nbk && j < nbk) L[(int64_t)(o + i) * m.r + (o + j)] = j <= i ? Ls[i][j] : 0.f;
+  if (bad && lane == 0) *d.flag = 1;
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    X[i * NB + lane] = ln <= i ? x[i] : 0.f;
   }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    tile[lane][j] = j <= ln ? a[j] : 0.f;
+  }
+  __syncthreads();
+  for (int rr = 0; rr < nbk; ++rr)
+    if (lane < nbk) L[(int64_t)(o + rr) * m.r + (o + lane)] = tile[rr][lane];
 }
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
-  hipLaunchKernelGGL(k_potf2, dim3(d.n), dim3(256), 0, s, d, jb);
+  hipLaunchKernelGGL(k_potf2, dim3(d.n), dim3(64), 0, s, d, jb);
   return hipGetLastError();
 }
 

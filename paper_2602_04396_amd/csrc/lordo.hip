@@ -263,7 +263,10 @@ struct ProgramBuilder {
       g.M = m.p; g.N = m.r; g.K = m.q;
       return true;
     });
-    int ycur = orth(true, 0, passes);
+    // Inside the power iteration the blocks only have to stay well conditioned (any basis of the
+    // same span serves the next product), so one shifted CholeskyQR pass is enough there; the basis
+    // that becomes Q gets the full number of passes.
+    int ycur = orth(true, 0, power_iters > 0 ? 1 : passes);
     for (int it = 0; it < power_iters; ++it) {
       // Z = Src^T Y
       gemm([&](int i, GemmDesc& g) {
@@ -274,7 +277,7 @@ struct ProgramBuilder {
         g.M = m.q; g.N = m.r; g.K = m.p;
         return true;
       });
-      int zcur = orth(false, 0, passes);
+      int zcur = orth(false, 0, 1);
       // Y = Src Z
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
@@ -284,7 +287,7 @@ struct ProgramBuilder {
         g.M = m.p; g.N = m.r; g.K = m.q;
         return true;
       });
-      ycur = orth(true, 0, passes);
+      ycur = orth(true, 0, it + 1 < power_iters ? 1 : passes);
     }
     // rotation: R = Q_new^T Q_old (and R o R)
     gemm([&](int i, GemmDesc& g) {
