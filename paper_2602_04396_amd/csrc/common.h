@@ -66,7 +66,8 @@ struct GemmDesc {
   OpRef A, B, C, C2;      // C2 (off < 0 = none) receives the elementwise square of the result
   int32_t M, N, K, mat;
   int64_t sAm, sAk, sBk, sBn;
-  int32_t ldc, a_bf16, b_bf16, pad;   // a_bf16: 0 fp32, 1 bf16, 2 = element type given at launch (refresh source)
+  int32_t ldc, a_bf16, b_bf16;        // a_bf16: 0 fp32, 1 bf16, 2 = element type given at launch (refresh source)
+  int32_t prec;                       // 0: fp32 matrix cores; 1: operands split into bf16 hi + lo (range-finder products)
   float alpha, beta;
   // split-K (ksplit > 1): slice s covers k in [s*klen, (s+1)*klen) and writes its raw M x N sum to
   // P + s*M*N; a reduction kernel then adds the slices in order and applies alpha, beta, C2

@@ -139,6 +139,170 @@ __device__ __forceinline__ void gemm_loop(f32x16 (&acc)[WB][WB], const Operand<T
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Split-bf16 variant of the K loop for the range-finder products (Alg. 2 sketch and power
+// iteration).  Operands go to LDS as bf16 planes in matrix-core fragment order -- a bf16 source is
+// exact, an fp32 operand becomes hi + lo (2^-16 relative) -- and the products run on
+// v_mfma_f32_32x32x16_bf16: hi*hi + hi*lo (+ lo*hi for an fp32 A).  The blocks that come out are
+// orthonormalised in fp32 afterwards, and the range finder is itself an approximation whose error
+// is orders of magnitude above 2^-17, so the subspace is unaffected.
+// Plane element (i, k) of a TMN x 32 tile: ((i/32)*4 + k/8) * 264 + (i%32)*8 + k%8 (eight elements
+// of padding per 32 x 8 group spread the groups over the LDS banks).
+// ---------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ int frag_index(int i, int k) { return ((i >> 5) * 4 + (k >> 3)) * 264 + (i & 31) * 8 + (k & 7); }
+
+// Operand tile of the split-bf16 loop; whole-vector access only (the caller falls back to the fp32
+// loop otherwise).  A thread owns up to four vectors of four elements; along k they pack directly,
+// along i the thread owns a 4 x 4 patch (four i, four consecutive k) and transposes it in registers.
+template <int TMN>
+struct OperandBF {
+  const char* base;
+  int64_t s_i, s_k;
+  int lim, kend, i0;
+  bool kfast;
+  static constexpr int NVK = TMN / 32;          // vectors per thread when k is the unit-stride direction
+
+  __device__ __forceinline__ void setup(const char* b, int64_t si, int64_t sk, int lim_, int kend_, int i0_) {
+    base = b; s_i = si; s_k = sk; lim = lim_; kend = kend_; i0 = i0_;
+    kfast = sk == 1 && si != 1;
+  }
+  // vector n of thread tid: first element (ii, kk); false if the thread has no such vector
+  __device__ __forceinline__ bool coords(int tid, int n, int& ii, int& kk) const {
+    if (kfast) {
+      if (n >= NVK) return false;
+      const int v = tid + n * 256;
+      kk = (v & 7) * 4; ii = v >> 3;
+      return true;
+    }
+    if (tid >= TMN * 2) return false;           // TMN/4 i-quads x 8 k-quads patches
+    ii = (tid % (TMN / 4)) * 4;
+    kk = (tid / (TMN / 4)) * 4 + n;
+    return true;
+  }
+  template <bool BF16>
+  __device__ __forceinline__ void fetch_raw(u32x4 (&raw)[4], int k0, int tid) const {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      int ii = 0, kk = 0;
+      const bool have = coords(tid, n, ii, kk);
+      const int gi = i0 + ii, gk = k0 + kk;
+      const int64_t at = (have && gi < lim && gk < kend) ? (int64_t)gi * s_i + (int64_t)gk * s_k : 0;
+      if constexpr (BF16) {
+        u32x2 w = *reinterpret_cast<const GAS u32x2*>((const GAS char*)base + at * 2);
+        raw[n].x = w.x; raw[n].y = w.y;
+      } else {
+        raw[n] = *reinterpret_cast<const GAS u32x4*>((const GAS char*)base + at * 4);
+      }
+    }
+  }
+  // Two fp32 values -> packed bf16 pair of their high parts, and of what is left.  The high part is
+  // the truncated upper half (so hi + rest is exact); the rest is truncated to bf16 as well, which
+  // leaves 2^-16 relative overall -- three vector operations per element.
+  static __device__ __forceinline__ void split2(uint32_t x0, uint32_t x1, uint32_t& hi, uint32_t& lo) {
+    hi = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
+    const float r0 = __uint_as_float(x0) - __uint_as_float(x0 & 0xffff0000u);
+    const float r1 = __uint_as_float(x1) - __uint_as_float(x1 & 0xffff0000u);
+    lo = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+  }
+  template <bool BF16>
+  __device__ __forceinline__ void stash(const u32x4 (&raw)[4], uint16_t* P_hi, uint16_t* P_lo, int k0, int tid) const {
+    if (kfast) {
+#pragma unroll
+      for (int n = 0; n < NVK; ++n) {
+        int ii = 0, kk = 0;
+        coords(tid, n, ii, kk);
+        const bool ok = i0 + ii < lim && k0 + kk < kend;
+        const int at = frag_index(ii, kk);                    // four consecutive k: 8 contiguous bytes
+        if constexpr (BF16) {
+          *reinterpret_cast<u32x2*>(P_hi + at) = ok ? u32x2{raw[n].x, raw[n].y} : u32x2{0u, 0u};
+        } else {
+          uint32_t h0, h1, l0, l1;
+          split2(raw[n].x, raw[n].y, h0, l0);
+          split2(raw[n].z, raw[n].w, h1, l1);
+          *reinterpret_cast<u32x2*>(P_hi + at) = ok ? u32x2{h0, h1} : u32x2{0u, 0u};
+          *reinterpret_cast<u32x2*>(P_lo + at) = ok ? u32x2{l0, l1} : u32x2{0u, 0u};
+        }
+      }
+    } else if (tid < TMN * 2) {
+      // 4 x 4 patch: vector n holds i = ii .. ii+3 at k = kfirst + n; row ii + e of the plane gets k = kfirst .. kfirst+3
+      int ii = 0, kfirst = 0;
+      coords(tid, 0, ii, kfirst);
+      const bool i_ok = i0 + ii < lim;
+      u32x4 r[4];
+#pragma unroll
+      for (int n = 0; n < 4; ++n) r[n] = (i_ok && k0 + kfirst + n < kend) ? raw[n] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int at = frag_index(ii + e, kfirst);
+        if constexpr (BF16) {                                 // element e of vector n: half (e & 1) of word e / 2
+          const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+          u32x2 h;
+          h.x = __builtin_amdgcn_perm(r[1][e >> 1], r[0][e >> 1], sel);
+          h.y = __builtin_amdgcn_perm(r[3][e >> 1], r[2][e >> 1], sel);
+          *reinterpret_cast<u32x2*>(P_hi + at) = h;
+        } else {
+          uint32_t h0, h1, l0, l1;
+          split2(r[0][e], r[1][e], h0, l0);
+          split2(r[2][e], r[3][e], h1, l1);
+          *reinterpret_cast<u32x2*>(P_hi + at) = u32x2{h0, h1};
+          *reinterpret_cast<u32x2*>(P_lo + at) = u32x2{l0, l1};
+        }
+      }
+    }
+  }
+};
+
+template <int WB, bool A_BF16, int TM>
+__device__ __forceinline__ void gemm_loop_bf(f32x16 (&acc)[WB][WB], const OperandBF<TM>& opA, const OperandBF<TM>& opB,
+                                             uint16_t* lds, int kbeg, int K, int tid, int lane, int wm, int wn) {
+  constexpr int PLANE = (TM / 32) * 4 * 264;                   // elements
+  uint16_t* A_hi = lds;
+  uint16_t* A_lo = lds + PLANE;
+  uint16_t* B_hi = lds + 2 * PLANE;
+  uint16_t* B_lo = lds + 3 * PLANE;
+  u32x4 ra[4], rb[4];
+  opA.template fetch_raw<A_BF16>(ra, kbeg, tid);
+  opB.template fetch_raw<false>(rb, kbeg, tid);
+  for (int k0 = kbeg; k0 < K; k0 += TK) {
+    __syncthreads();                           // previous tile fully consumed
+    opA.template stash<A_BF16>(ra, A_hi, A_lo, k0, tid);
+    opB.template stash<false>(rb, B_hi, B_lo, k0, tid);
+    __syncthreads();
+    if (k0 + TK < K) {
+      opA.template fetch_raw<A_BF16>(ra, k0 + TK, tid);
+      opB.template fetch_raw<false>(rb, k0 + TK, tid);
+    }
+    asm volatile("" ::: "memory");             // keep the loads above the arithmetic: they must be in flight during it
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 ah[WB], al[WB], bh[WB], bl[WB];
+      const int kg = 16 * ks + 8 * (lane >> 5);
+#pragma unroll
+      for (int a = 0; a < WB; ++a) {
+        const int at = frag_index(wm + 32 * a + (lane & 31), kg);
+        ah[a] = *reinterpret_cast<const bf16x8*>(A_hi + at);
+        if constexpr (!A_BF16) al[a] = *reinterpret_cast<const bf16x8*>(A_lo + at);
+      }
+#pragma unroll
+      for (int b = 0; b < WB; ++b) {
+        const int at = frag_index(wn + 32 * b + (lane & 31), kg);
+        bh[b] = *reinterpret_cast<const bf16x8*>(B_hi + at);
+        bl[b] = *reinterpret_cast<const bf16x8*>(B_lo + at);
+      }
+#pragma unroll
+      for (int a = 0; a < WB; ++a)
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], acc[a][b], 0, 0, 0);
+          if constexpr (!A_BF16) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[a], bh[b], acc[a][b], 0, 0, 0);
+        }
+    }
+  }
+}
+
 // 256 threads = 4 waves in a 2 x 2 grid; each wave WB x WB accumulator blocks of 32 x 32, so the
 // workgroup tile is 64*WB square (64 for small problems, 128 for large launches).  The next K tile
 // is fetched into registers while the matrix cores work on the one in LDS.
@@ -158,8 +322,10 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
   float* C = reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C, g.mat)));
   float* C2 = g.C2.off >= 0 ? reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C2, g.mat))) : nullptr;
 
-  __shared__ __attribute__((aligned(16))) float As[TK][PITCH];
-  __shared__ __attribute__((aligned(16))) float Bs[TK][PITCH];
+  __shared__ __attribute__((aligned(16))) float lds_raw[2 * TK * PITCH];      // As | Bs, or four bf16 planes
+  float (*As)[PITCH] = reinterpret_cast<float (*)[PITCH]>(lds_raw);
+  float (*Bs)[PITCH] = reinterpret_cast<float (*)[PITCH]>(lds_raw + TK * PITCH);
+  static_assert(sizeof(float) * 2 * TK * PITCH >= sizeof(uint16_t) * 4 * (TM / 32) * 4 * 264, "bf16 planes must fit");
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -177,7 +343,14 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  if (kbeg < K) {
+  if (kbeg < K && g.prec == 1 && opA.vec_ok && opB.vec_ok) {
+    OperandBF<TM> pa, pb;
+    pa.setup(opA.base, g.sAm, g.sAk, M, K, m0);
+    pb.setup(opB.base, g.sBn, g.sBk, N, K, n0);
+    uint16_t* planes = reinterpret_cast<uint16_t*>(lds_raw);
+    if (a_bf16) gemm_loop_bf<WB, true>(acc, pa, pb, planes, kbeg, K, tid, lane, wm, wn);
+    else gemm_loop_bf<WB, false>(acc, pa, pb, planes, kbeg, K, tid, lane, wm, wn);
+  } else if (kbeg < K) {
     const bool vec = opA.vec_ok && opB.vec_ok;
     if (a_bf16) {
       if (vec) gemm_loop<WB, true, true>(acc, opA, opB, As, Bs, kbeg, K, tid, lane, wm, wn);

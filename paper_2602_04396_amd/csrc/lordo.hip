@@ -257,7 +257,7 @@ struct ProgramBuilder {
     // Y = Src Omega
     gemm([&](int i, GemmDesc& g) {
       const MatDev& m = P.mat[i];
-      g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2;
+      g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2; g.prec = 1;
       g.B = ref_ext(EXT_OMEGA); g.sBk = m.r; g.sBn = 1;
       g.C = ref_arena(m.y[0]); g.ldc = m.r;
       g.M = m.p; g.N = m.r; g.K = m.q;
@@ -271,7 +271,7 @@ struct ProgramBuilder {
       // Z = Src^T Y
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2;
+        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2; g.prec = 1;
         g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.zw[0]); g.ldc = m.r;
         g.M = m.q; g.N = m.r; g.K = m.p;
@@ -281,7 +281,7 @@ struct ProgramBuilder {
       // Y = Src Z
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2;
+        g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2; g.prec = 1;
         g.B = ref_arena(m.zw[zcur]); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.y[0]); g.ldc = m.r;
         g.M = m.p; g.N = m.r; g.K = m.q;
