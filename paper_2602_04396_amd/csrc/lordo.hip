@@ -352,7 +352,9 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   }
   P.chunk_start_h[n] = chunks;
   P.nchunks = chunks;
-  P.mb = rp_max > 64 ? 4 : (rp_max > 32 ? 2 : 1);
+  // rank blocks of 32 per down-projection tile: the pipelined kernel (bf16 G) always takes four and
+  // leaves the waves of absent blocks idle; the plain kernel is instantiated for 1, 2 and 4
+  P.mb = (hp.grad_dtype == LORDO_BF16 || rp_max > 64) ? 4 : (rp_max > 32 ? 2 : 1);
   // Down-projection launch shape: the pipelined kernel (rank tiles of 128, bf16 G, 256-column
   // tiles) where it applies, else the plain kernel with 128-column tiles.
   P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16) ? 8 : 0;
@@ -370,13 +372,24 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.splits.assign(n, 1);
   P.nsplit = 1;
   if (tiles0 < 1536) {
+    // slices of about the shortest matrix's height; halved while the launch would still have fewer
+    // than about 1.5 workgroups per compute unit (a single tall matrix, for instance)
     int chunk = std::max(256, pp_min);
-    for (int i = 0; i < n; ++i) {
-      int want = (P.mat[i].pp + chunk - 1) / chunk;
-      int f = 1;
-      while (f * 2 <= want && f < 8) f *= 2;
-      P.splits[i] = f;
-      P.nsplit = std::max(P.nsplit, f);
+    for (;;) {
+      int64_t tiles = 0;
+      bool can_grow = false;
+      P.nsplit = 1;
+      for (int i = 0; i < n; ++i) {
+        int want = (P.mat[i].pp + chunk - 1) / chunk;
+        int f = 1;
+        while (f * 2 <= want && f < 8) f *= 2;
+        if (f < 8 && P.mat[i].pp / (2 * f) >= 256) can_grow = true;
+        P.splits[i] = f;
+        P.nsplit = std::max(P.nsplit, f);
+        tiles += (int64_t)f * ((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + 32 * P.mb - 1) / (32 * P.mb));
+      }
+      if (tiles >= 400 || !can_grow || chunk <= 256) break;
+      chunk = std::max(256, chunk / 2);
     }
   }
   // flat low-rank layout: matrices ordered by split factor, so that the Adam kernel knows the
