@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--no-events", action="store_true", help="skip the event-timed second pass")
     ap.add_argument("--refresh-every", type=int, default=None)
     ap.add_argument("--outer-every", type=int, default=None)
+    ap.add_argument("--update", default="plain", choices=["plain", "low-qhm", "full-qhm", "ef", "global"],
+                    help="update case of the local step: plain (default, the headline), low-rank / full-rank QHM (omega 0.9), "
+                         "error feedback, or global = full-rank QHM + error feedback (the paper's LoRDO-Global)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 1 GiB device copies (known traffic) to scale the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
@@ -57,10 +60,10 @@ def parse():
 KERNEL_OF_CLASS = {"down": "k_proj_down", "adam": "k_adam", "up": "k_proj_up", "outer": "k_pq<0>"}
 
 
-def measured_traffic(cfg, rank, kernel_class):
+def measured_traffic(cfg, rank, kernel_class, update="plain"):
     """HBM bytes per launch of a kernel class from the committed rocprofv3 counter summary of this
     workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy), or None if there is none."""
-    if rank is not None:
+    if rank is not None or update != "plain":
         return None
     path = os.path.join(ROOT, "profiles", f"{cfg}_hbm_traffic_pmc.txt")
     prefix = KERNEL_OF_CLASS.get(kernel_class)
@@ -82,16 +85,24 @@ def measured_traffic(cfg, rank, kernel_class):
     return best[1] if best else None
 
 
-def algorithmic_work(shapes, grad_bytes=2):
-    """Algorithmic bytes and flops per launch of each kernel class (unpadded sizes)."""
+def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False):
+    """Algorithmic bytes and flops per step of each kernel class (unpadded sizes).  With error feedback
+    the down-projection also reads the residual E, Adam also writes g as operand planes and the "up"
+    class holds a second launch (E <- G + E - Q g: E read and written, G read); the full-rank QHM
+    update reads G in the weight update."""
     spq = sum(p * q for p, q, r in shapes)
     spr = sum(p * r for p, q, r in shapes)
     srq = sum(r * q for p, q, r in shapes)
     flops = sum(2 * p * q * r for p, q, r in shapes)
+    up_bytes = 8 * spq + 4 * spr + 4 * srq + (grad_bytes * spq if qhm_full else 0)
+    up_flops = flops
+    if ef:
+        up_bytes += 8 * spq + grad_bytes * spq + 4 * spr + 4 * srq
+        up_flops += flops
     return {
-        "down": dict(bytes=grad_bytes * spq + 4 * spr + 4 * srq, flops=flops),
-        "adam": dict(bytes=24 * srq, flops=0),
-        "up": dict(bytes=8 * spq + 4 * spr + 4 * srq, flops=flops),
+        "down": dict(bytes=grad_bytes * spq + 4 * spr + 4 * srq + (4 * spq if ef else 0), flops=flops),
+        "adam": dict(bytes=(28 if ef else 24) * srq, flops=0),
+        "up": dict(bytes=up_bytes, flops=up_flops),
         "outer": dict(bytes=24 * spq, flops=0),
     }
 
@@ -222,8 +233,11 @@ def main():
     refresh_every = d["refresh_every"] if args.refresh_every is None else args.refresh_every
     n_sets = args.grad_sets or (4 if cfg in ("c1", "c2") else 2)
     shapes, W, G, Omega, D, grad_dtype = build_workload(torch, lordo, synth, cfg, args.rank, n_sets)
+    qhm_mode = {"plain": 0, "ef": 0, "low-qhm": 1, "full-qhm": 2, "global": 2}[args.update]
+    use_ef = args.update in ("ef", "global")
     hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=d["power_iters"],
-                       grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16)
+                       grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
+                       qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef)
     opt = lordo.Lordo(shapes, hp, W, torch)
     Wp = opt.ptrs(W)
     Gp = [opt.ptrs(g, grad_dtype) for g in G]
@@ -243,7 +257,7 @@ def main():
     ms_per_step = 1e3 * (t1 - t0) / args.steps
     opt.poll_status()
 
-    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2)
+    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2, ef=use_ef, qhm_full=qhm_mode == 2)
     kernels = {}
     roofline = None
     if not args.no_events:
@@ -277,11 +291,11 @@ def main():
         if t_mfma > t_hbm:
             ach = w["flops"] / avg_s / 1e12
             roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(cfg, args.rank, dom)}
+                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(cfg, args.rank, dom, args.update)}
         else:
             ach = w["bytes"] / avg_s / 1e9
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, args.rank, dom)}
+                        "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, args.rank, dom, args.update)}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -296,7 +310,8 @@ def main():
         "config": {"workload": WORKLOAD_TEXT[cfg] + (f", rank override {args.rank}" if args.rank else ""),
                    "matrices": len(shapes), "params": sum(p * q for p, q, r in shapes),
                    "refresh_every": refresh_every, "outer_every": outer_every, "power_iters": d["power_iters"],
-                   "grad_sets": n_sets, "outer": "nesterov lr 0.7 momentum 0.9 on a generated averaged pseudo-gradient"},
+                   "grad_sets": n_sets, "outer": "nesterov lr 0.7 momentum 0.9 on a generated averaged pseudo-gradient",
+                   "update": args.update},
         "roofline": roofline,
         "kernels": kernels,
         "cpu_baseline": cpu,

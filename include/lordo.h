@@ -54,6 +54,7 @@ extern "C" {
 #define LORDO_STATE_MOM     4   /* p x q  outer momentum b (only if outer_momentum!=0) */
 #define LORDO_STATE_GLOW    5   /* r x q  g of the last local step (read only)         */
 #define LORDO_STATE_NUPD    6   /* r x q  bracketed update N of the last local step (read only) */
+#define LORDO_STATE_ERR     7   /* p x q  error-feedback residual E (only if error_feedback != 0) */
 
 typedef struct lordo_ctx lordo_ctx;
 
@@ -70,9 +71,9 @@ typedef struct {
 typedef struct {
   double  beta1, beta2, eps;     /* moment decay rates; eps is added outside the root (Sec. 2)        */
   int32_t bias_correction;       /* 1: u/(1-beta1^t), v/(1-beta2^t) as in Sec. 2; 0: as Alg. 1 prints  */
-  int32_t qhm_mode;              /* 0 none.  1 (low-rank) and 2 (full-rank) are not built: LORDO_EINVAL */
-  double  omega;                 /* QHM mixing coefficient; ignored when qhm_mode == 0                  */
-  int32_t error_feedback;        /* 0.  1 is not built: LORDO_EINVAL                                    */
+  int32_t qhm_mode;              /* Alg. 1 update cases: 0 "No QHM", 1 "Low-Rank QHM", 2 "Full-Rank QHM" (Sec. 3.2) */
+  double  omega;                 /* QHM mixing coefficient in [0, 1]; ignored when qhm_mode == 0        */
+  int32_t error_feedback;        /* 1: keep the residual E and project G + E (Alg. 1 error-feedback lines) */
   int32_t outer_nesterov;        /* with outer_momentum != 0: 1 Nesterov, 0 heavy ball                  */
   double  outer_lr;              /* eta_s; 1.0 with outer_momentum 0 is plain averaging (Alg. 1)        */
   double  outer_momentum;        /* mu; 0 keeps no momentum buffer                                      */
@@ -94,12 +95,18 @@ int lordo_workspace_bytes(const lordo_shape* shapes, int32_t n, const lordo_hpar
 int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp,
                void* arena, size_t arena_bytes, void* const* W, void* stream);
 
-/* One local step on every matrix (Sec. 2; Alg. 1 inner loop, "No QHM" case):
- *   t <- t+1;  g = Q^T (grad_scale * G);  u <- beta1 u + (1-beta1) g;  v <- beta2 v + (1-beta2) g*g;
- *   N = (u/c1) / (sqrt(v/c2) + eps), c_i = 1-beta_i^t (1 if bias_correction == 0);  W <- W - lr * Q N.
+/* One local step on every matrix (Sec. 2; Alg. 1 inner loop):
+ *   t <- t+1;  A = grad_scale * G  (+ E with error feedback);  g = Q^T A;  [E <- A - Q g];
+ *   u <- beta1 u + (1-beta1) g;  v <- beta2 v + (1-beta2) g*g;  u^ = u/c1, v^ = v/c2, c_i = 1-beta_i^t
+ *   (1 if bias_correction == 0);  den = sqrt(v^) + eps;
+ *   qhm_mode 0:  N = u^ / den;                             W <- W - lr * Q N
+ *   qhm_mode 1:  N = (omega u^ + (1-omega) g) / den;       W <- W - lr * Q N
+ *   qhm_mode 2:  N = u^ / den;  s_j = mean_i den_ij;       W <- W - lr * ((1-omega) grad_scale G diag(1/s) + omega Q N)
  *   W   host array of n device pointers, fp32 p x q, updated in place.
  *   G   host array of n device pointers, p x q of hp.grad_dtype, read only.
- *   grad_scale  scalar the caller's gradient clipping produced (1 = none). */
+ *   grad_scale  scalar the caller's gradient clipping produced (1 = none).
+ * qhm_mode 2 and error feedback need q % 4 == 0 for every matrix, W aligned to 16 bytes and G to
+ * 8 bytes (bf16) or 16 bytes (fp32); otherwise LORDO_EINVAL and nothing is enqueued. */
 int lordo_local_step(lordo_ctx* ctx, void* const* W, const void* const* G,
                      double lr, double grad_scale, void* stream);
 

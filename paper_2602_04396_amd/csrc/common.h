@@ -40,6 +40,7 @@ struct MatDev {
   int64_t dinv;           // fp32 ceil(r/NB) blocks of NB x NB : inverses of the diagonal blocks of the factor
   int64_t rot, rot2;      // fp32 r x r : R = Q_new^T Q_old and its elementwise square
   int64_t part;           // fp32 split-K partial sums of the r x r products (Gram, R): slices x r x r
+  int64_t err;            // fp32 p x q error-feedback residual E (-1 without error feedback)
 };
 
 // Work item of the projection kernels.
@@ -102,9 +103,19 @@ constexpr int NB = 64;            // Cholesky / triangular-solve block size
 // proj.hip
 struct DownFuse;     // below: state arrays and coefficients of the Adam update fused into the down-projection
 hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_waves, bool g_vec, bool g_once, float* glow,
-                            int64_t split_stride, float grad_scale, bool g_is_f32, const DownFuse* fuse, hipStream_t s);
-hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
-                          const uint16_t* n_lo, float lr, hipStream_t s);
+                            int64_t split_stride, float grad_scale, bool g_is_f32, bool ef, const DownFuse* fuse, hipStream_t s);
+// Epilogue of the up-projection: target <- target + coef_acc * (Q B) + coef_g * G * c_j
+struct UpArgs {
+  float coef_acc;         // -eta (plain), -eta*omega (full-rank QHM), -1 (error-feedback residual)
+  float coef_g;           // 0 (plain), -eta*(1-omega)*grad_scale (full-rank QHM), grad_scale (residual)
+  int32_t target_err;     // 0: the caller's W; 1: the residual E kept in the arena
+  int32_t colscale;       // 1: c_j = 1 / mean over the rank of sqrt(v_hat) + eps (full-rank QHM); 0: c_j = 1
+  int32_t g_is_f32;       // element type of G
+  float eps;
+  const float* colpart;   // column sums left by the Adam kernel (colscale == 1)
+};
+hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* b_hi,
+                          const uint16_t* b_lo, const UpArgs& ua, hipStream_t s);
 // gemm32.hip
 hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int tile, int src_is_bf16,
                          hipStream_t s);
@@ -117,6 +128,10 @@ struct AdamArgs {
   int64_t grp_start[4];
   int64_t split_stride;
   int64_t first;          // flat position of the first element the stand-alone kernel updates
+  float qw, qg;           // update bracket (qw * u_hat + qg * g) / den: 1, 0 without low-rank QHM; omega, 1 - omega with it
+  float* colpart;         // full-rank QHM: per column and rank block of 32, sum of sqrt(v_hat) + eps (else null)
+  uint16_t* g_hi;         // error feedback: bf16 hi / lo operand planes of the summed g (else null)
+  uint16_t* g_lo;
 };
 struct DownFuse {
   float* u;

@@ -35,50 +35,87 @@ typedef uint32_t u32x4n __attribute__((ext_vector_type(4)));
 // last-level cache).  N is consumed by the up-projection right away and stays cacheable.
 __device__ __forceinline__ f32x4n ld_stream(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4n*>(p)); }
 __device__ __forceinline__ void st_stream(float* p, f32x4n x) { __builtin_nontemporal_store(x, reinterpret_cast<f32x4n*>(p)); }
+// COLSUM: also leave, per column and block of 32 rank indices, the sum of the denominators
+// sqrt(v_hat) + eps (the column scale of the full-rank quasi-hyperbolic update, Sec. 3.2, is their
+// mean over the rank).  Four threads of a workgroup hold the four octets of such a block: their
+// sums meet in LDS and are added in fixed order.  Padded rank indices contribute eps each; the
+// consumer subtracts that.
+template <bool COLSUM>
 __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, float* __restrict__ u,
                                               float* __restrict__ v, uint16_t* __restrict__ n_hi,
                                               uint16_t* __restrict__ n_lo, int64_t ngroups, AdamArgs a) {
+  __shared__ float part[COLSUM ? 256 : 1];
   int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (gidx >= ngroups) return;
+  const bool live = gidx < ngroups;
+  if (!COLSUM && !live) return;
   int64_t base = a.first + gidx * 8;
-  float g[8], uu[8], vv[8];
-  {
-    const f32x4n* gp = reinterpret_cast<const f32x4n*>(glow + base);
-    f32x4n a0 = __builtin_nontemporal_load(gp), a1 = __builtin_nontemporal_load(gp + 1);
-    g[0] = a0.x; g[1] = a0.y; g[2] = a0.z; g[3] = a0.w; g[4] = a1.x; g[5] = a1.y; g[6] = a1.z; g[7] = a1.w;
-    int nsplit = a.grp_nsplit[0];
+  float dsum = 0.f;
+  if (live) {
+    float g[8], uu[8], vv[8];
+    {
+      const f32x4n* gp = reinterpret_cast<const f32x4n*>(glow + base);
+      f32x4n a0 = __builtin_nontemporal_load(gp), a1 = __builtin_nontemporal_load(gp + 1);
+      g[0] = a0.x; g[1] = a0.y; g[2] = a0.z; g[3] = a0.w; g[4] = a1.x; g[5] = a1.y; g[6] = a1.z; g[7] = a1.w;
+      int nsplit = a.grp_nsplit[0];
 #pragma unroll
-    for (int i = 1; i < 4; ++i)
-      if (base >= a.grp_start[i]) nsplit = a.grp_nsplit[i];
-    for (int sidx = 1; sidx < nsplit; ++sidx) {         // deterministic split-K reduction, fixed order
-      const f32x4n* sp = reinterpret_cast<const f32x4n*>(glow + sidx * a.split_stride + base);
-      f32x4n b0 = __builtin_nontemporal_load(sp), b1 = __builtin_nontemporal_load(sp + 1);
-      g[0] += b0.x; g[1] += b0.y; g[2] += b0.z; g[3] += b0.w; g[4] += b1.x; g[5] += b1.y; g[6] += b1.z; g[7] += b1.w;
+      for (int i = 1; i < 4; ++i)
+        if (base >= a.grp_start[i]) nsplit = a.grp_nsplit[i];
+      for (int sidx = 1; sidx < nsplit; ++sidx) {         // deterministic split-K reduction, fixed order
+        const f32x4n* sp = reinterpret_cast<const f32x4n*>(glow + sidx * a.split_stride + base);
+        f32x4n b0 = __builtin_nontemporal_load(sp), b1 = __builtin_nontemporal_load(sp + 1);
+        g[0] += b0.x; g[1] += b0.y; g[2] += b0.z; g[3] += b0.w; g[4] += b1.x; g[5] += b1.y; g[6] += b1.z; g[7] += b1.w;
+      }
+      f32x4n u0 = ld_stream(u + base), u1 = ld_stream(u + base + 4);
+      uu[0] = u0.x; uu[1] = u0.y; uu[2] = u0.z; uu[3] = u0.w; uu[4] = u1.x; uu[5] = u1.y; uu[6] = u1.z; uu[7] = u1.w;
+      f32x4n v0 = ld_stream(v + base), v1 = ld_stream(v + base + 4);
+      vv[0] = v0.x; vv[1] = v0.y; vv[2] = v0.z; vv[3] = v0.w; vv[4] = v1.x; vv[5] = v1.y; vv[6] = v1.z; vv[7] = v1.w;
     }
-    f32x4n u0 = ld_stream(u + base), u1 = ld_stream(u + base + 4);
-    uu[0] = u0.x; uu[1] = u0.y; uu[2] = u0.z; uu[3] = u0.w; uu[4] = u1.x; uu[5] = u1.y; uu[6] = u1.z; uu[7] = u1.w;
-    f32x4n v0 = ld_stream(v + base), v1 = ld_stream(v + base + 4);
-    vv[0] = v0.x; vv[1] = v0.y; vv[2] = v0.z; vv[3] = v0.w; vv[4] = v1.x; vv[5] = v1.y; vv[6] = v1.z; vv[7] = v1.w;
-  }
-  uint32_t hi[8], lo[8];
+    uint32_t hi[8], lo[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float un = fmaf(a.b1, uu[e], a.omb1 * g[e]);
-    float vn = fmaf(a.b2, vv[e], a.omb2 * (g[e] * g[e]));
-    uu[e] = un;
-    vv[e] = vn;
-    float nn = (un * a.inv_c1) / (sqrtf(vn * a.inv_c2) + a.eps);
-    split_bf(nn, hi[e], lo[e]);
+    for (int e = 0; e < 8; ++e) {
+      float un = fmaf(a.b1, uu[e], a.omb1 * g[e]);
+      float vn = fmaf(a.b2, vv[e], a.omb2 * (g[e] * g[e]));
+      uu[e] = un;
+      vv[e] = vn;
+      const float den = sqrtf(vn * a.inv_c2) + a.eps;
+      dsum += den;
+      // Alg. 1 update bracket: u_hat / den, or (omega u_hat + (1 - omega) g) / den for the low-rank
+      // quasi-hyperbolic case; with qw = 1, qg = 0 the value is bit-identical to u_hat / den
+      float nn = fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;
+      split_bf(nn, hi[e], lo[e]);
+    }
+    st_stream(u + base, f32x4n{uu[0], uu[1], uu[2], uu[3]});
+    st_stream(u + base + 4, f32x4n{uu[4], uu[5], uu[6], uu[7]});
+    st_stream(v + base, f32x4n{vv[0], vv[1], vv[2], vv[3]});
+    st_stream(v + base + 4, f32x4n{vv[4], vv[5], vv[6], vv[7]});
+    u32x4n ph, pl;
+    ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
+    pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
+    *reinterpret_cast<u32x4n*>(n_hi + base) = ph;
+    *reinterpret_cast<u32x4n*>(n_lo + base) = pl;
+    if (a.g_hi) {            // error feedback: the summed g as operand planes of the residual update E = A - Q g
+#pragma unroll
+      for (int e = 0; e < 8; ++e) split_bf(g[e], hi[e], lo[e]);
+      ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
+      pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
+      *reinterpret_cast<u32x4n*>(a.g_hi + base) = ph;
+      *reinterpret_cast<u32x4n*>(a.g_lo + base) = pl;
+    }
   }
-  st_stream(u + base, f32x4n{uu[0], uu[1], uu[2], uu[3]});
-  st_stream(u + base + 4, f32x4n{uu[4], uu[5], uu[6], uu[7]});
-  st_stream(v + base, f32x4n{vv[0], vv[1], vv[2], vv[3]});
-  st_stream(v + base + 4, f32x4n{vv[4], vv[5], vv[6], vv[7]});
-  u32x4n ph, pl;
-  ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
-  pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
-  *reinterpret_cast<u32x4n*>(n_hi + base) = ph;
-  *reinterpret_cast<u32x4n*>(n_lo + base) = pl;
+  if constexpr (COLSUM) {
+    // group index = (column block * (rp/8) + octet) * 32 + column; a.first/8 and the group count of every
+    // matrix are multiples of 128, so threadIdx % 128 = (octet % 4) * 32 + column
+    part[threadIdx.x] = dsum;
+    __syncthreads();
+    if (live && (threadIdx.x & 96) == 0) {
+      const int t0 = threadIdx.x;
+      const float sum = ((part[t0] + part[t0 + 32]) + part[t0 + 64]) + part[t0 + 96];
+      // this thread holds octet 4*rb of rank block rb: its group index is (cb*(rp/8) + 4*rb)*32 + column,
+      // and the sum goes to (cb*(rp/32) + rb)*32 + column
+      const int64_t grp = base >> 3;
+      a.colpart[((grp & ~int64_t(31)) >> 2) + (grp & 31)] = sum;
+    }
+  }
 }
 
 hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
@@ -86,7 +123,8 @@ hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, ui
   int64_t ngroups = (nelem - a.first) / 8;            // a.first and nelem are multiples of 8
   if (ngroups <= 0) return hipSuccess;
   unsigned blocks = (unsigned)((ngroups + 255) / 256);
-  hipLaunchKernelGGL(k_adam, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
+  if (a.colpart) hipLaunchKernelGGL(k_adam<true>, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
+  else hipLaunchKernelGGL(k_adam<false>, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
   return hipGetLastError();
 }
 

@@ -46,6 +46,7 @@ struct Plan {
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
   int down_pipe = 0;                // waves of the pipelined down-projection (8: 256-column tiles, 4: 128-column; 0: plain kernel)
   bool g_once = true;               // every matrix has one rank tile of the down-projection: G is read exactly once
+  int64_t colpart = -1, g_hi = -1, g_lo = -1;   // full-rank QHM column sums; error-feedback planes of g
   int64_t adam_first = 0;           // flat position from which the stand-alone Adam kernel runs (elements before it are fused)
   int nsplit = 1;                   // largest split-K factor of the down-projection
   std::vector<int> splits;          // split-K factor per matrix (1, 2, 4 or 8)
@@ -322,7 +323,9 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
     if (s.rows > (1 << 24) || s.cols > (1 << 24) || s.rank > 4096) return LORDO_EINVAL;
   }
   if (!(hp->beta1 >= 0 && hp->beta1 < 1) || !(hp->beta2 >= 0 && hp->beta2 < 1) || !(hp->eps >= 0)) return LORDO_EINVAL;
-  if (hp->qhm_mode != 0 || hp->error_feedback != 0 || hp->reserved != 0) return LORDO_EINVAL;
+  if (hp->qhm_mode < 0 || hp->qhm_mode > 2 || (hp->error_feedback != 0 && hp->error_feedback != 1) || hp->reserved != 0)
+    return LORDO_EINVAL;
+  if (hp->qhm_mode != 0 && !(hp->omega >= 0.0 && hp->omega <= 1.0)) return LORDO_EINVAL;
   if (hp->power_iters < 0 || hp->power_iters > 8) return LORDO_EINVAL;
   if (hp->orth_passes != 0 && hp->orth_passes != 2 && hp->orth_passes != 3) return LORDO_EINVAL;
   if (hp->grad_dtype != LORDO_BF16 && hp->grad_dtype != LORDO_F32) return LORDO_EINVAL;
@@ -357,7 +360,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.mb = (hp.grad_dtype == LORDO_BF16 || rp_max > 64) ? 4 : (rp_max > 32 ? 2 : 1);
   // Down-projection launch shape: the pipelined kernel (rank tiles of 128, bf16 G, 256-column
   // tiles) where it applies, else the plain kernel with 128-column tiles.
-  P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16) ? 8 : 0;
+  P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16 && !hp.error_feedback) ? 8 : 0;
   P.g_once = rp_max <= 32 * P.mb;
   const int down_bn = P.down_pipe == 8 ? 256 : 128;
   P.up_waves = 4;
@@ -416,12 +419,14 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the launch has several rounds of workgroups and the epilogue of one overlaps the main loop of
   // another; a launch that needs split-K is a single round of workgroups in lock step, where the
   // stand-alone kernel is as fast and leaves the down-projection shorter.
-  P.adam_first = (P.down_pipe && P.nsplit == 1) ? lr : 0;
+  P.adam_first = (P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0) ? lr : 0;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);
   P.v = A.take(sizeof(float) * lr);
   P.n_hi = A.take(sizeof(uint16_t) * lr);
   P.n_lo = A.take(sizeof(uint16_t) * lr);
+  if (hp.qhm_mode == 2) P.colpart = A.take(sizeof(float) * (lr / 32));
+  if (hp.error_feedback) { P.g_hi = A.take(sizeof(uint16_t) * lr); P.g_lo = A.take(sizeof(uint16_t) * lr); }
   P.part_slices = small_out_split(P.mat.data(), n, nullptr);
   for (int i = 0; i < n; ++i) {
     MatDev& m = P.mat[i];
@@ -432,6 +437,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.qt_hi = A.take(planes); m.qt_lo = A.take(planes);
     m.anchor = A.take(pq * 4);
     m.mom = has_mom ? A.take(pq * 4) : -1;
+    m.err = hp.error_feedback ? A.take(pq * 4) : -1;
     m.y[0] = A.take(pr * 4); m.y[1] = A.take(pr * 4);
     for (int k = 0; k < 4; ++k) m.zw[k] = A.take(qr * 4);
     m.gram = A.take(rr * 4); m.lfac = A.take(rr * 4);
@@ -451,7 +457,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
           ProjTile t{};
           t.mat = i; t.m0 = m0; t.n0 = n0; t.split = sp;
           t.k0 = std::min(sp * klen, m.pp); t.k1 = std::min(t.k0 + klen, m.pp);
-          t.fuse = (P.down_pipe && P.nsplit == 1) ? 1 : 0;
+          t.fuse = (P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0) ? 1 : 0;
           down.push_back(t);
         }
     for (int m0 = 0; m0 < m.pp; m0 += 128)
@@ -644,16 +650,31 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
   a.split_stride = P.lr_total;
   a.first = P.adam_first;
+  const bool qhm_low = c->hp.qhm_mode == 1, qhm_full = c->hp.qhm_mode == 2, ef = c->hp.error_feedback != 0;
+  a.qw = qhm_low ? (float)c->hp.omega : 1.f;
+  a.qg = qhm_low ? (float)(1.0 - c->hp.omega) : 0.f;
+  a.colpart = qhm_full ? c->at<float>(P.colpart) : nullptr;
+  a.g_hi = ef ? c->at<uint16_t>(P.g_hi) : nullptr;
+  a.g_lo = ef ? c->at<uint16_t>(P.g_lo) : nullptr;
+  const bool g_f32 = c->hp.grad_dtype == LORDO_F32;
   bool g_vec = true;            // 4-byte accesses to a bf16 G need an even q and 4-byte aligned pointers
   for (int i = 0; i < c->n; ++i)
     if ((P.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 3) != 0) { g_vec = false; break; }
+  bool w_vec = true;            // 16-byte accesses to W need q % 4 == 0 and 16-byte aligned pointers
+  for (int i = 0; i < c->n; ++i)
+    if ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
+  if (qhm_full || ef) {         // the gradient-term epilogue reads four columns of G per lane
+    if (!w_vec) return LORDO_EINVAL;
+    for (int i = 0; i < c->n; ++i)
+      if ((reinterpret_cast<uintptr_t>(G[i]) & (g_f32 ? 15 : 7)) != 0) return LORDO_EINVAL;
+  }
   DownFuse fuse;
   fuse.u = c->at<float>(P.u); fuse.v = c->at<float>(P.v);
   fuse.n_hi = c->at<uint16_t>(P.n_hi); fuse.n_lo = c->at<uint16_t>(P.n_lo);
   fuse.a = a;
   c->prof.begin(LORDO_K_DOWN, s);
   HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, P.g_once, c->at<float>(P.glow),
-                          P.lr_total, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, &fuse, s));
+                          P.lr_total, (float)grad_scale, g_f32, ef, &fuse, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
   if (P.adam_first < P.lr_total)
@@ -661,11 +682,24 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
                        c->at<uint16_t>(P.n_lo), P.lr_total, a, s));
   c->prof.end(LORDO_K_ADAM, s);
   c->prof.begin(LORDO_K_UP, s);
-  bool w_vec = true;            // 16-byte accesses to W need q % 4 == 0 and 16-byte aligned pointers
-  for (int i = 0; i < c->n; ++i)
-    if ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
-  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, P.up_waves, c->at<uint16_t>(P.n_hi),
-                        c->at<uint16_t>(P.n_lo), (float)lr, s));
+  UpArgs ua{};
+  ua.g_is_f32 = g_f32 ? 1 : 0;
+  ua.eps = (float)c->hp.eps;
+  if (ef) {                     // E <- grad_scale*G + E - Q g (Alg. 1 error-feedback lines); reads the E the down-projection used
+    ua.coef_acc = -1.f; ua.coef_g = (float)grad_scale; ua.target_err = 1; ua.colscale = 0; ua.colpart = nullptr;
+    HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.g_hi),
+                          c->at<uint16_t>(P.g_lo), ua, s));
+  }
+  ua.target_err = 0;
+  if (qhm_full) {               // W <- W - eta [ (1-omega) G_hat diag(1/s) + omega Q N ]  (Alg. 1 "Full-Rank QHM")
+    ua.coef_acc = (float)(-lr * c->hp.omega);
+    ua.coef_g = (float)(-lr * (1.0 - c->hp.omega) * grad_scale);
+    ua.colscale = 1; ua.colpart = c->at<float>(P.colpart);
+  } else {
+    ua.coef_acc = (float)-lr; ua.coef_g = 0.f; ua.colscale = 0; ua.colpart = nullptr;
+  }
+  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
+                        c->at<uint16_t>(P.n_lo), ua, s));
   c->prof.end(LORDO_K_UP, s);
   c->t = t;
   return LORDO_OK;
@@ -760,6 +794,10 @@ int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, voi
       if (m.mom < 0) return LORDO_ESTATE;
       HIPCHK(launch_copy_f32(dst, c->at<float>(m.mom), (int64_t)m.p * m.q, s));
       break;
+    case LORDO_STATE_ERR:
+      if (m.err < 0) return LORDO_ESTATE;
+      HIPCHK(launch_copy_f32(dst, c->at<float>(m.err), (int64_t)m.p * m.q, s));
+      break;
     case LORDO_STATE_U: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.u), nullptr, nullptr, dst, 1, 0, s)); break;
     case LORDO_STATE_V: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.v), nullptr, nullptr, dst, 1, 0, s)); break;
     case LORDO_STATE_GLOW:
@@ -788,6 +826,10 @@ int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_sr
     case LORDO_STATE_MOM:
       if (m.mom < 0) return LORDO_ESTATE;
       HIPCHK(launch_copy_f32(c->at<float>(m.mom), src, (int64_t)m.p * m.q, s));
+      break;
+    case LORDO_STATE_ERR:
+      if (m.err < 0) return LORDO_ESTATE;
+      HIPCHK(launch_copy_f32(c->at<float>(m.err), src, (int64_t)m.p * m.q, s));
       break;
     case LORDO_STATE_U: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.u), src, s)); break;
     case LORDO_STATE_V: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.v), src, s)); break;

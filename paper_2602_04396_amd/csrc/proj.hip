@@ -145,9 +145,25 @@ __device__ __forceinline__ void store_gstage(const GStage<GF32>& st, u32x4* lds_
   }
 }
 
-template <int MB, bool GF32, int KG>
+// grad_scale * G + E of one stage (error feedback, Alg. 1: the projected matrix is the gradient plus the residual)
+template <bool GF32>
+__device__ __forceinline__ void add_residual(GStage<true>& out, const GStage<GF32>& g, const GStage<true>& e, float scale) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float g0, g1;
+    if constexpr (GF32) { g0 = __uint_as_float(g.x[2 * i]); g1 = __uint_as_float(g.x[2 * i + 1]); }
+    else { g0 = __uint_as_float(g.x[i] << 16); g1 = __uint_as_float(g.x[i] & 0xffff0000u); }
+    out.x[2 * i] = __float_as_uint(fmaf(scale, g0, __uint_as_float(e.x[2 * i])));
+    out.x[2 * i + 1] = __float_as_uint(fmaf(scale, g1, __uint_as_float(e.x[2 * i + 1])));
+  }
+}
+
+// EF: error feedback -- the contraction runs over A = grad_scale*G + E (E fp32, kept in the arena), staged as fp32
+// and split hi + lo on the fly like an fp32 gradient; the result is then not scaled again.
+template <int MB, bool GF32, int KG, bool EF>
 __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
                                                    int64_t split_stride, float grad_scale) {
+  constexpr bool SF32 = GF32 || EF;                           // staged operand is fp32 (three MFMA passes)
   constexpr int BK = 32 * KG;                                 // rows of G per pipeline stage
   constexpr int KGRPS = 4 * KG;                               // 8-row groups per stage
   const ProjTile t = tiles[blockIdx.x];
@@ -158,7 +174,7 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
 
   constexpr int STAGE_SLOTS = 4 * KGRPS * 32;                 // (nblk, kgrp, n) 16-byte slots
   __shared__ u32x4 lds_hi[2 * STAGE_SLOTS];
-  __shared__ u32x4 lds_lo[GF32 ? 2 * STAGE_SLOTS : 1];
+  __shared__ u32x4 lds_lo[SF32 ? 2 * STAGE_SLOTS : 1];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps row offsets scalar
@@ -177,6 +193,13 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
   gc.vec = (m.q & 1) == 0 && (reinterpret_cast<uintptr_t>(Gbase) & (2 * ES - 1)) == 0;
   gc.off0 = col < m.q ? (uint32_t)col * ES : OOB;
   gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * ES : OOB;
+  // residual E: fp32 p x q in the arena, same rows and columns
+  const uint32_t erow_bytes = (uint32_t)m.q * 4u;
+  const rsrc_t re = EF ? make_rsrc(d.arena + m.err, (uint32_t)klim * erow_bytes) : rs;
+  GCol ge;
+  ge.vec = (m.q & 1) == 0;
+  ge.off0 = col < m.q ? (uint32_t)col * 4u : OOB;
+  ge.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 4u : OOB;
   // this wave stages the 8-row groups h*4 + wave, h < KG; nblk = lane/16
   const int wslot = ((lane >> 4) * KGRPS + wave) * 32 + 2 * (lane & 15);
 
@@ -204,26 +227,42 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
   };
   const bool g_once = m.rp <= 32 * MB;                        // one rank tile: every G element is read exactly once
   GStage<GF32> st[KG];
+  GStage<true> se[EF ? KG : 1];
+  auto stage_out = [&](int h, u32x4* hi, u32x4* lo) {          // registers of stage part h -> LDS
+    if constexpr (EF) {
+      GStage<true> sa;
+      add_residual<GF32>(sa, st[h], se[h], grad_scale);
+      store_gstage<true>(sa, hi, lo, wslot + h * 4 * 32);
+    } else {
+      store_gstage<GF32>(st[h], hi, lo, wslot + h * 4 * 32);
+    }
+  };
 #pragma unroll
-  for (int h = 0; h < KG; ++h) if (g_once) load_gstage<GF32, STREAM>(st[h], rs, row_bytes, t.k0 + 8 * (h * 4 + wave), klim, gc);
+  for (int h = 0; h < KG; ++h) {
+    if (g_once) load_gstage<GF32, STREAM>(st[h], rs, row_bytes, t.k0 + 8 * (h * 4 + wave), klim, gc);
     else load_gstage<GF32, 0>(st[h], rs, row_bytes, t.k0 + 8 * (h * 4 + wave), klim, gc);
+    if constexpr (EF) load_gstage<true, 0>(se[h], re, erow_bytes, t.k0 + 8 * (h * 4 + wave), klim, ge);
+  }
   load_a(a_cur, t.k0);
 #pragma unroll
-  for (int h = 0; h < KG; ++h) store_gstage<GF32>(st[h], lds_hi, lds_lo, wslot + h * 4 * 32);
+  for (int h = 0; h < KG; ++h) stage_out(h, lds_hi, lds_lo);
   __syncthreads();
 
   for (int s = 0; s < nstages; ++s) {
     const int kr = t.k0 + s * BK;
     if (s + 1 < nstages) {
 #pragma unroll
-      for (int h = 0; h < KG; ++h) if (g_once) load_gstage<GF32, STREAM>(st[h], rs, row_bytes, kr + BK + 8 * (h * 4 + wave), klim, gc);
+      for (int h = 0; h < KG; ++h) {
+        if (g_once) load_gstage<GF32, STREAM>(st[h], rs, row_bytes, kr + BK + 8 * (h * 4 + wave), klim, gc);
         else load_gstage<GF32, 0>(st[h], rs, row_bytes, kr + BK + 8 * (h * 4 + wave), klim, gc);
+        if constexpr (EF) load_gstage<true, 0>(se[h], re, erow_bytes, kr + BK + 8 * (h * 4 + wave), klim, ge);
+      }
       load_a(a_nxt, kr + BK);
     }
     ISSUE_FENCE();
     if (active) {
       const u32x4* bh = lds_hi + (s & 1) * STAGE_SLOTS;
-      const u32x4* bl = lds_lo + (GF32 ? (s & 1) * STAGE_SLOTS : 0);
+      const u32x4* bl = lds_lo + (SF32 ? (s & 1) * STAGE_SLOTS : 0);
 #pragma unroll
       for (int ks = 0; ks < 2 * KG; ++ks) {
         bf16x8 a_hi = as_bf(a_cur[2 * ks]);
@@ -234,7 +273,7 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
           bf16x8 b = as_bf(bh[bslot]);
           acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[a], 0, 0, 0);
           acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[a], 0, 0, 0);
-          if constexpr (GF32) {
+          if constexpr (SF32) {
             bf16x8 b2 = as_bf(bl[bslot]);
             acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b2, acc[a], 0, 0, 0);
           }
@@ -245,8 +284,7 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
     if (s + 1 < nstages) {
 #pragma unroll
       for (int h = 0; h < KG; ++h)
-        store_gstage<GF32>(st[h], lds_hi + ((s + 1) & 1) * STAGE_SLOTS, lds_lo + (GF32 ? ((s + 1) & 1) * STAGE_SLOTS : 0),
-                           wslot + h * 4 * 32);
+        stage_out(h, lds_hi + ((s + 1) & 1) * STAGE_SLOTS, lds_lo + (SF32 ? ((s + 1) & 1) * STAGE_SLOTS : 0));
 #pragma unroll
       for (int i = 0; i < 4 * KG; ++i) a_cur[i] = a_nxt[i];
     }
@@ -264,9 +302,10 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
 #pragma unroll
     for (int vq = 0; vq < 4; ++vq) {
       int64_t o = (((int64_t)nbg * rgroups + 4 * mbg + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+      const float osc = EF ? 1.f : grad_scale;                // with error feedback the scale went into A
       f32x4 val;
-      val.x = grad_scale * acc[a][4 * vq];     val.y = grad_scale * acc[a][4 * vq + 1];
-      val.z = grad_scale * acc[a][4 * vq + 2]; val.w = grad_scale * acc[a][4 * vq + 3];
+      val.x = osc * acc[a][4 * vq];     val.y = osc * acc[a][4 * vq + 1];
+      val.z = osc * acc[a][4 * vq + 2]; val.w = osc * acc[a][4 * vq + 3];
       *reinterpret_cast<GAS f32x4*>(out + o) = val;
     }
   }
@@ -499,7 +538,7 @@ __global__ __launch_bounds__(64 * NW) void k_proj_down_pipe(DevCtx d, const Proj
 }
 
 hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_waves, bool g_vec, bool g_once, float* glow,
-                            int64_t split_stride, float grad_scale, bool g_is_f32, const DownFuse* fuse, hipStream_t s) {
+                            int64_t split_stride, float grad_scale, bool g_is_f32, bool ef, const DownFuse* fuse, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
   if (pipe_waves) {
@@ -517,8 +556,10 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
     return hipGetLastError();
   }
 #define LORDO_DOWN(MBV)                                                                                            \
-  if (g_is_f32) hipLaunchKernelGGL((k_proj_down<MBV, true, 1>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
-  else hipLaunchKernelGGL((k_proj_down<MBV, false, 2>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale);
+  if (ef && g_is_f32) hipLaunchKernelGGL((k_proj_down<MBV, true, 1, true>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
+  else if (ef) hipLaunchKernelGGL((k_proj_down<MBV, false, 1, true>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
+  else if (g_is_f32) hipLaunchKernelGGL((k_proj_down<MBV, true, 1, false>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
+  else hipLaunchKernelGGL((k_proj_down<MBV, false, 2, false>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale);
   if (mb == 4) { LORDO_DOWN(4) } else if (mb == 2) { LORDO_DOWN(2) } else { LORDO_DOWN(1) }
 #undef LORDO_DOWN
   return hipGetLastError();
@@ -715,9 +756,15 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 // fragments) are double-buffered; one barrier per chunk.
 // ---------------------------------------------------------------------------------------
 
-template <int NW>           // waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64)
+// WITH_G adds a gradient term to the epilogue: target <- target + coef_acc * (Q B) + coef_g * G * c_j, with
+//   full-rank quasi-hyperbolic update (Alg. 1, "Full-Rank QHM"; Sec. 3.2): target W, B = N, coef_acc = -eta*omega,
+//     coef_g = -eta*(1-omega)*grad_scale, c_j = 1 / mean_i(sqrt(v_hat_ij) + eps);
+//   error-feedback residual (Alg. 1 error-feedback lines): target E, B = g, coef_acc = -1, coef_g = grad_scale, c_j = 1
+//     (E <- grad_scale*G + E - Q g).
+template <int NW, bool WITH_G>     // NW waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64)
 __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
-                                                         const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
+                                                         const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, UpArgs ua) {
+  const float lr = -ua.coef_acc;
   constexpr int AM = NW == 4 ? 2 : 1;                      // row blocks per wave
   constexpr int WM = 4 / AM;                               // wave rows
   const ProjTile t = tiles[blockIdx.x];
@@ -765,7 +812,8 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 
   // W tile in row order: lane = (rr, c4): row rr + 8j of a block, columns 4*c4 .. 4*c4+3
   const uint32_t row_bytes = (uint32_t)q * 4u;
-  const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
+  const void* target = (WITH_G && ua.target_err) ? static_cast<const void*>(d.arena + m.err) : ext_ptr(d, EXT_W, t.mat);
+  const rsrc_t rw = make_rsrc(target, (uint32_t)p * row_bytes);
   const int rr = lane >> 3, c4 = lane & 7;
   uint32_t voff[2];
 #pragma unroll
@@ -773,8 +821,11 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     int col = 32 * (nb0 + b) + 4 * c4;
     voff[b] = col < q ? (uint32_t)rr * row_bytes + (uint32_t)c4 * 16u : OOB;
   }
+  // a group of eight rows that starts at or past the last row gets the size of the resource as its
+  // scalar offset, which puts every lane of the access out of range
   auto w_soff = [&](int a, int b, int j) -> uint32_t {
-    return (uint32_t)(32 * (mb0 + a) + 8 * j) * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u;
+    const int row = 32 * (mb0 + a) + 8 * j;
+    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u : (uint32_t)p * row_bytes;
   };
 
   issue_chunk(0, 0);
@@ -827,6 +878,45 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   __syncthreads();                // all waves are done reading fragments: reuse the memory for staging
 
   if (mb0 >= mblocks || nb0 >= nblocks) return;
+  // gradient term: four consecutive columns per lane, same rows as the W accesses
+  const uint32_t ges = ua.g_is_f32 ? 4u : 2u;
+  const uint32_t grow_bytes = (uint32_t)q * ges;
+  rsrc_t rg = rw;
+  f32x4 cscale[2] = {{1.f, 1.f, 1.f, 1.f}, {1.f, 1.f, 1.f, 1.f}};
+  if constexpr (WITH_G) {
+    rg = make_rsrc(ext_ptr(d, EXT_G, t.mat), (uint32_t)p * grow_bytes);
+    if (ua.colscale) {
+      const GAS float* cp = TO_GLOBAL(const float, ua.colpart) + m.lr_off / 32;
+      const int rblocks = m.rp / 32;
+      const float pad = (float)(m.rp - m.r) * ua.eps;          // padded rank indices hold v = 0: eps each
+      const float inv_r = 1.f / (float)m.r;
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        if (nb0 + b >= nblocks) continue;
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        for (int rb = 0; rb < rblocks; ++rb)                    // fixed order
+          sum += *reinterpret_cast<const GAS f32x4*>(cp + ((int64_t)(nb0 + b) * rblocks + rb) * 32 + 4 * c4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cscale[b][e] = 1.f / ((sum[e] - pad) * inv_r);
+      }
+    }
+  }
+  auto g_term = [&](int a, int b, int j) -> f32x4 {
+    const int row = 32 * (mb0 + a) + 8 * j;
+    const uint32_t soff = row < p ? (uint32_t)row * grow_bytes + (uint32_t)(32 * (nb0 + b)) * ges : (uint32_t)p * grow_bytes;
+    const int col = 32 * (nb0 + b) + 4 * c4;
+    const uint32_t vo = col < q ? (uint32_t)rr * grow_bytes + (uint32_t)c4 * 4u * ges : OOB;
+    f32x4 gv;
+    if (ua.g_is_f32) {
+      u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rg, vo, soff, 0);
+      gv.x = __uint_as_float(w.x); gv.y = __uint_as_float(w.y); gv.z = __uint_as_float(w.z); gv.w = __uint_as_float(w.w);
+    } else {
+      u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rg, vo, soff, 0);
+      gv.x = __uint_as_float(w.x << 16); gv.y = __uint_as_float(w.x & 0xffff0000u);
+      gv.z = __uint_as_float(w.y << 16); gv.w = __uint_as_float(w.y & 0xffff0000u);
+    }
+    return gv * cscale[b] * ua.coef_g;
+  };
   // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e
   float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
 #pragma unroll
@@ -840,6 +930,11 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
         *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
       }
       // LDS operations of one wave complete in order: the reads below see the writes above
+      f32x4 gt[4];
+      if constexpr (WITH_G) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) gt[j] = g_term(a, b, j);
+      }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
@@ -848,18 +943,28 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
         o.y = __float_as_uint(fmaf(-lr, x.y, __uint_as_float(wv[a][b][j].y)));
         o.z = __float_as_uint(fmaf(-lr, x.z, __uint_as_float(wv[a][b][j].z)));
         o.w = __float_as_uint(fmaf(-lr, x.w, __uint_as_float(wv[a][b][j].w)));
+        if constexpr (WITH_G) {
+          o.x = __float_as_uint(__uint_as_float(o.x) + gt[j].x); o.y = __float_as_uint(__uint_as_float(o.y) + gt[j].y);
+          o.z = __float_as_uint(__uint_as_float(o.z) + gt[j].z); o.w = __float_as_uint(__uint_as_float(o.w) + gt[j].w);
+        }
         __builtin_amdgcn_raw_buffer_store_b128(o, rw, voff[b], w_soff(a, b, j), STREAM);
       }
     }
 }
 
-hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, int nwaves, const uint16_t* n_hi,
-                          const uint16_t* n_lo, float lr, hipStream_t s) {
+hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* b_hi,
+                          const uint16_t* b_lo, const UpArgs& ua, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
-  if (vec && nwaves == 8) hipLaunchKernelGGL((k_proj_up_dma<8>), grid, dim3(512), 0, s, d, tiles, n_hi, n_lo, lr);
-  else if (vec) hipLaunchKernelGGL((k_proj_up_dma<4>), grid, block, 0, s, d, tiles, n_hi, n_lo, lr);
-  else hipLaunchKernelGGL((k_proj_up<false>), grid, block, 0, s, d, tiles, n_hi, n_lo, lr);
+  const bool with_g = ua.coef_g != 0.f || ua.target_err;
+  if (with_g) {
+    if (!vec) return hipErrorInvalidValue;       // the gradient-term epilogue exists for 16-byte row accesses only
+    hipLaunchKernelGGL((k_proj_up_dma<4, true>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+  } else if (vec) {
+    hipLaunchKernelGGL((k_proj_up_dma<4, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+  } else {
+    hipLaunchKernelGGL((k_proj_up<false>), grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc);
+  }
   return hipGetLastError();
 }
 

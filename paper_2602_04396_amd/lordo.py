@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "lib", "liblordo.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE, ENUMERIC = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-STATE_Q, STATE_U, STATE_V, STATE_ANCHOR, STATE_MOM, STATE_GLOW, STATE_NUPD = range(7)
+STATE_Q, STATE_U, STATE_V, STATE_ANCHOR, STATE_MOM, STATE_GLOW, STATE_NUPD, STATE_ERR = range(8)
 
 EXPORTS = [
     "lordo_workspace_bytes", "lordo_init", "lordo_local_step", "lordo_refresh_subspace",
@@ -199,7 +199,7 @@ class Lordo:
     # -- state ------------------------------------------------------------------------------------
     def _state_shape(self, mat, which):
         p, q, r = self.shapes[mat]
-        return {STATE_Q: (p, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q)}.get(which, (r, q))
+        return {STATE_Q: (p, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q), STATE_ERR: (p, q)}.get(which, (r, q))
 
     def get_state(self, mat, which):
         out = self.torch.empty(self._state_shape(mat, which), dtype=self.torch.float32, device=self.arena.device)

@@ -94,7 +94,8 @@ class Pair:
         assert np.all(np.abs(N_gpu[amb]) <= 1.0 + 1e-6)
         N_new = st.last_N.copy()
         N_new[amb] = N_gpu[amb]
-        self.W_orc[i] = self.W_orc[i] + lr * st.Q @ (st.last_N - N_new)
+        weight = self.ohp.omega if self.ohp.qhm_mode == "full" else 1.0      # share of Q N in the update
+        self.W_orc[i] = self.W_orc[i] + lr * weight * st.Q @ (st.last_N - N_new)
         st.last_N = N_new
         return int(amb.sum())
 
@@ -111,6 +112,8 @@ class Pair:
             }
             if check_N:
                 errs["N"] = rel_l2(self.get(i, L.STATE_NUPD), st.last_N)
+            if self.ohp.error_feedback:
+                errs["E"] = rel_l2(self.get(i, L.STATE_ERR), st.E)
             for k, e in errs.items():
                 worst[k] = max(worst.get(k, 0.0), e)
                 assert e <= tol, f"matrix {i} {self.shapes[i]}: rel L2 error of {k} = {e:.3e} > {tol}"

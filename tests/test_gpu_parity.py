@@ -69,6 +69,49 @@ def test_local_steps_bf16_aligned_shapes(torch):
     print("aligned shapes: worst rel L2", worst, flush=True)
 
 
+ALIGNED_SHAPES = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (130, 264, 128), (520, 392, 256)]
+
+
+@pytest.mark.parametrize("variant", ["low_qhm", "full_qhm", "error_feedback", "lordo_global", "ef_fp32_grads"])
+def test_local_steps_qhm_and_error_feedback(torch, variant):
+    """The other two update cases of Alg. 1 and its error-feedback lines, and their combination
+    (full-rank QHM with error feedback is the configuration the paper calls LoRDO-Global)."""
+    from paper_2602_04396_amd import lordo
+    kw = {"low_qhm": dict(qhm_mode="low", omega=0.7), "full_qhm": dict(qhm_mode="full", omega=0.9),
+          "error_feedback": dict(error_feedback=True), "lordo_global": dict(qhm_mode="full", omega=0.95, error_feedback=True),
+          "ef_fp32_grads": dict(error_feedback=True, qhm_mode="low", omega=0.5)}[variant]
+    mode = {"none": 0, "low": 1, "full": 2}[kw.get("qhm_mode", "none")]
+    bf16 = variant != "ef_fp32_grads"
+    shapes = ALIGNED_SHAPES
+    pair = Pair(torch, shapes, _weights(shapes, 15), orc.Hyper(**kw),
+                lordo.hparams(qhm_mode=mode, omega=kw.get("omega", 1.0), error_feedback=kw.get("error_feedback", False),
+                              grad_dtype=lordo.BF16 if bf16 else lordo.F32), _rand_Q(shapes, 15))
+    gens = _spiked(shapes, 15, 8, bf16=bf16)
+    for t in range(4):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3 * (1 + t), grad_scale=0.8 if t == 2 else 1.0, bf16=bf16,
+                        first_step_patch=(t == 0))
+        worst = pair.compare_local(TOL)
+    print(f"{variant}: worst rel L2 {worst}", flush=True)
+    if kw.get("error_feedback"):
+        # the residual is orthogonal to the subspace (Alg. 1: E = A - Q Q^T A)
+        for i, (p, q, r) in enumerate(shapes):
+            E = pair.get(i, lordo.STATE_ERR)
+            Q = pair.get(i, lordo.STATE_Q)
+            assert np.linalg.norm(Q.T @ E) <= 1e-4 * np.linalg.norm(E)
+
+
+def test_qhm_full_rejects_unaligned(torch):
+    from paper_2602_04396_amd import lordo
+    import torch as t
+    shapes = [(64, 70, 16)]                                   # q % 4 != 0
+    W = [t.zeros(64, 70, device="cuda")]
+    G = [t.zeros(64, 70, device="cuda", dtype=t.bfloat16)]
+    opt = lordo.Lordo(shapes, lordo.hparams(qhm_mode=2, omega=0.9), W, t)
+    with pytest.raises(lordo.LordoError) as e:
+        opt.local_step(W, G, 1e-3)
+    assert e.value.code == lordo.EINVAL
+
+
 def test_local_steps_identity_init_and_grad_scale(torch):
     """Q_0 = first r columns of I (the library's own initial state), grad_scale != 1."""
     from paper_2602_04396_amd import lordo
@@ -301,6 +344,9 @@ def test_state_roundtrip_and_errors(torch):
         lordo.Lordo([(8, 8, 9)], lordo.hparams(), [torch.zeros(8, 8, device="cuda")], torch)
     assert e.value.code == lordo.EINVAL
     with pytest.raises(lordo.LordoError) as e:
-        lordo.Lordo([(8, 8, 4)], lordo.hparams(qhm_mode=2), [torch.zeros(8, 8, device="cuda")], torch)
+        lordo.Lordo([(8, 8, 4)], lordo.hparams(qhm_mode=3), [torch.zeros(8, 8, device="cuda")], torch)
     assert e.value.code == lordo.EINVAL
+    with pytest.raises(lordo.LordoError) as e:                # no residual without error feedback
+        opt.get_state(0, lordo.STATE_ERR)
+    assert e.value.code == lordo.ESTATE
     opt.poll_status()
