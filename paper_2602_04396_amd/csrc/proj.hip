@@ -836,6 +836,32 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int j = 0; j < 4; ++j) wv[a][b][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff[b], w_soff(a, b, j), STREAM);
+  // gradient term (WITH_G): four consecutive columns per lane, same rows as the W accesses; a bf16 G tile is
+  // requested here, with the W tile, so that it arrives during the contraction
+  const uint32_t ges = ua.g_is_f32 ? 4u : 2u;
+  const uint32_t grow_bytes = (uint32_t)q * ges;
+  const rsrc_t rg = WITH_G ? make_rsrc(ext_ptr(d, EXT_G, t.mat), (uint32_t)p * grow_bytes) : rw;
+  auto g_soff = [&](int a, int b, int j) -> uint32_t {
+    const int row = 32 * (mb0 + a) + 8 * j;
+    return row < p ? (uint32_t)row * grow_bytes + (uint32_t)(32 * (nb0 + b)) * ges : (uint32_t)p * grow_bytes;
+  };
+  uint32_t gvoff[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    int col = 32 * (nb0 + b) + 4 * c4;
+    gvoff[b] = col < q ? (uint32_t)rr * grow_bytes + (uint32_t)c4 * 4u * ges : OOB;
+  }
+  u32x2 gpre[WITH_G ? AM : 1][2][4];
+  if constexpr (WITH_G) {
+    if (!ua.g_is_f32) {
+#pragma unroll
+      for (int a = 0; a < AM; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) gpre[a][b][j] = __builtin_amdgcn_raw_buffer_load_b64(rg, gvoff[b], g_soff(a, b, j), STREAM);
+    }
+  }
   ISSUE_FENCE();
 
   f32x16 acc[AM][2];
@@ -878,13 +904,8 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   __syncthreads();                // all waves are done reading fragments: reuse the memory for staging
 
   if (mb0 >= mblocks || nb0 >= nblocks) return;
-  // gradient term: four consecutive columns per lane, same rows as the W accesses
-  const uint32_t ges = ua.g_is_f32 ? 4u : 2u;
-  const uint32_t grow_bytes = (uint32_t)q * ges;
-  rsrc_t rg = rw;
   f32x4 cscale[2] = {{1.f, 1.f, 1.f, 1.f}, {1.f, 1.f, 1.f, 1.f}};
   if constexpr (WITH_G) {
-    rg = make_rsrc(ext_ptr(d, EXT_G, t.mat), (uint32_t)p * grow_bytes);
     if (ua.colscale) {
       const GAS float* cp = TO_GLOBAL(const float, ua.colpart) + m.lr_off / 32;
       const int rblocks = m.rp / 32;
@@ -902,16 +923,12 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     }
   }
   auto g_term = [&](int a, int b, int j) -> f32x4 {
-    const int row = 32 * (mb0 + a) + 8 * j;
-    const uint32_t soff = row < p ? (uint32_t)row * grow_bytes + (uint32_t)(32 * (nb0 + b)) * ges : (uint32_t)p * grow_bytes;
-    const int col = 32 * (nb0 + b) + 4 * c4;
-    const uint32_t vo = col < q ? (uint32_t)rr * grow_bytes + (uint32_t)c4 * 4u * ges : OOB;
     f32x4 gv;
     if (ua.g_is_f32) {
-      u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rg, vo, soff, 0);
+      u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rg, gvoff[b], g_soff(a, b, j), STREAM);
       gv.x = __uint_as_float(w.x); gv.y = __uint_as_float(w.y); gv.z = __uint_as_float(w.z); gv.w = __uint_as_float(w.w);
     } else {
-      u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rg, vo, soff, 0);
+      const u32x2 w = gpre[WITH_G ? a : 0][b][j];
       gv.x = __uint_as_float(w.x << 16); gv.y = __uint_as_float(w.x & 0xffff0000u);
       gv.z = __uint_as_float(w.y << 16); gv.w = __uint_as_float(w.y & 0xffff0000u);
     }
