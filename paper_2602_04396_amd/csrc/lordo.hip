@@ -44,7 +44,8 @@ struct Plan {
   int64_t nchunks = 0;
   int mb = 4;
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
-  int down_pipe = 0;                // waves of the pipelined down-projection (8: 256-column tiles, 4: 128-column; 0: plain kernel)
+  int down_pipe = 0;                // pipelined down-projection: rank blocks per wave (1: 128-rank tiles, 2: 256-rank), 0: plain kernel
+  int rank_tile = 128;              // rank indices per down-projection tile
   bool g_once = true;               // every matrix has one rank tile of the down-projection: G is read exactly once
   int64_t colpart = -1, g_hi = -1, g_lo = -1;   // full-rank QHM column sums; error-feedback planes of g
   int64_t adam_first = 0;           // flat position from which the stand-alone Adam kernel runs (elements before it are fused)
@@ -360,9 +361,10 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.mb = (hp.grad_dtype == LORDO_BF16 || rp_max > 64) ? 4 : (rp_max > 32 ? 2 : 1);
   // Down-projection launch shape: the pipelined kernel (rank tiles of 128, bf16 G, 256-column
   // tiles) where it applies, else the plain kernel with 128-column tiles.
-  P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16 && !hp.error_feedback) ? 8 : 0;
-  P.g_once = rp_max <= 32 * P.mb;
-  const int down_bn = P.down_pipe == 8 ? 256 : 128;
+  P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16 && !hp.error_feedback) ? (rp_max >= 256 ? 2 : 1) : 0;
+  P.rank_tile = P.down_pipe ? 128 * P.down_pipe : 32 * P.mb;
+  P.g_once = rp_max <= P.rank_tile;
+  const int down_bn = P.down_pipe ? 256 : 128;
   P.up_waves = 4;
 
   // Split-K of the down-projection.  With few output tiles (small models) the long contraction
@@ -371,7 +373,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the Adam kernel.  Factors are powers of two up to 8.
   int64_t tiles0 = 0;
   for (int i = 0; i < n; ++i)
-    tiles0 += (int64_t)((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + 32 * P.mb - 1) / (32 * P.mb));
+    tiles0 += (int64_t)((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + P.rank_tile - 1) / P.rank_tile);
   P.splits.assign(n, 1);
   P.nsplit = 1;
   if (tiles0 < 1536) {
@@ -389,7 +391,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
         if (f < 8 && P.mat[i].pp / (2 * f) >= 256) can_grow = true;
         P.splits[i] = f;
         P.nsplit = std::max(P.nsplit, f);
-        tiles += (int64_t)f * ((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + 32 * P.mb - 1) / (32 * P.mb));
+        tiles += (int64_t)f * ((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + P.rank_tile - 1) / P.rank_tile);
       }
       if (tiles >= 400 || !can_grow || chunk <= 256) break;
       chunk = std::max(256, chunk / 2);
@@ -452,7 +454,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     const int f = P.splits[i];
     const int klen = ((m.pp + f - 1) / f + 31) / 32 * 32;
     for (int n0 = 0; n0 < m.qp; n0 += down_bn)
-      for (int m0 = 0; m0 < m.rp; m0 += 32 * P.mb)
+      for (int m0 = 0; m0 < m.rp; m0 += P.rank_tile)
         for (int sp = 0; sp < f; ++sp) {
           ProjTile t{};
           t.mat = i; t.m0 = m0; t.n0 = n0; t.split = sp;

@@ -372,32 +372,43 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
   *TO_GLOBAL(u32x2, f.n_lo + at) = pl;
 }
 
-// NW = 8: 256-column tiles (wave w: rank block w % 4, column half w / 4); NW = 4: 128-column tiles.
+// 8 waves, 256-column tiles: wave w owns column half w / 4 (four column blocks) and RB rank blocks,
+// w % 4 + 4*rb: the tile spans 128*RB rank indices.  RB = 2 (ranks from 256 up) halves the number of
+// passes over G and the LDS reads per MFMA (each G fragment feeds two rank blocks); its 96 KiB of
+// LDS admit one workgroup per compute unit.
 // VEC: every G row is read with aligned 4-byte accesses (8 loads per stage, else 16).
+// GONCE: one rank tile per column block, G is read once (streaming loads).
 // A tile marked `fuse` holds the whole contraction (no split-K): its epilogue applies Adam to its
 // elements of the low-rank state instead of leaving that to a separate pass over g.
-template <int NW, bool VEC, bool GONCE>     // GONCE: one rank tile per column block, G is read once (streaming loads)
-__global__ __launch_bounds__(64 * NW) void k_proj_down_pipe(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
-                                                            int64_t split_stride, float grad_scale, FusedAdam fa) {
+template <int RB, bool VEC, bool GONCE>
+__global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
+                                                        int64_t split_stride, float grad_scale, FusedAdam fa) {
   constexpr int BK = 32;
-  constexpr int NH = NW / 4;                                   // column halves of 128
+  constexpr int NW = 8;
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
   const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
 
-  constexpr int GSLOTS = 4 * NH * 4 * 32;                      // (nblk, kgrp, n) 16-byte slots of one stage
-  constexpr int ASLOTS = 4 * 2 * 2 * 64;                       // (mblk, kstep, plane, lane)
-  __shared__ u32x4 gfrag[2 * GSLOTS];                          // 16 KiB per 128 columns
-  __shared__ u32x4 afrag[2 * ASLOTS];                          // 32 KiB
+  constexpr int GSLOTS = 8 * 4 * 32;                           // (nblk, kgrp, n) 16-byte slots of one stage: 16 KiB
+  constexpr int ASLOTS = 4 * RB * 2 * 2 * 64;                  // (mblk, kstep, plane, lane): 16 KiB per 128 rank indices
+  extern __shared__ u32x4 lds_dyn[];                           // 2 stages of each: 64 KiB (RB = 1) or 96 KiB (RB = 2)
+  u32x4* gfrag = lds_dyn;
+  u32x4* afrag = lds_dyn + 2 * GSLOTS;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mb = wave & 3, nh = wave >> 2;                     // compute role
-  const int kgrp = wave / NH, half = wave % NH;                // G staging role: 8-row group, column half
-  const int mbg = t.m0 / 32 + mb;
-  const bool active = mbg < m.rp / 32;
+  const int kgrp = wave >> 1, half = wave & 1;                 // G staging role: 8-row group, column half
+  const int rblocks = m.rp / 32;
+  int mbg[RB];
+  bool active[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    mbg[rb] = t.m0 / 32 + mb + 4 * rb;
+    active[rb] = mbg[rb] < rblocks;
+  }
 
   const int klim = t.k1 < m.p ? t.k1 : m.p;
   const void* Gbase = ext_ptr(d, EXT_G, t.mat);
@@ -410,15 +421,13 @@ __global__ __launch_bounds__(64 * NW) void k_proj_down_pipe(DevCtx d, const Proj
   gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 2u : OOB;
   const int wslot = ((4 * half + (lane >> 4)) * 4 + kgrp) * 32 + 2 * (lane & 15);
 
-  // Q fragments of a stage: f = (mblk*2 + kstep)*2 + plane, 16 of them; a wave brings in 16 / NW
-  // (mblk, kstep) pairs, both planes each
+  // Q fragments of a stage: (mblk, kstep) pairs, both planes each; 8*RB pairs, RB per wave
   const int64_t kgroups = m.pp / 8;
   const int kgmax = (int)kgroups - 2;
-  const int rblocks = m.rp / 32;
   auto issue_a = [&](int kr, int sbuf) {
 #pragma unroll
-    for (int j = 0; j < 8 / NW; ++j) {
-      const int pair = wave * (8 / NW) + j;                    // 0..7
+    for (int j = 0; j < RB; ++j) {
+      const int pair = wave * RB + j;                          // 0 .. 8*RB-1
       const int fmb = pair >> 1, fks = pair & 1;
       const int fmbg = t.m0 / 32 + fmb < rblocks ? t.m0 / 32 + fmb : rblocks - 1;
       int kg = kr / 8 + 2 * fks;
@@ -430,25 +439,54 @@ __global__ __launch_bounds__(64 * NW) void k_proj_down_pipe(DevCtx d, const Proj
     }
   };
 
-  f32x16 acc[4];
+  f32x16 acc[RB][4];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][a][i] = 0.f;
 
-  auto compute = [&](int sbuf) {
-    if (!active) return;
+  // Operand fragments of one k-step of 16: RB pairs of Q planes and the four G column blocks.
+  struct Frags { u32x4 ah[RB], al[RB], b[4]; };
+  auto load_frags = [&](Frags& f, int sbuf, int ks) {
     const u32x4* gb = gfrag + sbuf * GSLOTS;
-    const u32x4* ab = afrag + sbuf * ASLOTS + mb * 4 * 64;
+    const u32x4* ab = afrag + sbuf * ASLOTS;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 a_hi = as_bf(ab[(ks * 2 + 0) * 64 + lane]);
-      bf16x8 a_lo = as_bf(ab[(ks * 2 + 1) * 64 + lane]);
+    for (int rb = 0; rb < RB; ++rb) {
+      f.ah[rb] = ab[(((mb + 4 * rb) * 2 + ks) * 2 + 0) * 64 + lane];
+      f.al[rb] = ab[(((mb + 4 * rb) * 2 + ks) * 2 + 1) * 64 + lane];
+    }
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        bf16x8 b = as_bf(gb[((4 * nh + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31)]);
-        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, b, acc[a], 0, 0, 0);
-        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, b, acc[a], 0, 0, 0);
+    for (int a = 0; a < 4; ++a) f.b[a] = gb[((4 * nh + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31)];
+  };
+  auto mfma_frags = [&](const Frags& f) {
+    // an absent second rank block (rank not a multiple of 256) is multiplied anyway: its Q fragments
+    // repeat the last block and its accumulators are never stored; no branch splits the MFMA run
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        acc[rb][a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ah[rb]), as_bf(f.b[a]), acc[rb][a], 0, 0, 0);
+        acc[rb][a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.al[rb]), as_bf(f.b[a]), acc[rb][a], 0, 0, 0);
+      }
+  };
+  auto compute = [&](int sbuf) {
+    if (!active[0]) return;                                    // rank blocks are filled from the lowest: nothing to do
+    if constexpr (RB == 2) {
+      // both k-steps' fragments are requested before the first MFMA: the second set lands while the
+      // sixteen MFMAs of the first run
+      Frags f0, f1;
+      load_frags(f0, sbuf, 0);
+      load_frags(f1, sbuf, 1);
+      mfma_frags(f0);
+      mfma_frags(f1);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        Frags f;
+        load_frags(f, sbuf, ks);
+        mfma_frags(f);
       }
     }
   };
@@ -470,7 +508,7 @@ __global__ __launch_bounds__(64 * NW) void k_proj_down_pipe(DevCtx d, const Proj
   {                                                                                               \
     const int kr = t.k0 + (S) * BK;                                                               \
     if ((S) + 1 < nstages) issue_a(kr + BK, ((S) + 1) & 1);                                       \
-    load_gstage<false, GONCE ? STREAM : 0>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc);                    \
+    load_gstage<false, GONCE ? STREAM : 0>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc); \
     ISSUE_FENCE();                                                                                \
     compute((S) & 1);                                                                             \
     ISSUE_FENCE();                                                                                \
@@ -488,70 +526,89 @@ __global__ __launch_bounds__(64 * NW) void k_proj_down_pipe(DevCtx d, const Proj
   if (s < nstages) LORDO_DOWN_ITER(s, st1, st0)
 #undef LORDO_DOWN_ITER
 
-  if (!active) return;
   const int64_t base = m.lr_off;
   GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + base;
-  const bool fuse = t.fuse != 0;                                // uniform over the workgroup
+  const bool fuse = t.fuse != 0 && fa.u != nullptr;            // uniform over the workgroup
   const int64_t rgroups = m.rp / 8;
-  // offset of the lane's four consecutive rank indices of column block nbg, rank group 4*mbg + vq
-  auto offset_of = [&](int nbg, int vq) {
-    return (((int64_t)nbg * rgroups + 4 * mbg + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
-  };
-  if (!fuse) {
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    if (!active[rb]) continue;
+    // offset of the lane's four consecutive rank indices of column block nbg, rank group 4*mbg + vq
+    auto offset_of = [&](int nbg, int vq) {
+      return (((int64_t)nbg * rgroups + 4 * mbg[rb] + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+    };
+    if (!fuse) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int nbg = t.n0 / 32 + 4 * nh + a;
+        if (nbg >= m.qp / 32) continue;
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          f32x4 val;
+          val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
+          val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
+          *reinterpret_cast<GAS f32x4*>(out + offset_of(nbg, vq)) = val;
+        }
+      }
+      continue;
+    }
+    // fused Adam: the moments of a whole column block are requested before any of them is used
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       const int nbg = t.n0 / 32 + 4 * nh + a;
       if (nbg >= m.qp / 32) continue;
+      f32x4 uu[4], vv[4];
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        f32x4 val;
-        val.x = grad_scale * acc[a][4 * vq];     val.y = grad_scale * acc[a][4 * vq + 1];
-        val.z = grad_scale * acc[a][4 * vq + 2]; val.w = grad_scale * acc[a][4 * vq + 3];
-        *reinterpret_cast<GAS f32x4*>(out + offset_of(nbg, vq)) = val;
+        const int64_t at = base + offset_of(nbg, vq);
+        uu[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.u + at));
+        vv[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
       }
-    }
-    return;
-  }
-  // fused Adam: the moments of a whole column block are requested before any of them is used
+      ISSUE_FENCE();
 #pragma unroll
-  for (int a = 0; a < 4; ++a) {
-    const int nbg = t.n0 / 32 + 4 * nh + a;
-    if (nbg >= m.qp / 32) continue;
-    f32x4 uu[4], vv[4];
-#pragma unroll
-    for (int vq = 0; vq < 4; ++vq) {
-      const int64_t at = base + offset_of(nbg, vq);
-      uu[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.u + at));
-      vv[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
-    }
-    ISSUE_FENCE();
-#pragma unroll
-    for (int vq = 0; vq < 4; ++vq) {
-      const int64_t o = offset_of(nbg, vq);
-      f32x4 val;
-      val.x = grad_scale * acc[a][4 * vq];     val.y = grad_scale * acc[a][4 * vq + 1];
-      val.z = grad_scale * acc[a][4 * vq + 2]; val.w = grad_scale * acc[a][4 * vq + 3];
-      *reinterpret_cast<GAS f32x4*>(out + o) = val;
-      adam4(fa, base + o, val, uu[vq], vv[vq]);
+      for (int vq = 0; vq < 4; ++vq) {
+        const int64_t o = offset_of(nbg, vq);
+        f32x4 val;
+        val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
+        val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
+        *reinterpret_cast<GAS f32x4*>(out + o) = val;
+        adam4(fa, base + o, val, uu[vq], vv[vq]);
+      }
     }
   }
 }
 
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_waves, bool g_vec, bool g_once, float* glow,
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_rb, bool g_vec, bool g_once, float* glow,
                             int64_t split_stride, float grad_scale, bool g_is_f32, bool ef, const DownFuse* fuse, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
-  if (pipe_waves) {
+  if (pipe_rb) {       // pipelined kernel: 128 * pipe_rb rank indices per tile
     FusedAdam fa{};
     if (fuse) {
       fa.u = fuse->u; fa.v = fuse->v; fa.n_hi = fuse->n_hi; fa.n_lo = fuse->n_lo;
       fa.b1 = fuse->a.b1; fa.omb1 = fuse->a.omb1; fa.b2 = fuse->a.b2; fa.omb2 = fuse->a.omb2;
       fa.inv_c1 = fuse->a.inv_c1; fa.inv_c2 = fuse->a.inv_c2; fa.eps = fuse->a.eps;
     }
-#define LORDO_PIPE(VECV, ONCEV)                                                                                   \
-  hipLaunchKernelGGL((k_proj_down_pipe<8, VECV, ONCEV>), grid, dim3(512), 0, s, d, tiles, glow, split_stride, grad_scale, fa)
-    if (g_once) { if (g_vec) LORDO_PIPE(true, true); else LORDO_PIPE(false, true); }
-    else { if (g_vec) LORDO_PIPE(true, false); else LORDO_PIPE(false, false); }
+    // dynamic LDS: 64 KiB for 128-rank tiles, 96 KiB for 256-rank tiles (raised above the default limit once)
+    static bool lds_raised = false;
+    if (!lds_raised) {
+      const void* big[4] = {reinterpret_cast<const void*>(k_proj_down_pipe<2, true, true>), reinterpret_cast<const void*>(k_proj_down_pipe<2, true, false>),
+                            reinterpret_cast<const void*>(k_proj_down_pipe<2, false, true>), reinterpret_cast<const void*>(k_proj_down_pipe<2, false, false>)};
+      for (const void* f : big) {
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 98304);
+        if (e != hipSuccess) return e;
+      }
+      lds_raised = true;
+    }
+#define LORDO_PIPE(RBV, VECV, ONCEV)                                                                              \
+  hipLaunchKernelGGL((k_proj_down_pipe<RBV, VECV, ONCEV>), grid, dim3(512), (RBV == 2 ? 98304 : 65536), s, d, tiles, glow, split_stride, grad_scale, fa)
+    if (pipe_rb == 2) {
+      if (g_once) { if (g_vec) LORDO_PIPE(2, true, true); else LORDO_PIPE(2, false, true); }
+      else { if (g_vec) LORDO_PIPE(2, true, false); else LORDO_PIPE(2, false, false); }
+    } else {
+      if (g_once) { if (g_vec) LORDO_PIPE(1, true, true); else LORDO_PIPE(1, false, true); }
+      else { if (g_vec) LORDO_PIPE(1, true, false); else LORDO_PIPE(1, false, false); }
+    }
 #undef LORDO_PIPE
     return hipGetLastError();
   }
