@@ -145,6 +145,12 @@ int lordo_set_step(lordo_ctx* ctx, int64_t t);
  * last poll (the latch is cleared), else LORDO_OK. */
 int lordo_poll_status(lordo_ctx* ctx, void* stream);
 
+/* Similarity of consecutive subspaces (Sec. 5.1, Metrics): for every matrix the mean squared singular
+ * value of R = Q_new^T Q_old of the last lordo_refresh_subspace, (1/r) sum sigma_i^2 = ||R||_F^2 / r
+ * (1: same subspace, 0: orthogonal).  dev_out: device array of n floats.  LORDO_ESTATE before the
+ * first refresh. */
+int lordo_get_mssv(lordo_ctx* ctx, float* dev_out, void* stream);
+
 /* Measurement aid: with profiling on, every kernel class below is bracketed by a pair of HIP events
  * on the caller's stream (a few microseconds of overhead per launch).  lordo_profile_read
  * synchronises `stream` and returns the summed event time and the number of spans of one class

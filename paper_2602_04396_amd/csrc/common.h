@@ -154,6 +154,7 @@ hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int6
 hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
 // refresh helpers (grouped over all matrices)
 hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s);
+hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
 hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
 hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);

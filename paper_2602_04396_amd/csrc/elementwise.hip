@@ -375,6 +375,27 @@ __global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef) {
   float shift = coef * red[0];
   for (int i = threadIdx.x; i < m.r; i += 256) S[(int64_t)i * m.r + i] += shift;
 }
+// Mean squared singular value of R = Q_new^T Q_old of the last refresh (Sec. 5.1, Metrics):
+// (1/r) sum_i sigma_i^2 = ||R||_F^2 / r, from the elementwise square the rotation already keeps.
+__global__ __launch_bounds__(256) void k_mssv(DevCtx d, float* __restrict__ out) {
+  const MatDev& m = d.mats[blockIdx.x];
+  const float* R2 = reinterpret_cast<const float*>(d.arena + m.rot2);
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < m.r * m.r; i += 256) acc += R2[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = red[0] / (float)m.r;
+}
+hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(k_mssv, dim3(d.n), dim3(256), 0, s, d, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s) {
   hipLaunchKernelGGL(k_gram_shift, dim3(d.n), dim3(256), 0, s, d, coef);
   return hipGetLastError();

@@ -299,7 +299,7 @@ struct ProgramBuilder {
       g.C = ref_arena(m.rot); g.C2 = ref_arena(m.rot2); g.ldc = m.r;
       g.M = m.r; g.N = m.r; g.K = m.p;
       return true;
-    }, true, true);
+    }, false, true);          // always: the similarity diagnostic (Sec. 5.1, MSSV) reads R o R even when nothing is rotated
     simple(OP_ROT_PRE, 0, 0.f, true);
     for (int which = 0; which < 2; ++which)
       gemm([&](int i, GemmDesc& g) {
@@ -525,6 +525,7 @@ struct lordo_ctx {
   Plan plan;
   DevCtx dev{};
   int64_t t = 0;
+  bool refreshed = false;        // a subspace refresh has run: R = Q_new^T Q_old of the last one is in the arena
   int device = 0;
   // cached caller pointer tables: EXT_SLOTS per kind, replaced round-robin
   std::vector<void*> shadow[EXT_COUNT][EXT_SLOTS];
@@ -746,6 +747,7 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
     }
   }
   c->prof.end(LORDO_K_REFRESH, s);
+  c->refreshed = true;
   return LORDO_OK;
 }
 
@@ -837,6 +839,13 @@ int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_sr
     case LORDO_STATE_V: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.v), src, s)); break;
     default: return LORDO_EINVAL;
   }
+  return LORDO_OK;
+}
+
+int lordo_get_mssv(lordo_ctx* c, float* dev_out, void* stream) {
+  if (!c || !dev_out) return LORDO_EINVAL;
+  if (!c->refreshed) return LORDO_ESTATE;
+  HIPCHK(launch_mssv(c->dev, dev_out, reinterpret_cast<hipStream_t>(stream)));
   return LORDO_OK;
 }
 

@@ -20,7 +20,7 @@ EXPORTS = [
     "lordo_workspace_bytes", "lordo_init", "lordo_local_step", "lordo_refresh_subspace",
     "lordo_export_pseudograd", "lordo_outer_step", "lordo_get_state", "lordo_set_state",
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
-    "lordo_profile_enable", "lordo_profile_read",
+    "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv",
 ]
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
@@ -74,6 +74,7 @@ def load() -> C.CDLL:
     lib.lordo_outer_step.argtypes = [vp, vpp, vpp, vp]
     lib.lordo_get_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_set_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
+    lib.lordo_get_mssv.argtypes = [vp, vp, vp]
     lib.lordo_get_step.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.lordo_set_step.argtypes = [vp, C.c_int64]
     lib.lordo_poll_status.argtypes = [vp, vp]
@@ -211,6 +212,12 @@ class Lordo:
         if tuple(src.shape) != want or src.dtype != self.torch.float32 or not src.is_contiguous() or not src.is_cuda:
             raise ValueError(f"expected contiguous CUDA float32 tensor of shape {want}")
         _check(self.lib.lordo_set_state(self.ctx, mat, which, C.c_void_p(src.data_ptr()), self._stream()))
+
+    def mssv(self):
+        """Per matrix: mean squared singular value of Q_new^T Q_old of the last refresh (tensor of n floats)."""
+        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.arena.device)
+        _check(self.lib.lordo_get_mssv(self.ctx, C.c_void_p(out.data_ptr()), self._stream()))
+        return out
 
     @property
     def step(self):

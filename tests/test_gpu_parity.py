@@ -229,7 +229,15 @@ def test_refresh_rotates_moments(torch):
         Src = [g.draw(100) for g in gens]
         Om = [synth.omega(np.random.default_rng(synth.seed_for(20, 900 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
         Qu_before = [pair.st[i].Q @ pair.st[i].u for i in range(len(shapes))]
+        Q_old = [pair.st[i].Q.copy() for i in range(len(shapes))]
+        with pytest.raises(lordo.LordoError):                 # no refresh yet: nothing to report
+            pair.opt.mssv()
         dists, orths = pair.refresh(Src, Om, bf16=bf16)
+        # similarity diagnostic (Sec. 5.1): basis-free, so the oracle's own new basis serves
+        mssv_gpu = pair.opt.mssv().cpu().numpy()
+        for i, (p, q, r) in enumerate(shapes):
+            Qo = orc.range_finder(np.asarray(Src[i], dtype=np.float64), np.asarray(Om[i], dtype=np.float64), power_iters)
+            assert abs(mssv_gpu[i] - orc.mssv(Qo, Q_old[i])) <= 1e-4, f"MSSV of matrix {i}"
         print(f"refresh q_it={power_iters} bf16={bf16}: dist {np.round(dists, 6)} orth {np.round(orths, 7)}", flush=True)
         assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
         for i in range(len(shapes)):
