@@ -623,22 +623,13 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Up-projection with the weight update fused.  Workgroup tile 128 x 128 of W, 4 waves in a
+// Up-projection with the weight update fused, fallback for any q and any alignment of W (the main
+// path below needs q % 4 == 0 and 16-byte aligned W).  Workgroup tile 128 x 128 of W, 4 waves in a
 // 2 x 2 grid, each wave 64 x 64 = 2 x 2 accumulator blocks.  Operand fragments come straight from
 // the packed planes (one coalesced 1 KiB read per wave and fragment), double-buffered in registers;
-// the W tile is fetched through a buffer resource before the contraction so its latency hides
-// behind it.
-//
-// The vector-memory front end costs about 16 cycles per instruction whatever its width and one
-// tag look-up per cache line touched, so W is best moved with 16-byte accesses that cover whole
-// 128-byte lines.  VEC = true (q % 4 == 0, W 16-byte aligned): the matrix core computes the
-// transposed block (Q N)^T = N^T Q^T, which puts four consecutive COLUMNS of a row in a lane's
-// four consecutive accumulator registers; each 32 x 32 block then goes through a per-wave LDS
-// buffer (16-byte writes, 16-byte reads) into row order, where 8 lanes cover one 128-byte line of
-// a row, and is combined with the W values that were fetched in that same order.
-// VEC = false: plain orientation, one dword per access, any q and alignment.
+// the W tile is fetched through a buffer resource, one dword per access, before the contraction so
+// that its latency hides behind it.
 // ---------------------------------------------------------------------------------------
-template <bool VEC>
 __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __restrict__ tiles,
                                                  const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
   const ProjTile t = tiles[blockIdx.x];
@@ -649,9 +640,6 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   const GAS u32x4* nh = TO_GLOBAL(const u32x4, n_hi + m.lr_off);
   const GAS u32x4* nl = TO_GLOBAL(const u32x4, n_lo + m.lr_off);
 
-  constexpr int TP = 36;                                   // LDS pitch (floats) of the 32 x 32 staging block
-  __shared__ float stage[VEC ? 4 * 32 * TP : 1];
-
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps row offsets scalar
   const int mb0 = t.m0 / 32 + 2 * (wave & 1);
@@ -661,47 +649,30 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   const int p = m.p, q = m.q;
   const int64_t rgroups = m.rp / 8;
 
-  // W is a buffer of p*q floats: rows past p fall outside it (reads give 0, writes are dropped); a
-  // lane whose columns are outside the matrix gets an offset outside the buffer.  The lane supplies
-  // its part of the offset, the block / register part is scalar.
+  // W is a buffer of p*q floats: a lane whose column or row is outside the matrix gets an offset
+  // outside the buffer (reads give 0, writes are dropped).  Register v of block (a, b) is row
+  // 8*(v/4) + 4*(lane/32) + v%4, column lane%32: the lane supplies its part of the offset, the
+  // block / register part is scalar, and a row at or past p gets the size of the resource.
   const uint32_t row_bytes = (uint32_t)q * 4u;
   const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
-  // VEC: lane = (rr, c4): row rr + 8j of a block, columns 4*c4 .. 4*c4+3
-  // else: register v of block (a, b) is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
-  const int rr = lane >> 3, c4 = lane & 7;
   uint32_t voff[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
-    if constexpr (VEC) {
-      int col = 32 * (nb0 + b) + 4 * c4;
-      voff[b] = col < q ? (uint32_t)rr * row_bytes + (uint32_t)c4 * 16u : OOB;
-    } else {
-      int col = 32 * (nb0 + b) + (lane & 31);
-      voff[b] = col < q ? (uint32_t)(4 * (lane >> 5)) * row_bytes + (uint32_t)(lane & 31) * 4u : OOB;
-    }
+    int col = 32 * (nb0 + b) + (lane & 31);
+    voff[b] = col < q ? (uint32_t)(4 * (lane >> 5)) * row_bytes + (uint32_t)(lane & 31) * 4u : OOB;
   }
-  auto w_soff = [&](int a, int b, int v) -> uint32_t {      // v: register (scalar path) or 4*j (vector path, rows 8j)
-    int row = VEC ? 32 * (mb0 + a) + 8 * (v >> 2) : 32 * (mb0 + a) + 8 * (v >> 2) + (v & 3);
-    return (uint32_t)row * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u;
+  auto w_soff = [&](int a, int b, int v) -> uint32_t {
+    const int row = 32 * (mb0 + a) + 8 * (v >> 2) + (v & 3);
+    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u : (uint32_t)p * row_bytes;
   };
   float wv[2][2][16];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      if constexpr (VEC) {
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rw, voff[b], w_soff(a, b, 4 * j), STREAM);
-          wv[a][b][4 * j] = __uint_as_float(x.x); wv[a][b][4 * j + 1] = __uint_as_float(x.y);
-          wv[a][b][4 * j + 2] = __uint_as_float(x.z); wv[a][b][4 * j + 3] = __uint_as_float(x.w);
-        }
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], w_soff(a, b, v), STREAM));
-      }
-    }
+      for (int v = 0; v < 16; ++v)
+        wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], w_soff(a, b, v), STREAM));
   ISSUE_FENCE();
 
   f32x16 acc[2][2];
@@ -742,15 +713,9 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        if constexpr (VEC) {         // transposed block: N fragment first
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.nh[b]), as_bf(f.qh[a]), acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.nl[b]), as_bf(f.qh[a]), acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.nh[b]), as_bf(f.ql[a]), acc[a][b], 0, 0, 0);
-        } else {
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.qh[a]), as_bf(f.nh[b]), acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.qh[a]), as_bf(f.nl[b]), acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ql[a]), as_bf(f.nh[b]), acc[a][b], 0, 0, 0);
-        }
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.qh[a]), as_bf(f.nh[b]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.qh[a]), as_bf(f.nl[b]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ql[a]), as_bf(f.nh[b]), acc[a][b], 0, 0, 0);
       }
   };
   Frags f0, f1;
@@ -764,53 +729,32 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
     compute(f1);
   }
   ISSUE_FENCE();
-
-  if constexpr (VEC) {
-    // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e
-    float* T = stage + wave * 32 * TP;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
+    for (int v = 0; v < 16; ++v)
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          f32x4 x;
-          x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
-          *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
-        }
-        // LDS operations of one wave complete in order: the reads below see the writes above
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
-          u32x4 o;
-          o.x = __float_as_uint(fmaf(-lr, x.x, wv[a][b][4 * j]));
-          o.y = __float_as_uint(fmaf(-lr, x.y, wv[a][b][4 * j + 1]));
-          o.z = __float_as_uint(fmaf(-lr, x.z, wv[a][b][4 * j + 2]));
-          o.w = __float_as_uint(fmaf(-lr, x.w, wv[a][b][4 * j + 3]));
-          __builtin_amdgcn_raw_buffer_store_b128(o, rw, voff[b], w_soff(a, b, 4 * j), STREAM);
-        }
-      }
-  } else {
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(fmaf(-lr, acc[a][b][v], wv[a][b][v])), rw, voff[b],
-                                                w_soff(a, b, v), STREAM);
-  }
+      for (int b = 0; b < 2; ++b)
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(fmaf(-lr, acc[a][b][v], wv[a][b][v])), rw, voff[b],
+                                              w_soff(a, b, v), STREAM);
 }
 
 // ---------------------------------------------------------------------------------------
-// Up-projection, main path (q % 4 == 0, W 16-byte aligned).  Same tile and wave layout, transposed
-// accumulators and LDS-transposed epilogue as k_proj_up<true>, but the operand fragments are
-// brought in ONCE per workgroup by direct global-to-LDS loads (each 1 KiB fragment is one
-// 16-byte-per-lane load that lands in lane order, so no registers and no transposition are
-// involved) and every wave then reads its fragments from LDS.  This halves the bytes that pass
-// through the vector L1 (each fragment is needed by two of the four waves), which is what bounds
-// the register-fed variant.  Chunks of 32 of the contraction (2 MFMA k-steps, 32 KiB of
-// fragments) are double-buffered; one barrier per chunk.
+// Up-projection, main path (q % 4 == 0, W 16-byte aligned).  Same tile and wave layout as the
+// fallback above.
+// W access.  The vector-memory front end costs about 16 cycles per instruction whatever its width
+// and one tag look-up per cache line touched, so W is moved with 16-byte accesses that cover whole
+// 128-byte lines: the matrix core computes the transposed block (Q N)^T = N^T Q^T, which puts four
+// consecutive COLUMNS of a row in a lane's four consecutive accumulator registers; each 32 x 32
+// block then goes through a per-wave LDS buffer (16-byte writes, 16-byte reads) into row order,
+// where 8 lanes cover one 128-byte line of a row, and is combined with the W values that were
+// fetched in that same order.
+// Operands.  The fragments are brought in ONCE per workgroup by direct global-to-LDS loads (each
+// 1 KiB fragment is one 16-byte-per-lane load that lands in lane order, so no registers and no
+// transposition are involved) and every wave then reads its fragments from LDS.  This halves the
+// bytes that pass through the vector L1 (each fragment is needed by two of the four waves), which
+// is what bounds a register-fed variant.  Chunks of 32 of the contraction (2 MFMA k-steps, 32 KiB
+// of fragments) are double-buffered; one barrier per chunk.
 // ---------------------------------------------------------------------------------------
 
 // WITH_G adds a gradient term to the epilogue: target <- target + coef_acc * (Q B) + coef_g * G * c_j, with
@@ -1037,7 +981,7 @@ hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bo
   } else if (vec) {
     hipLaunchKernelGGL((k_proj_up_dma<4, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else {
-    hipLaunchKernelGGL((k_proj_up<false>), grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc);
+    hipLaunchKernelGGL(k_proj_up, grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc);
   }
   return hipGetLastError();
 }

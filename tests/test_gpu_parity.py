@@ -112,6 +112,29 @@ def test_qhm_full_rejects_unaligned(torch):
     assert e.value.code == lordo.EINVAL
 
 
+def test_local_steps_degenerate_shapes(torch):
+    """Smallest and most lopsided matrices: a single element, a single column, r = p, r > q, one row block."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(1, 1, 1), (2, 8, 2), (33, 1, 5), (5, 12, 5), (40, 4, 40), (31, 257, 31)]
+    for bf16 in (True, False):
+        pair = Pair(torch, shapes, _weights(shapes, 16), orc.Hyper(),
+                    lordo.hparams(grad_dtype=lordo.BF16 if bf16 else lordo.F32), _rand_Q(shapes, 16))
+        rng = np.random.default_rng(synth.seed_for(16, 1 if bf16 else 2))
+        for t in range(3):
+            G = [(1e-3 * rng.standard_normal((p, q))).astype(np.float32) for p, q, r in shapes]
+            if bf16:
+                G = [synth.bf16_round(g) for g in G]
+            pair.local_step(G, lr=1e-3, bf16=bf16, first_step_patch=(t == 0))
+        pair.compare_local(TOL)
+
+
+def test_empty_and_invalid_sets(torch):
+    from paper_2602_04396_amd import lordo
+    with pytest.raises(lordo.LordoError) as e:
+        lordo.workspace_bytes([], lordo.hparams())
+    assert e.value.code == lordo.EINVAL
+
+
 def test_local_steps_identity_init_and_grad_scale(torch):
     """Q_0 = first r columns of I (the library's own initial state), grad_scale != 1."""
     from paper_2602_04396_amd import lordo
