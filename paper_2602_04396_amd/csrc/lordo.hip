@@ -462,12 +462,18 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
           t.fuse = (P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0) ? 1 : 0;
           down.push_back(t);
         }
-    for (int m0 = 0; m0 < m.pp; m0 += 128)
-      for (int n0 = 0; n0 < m.qp; n0 += 128) {
-        ProjTile t{};
-        t.mat = i; t.m0 = m0; t.n0 = n0;
-        up.push_back(t);
-      }
+    // Up-projection tiles in super-blocks of 8 x 8: the 64 workgroups an XCD runs at a time then share
+    // eight row blocks of Q and eight column blocks of N (4 MiB at r = 512, the size of its L2) instead
+    // of one row block and 64 column blocks, so the operand planes are re-read from L2 and not from HBM
+    constexpr int SB = 8 * 128;
+    for (int ms = 0; ms < m.pp; ms += SB)
+      for (int ns = 0; ns < m.qp; ns += SB)
+        for (int m0 = ms; m0 < std::min(ms + SB, m.pp); m0 += 128)
+          for (int n0 = ns; n0 < std::min(ns + SB, m.qp); n0 += 128) {
+            ProjTile t{};
+            t.mat = i; t.m0 = m0; t.n0 = n0;
+            up.push_back(t);
+          }
   }
   P.down_h = xcd_order(down);
   P.up_h = xcd_order(up);
