@@ -518,24 +518,37 @@ hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
 // the paper's r x q arrays): zw[2] = u_hat^T, zw[3] = (v_hat - u_hat^2)^T; the two GEMMs leave
 // zw[0] = (R u_hat)^T and zw[1] = ((R o R)(v_hat - u_hat^2))^T.
 // ---------------------------------------------------------------------------------------
+// Both kernels move eight consecutive rank indices of one column per thread, as two 16-byte accesses
+// where r % 4 == 0.  k_rot_pre numbers its threads so that eight neighbours hold eight consecutive
+// octets of one column: their writes to the plain temporaries form one 256-byte run (the blocked
+// side is then read in 32-byte pieces, which costs far less than scattered partial-line writes).
+// k_rot_post keeps the flat numbering: its writes go to the blocked arrays, contiguous over threads.
 __global__ __launch_bounds__(256) void k_rot_pre(DevCtx d, const float* __restrict__ u, const float* __restrict__ v,
                                                  float inv_c1, float inv_c2) {
   const MatDev& m = d.mats[blockIdx.y];
   float* uh = reinterpret_cast<float*>(d.arena + m.zw[2]);
   float* var = reinterpret_cast<float*>(d.arena + m.zw[3]);
-  int64_t ngroups = (int64_t)m.qp * m.rp / 8;
-  int64_t per_jb = (int64_t)(m.rp / 8) * 32;
-  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
-    int64_t jb = g / per_jb, rem = g % per_jb;
-    int64_t i8 = rem / 32, j = jb * 32 + rem % 32;
-    if (j >= m.q) continue;
-    for (int e = 0; e < 8; ++e) {
-      int64_t i = i8 * 8 + e;
-      if (i >= m.r) break;
-      float a = u[m.lr_off + g * 8 + e] * inv_c1;
-      float b = v[m.lr_off + g * 8 + e] * inv_c2;
-      uh[j * m.r + i] = a;
-      var[j * m.r + i] = b - a * a;
+  const int64_t octets = m.rp / 8;                     // rank octets per column; a multiple of 4
+  const int64_t ngroups = (int64_t)m.qp * octets;
+  const bool vec = (m.r & 3) == 0;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < ngroups; t += (int64_t)gridDim.x * 256) {
+    // t = (column * octets/4 + octet quad) * 4 + octet in quad: four neighbours share a column
+    const int64_t j = t / octets, i8 = t % octets;
+    if (j >= m.q || i8 * 8 >= m.r) continue;
+    const int64_t src = m.lr_off + (((j >> 5) * octets + i8) * 32 + (j & 31)) * 8;
+    const f32x4n u0 = *reinterpret_cast<const f32x4n*>(u + src), u1 = *reinterpret_cast<const f32x4n*>(u + src + 4);
+    const f32x4n v0 = *reinterpret_cast<const f32x4n*>(v + src), v1 = *reinterpret_cast<const f32x4n*>(v + src + 4);
+    const f32x4n a0 = u0 * inv_c1, a1 = u1 * inv_c1;
+    const f32x4n b0 = v0 * inv_c2 - a0 * a0, b1 = v1 * inv_c2 - a1 * a1;
+    const int64_t dst = j * m.r + i8 * 8;
+    if (vec && i8 * 8 + 8 <= m.r) {
+      *reinterpret_cast<f32x4n*>(uh + dst) = a0;  *reinterpret_cast<f32x4n*>(uh + dst + 4) = a1;
+      *reinterpret_cast<f32x4n*>(var + dst) = b0; *reinterpret_cast<f32x4n*>(var + dst + 4) = b1;
+    } else {
+      for (int e = 0; e < 8 && i8 * 8 + e < m.r; ++e) {
+        uh[dst + e] = e < 4 ? a0[e] : a1[e - 4];
+        var[dst + e] = e < 4 ? b0[e] : b1[e - 4];
+      }
     }
   }
 }
@@ -549,19 +562,28 @@ __global__ __launch_bounds__(256) void k_rot_post(DevCtx d, float* __restrict__ 
   const float* a2 = reinterpret_cast<const float*>(d.arena + m.zw[1]);
   int64_t ngroups = (int64_t)m.qp * m.rp / 8;
   int64_t per_jb = (int64_t)(m.rp / 8) * 32;
+  const bool vec = (m.r & 3) == 0;
   for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
     int64_t jb = g / per_jb, rem = g % per_jb;
     int64_t i8 = rem / 32, j = jb * 32 + rem % 32;
-    for (int e = 0; e < 8; ++e) {
-      int64_t i = i8 * 8 + e;
-      float un = 0.f, vn = 0.f;
-      if (j < m.q && i < m.r) {
-        float ru = a1[j * m.r + i];
-        un = c1 * ru;                                  // R u = c1 * R u_hat
-        vn = c2 * fabsf(a2[j * m.r + i] + ru * ru);
+    f32x4n ru[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, rv[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    if (j < m.q && i8 * 8 < m.r) {
+      const int64_t src = j * m.r + i8 * 8;
+      if (vec && i8 * 8 + 8 <= m.r) {
+        ru[0] = *reinterpret_cast<const f32x4n*>(a1 + src); ru[1] = *reinterpret_cast<const f32x4n*>(a1 + src + 4);
+        rv[0] = *reinterpret_cast<const f32x4n*>(a2 + src); rv[1] = *reinterpret_cast<const f32x4n*>(a2 + src + 4);
+      } else {
+        for (int e = 0; e < 8 && i8 * 8 + e < m.r; ++e) { ru[e >> 2][e & 3] = a1[src + e]; rv[e >> 2][e & 3] = a2[src + e]; }
       }
-      u[m.lr_off + g * 8 + e] = un;
-      v[m.lr_off + g * 8 + e] = vn;
+    }
+    // R u = c1 * R u_hat;  v = c2 | (R o R)(v_hat - u_hat^2) + (R u_hat)^2 |; zero in the padding
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      f32x4n un = ru[h] * c1, vn;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) vn[e] = c2 * fabsf(rv[h][e] + ru[h][e] * ru[h][e]);
+      *reinterpret_cast<f32x4n*>(u + m.lr_off + g * 8 + 4 * h) = un;
+      *reinterpret_cast<f32x4n*>(v + m.lr_off + g * 8 + 4 * h) = vn;
     }
   }
 }
