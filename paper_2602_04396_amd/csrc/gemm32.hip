@@ -142,10 +142,12 @@ __device__ __forceinline__ void gemm_loop(f32x16 (&acc)[WB][WB], const Operand<T
 // ---------------------------------------------------------------------------------------
 // Split-bf16 variant of the K loop for the range-finder products (Alg. 2 sketch and power
 // iteration).  Operands go to LDS as bf16 planes in matrix-core fragment order -- a bf16 source is
-// exact, an fp32 operand becomes hi + lo (2^-16 relative) -- and the products run on
-// v_mfma_f32_32x32x16_bf16: hi*hi + hi*lo (+ lo*hi for an fp32 A).  The blocks that come out are
-// orthonormalised in fp32 afterwards, and the range finder is itself an approximation whose error
-// is orders of magnitude above 2^-17, so the subspace is unaffected.
+// exact, an fp32 operand becomes hi + mid + lo (2^-24 relative, as exact as fp32) -- and the
+// products run on v_mfma_f32_32x32x16_bf16: three passes for a bf16 source, six for an fp32 one
+// (all products of terms down to 2^-24).  Two terms (2^-16) are not enough: the trailing directions
+// of the range finder's block sit in the noise of the source, where gaps between singular values are
+// of the order of a percent, and a 2^-16 perturbation moved the subspace by up to 9e-4 in Frobenius
+// norm of the projector, against 3e-5 for fp32 arithmetic.
 // Plane element (i, k) of a TMN x 32 tile: ((i/32)*4 + k/8) * 264 + (i%32)*8 + k%8 (eight elements
 // of padding per 32 x 8 group spread the groups over the LDS banks).
 // ---------------------------------------------------------------------------------------
@@ -197,17 +199,21 @@ struct OperandBF {
       }
     }
   }
-  // Two fp32 values -> packed bf16 pair of their high parts, and of what is left.  The high part is
-  // the truncated upper half (so hi + rest is exact); the rest is truncated to bf16 as well, which
-  // leaves 2^-16 relative overall -- three vector operations per element.
-  static __device__ __forceinline__ void split2(uint32_t x0, uint32_t x1, uint32_t& hi, uint32_t& lo) {
-    hi = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
+  // Two fp32 values -> three packed bf16 pairs whose sum is the values to 2^-24: hi is the truncated
+  // upper half, mid the truncated upper half of the (exactly representable) remainder, lo the
+  // truncated rest -- about five vector operations per element.
+  static __device__ __forceinline__ void split3(uint32_t x0, uint32_t x1, uint32_t (&t)[3]) {
+    t[0] = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
     const float r0 = __uint_as_float(x0) - __uint_as_float(x0 & 0xffff0000u);
     const float r1 = __uint_as_float(x1) - __uint_as_float(x1 & 0xffff0000u);
-    lo = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+    t[1] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+    const float s0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xffff0000u);
+    const float s1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+    t[2] = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
   }
+  // P: the operand's planes (one for an exact bf16 operand, three for an fp32 one), PLANE elements apart
   template <bool BF16>
-  __device__ __forceinline__ void stash(const u32x4 (&raw)[4], uint16_t* P_hi, uint16_t* P_lo, int k0, int tid) const {
+  __device__ __forceinline__ void stash(const u32x4 (&raw)[4], uint16_t* P, int plane, int k0, int tid) const {
     if (kfast) {
 #pragma unroll
       for (int n = 0; n < NVK; ++n) {
@@ -216,13 +222,13 @@ struct OperandBF {
         const bool ok = i0 + ii < lim && k0 + kk < kend;
         const int at = frag_index(ii, kk);                    // four consecutive k: 8 contiguous bytes
         if constexpr (BF16) {
-          *reinterpret_cast<u32x2*>(P_hi + at) = ok ? u32x2{raw[n].x, raw[n].y} : u32x2{0u, 0u};
+          *reinterpret_cast<u32x2*>(P + at) = ok ? u32x2{raw[n].x, raw[n].y} : u32x2{0u, 0u};
         } else {
-          uint32_t h0, h1, l0, l1;
-          split2(raw[n].x, raw[n].y, h0, l0);
-          split2(raw[n].z, raw[n].w, h1, l1);
-          *reinterpret_cast<u32x2*>(P_hi + at) = ok ? u32x2{h0, h1} : u32x2{0u, 0u};
-          *reinterpret_cast<u32x2*>(P_lo + at) = ok ? u32x2{l0, l1} : u32x2{0u, 0u};
+          uint32_t ta[3], tb[3];
+          split3(raw[n].x, raw[n].y, ta);
+          split3(raw[n].z, raw[n].w, tb);
+#pragma unroll
+          for (int c = 0; c < 3; ++c) *reinterpret_cast<u32x2*>(P + c * plane + at) = ok ? u32x2{ta[c], tb[c]} : u32x2{0u, 0u};
         }
       }
     } else if (tid < TMN * 2) {
@@ -241,13 +247,13 @@ struct OperandBF {
           u32x2 h;
           h.x = __builtin_amdgcn_perm(r[1][e >> 1], r[0][e >> 1], sel);
           h.y = __builtin_amdgcn_perm(r[3][e >> 1], r[2][e >> 1], sel);
-          *reinterpret_cast<u32x2*>(P_hi + at) = h;
+          *reinterpret_cast<u32x2*>(P + at) = h;
         } else {
-          uint32_t h0, h1, l0, l1;
-          split2(r[0][e], r[1][e], h0, l0);
-          split2(r[2][e], r[3][e], h1, l1);
-          *reinterpret_cast<u32x2*>(P_hi + at) = u32x2{h0, h1};
-          *reinterpret_cast<u32x2*>(P_lo + at) = u32x2{l0, l1};
+          uint32_t ta[3], tb[3];
+          split3(r[0][e], r[1][e], ta);
+          split3(r[2][e], r[3][e], tb);
+#pragma unroll
+          for (int c = 0; c < 3; ++c) *reinterpret_cast<u32x2*>(P + c * plane + at) = u32x2{ta[c], tb[c]};
         }
       }
     }
@@ -258,17 +264,16 @@ template <int WB, bool A_BF16, int TM>
 __device__ __forceinline__ void gemm_loop_bf(f32x16 (&acc)[WB][WB], const OperandBF<TM>& opA, const OperandBF<TM>& opB,
                                              uint16_t* lds, int kbeg, int K, int tid, int lane, int wm, int wn) {
   constexpr int PLANE = (TM / 32) * 4 * 264;                   // elements
-  uint16_t* A_hi = lds;
-  uint16_t* A_lo = lds + PLANE;
-  uint16_t* B_hi = lds + 2 * PLANE;
-  uint16_t* B_lo = lds + 3 * PLANE;
+  constexpr int NA = A_BF16 ? 1 : 3;                           // planes of A; B always has three
+  uint16_t* PA = lds;
+  uint16_t* PB = lds + NA * PLANE;
   u32x4 ra[4], rb[4];
   opA.template fetch_raw<A_BF16>(ra, kbeg, tid);
   opB.template fetch_raw<false>(rb, kbeg, tid);
   for (int k0 = kbeg; k0 < K; k0 += TK) {
     __syncthreads();                           // previous tile fully consumed
-    opA.template stash<A_BF16>(ra, A_hi, A_lo, k0, tid);
-    opB.template stash<false>(rb, B_hi, B_lo, k0, tid);
+    opA.template stash<A_BF16>(ra, PA, PLANE, k0, tid);
+    opB.template stash<false>(rb, PB, PLANE, k0, tid);
     __syncthreads();
     if (k0 + TK < K) {
       opA.template fetch_raw<A_BF16>(ra, k0 + TK, tid);
@@ -277,28 +282,30 @@ __device__ __forceinline__ void gemm_loop_bf(f32x16 (&acc)[WB][WB], const Operan
     asm volatile("" ::: "memory");             // keep the loads above the arithmetic: they must be in flight during it
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 ah[WB], al[WB], bh[WB], bl[WB];
+      bf16x8 fa[NA][WB], fb[3][WB];
       const int kg = 16 * ks + 8 * (lane >> 5);
 #pragma unroll
       for (int a = 0; a < WB; ++a) {
         const int at = frag_index(wm + 32 * a + (lane & 31), kg);
-        ah[a] = *reinterpret_cast<const bf16x8*>(A_hi + at);
-        if constexpr (!A_BF16) al[a] = *reinterpret_cast<const bf16x8*>(A_lo + at);
+#pragma unroll
+        for (int c = 0; c < NA; ++c) fa[c][a] = *reinterpret_cast<const bf16x8*>(PA + c * PLANE + at);
       }
 #pragma unroll
       for (int b = 0; b < WB; ++b) {
         const int at = frag_index(wn + 32 * b + (lane & 31), kg);
-        bh[b] = *reinterpret_cast<const bf16x8*>(B_hi + at);
-        bl[b] = *reinterpret_cast<const bf16x8*>(B_lo + at);
+#pragma unroll
+        for (int c = 0; c < 3; ++c) fb[c][b] = *reinterpret_cast<const bf16x8*>(PB + c * PLANE + at);
       }
+      // every product of terms down to 2^-24: (a0, b0..b2) for an exact A; plus (a1, b0), (a1, b1), (a2, b0)
 #pragma unroll
-      for (int a = 0; a < WB; ++a)
+      for (int ca = 0; ca < NA; ++ca)
 #pragma unroll
-        for (int b = 0; b < WB; ++b) {
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], acc[a][b], 0, 0, 0);
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], acc[a][b], 0, 0, 0);
-          if constexpr (!A_BF16) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[a], bh[b], acc[a][b], 0, 0, 0);
-        }
+        for (int cb = 0; cb + ca < 3; ++cb)
+#pragma unroll
+          for (int a = 0; a < WB; ++a)
+#pragma unroll
+            for (int b = 0; b < WB; ++b)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ca][a], fb[cb][b], acc[a][b], 0, 0, 0);
     }
   }
 }
@@ -322,10 +329,12 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
   float* C = reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C, g.mat)));
   float* C2 = g.C2.off >= 0 ? reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C2, g.mat))) : nullptr;
 
-  __shared__ __attribute__((aligned(16))) float lds_raw[2 * TK * PITCH];      // As | Bs, or four bf16 planes
+  // As | Bs of the fp32 loop, or up to six bf16 planes of the split loop
+  constexpr int LDS_FLOATS = 2 * TK * PITCH > 3 * (TM / 32) * 4 * 264 ? 2 * TK * PITCH : 3 * (TM / 32) * 4 * 264;
+  __shared__ __attribute__((aligned(16))) float lds_raw[LDS_FLOATS];
   float (*As)[PITCH] = reinterpret_cast<float (*)[PITCH]>(lds_raw);
   float (*Bs)[PITCH] = reinterpret_cast<float (*)[PITCH]>(lds_raw + TK * PITCH);
-  static_assert(sizeof(float) * 2 * TK * PITCH >= sizeof(uint16_t) * 4 * (TM / 32) * 4 * 264, "bf16 planes must fit");
+  static_assert(sizeof(lds_raw) >= sizeof(uint16_t) * 6 * (TM / 32) * 4 * 264, "six bf16 planes must fit");
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
