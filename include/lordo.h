@@ -121,6 +121,20 @@ int lordo_local_step(lordo_ctx* ctx, void* const* W, const void* const* G,
 int lordo_refresh_subspace(lordo_ctx* ctx, const void* const* Src, int32_t src_dtype,
                            const void* const* Omega, void* stream);
 
+/* Refresh of the local variant (Alg. 2): the projection is computed from this step's clipped
+ * gradient plus the error buffer, Q_new = ComputeProjection(grad_scale * G + E), with the same
+ * range finder and moment rotation as lordo_refresh_subspace.  Needs hp.error_feedback = 1.
+ * The sum is formed in place: after this call the error buffer holds grad_scale * G + E, and the
+ * NEXT call on this context must be lordo_local_step with the same G array (same pointers; its
+ * grad_scale then only scales the full-rank QHM term), which takes g = Q^T (buffer) and leaves
+ * E = buffer - Q g, exactly the step of Alg. 2 that follows the refresh.  Until then
+ * lordo_refresh_subspace*, and get/set of LORDO_STATE_ERR, return LORDO_ESTATE; so does a local step
+ * with other gradient pointers.
+ *   G      host array of n device pointers, p x q of hp.grad_dtype, read only.
+ *   Omega  host array of n device pointers, q x r fp32 Gaussian start blocks, read only. */
+int lordo_refresh_subspace_local(lordo_ctx* ctx, const void* const* G, double grad_scale,
+                                 const void* const* Omega, void* stream);
+
 /* This worker's pseudo-gradient (App. A.1): DeltaOut_i <- anchor_i - W_i, fp32 p x q. */
 int lordo_export_pseudograd(lordo_ctx* ctx, const void* const* W, void* const* DeltaOut, void* stream);
 

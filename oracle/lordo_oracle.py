@@ -206,6 +206,12 @@ def refresh_subspace(st: MatrixState, A_src: np.ndarray, Omega: np.ndarray, hp: 
     return Q_new
 
 
+def local_variant_source(st: MatrixState, G: np.ndarray, grad_scale: float = 1.0) -> np.ndarray:
+    """Argument of ComputeProjection in the local variant (Alg. 2): the clipped gradient of the
+    step plus the error buffer the previous step left, G_hat_t + E_{t-1}."""
+    return grad_scale * np.asarray(G, dtype=F64) + st.E
+
+
 def mssv(Q_new: np.ndarray, Q_old: np.ndarray) -> float:
     """Mean squared singular value of R = Q_new^T Q_old (Sec. 5.1, Metrics):
     (1/r) sum sigma_i^2 = ||R||_F^2 / r."""

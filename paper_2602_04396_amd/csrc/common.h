@@ -152,6 +152,7 @@ struct OuterArgs { float lr, mu; int32_t nesterov, has_mom, own_delta; };
 hipError_t launch_outer(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s);
 hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
 hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
+hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s);
 // refresh helpers (grouped over all matrices)
 hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s);
 hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);

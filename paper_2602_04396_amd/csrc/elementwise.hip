@@ -28,6 +28,7 @@ __device__ __forceinline__ void split_bf(float x, uint32_t& hi, uint32_t& lo) {
 // fused low-rank Adam: one thread per 8 consecutive elements of the flat arena
 // ---------------------------------------------------------------------------------------
 typedef float f32x4n __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2n __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4n __attribute__((ext_vector_type(4)));
 
 // g is read for the last time here and the moments are not touched again before the next step, a
@@ -353,6 +354,52 @@ hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int6
 hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s) {
   OuterArgs a{};
   hipLaunchKernelGGL(k_pq<2>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  return hipGetLastError();
+}
+
+// E <- E + scale * G for every matrix (Alg. 2: the projection of the local variant is computed from
+// the gradient plus the error buffer; the sum is formed in place in the buffer).
+template <bool GF32>
+__global__ __launch_bounds__(256) void k_fold_grad(DevCtx d, const int64_t* __restrict__ chunk_start, float scale) {
+  const int64_t b = blockIdx.x;
+  const int mat = find_mat(chunk_start, d.n, b);
+  const MatDev& m = d.mats[mat];
+  const int64_t total = (int64_t)m.p * m.q;
+  const int64_t off = (b - chunk_start[mat]) * CHUNK;
+  float* E = reinterpret_cast<float*>(d.arena + m.err);
+  const void* G = ext_ptr(d, EXT_G, mat);
+  const bool vec = (total % 4 == 0) && (reinterpret_cast<uintptr_t>(G) & (GF32 ? 15 : 7)) == 0;
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    const int64_t i0 = off + rep * 1024 + threadIdx.x * 4;
+    if (i0 >= total) continue;
+    if (vec) {
+      float g[4];
+      if constexpr (GF32) {
+        f32x4n t = ld_stream(reinterpret_cast<const float*>(G) + i0);
+        g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w;
+      } else {
+        const u32x2n t = __builtin_nontemporal_load(reinterpret_cast<const u32x2n*>(reinterpret_cast<const uint16_t*>(G) + i0));
+        g[0] = __uint_as_float(t.x << 16); g[1] = __uint_as_float(t.x & 0xffff0000u);
+        g[2] = __uint_as_float(t.y << 16); g[3] = __uint_as_float(t.y & 0xffff0000u);
+      }
+      f32x4n e = ld_stream(E + i0);
+      e.x = fmaf(scale, g[0], e.x); e.y = fmaf(scale, g[1], e.y); e.z = fmaf(scale, g[2], e.z); e.w = fmaf(scale, g[3], e.w);
+      st_stream(E + i0, e);
+    } else {
+      const int cnt = total - i0 < 4 ? (int)(total - i0) : 4;
+      for (int e = 0; e < cnt; ++e) {
+        float g;
+        if constexpr (GF32) g = reinterpret_cast<const float*>(G)[i0 + e];
+        else g = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(G)[i0 + e] << 16);
+        E[i0 + e] = fmaf(scale, g, E[i0 + e]);
+      }
+    }
+  }
+}
+hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s) {
+  if (g_is_f32) hipLaunchKernelGGL(k_fold_grad<true>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, scale);
+  else hipLaunchKernelGGL(k_fold_grad<false>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, scale);
   return hipGetLastError();
 }
 

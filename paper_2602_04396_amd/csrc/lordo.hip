@@ -532,6 +532,10 @@ struct lordo_ctx {
   DevCtx dev{};
   int64_t t = 0;
   bool refreshed = false;        // a subspace refresh has run: R = Q_new^T Q_old of the last one is in the arena
+  // lordo_refresh_subspace_local left grad_scale * G + E in the error buffer; the next local step must
+  // come with the same gradient pointers and takes its projected matrix from the buffer alone
+  bool grad_folded = false;
+  std::vector<const void*> folded_g;
   int device = 0;
   // cached caller pointer tables: EXT_SLOTS per kind, replaced round-robin
   std::vector<void*> shadow[EXT_COUNT][EXT_SLOTS];
@@ -645,6 +649,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (rc != LORDO_OK) return rc;
   rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
   if (rc != LORDO_OK) return rc;
+  // after lordo_refresh_subspace_local the error buffer already holds grad_scale * G + E of this step
+  const bool folded = c->grad_folded;
+  if (folded && std::memcmp(c->folded_g.data(), G, sizeof(void*) * c->n) != 0) return LORDO_ESTATE;
+  const double proj_scale = folded ? 0.0 : grad_scale;
   const int64_t t = c->t + 1;
   double c1 = 1.0, c2 = 1.0;
   if (c->hp.bias_correction) {
@@ -683,7 +691,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   fuse.a = a;
   c->prof.begin(LORDO_K_DOWN, s);
   HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, P.g_once, c->at<float>(P.glow),
-                          P.lr_total, (float)grad_scale, g_f32, ef, &fuse, s));
+                          P.lr_total, (float)proj_scale, g_f32, ef, &fuse, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
   if (P.adam_first < P.lr_total)
@@ -695,7 +703,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   ua.g_is_f32 = g_f32 ? 1 : 0;
   ua.eps = (float)c->hp.eps;
   if (ef) {                     // E <- grad_scale*G + E - Q g (Alg. 1 error-feedback lines); reads the E the down-projection used
-    ua.coef_acc = -1.f; ua.coef_g = (float)grad_scale; ua.target_err = 1; ua.colscale = 0; ua.colpart = nullptr;
+    ua.coef_acc = -1.f; ua.coef_g = (float)proj_scale; ua.target_err = 1; ua.colscale = 0; ua.colpart = nullptr;
     HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.g_hi),
                           c->at<uint16_t>(P.g_lo), ua, s));
   }
@@ -711,18 +719,13 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
                         c->at<uint16_t>(P.n_lo), ua, s));
   c->prof.end(LORDO_K_UP, s);
   c->t = t;
+  c->grad_folded = false;
   return LORDO_OK;
 }
 
-int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, void* stream) {
-  if (!c || !Src || !Omega) return LORDO_EINVAL;
-  if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
-  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+// Runs the refresh program on the source table currently selected in EXT_SRC.
+static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s) {
   Plan& P = c->plan;
-  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
-  if (rc != LORDO_OK) return rc;
-  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
-  if (rc != LORDO_OK) return rc;
   const bool rotate = c->t > 0;
   double c1 = 1.0, c2 = 1.0;
   if (c->hp.bias_correction && rotate) {
@@ -755,6 +758,38 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   c->prof.end(LORDO_K_REFRESH, s);
   c->refreshed = true;
   return LORDO_OK;
+}
+
+int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, void* stream) {
+  if (!c || !Src || !Omega) return LORDO_EINVAL;
+  if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
+  if (c->grad_folded) return LORDO_ESTATE;          // the error buffer holds a folded gradient: a local step must consume it first
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
+  if (rc != LORDO_OK) return rc;
+  return run_refresh(c, src_dtype, s);
+}
+
+int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {
+  if (!c || !G || !Omega || !std::isfinite(grad_scale)) return LORDO_EINVAL;
+  if (!c->hp.error_feedback || c->grad_folded) return LORDO_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  Plan& P = c->plan;
+  int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
+  if (rc != LORDO_OK) return rc;
+  std::vector<void*> src(c->n);
+  for (int i = 0; i < c->n; ++i) src[i] = c->dev.arena + P.mat[i].err;
+  rc = c->set_ext(EXT_SRC, src.data(), s);
+  if (rc != LORDO_OK) return rc;
+  // E <- grad_scale * G + E (Alg. 2, argument of ComputeProjection), then the same refresh program on it
+  HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
+  c->grad_folded = true;
+  c->folded_g.assign(G, G + c->n);
+  return run_refresh(c, LORDO_F32, s);
 }
 
 int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* DeltaOut, void* stream) {
@@ -805,7 +840,7 @@ int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, voi
       HIPCHK(launch_copy_f32(dst, c->at<float>(m.mom), (int64_t)m.p * m.q, s));
       break;
     case LORDO_STATE_ERR:
-      if (m.err < 0) return LORDO_ESTATE;
+      if (m.err < 0 || c->grad_folded) return LORDO_ESTATE;      // folded: the buffer holds G + E until the next local step
       HIPCHK(launch_copy_f32(dst, c->at<float>(m.err), (int64_t)m.p * m.q, s));
       break;
     case LORDO_STATE_U: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.u), nullptr, nullptr, dst, 1, 0, s)); break;
@@ -838,7 +873,7 @@ int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_sr
       HIPCHK(launch_copy_f32(c->at<float>(m.mom), src, (int64_t)m.p * m.q, s));
       break;
     case LORDO_STATE_ERR:
-      if (m.err < 0) return LORDO_ESTATE;
+      if (m.err < 0 || c->grad_folded) return LORDO_ESTATE;
       HIPCHK(launch_copy_f32(c->at<float>(m.err), src, (int64_t)m.p * m.q, s));
       break;
     case LORDO_STATE_U: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.u), src, s)); break;

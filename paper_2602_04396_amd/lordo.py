@@ -20,7 +20,7 @@ EXPORTS = [
     "lordo_workspace_bytes", "lordo_init", "lordo_local_step", "lordo_refresh_subspace",
     "lordo_export_pseudograd", "lordo_outer_step", "lordo_get_state", "lordo_set_state",
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
-    "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv",
+    "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv", "lordo_refresh_subspace_local",
 ]
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
@@ -70,6 +70,7 @@ def load() -> C.CDLL:
     lib.lordo_init.argtypes = [C.POINTER(vp), C.POINTER(Shape), C.c_int32, C.POINTER(HParams), vp, C.c_size_t, vpp, vp]
     lib.lordo_local_step.argtypes = [vp, vpp, vpp, C.c_double, C.c_double, vp]
     lib.lordo_refresh_subspace.argtypes = [vp, vpp, C.c_int32, vpp, vp]
+    lib.lordo_refresh_subspace_local.argtypes = [vp, vpp, C.c_double, vpp, vp]
     lib.lordo_export_pseudograd.argtypes = [vp, vpp, vpp, vp]
     lib.lordo_outer_step.argtypes = [vp, vpp, vpp, vp]
     lib.lordo_get_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
@@ -183,6 +184,12 @@ class Lordo:
         if dt not in (self.torch.bfloat16, self.torch.float32):
             raise ValueError("refresh source must be bf16 or fp32")
         _check(self.lib.lordo_refresh_subspace(self.ctx, _ptr_array(Src), code, _ptr_array(Omega), self._stream()))
+
+    def refresh_subspace_local(self, G, Omega, grad_scale=1.0):
+        """Alg. 2 refresh from grad_scale * G + E; the next call must be local_step with the same G."""
+        self._check_tensors(G, self._grad_dtype(), "pq")
+        self._check_tensors(Omega, self.torch.float32, "qr")
+        _check(self.lib.lordo_refresh_subspace_local(self.ctx, _ptr_array(G), float(grad_scale), _ptr_array(Omega), self._stream()))
 
     def export_pseudograd(self, W, out):
         self._check_tensors(W, self.torch.float32, "pq")

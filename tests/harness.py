@@ -69,7 +69,8 @@ class Pair:
 
     def local_step(self, G, lr, grad_scale=1.0, bf16=True, first_step_patch=False):
         """G: list of float32 arrays (already bf16-representable when bf16=True)."""
-        Gd = self.to_dev(G, bf16)
+        Gd = getattr(self, "_held_G", None) or self.to_dev(G, bf16)     # the tensors a local-variant refresh was given
+        self._held_G = None
         self.opt.local_step(self.W_gpu, Gd, lr, grad_scale)
         self.torch.cuda.synchronize()
         patched = 0
@@ -113,7 +114,12 @@ class Pair:
             if check_N:
                 errs["N"] = rel_l2(self.get(i, L.STATE_NUPD), st.last_N)
             if self.ohp.error_feedback:
-                errs["E"] = rel_l2(self.get(i, L.STATE_ERR), st.E)
+                # E = A - Q g is a difference of two matrices of the size of A = G_hat + E_prev: an error
+                # of tol * ||g|| in g alone (the bound on g above) moves E by tol * ||A|| when Q holds most
+                # of A, however small E itself is.  So E is held to tol relative to ||A||, and
+                # ||A||^2 = ||g||^2 + ||E||^2 for orthonormal Q.
+                scale = np.sqrt(np.sum(st.last_g * st.last_g) + np.sum(st.E * st.E))
+                errs["E"] = float(np.linalg.norm(self.get(i, L.STATE_ERR) - st.E) / max(scale, 1e-300))
             for k, e in errs.items():
                 worst[k] = max(worst.get(k, 0.0), e)
                 assert e <= tol, f"matrix {i} {self.shapes[i]}: rel L2 error of {k} = {e:.3e} > {tol}"
@@ -133,6 +139,25 @@ class Pair:
             orths.append(float(np.linalg.norm(Qg.T @ Qg - np.eye(r))))
             Qo = orc.range_finder(np.asarray(Src[i], dtype=np.float64), np.asarray(Omega[i], dtype=np.float64),
                                   self.ohp.power_iters)
+            dists.append(projector_distance(Qg, Qo))
+            orc.refresh_subspace(self.st[i], None, None, self.ohp, Q_forced=Qg)
+        return dists, orths
+
+    def refresh_local(self, G, Omega, grad_scale=1.0, bf16=True):
+        """Refresh of the local variant (Alg. 2): the library folds the gradient into its error
+        buffer and refreshes from the sum; the oracle forms G_hat + E itself.  The following
+        `local_step` must be given the same G; the device tensors are kept for it."""
+        L = self.lordo
+        self._held_G = self.to_dev(G, bf16)
+        Od = self.to_dev(Omega, False)
+        self.opt.refresh_subspace_local(self._held_G, Od, grad_scale)
+        self.opt.poll_status()
+        dists, orths = [], []
+        for i, (p, q, r) in enumerate(self.shapes):
+            Qg = self.get(i, L.STATE_Q)
+            orths.append(float(np.linalg.norm(Qg.T @ Qg - np.eye(r))))
+            src = orc.local_variant_source(self.st[i], np.asarray(G[i], dtype=np.float64), grad_scale)
+            Qo = orc.range_finder(src, np.asarray(Omega[i], dtype=np.float64), self.ohp.power_iters)
             dists.append(projector_distance(Qg, Qo))
             orc.refresh_subspace(self.st[i], None, None, self.ohp, Q_forced=Qg)
         return dists, orths

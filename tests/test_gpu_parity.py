@@ -276,6 +276,55 @@ def test_refresh_rotates_moments(torch):
         pair.compare_local(TOL)
 
 
+@pytest.mark.parametrize("bf16", [True, False])
+def test_local_variant_refresh_from_gradient_plus_residual(torch, bf16):
+    """Call order of the local variant (Alg. 2): identity Q_0, a step, then a refresh computed from
+    this step's gradient plus the error buffer followed by the step on the same gradient, more
+    steps, and a second refresh; low-rank QHM as the paper pairs it with this variant."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128)]
+    ohp = orc.Hyper(error_feedback=True, qhm_mode="low", omega=0.9, power_iters=1)
+    ghp = lordo.hparams(error_feedback=True, qhm_mode=1, omega=0.9, power_iters=1, grad_dtype=lordo.BF16 if bf16 else lordo.F32)
+    pair = Pair(torch, shapes, _weights(shapes, 24), ohp, ghp)          # Q_0 = identity columns
+    gens = _spiked(shapes, 24, 8, bf16=bf16)
+    Om = [synth.omega(np.random.default_rng(synth.seed_for(24, 900 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+    t = 0
+    pair.local_step([g.draw(t) for g in gens], lr=1e-3, bf16=bf16, first_step_patch=True)
+    pair.compare_local(TOL)
+    for window in range(2):
+        t += 1
+        G = [g.draw(t) for g in gens]
+        scale = 0.7 if window == 1 else 1.0
+        dists, orths = pair.refresh_local(G, Om, grad_scale=scale, bf16=bf16)
+        print(f"local-variant refresh {window} bf16={bf16}: dist {np.round(dists, 6)} orth {np.round(orths, 7)}", flush=True)
+        assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
+        # the buffer holds G + E until the step that consumes it
+        with pytest.raises(lordo.LordoError) as e:
+            pair.opt.get_state(0, lordo.STATE_ERR)
+        assert e.value.code == lordo.ESTATE
+        with pytest.raises(lordo.LordoError) as e:
+            pair.opt.refresh_subspace(pair._held_G, pair.to_dev(Om, False))
+        assert e.value.code == lordo.ESTATE
+        with pytest.raises(lordo.LordoError) as e:                     # other gradient tensors than the folded ones
+            pair.opt.local_step(pair.W_gpu, pair.to_dev(G, bf16), 1e-3)
+        assert e.value.code == lordo.ESTATE
+        pair.local_step(G, lr=1e-3, grad_scale=scale, bf16=bf16)
+        pair.compare_local(TOL)
+        for _ in range(2):
+            t += 1
+            pair.local_step([g.draw(t) for g in gens], lr=1e-3, bf16=bf16)
+        pair.compare_local(TOL)
+    for i, (p, q, r) in enumerate(shapes):
+        E = pair.get(i, lordo.STATE_ERR)
+        Q = pair.get(i, lordo.STATE_Q)
+        assert np.linalg.norm(Q.T @ E) <= 1e-4 * np.linalg.norm(E)
+    # without error feedback there is no buffer to refresh from
+    plain = Pair(torch, shapes[:1], _weights(shapes[:1], 24), orc.Hyper(), lordo.hparams())
+    with pytest.raises(lordo.LordoError) as e:
+        plain.opt.refresh_subspace_local(plain.to_dev([gens[0].draw(0)], True), plain.to_dev(Om[:1], False))
+    assert e.value.code == lordo.ESTATE
+
+
 def test_refresh_before_first_step_and_exact_reconstruction(torch):
     """rank(Src) = r exactly: the refreshed Q must reproduce Src (Q Q^T Src = Src); t = 0: no rotation."""
     from paper_2602_04396_amd import lordo

@@ -180,6 +180,34 @@ def test_error_feedback_telescopes_and_is_orthogonal_to_Q():
     assert rel(sumQg + st.E, sumG) < 1e-13
 
 
+def test_local_variant_projection_sees_the_error_buffer():
+    """Alg. 2: Q = ComputeProjection(G_t + E_{t-1}).  Build a gradient and a residual whose SUM has
+    rank r while each alone has full rank: the step after the refresh then leaves E_t = 0 (the new
+    span holds all of G + E), which a projection computed from G alone would not give."""
+    rng = rng_of(31)
+    p, q, r = 20, 14, 3
+    hp = orc.Hyper(error_feedback=True, power_iters=2)
+    W = rng.standard_normal((p, q))
+    st = orc.init_state(W, r)                                   # Q_0 = identity columns (Alg. 2, Require)
+    W = orc.local_step(st, W, rng.standard_normal((p, q)), 1e-3, hp)
+    assert np.linalg.matrix_rank(st.E) > r
+    low = rng.standard_normal((p, r)) @ rng.standard_normal((r, q))
+    G = (low - st.E) / 0.5                                      # 0.5 * G + E = low
+    assert np.linalg.matrix_rank(G) > r
+    src = orc.local_variant_source(st, G, grad_scale=0.5)
+    assert rel(src, low) < 1e-12
+    orc.refresh_subspace(st, src, rng.standard_normal((q, r)), hp)
+    W = orc.local_step(st, W, G, 1e-3, hp, grad_scale=0.5)
+    assert np.abs(st.E).max() < 1e-10 * np.abs(low).max()
+    # same construction, projection from the gradient alone: the residual survives
+    st2 = orc.init_state(W, r)
+    orc.local_step(st2, W, rng.standard_normal((p, q)), 1e-3, hp)
+    G2 = (low - st2.E) / 0.5
+    orc.refresh_subspace(st2, 0.5 * G2, rng.standard_normal((q, r)), hp)
+    orc.local_step(st2, W, G2, 1e-3, hp, grad_scale=0.5)
+    assert np.abs(st2.E).max() > 1e-3 * np.abs(low).max()
+
+
 @pytest.mark.parametrize("mode", ["low", "full"])
 def test_qhm_omega_one_is_no_qhm(mode):
     """Alg. 1: at omega = 1 both QHM cases are the "No QHM" case."""
