@@ -49,9 +49,10 @@ def parse():
     ap.add_argument("--no-events", action="store_true", help="skip the event-timed second pass")
     ap.add_argument("--refresh-every", type=int, default=None)
     ap.add_argument("--outer-every", type=int, default=None)
-    ap.add_argument("--update", default="plain", choices=["plain", "low-qhm", "full-qhm", "ef", "global"],
+    ap.add_argument("--update", default="plain", choices=["plain", "low-qhm", "full-qhm", "ef", "global", "local", "uplink"],
                     help="update case of the local step: plain (default, the headline), low-rank / full-rank QHM (omega 0.9), "
-                         "error feedback, or global = full-rank QHM + error feedback (the paper's LoRDO-Global)")
+                         "error feedback, global = full-rank QHM + error feedback (the paper's LoRDO-Global), local = low-rank QHM + error "
+                         "feedback with the refresh of Alg. 2, uplink = plain with the r x q up-link buffer and the outer step fed from it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 1 GiB device copies (known traffic) to scale the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
@@ -126,14 +127,19 @@ def build_workload(torch, lordo, synth, cfg, rank, n_sets):
     return shapes, W, G, Omega, D, grad_dtype
 
 
-def run_steps(opt, Wp, Gp, Dp, Op, steps, outer_every, refresh_every, lr, start=0):
+def run_steps(opt, Wp, Gp, Dp, Op, steps, outer_every, refresh_every, lr, start=0, local_variant=False, Ap=None):
     n_sets = len(Gp)
     for i in range(start, start + steps):
         g = Gp[i % n_sets]
+        if local_variant and refresh_every and (i + 1) % refresh_every == 0:
+            opt.refresh_subspace_local(g, Op)        # Alg. 2: projection from this step's gradient plus the error buffer
         opt.local_step(Wp, g, lr)
         if outer_every and (i + 1) % outer_every == 0:
-            opt.outer_step(Wp, Dp)
-        if refresh_every and (i + 1) % refresh_every == 0:
+            if Ap is not None:
+                opt.outer_step_lowrank(Wp, Ap)       # App. A.5.1: Delta = Q mean(A), no p x q pseudo-gradient
+            else:
+                opt.outer_step(Wp, Dp)
+        if not local_variant and refresh_every and (i + 1) % refresh_every == 0:
             opt.refresh_subspace(g, Op)
 
 
@@ -233,25 +239,35 @@ def main():
     refresh_every = d["refresh_every"] if args.refresh_every is None else args.refresh_every
     n_sets = args.grad_sets or (4 if cfg in ("c1", "c2") else 2)
     shapes, W, G, Omega, D, grad_dtype = build_workload(torch, lordo, synth, cfg, args.rank, n_sets)
-    qhm_mode = {"plain": 0, "ef": 0, "low-qhm": 1, "full-qhm": 2, "global": 2}[args.update]
-    use_ef = args.update in ("ef", "global")
+    qhm_mode = {"plain": 0, "ef": 0, "low-qhm": 1, "full-qhm": 2, "global": 2, "local": 1, "uplink": 0}[args.update]
+    uplink = args.update == "uplink"
+    if uplink and outer_every and refresh_every:       # the buffer is tied to Q: refresh only right after an outer step
+        refresh_every = max(outer_every, refresh_every // outer_every * outer_every)
+    use_ef = args.update in ("ef", "global", "local")
+    local_variant = args.update == "local"
     hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=d["power_iters"],
                        grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
-                       qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef)
+                       qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef, uplink_buffer=uplink)
     opt = lordo.Lordo(shapes, hp, W, torch)
     Wp = opt.ptrs(W)
     Gp = [opt.ptrs(g, grad_dtype) for g in G]
     Dp = opt.ptrs(D)
     Op = opt.ptrs(Omega, torch.float32, "qr")
+    Ap = None
+    if uplink:    # stand-in for the mean of the workers' buffers: eta * H times a unit-scale low-rank update
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(synth.seed_for(int(cfg[1:]), 998))
+        Ap = opt.ptrs([(1e-3 * max(outer_every, 1)) * torch.randn(r, q, generator=gen, device="cuda") for p, q, r in shapes],
+                      torch.float32, "rq")
     lr = 1e-3
     # a first projection from the first gradient set, as a training run would have
     opt.refresh_subspace(Gp[0], Op)
     opt.poll_status()
 
-    run_steps(opt, Wp, Gp, Dp, Op, args.warmup, outer_every, refresh_every, lr, start=0)
+    run_steps(opt, Wp, Gp, Dp, Op, args.warmup, outer_every, refresh_every, lr, start=0, local_variant=local_variant, Ap=Ap)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_steps(opt, Wp, Gp, Dp, Op, args.steps, outer_every, refresh_every, lr, start=0)
+    run_steps(opt, Wp, Gp, Dp, Op, args.steps, outer_every, refresh_every, lr, start=0, local_variant=local_variant, Ap=Ap)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = 1e3 * (t1 - t0) / args.steps
@@ -262,9 +278,9 @@ def main():
     roofline = None
     if not args.no_events:
         opt.profile_enable(True)
-        run_steps(opt, Wp, Gp, Dp, Op, args.steps, outer_every, refresh_every, lr, start=0)
+        run_steps(opt, Wp, Gp, Dp, Op, args.steps, outer_every, refresh_every, lr, start=0, local_variant=local_variant, Ap=Ap)
         if not outer_every:          # workloads that time the outer step and the refresh on their own
-            opt.outer_step(Wp, Dp)
+            opt.outer_step_lowrank(Wp, Ap) if uplink else opt.outer_step(Wp, Dp)
         if not refresh_every:
             opt.refresh_subspace(Gp[0], Op)
         torch.cuda.synchronize()

@@ -55,6 +55,7 @@ extern "C" {
 #define LORDO_STATE_GLOW    5   /* r x q  g of the last local step (read only)         */
 #define LORDO_STATE_NUPD    6   /* r x q  bracketed update N of the last local step (read only) */
 #define LORDO_STATE_ERR     7   /* p x q  error-feedback residual E (only if error_feedback != 0) */
+#define LORDO_STATE_UPLINK  8   /* r x q  up-link buffer A (only if uplink_buffer != 0)           */
 
 typedef struct lordo_ctx lordo_ctx;
 
@@ -80,7 +81,8 @@ typedef struct {
   int32_t power_iters;           /* block power iterations of the range finder, 0..8                    */
   int32_t orth_passes;           /* CholeskyQR passes per orthonormalisation: 2 (default if 0) or 3     */
   int32_t grad_dtype;            /* LORDO_BF16 or LORDO_F32: element type of every G                    */
-  int32_t reserved;              /* must be 0                                                           */
+  int32_t uplink_buffer;         /* 1: keep the r x q up-link buffer A = sum over the window of eta_t N_t (App. A.5.1);
+                                    not with qhm_mode 2, whose update has no low-rank form              */
 } lordo_hparams;
 
 /* Bytes of arena lordo_init needs for these shapes and hyper-parameters (host call). */
@@ -144,6 +146,21 @@ int lordo_export_pseudograd(lordo_ctx* ctx, const void* const* W, void* const* D
  *   mu != 0:  b <- mu b + D;  W <- anchor - eta_s (D + mu b) (Nesterov) or anchor - eta_s b (heavy ball)
  * then anchor <- W.  W is written (and read only when AvgDelta == NULL). */
 int lordo_outer_step(lordo_ctx* ctx, void* const* W, const void* const* AvgDelta, void* stream);
+
+/* Up-link time buffer (App. A.5.1, "Worker Communication"; memory-overhead table): with
+ * hp.uplink_buffer = 1 every local step also does A <- A + lr * N (r x q per matrix, N the bracketed
+ * low-rank update of that step), so that between two outer steps anchor - W = Q A and only A has to
+ * be sent.  The buffer is in coordinates of the current Q: lordo_refresh_subspace* return
+ * LORDO_ESTATE while it is non-empty (local steps taken since the last outer step); both outer-step
+ * calls clear it.
+ * lordo_export_uplink: AccOut_i <- A_i, plain row-major fp32 r x q (host array of n device pointers).
+ * lordo_outer_step_lowrank: the outer step of lordo_outer_step with Delta_i = Q_i AvgAcc_i, AvgAcc the
+ *   cross-worker mean of the exported buffers (fp32 r x q each; NULL: this worker's own buffer), formed
+ *   tile by tile inside the update -- no p x q pseudo-gradient is materialised.  Every worker must hold
+ *   the same Q (the global variant).  Overwrites the planes behind LORDO_STATE_NUPD.
+ * Both return LORDO_ESTATE without hp.uplink_buffer. */
+int lordo_export_uplink(lordo_ctx* ctx, void* const* AccOut, void* stream);
+int lordo_outer_step_lowrank(lordo_ctx* ctx, void* const* W, const void* const* AvgAcc, void* stream);
 
 /* Copy one state tensor of matrix `mat` to / from a plain row-major fp32 device buffer of the
  * shape listed at the selector.  set_state(Q) expects orthonormal columns and rebuilds the packed

@@ -53,6 +53,7 @@ class Hyper:
     qhm_mode: str = "none"          # "none" | "low" | "full"   (Alg. 1, three cases of the update)
     omega: float = 1.0
     error_feedback: bool = False    # Alg. 1, error-feedback lines
+    uplink_buffer: bool = False     # App. A.5.1: accumulate the low-rank updates of the window
     outer_lr: float = 1.0           # OuterOpt: averaging by default (Alg. 1, Require)
     outer_momentum: float = 0.0
     outer_nesterov: bool = False
@@ -68,6 +69,7 @@ class MatrixState:
     anchor: np.ndarray              # p x q : x_{t-K_x}
     E: np.ndarray | None = None     # p x q
     b: np.ndarray | None = None     # p x q
+    A: np.ndarray | None = None     # r x q : up-link time buffer, sum over the window of eta_t N_t
     t: int = 0
     last_g: np.ndarray | None = field(default=None, repr=False)
     last_N: np.ndarray | None = field(default=None, repr=False)
@@ -87,7 +89,7 @@ def init_state(W0: np.ndarray, r: int, Q0: np.ndarray | None = None) -> MatrixSt
     Q = identity_projection(p, r) if Q0 is None else np.array(Q0, dtype=F64)
     assert Q.shape == (p, r)
     return MatrixState(Q=Q, u=np.zeros((r, q)), v=np.zeros((r, q)), anchor=W0.copy(),
-                       E=np.zeros((p, q)), b=np.zeros((p, q)), t=0)
+                       E=np.zeros((p, q)), b=np.zeros((p, q)), A=np.zeros((r, q)), t=0)
 
 
 # ----------------------------------------------------------------------------
@@ -142,6 +144,9 @@ def local_step(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyp
     st.u, st.v = update_moments(st.u, st.v, g, hp.beta1, hp.beta2)
     N = low_rank_direction(st.u, st.v, g, st.t, hp)
     st.last_g, st.last_N = g, N
+    if hp.uplink_buffer:                               # App. A.5.1: sum_tau eta_tau alpha_tau, alpha the bracketed term
+        assert hp.qhm_mode != "full", "the full-rank QHM update has no low-rank form (App. A.5.1)"
+        st.A = st.A + lr * N
     if hp.qhm_mode == "full":
         _, c2 = bias_factors(st.t, hp)
         col_scale = np.mean(np.sqrt(st.v / c2) + hp.eps, axis=0)      # mu(.) over the rank index
@@ -227,6 +232,14 @@ def pseudo_gradient(st: MatrixState, W: np.ndarray) -> np.ndarray:
     return st.anchor - np.asarray(W, dtype=F64)
 
 
+def outer_step_lowrank(st: MatrixState, avg_A: np.ndarray, hp: Hyper) -> np.ndarray:
+    """Outer step from the averaged up-link buffers (App. A.5.1): with one projection shared by all
+    workers the mean pseudo-gradient is rebuilt as Delta = Q mean_m(A^m), then the ordinary outer
+    step; a new window starts with an empty buffer."""
+    W_new = outer_step(st, st.Q @ np.asarray(avg_A, dtype=F64), hp)
+    return W_new
+
+
 def outer_step(st: MatrixState, avg_delta: np.ndarray, hp: Hyper) -> np.ndarray:
     """x <- OuterOpt(Delta, x_{t-K_x}).  Plain: x = anchor - eta_s Delta (eta_s = 1 is
     averaging).  With momentum mu: b <- mu b + Delta; step = Delta + mu b (Nesterov)
@@ -236,4 +249,6 @@ def outer_step(st: MatrixState, avg_delta: np.ndarray, hp: Hyper) -> np.ndarray:
     step = D + hp.outer_momentum * st.b if hp.outer_nesterov else st.b
     W_new = st.anchor - hp.outer_lr * step
     st.anchor = W_new.copy()
+    if st.A is not None:
+        st.A = np.zeros_like(st.A)                     # the window's accumulated update has been consumed
     return W_new

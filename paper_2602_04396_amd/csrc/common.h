@@ -108,7 +108,7 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 struct UpArgs {
   float coef_acc;         // -eta (plain), -eta*omega (full-rank QHM), -1 (error-feedback residual)
   float coef_g;           // 0 (plain), -eta*(1-omega)*grad_scale (full-rank QHM), grad_scale (residual)
-  int32_t target_err;     // 0: the caller's W; 1: the residual E kept in the arena
+  int32_t target_err;     // 0: the caller's W; 1: the residual E kept in the arena; 2: the outer momentum b
   int32_t colscale;       // 1: c_j = 1 / mean over the rank of sqrt(v_hat) + eps (full-rank QHM); 0: c_j = 1
   int32_t g_is_f32;       // element type of G
   float eps;
@@ -132,6 +132,8 @@ struct AdamArgs {
   float* colpart;         // full-rank QHM: per column and rank block of 32, sum of sqrt(v_hat) + eps (else null)
   uint16_t* g_hi;         // error feedback: bf16 hi / lo operand planes of the summed g (else null)
   uint16_t* g_lo;
+  float* acc;             // up-link buffer (App. A.5.1): acc += lr * N every step (else null)
+  float lr;
 };
 struct DownFuse {
   float* u;
@@ -150,6 +152,8 @@ hipError_t launch_copy_f32(float* dst, const float* src, int64_t n, hipStream_t 
 // p x q elementwise family: chunk_start (device) has n+1 entries, prefix sums of per-matrix chunk counts
 struct OuterArgs { float lr, mu; int32_t nesterov, has_mom, own_delta; };
 hipError_t launch_outer(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s);
+hipError_t launch_outer_base(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s);
+hipError_t launch_split_planes(const float* src, uint16_t* p_hi, uint16_t* p_lo, int64_t nelem, hipStream_t s);
 hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
 hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
 hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s);
@@ -164,5 +168,6 @@ hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s);
 hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, const uint16_t* n_hi, const uint16_t* n_lo,
                               float* dst, int nsplit, int64_t stride, hipStream_t s);
 hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s);
+hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hipStream_t s);
 
 }  // namespace lordo

@@ -72,6 +72,7 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
       vv[0] = v0.x; vv[1] = v0.y; vv[2] = v0.z; vv[3] = v0.w; vv[4] = v1.x; vv[5] = v1.y; vv[6] = v1.z; vv[7] = v1.w;
     }
     uint32_t hi[8], lo[8];
+    float nv[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float un = fmaf(a.b1, uu[e], a.omb1 * g[e]);
@@ -84,6 +85,14 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
       // quasi-hyperbolic case; with qw = 1, qg = 0 the value is bit-identical to u_hat / den
       float nn = fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;
       split_bf(nn, hi[e], lo[e]);
+      nv[e] = nn;
+    }
+    if (a.acc) {               // App. A.5.1: sum over the window of eta_t times the low-rank update
+      f32x4n c0 = ld_stream(a.acc + base), c1 = ld_stream(a.acc + base + 4);
+      c0.x = fmaf(a.lr, nv[0], c0.x); c0.y = fmaf(a.lr, nv[1], c0.y); c0.z = fmaf(a.lr, nv[2], c0.z); c0.w = fmaf(a.lr, nv[3], c0.w);
+      c1.x = fmaf(a.lr, nv[4], c1.x); c1.y = fmaf(a.lr, nv[5], c1.y); c1.z = fmaf(a.lr, nv[6], c1.z); c1.w = fmaf(a.lr, nv[7], c1.w);
+      st_stream(a.acc + base, c0);
+      st_stream(a.acc + base + 4, c1);
     }
     st_stream(u + base, f32x4n{uu[0], uu[1], uu[2], uu[3]});
     st_stream(u + base + 4, f32x4n{uu[4], uu[5], uu[6], uu[7]});
@@ -117,6 +126,30 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
       a.colpart[((grp & ~int64_t(31)) >> 2) + (grp & 31)] = sum;
     }
   }
+}
+
+// fp32 array in operand layout -> bf16 hi / lo planes (the low-rank pseudo-gradient as B operand of the up-projection)
+__global__ __launch_bounds__(256) void k_split_planes(const float* __restrict__ src, uint16_t* __restrict__ p_hi,
+                                                      uint16_t* __restrict__ p_lo, int64_t ngroups) {
+  const int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (gidx >= ngroups) return;
+  const int64_t base = gidx * 8;
+  const f32x4n a0 = *reinterpret_cast<const f32x4n*>(src + base), a1 = *reinterpret_cast<const f32x4n*>(src + base + 4);
+  const float x[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+  uint32_t hi[8], lo[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) split_bf(x[e], hi[e], lo[e]);
+  u32x4n ph, pl;
+  ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
+  pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
+  *reinterpret_cast<u32x4n*>(p_hi + base) = ph;
+  *reinterpret_cast<u32x4n*>(p_lo + base) = pl;
+}
+hipError_t launch_split_planes(const float* src, uint16_t* p_hi, uint16_t* p_lo, int64_t nelem, hipStream_t s) {
+  const int64_t ngroups = nelem / 8;                  // nelem is a multiple of 8
+  if (ngroups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_split_planes, dim3((unsigned)((ngroups + 255) / 256)), dim3(256), 0, s, src, p_hi, p_lo, ngroups);
+  return hipGetLastError();
 }
 
 hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, uint16_t* n_lo, int64_t nelem,
@@ -268,7 +301,7 @@ __device__ __forceinline__ int find_mat(const int64_t* chunk_start, int n, int64
   return lo;
 }
 
-template <int MODE>   // 0 outer step, 1 export delta, 2 anchor <- W
+template <int MODE>   // 0 outer step, 1 export delta, 2 anchor <- W, 3 part of the outer step that does not depend on Delta
 __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict__ chunk_start, OuterArgs a) {
   int64_t b = blockIdx.x;
   int mat = find_mat(chunk_start, d.n, b);
@@ -291,16 +324,16 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
     int cnt = total - i0 < 4 ? (int)(total - i0) : 4;
     if (vec) {       // every array here is touched once per call and is far larger than the caches: streaming accesses
       f32x4n t;
-      if (MODE != 0 || a.own_delta) { t = ld_stream(W + i0); w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w; }
+      if ((MODE != 0 && MODE != 3) || (MODE == 0 && a.own_delta)) { t = ld_stream(W + i0); w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w; }
       if (MODE != 2) { t = ld_stream(anchor + i0); an[0] = t.x; an[1] = t.y; an[2] = t.z; an[3] = t.w; }
       if (din) { t = ld_stream(din + i0); dl[0] = t.x; dl[1] = t.y; dl[2] = t.z; dl[3] = t.w; }
-      if (MODE == 0 && mom) { t = ld_stream(mom + i0); bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w; }
+      if ((MODE == 0 || MODE == 3) && mom) { t = ld_stream(mom + i0); bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w; }
     } else {
       for (int e = 0; e < cnt; ++e) {
-        if (MODE != 0 || a.own_delta) w[e] = W[i0 + e];
+        if ((MODE != 0 && MODE != 3) || (MODE == 0 && a.own_delta)) w[e] = W[i0 + e];
         if (MODE != 2) an[e] = anchor[i0 + e];
         if (din) dl[e] = din[i0 + e];
-        if (MODE == 0 && mom) bb[e] = mom[i0 + e];
+        if ((MODE == 0 || MODE == 3) && mom) bb[e] = mom[i0 + e];
       }
     }
     float o0[4], o1[4];
@@ -317,8 +350,18 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
         o0[e] = fmaf(-a.lr, step, an[e]);
       } else if (MODE == 1) {
         o0[e] = an[e] - w[e];
-      } else {
+      } else if (MODE == 2) {
         o0[e] = w[e];
+      } else {
+        // outer step with Delta = Q A still to be added by the up-projection kernel:
+        // b' = mu b + Delta;  W' = anchor - lr (Delta + mu b') (Nesterov) or anchor - lr b' (heavy ball)
+        // => b <- mu b,  W <- anchor - lr mu (mu b)  or  anchor - lr (mu b)
+        o0[e] = an[e];
+        if (mom) {
+          const float bn = a.mu * bb[e];
+          o1[e] = bn;
+          o0[e] = fmaf(-a.lr, a.nesterov ? a.mu * bn : bn, an[e]);
+        }
       }
     }
     if (vec) {
@@ -329,14 +372,18 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
         if (mom) st_stream(mom + i0, f32x4n{o1[0], o1[1], o1[2], o1[3]});
       } else if (MODE == 1) {
         st_stream(dout + i0, t0);
-      } else {
+      } else if (MODE == 2) {
         st_stream(anchor + i0, t0);
+      } else {             // the up-projection kernel reads both again right away: cacheable stores
+        *reinterpret_cast<f32x4n*>(W + i0) = t0;
+        if (mom) *reinterpret_cast<f32x4n*>(mom + i0) = f32x4n{o1[0], o1[1], o1[2], o1[3]};
       }
     } else {
       for (int e = 0; e < cnt; ++e) {
         if (MODE == 0) { W[i0 + e] = o0[e]; anchor[i0 + e] = o0[e]; if (mom) mom[i0 + e] = o1[e]; }
         else if (MODE == 1) dout[i0 + e] = o0[e];
-        else anchor[i0 + e] = o0[e];
+        else if (MODE == 2) anchor[i0 + e] = o0[e];
+        else { W[i0 + e] = o0[e]; if (mom) mom[i0 + e] = o1[e]; }
       }
     }
   }
@@ -344,6 +391,10 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
 
 hipError_t launch_outer(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(k_pq<0>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  return hipGetLastError();
+}
+hipError_t launch_outer_base(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_pq<3>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
   return hipGetLastError();
 }
 hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s) {
@@ -673,6 +724,27 @@ __global__ __launch_bounds__(256) void k_plain_to_lr(DevCtx d, int mat, float* l
 }
 hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s) {
   hipLaunchKernelGGL(k_plain_to_lr, dim3(256), dim3(256), 0, s, d, mat, lr_arr, src);
+  return hipGetLastError();
+}
+
+// All matrices at once, plain r x q buffers from the caller's pointer tables (up-link buffer exchange):
+// TO_PLAIN: table EXT_DOUT <- lr_arr;  else lr_arr <- table EXT_DIN.  Padded positions are not touched.
+template <bool TO_PLAIN>
+__global__ __launch_bounds__(256) void k_lr_exchange(DevCtx d, float* lr_arr) {
+  const int mat = blockIdx.y;
+  const MatDev& m = d.mats[mat];
+  float* ext = reinterpret_cast<float*>(ext_ptr(d, TO_PLAIN ? EXT_DOUT : EXT_DIN, mat));
+  const int64_t total = (int64_t)m.r * m.q;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t i = t / m.q, j = t % m.q;
+    const int64_t at = m.lr_off + bl_index(j, i, m.rp);
+    if (TO_PLAIN) ext[t] = lr_arr[at];
+    else lr_arr[at] = ext[t];
+  }
+}
+hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hipStream_t s) {
+  if (to_plain) hipLaunchKernelGGL(k_lr_exchange<true>, dim3(64, d.n), dim3(256), 0, s, d, lr_arr);
+  else hipLaunchKernelGGL(k_lr_exchange<false>, dim3(64, d.n), dim3(256), 0, s, d, lr_arr);
   return hipGetLastError();
 }
 

@@ -48,6 +48,7 @@ struct Plan {
   int rank_tile = 128;              // rank indices per down-projection tile
   bool g_once = true;               // every matrix has one rank tile of the down-projection: G is read exactly once
   int64_t colpart = -1, g_hi = -1, g_lo = -1;   // full-rank QHM column sums; error-feedback planes of g
+  int64_t acc = -1;                 // up-link buffer: flat low-rank array, sum over the window of lr * N
   int64_t adam_first = 0;           // flat position from which the stand-alone Adam kernel runs (elements before it are fused)
   int nsplit = 1;                   // largest split-K factor of the down-projection
   std::vector<int> splits;          // split-K factor per matrix (1, 2, 4 or 8)
@@ -324,8 +325,9 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
     if (s.rows > (1 << 24) || s.cols > (1 << 24) || s.rank > 4096) return LORDO_EINVAL;
   }
   if (!(hp->beta1 >= 0 && hp->beta1 < 1) || !(hp->beta2 >= 0 && hp->beta2 < 1) || !(hp->eps >= 0)) return LORDO_EINVAL;
-  if (hp->qhm_mode < 0 || hp->qhm_mode > 2 || (hp->error_feedback != 0 && hp->error_feedback != 1) || hp->reserved != 0)
-    return LORDO_EINVAL;
+  if (hp->qhm_mode < 0 || hp->qhm_mode > 2 || (hp->error_feedback != 0 && hp->error_feedback != 1)) return LORDO_EINVAL;
+  // the up-link buffer holds the update in low-rank form; the full-rank QHM update has no such form (App. A.5.1)
+  if ((hp->uplink_buffer != 0 && hp->uplink_buffer != 1) || (hp->uplink_buffer && hp->qhm_mode == 2)) return LORDO_EINVAL;
   if (hp->qhm_mode != 0 && !(hp->omega >= 0.0 && hp->omega <= 1.0)) return LORDO_EINVAL;
   if (hp->power_iters < 0 || hp->power_iters > 8) return LORDO_EINVAL;
   if (hp->orth_passes != 0 && hp->orth_passes != 2 && hp->orth_passes != 3) return LORDO_EINVAL;
@@ -421,7 +423,8 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the launch has several rounds of workgroups and the epilogue of one overlaps the main loop of
   // another; a launch that needs split-K is a single round of workgroups in lock step, where the
   // stand-alone kernel is as fast and leaves the down-projection shorter.
-  P.adam_first = (P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0) ? lr : 0;
+  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0 && !hp.uplink_buffer;
+  P.adam_first = fuse_adam ? lr : 0;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);
   P.v = A.take(sizeof(float) * lr);
@@ -429,6 +432,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.n_lo = A.take(sizeof(uint16_t) * lr);
   if (hp.qhm_mode == 2) P.colpart = A.take(sizeof(float) * (lr / 32));
   if (hp.error_feedback) { P.g_hi = A.take(sizeof(uint16_t) * lr); P.g_lo = A.take(sizeof(uint16_t) * lr); }
+  if (hp.uplink_buffer) P.acc = A.take(sizeof(float) * lr);
   P.part_slices = small_out_split(P.mat.data(), n, nullptr);
   for (int i = 0; i < n; ++i) {
     MatDev& m = P.mat[i];
@@ -459,7 +463,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
           ProjTile t{};
           t.mat = i; t.m0 = m0; t.n0 = n0; t.split = sp;
           t.k0 = std::min(sp * klen, m.pp); t.k1 = std::min(t.k0 + klen, m.pp);
-          t.fuse = (P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0) ? 1 : 0;
+          t.fuse = fuse_adam ? 1 : 0;
           down.push_back(t);
         }
     // Up-projection tiles in super-blocks of 8 x 8: the 64 workgroups an XCD runs at a time then share
@@ -535,6 +539,7 @@ struct lordo_ctx {
   // lordo_refresh_subspace_local left grad_scale * G + E in the error buffer; the next local step must
   // come with the same gradient pointers and takes its projected matrix from the buffer alone
   bool grad_folded = false;
+  int64_t window_steps = 0;      // local steps since the last outer step: what the up-link buffer holds
   std::vector<const void*> folded_g;
   int device = 0;
   // cached caller pointer tables: EXT_SLOTS per kind, replaced round-robin
@@ -673,6 +678,8 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   a.colpart = qhm_full ? c->at<float>(P.colpart) : nullptr;
   a.g_hi = ef ? c->at<uint16_t>(P.g_hi) : nullptr;
   a.g_lo = ef ? c->at<uint16_t>(P.g_lo) : nullptr;
+  a.acc = c->hp.uplink_buffer ? c->at<float>(P.acc) : nullptr;
+  a.lr = (float)lr;
   const bool g_f32 = c->hp.grad_dtype == LORDO_F32;
   bool g_vec = true;            // 4-byte accesses to a bf16 G need an even q and 4-byte aligned pointers
   for (int i = 0; i < c->n; ++i)
@@ -720,11 +727,13 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   c->prof.end(LORDO_K_UP, s);
   c->t = t;
   c->grad_folded = false;
+  ++c->window_steps;
   return LORDO_OK;
 }
 
-// Runs the refresh program on the source table currently selected in EXT_SRC.
-static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s) {
+// Runs the refresh program on the source table currently selected in EXT_SRC; with `fold` the error
+// buffer first takes E <- fold_scale * G + E (Alg. 2, argument of ComputeProjection).
+static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold = false, double fold_scale = 0.0) {
   Plan& P = c->plan;
   const bool rotate = c->t > 0;
   double c1 = 1.0, c2 = 1.0;
@@ -735,6 +744,8 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s) {
   const GemmDesc* descs = c->at<GemmDesc>(P.descs);
   const GemmTile* tiles = c->at<GemmTile>(P.gtiles);
   c->prof.begin(LORDO_K_REFRESH, s);
+  if (fold)
+    HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)fold_scale, c->hp.grad_dtype == LORDO_F32, s));
   for (const Op& op : P.ops) {
     if (op.rot_only && !rotate) continue;
     switch (op.kind) {
@@ -764,6 +775,7 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   if (!c || !Src || !Omega) return LORDO_EINVAL;
   if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
   if (c->grad_folded) return LORDO_ESTATE;          // the error buffer holds a folded gradient: a local step must consume it first
+  if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;   // the buffer is in coordinates of the current Q
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
   if (rc != LORDO_OK) return rc;
@@ -775,6 +787,7 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
 int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {
   if (!c || !G || !Omega || !std::isfinite(grad_scale)) return LORDO_EINVAL;
   if (!c->hp.error_feedback || c->grad_folded) return LORDO_ESTATE;
+  if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   Plan& P = c->plan;
   int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
@@ -785,11 +798,9 @@ int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad
   for (int i = 0; i < c->n; ++i) src[i] = c->dev.arena + P.mat[i].err;
   rc = c->set_ext(EXT_SRC, src.data(), s);
   if (rc != LORDO_OK) return rc;
-  // E <- grad_scale * G + E (Alg. 2, argument of ComputeProjection), then the same refresh program on it
-  HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)grad_scale, c->hp.grad_dtype == LORDO_F32, s));
   c->grad_folded = true;
   c->folded_g.assign(G, G + c->n);
-  return run_refresh(c, LORDO_F32, s);
+  return run_refresh(c, LORDO_F32, s, true, grad_scale);
 }
 
 int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* DeltaOut, void* stream) {
@@ -822,7 +833,69 @@ int lordo_outer_step(lordo_ctx* c, void* const* W, const void* const* AvgDelta, 
   }
   c->prof.begin(LORDO_K_OUTER, s);
   HIPCHK(launch_outer(c->dev, c->at<int64_t>(c->plan.chunk_start), c->plan.nchunks, a, s));
+  if (c->hp.uplink_buffer) HIPCHK(launch_fill_zero(c->at<void>(c->plan.acc), sizeof(float) * c->plan.lr_total, s));
   c->prof.end(LORDO_K_OUTER, s);
+  c->window_steps = 0;
+  return LORDO_OK;
+}
+
+int lordo_export_uplink(lordo_ctx* c, void* const* AccOut, void* stream) {
+  if (!c || !AccOut) return LORDO_EINVAL;
+  if (!c->hp.uplink_buffer) return LORDO_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc = c->set_ext(EXT_DOUT, AccOut, s);
+  if (rc != LORDO_OK) return rc;
+  c->prof.begin(LORDO_K_EXPORT, s);
+  HIPCHK(launch_lr_exchange(c->dev, c->at<float>(c->plan.acc), true, s));
+  c->prof.end(LORDO_K_EXPORT, s);
+  return LORDO_OK;
+}
+
+int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* AvgAcc, void* stream) {
+  if (!c || !W) return LORDO_EINVAL;
+  if (!c->hp.uplink_buffer) return LORDO_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  Plan& P = c->plan;
+  int rc = c->set_ext(EXT_W, W, s);
+  if (rc != LORDO_OK) return rc;
+  if (AvgAcc) {
+    rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(AvgAcc)), s);
+    if (rc != LORDO_OK) return rc;
+  }
+  bool w_vec = true;
+  for (int i = 0; i < c->n; ++i)
+    if ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
+  OuterArgs a;
+  a.lr = (float)c->hp.outer_lr;
+  a.mu = (float)c->hp.outer_momentum;
+  a.nesterov = c->hp.outer_nesterov ? 1 : 0;
+  a.has_mom = c->hp.outer_momentum != 0.0 ? 1 : 0;
+  a.own_delta = 0;
+  const int64_t* chunks = c->at<int64_t>(P.chunk_start);
+  c->prof.begin(LORDO_K_OUTER, s);
+  // the averaged buffer replaces this worker's own (which the step clears anyway); its bf16 hi / lo planes
+  // take the place of N as B operand of the up-projection kernel: Delta = Q A (App. A.5.1)
+  if (AvgAcc) HIPCHK(launch_lr_exchange(c->dev, c->at<float>(P.acc), false, s));
+  HIPCHK(launch_split_planes(c->at<float>(P.acc), c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), P.lr_total, s));
+  // b' = mu b + Delta, W' = anchor - eta_s (Delta + mu b') or anchor - eta_s b': the part without Delta
+  // elementwise, then Delta through the up-projection into W and into b
+  HIPCHK(launch_outer_base(c->dev, chunks, P.nchunks, a, s));
+  UpArgs ua{};
+  ua.coef_g = 0.f; ua.colscale = 0; ua.colpart = nullptr; ua.g_is_f32 = 0; ua.eps = 0.f;
+  ua.target_err = 0;
+  ua.coef_acc = (float)(-c->hp.outer_lr * ((a.has_mom && a.nesterov) ? 1.0 + c->hp.outer_momentum : 1.0));
+  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
+                        c->at<uint16_t>(P.n_lo), ua, s));
+  if (a.has_mom) {
+    ua.target_err = 2;
+    ua.coef_acc = 1.f;
+    HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
+                          c->at<uint16_t>(P.n_lo), ua, s));
+  }
+  HIPCHK(launch_anchor_from_w(c->dev, chunks, P.nchunks, s));
+  HIPCHK(launch_fill_zero(c->at<void>(P.acc), sizeof(float) * P.lr_total, s));
+  c->prof.end(LORDO_K_OUTER, s);
+  c->window_steps = 0;
   return LORDO_OK;
 }
 
@@ -842,6 +915,10 @@ int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, voi
     case LORDO_STATE_ERR:
       if (m.err < 0 || c->grad_folded) return LORDO_ESTATE;      // folded: the buffer holds G + E until the next local step
       HIPCHK(launch_copy_f32(dst, c->at<float>(m.err), (int64_t)m.p * m.q, s));
+      break;
+    case LORDO_STATE_UPLINK:
+      if (P.acc < 0) return LORDO_ESTATE;
+      HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.acc), nullptr, nullptr, dst, 1, 0, s));
       break;
     case LORDO_STATE_U: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.u), nullptr, nullptr, dst, 1, 0, s)); break;
     case LORDO_STATE_V: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.v), nullptr, nullptr, dst, 1, 0, s)); break;
@@ -875,6 +952,10 @@ int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_sr
     case LORDO_STATE_ERR:
       if (m.err < 0 || c->grad_folded) return LORDO_ESTATE;
       HIPCHK(launch_copy_f32(c->at<float>(m.err), src, (int64_t)m.p * m.q, s));
+      break;
+    case LORDO_STATE_UPLINK:
+      if (P.acc < 0) return LORDO_ESTATE;
+      HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.acc), src, s));
       break;
     case LORDO_STATE_U: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.u), src, s)); break;
     case LORDO_STATE_V: HIPCHK(launch_plain_to_lr(c->dev, mat, c->at<float>(P.v), src, s)); break;

@@ -631,7 +631,7 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 // that its latency hides behind it.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __restrict__ tiles,
-                                                 const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr) {
+                                                 const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr, int to_mom) {
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
   const MatDev m = d.mats[t.mat];
@@ -654,7 +654,7 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   // 8*(v/4) + 4*(lane/32) + v%4, column lane%32: the lane supplies its part of the offset, the
   // block / register part is scalar, and a row at or past p gets the size of the resource.
   const uint32_t row_bytes = (uint32_t)q * 4u;
-  const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
+  const rsrc_t rw = make_rsrc(to_mom ? static_cast<void*>(d.arena + m.mom) : ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
   uint32_t voff[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
@@ -813,7 +813,8 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 
   // W tile in row order: lane = (rr, c4): row rr + 8j of a block, columns 4*c4 .. 4*c4+3
   const uint32_t row_bytes = (uint32_t)q * 4u;
-  const void* target = (WITH_G && ua.target_err) ? static_cast<const void*>(d.arena + m.err) : ext_ptr(d, EXT_W, t.mat);
+  const void* target = ua.target_err == 1 ? static_cast<const void*>(d.arena + m.err)
+                       : ua.target_err == 2 ? static_cast<const void*>(d.arena + m.mom) : ext_ptr(d, EXT_W, t.mat);
   const rsrc_t rw = make_rsrc(target, (uint32_t)p * row_bytes);
   const int rr = lane >> 3, c4 = lane & 7;
   uint32_t voff[2];
@@ -974,14 +975,14 @@ hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bo
                           const uint16_t* b_lo, const UpArgs& ua, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
-  const bool with_g = ua.coef_g != 0.f || ua.target_err;
+  const bool with_g = ua.coef_g != 0.f || ua.target_err == 1;
   if (with_g) {
     if (!vec) return hipErrorInvalidValue;       // the gradient-term epilogue exists for 16-byte row accesses only
     hipLaunchKernelGGL((k_proj_up_dma<4, true>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else if (vec) {
     hipLaunchKernelGGL((k_proj_up_dma<4, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else {
-    hipLaunchKernelGGL(k_proj_up, grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc);
+    hipLaunchKernelGGL(k_proj_up, grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc, ua.target_err == 2 ? 1 : 0);
   }
   return hipGetLastError();
 }

@@ -14,13 +14,14 @@ LIB_PATH = os.path.join(HERE, "lib", "liblordo.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE, ENUMERIC = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-STATE_Q, STATE_U, STATE_V, STATE_ANCHOR, STATE_MOM, STATE_GLOW, STATE_NUPD, STATE_ERR = range(8)
+STATE_Q, STATE_U, STATE_V, STATE_ANCHOR, STATE_MOM, STATE_GLOW, STATE_NUPD, STATE_ERR, STATE_UPLINK = range(9)
 
 EXPORTS = [
     "lordo_workspace_bytes", "lordo_init", "lordo_local_step", "lordo_refresh_subspace",
     "lordo_export_pseudograd", "lordo_outer_step", "lordo_get_state", "lordo_set_state",
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
     "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv", "lordo_refresh_subspace_local",
+    "lordo_export_uplink", "lordo_outer_step_lowrank",
 ]
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
@@ -37,15 +38,15 @@ class HParams(C.Structure):
         ("error_feedback", C.c_int32), ("outer_nesterov", C.c_int32),
         ("outer_lr", C.c_double), ("outer_momentum", C.c_double),
         ("power_iters", C.c_int32), ("orth_passes", C.c_int32),
-        ("grad_dtype", C.c_int32), ("reserved", C.c_int32),
+        ("grad_dtype", C.c_int32), ("uplink_buffer", C.c_int32),
     ]
 
 
 def hparams(beta1=0.9, beta2=0.999, eps=1e-8, bias_correction=True, outer_lr=1.0, outer_momentum=0.0,
             outer_nesterov=False, power_iters=2, orth_passes=2, grad_dtype=BF16, qhm_mode=0, omega=1.0,
-            error_feedback=False) -> HParams:
+            error_feedback=False, uplink_buffer=False) -> HParams:
     return HParams(beta1, beta2, eps, int(bias_correction), qhm_mode, omega, int(error_feedback),
-                   int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, 0)
+                   int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, int(uplink_buffer))
 
 
 class LordoError(RuntimeError):
@@ -73,6 +74,8 @@ def load() -> C.CDLL:
     lib.lordo_refresh_subspace_local.argtypes = [vp, vpp, C.c_double, vpp, vp]
     lib.lordo_export_pseudograd.argtypes = [vp, vpp, vpp, vp]
     lib.lordo_outer_step.argtypes = [vp, vpp, vpp, vp]
+    lib.lordo_export_uplink.argtypes = [vp, vpp, vp]
+    lib.lordo_outer_step_lowrank.argtypes = [vp, vpp, vpp, vp]
     lib.lordo_get_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_set_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_get_mssv.argtypes = [vp, vp, vp]
@@ -163,7 +166,7 @@ class Lordo:
         if len(ts) != self.n:
             raise ValueError("one tensor per matrix expected")
         for t, (p, q, r) in zip(ts, self.shapes):
-            want = {"pq": (p, q), "qr": (q, r)}[kind]
+            want = {"pq": (p, q), "qr": (q, r), "rq": (r, q)}[kind]
             if tuple(t.shape) != want or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
                 raise ValueError(f"expected contiguous CUDA {dtype} tensor of shape {want}, got {t.dtype} {tuple(t.shape)}")
 
@@ -203,6 +206,20 @@ class Lordo:
             _check(self.lib.lordo_outer_step(self.ctx, _ptr_array(W), _ptr_array(avg_delta), self._stream()))
         else:
             _check(self.lib.lordo_outer_step(self.ctx, _ptr_array(W), None, self._stream()))
+
+    def export_uplink(self, out):
+        """out_i <- the r x q up-link buffer of matrix i (App. A.5.1)."""
+        self._check_tensors(out, self.torch.float32, "rq")
+        _check(self.lib.lordo_export_uplink(self.ctx, _ptr_array(out), self._stream()))
+
+    def outer_step_lowrank(self, W, avg_acc=None):
+        """Outer step with Delta = Q avg_acc (avg_acc: mean of the workers' exported buffers; None: own buffer)."""
+        self._check_tensors(W, self.torch.float32, "pq")
+        if avg_acc is not None:
+            self._check_tensors(avg_acc, self.torch.float32, "rq")
+            _check(self.lib.lordo_outer_step_lowrank(self.ctx, _ptr_array(W), _ptr_array(avg_acc), self._stream()))
+        else:
+            _check(self.lib.lordo_outer_step_lowrank(self.ctx, _ptr_array(W), None, self._stream()))
 
     # -- state ------------------------------------------------------------------------------------
     def _state_shape(self, mat, which):

@@ -97,6 +97,8 @@ class Pair:
         N_new[amb] = N_gpu[amb]
         weight = self.ohp.omega if self.ohp.qhm_mode == "full" else 1.0      # share of Q N in the update
         self.W_orc[i] = self.W_orc[i] + lr * weight * st.Q @ (st.last_N - N_new)
+        if self.ohp.uplink_buffer:
+            st.A = st.A + lr * (N_new - st.last_N)
         st.last_N = N_new
         return int(amb.sum())
 
@@ -120,6 +122,8 @@ class Pair:
                 # ||A||^2 = ||g||^2 + ||E||^2 for orthonormal Q.
                 scale = np.sqrt(np.sum(st.last_g * st.last_g) + np.sum(st.E * st.E))
                 errs["E"] = float(np.linalg.norm(self.get(i, L.STATE_ERR) - st.E) / max(scale, 1e-300))
+            if self.ohp.uplink_buffer:
+                errs["A"] = rel_l2(self.get(i, L.STATE_UPLINK), st.A)
             for k, e in errs.items():
                 worst[k] = max(worst.get(k, 0.0), e)
                 assert e <= tol, f"matrix {i} {self.shapes[i]}: rel L2 error of {k} = {e:.3e} > {tol}"

@@ -52,7 +52,8 @@ def test_workspace_bytes_scales_and_validates(lib):
     with_ef = lordo.workspace_bytes(shapes, lordo.hparams(error_feedback=True))
     assert with_ef - c2 >= sum(4 * p * q for p, q, r in shapes)          # the residual E
     assert lordo.workspace_bytes(shapes, lordo.hparams(qhm_mode=2, omega=0.9)) > c2   # column sums
-    for bad_hp in (lordo.hparams(qhm_mode=3), lordo.hparams(qhm_mode=1, omega=1.5), lordo.hparams(beta1=1.0),
+    assert lordo.workspace_bytes(shapes, lordo.hparams(uplink_buffer=True)) - c2 >= sum(4 * r * q for p, q, r in shapes)
+    for bad_hp in (lordo.hparams(qhm_mode=3), lordo.hparams(qhm_mode=2, omega=0.9, uplink_buffer=True), lordo.hparams(qhm_mode=1, omega=1.5), lordo.hparams(beta1=1.0),
                    lordo.hparams(power_iters=9), lordo.hparams(orth_passes=5), lordo.hparams(grad_dtype=7)):
         with pytest.raises(lordo.LordoError) as e:
             lordo.workspace_bytes([(8, 8, 4)], bad_hp)

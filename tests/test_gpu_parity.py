@@ -403,6 +403,72 @@ def test_outer_step(torch, mode):
         pass
 
 
+@pytest.mark.parametrize("mode", ["average", "nesterov", "heavy_ball_lowqhm", "own_buffer_unaligned"])
+def test_uplink_buffer_and_lowrank_outer_step(torch, mode):
+    """Up-link time buffer (App. A.5.1): A accumulates eta_t N_t over the window, Q A is the dense
+    pseudo-gradient, and the outer step fed the mean of the workers' buffers matches the oracle's."""
+    from paper_2602_04396_amd import lordo
+    kw = dict(average=dict(outer_lr=1.0), nesterov=dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True),
+              heavy_ball_lowqhm=dict(outer_lr=0.5, outer_momentum=0.8, qhm_mode="low", omega=0.8),
+              own_buffer_unaligned=dict(outer_lr=0.9, outer_momentum=0.5, outer_nesterov=True))[mode]
+    shapes = [(100, 77, 8), (33, 2049, 4), (130, 67, 33)] if mode == "own_buffer_unaligned" else \
+             [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128)]
+    ohp = orc.Hyper(uplink_buffer=True, **kw)
+    gkw = {k: v for k, v in kw.items() if k != "qhm_mode"}
+    ghp = lordo.hparams(uplink_buffer=True, qhm_mode=1 if kw.get("qhm_mode") == "low" else 0, **gkw)
+    pair = Pair(torch, shapes, _weights(shapes, 33), ohp, ghp, _rand_Q(shapes, 33))
+    gens = _spiked(shapes, 33, 4)
+    n = len(shapes)
+    step = 0
+    for window in range(2):
+        for k in range(3):
+            pair.local_step([g.draw(step) for g in gens], lr=1e-3 * (1 + k), first_step_patch=(step == 0))
+            step += 1
+        pair.compare_local(TOL)                                   # includes the buffer A against the oracle's
+        out = [torch.empty(r, q, dtype=torch.float32, device="cuda") for p, q, r in shapes]
+        pair.opt.export_uplink(out)
+        dense = [torch.empty_like(w) for w in pair.W_gpu]
+        pair.opt.export_pseudograd(pair.W_gpu, dense)
+        for i in range(n):
+            assert torch.equal(out[i], pair.opt.get_state(i, lordo.STATE_UPLINK))
+            Qg = pair.get(i, lordo.STATE_Q)
+            assert rel_l2(Qg @ out[i].cpu().numpy().astype(np.float64), dense[i].cpu().numpy()) <= TOL   # anchor - W = Q A
+        with pytest.raises(lordo.LordoError) as e:                # the buffer is in coordinates of the current Q
+            pair.opt.refresh_subspace(pair.to_dev([g.draw(0) for g in gens], True),
+                                      pair.to_dev([np.zeros((q, r), np.float32) for p, q, r in shapes], False))
+        assert e.value.code == lordo.ESTATE
+        if mode == "own_buffer_unaligned":
+            avg = [o.cpu().numpy() for o in out]
+            pair.opt.outer_step_lowrank(pair.W_gpu, None)
+        else:
+            rng = np.random.default_rng(synth.seed_for(33, 700 + window))
+            other = [(rng.standard_normal((r, q)) * 3e-3).astype(np.float32) for p, q, r in shapes]   # another worker's buffer
+            avg = [(0.5 * (out[i].cpu().numpy().astype(np.float64) + other[i])).astype(np.float32) for i in range(n)]
+            pair.opt.outer_step_lowrank(pair.W_gpu, pair.to_dev(avg, False))
+        pair.opt.poll_status()
+        for i in range(n):
+            Wn = orc.outer_step_lowrank(pair.st[i], np.asarray(avg[i], dtype=np.float64), ohp)
+            pair.W_orc[i] = Wn
+            got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
+            assert rel_l2(got - pair.W0[i], Wn - pair.W0[i]) <= TOL, f"{mode} window {window} matrix {i}"
+            assert torch.equal(pair.opt.get_state(i, lordo.STATE_ANCHOR), pair.W_gpu[i])
+            if ohp.outer_momentum != 0:
+                assert rel_l2(pair.get(i, lordo.STATE_MOM), pair.st[i].b) <= TOL
+            assert not pair.opt.get_state(i, lordo.STATE_UPLINK).any()      # a new window starts empty
+    # the dense outer step ends a window too
+    pair.local_step([g.draw(step) for g in gens], lr=1e-3)
+    pair.opt.outer_step(pair.W_gpu, None)
+    assert not pair.opt.get_state(0, lordo.STATE_UPLINK).any()
+    # no buffer configured: the calls say so
+    plain = Pair(torch, shapes[:1], _weights(shapes[:1], 33), orc.Hyper(), lordo.hparams())
+    for call in (lambda: plain.opt.outer_step_lowrank(plain.W_gpu, None),
+                 lambda: plain.opt.export_uplink([torch.empty(shapes[0][2], shapes[0][1], device="cuda")]),
+                 lambda: plain.opt.get_state(0, lordo.STATE_UPLINK)):
+        with pytest.raises(lordo.LordoError) as e:
+            call()
+        assert e.value.code == lordo.ESTATE
+
+
 def test_state_roundtrip_and_errors(torch):
     from paper_2602_04396_amd import lordo
     p, q, r = 70, 45, 9

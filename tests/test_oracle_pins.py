@@ -208,6 +208,51 @@ def test_local_variant_projection_sees_the_error_buffer():
     assert np.abs(st2.E).max() > 1e-3 * np.abs(low).max()
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(qhm_mode="low", omega=0.6), dict(error_feedback=True)])
+def test_uplink_buffer_rebuilds_the_dense_pseudo_gradient(kw):
+    """App. A.5.1: over a window with a fixed Q the dense pseudo-gradient x_{t-K} - x_t equals
+    Q sum_tau eta_tau alpha_tau, so the r x q buffer carries all of it (no QHM and low-rank QHM)."""
+    rng = rng_of(41)
+    p, q, r = 17, 11, 4
+    hp = orc.Hyper(uplink_buffer=True, **kw)
+    W = rng.standard_normal((p, q))
+    st = orc.init_state(W, r, synth.orthonormal(rng, p, r))
+    for k in range(5):
+        W = orc.local_step(st, W, rng.standard_normal((p, q)), 1e-3 * (1 + k), hp)      # a learning-rate schedule
+    assert rel(st.Q @ st.A, orc.pseudo_gradient(st, W)) < 1e-12
+    assert np.linalg.matrix_rank(orc.pseudo_gradient(st, W), tol=1e-10) == r
+
+
+@pytest.mark.parametrize("outer", [dict(outer_lr=1.0), dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True),
+                                   dict(outer_lr=0.5, outer_momentum=0.8)])
+def test_outer_step_from_averaged_buffers_equals_dense_outer_step(outer):
+    """Workers that share Q: the outer step fed the mean of the r x q buffers gives the model and
+    momentum of the outer step fed the mean of the dense pseudo-gradients, over two windows."""
+    rng = rng_of(42)
+    p, q, r, M = 14, 9, 3, 3
+    hp = orc.Hyper(uplink_buffer=True, **outer)
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    low = [orc.init_state(W0, r, Q) for _ in range(M)]
+    dense = [orc.init_state(W0, r, Q) for _ in range(M)]
+    W_low = [W0.copy() for _ in range(M)]
+    W_dense = [W0.copy() for _ in range(M)]
+    for window in range(2):
+        for k in range(3):
+            for m in range(M):
+                G = rng.standard_normal((p, q))
+                W_low[m] = orc.local_step(low[m], W_low[m], G, 2e-3, hp)
+                W_dense[m] = orc.local_step(dense[m], W_dense[m], G, 2e-3, hp)
+        mean_A = sum(st.A for st in low) / M
+        mean_D = sum(orc.pseudo_gradient(dense[m], W_dense[m]) for m in range(M)) / M
+        for m in range(M):
+            W_low[m] = orc.outer_step_lowrank(low[m], mean_A, hp)
+            W_dense[m] = orc.outer_step(dense[m], mean_D, hp)
+            assert rel(W_low[m], W_dense[m]) < 1e-12
+            assert np.abs(low[m].b - dense[m].b).max() < 1e-12
+            assert not low[m].A.any()
+
+
 @pytest.mark.parametrize("mode", ["low", "full"])
 def test_qhm_omega_one_is_no_qhm(mode):
     """Alg. 1: at omega = 1 both QHM cases are the "No QHM" case."""
