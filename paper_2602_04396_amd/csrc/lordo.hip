@@ -363,7 +363,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.mb = (hp.grad_dtype == LORDO_BF16 || rp_max > 64) ? 4 : (rp_max > 32 ? 2 : 1);
   // Down-projection launch shape: the pipelined kernel (rank tiles of 128, bf16 G, 256-column
   // tiles) where it applies, else the plain kernel with 128-column tiles.
-  P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16 && !hp.error_feedback) ? (rp_max >= 256 ? 2 : 1) : 0;
+  P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16) ? (rp_max >= 256 ? 2 : 1) : 0;
   P.rank_tile = P.down_pipe ? 128 * P.down_pipe : 32 * P.mb;
   P.g_once = rp_max <= P.rank_tile;
   const int down_bn = P.down_pipe ? 256 : 128;
@@ -423,7 +423,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the launch has several rounds of workgroups and the epilogue of one overlaps the main loop of
   // another; a launch that needs split-K is a single round of workgroups in lock step, where the
   // stand-alone kernel is as fast and leaves the down-projection shorter.
-  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0 && !hp.uplink_buffer;
+  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0 && !hp.uplink_buffer && !hp.error_feedback;
   P.adam_first = fuse_adam ? lr : 0;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);

@@ -380,7 +380,11 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
 // GONCE: one rank tile per column block, G is read once (streaming loads).
 // A tile marked `fuse` holds the whole contraction (no split-K): its epilogue applies Adam to its
 // elements of the low-rank state instead of leaving that to a separate pass over g.
-template <int RB, bool VEC, bool GONCE>
+// EF: error feedback (Alg. 1): the contraction runs over A = grad_scale * G + E, E the fp32 residual in the
+// arena.  E rows travel with the G rows of their stage; the sum is formed in registers when the stage
+// goes to LDS, as bf16 hi and lo planes (one more 16 KiB plane per stage and a third MFMA pass), and
+// the result is not scaled again.
+template <int RB, bool VEC, bool GONCE, bool EF>
 __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
                                                         int64_t split_stride, float grad_scale, FusedAdam fa) {
   constexpr int BK = 32;
@@ -393,9 +397,10 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
 
   constexpr int GSLOTS = 8 * 4 * 32;                           // (nblk, kgrp, n) 16-byte slots of one stage: 16 KiB
   constexpr int ASLOTS = 4 * RB * 2 * 2 * 64;                  // (mblk, kstep, plane, lane): 16 KiB per 128 rank indices
-  extern __shared__ u32x4 lds_dyn[];                           // 2 stages of each: 64 KiB (RB = 1) or 96 KiB (RB = 2)
+  extern __shared__ u32x4 lds_dyn[];                           // 2 stages of each: 64 KiB (RB = 1) or 96 KiB (RB = 2), + 32 KiB with EF
   u32x4* gfrag = lds_dyn;
-  u32x4* afrag = lds_dyn + 2 * GSLOTS;
+  u32x4* glo = lds_dyn + 2 * GSLOTS;                           // EF: lo plane of the staged sum
+  u32x4* afrag = lds_dyn + (EF ? 4 : 2) * GSLOTS;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -420,6 +425,13 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   gc.off0 = col < m.q ? (uint32_t)col * 2u : OOB;
   gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 2u : OOB;
   const int wslot = ((4 * half + (lane >> 4)) * 4 + kgrp) * 32 + 2 * (lane & 15);
+  // residual E: fp32 p x q in the arena, same rows and columns (8-byte accesses need an even q: VEC)
+  const uint32_t erow_bytes = (uint32_t)m.q * 4u;
+  const rsrc_t re = EF ? make_rsrc(d.arena + m.err, (uint32_t)klim * erow_bytes) : rs;
+  GCol ge;
+  ge.vec = VEC;
+  ge.off0 = col < m.q ? (uint32_t)col * 4u : OOB;
+  ge.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 4u : OOB;
 
   // Q fragments of a stage: (mblk, kstep) pairs, both planes each; 8*RB pairs, RB per wave
   const int64_t kgroups = m.pp / 8;
@@ -448,10 +460,14 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
       for (int i = 0; i < 16; ++i) acc[rb][a][i] = 0.f;
 
   // Operand fragments of one k-step of 16: RB pairs of Q planes and the four G column blocks.
-  struct Frags { u32x4 ah[RB], al[RB], b[4]; };
+  struct Frags { u32x4 ah[RB], al[RB], b[4], bl[EF ? 4 : 1]; };
   auto load_frags = [&](Frags& f, int sbuf, int ks) {
     const u32x4* gb = gfrag + sbuf * GSLOTS;
     const u32x4* ab = afrag + sbuf * ASLOTS;
+    if constexpr (EF) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) f.bl[a] = glo[sbuf * GSLOTS + ((4 * nh + a) * 4 + 2 * ks + (lane >> 5)) * 32 + (lane & 31)];
+    }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       f.ah[rb] = ab[(((mb + 4 * rb) * 2 + ks) * 2 + 0) * 64 + lane];
@@ -469,6 +485,8 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
       for (int rb = 0; rb < RB; ++rb) {
         acc[rb][a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ah[rb]), as_bf(f.b[a]), acc[rb][a], 0, 0, 0);
         acc[rb][a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.al[rb]), as_bf(f.b[a]), acc[rb][a], 0, 0, 0);
+        if constexpr (EF)
+          acc[rb][a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f.ah[rb]), as_bf(f.bl[a]), acc[rb][a], 0, 0, 0);
       }
   };
   auto compute = [&](int sbuf) {
@@ -497,39 +515,60 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   // the resource), so the loads of stages past the last one are issued unconditionally: the number of
   // outstanding loads is then the same in every iteration, which the explicit waits rely on.
   GStage<false> st0, st1;
+  GStage<true> se0, se1;                                       // EF: rows of E of the same stages
+  constexpr int GAUX = GONCE ? STREAM : 0;
+  // outstanding loads of one stage: 8 (or 16 two-byte ones) of G, as many again of E
+  auto wait_one_stage = [&]() {
+    if constexpr (VEC && !EF) WAIT_VM_BARRIER(8);
+    else if constexpr (VEC == EF) WAIT_VM_BARRIER(16);
+    else WAIT_VM_BARRIER(32);
+  };
+  auto stage_out = [&](const GStage<false>& g, const GStage<true>& e, int sbuf) {
+    if constexpr (EF) {
+      GStage<true> sa;
+      add_residual<false>(sa, g, e, grad_scale);
+      store_gstage<true>(sa, gfrag + sbuf * GSLOTS, glo + sbuf * GSLOTS, wslot);
+    } else {
+      store_gstage<false>(g, gfrag + sbuf * GSLOTS, nullptr, wslot);
+    }
+  };
   issue_a(t.k0, 0);
-  load_gstage<false, GONCE ? STREAM : 0>(st0, rs, row_bytes, krow0, klim, gc);                  // stage 0
-  load_gstage<false, GONCE ? STREAM : 0>(st1, rs, row_bytes, krow0 + BK, klim, gc);             // stage 1
-  store_gstage<false>(st0, gfrag, nullptr, wslot);
-  if constexpr (VEC) WAIT_VM_BARRIER(8); else WAIT_VM_BARRIER(16);
+  load_gstage<false, GAUX>(st0, rs, row_bytes, krow0, klim, gc);                  // stage 0
+  if constexpr (EF) load_gstage<true, GAUX>(se0, re, erow_bytes, krow0, klim, ge);
+  load_gstage<false, GAUX>(st1, rs, row_bytes, krow0 + BK, klim, gc);             // stage 1
+  if constexpr (EF) load_gstage<true, GAUX>(se1, re, erow_bytes, krow0 + BK, klim, ge);
+  stage_out(st0, se0, 0);
+  wait_one_stage();
 
   // one iteration; NEXT holds stage s+1 (read one iteration ago), LOAD receives stage s+2
-#define LORDO_DOWN_ITER(S, NEXT, LOAD)                                                            \
+#define LORDO_DOWN_ITER(S, NEXT, LOAD, NEXTE, LOADE)                                              \
   {                                                                                               \
     const int kr = t.k0 + (S) * BK;                                                               \
     if ((S) + 1 < nstages) issue_a(kr + BK, ((S) + 1) & 1);                                       \
-    load_gstage<false, GONCE ? STREAM : 0>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc); \
+    load_gstage<false, GAUX>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc);              \
+    if constexpr (EF) load_gstage<true, GAUX>(LOADE, re, erow_bytes, krow0 + ((S) + 2) * BK, klim, ge); \
     ISSUE_FENCE();                                                                                \
     compute((S) & 1);                                                                             \
     ISSUE_FENCE();                                                                                \
-    store_gstage<false>(NEXT, gfrag + (((S) + 1) & 1) * GSLOTS, nullptr, wslot);                  \
-    if constexpr (VEC) WAIT_VM_BARRIER(8); else WAIT_VM_BARRIER(16);                              \
+    stage_out(NEXT, NEXTE, ((S) + 1) & 1);                                                        \
+    wait_one_stage();                                                                             \
   }
   // two stages per trip so that the two register sets alternate statically; the odd last stage is
   // peeled (an exit in the middle of the trip would make the compiler treat loads as outstanding
   // at the loop head that are not)
   int s = 0;
   for (; s + 1 < nstages; s += 2) {
-    LORDO_DOWN_ITER(s, st1, st0)
-    LORDO_DOWN_ITER(s + 1, st0, st1)
+    LORDO_DOWN_ITER(s, st1, st0, se1, se0)
+    LORDO_DOWN_ITER(s + 1, st0, st1, se0, se1)
   }
-  if (s < nstages) LORDO_DOWN_ITER(s, st1, st0)
+  if (s < nstages) LORDO_DOWN_ITER(s, st1, st0, se1, se0)
 #undef LORDO_DOWN_ITER
 
   const int64_t base = m.lr_off;
   GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + base;
   const bool fuse = t.fuse != 0 && fa.u != nullptr;            // uniform over the workgroup
   const int64_t rgroups = m.rp / 8;
+  const float osc = EF ? 1.f : grad_scale;                     // with error feedback the scale went into the staged sum
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     if (!active[rb]) continue;
@@ -545,8 +584,8 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
           f32x4 val;
-          val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
-          val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
+          val.x = osc * acc[rb][a][4 * vq];     val.y = osc * acc[rb][a][4 * vq + 1];
+          val.z = osc * acc[rb][a][4 * vq + 2]; val.w = osc * acc[rb][a][4 * vq + 3];
           *reinterpret_cast<GAS f32x4*>(out + offset_of(nbg, vq)) = val;
         }
       }
@@ -569,13 +608,45 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
       for (int vq = 0; vq < 4; ++vq) {
         const int64_t o = offset_of(nbg, vq);
         f32x4 val;
-        val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
-        val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
+        val.x = osc * acc[rb][a][4 * vq];     val.y = osc * acc[rb][a][4 * vq + 1];
+        val.z = osc * acc[rb][a][4 * vq + 2]; val.w = osc * acc[rb][a][4 * vq + 3];
         *reinterpret_cast<GAS f32x4*>(out + o) = val;
         adam4(fa, base + o, val, uu[vq], vv[vq]);
       }
     }
   }
+}
+
+// One instantiation of the pipelined kernel; its dynamic LDS (64 KiB for 128-rank tiles, 96 KiB for
+// 256-rank tiles, 32 KiB more with error feedback) is raised above the default limit at first use.
+template <int RB, bool VEC, bool GONCE, bool EF>
+static hipError_t launch_pipe(dim3 grid, const DevCtx& d, const ProjTile* tiles, float* glow, int64_t split_stride,
+                              float grad_scale, const FusedAdam& fa, hipStream_t s) {
+  constexpr int LDS_BYTES = (RB == 2 ? 98304 : 65536) + (EF ? 32768 : 0);
+  static bool raised = false;
+  if (LDS_BYTES > 65536 && !raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_down_pipe<RB, VEC, GONCE, EF>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL((k_proj_down_pipe<RB, VEC, GONCE, EF>), grid, dim3(512), LDS_BYTES, s, d, tiles, glow, split_stride, grad_scale, fa);
+  return hipGetLastError();
+}
+template <int RB, bool EF>
+static hipError_t launch_pipe_vo(bool g_vec, bool g_once, dim3 grid, const DevCtx& d, const ProjTile* tiles, float* glow,
+                                 int64_t split_stride, float grad_scale, const FusedAdam& fa, hipStream_t s) {
+  if (g_once) return g_vec ? launch_pipe<RB, true, true, EF>(grid, d, tiles, glow, split_stride, grad_scale, fa, s)
+                           : launch_pipe<RB, false, true, EF>(grid, d, tiles, glow, split_stride, grad_scale, fa, s);
+  return g_vec ? launch_pipe<RB, true, false, EF>(grid, d, tiles, glow, split_stride, grad_scale, fa, s)
+               : launch_pipe<RB, false, false, EF>(grid, d, tiles, glow, split_stride, grad_scale, fa, s);
+}
+static hipError_t launch_pipe_select(int rb, bool g_vec, bool g_once, bool ef, dim3 grid, const DevCtx& d, const ProjTile* tiles,
+                                     float* glow, int64_t split_stride, float grad_scale, const FusedAdam& fa, hipStream_t s) {
+  if (rb == 2) return ef ? launch_pipe_vo<2, true>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)
+                         : launch_pipe_vo<2, false>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s);
+  return ef ? launch_pipe_vo<1, true>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)
+            : launch_pipe_vo<1, false>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s);
 }
 
 hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_rb, bool g_vec, bool g_once, float* glow,
@@ -589,28 +660,7 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
       fa.b1 = fuse->a.b1; fa.omb1 = fuse->a.omb1; fa.b2 = fuse->a.b2; fa.omb2 = fuse->a.omb2;
       fa.inv_c1 = fuse->a.inv_c1; fa.inv_c2 = fuse->a.inv_c2; fa.eps = fuse->a.eps;
     }
-    // dynamic LDS: 64 KiB for 128-rank tiles, 96 KiB for 256-rank tiles (raised above the default limit once)
-    static bool lds_raised = false;
-    if (!lds_raised) {
-      const void* big[4] = {reinterpret_cast<const void*>(k_proj_down_pipe<2, true, true>), reinterpret_cast<const void*>(k_proj_down_pipe<2, true, false>),
-                            reinterpret_cast<const void*>(k_proj_down_pipe<2, false, true>), reinterpret_cast<const void*>(k_proj_down_pipe<2, false, false>)};
-      for (const void* f : big) {
-        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 98304);
-        if (e != hipSuccess) return e;
-      }
-      lds_raised = true;
-    }
-#define LORDO_PIPE(RBV, VECV, ONCEV)                                                                              \
-  hipLaunchKernelGGL((k_proj_down_pipe<RBV, VECV, ONCEV>), grid, dim3(512), (RBV == 2 ? 98304 : 65536), s, d, tiles, glow, split_stride, grad_scale, fa)
-    if (pipe_rb == 2) {
-      if (g_once) { if (g_vec) LORDO_PIPE(2, true, true); else LORDO_PIPE(2, false, true); }
-      else { if (g_vec) LORDO_PIPE(2, true, false); else LORDO_PIPE(2, false, false); }
-    } else {
-      if (g_once) { if (g_vec) LORDO_PIPE(1, true, true); else LORDO_PIPE(1, false, true); }
-      else { if (g_vec) LORDO_PIPE(1, true, false); else LORDO_PIPE(1, false, false); }
-    }
-#undef LORDO_PIPE
-    return hipGetLastError();
+    return launch_pipe_select(pipe_rb, g_vec, g_once, ef, grid, d, tiles, glow, split_stride, grad_scale, fa, s);
   }
 #define LORDO_DOWN(MBV)                                                                                            \
   if (ef && g_is_f32) hipLaunchKernelGGL((k_proj_down<MBV, true, 1, true>), grid, block, 0, s, d, tiles, glow, split_stride, grad_scale); \
