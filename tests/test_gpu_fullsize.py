@@ -74,6 +74,81 @@ def test_c2_full_size_sampled_columns():
         assert torch.isfinite(W[i]).all()
 
 
+@pytest.mark.parametrize("variant", ["global", "ef_lowqhm_uplink"])
+def test_c2_full_size_variants_sampled_columns(variant):
+    """The optional update cases at the benchmark's size and launch shape (split-K down-projection with
+    the residual in its pipeline, gradient-term epilogues, up-link buffer): error feedback with full-rank
+    QHM (the paper's global variant), and error feedback with low-rank QHM and the up-link buffer followed
+    by the outer step from that buffer.  Every formula acts column by column, so sampled columns serve."""
+    import torch
+    import bench
+    from paper_2602_04396_amd import lordo
+    shapes, W, G, Omega, D, grad_dtype = bench.build_workload(torch, lordo, synth, "c2", None, 3)
+    full = variant == "global"
+    omega = 0.9 if full else 0.8
+    outer = dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True)
+    hp = lordo.hparams(power_iters=2, error_feedback=True, qhm_mode=2 if full else 1, omega=omega, uplink_buffer=not full, **outer)
+    ohp = orc.Hyper(error_feedback=True, qhm_mode="full" if full else "low", omega=omega, uplink_buffer=not full, **outer)
+    W0 = [w.clone() for w in W]
+    opt = lordo.Lordo(shapes, hp, W, torch)
+    Wp = opt.ptrs(W)
+    Gp = [opt.ptrs(g, grad_dtype) for g in G]
+    opt.refresh_subspace(Gp[0], opt.ptrs(Omega, torch.float32, "qr"))
+    opt.poll_status()
+    rng = np.random.default_rng(synth.seed_for(2, 4343))
+    picked = [0, 4, 5, 71]
+    sample = {}
+    for i in picked:
+        p, q, r = shapes[i]
+        Q = opt.get_state(i, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+        cols = np.unique(np.concatenate([[0, q - 1, 127, 128, 255, 256], rng.integers(0, q, 10)]))
+        st = orc.init_state(W0[i][:, cols].cpu().numpy().astype(np.float64), r, Q)
+        sample[i] = dict(Q=Q, cols=cols, st=st, W=st.anchor.copy())
+
+    def cols_of(i, which):
+        return opt.get_state(i, which).cpu().numpy().astype(np.float64)[:, sample[i]["cols"]]
+
+    for step, lr in enumerate([1e-3, 2e-3]):
+        opt.local_step(Wp, Gp[1 + step], lr, grad_scale=0.9)
+        torch.cuda.synchronize()
+        for i in picked:
+            sm = sample[i]
+            st, Q, cols = sm["st"], sm["Q"], sm["cols"]
+            Gc = G[1 + step][i][:, cols].float().cpu().numpy().astype(np.float64)
+            sm["W"] = orc.local_step(st, sm["W"], Gc, lr, ohp, grad_scale=0.9)
+            n_gpu = cols_of(i, lordo.STATE_NUPD)
+            if step == 0:      # the first update is the sign of g: take the library's where g is zero to working precision
+                amb = np.abs(st.last_g) < 1e-4 * np.sqrt(np.mean(st.last_g ** 2))
+                assert np.all(np.abs(n_gpu[amb]) <= 1 + 1e-6)
+                N_new = np.where(amb, n_gpu, st.last_N)
+                sm["W"] = sm["W"] + lr * (omega if full else 1.0) * Q @ (st.last_N - N_new)
+                if ohp.uplink_buffer:
+                    st.A = st.A + lr * (N_new - st.last_N)
+                st.last_N = N_new
+            where = f"{variant}, matrix {i}, step {step}"
+            assert rel_l2(cols_of(i, lordo.STATE_GLOW), st.last_g) <= TOL, "g, " + where
+            assert rel_l2(cols_of(i, lordo.STATE_U), st.u) <= TOL, "u, " + where
+            assert rel_l2(cols_of(i, lordo.STATE_V), st.v) <= TOL, "v, " + where
+            assert rel_l2(n_gpu, st.last_N) <= TOL, "N, " + where
+            W_now = W[i][:, cols].cpu().numpy().astype(np.float64)
+            assert rel_l2(W_now - st.anchor, sm["W"] - st.anchor) <= TOL, "weight change, " + where
+            a_norm = np.sqrt(np.sum(st.last_g ** 2) + np.sum(st.E ** 2))       # E = A - Q g: error relative to ||A||
+            assert np.linalg.norm(cols_of(i, lordo.STATE_ERR) - st.E) <= TOL * a_norm, "E, " + where
+            if ohp.uplink_buffer:
+                assert rel_l2(cols_of(i, lordo.STATE_UPLINK), st.A) <= TOL, "A, " + where
+    if ohp.uplink_buffer:
+        opt.outer_step_lowrank(Wp, None)
+        torch.cuda.synchronize()
+        for i in picked:
+            sm = sample[i]
+            Wn = orc.outer_step_lowrank(sm["st"], sm["st"].A.copy(), ohp)
+            got = W[i][:, sm["cols"]].cpu().numpy().astype(np.float64)
+            W0c = W0[i][:, sm["cols"]].cpu().numpy().astype(np.float64)
+            assert rel_l2(got - W0c, Wn - W0c) <= TOL, f"outer step from the buffer, matrix {i}"
+            assert torch.equal(opt.get_state(i, lordo.STATE_ANCHOR), W[i])
+    opt.poll_status()
+
+
 def test_many_tiles_fused_adam_sampled_columns():
     """A launch with so many down-projection tiles that no matrix is split: the Adam update then runs
     in the epilogue of the down-projection.  One short, very wide matrix (160 x 393216, r = 128) keeps
