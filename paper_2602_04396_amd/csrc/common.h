@@ -113,6 +113,10 @@ struct UpArgs {
   int32_t g_is_f32;       // element type of G
   float eps;
   const float* colpart;   // column sums left by the Adam kernel (colscale == 1)
+  // outer step from the up-link buffers: target W, coef_acc = -eta_s, B = averaged buffer; the epilogue reads the
+  // anchor instead of W and also writes the anchor and the momentum b
+  int32_t outer, nesterov, has_mom;
+  float mu;
 };
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* b_hi,
                           const uint16_t* b_lo, const UpArgs& ua, hipStream_t s);

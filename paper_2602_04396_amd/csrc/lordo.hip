@@ -877,12 +877,25 @@ int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* Av
   // take the place of N as B operand of the up-projection kernel: Delta = Q A (App. A.5.1)
   if (AvgAcc) HIPCHK(launch_lr_exchange(c->dev, c->at<float>(P.acc), false, s));
   HIPCHK(launch_split_planes(c->at<float>(P.acc), c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), P.lr_total, s));
-  // b' = mu b + Delta, W' = anchor - eta_s (Delta + mu b') or anchor - eta_s b': the part without Delta
-  // elementwise, then Delta through the up-projection into W and into b
-  HIPCHK(launch_outer_base(c->dev, chunks, P.nchunks, a, s));
   UpArgs ua{};
   ua.coef_g = 0.f; ua.colscale = 0; ua.colpart = nullptr; ua.g_is_f32 = 0; ua.eps = 0.f;
   ua.target_err = 0;
+  if (w_vec) {
+    // one pass: Delta = Q A stays in the accumulators of the up-projection kernel, whose epilogue reads the
+    // anchor and the momentum and writes W, the anchor and the momentum
+    ua.outer = 1; ua.nesterov = a.nesterov; ua.has_mom = a.has_mom; ua.mu = a.mu;
+    ua.coef_acc = (float)-c->hp.outer_lr;
+    HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), true, c->at<uint16_t>(P.n_hi),
+                          c->at<uint16_t>(P.n_lo), ua, s));
+    HIPCHK(launch_fill_zero(c->at<void>(P.acc), sizeof(float) * P.lr_total, s));
+    c->prof.end(LORDO_K_OUTER, s);
+    c->window_steps = 0;
+    return LORDO_OK;
+  }
+  // any q, any alignment of W: b' = mu b + Delta, W' = anchor - eta_s (Delta + mu b') or anchor - eta_s b' in
+  // separate passes -- the part without Delta elementwise, then Delta through the fallback up-projection
+  // kernel into W and into b, then anchor <- W
+  HIPCHK(launch_outer_base(c->dev, chunks, P.nchunks, a, s));
   ua.coef_acc = (float)(-c->hp.outer_lr * ((a.has_mom && a.nesterov) ? 1.0 + c->hp.outer_momentum : 1.0));
   HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
                         c->at<uint16_t>(P.n_lo), ua, s));

@@ -812,9 +812,15 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 //     coef_g = -eta*(1-omega)*grad_scale, c_j = 1 / mean_i(sqrt(v_hat_ij) + eps);
 //   error-feedback residual (Alg. 1 error-feedback lines): target E, B = g, coef_acc = -1, coef_g = grad_scale, c_j = 1
 //     (E <- grad_scale*G + E - Q g).
-template <int NW, bool WITH_G>     // NW waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64)
+// EPI = 2 is the outer step fed from the averaged up-link buffers (App. A.5.1; Alg. 1 OuterOpt): B = mean of the buffers,
+//   Delta = Q B stays in the accumulators, the tile that is read is the anchor, and the epilogue does
+//   b <- mu b + Delta;  x <- anchor - eta_s (Delta + mu b) (Nesterov), anchor - eta_s b (heavy ball) or anchor - eta_s Delta
+//   (no momentum);  W <- x, anchor <- x.
+template <int NW, int EPI>         // NW waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64); EPI 0 plain, 1 gradient term, 2 outer step
 __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
                                                          const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, UpArgs ua) {
+  constexpr bool WITH_G = EPI == 1;
+  constexpr bool OUTER = EPI == 2;
   const float lr = -ua.coef_acc;
   constexpr int AM = NW == 4 ? 2 : 1;                      // row blocks per wave
   constexpr int WM = 4 / AM;                               // wave rows
@@ -865,7 +871,11 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   const uint32_t row_bytes = (uint32_t)q * 4u;
   const void* target = ua.target_err == 1 ? static_cast<const void*>(d.arena + m.err)
                        : ua.target_err == 2 ? static_cast<const void*>(d.arena + m.mom) : ext_ptr(d, EXT_W, t.mat);
-  const rsrc_t rw = make_rsrc(target, (uint32_t)p * row_bytes);
+  const rsrc_t rw_out = make_rsrc(target, (uint32_t)p * row_bytes);
+  // outer step: the tile read before the contraction is the anchor; the momentum tile is read in the epilogue
+  const rsrc_t ranchor = make_rsrc(d.arena + m.anchor, (uint32_t)p * row_bytes);
+  const rsrc_t rmom = make_rsrc(d.arena + (OUTER && ua.has_mom ? m.mom : m.anchor), (uint32_t)p * row_bytes);
+  const rsrc_t rw = OUTER ? ranchor : rw_out;
   const int rr = lane >> 3, c4 = lane & 7;
   uint32_t voff[2];
 #pragma unroll
@@ -1004,6 +1014,13 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 #pragma unroll
         for (int j = 0; j < 4; ++j) gt[j] = g_term(a, b, j);
       }
+      u32x4 mv[4];
+      if constexpr (OUTER) {
+        if (ua.has_mom) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) mv[j] = __builtin_amdgcn_raw_buffer_load_b128(rmom, voff[b], w_soff(a, b, j), STREAM);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
@@ -1016,7 +1033,26 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
           o.x = __float_as_uint(__uint_as_float(o.x) + gt[j].x); o.y = __float_as_uint(__uint_as_float(o.y) + gt[j].y);
           o.z = __float_as_uint(__uint_as_float(o.z) + gt[j].z); o.w = __float_as_uint(__uint_as_float(o.w) + gt[j].w);
         }
-        __builtin_amdgcn_raw_buffer_store_b128(o, rw, voff[b], w_soff(a, b, j), STREAM);
+        if constexpr (OUTER) {
+          f32x4 step = x;                                    // Delta
+          if (ua.has_mom) {
+            const f32x4 bo = {__uint_as_float(mv[j].x), __uint_as_float(mv[j].y), __uint_as_float(mv[j].z), __uint_as_float(mv[j].w)};
+            f32x4 bn;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              bn[e] = fmaf(ua.mu, bo[e], x[e]);
+              step[e] = ua.nesterov ? fmaf(ua.mu, bn[e], x[e]) : bn[e];
+            }
+            u32x4 bs = {__float_as_uint(bn.x), __float_as_uint(bn.y), __float_as_uint(bn.z), __float_as_uint(bn.w)};
+            __builtin_amdgcn_raw_buffer_store_b128(bs, rmom, voff[b], w_soff(a, b, j), STREAM);
+          }
+          o.x = __float_as_uint(fmaf(-lr, step.x, __uint_as_float(wv[a][b][j].x)));
+          o.y = __float_as_uint(fmaf(-lr, step.y, __uint_as_float(wv[a][b][j].y)));
+          o.z = __float_as_uint(fmaf(-lr, step.z, __uint_as_float(wv[a][b][j].z)));
+          o.w = __float_as_uint(fmaf(-lr, step.w, __uint_as_float(wv[a][b][j].w)));
+          __builtin_amdgcn_raw_buffer_store_b128(o, ranchor, voff[b], w_soff(a, b, j), STREAM);
+        }
+        __builtin_amdgcn_raw_buffer_store_b128(o, rw_out, voff[b], w_soff(a, b, j), STREAM);
       }
     }
 }
@@ -1026,11 +1062,14 @@ hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bo
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
   const bool with_g = ua.coef_g != 0.f || ua.target_err == 1;
-  if (with_g) {
+  if (ua.outer) {
+    if (!vec) return hipErrorInvalidValue;       // the outer-step epilogue exists for 16-byte row accesses only
+    hipLaunchKernelGGL((k_proj_up_dma<4, 2>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+  } else if (with_g) {
     if (!vec) return hipErrorInvalidValue;       // the gradient-term epilogue exists for 16-byte row accesses only
-    hipLaunchKernelGGL((k_proj_up_dma<4, true>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    hipLaunchKernelGGL((k_proj_up_dma<4, 1>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else if (vec) {
-    hipLaunchKernelGGL((k_proj_up_dma<4, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    hipLaunchKernelGGL((k_proj_up_dma<4, 0>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else {
     hipLaunchKernelGGL(k_proj_up, grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc, ua.target_err == 2 ? 1 : 0);
   }
