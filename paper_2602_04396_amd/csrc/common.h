@@ -168,6 +168,11 @@ hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
 hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
 hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);
 hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s);
+hipError_t launch_pack_y(const DevCtx& d, int ybuf, hipStream_t s);
+hipError_t launch_pack_block(const DevCtx& d, int zbuf, uint16_t* p_hi, uint16_t* p_lo, hipStream_t s);
+hipError_t launch_src_times_block(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* b_hi, const uint16_t* b_lo,
+                                  hipStream_t s);
+hipError_t launch_glow_to_z(const DevCtx& d, const float* glow, int zbuf, const AdamArgs& a, hipStream_t s);
 // state exchange with plain row-major buffers (one matrix)
 hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, const uint16_t* n_hi, const uint16_t* n_lo,
                               float* dst, int nsplit, int64_t stride, hipStream_t s);

@@ -284,6 +284,86 @@ __global__ __launch_bounds__(256) void k_q_from_y(DevCtx d, int ybuf) {
   int64_t total = (int64_t)m.p * m.r;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) q32[i] = y[i];
 }
+// Range-finder product Z = Src^T Y on the down-projection kernel (Alg. 2 of the refresh: the product has the
+// shape of g = Q^T G with Y in the place of Q): Y (plain p x r, buffer ybuf) -> the down-projection operand
+// planes.  The planes hold Q between refreshes; the refresh repacks them from the new Q when it ends.
+__global__ __launch_bounds__(256) void k_pack_y(DevCtx d, int ybuf) {
+  const MatDev& m = d.mats[blockIdx.y];
+  const float* y = reinterpret_cast<const float*>(d.arena + m.y[ybuf]);
+  uint16_t* qt_hi = reinterpret_cast<uint16_t*>(d.arena + m.qt_hi);
+  uint16_t* qt_lo = reinterpret_cast<uint16_t*>(d.arena + m.qt_lo);
+  const int64_t ngroups = (int64_t)m.pp * m.rp / 8;
+  const int64_t per_ib = (int64_t)(m.pp / 8) * 32;
+  // thread -> (rank block, row octet, rank in block) with the rank fastest: reads of one row are contiguous
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
+    const int64_t ib = g / per_ib, rem = g % per_ib;
+    const int64_t k8 = rem / 32, i = ib * 32 + rem % 32;
+    uint32_t hi[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int64_t row = k8 * 8 + e;
+      const float x = (row < m.p && i < m.r) ? y[row * m.r + i] : 0.0f;
+      split_bf(x, hi[e], lo[e]);
+    }
+    *reinterpret_cast<uint4*>(qt_hi + g * 8) = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+    *reinterpret_cast<uint4*>(qt_lo + g * 8) = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+  }
+}
+hipError_t launch_pack_y(const DevCtx& d, int ybuf, hipStream_t s) {
+  hipLaunchKernelGGL(k_pack_y, dim3(128, d.n), dim3(256), 0, s, d, ybuf);
+  return hipGetLastError();
+}
+// The result of that product, left by the down-projection kernel in the layout of g (split-K slices
+// included), as the plain q x r block Z: Z[j][i] = sum over slices of g(i, j), slices added in order.
+__global__ __launch_bounds__(256) void k_glow_to_z(DevCtx d, const float* __restrict__ glow, int zbuf, AdamArgs a) {
+  const MatDev& m = d.mats[blockIdx.y];
+  float* z = reinterpret_cast<float*>(d.arena + m.zw[zbuf]);
+  int nsplit = a.grp_nsplit[0];
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (m.lr_off >= a.grp_start[i]) nsplit = a.grp_nsplit[i];
+  const int64_t total = (int64_t)m.q * m.r;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t j = t / m.r, i = t % m.r;
+    const int64_t src = m.lr_off + bl_index(j, i, m.rp);
+    float acc = glow[src];
+    for (int sp = 1; sp < nsplit; ++sp) acc += glow[src + sp * a.split_stride];
+    z[t] = acc;
+  }
+}
+hipError_t launch_glow_to_z(const DevCtx& d, const float* glow, int zbuf, const AdamArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_glow_to_z, dim3(64, d.n), dim3(256), 0, s, d, glow, zbuf, a);
+  return hipGetLastError();
+}
+// The q x r block of the products Y = Src B (B = Omega from the caller's table when zbuf < 0, else the
+// orthonormalised Z in buffer zbuf) as bf16 hi / lo planes in operand layout (m = rank, k = column j),
+// at this matrix's place in the flat plane arrays.
+__global__ __launch_bounds__(256) void k_pack_block(DevCtx d, int zbuf, uint16_t* __restrict__ p_hi, uint16_t* __restrict__ p_lo) {
+  const MatDev& m = d.mats[blockIdx.y];
+  const float* z = zbuf < 0 ? reinterpret_cast<const float*>(ext_ptr(d, EXT_OMEGA, blockIdx.y))
+                            : reinterpret_cast<const float*>(d.arena + m.zw[zbuf]);
+  uint16_t* hi_p = p_hi + m.lr_off;
+  uint16_t* lo_p = p_lo + m.lr_off;
+  const int64_t ngroups = (int64_t)m.qp * m.rp / 8;
+  const int64_t per_ib = (int64_t)(m.qp / 8) * 32;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
+    const int64_t ib = g / per_ib, rem = g % per_ib;
+    const int64_t k8 = rem / 32, i = ib * 32 + rem % 32;       // rank fastest over the threads: reads of one row of Z are contiguous
+    uint32_t hi[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int64_t j = k8 * 8 + e;
+      const float x = (j < m.q && i < m.r) ? z[j * m.r + i] : 0.0f;
+      split_bf(x, hi[e], lo[e]);
+    }
+    *reinterpret_cast<uint4*>(hi_p + g * 8) = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+    *reinterpret_cast<uint4*>(lo_p + g * 8) = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+  }
+}
+hipError_t launch_pack_block(const DevCtx& d, int zbuf, uint16_t* p_hi, uint16_t* p_lo, hipStream_t s) {
+  hipLaunchKernelGGL(k_pack_block, dim3(128, d.n), dim3(256), 0, s, d, zbuf, p_hi, p_lo);
+  return hipGetLastError();
+}
 hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s) {
   hipLaunchKernelGGL(k_q_from_y, dim3(128, d.n), dim3(256), 0, s, d, ybuf);
   return hipGetLastError();

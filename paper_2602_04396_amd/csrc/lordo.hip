@@ -5,6 +5,7 @@
 #include "../../include/lordo.h"
 #include "common.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -35,6 +36,8 @@ struct Op {
   int iarg = 0;                     // OP_POTF2: block index; OP_Q_FROM_Y: y buffer
   float farg = 0.f;                 // OP_SHIFT: coefficient
   bool rot_only = false;            // part of the moment rotation (skipped while t == 0)
+  int fast = 0;                     // OP_GEMM: 1 = the product Z = Src^T Y, which the down-projection kernel can take over (iarg: y buffer);
+                                    // 2 = a product Y = Src B for the source-streaming kernel (iarg: z buffer of B, -1 = Omega)
 };
 
 struct Plan {
@@ -58,7 +61,9 @@ struct Plan {
   int64_t flag, mats, ext, chunk_start, down_tiles, up_tiles, descs, gtiles, glow, u, v, n_hi, n_lo;
   std::vector<MatDev> mat;
   std::vector<int64_t> chunk_start_h;
-  std::vector<ProjTile> down_h, up_h;
+  std::vector<ProjTile> down_h, up_h, ytile_h;       // ytile: 128 rows x 128 ranks tiles of the products Y = Src B
+  int64_t ytiles = 0;
+  bool y_fast_shapes = false;       // every matrix has q % 32 == 0 and r % 4 == 0
   std::vector<GemmDesc> desc_h;
   std::vector<GemmTile> gtile_h;
   std::vector<Op> ops;
@@ -266,6 +271,8 @@ struct ProgramBuilder {
       g.M = m.p; g.N = m.r; g.K = m.q;
       return true;
     });
+    P.ops.back().fast = 2;
+    P.ops.back().iarg = -1;
     // Inside the power iteration the blocks only have to stay well conditioned (any basis of the
     // same span serves the next product), so one shifted CholeskyQR pass is enough there; the basis
     // that becomes Q gets the full number of passes.
@@ -280,6 +287,8 @@ struct ProgramBuilder {
         g.M = m.q; g.N = m.r; g.K = m.p;
         return true;
       });
+      P.ops.back().fast = 1;
+      P.ops.back().iarg = ycur;
       int zcur = orth(false, 0, 1);
       // Y = Src Z
       gemm([&](int i, GemmDesc& g) {
@@ -290,6 +299,8 @@ struct ProgramBuilder {
         g.M = m.p; g.N = m.r; g.K = m.q;
         return true;
       });
+      P.ops.back().fast = 2;
+      P.ops.back().iarg = zcur;
       ycur = orth(true, 0, it + 1 < power_iters ? 1 : passes);
     }
     // rotation: R = Q_new^T Q_old (and R o R)
@@ -483,6 +494,25 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.up_h = xcd_order(up);
   P.down_tiles = A.take(sizeof(ProjTile) * P.down_h.size());
   P.up_tiles = A.take(sizeof(ProjTile) * P.up_h.size());
+  {   // products Y = Src B of the refresh: tiles of 128 rows x 128 rank indices, matrices with a long contraction first
+    std::vector<ProjTile> yt;
+    std::vector<int> order(n);
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return P.mat[a].q > P.mat[b].q; });
+    P.y_fast_shapes = true;
+    for (int i : order) {
+      const MatDev& m = P.mat[i];
+      if ((m.q & 31) != 0 || (m.r & 3) != 0) P.y_fast_shapes = false;
+      for (int m0 = 0; m0 < m.pp; m0 += 128)
+        for (int n0 = 0; n0 < m.rp; n0 += 128) {
+          ProjTile t{};
+          t.mat = i; t.m0 = m0; t.n0 = n0;
+          yt.push_back(t);
+        }
+    }
+    P.ytile_h = yt;            // launch order = list order: workgroups with the longest contraction start first
+    P.ytiles = A.take(sizeof(ProjTile) * P.ytile_h.size());
+  }
   // refresh program
   ProgramBuilder pb(P, n);
   pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes);
@@ -624,6 +654,7 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
   INITCHK(hipMemcpy(c->at<void>(P.chunk_start), P.chunk_start_h.data(), sizeof(int64_t) * (n + 1), hipMemcpyHostToDevice));
   INITCHK(hipMemcpy(c->at<void>(P.down_tiles), P.down_h.data(), sizeof(ProjTile) * P.down_h.size(), hipMemcpyHostToDevice));
   INITCHK(hipMemcpy(c->at<void>(P.up_tiles), P.up_h.data(), sizeof(ProjTile) * P.up_h.size(), hipMemcpyHostToDevice));
+  INITCHK(hipMemcpy(c->at<void>(P.ytiles), P.ytile_h.data(), sizeof(ProjTile) * P.ytile_h.size(), hipMemcpyHostToDevice));
   if (!P.desc_h.empty())
     INITCHK(hipMemcpy(c->at<void>(P.descs), P.desc_h.data(), sizeof(GemmDesc) * P.desc_h.size(), hipMemcpyHostToDevice));
   if (!P.gtile_h.empty())
@@ -733,7 +764,8 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
 
 // Runs the refresh program on the source table currently selected in EXT_SRC; with `fold` the error
 // buffer first takes E <- fold_scale * G + E (Alg. 2, argument of ComputeProjection).
-static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold = false, double fold_scale = 0.0) {
+static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold = false, double fold_scale = 0.0,
+                       bool proj_kernels = false, bool stream_kernel = false) {
   Plan& P = c->plan;
   const bool rotate = c->t > 0;
   double c1 = 1.0, c2 = 1.0;
@@ -750,6 +782,26 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
     if (op.rot_only && !rotate) continue;
     switch (op.kind) {
       case OP_GEMM:
+        if (op.fast == 1 && proj_kernels) {
+          // Z = Src^T Y has the shape of the down-projection g = Q^T G: Y goes into the operand planes of Q
+          // (the refresh repacks them at its end), the source takes the place of the gradient, and the
+          // result comes back from the layout of g as the plain q x r block
+          AdamArgs a{};
+          for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
+          a.split_stride = P.lr_total;
+          HIPCHK(launch_pack_y(c->dev, op.iarg, s));
+          HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, true, P.g_once,
+                                  c->at<float>(P.glow), P.lr_total, 1.f, false, false, nullptr, s));
+          HIPCHK(launch_glow_to_z(c->dev, c->at<float>(P.glow), 0, a, s));
+          break;
+        }
+        if (op.fast == 2 && stream_kernel) {
+          // Y = Src B: B (Omega or Z) goes, as bf16 hi / lo planes, where the planes of N live between steps
+          HIPCHK(launch_pack_block(c->dev, op.iarg, c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), s));
+          HIPCHK(launch_src_times_block(c->dev, c->at<ProjTile>(P.ytiles), (int)P.ytile_h.size(), c->at<uint16_t>(P.n_hi),
+                                        c->at<uint16_t>(P.n_lo), s));
+          break;
+        }
         HIPCHK(launch_gemm32(c->dev, descs, tiles + op.tile_first, op.ntiles, op.tile, src_dtype == LORDO_BF16, s));
         if (op.split) HIPCHK(launch_gemm_reduce(c->dev, descs + op.desc_first, op.ndescs, s));
         break;
@@ -781,7 +833,20 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   if (rc != LORDO_OK) return rc;
   rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
   if (rc != LORDO_OK) return rc;
-  return run_refresh(c, src_dtype, s);
+  // a bf16 source with the alignment the pipelined down-projection kernel reads gradients with lets that
+  // kernel take the products of the power iteration that have its shape
+  bool proj_kernels = src_dtype == LORDO_BF16 && c->plan.down_pipe != 0;
+  for (int i = 0; i < c->n && proj_kernels; ++i)
+    if ((c->plan.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & 3) != 0) proj_kernels = false;
+  if (proj_kernels) {
+    rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+    if (rc != LORDO_OK) return rc;
+  }
+  // the products contracted over the columns stream a bf16 source straight into matrix-core fragment order
+  bool stream_kernel = src_dtype == LORDO_BF16 && c->plan.y_fast_shapes;
+  for (int i = 0; i < c->n && stream_kernel; ++i)
+    if ((reinterpret_cast<uintptr_t>(Src[i]) & 15) != 0) stream_kernel = false;
+  return run_refresh(c, src_dtype, s, false, 0.0, proj_kernels, stream_kernel);
 }
 
 int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {

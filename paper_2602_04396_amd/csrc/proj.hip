@@ -1057,6 +1057,149 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Range-finder products with the contraction over the columns of the source: Y = Src B, B = Omega or the
+// orthonormalised block Z (q x r), Src bf16 p x q (Sec. 2 ComputeProjection; sketch and second half of a power
+// iteration).  Tile = 128 rows of Src x 128 rank indices, 4 waves in a 2 x 2 grid, wave tile 64 x 64.
+// The matrix core computes D[rank][row] = B^T(rank, j) Src^T(j, row):
+//   A operand  the planes of B in operand layout (m = rank, k = column j), bf16 hi + lo, two passes;
+//   B operand  Src itself: the fragment of a k-step wants, per lane, 8 consecutive j of one row -- 16
+//              contiguous bytes of the row-major source -- so the source goes from global memory straight into
+//              LDS in fragment order (one 16-byte global-to-LDS load per lane and fragment), untransposed and
+//              unconverted.
+// Fragments arrive once per workgroup in chunks of 32 columns (24 KiB) through a ring of three LDS buffers:
+// while chunk c is multiplied, chunks c+1 and c+2 are in flight (the tiles with the longest contraction run
+// alone at the end of the launch, one workgroup per compute unit, and are bound by memory latency).  The
+// loads are issued from inline assembly with explicit waits, as in the pipelined down-projection kernel;
+// past the last chunk the last one is loaded again, so that the number of outstanding loads is the same in
+// every iteration.  The epilogue is the row-order store of the up-projection kernel (per-wave LDS tile,
+// 16-byte stores along the rows of Y).
+// Needs q % 32 == 0, r % 4 == 0 and a 16-byte aligned source; rows past p are read from row p-1 and not stored.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_src_times_block(DevCtx d, const ProjTile* __restrict__ tiles,
+                                                         const uint16_t* __restrict__ b_hi, const uint16_t* __restrict__ b_lo) {
+  const ProjTile t = tiles[blockIdx.x];
+  if (t.mat < 0) return;
+  const MatDev m = d.mats[t.mat];
+  const GAS u32x4* bh = TO_GLOBAL(const u32x4, b_hi + m.lr_off);
+  const GAS u32x4* bl = TO_GLOBAL(const u32x4, b_lo + m.lr_off);
+  const GAS uint16_t* src = TO_GLOBAL(const uint16_t, ext_ptr(d, EXT_SRC, t.mat));
+
+  // fragment slot (64 x 16 bytes) of chunk buffer s: s*24 + [B planes: (blk*2 + ks)*2 + plane | 16 + blk*2 + ks : Src]
+  constexpr int TP = 36;
+  constexpr int SLOTS = 24;
+  extern __shared__ u32x4 lds_dyn[];                       // 3 x 24 KiB
+  u32x4* frag = lds_dyn;
+  static_assert(sizeof(u32x4) * 3 * SLOTS * 64 >= sizeof(float) * 4 * 32 * TP, "staging blocks must fit");
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave & 1, wn = wave >> 1;                 // row-block pair, rank-block pair of this wave
+  const int p = m.p, q = m.q, r = m.r;
+  const int rblocks = m.rp / 32;
+  const int64_t kgroups = m.qp / 8;
+  const int nchunks = q / 32;
+
+  // feeding role: wave w brings in rank block w of B (2 k-steps x 2 planes) and row block w of Src (2 k-steps)
+  const int rbf = t.n0 / 32 + wave < rblocks ? t.n0 / 32 + wave : rblocks - 1;
+  const GAS u32x4* bsrc[2] = {bh + (int64_t)rbf * kgroups * 32 + lane, bl + (int64_t)rbf * kgroups * 32 + lane};
+  int frow = t.m0 + 32 * wave + (lane & 31);
+  frow = frow < p ? frow : p - 1;
+  const GAS uint16_t* srow = src + (int64_t)frow * q + 8 * (lane >> 5);
+  auto issue_chunk = [&](int c, int s) {                   // six loads per wave
+    c = c < nchunks ? c : nchunks - 1;
+    u32x4* base = frag + s * SLOTS * 64;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int pl = 0; pl < 2; ++pl) dma16_async(bsrc[pl] + (int64_t)(2 * c + ks) * 64, base + ((wave * 2 + ks) * 2 + pl) * 64);
+      dma16_async(reinterpret_cast<const GAS u32x4*>(srow + 32 * c + 16 * ks), base + (16 + wave * 2 + ks) * 64);
+    }
+  };
+
+  f32x16 acc[2][2];                                        // [rank block][row block]
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  issue_chunk(0, 0);
+  issue_chunk(1, 1);
+  int sbuf = 0;                                            // c % 3
+  for (int c = 0; c < nchunks; ++c) {
+    WAIT_VM_BARRIER(6);           // only chunk c+1 may be outstanding: this wave's part of chunk c has landed;
+                                  // barrier: chunk c visible to all waves, every wave is done with chunk c-1
+    issue_chunk(c + 2, sbuf == 0 ? 2 : sbuf - 1);          // into the buffer of chunk c-1
+    ISSUE_FENCE();
+    const u32x4* fb = frag + sbuf * SLOTS * 64;
+    sbuf = sbuf == 2 ? 0 : sbuf + 1;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      u32x4 zh[2], zl[2], sv[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        zh[a] = fb[(((2 * wn + a) * 2 + ks) * 2 + 0) * 64 + lane];
+        zl[a] = fb[(((2 * wn + a) * 2 + ks) * 2 + 1) * 64 + lane];
+      }
+#pragma unroll
+      for (int b = 0; b < 2; ++b) sv[b] = fb[(16 + (2 * wm + b) * 2 + ks) * 64 + lane];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(zh[a]), as_bf(sv[b]), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(zl[a]), as_bf(sv[b]), acc[a][b], 0, 0, 0);
+        }
+    }
+  }
+  WAIT_VM_BARRIER(0);             // the repeated loads of the last chunk have landed and all waves are done reading
+                                  // fragments: reuse the memory for staging
+
+  // accumulator register 4*vq+e of lane l: row l%32 of the row block, rank 8*vq + 4*(l/32) + e of the rank block
+  const uint32_t yrow_bytes = (uint32_t)r * 4u;
+  const rsrc_t ry = make_rsrc(d.arena + m.y[0], (uint32_t)p * yrow_bytes);      // the products write buffer 0 of the pair
+  const int rr = lane >> 3, c4 = lane & 7;
+  float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int rank0 = t.n0 + 32 * (2 * wn + a), row0 = t.m0 + 32 * (2 * wm + b);
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        f32x4 x;
+        x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
+        *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
+      }
+      // LDS operations of one wave complete in order: the reads below see the writes above
+      const uint32_t voff = rank0 + 4 * c4 < r ? (uint32_t)rr * yrow_bytes + (uint32_t)(rank0 + 4 * c4) * 4u : OOB;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
+        const int row = row0 + 8 * j;                       // first of the eight rows this access covers
+        const uint32_t soff = row < p ? (uint32_t)row * yrow_bytes : (uint32_t)p * yrow_bytes;
+        u32x4 o = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
+        __builtin_amdgcn_raw_buffer_store_b128(o, ry, voff, soff, 0);
+      }
+    }
+}
+
+hipError_t launch_src_times_block(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* b_hi, const uint16_t* b_lo,
+                                  hipStream_t s) {
+  if (ntiles <= 0) return hipSuccess;
+  constexpr int LDS_BYTES = 3 * 24 * 1024;
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_src_times_block), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(k_src_times_block, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo);
+  return hipGetLastError();
+}
+
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* b_hi,
                           const uint16_t* b_lo, const UpArgs& ua, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;

@@ -236,13 +236,17 @@ def test_config1_constant_gradient_closed_form(torch):
     assert rel_l2(got, -1e-2 * Q @ N) <= TOL
 
 
-def test_refresh_rotates_moments(torch):
+@pytest.mark.parametrize("shape_set", ["ragged", "aligned"])
+def test_refresh_rotates_moments(torch, shape_set):
     """Refresh after some steps: subspace against the oracle's own range finder, then moments
     against the oracle's rotation done with the library's basis (the rotation depends on the basis,
-    which is only fixed up to rounding-level differences), plus a basis-free check."""
+    which is only fixed up to rounding-level differences), plus a basis-free check.  The aligned
+    shapes (q % 32 == 0, r % 4 == 0) with a bf16 source take the range-finder products through the
+    projection-type kernels, the ragged ones through the grouped GEMM."""
     from paper_2602_04396_amd import lordo
-    shapes = [(200, 330, 48), (300, 129, 33), (96, 160, 20), (256, 192, 128)]
-    for power_iters, bf16 in [(1, True), (2, False), (0, True)]:
+    shapes = [(200, 330, 48), (300, 129, 33), (96, 160, 20), (256, 192, 128)] if shape_set == "ragged" else \
+             [(200, 320, 48), (300, 128, 32), (130, 160, 20), (256, 192, 128), (520, 384, 256)]
+    for power_iters, bf16 in [(1, True), (2, False), (0, True), (2, True)]:
         ohp = orc.Hyper(power_iters=power_iters)
         ghp = lordo.hparams(power_iters=power_iters, grad_dtype=lordo.BF16 if bf16 else lordo.F32)
         pair = Pair(torch, shapes, _weights(shapes, 20), ohp, ghp, _rand_Q(shapes, 20))
