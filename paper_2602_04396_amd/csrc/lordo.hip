@@ -141,6 +141,10 @@ struct ProgramBuilder {
       g.beta = 0.f;
       g.mat = i;
       g.ksplit = 1;
+      // every product of the program runs on the bf16 matrix cores with operands split into three terms
+      // (as exact as fp32, and faster than the fp32 matrix-core path from r = 256 up); the kernel falls back
+      // to fp32 matrix cores for operands it cannot read with 16-byte accesses
+      g.prec = 1;
       if (!make(i, g)) continue;
       if (g.M <= 0 || g.N <= 0 || g.K <= 0) continue;
       if (g.M < 128 || g.N < 128) big_ok = false;
@@ -243,7 +247,7 @@ struct ProgramBuilder {
             g.C = ref_arena(buf_of(i, cur) + (int64_t)jb * NB * 4); g.ldc = m.r;
             g.M = rows_of(i); g.N = nbk; g.K = jb * NB;
             g.alpha = -1.f; g.beta = 1.f;
-            return true;
+                return true;
           });
         gemm([&](int i, GemmDesc& g) {
           const MatDev& m = P.mat[i];
@@ -253,7 +257,7 @@ struct ProgramBuilder {
           g.B = ref_arena(m.dinv + (int64_t)jb * NB * NB * 4); g.sBk = 1; g.sBn = NB;
           g.C = ref_arena(buf_of(i, dst) + (int64_t)jb * NB * 4); g.ldc = m.r;
           g.M = rows_of(i); g.N = nbk; g.K = nbk;
-          return true;
+            return true;
         });
       }
       cur = dst;
