@@ -733,7 +733,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   fuse.a = a;
   c->prof.begin(LORDO_K_DOWN, s);
   HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, P.g_once, c->at<float>(P.glow),
-                          P.lr_total, (float)proj_scale, g_f32, ef, &fuse, s));
+                          P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
   if (P.adam_first < P.lr_total)
@@ -795,7 +795,7 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
           a.split_stride = P.lr_total;
           HIPCHK(launch_pack_y(c->dev, op.iarg, s));
           HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, true, P.g_once,
-                                  c->at<float>(P.glow), P.lr_total, 1.f, false, false, nullptr, s));
+                                  c->at<float>(P.glow), P.lr_total, 1.f, false, src_dtype == LORDO_F32 ? 2 : 0, nullptr, s));
           HIPCHK(launch_glow_to_z(c->dev, c->at<float>(P.glow), 0, a, s));
           break;
         }
@@ -839,14 +839,19 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   if (rc != LORDO_OK) return rc;
   // a bf16 source with the alignment the pipelined down-projection kernel reads gradients with lets that
   // kernel take the products of the power iteration that have its shape
-  bool proj_kernels = src_dtype == LORDO_BF16 && c->plan.down_pipe != 0;
+  // (an fp32 source too: that kernel then stages it as bf16 hi + lo planes, as it does the error-feedback sum)
+  bool proj_kernels = c->plan.down_pipe != 0;
+  const uintptr_t pair_mask = src_dtype == LORDO_BF16 ? 3 : 7;       // two adjacent columns with one access
   for (int i = 0; i < c->n && proj_kernels; ++i)
-    if ((c->plan.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & 3) != 0) proj_kernels = false;
-  if (proj_kernels) {
+    if ((c->plan.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & pair_mask) != 0) proj_kernels = false;
+  if (proj_kernels && src_dtype == LORDO_BF16) {
     rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
     if (rc != LORDO_OK) return rc;
   }
   // the products contracted over the columns stream a bf16 source straight into matrix-core fragment order
+  // (bf16 only: an fp32 source would have to be cut to bf16 hi + lo, 2^-18, on the way, which moved the projector by
+  // 3e-4 .. 4e-4 on the parity shapes; it keeps the three-term GEMM for these products.  In the products of the
+  // other orientation, above, the same cut costs 1e-4 and is taken.)
   bool stream_kernel = src_dtype == LORDO_BF16 && c->plan.y_fast_shapes;
   for (int i = 0; i < c->n && stream_kernel; ++i)
     if ((reinterpret_cast<uintptr_t>(Src[i]) & 15) != 0) stream_kernel = false;
@@ -869,7 +874,10 @@ int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad
   if (rc != LORDO_OK) return rc;
   c->grad_folded = true;
   c->folded_g.assign(G, G + c->n);
-  return run_refresh(c, LORDO_F32, s, true, grad_scale);
+  bool proj_kernels = P.down_pipe != 0;                // the residual is 256-byte aligned; pairs of columns need an even q
+  for (int i = 0; i < c->n && proj_kernels; ++i)
+    if ((P.mat[i].q & 1) != 0) proj_kernels = false;
+  return run_refresh(c, LORDO_F32, s, true, grad_scale, proj_kernels, false);
 }
 
 int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* DeltaOut, void* stream) {

@@ -384,9 +384,13 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
 // arena.  E rows travel with the G rows of their stage; the sum is formed in registers when the stage
 // goes to LDS, as bf16 hi and lo planes (one more 16 KiB plane per stage and a third MFMA pass), and
 // the result is not scaled again.
-template <int RB, bool VEC, bool GONCE, bool EF>
+// EFM = 2: the projected matrix is an fp32 matrix alone (no G): the fp32 source of a subspace refresh, taken
+// from the caller's source table -- the product Z = Src^T Y of the power iteration has the shape of g = Q^T G.
+template <int RB, bool VEC, bool GONCE, int EFM>
 __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
                                                         int64_t split_stride, float grad_scale, FusedAdam fa) {
+  constexpr bool EF = EFM != 0;                                // an fp32 operand is staged: hi and lo planes, three passes
+  constexpr bool SRC32 = EFM == 2;                             // ... and it is the whole operand
   constexpr int BK = 32;
   constexpr int NW = 8;
   const ProjTile t = tiles[blockIdx.x];
@@ -427,7 +431,8 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   const int wslot = ((4 * half + (lane >> 4)) * 4 + kgrp) * 32 + 2 * (lane & 15);
   // residual E: fp32 p x q in the arena, same rows and columns (8-byte accesses need an even q: VEC)
   const uint32_t erow_bytes = (uint32_t)m.q * 4u;
-  const rsrc_t re = EF ? make_rsrc(d.arena + m.err, (uint32_t)klim * erow_bytes) : rs;
+  const rsrc_t re = SRC32 ? make_rsrc(ext_ptr(d, EXT_SRC, t.mat), (uint32_t)klim * erow_bytes)
+                          : (EF ? make_rsrc(d.arena + m.err, (uint32_t)klim * erow_bytes) : rs);
   GCol ge;
   ge.vec = VEC;
   ge.off0 = col < m.q ? (uint32_t)col * 4u : OOB;
@@ -518,13 +523,16 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   GStage<true> se0, se1;                                       // EF: rows of E of the same stages
   constexpr int GAUX = GONCE ? STREAM : 0;
   // outstanding loads of one stage: 8 (or 16 two-byte ones) of G, as many again of E
+  constexpr int NLOADS = ((SRC32 ? 0 : 1) + (EF ? 1 : 0)) * (VEC ? 8 : 16);
   auto wait_one_stage = [&]() {
-    if constexpr (VEC && !EF) WAIT_VM_BARRIER(8);
-    else if constexpr (VEC == EF) WAIT_VM_BARRIER(16);
+    if constexpr (NLOADS == 8) WAIT_VM_BARRIER(8);
+    else if constexpr (NLOADS == 16) WAIT_VM_BARRIER(16);
     else WAIT_VM_BARRIER(32);
   };
   auto stage_out = [&](const GStage<false>& g, const GStage<true>& e, int sbuf) {
-    if constexpr (EF) {
+    if constexpr (SRC32) {
+      store_gstage<true>(e, gfrag + sbuf * GSLOTS, glo + sbuf * GSLOTS, wslot);
+    } else if constexpr (EF) {
       GStage<true> sa;
       add_residual<false>(sa, g, e, grad_scale);
       store_gstage<true>(sa, gfrag + sbuf * GSLOTS, glo + sbuf * GSLOTS, wslot);
@@ -533,9 +541,9 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
     }
   };
   issue_a(t.k0, 0);
-  load_gstage<false, GAUX>(st0, rs, row_bytes, krow0, klim, gc);                  // stage 0
+  if constexpr (!SRC32) load_gstage<false, GAUX>(st0, rs, row_bytes, krow0, klim, gc);                  // stage 0
   if constexpr (EF) load_gstage<true, GAUX>(se0, re, erow_bytes, krow0, klim, ge);
-  load_gstage<false, GAUX>(st1, rs, row_bytes, krow0 + BK, klim, gc);             // stage 1
+  if constexpr (!SRC32) load_gstage<false, GAUX>(st1, rs, row_bytes, krow0 + BK, klim, gc);             // stage 1
   if constexpr (EF) load_gstage<true, GAUX>(se1, re, erow_bytes, krow0 + BK, klim, ge);
   stage_out(st0, se0, 0);
   wait_one_stage();
@@ -545,7 +553,7 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   {                                                                                               \
     const int kr = t.k0 + (S) * BK;                                                               \
     if ((S) + 1 < nstages) issue_a(kr + BK, ((S) + 1) & 1);                                       \
-    load_gstage<false, GAUX>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc);              \
+    if constexpr (!SRC32) load_gstage<false, GAUX>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc); \
     if constexpr (EF) load_gstage<true, GAUX>(LOADE, re, erow_bytes, krow0 + ((S) + 2) * BK, klim, ge); \
     ISSUE_FENCE();                                                                                \
     compute((S) & 1);                                                                             \
@@ -619,10 +627,10 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
 
 // One instantiation of the pipelined kernel; its dynamic LDS (64 KiB for 128-rank tiles, 96 KiB for
 // 256-rank tiles, 32 KiB more with error feedback) is raised above the default limit at first use.
-template <int RB, bool VEC, bool GONCE, bool EF>
+template <int RB, bool VEC, bool GONCE, int EF>
 static hipError_t launch_pipe(dim3 grid, const DevCtx& d, const ProjTile* tiles, float* glow, int64_t split_stride,
                               float grad_scale, const FusedAdam& fa, hipStream_t s) {
-  constexpr int LDS_BYTES = (RB == 2 ? 98304 : 65536) + (EF ? 32768 : 0);
+  constexpr int LDS_BYTES = (RB == 2 ? 98304 : 65536) + (EF != 0 ? 32768 : 0);
   static bool raised = false;
   if (LDS_BYTES > 65536 && !raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_down_pipe<RB, VEC, GONCE, EF>),
@@ -633,7 +641,7 @@ static hipError_t launch_pipe(dim3 grid, const DevCtx& d, const ProjTile* tiles,
   hipLaunchKernelGGL((k_proj_down_pipe<RB, VEC, GONCE, EF>), grid, dim3(512), LDS_BYTES, s, d, tiles, glow, split_stride, grad_scale, fa);
   return hipGetLastError();
 }
-template <int RB, bool EF>
+template <int RB, int EF>
 static hipError_t launch_pipe_vo(bool g_vec, bool g_once, dim3 grid, const DevCtx& d, const ProjTile* tiles, float* glow,
                                  int64_t split_stride, float grad_scale, const FusedAdam& fa, hipStream_t s) {
   if (g_once) return g_vec ? launch_pipe<RB, true, true, EF>(grid, d, tiles, glow, split_stride, grad_scale, fa, s)
@@ -641,16 +649,18 @@ static hipError_t launch_pipe_vo(bool g_vec, bool g_once, dim3 grid, const DevCt
   return g_vec ? launch_pipe<RB, true, false, EF>(grid, d, tiles, glow, split_stride, grad_scale, fa, s)
                : launch_pipe<RB, false, false, EF>(grid, d, tiles, glow, split_stride, grad_scale, fa, s);
 }
-static hipError_t launch_pipe_select(int rb, bool g_vec, bool g_once, bool ef, dim3 grid, const DevCtx& d, const ProjTile* tiles,
+static hipError_t launch_pipe_select(int rb, bool g_vec, bool g_once, int ef, dim3 grid, const DevCtx& d, const ProjTile* tiles,
                                      float* glow, int64_t split_stride, float grad_scale, const FusedAdam& fa, hipStream_t s) {
-  if (rb == 2) return ef ? launch_pipe_vo<2, true>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)
-                         : launch_pipe_vo<2, false>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s);
-  return ef ? launch_pipe_vo<1, true>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)
-            : launch_pipe_vo<1, false>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s);
+#define LORDO_PIPE_RB(RBV)                                                                                               \
+  (ef == 2 ? launch_pipe_vo<RBV, 2>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)                \
+   : ef == 1 ? launch_pipe_vo<RBV, 1>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)              \
+             : launch_pipe_vo<RBV, 0>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s))
+  return rb == 2 ? LORDO_PIPE_RB(2) : LORDO_PIPE_RB(1);
+#undef LORDO_PIPE_RB
 }
 
 hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_rb, bool g_vec, bool g_once, float* glow,
-                            int64_t split_stride, float grad_scale, bool g_is_f32, bool ef, const DownFuse* fuse, hipStream_t s) {
+                            int64_t split_stride, float grad_scale, bool g_is_f32, int ef, const DownFuse* fuse, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
   if (pipe_rb) {       // pipelined kernel: 128 * pipe_rb rank indices per tile
@@ -1057,6 +1067,41 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     }
 }
 
+// Epilogue of the Y = Src B kernels: the 2 x 2 accumulator blocks of a wave (register 4*vq+e of lane l: row l%32
+// of the row block, rank 8*vq + 4*(l/32) + e of the rank block) go through a per-wave LDS tile into row order
+// and out to buffer 0 of the Y pair with 16-byte stores along the rows.
+__device__ __forceinline__ void store_y_tile(const DevCtx& d, const MatDev& m, const ProjTile& t, const f32x16 (&acc)[2][2],
+                                             float* lds_stage, int wave, int lane, int wm, int wn) {
+  constexpr int TP = 36;
+  const int p = m.p, r = m.r;
+  const uint32_t yrow_bytes = (uint32_t)r * 4u;
+  const rsrc_t ry = make_rsrc(d.arena + m.y[0], (uint32_t)p * yrow_bytes);
+  const int rr = lane >> 3, c4 = lane & 7;
+  float* T = lds_stage + wave * 32 * TP;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int rank0 = t.n0 + 32 * (2 * wn + a), row0 = t.m0 + 32 * (2 * wm + b);
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        f32x4 x;
+        x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
+        *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
+      }
+      // LDS operations of one wave complete in order: the reads below see the writes above
+      const uint32_t voff = rank0 + 4 * c4 < r ? (uint32_t)rr * yrow_bytes + (uint32_t)(rank0 + 4 * c4) * 4u : OOB;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
+        const int row = row0 + 8 * j;                       // first of the eight rows this access covers
+        const uint32_t soff = row < p ? (uint32_t)row * yrow_bytes : (uint32_t)p * yrow_bytes;
+        u32x4 o = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
+        __builtin_amdgcn_raw_buffer_store_b128(o, ry, voff, soff, 0);
+      }
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // Range-finder products with the contraction over the columns of the source: Y = Src B, B = Omega or the
 // orthonormalised block Z (q x r), Src bf16 p x q (Sec. 2 ComputeProjection; sketch and second half of a power
@@ -1157,33 +1202,7 @@ __global__ __launch_bounds__(256) void k_src_times_block(DevCtx d, const ProjTil
   WAIT_VM_BARRIER(0);             // the repeated loads of the last chunk have landed and all waves are done reading
                                   // fragments: reuse the memory for staging
 
-  // accumulator register 4*vq+e of lane l: row l%32 of the row block, rank 8*vq + 4*(l/32) + e of the rank block
-  const uint32_t yrow_bytes = (uint32_t)r * 4u;
-  const rsrc_t ry = make_rsrc(d.arena + m.y[0], (uint32_t)p * yrow_bytes);      // the products write buffer 0 of the pair
-  const int rr = lane >> 3, c4 = lane & 7;
-  float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int rank0 = t.n0 + 32 * (2 * wn + a), row0 = t.m0 + 32 * (2 * wm + b);
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        f32x4 x;
-        x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
-        *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
-      }
-      // LDS operations of one wave complete in order: the reads below see the writes above
-      const uint32_t voff = rank0 + 4 * c4 < r ? (uint32_t)rr * yrow_bytes + (uint32_t)(rank0 + 4 * c4) * 4u : OOB;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
-        const int row = row0 + 8 * j;                       // first of the eight rows this access covers
-        const uint32_t soff = row < p ? (uint32_t)row * yrow_bytes : (uint32_t)p * yrow_bytes;
-        u32x4 o = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
-        __builtin_amdgcn_raw_buffer_store_b128(o, ry, voff, soff, 0);
-      }
-    }
+  store_y_tile(d, m, t, acc, reinterpret_cast<float*>(frag), wave, lane, wm, wn);
 }
 
 hipError_t launch_src_times_block(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* b_hi, const uint16_t* b_lo,

@@ -246,7 +246,9 @@ def test_refresh_rotates_moments(torch, shape_set):
     from paper_2602_04396_amd import lordo
     shapes = [(200, 330, 48), (300, 129, 33), (96, 160, 20), (256, 192, 128)] if shape_set == "ragged" else \
              [(200, 320, 48), (300, 128, 32), (130, 160, 20), (256, 192, 128), (520, 384, 256)]
-    for power_iters, bf16 in [(1, True), (2, False), (0, True), (2, True)]:
+    # (power iterations, bf16 gradients, bf16 refresh source): the last case is an fp32 source (an averaged
+    # pseudo-gradient, Alg. 1) in a context planned for bf16 gradients
+    for power_iters, bf16, src_bf16 in [(1, True, True), (2, False, False), (0, True, True), (2, True, True), (1, True, False)]:
         ohp = orc.Hyper(power_iters=power_iters)
         ghp = lordo.hparams(power_iters=power_iters, grad_dtype=lordo.BF16 if bf16 else lordo.F32)
         pair = Pair(torch, shapes, _weights(shapes, 20), ohp, ghp, _rand_Q(shapes, 20))
@@ -254,18 +256,20 @@ def test_refresh_rotates_moments(torch, shape_set):
         for t in range(3):
             pair.local_step([g.draw(t) for g in gens], lr=1e-3, bf16=bf16, first_step_patch=(t == 0))
         Src = [g.draw(100) for g in gens]
+        if bf16 and not src_bf16:          # something fp32 that is not bf16-representable
+            Src = [(0.75 * a + 0.25 * g.draw(101)).astype(np.float32) for a, g in zip(Src, gens)]
         Om = [synth.omega(np.random.default_rng(synth.seed_for(20, 900 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
         Qu_before = [pair.st[i].Q @ pair.st[i].u for i in range(len(shapes))]
         Q_old = [pair.st[i].Q.copy() for i in range(len(shapes))]
         with pytest.raises(lordo.LordoError):                 # no refresh yet: nothing to report
             pair.opt.mssv()
-        dists, orths = pair.refresh(Src, Om, bf16=bf16)
+        dists, orths = pair.refresh(Src, Om, bf16=src_bf16)
         # similarity diagnostic (Sec. 5.1): basis-free, so the oracle's own new basis serves
         mssv_gpu = pair.opt.mssv().cpu().numpy()
         for i, (p, q, r) in enumerate(shapes):
             Qo = orc.range_finder(np.asarray(Src[i], dtype=np.float64), np.asarray(Om[i], dtype=np.float64), power_iters)
             assert abs(mssv_gpu[i] - orc.mssv(Qo, Q_old[i])) <= 1e-4, f"MSSV of matrix {i}"
-        print(f"refresh q_it={power_iters} bf16={bf16}: dist {np.round(dists, 6)} orth {np.round(orths, 7)}", flush=True)
+        print(f"refresh {shape_set} q_it={power_iters} bf16 grads={bf16} source={src_bf16}: dist {np.round(dists, 6)} orth {np.round(orths, 7)}", flush=True)
         assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
         for i in range(len(shapes)):
             u_g = pair.get(i, lordo.STATE_U)
