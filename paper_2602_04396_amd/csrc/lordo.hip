@@ -82,7 +82,7 @@ static int small_out_split(const MatDev* mats, int n, int* tile_out) {
     t128 += (int64_t)((r + 127) / 128) * ((r + 127) / 128);
     t64 += (int64_t)((r + 63) / 64) * ((r + 63) / 64);
   }
-  const bool big = big_ok && t128 >= 512;
+  const bool big = big_ok;           // r x r outputs with r >= 128: 128-wide tiles read the tall operand half as often
   if (tile_out) *tile_out = big ? 128 : 64;
   const int64_t tiles = big ? t128 : t64;
   if (tiles <= 0 || tiles >= 1024) return 1;
@@ -152,7 +152,7 @@ struct ProgramBuilder {
       tiles64 += (int64_t)((g.M + 63) / 64) * ((g.N + 63) / 64);
       made.push_back(g);
     }
-    op.tile = (big_ok && tiles128 >= 512) ? 128 : 64;
+    op.tile = (big_ok && (tiles128 >= 512 || small_out)) ? 128 : 64;
     const int64_t tiles = op.tile == 128 ? tiles128 : tiles64;
     int ksplit = 1;
     if (small_out && tiles > 0 && tiles < 1024)
