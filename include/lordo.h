@@ -52,8 +52,9 @@ extern "C" {
 #define LORDO_STATE_V       2   /* r x q  second moment                                */
 #define LORDO_STATE_ANCHOR  3   /* p x q  x_{t-K_x}, the model at the last outer step  */
 #define LORDO_STATE_MOM     4   /* p x q  outer momentum b (only if outer_momentum!=0) */
-#define LORDO_STATE_GLOW    5   /* r x q  g of the last local step (read only)         */
-#define LORDO_STATE_NUPD    6   /* r x q  bracketed update N of the last local step (read only) */
+#define LORDO_STATE_GLOW    5   /* r x q  g of the last local step (read only; scratch of a refresh)         */
+#define LORDO_STATE_NUPD    6   /* r x q  bracketed update N of the last local step (read only; scratch of a
+                                          refresh and of lordo_outer_step_lowrank) */
 #define LORDO_STATE_ERR     7   /* p x q  error-feedback residual E (only if error_feedback != 0) */
 #define LORDO_STATE_UPLINK  8   /* r x q  up-link buffer A (only if uplink_buffer != 0)           */
 
@@ -119,7 +120,10 @@ int lordo_local_step(lordo_ctx* ctx, void* const* W, const void* const* G,
  *  R = Q_new^T Q;  u <- R u;  v <- c2 | (R o R)(v/c2 - (u/c1)^2) + (R u/c1)^2 |;  finally Q <- Q_new).
  *   Src        host array of n device pointers, p x q each, element type src_dtype
  *              (a gradient, or an averaged pseudo-gradient); read only.  Every entry non-NULL.
- *   Omega      host array of n device pointers, q x r fp32 Gaussian start blocks, read only. */
+ *   Omega      host array of n device pointers, q x r fp32 Gaussian start blocks, read only.
+ * The storage behind LORDO_STATE_GLOW and LORDO_STATE_NUPD serves as scratch: both hold the values of the
+ * last local step only until the next refresh.  With hp.uplink_buffer the call returns LORDO_ESTATE while
+ * the buffer is non-empty (see lordo_export_uplink). */
 int lordo_refresh_subspace(lordo_ctx* ctx, const void* const* Src, int32_t src_dtype,
                            const void* const* Omega, void* stream);
 
