@@ -38,6 +38,7 @@ struct MatDev {
   int64_t zw[4];          // fp32 q x r; zw[0], zw[1] ping-pong of the q-side block, all four rotation temporaries
   int64_t gram, lfac;     // fp32 r x r : Gram matrix (consumed by the factorisation) and its Cholesky factor
   int64_t dinv;           // fp32 ceil(r/NB) blocks of NB x NB : inverses of the diagonal blocks of the factor
+  int64_t minv;           // fp32 r x r : inverse of the whole factor, lower triangular (zeros above the diagonal are never written)
   int64_t rot, rot2;      // fp32 r x r : R = Q_new^T Q_old and its elementwise square
   int64_t part;           // fp32 split-K partial sums of the r x r products (Gram, R): slices x r x r
   int64_t err;            // fp32 p x q error-feedback residual E (-1 without error feedback)
@@ -74,6 +75,7 @@ struct GemmDesc {
   // P + s*M*N; a reduction kernel then adds the slices in order and applies alpha, beta, C2
   int32_t ksplit, klen;
   OpRef P;
+  int32_t tri, pad_;      // tri = 1: B(k, n) = 0 for k > n (transposed lower-triangular factor): the contraction of a column tile ends at its last column
 };
 
 struct GemmTile { int32_t desc; int16_t tm, tn; int16_t ks, pad; };
@@ -165,6 +167,7 @@ hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t
 hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s);
 hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
+hipError_t launch_diag_inverses(const DevCtx& d, hipStream_t s);
 hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
 hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);
 hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s);

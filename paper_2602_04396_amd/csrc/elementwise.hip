@@ -686,6 +686,23 @@ __global__ __launch_bounds__(64) void k_potf2(DevCtx d, int jb) {
   for (int rr = 0; rr < nbk; ++rr)
     if (lane < nbk) L[(int64_t)(o + rr) * m.r + (o + lane)] = tile[rr][lane];
 }
+// The inverses of the diagonal blocks, copied to their places on the diagonal of the r x r inverse of the
+// whole factor (the rows below are then built from them by products).
+__global__ __launch_bounds__(256) void k_diag_inverses(DevCtx d) {
+  const MatDev& m = d.mats[blockIdx.x];
+  const float* X = reinterpret_cast<const float*>(d.arena + m.dinv);
+  float* M = reinterpret_cast<float*>(d.arena + m.minv);
+  const int nblocks = (m.r + NB - 1) / NB;
+  for (int t = threadIdx.x; t < nblocks * NB * NB; t += 256) {
+    const int jb = t / (NB * NB), i = (t / NB) % NB, j = t % NB;
+    const int row = jb * NB + i, col = jb * NB + j;
+    if (row < m.r && col < m.r) M[(int64_t)row * m.r + col] = X[t];
+  }
+}
+hipError_t launch_diag_inverses(const DevCtx& d, hipStream_t s) {
+  hipLaunchKernelGGL(k_diag_inverses, dim3(d.n), dim3(256), 0, s, d);
+  return hipGetLastError();
+}
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
   hipLaunchKernelGGL(k_potf2, dim3(d.n), dim3(64), 0, s, d, jb);
   return hipGetLastError();

@@ -323,8 +323,9 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
   const GemmDesc g = descs[t.desc];
   const int M = g.M, N = g.N;
   const int kbeg = g.ksplit > 1 ? t.ks * g.klen : 0;
-  const int K = g.ksplit > 1 ? (kbeg + g.klen < g.K ? kbeg + g.klen : g.K) : g.K;     // end of this slice
+  int K = g.ksplit > 1 ? (kbeg + g.klen < g.K ? kbeg + g.klen : g.K) : g.K;           // end of this slice
   const int m0 = t.tm * TM, n0 = t.tn * TN;
+  if (g.tri && n0 + TN < K) K = n0 + TN;            // B is zero below this tile's last column
   const int a_bf16 = g.a_bf16 == 2 ? src_is_bf16 : g.a_bf16;
   float* C = reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C, g.mat)));
   float* C2 = g.C2.off >= 0 ? reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C2, g.mat))) : nullptr;

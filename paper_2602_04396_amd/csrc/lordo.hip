@@ -25,7 +25,7 @@ namespace {
     }                                                                                             \
   } while (0)
 
-enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK };
+enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK };
 
 struct Op {
   int kind;
@@ -125,7 +125,7 @@ struct ProgramBuilder {
   // One grouped GEMM launch.  `small_out` marks r x r products with a long contraction (Gram matrix,
   // rotation matrix): with few output tiles they are split along K so that the chip is filled.
   template <class F>
-  void gemm(F make, bool rot_only = false, bool small_out = false) {       // make(i, desc) -> false to skip matrix i
+  void gemm(F make, bool rot_only = false, bool small_out = false, bool lower_only = false) {   // make(i, desc) -> false to skip matrix i
     Op op;
     op.kind = OP_GEMM;
     op.tile_first = (int)P.gtile_h.size();
@@ -172,8 +172,10 @@ struct ProgramBuilder {
       P.desc_h.push_back(g);
       for (int sl = 0; sl < g.ksplit; ++sl)
         for (int tm = 0; tm < (g.M + op.tile - 1) / op.tile; ++tm)
-          for (int tn = 0; tn < (g.N + op.tile - 1) / op.tile; ++tn)
+          for (int tn = 0; tn < (g.N + op.tile - 1) / op.tile; ++tn) {
+            if (lower_only && tn > tm) continue;      // symmetric result of which only the lower triangle is read
             P.gtile_h.push_back(GemmTile{di, (int16_t)tm, (int16_t)tn, (int16_t)sl, 0});
+          }
     }
     op.ndescs = (int)P.desc_h.size() - op.desc_first;
     op.ntiles = (int)P.gtile_h.size() - op.tile_first;
@@ -204,7 +206,7 @@ struct ProgramBuilder {
         g.C = ref_arena(m.gram); g.ldc = m.r;
         g.M = m.r; g.N = m.r; g.K = rows_of(i);
         return true;
-      }, false, true);
+      }, false, true, true);      // the factorisation reads the lower triangle only
       if (pass == 0) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
       for (int jb = 0; jb < max_blocks; ++jb) {
         simple(OP_POTF2, jb);
@@ -234,32 +236,45 @@ struct ProgramBuilder {
           return true;
         });
       }
-      // Q = X L^{-T}, block column by block column: Q_j = (X_j - Q_{<j} L_{j,<j}^T) L_jj^{-T}
-      int dst = 1 - cur;
-      for (int jb = 0; jb < max_blocks; ++jb) {
-        if (jb > 0)
-          gemm([&](int i, GemmDesc& g) {
-            const MatDev& m = P.mat[i];
-            int nbk = std::min(NB, m.r - jb * NB);
-            if (nbk <= 0) return false;
-            g.A = ref_arena(buf_of(i, dst)); g.sAm = m.r; g.sAk = 1;
-            g.B = ref_arena(m.lfac + (int64_t)jb * NB * m.r * 4); g.sBk = 1; g.sBn = m.r;
-            g.C = ref_arena(buf_of(i, cur) + (int64_t)jb * NB * 4); g.ldc = m.r;
-            g.M = rows_of(i); g.N = nbk; g.K = jb * NB;
-            g.alpha = -1.f; g.beta = 1.f;
-                return true;
-          });
+      simple(OP_DIAG_INV);
+      // M = L^{-1}, row block by row block from the inverses of the diagonal blocks:
+      // M[i, <i] = -M_ii (L[i, <i] M[<i, <i]); the Gram buffer, consumed by the factorisation, holds the inner product
+      for (int ib = 1; ib < max_blocks; ++ib) {
         gemm([&](int i, GemmDesc& g) {
           const MatDev& m = P.mat[i];
-          int nbk = std::min(NB, m.r - jb * NB);
+          const int nbk = std::min(NB, m.r - ib * NB);
           if (nbk <= 0) return false;
-          g.A = ref_arena(buf_of(i, cur) + (int64_t)jb * NB * 4); g.sAm = m.r; g.sAk = 1;
-          g.B = ref_arena(m.dinv + (int64_t)jb * NB * NB * 4); g.sBk = 1; g.sBn = NB;
-          g.C = ref_arena(buf_of(i, dst) + (int64_t)jb * NB * 4); g.ldc = m.r;
-          g.M = rows_of(i); g.N = nbk; g.K = nbk;
-            return true;
+          const int64_t row = (int64_t)ib * NB * m.r * 4;
+          g.A = ref_arena(m.lfac + row); g.sAm = m.r; g.sAk = 1;
+          g.B = ref_arena(m.minv); g.sBk = m.r; g.sBn = 1;
+          g.C = ref_arena(m.gram + row); g.ldc = m.r;
+          g.M = nbk; g.N = ib * NB; g.K = ib * NB;
+          return true;
+        });
+        gemm([&](int i, GemmDesc& g) {
+          const MatDev& m = P.mat[i];
+          const int nbk = std::min(NB, m.r - ib * NB);
+          if (nbk <= 0) return false;
+          const int64_t row = (int64_t)ib * NB * m.r * 4;
+          g.A = ref_arena(m.minv + row + (int64_t)ib * NB * 4); g.sAm = m.r; g.sAk = 1;
+          g.B = ref_arena(m.gram + row); g.sBk = m.r; g.sBn = 1;
+          g.C = ref_arena(m.minv + row); g.ldc = m.r;
+          g.M = nbk; g.N = ib * NB; g.K = nbk;
+          g.alpha = -1.f;
+          return true;
         });
       }
+      // Q = X M^T in one product over the full rank (the contraction of a column tile stops at its last column)
+      int dst = 1 - cur;
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_arena(buf_of(i, cur)); g.sAm = m.r; g.sAk = 1;
+        g.B = ref_arena(m.minv); g.sBk = 1; g.sBn = m.r;
+        g.C = ref_arena(buf_of(i, dst)); g.ldc = m.r;
+        g.M = rows_of(i); g.N = m.r; g.K = m.r;
+        g.tri = 1;
+        return true;
+      });
       cur = dst;
     }
     return cur;
@@ -463,6 +478,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     for (int k = 0; k < 4; ++k) m.zw[k] = A.take(qr * 4);
     m.gram = A.take(rr * 4); m.lfac = A.take(rr * 4);
     m.dinv = A.take((size_t)((m.r + NB - 1) / NB) * NB * NB * 4);
+    m.minv = A.take(rr * 4);
     m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
     m.part = A.take(rr * 4 * P.part_slices);
   }
@@ -811,6 +827,7 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
         break;
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
+      case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
       case OP_ROT_PRE:
         HIPCHK(launch_rot_pre(c->dev, c->at<float>(P.u), c->at<float>(P.v), (float)(1.0 / c1), (float)(1.0 / c2), s));
         break;
