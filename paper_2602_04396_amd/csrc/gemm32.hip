@@ -260,24 +260,27 @@ struct OperandBF {
   }
 };
 
+// same_ab (uniform): the tile of B is the tile of A (a diagonal tile of a Gram matrix X^T X): it is fetched and
+// split once and the B fragments are read from the planes of A.
 template <int WB, bool A_BF16, int TM>
 __device__ __forceinline__ void gemm_loop_bf(f32x16 (&acc)[WB][WB], const OperandBF<TM>& opA, const OperandBF<TM>& opB,
-                                             uint16_t* lds, int kbeg, int K, int tid, int lane, int wm, int wn) {
+                                             uint16_t* lds, int kbeg, int K, int tid, int lane, int wm, int wn, bool same_ab) {
   constexpr int PLANE = (TM / 32) * 4 * 264;                   // elements
   constexpr int NA = A_BF16 ? 1 : 3;                           // planes of A; B always has three
   uint16_t* PA = lds;
-  uint16_t* PB = lds + NA * PLANE;
+  uint16_t* PB = (!A_BF16 && same_ab) ? lds : lds + NA * PLANE;
+  const bool own_b = A_BF16 || !same_ab;
   u32x4 ra[4], rb[4];
   opA.template fetch_raw<A_BF16>(ra, kbeg, tid);
-  opB.template fetch_raw<false>(rb, kbeg, tid);
+  if (own_b) opB.template fetch_raw<false>(rb, kbeg, tid);
   for (int k0 = kbeg; k0 < K; k0 += TK) {
     __syncthreads();                           // previous tile fully consumed
     opA.template stash<A_BF16>(ra, PA, PLANE, k0, tid);
-    opB.template stash<false>(rb, PB, PLANE, k0, tid);
+    if (own_b) opB.template stash<false>(rb, PB, PLANE, k0, tid);
     __syncthreads();
     if (k0 + TK < K) {
       opA.template fetch_raw<A_BF16>(ra, k0 + TK, tid);
-      opB.template fetch_raw<false>(rb, k0 + TK, tid);
+      if (own_b) opB.template fetch_raw<false>(rb, k0 + TK, tid);
     }
     asm volatile("" ::: "memory");             // keep the loads above the arithmetic: they must be in flight during it
 #pragma unroll
@@ -358,8 +361,10 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
     pa.setup(opA.base, g.sAm, g.sAk, M, K, m0);
     pb.setup(opB.base, g.sBn, g.sBk, N, K, n0);
     uint16_t* planes = reinterpret_cast<uint16_t*>(lds_raw);
-    if (a_bf16) gemm_loop_bf<WB, true>(acc, pa, pb, planes, kbeg, K, tid, lane, wm, wn);
-    else gemm_loop_bf<WB, false>(acc, pa, pb, planes, kbeg, K, tid, lane, wm, wn);
+    // same matrix, same strides with the roles of the two indices swapped, same tile: A(m, k) = B(k, n = m)
+    const bool same_ab = g.A.off == g.B.off && g.A.ext == g.B.ext && g.sAm == g.sBn && g.sAk == g.sBk && m0 == n0 && M == N;
+    if (a_bf16) gemm_loop_bf<WB, true>(acc, pa, pb, planes, kbeg, K, tid, lane, wm, wn, false);
+    else gemm_loop_bf<WB, false>(acc, pa, pb, planes, kbeg, K, tid, lane, wm, wn, same_ab);
   } else if (kbeg < K) {
     const bool vec = opA.vec_ok && opB.vec_ok;
     if (a_bf16) {
