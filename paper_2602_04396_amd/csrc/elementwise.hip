@@ -1,10 +1,14 @@
 // Elementwise, packing and small dense kernels of the LoRDO library (gfx950).
-//   k_adam          fused low-rank Adam update on the flat low-rank arena (Sec. 2; Alg. 1 moment lines)
-//   k_outer         outer step on the pseudo-gradient (Alg. 1 OuterOpt; App. A.2, D.4)
-//   k_export_delta  pseudo-gradient anchor - W (App. A.1)
-//   k_pack_q        split of the fp32 projection into bf16 hi/lo operand planes
-//   k_potf2         Cholesky of one diagonal block and its inverse (CholeskyQR)
-//   k_rot_pre/post  elementwise parts of the moment rotation (Alg. 1 rotation lines)
+//   k_adam            fused low-rank Adam update on the flat low-rank arena (Sec. 2; Alg. 1 moment lines), with the
+//                     low-rank QHM bracket, the column sums of the full-rank QHM scale (Sec. 3.2), the planes of g
+//                     for the error-feedback residual and the up-link buffer (App. A.5.1) as options
+//   k_pq<MODE>        p x q family: outer step (Alg. 1 OuterOpt; App. A.2, D.4), pseudo-gradient anchor - W
+//                     (App. A.1), anchor copy, and the part of the outer step that does not depend on Delta
+//   k_fold_grad       E <- E + s G, the projection source of the local variant (Alg. 2)
+//   k_pack_q / k_pack_y / k_pack_block / k_split_planes   fp32 -> bf16 hi/lo operand planes in matrix-core order
+//   k_glow_to_z, k_lr_to_plain, k_plain_to_lr, k_lr_exchange   between the operand layout of the low-rank state and plain buffers
+//   k_gram_shift, k_potf2, k_diag_inverses   CholeskyQR: diagonal shift, Cholesky of a diagonal block and its inverse
+//   k_rot_pre / k_rot_post, k_mssv   elementwise parts of the moment rotation (Alg. 1 rotation lines); similarity diagnostic (Sec. 5.1)
 #include "common.h"
 
 namespace lordo {

@@ -1,8 +1,11 @@
-// Grouped fp32 GEMM on the fp32 matrix cores (v_mfma_f32_32x32x2_f32) for the subspace refresh:
-// range-finder products, Gram matrices, blocked Cholesky / triangular solves and the moment
-// rotation.  One launch runs a list of independent problems (one per weight matrix); a tile
-// table maps each workgroup to (problem, tile).  Operands are addressed by element strides, so
-// any transpose and the bf16 gradient type are handled by the loader; accumulation is fp32.
+// Grouped GEMM for the subspace refresh: range-finder products (any shape and alignment), Gram matrices,
+// blocked Cholesky panels, the inverse of the factor and its application, and the moment rotation.
+// One launch runs a list of independent problems (one per weight matrix); a tile table maps each
+// workgroup to (problem, tile, K slice).  Operands are addressed by element strides, so any transpose
+// and the bf16 gradient type are handled by the loader; accumulation is fp32.  Arithmetic: operands that
+// can be read with 16-byte accesses are split into bf16 terms (three per fp32 operand: as exact as fp32)
+// and multiplied on v_mfma_f32_32x32x16_bf16; anything else runs on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32).
 #include "common.h"
 
 namespace lordo {

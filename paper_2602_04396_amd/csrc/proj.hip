@@ -2,6 +2,9 @@
 //
 //   down:  g = Q^T (s G)      (Sec. 2; Alg. 1 "low-rank gradient signal")   contraction over the p rows
 //   up:    W <- W - eta Q N   (Sec. 2; Alg. 1 parameter update)             contraction over the rank
+// with their variants (error feedback, full-rank QHM term, residual update, outer step from the up-link
+// buffers), and the range-finder products of the refresh that have the same shapes: Z = Src^T Y runs on the
+// down-projection kernel, Y = Src B on k_src_times_block (contraction over the q columns).
 //
 // fp32 operands the library owns (Q, N) are kept as two bf16 planes hi + lo (x = hi + lo up to
 // 2^-17 relative), already in the lane order of the MFMA operand fragment, so a fragment is one
