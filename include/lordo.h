@@ -98,6 +98,14 @@ int lordo_workspace_bytes(const lordo_shape* shapes, int32_t n, const lordo_hpar
 int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp,
                void* arena, size_t arena_bytes, void* const* W, void* stream);
 
+/* Random initial projection of the global variant (Alg. 1 "Require": Q_0 random, against the identity
+ * columns of Alg. 2 that lordo_init leaves): Q_0 = orthonormal basis of the caller's block, by the same
+ * CholeskyQR as the refresh (columns signed so that the triangular factor has a positive diagonal).
+ *   Block  host array of n device pointers, p x r fp32 each (e.g. Gaussian), read only, full column rank.
+ * Valid only before the first local step (LORDO_ESTATE afterwards: changing the basis of running moments
+ * is what lordo_refresh_subspace does). */
+int lordo_init_projection(lordo_ctx* ctx, const void* const* Block, void* stream);
+
 /* One local step on every matrix (Sec. 2; Alg. 1 inner loop):
  *   t <- t+1;  A = grad_scale * G  (+ E with error feedback);  g = Q^T A;  [E <- A - Q g];
  *   u <- beta1 u + (1-beta1) g;  v <- beta2 v + (1-beta2) g*g;  u^ = u/c1, v^ = v/c2, c_i = 1-beta_i^t

@@ -173,6 +173,12 @@ def orth(Y: np.ndarray) -> np.ndarray:
     return Qf * s[None, :]
 
 
+def initial_projection(block: np.ndarray) -> np.ndarray:
+    """Q_0 of the global variant (Alg. 1, Require: a random initial projection): the orthonormal
+    basis of a random p x r block, made unique by the positive diagonal of its triangular factor."""
+    return orth(np.asarray(block, dtype=F64))
+
+
 def range_finder(A: np.ndarray, Omega: np.ndarray, power_iters: int) -> np.ndarray:
     """Block power iteration with a Gaussian start, orthonormalised after every product:
     Y = orth(A Omega); repeat: Z = orth(A^T Y); Y = orth(A Z)."""

@@ -171,6 +171,7 @@ hipError_t launch_diag_inverses(const DevCtx& d, hipStream_t s);
 hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
 hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);
 hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s);
+hipError_t launch_y_from_ext(const DevCtx& d, hipStream_t s);
 hipError_t launch_pack_y(const DevCtx& d, int ybuf, hipStream_t s);
 hipError_t launch_pack_block(const DevCtx& d, int zbuf, uint16_t* p_hi, uint16_t* p_lo, hipStream_t s);
 hipError_t launch_src_times_block(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* b_hi, const uint16_t* b_lo,

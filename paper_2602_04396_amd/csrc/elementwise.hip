@@ -368,6 +368,18 @@ hipError_t launch_pack_block(const DevCtx& d, int zbuf, uint16_t* p_hi, uint16_t
   hipLaunchKernelGGL(k_pack_block, dim3(128, d.n), dim3(256), 0, s, d, zbuf, p_hi, p_lo);
   return hipGetLastError();
 }
+// buffer 0 of the Y pair <- the caller's p x r block (table EXT_DIN): start of the initial projection
+__global__ __launch_bounds__(256) void k_y_from_ext(DevCtx d) {
+  const MatDev& m = d.mats[blockIdx.y];
+  float* y = reinterpret_cast<float*>(d.arena + m.y[0]);
+  const float* src = reinterpret_cast<const float*>(ext_ptr(d, EXT_DIN, blockIdx.y));
+  const int64_t total = (int64_t)m.p * m.r;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) y[i] = src[i];
+}
+hipError_t launch_y_from_ext(const DevCtx& d, hipStream_t s) {
+  hipLaunchKernelGGL(k_y_from_ext, dim3(128, d.n), dim3(256), 0, s, d);
+  return hipGetLastError();
+}
 hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s) {
   hipLaunchKernelGGL(k_q_from_y, dim3(128, d.n), dim3(256), 0, s, d, ybuf);
   return hipGetLastError();

@@ -25,7 +25,7 @@ namespace {
     }                                                                                             \
   } while (0)
 
-enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK };
+enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT };
 
 struct Op {
   int kind;
@@ -66,7 +66,8 @@ struct Plan {
   bool y_fast_shapes = false;       // every matrix has q % 32 == 0 and r % 4 == 0
   std::vector<GemmDesc> desc_h;
   std::vector<GemmTile> gtile_h;
-  std::vector<Op> ops;
+  std::vector<Op> ops;              // the refresh
+  std::vector<Op> init_ops;         // Q_0 from a caller-supplied block: copy, orthonormalise, pack
 };
 
 constexpr int MAX_KSPLIT = 16;
@@ -278,6 +279,18 @@ struct ProgramBuilder {
       cur = dst;
     }
     return cur;
+  }
+
+  // Q_0 = orth(block supplied by the caller) (Alg. 1 Require: a random initial projection)
+  void build_init(int passes) {
+    std::vector<Op> saved;
+    saved.swap(P.ops);
+    simple(OP_Y_FROM_EXT);
+    const int ycur = orth(true, 0, passes);
+    simple(OP_Q_FROM_Y, ycur);
+    simple(OP_PACK);
+    P.init_ops.swap(P.ops);
+    P.ops.swap(saved);
   }
 
   void build(int power_iters, int passes) {
@@ -536,6 +549,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // refresh program
   ProgramBuilder pb(P, n);
   pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes);
+  pb.build_init(hp.orth_passes == 0 ? 2 : hp.orth_passes);
   P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
   P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());
   P.bytes = A.cur;
@@ -782,6 +796,9 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   return LORDO_OK;
 }
 
+static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, hipStream_t s, bool rotate, double c1, double c2,
+                   bool proj_kernels, bool stream_kernel);
+
 // Runs the refresh program on the source table currently selected in EXT_SRC; with `fold` the error
 // buffer first takes E <- fold_scale * G + E (Alg. 2, argument of ComputeProjection).
 static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold = false, double fold_scale = 0.0,
@@ -793,12 +810,23 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
     c1 = 1.0 - std::pow(c->hp.beta1, (double)c->t);
     c2 = 1.0 - std::pow(c->hp.beta2, (double)c->t);
   }
-  const GemmDesc* descs = c->at<GemmDesc>(P.descs);
-  const GemmTile* tiles = c->at<GemmTile>(P.gtiles);
   c->prof.begin(LORDO_K_REFRESH, s);
   if (fold)
     HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)fold_scale, c->hp.grad_dtype == LORDO_F32, s));
-  for (const Op& op : P.ops) {
+  int rc = run_ops(c, P.ops, src_dtype, s, rotate, c1, c2, proj_kernels, stream_kernel);
+  if (rc != LORDO_OK) return rc;
+  c->prof.end(LORDO_K_REFRESH, s);
+  c->refreshed = true;
+  return LORDO_OK;
+}
+
+// Enqueues one static program (the refresh, or the initial projection).
+static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, hipStream_t s, bool rotate, double c1, double c2,
+                   bool proj_kernels, bool stream_kernel) {
+  Plan& P = c->plan;
+  const GemmDesc* descs = c->at<GemmDesc>(P.descs);
+  const GemmTile* tiles = c->at<GemmTile>(P.gtiles);
+  for (const Op& op : ops) {
     if (op.rot_only && !rotate) continue;
     switch (op.kind) {
       case OP_GEMM:
@@ -836,11 +864,10 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
         break;
       case OP_Q_FROM_Y: HIPCHK(launch_q_from_y(c->dev, op.iarg, s)); break;
       case OP_PACK: HIPCHK(launch_pack_q(c->dev, 0, c->n, s)); break;
+      case OP_Y_FROM_EXT: HIPCHK(launch_y_from_ext(c->dev, s)); break;
       default: return LORDO_ESTATE;
     }
   }
-  c->prof.end(LORDO_K_REFRESH, s);
-  c->refreshed = true;
   return LORDO_OK;
 }
 
@@ -895,6 +922,15 @@ int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad
   for (int i = 0; i < c->n && proj_kernels; ++i)
     if ((P.mat[i].q & 1) != 0) proj_kernels = false;
   return run_refresh(c, LORDO_F32, s, true, grad_scale, proj_kernels, false);
+}
+
+int lordo_init_projection(lordo_ctx* c, const void* const* Block, void* stream) {
+  if (!c || !Block) return LORDO_EINVAL;
+  if (c->t != 0 || c->grad_folded) return LORDO_ESTATE;      // the moments would have to be rotated: that is what a refresh does
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(Block)), s);
+  if (rc != LORDO_OK) return rc;
+  return run_ops(c, c->plan.init_ops, LORDO_F32, s, false, 1.0, 1.0, false, false);
 }
 
 int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* DeltaOut, void* stream) {

@@ -21,7 +21,7 @@ EXPORTS = [
     "lordo_export_pseudograd", "lordo_outer_step", "lordo_get_state", "lordo_set_state",
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
     "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv", "lordo_refresh_subspace_local",
-    "lordo_export_uplink", "lordo_outer_step_lowrank",
+    "lordo_export_uplink", "lordo_outer_step_lowrank", "lordo_init_projection",
 ]
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
@@ -74,6 +74,7 @@ def load() -> C.CDLL:
     lib.lordo_refresh_subspace_local.argtypes = [vp, vpp, C.c_double, vpp, vp]
     lib.lordo_export_pseudograd.argtypes = [vp, vpp, vpp, vp]
     lib.lordo_outer_step.argtypes = [vp, vpp, vpp, vp]
+    lib.lordo_init_projection.argtypes = [vp, vpp, vp]
     lib.lordo_export_uplink.argtypes = [vp, vpp, vp]
     lib.lordo_outer_step_lowrank.argtypes = [vp, vpp, vpp, vp]
     lib.lordo_get_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
@@ -166,7 +167,7 @@ class Lordo:
         if len(ts) != self.n:
             raise ValueError("one tensor per matrix expected")
         for t, (p, q, r) in zip(ts, self.shapes):
-            want = {"pq": (p, q), "qr": (q, r), "rq": (r, q)}[kind]
+            want = {"pq": (p, q), "qr": (q, r), "rq": (r, q), "pr": (p, r)}[kind]
             if tuple(t.shape) != want or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
                 raise ValueError(f"expected contiguous CUDA {dtype} tensor of shape {want}, got {t.dtype} {tuple(t.shape)}")
 
@@ -178,6 +179,11 @@ class Lordo:
         self._check_tensors(W, self.torch.float32, "pq")
         self._check_tensors(G, self._grad_dtype(), "pq")
         _check(self.lib.lordo_local_step(self.ctx, _ptr_array(W), _ptr_array(G), float(lr), float(grad_scale), self._stream()))
+
+    def init_projection(self, block):
+        """Q_0 = orthonormal basis of the p x r blocks given (Alg. 1: random initial projection)."""
+        self._check_tensors(block, self.torch.float32, "pr")
+        _check(self.lib.lordo_init_projection(self.ctx, _ptr_array(block), self._stream()))
 
     def refresh_subspace(self, Src, Omega):
         dt = (Src.tensors if isinstance(Src, PtrList) else Src)[0].dtype

@@ -477,6 +477,32 @@ def test_uplink_buffer_and_lowrank_outer_step(torch, mode):
         assert e.value.code == lordo.ESTATE
 
 
+def test_random_initial_projection(torch):
+    """Alg. 1 starts from a random projection: Q_0 = orth(Gaussian block) on the device against the oracle's
+    (the factorisation with positive diagonal is unique, so the bases agree element by element), then steps."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(200, 330, 48), (300, 129, 33), (96, 160, 20), (256, 192, 128), (520, 392, 256)]
+    ohp, ghp = orc.Hyper(), lordo.hparams()
+    pair = Pair(torch, shapes, _weights(shapes, 26), ohp, ghp)
+    blocks = [np.random.default_rng(synth.seed_for(26, 300 + i)).standard_normal((p, r)).astype(np.float32)
+              for i, (p, q, r) in enumerate(shapes)]
+    pair.opt.init_projection(pair.to_dev(blocks, False))
+    pair.opt.poll_status()
+    for i, (p, q, r) in enumerate(shapes):
+        Qg = pair.get(i, lordo.STATE_Q)
+        Qo = orc.initial_projection(blocks[i])
+        assert np.linalg.norm(Qg.T @ Qg - np.eye(r)) <= TOL_ORTH
+        assert rel_l2(Qg, Qo) <= TOL, f"Q_0 of matrix {i}"
+        pair.st[i].Q = Qg                      # the oracle continues from the fp32 basis the library holds
+    gens = _spiked(shapes, 26, 8)
+    for t in range(2):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3, first_step_patch=(t == 0))
+    pair.compare_local(TOL)
+    with pytest.raises(lordo.LordoError) as e:     # moments are running: only a refresh may change the basis now
+        pair.opt.init_projection(pair.to_dev(blocks, False))
+    assert e.value.code == lordo.ESTATE
+
+
 def test_state_roundtrip_and_errors(torch):
     from paper_2602_04396_amd import lordo
     p, q, r = 70, 45, 9
