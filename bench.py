@@ -108,6 +108,20 @@ def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False):
     }
 
 
+def refresh_flops(shapes, q_it, rotate=True):
+    """Algorithmic flops of one subspace refresh: 2 q_it + 1 products with the source, CholeskyQR passes
+    (symmetric Gram r^2 rows, factorisation r^3 / 3, triangular apply r^2 rows; one pass per intermediate
+    block, two for the final basis) and the moment rotation (R = Q_new^T Q_old, R u, (R o R) w)."""
+    total = 0
+    for p, q, r in shapes:
+        total += (2 * q_it + 1) * 2 * p * q * r
+        y_passes = (q_it + 2) if q_it > 0 else 2
+        total += y_passes * (2 * p * r * r + r ** 3 // 3) + q_it * (2 * q * r * r + r ** 3 // 3)
+        if rotate:
+            total += 2 * p * r * r + 4 * r * r * q
+    return total
+
+
 def build_workload(torch, lordo, synth, cfg, rank, n_sets):
     shapes = synth.config_shapes(cfg, rank)
     d = synth.CONFIG_DEFAULTS[cfg]
@@ -296,6 +310,8 @@ def main():
                 entry["GBps"] = work[name]["bytes"] / (avg * 1e-3) / 1e9
                 if work[name]["flops"]:
                     entry["TFLOPps"] = work[name]["flops"] / (avg * 1e-3) / 1e12
+            if name == "refresh":
+                entry["TFLOPps"] = refresh_flops(shapes, d["power_iters"]) / (avg * 1e-3) / 1e12
             kernels[name] = entry
             total_by[name] = ms
         opt.profile_enable(False)
