@@ -104,7 +104,7 @@ constexpr int NB = 64;            // Cholesky / triangular-solve block size
 // ---------------------------------------------------------------------------------------
 // proj.hip
 struct DownFuse;     // below: state arrays and coefficients of the Adam update fused into the down-projection
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_rb, bool g_vec, bool g_once, float* glow,
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_rb, bool g_vec, bool g_tr, bool g_once, float* glow,
                             int64_t split_stride, float grad_scale, bool g_is_f32, int ef, const DownFuse* fuse, hipStream_t s);
 // Epilogue of the up-projection: target <- target + coef_acc * (Q B) + coef_g * G * c_j
 struct UpArgs {

@@ -762,7 +762,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   fuse.n_hi = c->at<uint16_t>(P.n_hi); fuse.n_lo = c->at<uint16_t>(P.n_lo);
   fuse.a = a;
   c->prof.begin(LORDO_K_DOWN, s);
-  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, P.g_once, c->at<float>(P.glow),
+  bool g_tr = true;             // 16-byte global-to-LDS loads of G need q % 8 == 0 and 16-byte aligned pointers
+  for (int i = 0; i < c->n && g_tr; ++i)
+    if ((P.mat[i].q & 7) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 15) != 0) g_tr = false;
+  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, g_tr, P.g_once, c->at<float>(P.glow),
                           P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
@@ -797,12 +800,12 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
 }
 
 static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, hipStream_t s, bool rotate, double c1, double c2,
-                   bool proj_kernels, bool stream_kernel);
+                   bool proj_kernels, bool stream_kernel, bool proj_tr = false);
 
 // Runs the refresh program on the source table currently selected in EXT_SRC; with `fold` the error
 // buffer first takes E <- fold_scale * G + E (Alg. 2, argument of ComputeProjection).
 static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold = false, double fold_scale = 0.0,
-                       bool proj_kernels = false, bool stream_kernel = false) {
+                       bool proj_kernels = false, bool stream_kernel = false, bool proj_tr = false) {
   Plan& P = c->plan;
   const bool rotate = c->t > 0;
   double c1 = 1.0, c2 = 1.0;
@@ -813,7 +816,7 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
   c->prof.begin(LORDO_K_REFRESH, s);
   if (fold)
     HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)fold_scale, c->hp.grad_dtype == LORDO_F32, s));
-  int rc = run_ops(c, P.ops, src_dtype, s, rotate, c1, c2, proj_kernels, stream_kernel);
+  int rc = run_ops(c, P.ops, src_dtype, s, rotate, c1, c2, proj_kernels, stream_kernel, proj_tr);
   if (rc != LORDO_OK) return rc;
   c->prof.end(LORDO_K_REFRESH, s);
   c->refreshed = true;
@@ -822,7 +825,7 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
 
 // Enqueues one static program (the refresh, or the initial projection).
 static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, hipStream_t s, bool rotate, double c1, double c2,
-                   bool proj_kernels, bool stream_kernel) {
+                   bool proj_kernels, bool stream_kernel, bool proj_tr) {
   Plan& P = c->plan;
   const GemmDesc* descs = c->at<GemmDesc>(P.descs);
   const GemmTile* tiles = c->at<GemmTile>(P.gtiles);
@@ -838,7 +841,7 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
           for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
           a.split_stride = P.lr_total;
           HIPCHK(launch_pack_y(c->dev, op.iarg, s));
-          HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, true, P.g_once,
+          HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, true, proj_tr, P.g_once,
                                   c->at<float>(P.glow), P.lr_total, 1.f, false, src_dtype == LORDO_F32 ? 2 : 0, nullptr, s));
           HIPCHK(launch_glow_to_z(c->dev, c->at<float>(P.glow), 0, a, s));
           break;
@@ -899,7 +902,11 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   bool stream_kernel = src_dtype == LORDO_BF16 && c->plan.y_fast_shapes;
   for (int i = 0; i < c->n && stream_kernel; ++i)
     if ((reinterpret_cast<uintptr_t>(Src[i]) & 15) != 0) stream_kernel = false;
-  return run_refresh(c, src_dtype, s, false, 0.0, proj_kernels, stream_kernel);
+  // global-to-LDS loads of a bf16 source in the down-projection kernel: q % 8 == 0, 16-byte aligned
+  bool proj_tr = proj_kernels && src_dtype == LORDO_BF16;
+  for (int i = 0; i < c->n && proj_tr; ++i)
+    if ((c->plan.mat[i].q & 7) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & 15) != 0) proj_tr = false;
+  return run_refresh(c, src_dtype, s, false, 0.0, proj_kernels, stream_kernel, proj_tr);
 }
 
 int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {

@@ -338,6 +338,11 @@ __device__ __forceinline__ void dma16_async(const GAS u32x4* src, u32x4* lds_dst
   const uint32_t lds_addr = (uint32_t)(uintptr_t)(LDS_AS void*)lds_dst_wave_base;
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
 }
+// The same with the non-temporal bit: for data that is read once (streaming lines in L2 and the last-level cache).
+__device__ __forceinline__ void dma16_async_nt(const GAS u32x4* src, u32x4* lds_dst_wave_base) {
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(LDS_AS void*)lds_dst_wave_base;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(src), "s"(lds_addr) : "memory", "m0");
+}
 #pragma clang diagnostic pop
 
 // Wait until at most N vector-memory operations are outstanding and all LDS operations are done,
@@ -628,6 +633,217 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Down-projection with the gradient moved by global-to-LDS loads only (bf16 G, q % 8 == 0, G 16-byte aligned).
+// The matrix-core operand wants, per lane, 8 consecutive ROWS of one column of G, which is row-major: in the
+// kernel above the rows pass through registers, are transposed there and written to LDS in fragment order.
+// gfx950 can do that transposition while READING LDS (ds_read_b64_tr_b16: sixteen lanes each fetch 8 bytes,
+// i.e. 4 consecutive columns of one row; the 4 x 16 block they cover -- lanes 4e .. 4e+3 hold row e -- comes
+// back with lane i holding column i, one element per row e; layout checked on the hardware).  So the G tile of
+// a stage (32 rows x 256 columns, 16 KiB) goes to LDS untouched, row-major, two rows per 1 KiB load, and a
+// fragment is two such reads (rows 0..3 and 4..7 of the lane's 8).  No vector ALU work and no LDS write per
+// stage is left, and with registers out of the path the ring can be deeper: NS stages of G and of the Q
+// fragments, NS - 1 of them in flight.
+// Bank spreading: a row is 512 bytes, so the 4 rows of one transposing read would meet in the same banks; the
+// 16-byte unit u of row k is therefore stored at unit u ^ 4 (k % 4) of the row (the per-lane global address
+// of the load picks the columns that land at each position).
+// Rows past the matrix are read from its last row: the operand planes of Q are zero there.  Column segments
+// past the last column are read from the last full segment (the results of such columns are never stored
+// beyond the padding of the low-rank state, which nothing reads).
+// ---------------------------------------------------------------------------------------
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x2 lds_read_tr16(const u32x4* lds_base, uint32_t byte_off) {
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (LDS_AS s16x4*)((LDS_AS char*)(LDS_AS void*)lds_base + byte_off));
+  return __builtin_bit_cast(u32x2, v);
+}
+
+template <int RB, bool GONCE>
+__global__ __launch_bounds__(512) void k_proj_down_tr(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
+                                                      int64_t split_stride, float grad_scale, FusedAdam fa) {
+  constexpr int BK = 32;
+  constexpr int NS = RB == 2 ? 3 : 4;                          // ring depth: 4 x 32 KiB or 3 x 48 KiB
+  constexpr int GSLOTS = 32 * 32;                              // 16-byte units of the raw G tile of a stage
+  constexpr int ASLOTS = 4 * RB * 2 * 2 * 64;                  // (mblk, kstep, plane, lane)
+  constexpr int SSLOTS = GSLOTS + ASLOTS;
+  constexpr int NDMA = 2 + 2 * RB;                             // loads per wave and stage
+  const ProjTile t = tiles[blockIdx.x];
+  if (t.mat < 0) return;
+  const MatDev m = d.mats[t.mat];
+  const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
+  const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
+  extern __shared__ u32x4 lds_dyn[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mb = wave & 3, nh = wave >> 2;
+  const int rblocks = m.rp / 32;
+  int mbg[RB];
+  bool active[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    mbg[rb] = t.m0 / 32 + mb + 4 * rb;
+    active[rb] = mbg[rb] < rblocks;
+  }
+
+  // G loads of this wave: chunks 2*wave and 2*wave + 1 of a stage = rows 4*wave .. 4*wave + 3
+  const GAS uint16_t* G = TO_GLOBAL(const uint16_t, ext_ptr(d, EXT_G, t.mat));
+  const int p = m.p, q = m.q;
+  const int last_seg = q / 8 - 1;
+  int grow[2];                                                 // row inside the stage
+  int64_t gcol[2];                                             // first column of the 16-byte segment this lane fetches
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    grow[j] = 4 * wave + 2 * j + (lane >> 5);
+    int seg = t.n0 / 8 + ((lane & 31) ^ (4 * (grow[j] & 3)));
+    seg = seg < last_seg ? seg : last_seg;
+    gcol[j] = (int64_t)seg * 8;
+  }
+  const int64_t kgroups = m.pp / 8;
+  const int kgmax = (int)kgroups - 2;
+  auto issue_stage = [&](int sidx, int sbuf) {                 // NDMA loads
+    const int kr = t.k0 + sidx * BK;
+    u32x4* gdst = lds_dyn + sbuf * SSLOTS;
+    u32x4* adst = gdst + GSLOTS;
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+      const int pair = wave * RB + j;
+      const int fmb = pair >> 1, fks = pair & 1;
+      const int fmbg = t.m0 / 32 + fmb < rblocks ? t.m0 / 32 + fmb : rblocks - 1;
+      int kg = kr / 8 + 2 * fks;
+      kg = kg < kgmax ? kg : kgmax;
+      const int64_t src = ((int64_t)fmbg * kgroups + kg) * 32 + lane;
+      dma16_async(qt_hi + src, adst + pair * 2 * 64);
+      dma16_async(qt_lo + src, adst + pair * 2 * 64 + 64);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int row = kr + grow[j];
+      row = row < p ? row : p - 1;
+      const GAS u32x4* gsrc = reinterpret_cast<const GAS u32x4*>(G + (int64_t)row * q + gcol[j]);
+      if constexpr (GONCE) dma16_async_nt(gsrc, gdst + (2 * wave + j) * 64);
+      else dma16_async(gsrc, gdst + (2 * wave + j) * 64);
+    }
+  };
+
+  // transposing reads: lane = (g, i), g = lane / 16, i = lane % 16; as a source it fetches row 8 (g / 2) + i / 4
+  // (+ 4 for the second read) of the k-step, columns 16 (g % 2) + 4 (i % 4) .. + 3 of the column block
+  const int tg = lane >> 4, ti = lane & 15;
+  uint32_t toff[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int unit = (16 * nh + 4 * (a ^ (ti >> 2)) + 2 * (tg & 1) + ((ti >> 1) & 1));    // u ^ 4 (k % 4), k % 4 = i / 4
+    toff[a] = (uint32_t)((8 * (tg >> 1) + (ti >> 2)) * 512 + unit * 16 + (ti & 1) * 8);
+  }
+
+  f32x16 acc[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][a][i] = 0.f;
+
+  auto compute = [&](int sbuf) {
+    if (!active[0]) return;
+    const u32x4* gb = lds_dyn + sbuf * SSLOTS;
+    const u32x4* ab = gb + GSLOTS;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      u32x4 ah[RB], al[RB], b[4];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        ah[rb] = ab[(((mb + 4 * rb) * 2 + ks) * 2 + 0) * 64 + lane];
+        al[rb] = ab[(((mb + 4 * rb) * 2 + ks) * 2 + 1) * 64 + lane];
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const u32x2 lo = lds_read_tr16(gb, toff[a] + (16 * ks) * 512);
+        const u32x2 hi = lds_read_tr16(gb, toff[a] + (16 * ks + 4) * 512);
+        b[a] = u32x4{lo.x, lo.y, hi.x, hi.y};
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          acc[rb][a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(ah[rb]), as_bf(b[a]), acc[rb][a], 0, 0, 0);
+          acc[rb][a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(al[rb]), as_bf(b[a]), acc[rb][a], 0, 0, 0);
+        }
+    }
+  };
+
+  const int nstages = (t.k1 - t.k0 + BK - 1) / BK;
+  // stages past the last one are loaded all the same (rows clamped, fragments clamped): the number of loads in
+  // flight is then the same in every iteration, which the explicit waits count on
+#pragma unroll
+  for (int s0 = 0; s0 < NS - 1; ++s0) issue_stage(s0, s0);
+  int sbuf = 0;
+  for (int s = 0; s < nstages; ++s) {
+    // at most NS - 2 younger stages outstanding: stage s has landed; barrier: visible to all, stage s-1 consumed by all
+    if constexpr ((NS - 2) * NDMA == 8) WAIT_VM_BARRIER(8);
+    else WAIT_VM_BARRIER(6);
+    static_assert((NS - 2) * NDMA == 8 || (NS - 2) * NDMA == 6, "wait count");
+    int nbuf = sbuf + NS - 1;
+    nbuf = nbuf >= NS ? nbuf - NS : nbuf;
+    issue_stage(s + NS - 1, nbuf);                              // into the buffer of stage s-1
+    ISSUE_FENCE();
+    compute(sbuf);
+    sbuf = sbuf + 1 == NS ? 0 : sbuf + 1;
+  }
+  WAIT_VM_BARRIER(0);             // the loads past the last stage must land before this workgroup's LDS is released
+
+  const int64_t base = m.lr_off;
+  GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + base;
+  const bool fuse = t.fuse != 0 && fa.u != nullptr;
+  const int64_t rgroups = m.rp / 8;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    if (!active[rb]) continue;
+    auto offset_of = [&](int nbg, int vq) {
+      return (((int64_t)nbg * rgroups + 4 * mbg[rb] + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+    };
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int nbg = t.n0 / 32 + 4 * nh + a;
+      if (nbg >= m.qp / 32) continue;
+      f32x4 uu[4], vv[4];
+      if (fuse) {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const int64_t at = base + offset_of(nbg, vq);
+          uu[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.u + at));
+          vv[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
+        }
+        ISSUE_FENCE();
+      }
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        const int64_t o = offset_of(nbg, vq);
+        f32x4 val;
+        val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
+        val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
+        *reinterpret_cast<GAS f32x4*>(out + o) = val;
+        if (fuse) adam4(fa, base + o, val, uu[vq], vv[vq]);
+      }
+    }
+  }
+}
+
+template <int RB, bool GONCE>
+static hipError_t launch_down_tr(dim3 grid, const DevCtx& d, const ProjTile* tiles, float* glow, int64_t split_stride,
+                                 float grad_scale, const FusedAdam& fa, hipStream_t s) {
+  constexpr int LDS_BYTES = (RB == 2 ? 3 * 48 : 4 * 32) * 1024;
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_down_tr<RB, GONCE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL((k_proj_down_tr<RB, GONCE>), grid, dim3(512), LDS_BYTES, s, d, tiles, glow, split_stride, grad_scale, fa);
+  return hipGetLastError();
+}
+
 // One instantiation of the pipelined kernel; its dynamic LDS (64 KiB for 128-rank tiles, 96 KiB for
 // 256-rank tiles, 32 KiB more with error feedback) is raised above the default limit at first use.
 template <int RB, bool VEC, bool GONCE, int EF>
@@ -662,7 +878,7 @@ static hipError_t launch_pipe_select(int rb, bool g_vec, bool g_once, int ef, di
 #undef LORDO_PIPE_RB
 }
 
-hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_rb, bool g_vec, bool g_once, float* glow,
+hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, int mb, int pipe_rb, bool g_vec, bool g_tr, bool g_once, float* glow,
                             int64_t split_stride, float grad_scale, bool g_is_f32, int ef, const DownFuse* fuse, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
@@ -673,6 +889,12 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
       fa.b1 = fuse->a.b1; fa.omb1 = fuse->a.omb1; fa.b2 = fuse->a.b2; fa.omb2 = fuse->a.omb2;
       fa.inv_c1 = fuse->a.inv_c1; fa.inv_c2 = fuse->a.inv_c2; fa.eps = fuse->a.eps;
     }
+    // 256-rank tiles (ranks from 256 up, where the matrix cores bound the kernel): gradient by global-to-LDS loads,
+    // transposed while it is read from LDS -- 8 to 11 % faster there than staging through registers; with 128-rank
+    // tiles (memory-bound, two workgroups per compute unit) the register-staged kernel is as fast or faster
+    if (g_tr && ef == 0 && pipe_rb == 2)
+      return g_once ? launch_down_tr<2, true>(grid, d, tiles, glow, split_stride, grad_scale, fa, s)
+                    : launch_down_tr<2, false>(grid, d, tiles, glow, split_stride, grad_scale, fa, s);
     return launch_pipe_select(pipe_rb, g_vec, g_once, ef, grid, d, tiles, glow, split_stride, grad_scale, fa, s);
   }
 #define LORDO_DOWN(MBV)                                                                                            \

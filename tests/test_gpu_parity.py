@@ -69,6 +69,20 @@ def test_local_steps_bf16_aligned_shapes(torch):
     print("aligned shapes: worst rel L2", worst, flush=True)
 
 
+def test_local_steps_large_ranks_several_rank_tiles(torch):
+    """Ranks above 256: several 256-rank tiles per column block of the down-projection (the gradient is then read
+    through L2 by each of them, with a ragged last tile), several rank chunks in the up-projection; 600 columns are
+    two 256-column tiles and a ragged third."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(400, 264, 320), (640, 600, 544), (96, 72, 20)]
+    pair = Pair(torch, shapes, _weights(shapes, 16), orc.Hyper(), lordo.hparams(grad_dtype=lordo.BF16), _rand_Q(shapes, 16))
+    gens = _spiked(shapes, 16, 8)
+    for t in range(3):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3, first_step_patch=(t == 0))
+        worst = pair.compare_local(TOL)
+    print("large ranks: worst rel L2", worst, flush=True)
+
+
 ALIGNED_SHAPES = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (130, 264, 128), (520, 392, 256)]
 
 
