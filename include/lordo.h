@@ -167,12 +167,29 @@ int lordo_outer_step(lordo_ctx* ctx, void* const* W, const void* const* AvgDelta
  * calls clear it.
  * lordo_export_uplink: AccOut_i <- A_i, plain row-major fp32 r x q (host array of n device pointers).
  * lordo_outer_step_lowrank: the outer step of lordo_outer_step with Delta_i = Q_i AvgAcc_i, AvgAcc the
- *   cross-worker mean of the exported buffers (fp32 r x q each; NULL: this worker's own buffer), formed
+ *   cross-worker mean of the exported buffers (fp32 r x q each; NULL: the buffer as it lies in the
+ *   workspace -- this worker's own, or the mean if the packed payload was averaged in place), formed
  *   tile by tile inside the update -- no p x q pseudo-gradient is materialised.  Every worker must hold
  *   the same Q (the global variant).  Overwrites the planes behind LORDO_STATE_NUPD.
  * Both return LORDO_ESTATE without hp.uplink_buffer. */
 int lordo_export_uplink(lordo_ctx* ctx, void* const* AccOut, void* stream);
 int lordo_outer_step_lowrank(lordo_ctx* ctx, void* const* W, const void* const* AvgAcc, void* stream);
+
+/* Packed synchronisation payload (Alg. 1, synchronisation of the optimizer states; App. A.5.1, "Worker
+ * Communication"): everything a worker sends at a synchronisation -- first moments, second moments and,
+ * with hp.uplink_buffer, the up-link buffers, of ALL matrices -- lies in one contiguous fp32 region of the
+ * workspace, [u | v | A], so that a single in-place all-reduce(mean) over it replaces one collective per
+ * matrix and tensor and no copy into a send buffer is needed.  The order of the elements inside the
+ * region is internal (operand layout with zero padding) but depends on (shapes, hparams) alone: element k
+ * means the same on every worker that was initialised alike, and padding is zero everywhere, so an
+ * elementwise mean of the regions is the mean of every tensor.
+ *   *dev_ptr        device pointer into the workspace (owned by the context, valid until lordo_destroy)
+ *   *count          fp32 elements in the region
+ *   *moments_count  (may be NULL) elements of the leading [u | v] part; the rest is A
+ * The caller reads and writes the region on the stream it passes to the neighbouring library calls.  After
+ * averaging it in place, lordo_outer_step_lowrank(ctx, W, NULL, stream) consumes the averaged A where it
+ * lies.  Per-tensor access in plain row-major layout stays with lordo_get_state / lordo_set_state. */
+int lordo_sync_payload(lordo_ctx* ctx, void** dev_ptr, size_t* count, size_t* moments_count);
 
 /* Copy one state tensor of matrix `mat` to / from a plain row-major fp32 device buffer of the
  * shape listed at the selector.  set_state(Q) expects orthonormal columns and rebuilds the packed

@@ -471,11 +471,11 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);
   P.v = A.take(sizeof(float) * lr);
+  if (hp.uplink_buffer) P.acc = A.take(sizeof(float) * lr);   // directly behind u and v: [u | v | A] is the packed payload
   P.n_hi = A.take(sizeof(uint16_t) * lr);
   P.n_lo = A.take(sizeof(uint16_t) * lr);
   if (hp.qhm_mode == 2) P.colpart = A.take(sizeof(float) * (lr / 32));
   if (hp.error_feedback) { P.g_hi = A.take(sizeof(uint16_t) * lr); P.g_lo = A.take(sizeof(uint16_t) * lr); }
-  if (hp.uplink_buffer) P.acc = A.take(sizeof(float) * lr);
   P.part_slices = small_out_split(P.mat.data(), n, nullptr);
   for (int i = 0; i < n; ++i) {
     MatDev& m = P.mat[i];
@@ -985,6 +985,19 @@ int lordo_export_uplink(lordo_ctx* c, void* const* AccOut, void* stream) {
   c->prof.begin(LORDO_K_EXPORT, s);
   HIPCHK(launch_lr_exchange(c->dev, c->at<float>(c->plan.acc), true, s));
   c->prof.end(LORDO_K_EXPORT, s);
+  return LORDO_OK;
+}
+
+int lordo_sync_payload(lordo_ctx* c, void** dev_ptr, size_t* count, size_t* moments_count) {
+  if (!c || !dev_ptr || !count) return LORDO_EINVAL;
+  const Plan& P = c->plan;
+  const size_t lr = (size_t)P.lr_total;
+  // the three flat arrays were taken from the arena back to back (their sizes are multiples of the arena's granule)
+  if (P.v != P.u + (int64_t)(sizeof(float) * lr) || (c->hp.uplink_buffer && P.acc != P.v + (int64_t)(sizeof(float) * lr)))
+    return LORDO_ESTATE;
+  *dev_ptr = c->at<void>(P.u);
+  *count = lr * (c->hp.uplink_buffer ? 3 : 2);
+  if (moments_count) *moments_count = lr * 2;
   return LORDO_OK;
 }
 

@@ -21,7 +21,7 @@ EXPORTS = [
     "lordo_export_pseudograd", "lordo_outer_step", "lordo_get_state", "lordo_set_state",
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
     "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv", "lordo_refresh_subspace_local",
-    "lordo_export_uplink", "lordo_outer_step_lowrank", "lordo_init_projection",
+    "lordo_export_uplink", "lordo_outer_step_lowrank", "lordo_init_projection", "lordo_sync_payload",
 ]
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
@@ -77,6 +77,7 @@ def load() -> C.CDLL:
     lib.lordo_init_projection.argtypes = [vp, vpp, vp]
     lib.lordo_export_uplink.argtypes = [vp, vpp, vp]
     lib.lordo_outer_step_lowrank.argtypes = [vp, vpp, vpp, vp]
+    lib.lordo_sync_payload.argtypes = [vp, vpp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     lib.lordo_get_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_set_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_get_mssv.argtypes = [vp, vp, vp]
@@ -226,6 +227,15 @@ class Lordo:
             _check(self.lib.lordo_outer_step_lowrank(self.ctx, _ptr_array(W), _ptr_array(avg_acc), self._stream()))
         else:
             _check(self.lib.lordo_outer_step_lowrank(self.ctx, _ptr_array(W), None, self._stream()))
+
+    def sync_payload(self):
+        """(payload, moments_count): the contiguous fp32 region [u | v | A] of the workspace as a tensor view
+        (Alg. 1 synchronisation; App. A.5.1) and the number of leading elements that are moments."""
+        ptr, count, moments = C.c_void_p(), C.c_size_t(), C.c_size_t()
+        _check(self.lib.lordo_sync_payload(self.ctx, C.byref(ptr), C.byref(count), C.byref(moments)))
+        off = ptr.value - self.arena.data_ptr()
+        assert 0 <= off and off + 4 * count.value <= self.arena.numel()
+        return self.arena[off:off + 4 * count.value].view(self.torch.float32), moments.value
 
     # -- state ------------------------------------------------------------------------------------
     def _state_shape(self, mat, which):

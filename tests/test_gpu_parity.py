@@ -491,6 +491,61 @@ def test_uplink_buffer_and_lowrank_outer_step(torch, mode):
         assert e.value.code == lordo.ESTATE
 
 
+def test_packed_sync_payload_two_workers(torch):
+    """Synchronisation through the packed payload (Alg. 1 synchronisation of the optimizer states; App. A.5.1): two
+    workers with the same Q and different gradients average the contiguous region [u | v | A] in place -- what a single
+    all-reduce(mean) would do -- and take the low-rank outer step from the averaged buffer where it lies.  Every tensor
+    must equal the mean of the two oracle workers' tensors, and both workers must end with identical weights."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128)]
+    kw = dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True)
+    ohp, ghp = orc.Hyper(uplink_buffer=True, **kw), lordo.hparams(uplink_buffer=True, **kw)
+    n = len(shapes)
+    W0, Q0 = _weights(shapes, 35), _rand_Q(shapes, 35)
+    workers = [Pair(torch, shapes, W0, ohp, ghp, Q0) for _ in range(2)]
+    gens = [_spiked(shapes, 35 + 40 * w, 4) for w in range(2)]
+    step = 0
+    for window in range(2):
+        for k in range(3):
+            for w, pair in enumerate(workers):
+                pair.local_step([g.draw(step) for g in gens[w]], lr=1e-3 * (1 + k), first_step_patch=(step == 0))
+            step += 1
+        for pair in workers:
+            pair.compare_local(TOL)
+        views = [pair.opt.sync_payload() for pair in workers]
+        lr_total = views[0][1] // 2
+        assert views[0][0].numel() == 3 * lr_total and views[0][1] == views[1][1]
+        assert lr_total >= sum(r * q for p, q, r in shapes)
+        mean = (views[0][0] + views[1][0]) * 0.5                   # the collective, stood in for by one elementwise mean
+        for v, _ in views:
+            v.copy_(mean)
+        # oracle: the same means, tensor by tensor
+        for i in range(n):
+            u = 0.5 * (workers[0].st[i].u + workers[1].st[i].u)
+            v = 0.5 * (workers[0].st[i].v + workers[1].st[i].v)
+            A = 0.5 * (workers[0].st[i].A + workers[1].st[i].A)
+            for pair in workers:
+                pair.st[i].u, pair.st[i].v = u.copy(), v.copy()
+                assert rel_l2(pair.get(i, lordo.STATE_U), u) <= TOL
+                assert rel_l2(pair.get(i, lordo.STATE_V), v) <= TOL
+                assert rel_l2(pair.get(i, lordo.STATE_UPLINK), A) <= TOL
+                pair.W_orc[i] = orc.outer_step_lowrank(pair.st[i], A, ohp)
+        for pair in workers:
+            pair.opt.outer_step_lowrank(pair.W_gpu, None)
+            pair.opt.poll_status()
+        for i in range(n):
+            for pair in workers:
+                got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
+                assert rel_l2(got - pair.W0[i], pair.W_orc[i] - pair.W0[i]) <= TOL, f"window {window} matrix {i}"
+                assert rel_l2(pair.get(i, lordo.STATE_MOM), pair.st[i].b) <= TOL
+                assert not pair.opt.get_state(i, lordo.STATE_UPLINK).any()
+            assert torch.equal(workers[0].W_gpu[i], workers[1].W_gpu[i])       # same inputs, deterministic kernels
+    # without the up-link buffer the payload is the moments alone
+    plain = Pair(torch, shapes[:2], _weights(shapes[:2], 35), orc.Hyper(), lordo.hparams())
+    view, moments = plain.opt.sync_payload()
+    assert view.numel() == moments
+
+
 def test_random_initial_projection(torch):
     """Alg. 1 starts from a random projection: Q_0 = orth(Gaussian block) on the device against the oracle's
     (the factorisation with positive diagonal is unique, so the bases agree element by element), then steps."""
