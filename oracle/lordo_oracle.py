@@ -58,6 +58,7 @@ class Hyper:
     outer_momentum: float = 0.0
     outer_nesterov: bool = False
     power_iters: int = 2
+    rayleigh_ritz: bool = False     # order the basis as singular vectors (Sec. 2: Q = first r columns of U)
 
 
 @dataclass
@@ -190,6 +191,22 @@ def range_finder(A: np.ndarray, Omega: np.ndarray, power_iters: int) -> np.ndarr
     return Y
 
 
+def rayleigh_ritz(Q: np.ndarray, A: np.ndarray):
+    """Turn an orthonormal basis Q of (approximately) the leading left singular subspace of A into
+    (approximate) singular vectors in the order of Sec. 2's ComputeProjection (Q = U[:, :r] of the SVD,
+    largest singular value first): B = Q^T A (r x q) is the matrix restricted to the subspace;
+    B = U_B S V^T is a small SVD; Q U_B are the Ritz vectors and S the Ritz values.  The span is unchanged.
+    Each column is signed so that its entry of largest magnitude is positive.  Returns (Q U_B, S)."""
+    Q = np.asarray(Q, dtype=F64)
+    B = Q.T @ np.asarray(A, dtype=F64)
+    U_B, S, _ = np.linalg.svd(B, full_matrices=False)
+    Qr = Q @ U_B[:, :Q.shape[1]]
+    lead = np.argmax(np.abs(Qr), axis=0)
+    sign = np.sign(Qr[lead, np.arange(Qr.shape[1])])
+    sign[sign == 0] = 1.0
+    return Qr * sign[None, :], S[:Q.shape[1]]
+
+
 def rotate_moments(Q_new, Q_old, u, v, t: int, hp: Hyper):
     """Alg. 1, "rotate the first / second moment locally" (same lines in Alg. 2):
     R = Q_new^T Q_old;  u <- R u;
@@ -209,8 +226,12 @@ def refresh_subspace(st: MatrixState, A_src: np.ndarray, Omega: np.ndarray, hp: 
     """New projection from A_src, then rotation of both moments into it.
     `Q_forced` replaces the computed basis (tests use it to teacher-force the
     basis the other implementation found; the rotation is basis dependent)."""
-    Q_new = range_finder(A_src, Omega, hp.power_iters) if Q_forced is None \
-        else np.asarray(Q_forced, dtype=F64)
+    if Q_forced is None:
+        Q_new = range_finder(A_src, Omega, hp.power_iters)
+        if hp.rayleigh_ritz:
+            Q_new, _ = rayleigh_ritz(Q_new, A_src)
+    else:
+        Q_new = np.asarray(Q_forced, dtype=F64)
     if st.t > 0:                                        # before any step both moments are zero
         st.u, st.v = rotate_moments(Q_new, st.Q, st.u, st.v, st.t, hp)
     st.Q = Q_new

@@ -369,6 +369,52 @@ def test_range_finder_reaches_svd_projector_with_a_gap():
     assert np.linalg.norm(Q @ Q.T - Qs @ Qs.T) < 1e-9
 
 
+def test_rayleigh_ritz_gives_the_ordered_singular_vectors_of_the_svd_projection():
+    """With a gap at r and a converged range finder, the Rayleigh-Ritz step turns the basis into the columns of
+    U[:, :r] of the paper's SVD projection (Sec. 2), in its order, up to the sign of each column, and returns
+    the leading singular values.  The full SVD of A by the library is the external reference."""
+    rng = rng_of(41)
+    p, q, r = 48, 40, 5
+    sv = np.concatenate([np.array([9.0, 7.5, 6.5, 5.5, 5.0]), 0.5 * rng.random(q - r)])
+    A = (synth.orthonormal(rng, p, p)[:, :q] * sv) @ synth.orthonormal(rng, q, q).T
+    Q = orc.range_finder(A, rng.standard_normal((q, r)), 12)
+    Qr, S = orc.rayleigh_ritz(Q, A)
+    U, S_full, _ = np.linalg.svd(A, full_matrices=False)
+    assert np.allclose(S, S_full[:r], rtol=1e-10)
+    overlaps = np.abs(np.sum(Qr * U[:, :r], axis=0))           # |<column i, u_i>|
+    assert np.all(overlaps > 1 - 1e-9)
+    # a transposed small factor or an unsorted order would fail here: column 0 must be u_1, not any other
+    assert abs(Qr[:, 0] @ U[:, 0]) > 1 - 1e-9 and abs(Qr[:, 0] @ U[:, 1]) < 1e-6
+    # sign convention: the entry of largest magnitude of every column is positive
+    assert np.all(Qr[np.argmax(np.abs(Qr), axis=0), np.arange(r)] > 0)
+
+
+def test_rayleigh_ritz_keeps_the_span_and_diagonalises_the_restricted_matrix():
+    """For ANY orthonormal Q (no convergence assumed): same projector, orthonormal columns, Q'^T A A^T Q' diagonal
+    with the squared Ritz values in descending order, and their sum equal to the energy ||Q^T A||_F^2 the
+    subspace captures."""
+    rng = rng_of(42)
+    p, q, r = 37, 29, 6
+    A = rng.standard_normal((p, q))
+    Q = synth.orthonormal(rng, p, r)
+    Qr, S = orc.rayleigh_ritz(Q, A)
+    assert np.linalg.norm(Qr @ Qr.T - Q @ Q.T) < 1e-12
+    assert np.abs(Qr.T @ Qr - np.eye(r)).max() < 1e-12
+    D = Qr.T @ A @ A.T @ Qr
+    assert np.abs(D - np.diag(S * S)).max() < 1e-10
+    assert np.all(np.diff(S) <= 0)
+    assert abs(np.sum(S * S) - np.linalg.norm(Q.T @ A) ** 2) < 1e-10
+    # refresh_subspace applies it when asked to
+    hp = orc.Hyper(power_iters=1, rayleigh_ritz=True)
+    st = orc.init_state(np.zeros((p, q)), r)
+    Om = rng.standard_normal((q, r))
+    Qn = orc.refresh_subspace(st, A, Om, hp)
+    Qplain = orc.range_finder(A, Om, 1)
+    assert np.linalg.norm(Qn @ Qn.T - Qplain @ Qplain.T) < 1e-12
+    Dn = Qn.T @ A @ A.T @ Qn
+    assert np.abs(Dn - np.diag(np.diag(Dn))).max() < 1e-10 and np.all(np.diff(np.diag(Dn)) <= 1e-12)
+
+
 def test_range_finder_rank_deficient_source_still_reconstructs():
     """rank(A) < r: the basis is completed arbitrarily; only Q^T Q = I and Q Q^T A = A are fixed."""
     rng = rng_of(16)
