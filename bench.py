@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-events", action="store_true", help="skip the event-timed second pass")
     ap.add_argument("--refresh-every", type=int, default=None)
     ap.add_argument("--outer-every", type=int, default=None)
+    ap.add_argument("--rayleigh-ritz", action="store_true",
+                    help="end every refresh with the Rayleigh-Ritz step (basis ordered as singular vectors; ranks up to 128)")
     ap.add_argument("--update", default="plain", choices=["plain", "low-qhm", "full-qhm", "ef", "global", "local", "uplink"],
                     help="update case of the local step: plain (default, the headline), low-rank / full-rank QHM (omega 0.9), "
                          "error feedback, global = full-rank QHM + error feedback (the paper's LoRDO-Global), local = low-rank QHM + error "
@@ -261,7 +263,8 @@ def main():
     local_variant = args.update == "local"
     hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=d["power_iters"],
                        grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
-                       qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef, uplink_buffer=uplink)
+                       qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef, uplink_buffer=uplink,
+                       rayleigh_ritz=args.rayleigh_ritz)
     opt = lordo.Lordo(shapes, hp, W, torch)
     Wp = opt.ptrs(W)
     Gp = [opt.ptrs(g, grad_dtype) for g in G]
@@ -343,7 +346,7 @@ def main():
                    "matrices": len(shapes), "params": sum(p * q for p, q, r in shapes),
                    "refresh_every": refresh_every, "outer_every": outer_every, "power_iters": d["power_iters"],
                    "grad_sets": n_sets, "outer": "nesterov lr 0.7 momentum 0.9 on a generated averaged pseudo-gradient",
-                   "update": args.update},
+                   "update": args.update, "rayleigh_ritz": bool(args.rayleigh_ritz)},
         "roofline": roofline,
         "kernels": kernels,
         "cpu_baseline": cpu,

@@ -57,6 +57,8 @@ extern "C" {
                                           refresh and of lordo_outer_step_lowrank) */
 #define LORDO_STATE_ERR     7   /* p x q  error-feedback residual E (only if error_feedback != 0) */
 #define LORDO_STATE_UPLINK  8   /* r x q  up-link buffer A (only if uplink_buffer != 0)           */
+#define LORDO_STATE_RITZ    9   /* r      Ritz values of the last refresh, descending: the singular values of the source
+                                          restricted to span(Q) (read only; only if rayleigh_ritz != 0, after a refresh) */
 
 typedef struct lordo_ctx lordo_ctx;
 
@@ -84,6 +86,11 @@ typedef struct {
   int32_t grad_dtype;            /* LORDO_BF16 or LORDO_F32: element type of every G                    */
   int32_t uplink_buffer;         /* 1: keep the r x q up-link buffer A = sum over the window of eta_t N_t (App. A.5.1);
                                     not with qhm_mode 2, whose update has no low-rank form              */
+  int32_t rayleigh_ritz;         /* 1: every refresh ends with a Rayleigh-Ritz step, so that the columns of Q are the
+                                    approximate left singular vectors of the source, largest singular value first, as
+                                    the SVD projection of Sec. 2 orders them (0: an unordered orthonormal basis of the
+                                    same subspace).  Needs every rank <= 128 (LORDO_EINVAL otherwise)        */
+  int32_t reserved;              /* must be 0 */
 } lordo_hparams;
 
 /* Bytes of arena lordo_init needs for these shapes and hyper-parameters (host call). */

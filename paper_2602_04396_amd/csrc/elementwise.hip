@@ -725,6 +725,190 @@ hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Rayleigh-Ritz step of the refresh (Sec. 2 ComputeProjection wants Q = the first r columns of U, largest
+// singular value first): eigen-decomposition T = U diag(lambda) U^T of the r x r matrix T = (Q^T Src)(Q^T Src)^T,
+// r <= 128, one workgroup per matrix, T and U in LDS (odd row pitch).  Cyclic two-sided Jacobi with the
+// round-robin order: a sweep is n-1 rounds of n/2 disjoint plane rotations (n = r rounded up to even; the
+// added index has a zero row and column and is never rotated).  A round has three phases separated by
+// barriers: the n/2 rotations (c, s) that annihilate T[p][q]; columns p, q of T and of U combined; rows p, q
+// of T combined.  A rotation is skipped where |T[p][q]| is below 1e-7 sqrt(T[p][p] T[q][q]) or below
+// 3e-8 of the largest diagonal entry (the entries of T carry that much rounding already); the iteration
+// ends with the first sweep that rotates nothing, after at most 15 sweeps.
+// Output: column k of `lfac` (r x r row-major) = eigenvector of the k-th largest eigenvalue, signed so that
+// its entry of largest magnitude is positive; ritz[k] = sqrt(max(lambda_k, 0)), the Ritz values of Src.
+// Reads the lower triangle of `gram` only.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
+  const MatDev m = d.mats[blockIdx.x];
+  const int r = m.r;
+  if (r > 128 || m.ritz < 0) return;
+  const int n = (r + 1) & ~1;
+  const int ld = n + 1;
+  const int half = n / 2;
+  extern __shared__ float jsm[];
+  float* A = jsm;
+  float* V = A + n * ld;
+  float* cs = V + n * ld;                 // c[0..half), s[0..half)
+  float* lam = cs + n;                    // n
+  __shared__ int rotated;
+  __shared__ float amax_s;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const float* T = reinterpret_cast<const float*>(d.arena + m.gram);
+
+  for (int idx = tid; idx < n * n; idx += nt) {
+    const int i = idx / n, j = idx - i * n;
+    float v = 0.f;
+    if (i < r && j < r) v = i >= j ? T[(int64_t)i * r + j] : T[(int64_t)j * r + i];
+    A[i * ld + j] = v;
+    V[i * ld + j] = i == j ? 1.f : 0.f;
+  }
+  if (tid == 0) rotated = 0;
+  __syncthreads();
+  if (tid < 64) {                         // largest diagonal entry (one wave)
+    float mx = 0.f;
+    for (int i = tid; i < r; i += 64) mx = fmaxf(mx, fabsf(A[i * ld + i]));
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (tid == 0) amax_s = mx;
+  }
+  __syncthreads();
+  const float abs_thr = 3e-8f * amax_s;
+  const int mm = n - 1;                   // players 0 .. mm-1 rotate, player mm stays
+  int* pairs = reinterpret_cast<int*>(lam);   // p | q << 8 of the round's pairs (the eigenvalue array is filled at the end)
+
+  // work items of the two update phases: (pair k, row or column i), the same for every round.  A wave takes up to
+  // four pairs and its lanes the rows (columns) lane and lane + 64: the rotation of a pair is read once per wave
+  // and phase, and the lanes of an access fall on consecutive rows (columns).
+  constexpr int ITEMS = 8;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int kpw = (half + (nt >> 6) - 1) / (nt >> 6);      // pairs per wave, at most 4
+  int kk[ITEMS], ii[ITEMS];
+#pragma unroll
+  for (int j = 0; j < ITEMS; ++j) {
+    const int a = j >> 1, k = wave * kpw + a, i = lane + 64 * (j & 1);
+    kk[j] = (a < kpw && k < half && i < n) ? k : -1;
+    ii[j] = i;
+  }
+
+  for (int sweep = 0; sweep < 15; ++sweep) {
+    for (int round = 0; round < mm; ++round) {
+      // pair k of this round (circle method): k = 0: (round % mm, mm); k > 0: ((round + k) % mm, (round + mm - k) % mm)
+      if (tid < half) {
+        const int k = tid;
+        int a = (round + k) % mm, b = k == 0 ? mm : (round + mm - k) % mm;
+        const int pi = a < b ? a : b, qi = a < b ? b : a;
+        const float app = A[pi * ld + pi], aqq = A[qi * ld + qi], apq = A[pi * ld + qi];
+        float c = 1.f, sn = 0.f;
+        const float mag = fabsf(apq);
+        if (mag > abs_thr && mag > 1e-7f * sqrtf(fabsf(app * aqq))) {
+          const float tau = (aqq - app) / (2.f * apq);
+          const float t = copysignf(1.f, tau) / (fabsf(tau) + sqrtf(1.f + tau * tau));
+          c = 1.f / sqrtf(1.f + t * t);
+          sn = t * c;
+          rotated = 1;                    // benign race: every writer stores 1
+        }
+        cs[k] = c;
+        cs[half + k] = sn;
+        pairs[k] = pi | (qi << 8);
+      }
+      __syncthreads();
+      // columns p, q of T and U:  x_p' = c x_p - s x_q,  x_q' = s x_p + c x_q.  All operands of a thread's items
+      // are read before any is written, so that the LDS reads overlap.
+      {
+        float c8[ITEMS], s8[ITEMS], ap[ITEMS], aq[ITEMS], vp[ITEMS], vq[ITEMS];
+        int op[ITEMS], oq[ITEMS];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+          s8[j] = 0.f;
+          if (kk[j] >= 0) {
+            const int pr = pairs[kk[j]];
+            c8[j] = cs[kk[j]]; s8[j] = cs[half + kk[j]];
+            op[j] = ii[j] * ld + (pr & 255); oq[j] = ii[j] * ld + (pr >> 8);
+            ap[j] = A[op[j]]; aq[j] = A[oq[j]];
+            vp[j] = V[op[j]]; vq[j] = V[oq[j]];
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+          if (s8[j] != 0.f) {
+            A[op[j]] = c8[j] * ap[j] - s8[j] * aq[j];
+            A[oq[j]] = s8[j] * ap[j] + c8[j] * aq[j];
+            V[op[j]] = c8[j] * vp[j] - s8[j] * vq[j];
+            V[oq[j]] = s8[j] * vp[j] + c8[j] * vq[j];
+          }
+      }
+      __syncthreads();
+      // rows p, q of T
+      {
+        float c8[ITEMS], s8[ITEMS], ap[ITEMS], aq[ITEMS];
+        int op[ITEMS], oq[ITEMS];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+          s8[j] = 0.f;
+          if (kk[j] >= 0) {
+            const int pr = pairs[kk[j]];
+            c8[j] = cs[kk[j]]; s8[j] = cs[half + kk[j]];
+            op[j] = (pr & 255) * ld + ii[j]; oq[j] = (pr >> 8) * ld + ii[j];
+            ap[j] = A[op[j]]; aq[j] = A[oq[j]];
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+          if (s8[j] != 0.f) {
+            A[op[j]] = c8[j] * ap[j] - s8[j] * aq[j];
+            A[oq[j]] = s8[j] * ap[j] + c8[j] * aq[j];
+          }
+      }
+      __syncthreads();
+    }
+    const int any = rotated;              // all rounds of the sweep are behind a barrier
+    __syncthreads();
+    if (tid == 0) rotated = 0;
+    __syncthreads();
+    if (!any) break;
+#ifdef LORDO_JACOBI_DEBUG
+    if (tid == 0 && blockIdx.x < 3) printf("jacobi mat %d r %d sweep %d done\n", (int)blockIdx.x, r, sweep);
+#endif
+  }
+
+  for (int i = tid; i < n; i += nt) lam[i] = i < r ? A[i * ld + i] : 0.f;
+  __syncthreads();
+  // descending order (ties by index); one thread per eigenvector writes its column
+  for (int i = tid; i < r; i += nt) {
+    const float li = lam[i];
+    int rank = 0;
+    for (int j = 0; j < r; ++j) rank += (lam[j] > li || (lam[j] == li && j < i)) ? 1 : 0;
+    float best = 0.f, bestv = 1.f;
+    for (int row = 0; row < r; ++row) {
+      const float v = V[row * ld + i];
+      if (fabsf(v) > best) { best = fabsf(v); bestv = v; }
+    }
+    const float sg = bestv < 0.f ? -1.f : 1.f;
+    float* U = reinterpret_cast<float*>(d.arena + m.lfac);
+    for (int row = 0; row < r; ++row) U[(int64_t)row * r + rank] = sg * V[row * ld + i];
+    reinterpret_cast<float*>(d.arena + m.ritz)[rank] = sqrtf(fmaxf(li, 0.f));
+    if (!(fabsf(li) <= 3.0e38f)) *d.flag = 1;      // NaN or infinity in the Ritz matrix
+  }
+}
+size_t jacobi_lds_bytes(int rmax) {
+  const int n = (rmax + 1) & ~1;
+  return sizeof(float) * ((size_t)2 * n * (n + 1) + 2 * n);
+}
+hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, hipStream_t s) {
+  if (rmax > 128) return hipErrorInvalidValue;
+  const size_t lds = jacobi_lds_bytes(rmax);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_eigh), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)jacobi_lds_bytes(128));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int threads = rmax > 64 ? 1024 : (rmax > 32 ? 512 : 256);
+  hipLaunchKernelGGL(k_jacobi_eigh, dim3(d.n), dim3(threads), lds, s, d);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // moment rotation, elementwise parts.  Plain temporaries are q x r row-major (the transposes of
 // the paper's r x q arrays): zw[2] = u_hat^T, zw[3] = (v_hat - u_hat^2)^T; the two GEMMs leave
 // zw[0] = (R u_hat)^T and zw[1] = ((R o R)(v_hat - u_hat^2))^T.

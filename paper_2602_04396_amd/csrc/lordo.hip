@@ -25,7 +25,7 @@ namespace {
     }                                                                                             \
   } while (0)
 
-enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT };
+enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT, OP_EIGH };
 
 struct Op {
   int kind;
@@ -47,6 +47,7 @@ struct Plan {
   int64_t nchunks = 0;
   int mb = 4;
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
+  int r_max = 0;                    // largest rank of any matrix
   int down_pipe = 0;                // pipelined down-projection: rank blocks per wave (1: 128-rank tiles, 2: 256-rank), 0: plain kernel
   int rank_tile = 128;              // rank indices per down-projection tile
   bool g_once = true;               // every matrix has one rank tile of the down-projection: G is read exactly once
@@ -193,7 +194,7 @@ struct ProgramBuilder {
 
   // Thin QR of the block held in buffer `cur` of the pair selected by `buf` (rows = p or q),
   // by `passes` rounds of CholeskyQR; returns the buffer index that holds the result.
-  int orth(bool y_side, int cur, int passes) {
+  int orth(bool y_side, int cur, int passes, bool shifted = true) {
     auto buf_of = [&](int i, int which) { return y_side ? P.mat[i].y[which] : P.mat[i].zw[which]; };
     auto rows_of = [&](int i) { return y_side ? P.mat[i].p : P.mat[i].q; };
     int max_blocks = 0;
@@ -208,7 +209,7 @@ struct ProgramBuilder {
         g.M = m.r; g.N = m.r; g.K = rows_of(i);
         return true;
       }, false, true, true);      // the factorisation reads the lower triangle only
-      if (pass == 0) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
+      if (pass == 0 && shifted) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
       for (int jb = 0; jb < max_blocks; ++jb) {
         simple(OP_POTF2, jb);
         // L_21 = S_21 L_11^{-T}
@@ -293,7 +294,7 @@ struct ProgramBuilder {
     P.ops.swap(saved);
   }
 
-  void build(int power_iters, int passes) {
+  void build(int power_iters, int passes, bool rayleigh_ritz) {
     // Y = Src Omega
     gemm([&](int i, GemmDesc& g) {
       const MatDev& m = P.mat[i];
@@ -335,6 +336,41 @@ struct ProgramBuilder {
       P.ops.back().iarg = zcur;
       ycur = orth(true, 0, it + 1 < power_iters ? 1 : passes);
     }
+    if (rayleigh_ritz) {
+      // Rayleigh-Ritz step (Sec. 2: Q = the first r columns of U, largest singular value first):
+      // Z = Src^T Y (= B^T, B the source restricted to the subspace), T = Z^T Z = B B^T, T = U diag U^T, Y <- Y U
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2; g.prec = 1;
+        g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.zw[0]); g.ldc = m.r;
+        g.M = m.q; g.N = m.r; g.K = m.p;
+        return true;
+      });
+      P.ops.back().fast = 1;
+      P.ops.back().iarg = ycur;
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_arena(m.zw[0]); g.sAm = 1; g.sAk = m.r;
+        g.B = ref_arena(m.zw[0]); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.gram); g.ldc = m.r;
+        g.M = m.r; g.N = m.r; g.K = m.q;
+        return true;
+      }, false, true, true);      // the eigen-solver reads the lower triangle only
+      simple(OP_EIGH);            // eigenvectors, by descending eigenvalue, into the buffer of the Cholesky factor
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_arena(m.y[ycur]); g.sAm = m.r; g.sAk = 1;
+        g.B = ref_arena(m.lfac); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.y[1 - ycur]); g.ldc = m.r;
+        g.M = m.p; g.N = m.r; g.K = m.r;
+        return true;
+      });
+      // the accumulated plane rotations are orthogonal to about 1e-6 per entry only: one CholeskyQR pass (unshifted:
+      // the block is orthonormal to 1e-4 already) brings the columns back to working precision without changing
+      // their order or, visibly, their directions
+      ycur = orth(true, 1 - ycur, 1, false);
+    }
     // rotation: R = Q_new^T Q_old (and R o R)
     gemm([&](int i, GemmDesc& g) {
       const MatDev& m = P.mat[i];
@@ -373,6 +409,10 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
   if ((hp->uplink_buffer != 0 && hp->uplink_buffer != 1) || (hp->uplink_buffer && hp->qhm_mode == 2)) return LORDO_EINVAL;
   if (hp->qhm_mode != 0 && !(hp->omega >= 0.0 && hp->omega <= 1.0)) return LORDO_EINVAL;
   if (hp->power_iters < 0 || hp->power_iters > 8) return LORDO_EINVAL;
+  if ((hp->rayleigh_ritz != 0 && hp->rayleigh_ritz != 1) || hp->reserved != 0) return LORDO_EINVAL;
+  if (hp->rayleigh_ritz)          // the r x r eigen-solver keeps its two matrices in the LDS of one compute unit
+    for (int i = 0; i < n; ++i)
+      if (shapes[i].rank > 128) return LORDO_EINVAL;
   if (hp->orth_passes != 0 && hp->orth_passes != 2 && hp->orth_passes != 3) return LORDO_EINVAL;
   if (hp->grad_dtype != LORDO_BF16 && hp->grad_dtype != LORDO_F32) return LORDO_EINVAL;
   if (!std::isfinite(hp->outer_lr) || !std::isfinite(hp->outer_momentum)) return LORDO_EINVAL;
@@ -395,6 +435,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.p = (int)shapes[i].rows; m.q = (int)shapes[i].cols; m.r = shapes[i].rank;
     m.pp = (int)pad32(m.p); m.qp = (int)pad32(m.q); m.rp = (int)pad32(m.r);
     rp_max = std::max(rp_max, m.rp);
+    P.r_max = std::max(P.r_max, (int)m.r);
     pp_min = std::min(pp_min, m.pp);
     P.chunk_start_h[i] = chunks;
     chunks += ((int64_t)m.p * m.q + CHUNK - 1) / CHUNK;
@@ -494,6 +535,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.minv = A.take(rr * 4);
     m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
     m.part = A.take(rr * 4 * P.part_slices);
+    m.ritz = hp.rayleigh_ritz ? A.take((size_t)m.r * 4) : -1;
   }
   // projection tile tables
   std::vector<ProjTile> down, up;
@@ -548,7 +590,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   }
   // refresh program
   ProgramBuilder pb(P, n);
-  pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes);
+  pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes, hp.rayleigh_ritz != 0);
   pb.build_init(hp.orth_passes == 0 ? 2 : hp.orth_passes);
   P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
   P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());
@@ -859,6 +901,7 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
+      case OP_EIGH: HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, s)); break;
       case OP_ROT_PRE:
         HIPCHK(launch_rot_pre(c->dev, c->at<float>(P.u), c->at<float>(P.v), (float)(1.0 / c1), (float)(1.0 / c2), s));
         break;
@@ -1082,6 +1125,10 @@ int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, voi
     case LORDO_STATE_UPLINK:
       if (P.acc < 0) return LORDO_ESTATE;
       HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.acc), nullptr, nullptr, dst, 1, 0, s));
+      break;
+    case LORDO_STATE_RITZ:
+      if (m.ritz < 0 || !c->refreshed) return LORDO_ESTATE;
+      HIPCHK(launch_copy_f32(dst, c->at<float>(m.ritz), (int64_t)m.r, s));
       break;
     case LORDO_STATE_U: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.u), nullptr, nullptr, dst, 1, 0, s)); break;
     case LORDO_STATE_V: HIPCHK(launch_lr_to_plain(c->dev, mat, c->at<float>(P.v), nullptr, nullptr, dst, 1, 0, s)); break;

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "lib", "liblordo.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE, ENUMERIC = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-STATE_Q, STATE_U, STATE_V, STATE_ANCHOR, STATE_MOM, STATE_GLOW, STATE_NUPD, STATE_ERR, STATE_UPLINK = range(9)
+STATE_Q, STATE_U, STATE_V, STATE_ANCHOR, STATE_MOM, STATE_GLOW, STATE_NUPD, STATE_ERR, STATE_UPLINK, STATE_RITZ = range(10)
 
 EXPORTS = [
     "lordo_workspace_bytes", "lordo_init", "lordo_local_step", "lordo_refresh_subspace",
@@ -39,14 +39,16 @@ class HParams(C.Structure):
         ("outer_lr", C.c_double), ("outer_momentum", C.c_double),
         ("power_iters", C.c_int32), ("orth_passes", C.c_int32),
         ("grad_dtype", C.c_int32), ("uplink_buffer", C.c_int32),
+        ("rayleigh_ritz", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
 def hparams(beta1=0.9, beta2=0.999, eps=1e-8, bias_correction=True, outer_lr=1.0, outer_momentum=0.0,
             outer_nesterov=False, power_iters=2, orth_passes=2, grad_dtype=BF16, qhm_mode=0, omega=1.0,
-            error_feedback=False, uplink_buffer=False) -> HParams:
+            error_feedback=False, uplink_buffer=False, rayleigh_ritz=False) -> HParams:
     return HParams(beta1, beta2, eps, int(bias_correction), qhm_mode, omega, int(error_feedback),
-                   int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, int(uplink_buffer))
+                   int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, int(uplink_buffer),
+                   int(rayleigh_ritz), 0)
 
 
 class LordoError(RuntimeError):
@@ -240,7 +242,7 @@ class Lordo:
     # -- state ------------------------------------------------------------------------------------
     def _state_shape(self, mat, which):
         p, q, r = self.shapes[mat]
-        return {STATE_Q: (p, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q), STATE_ERR: (p, q)}.get(which, (r, q))
+        return {STATE_Q: (p, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q), STATE_ERR: (p, q), STATE_RITZ: (r,)}.get(which, (r, q))
 
     def get_state(self, mat, which):
         out = self.torch.empty(self._state_shape(mat, which), dtype=self.torch.float32, device=self.arena.device)

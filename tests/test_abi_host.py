@@ -29,7 +29,8 @@ def test_exports_every_declared_symbol(lib):
 
 def test_struct_layout_matches_header():
     assert C.sizeof(lordo.Shape) == 24
-    assert C.sizeof(lordo.HParams) == 80
+    assert C.sizeof(lordo.HParams) == 88
+    assert lordo.HParams.rayleigh_ritz.offset == 80
     assert lordo.HParams.omega.offset == 32 and lordo.HParams.outer_lr.offset == 48
     assert lordo.HParams.power_iters.offset == 64 and lordo.HParams.grad_dtype.offset == 72
 
@@ -53,6 +54,10 @@ def test_workspace_bytes_scales_and_validates(lib):
     assert with_ef - c2 >= sum(4 * p * q for p, q, r in shapes)          # the residual E
     assert lordo.workspace_bytes(shapes, lordo.hparams(qhm_mode=2, omega=0.9)) > c2   # column sums
     assert lordo.workspace_bytes(shapes, lordo.hparams(uplink_buffer=True)) - c2 >= sum(4 * r * q for p, q, r in shapes)
+    assert lordo.workspace_bytes(shapes, lordo.hparams(rayleigh_ritz=True)) - c2 >= sum(4 * r for p, q, r in shapes)   # Ritz values
+    with pytest.raises(lordo.LordoError) as e:                   # the eigen-solver of the Rayleigh-Ritz step takes ranks up to 128
+        lordo.workspace_bytes([(512, 512, 129)], lordo.hparams(rayleigh_ritz=True))
+    assert e.value.code == lordo.EINVAL
     for bad_hp in (lordo.hparams(qhm_mode=3), lordo.hparams(qhm_mode=2, omega=0.9, uplink_buffer=True), lordo.hparams(qhm_mode=1, omega=1.5), lordo.hparams(beta1=1.0),
                    lordo.hparams(power_iters=9), lordo.hparams(orth_passes=5), lordo.hparams(grad_dtype=7)):
         with pytest.raises(lordo.LordoError) as e:

@@ -347,6 +347,63 @@ def test_local_variant_refresh_from_gradient_plus_residual(torch, bf16):
     assert e.value.code == lordo.ESTATE
 
 
+@pytest.mark.parametrize("src_bf16", [True, False], ids=["bf16_source", "fp32_source"])
+def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16):
+    """Refresh that ends with the Rayleigh-Ritz step (Sec. 2: Q = the first r columns of U, largest singular
+    value first).  Unique quantities are compared with the oracle: the subspace (projector), the Ritz values,
+    and -- where a singular value is separated from its neighbours -- the column itself up to its sign.  For
+    all columns: Q^T Src Src^T Q must be diagonal with descending entries.  Then moments and steps as usual."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128), (130, 257, 7), (384, 640, 127)]
+    ohp = orc.Hyper(power_iters=2, rayleigh_ritz=True)
+    ghp = lordo.hparams(power_iters=2, rayleigh_ritz=True)
+    pair = Pair(torch, shapes, _weights(shapes, 37), ohp, ghp, _rand_Q(shapes, 37))
+    gens = _spiked(shapes, 37, 6)
+    for t in range(2):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3, first_step_patch=(t == 0))
+    with pytest.raises(lordo.LordoError) as e:                  # no refresh yet
+        pair.opt.get_state(0, lordo.STATE_RITZ)
+    assert e.value.code == lordo.ESTATE
+    Src = [g.draw(100) for g in gens]
+    if not src_bf16:
+        Src = [(0.75 * a + 0.25 * g.draw(101)).astype(np.float32) for a, g in zip(Src, gens)]
+    Om = [synth.omega(np.random.default_rng(synth.seed_for(37, 900 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+    dists, orths = pair.refresh(Src, Om, bf16=src_bf16)
+    print(f"rayleigh-ritz refresh: dist {np.round(dists, 6)} orth {np.round(orths, 7)}", flush=True)
+    assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
+    for i, (p, q, r) in enumerate(shapes):
+        A = np.asarray(Src[i], dtype=np.float64)
+        Qg = pair.get(i, lordo.STATE_Q)
+        ritz = pair.opt.get_state(i, lordo.STATE_RITZ).cpu().numpy().astype(np.float64)
+        Qo, S = orc.rayleigh_ritz(orc.range_finder(A, np.asarray(Om[i], dtype=np.float64), ohp.power_iters), A)
+        assert np.all(np.diff(ritz) <= 0)
+        assert np.max(np.abs(ritz - S) / S) <= TOL, f"Ritz values of matrix {i}"
+        D = Qg.T @ A @ A.T @ Qg
+        d = np.diag(D)
+        assert np.linalg.norm(D - np.diag(d)) <= 1e-5 * np.linalg.norm(D), f"matrix {i}: restricted matrix not diagonal"
+        assert np.all(np.diff(d) <= 1e-5 * d[0]), f"matrix {i}: columns not in descending order"
+        assert np.max(np.abs(np.sqrt(d) - ritz) / ritz) <= TOL
+        # columns whose singular value is separated by 5 % from both neighbours are fixed up to sign; the two
+        # bases differ by the subspace error divided by the gap at most (a few times, to be safe)
+        nb = np.concatenate([[np.inf], S, [0.0]])
+        gap = np.minimum(nb[:-2] - S, S - nb[2:]) / S
+        sep = np.where(gap >= 0.05)[0]
+        assert len(sep) >= 3, f"matrix {i}: the input recipe should leave separated spikes"
+        for k in sep:
+            resid = Qg[:, k] - (Qg[:, k] @ Qo[:, k]) * Qo[:, k]       # part of the library's column outside the oracle's
+            sin = float(np.linalg.norm(resid) / np.linalg.norm(Qg[:, k]))
+            assert sin <= 4.0 * (dists[i] + 1e-5) / gap[k], f"matrix {i} column {k}: sin {sin:.2e}, gap {gap[k]:.3f}"
+    for i in range(len(shapes)):
+        assert rel_l2(pair.get(i, lordo.STATE_U), pair.st[i].u) <= TOL
+        assert rel_l2(pair.get(i, lordo.STATE_V), pair.st[i].v) <= TOL
+    for t in range(2, 4):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3)
+    pair.compare_local(TOL)
+    with pytest.raises(lordo.LordoError) as e:                  # the eigen-solver takes ranks up to 128
+        lordo.Lordo([(512, 256, 129)], ghp, [torch.zeros(512, 256, device="cuda")], torch)
+    assert e.value.code == lordo.EINVAL
+
+
 def test_refresh_before_first_step_and_exact_reconstruction(torch):
     """rank(Src) = r exactly: the refreshed Q must reproduce Src (Q Q^T Src = Src); t = 0: no rotation."""
     from paper_2602_04396_amd import lordo
