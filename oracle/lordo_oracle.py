@@ -254,6 +254,13 @@ def mssv(Q_new: np.ndarray, Q_old: np.ndarray) -> float:
 # ----------------------------------------------------------------------------
 # outer step (Alg. 1 sync branch; App. A.1, A.2; App. D.4, D.5)
 # ----------------------------------------------------------------------------
+def stable_rank(A: np.ndarray) -> float:
+    """Stable rank (Sec. 5.1, Metrics): sr(A) = ||A||_F^2 / ||A||_2^2, the spectral norm from the library SVD."""
+    A = np.asarray(A, dtype=F64)
+    sigma = np.linalg.svd(A, compute_uv=False)
+    return float(np.sum(A * A) / sigma[0] ** 2)
+
+
 def pseudo_gradient(st: MatrixState, W: np.ndarray) -> np.ndarray:
     """Delta^m = x_{t-K_x} - x_t  (App. A.1 sign convention)."""
     return st.anchor - np.asarray(W, dtype=F64)

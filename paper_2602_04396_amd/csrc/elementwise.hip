@@ -8,6 +8,7 @@
 //   k_pack_q / k_pack_y / k_pack_block / k_split_planes   fp32 -> bf16 hi/lo operand planes in matrix-core order
 //   k_glow_to_z, k_lr_to_plain, k_plain_to_lr, k_lr_exchange   between the operand layout of the low-rank state and plain buffers
 //   k_gram_shift, k_potf2, k_diag_inverses   CholeskyQR: diagonal shift, Cholesky of a diagonal block and its inverse
+//   k_jacobi_eigh     eigen-decomposition of the r x r Ritz matrix (Rayleigh-Ritz step: basis ordered as in Sec. 2's SVD projection)
 //   k_rot_pre / k_rot_post, k_mssv   elementwise parts of the moment rotation (Alg. 1 rotation lines); similarity diagnostic (Sec. 5.1)
 #include "common.h"
 
@@ -865,9 +866,6 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
     if (tid == 0) rotated = 0;
     __syncthreads();
     if (!any) break;
-#ifdef LORDO_JACOBI_DEBUG
-    if (tid == 0 && blockIdx.x < 3) printf("jacobi mat %d r %d sweep %d done\n", (int)blockIdx.x, r, sweep);
-#endif
   }
 
   for (int i = tid; i < n; i += nt) lam[i] = i < r ? A[i * ld + i] : 0.f;

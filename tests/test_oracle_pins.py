@@ -415,6 +415,20 @@ def test_rayleigh_ritz_keeps_the_span_and_diagonalises_the_restricted_matrix():
     assert np.abs(Dn - np.diag(np.diag(Dn))).max() < 1e-10 and np.all(np.diff(np.diag(Dn)) <= 1e-12)
 
 
+def test_stable_rank_closed_forms():
+    """sr = ||A||_F^2 / ||A||_2^2 (Sec. 5.1): n for an orthogonal n x n matrix, 1 for rank one, 25/16 for diag(3, 4),
+    invariant under orthogonal factors and scaling, never above the rank."""
+    rng = rng_of(43)
+    assert abs(orc.stable_rank(synth.orthonormal(rng, 12, 12)) - 12.0) < 1e-10
+    assert abs(orc.stable_rank(np.outer(rng.standard_normal(9), rng.standard_normal(7))) - 1.0) < 1e-12
+    assert abs(orc.stable_rank(np.diag([3.0, 4.0])) - 25.0 / 16.0) < 1e-12
+    A = rng.standard_normal((14, 9))
+    B = 3.5 * synth.orthonormal(rng, 14, 14) @ A @ synth.orthonormal(rng, 9, 9)
+    assert abs(orc.stable_rank(A) - orc.stable_rank(B)) < 1e-10
+    low = rng.standard_normal((14, 3)) @ rng.standard_normal((3, 9))
+    assert 1.0 <= orc.stable_rank(low) <= 3.0 + 1e-12
+
+
 def test_range_finder_rank_deficient_source_still_reconstructs():
     """rank(A) < r: the basis is completed arbitrarily; only Q^T Q = I and Q Q^T A = A are fixed."""
     rng = rng_of(16)
