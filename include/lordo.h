@@ -218,6 +218,12 @@ int lordo_poll_status(lordo_ctx* ctx, void* stream);
  * first refresh. */
 int lordo_get_mssv(lordo_ctx* ctx, float* dev_out, void* stream);
 
+/* Stable rank of the source of the last refresh (Sec. 5.1, Metrics): sr = ||Src||_F^2 / ||Src||_2^2 for every matrix,
+ * the Frobenius norm summed over the source during the refresh, the spectral norm taken as the leading Ritz value
+ * (exact up to the convergence of the range finder's first direction).  dev_out: device array of n floats.
+ * LORDO_ESTATE without hp.rayleigh_ritz or before the first refresh. */
+int lordo_get_stable_rank(lordo_ctx* ctx, float* dev_out, void* stream);
+
 /* Measurement aid: with profiling on, every kernel class below is bracketed by a pair of HIP events
  * on the caller's stream (a few microseconds of overhead per launch).  lordo_profile_read
  * synchronises `stream` and returns the summed event time and the number of spans of one class

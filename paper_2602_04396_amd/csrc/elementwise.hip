@@ -9,6 +9,7 @@
 //   k_glow_to_z, k_lr_to_plain, k_plain_to_lr, k_lr_exchange   between the operand layout of the low-rank state and plain buffers
 //   k_gram_shift, k_potf2, k_diag_inverses   CholeskyQR: diagonal shift, Cholesky of a diagonal block and its inverse
 //   k_jacobi_eigh     eigen-decomposition of the r x r Ritz matrix (Rayleigh-Ritz step: basis ordered as in Sec. 2's SVD projection)
+//   k_frob2_chunks / k_frob2_sum / k_stable_rank   squared Frobenius norm of the refresh source and its stable rank (Sec. 5.1)
 //   k_rot_pre / k_rot_post, k_mssv   elementwise parts of the moment rotation (Alg. 1 rotation lines); similarity diagnostic (Sec. 5.1)
 #include "common.h"
 
@@ -588,6 +589,70 @@ __global__ __launch_bounds__(256) void k_mssv(DevCtx d, float* __restrict__ out)
 }
 hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s) {
   hipLaunchKernelGGL(k_mssv, dim3(d.n), dim3(256), 0, s, d, out);
+  return hipGetLastError();
+}
+
+// Stable rank of the refresh source (Sec. 5.1, Metrics): sr = ||Src||_F^2 / ||Src||_2^2.  The squared Frobenius norm is
+// summed here, per workgroup over CHUNK elements and then per matrix over its workgroups, both in a fixed order; the
+// spectral norm is the leading Ritz value of the Rayleigh-Ritz step.
+template <bool SF32>
+__global__ __launch_bounds__(256) void k_frob2_chunks(DevCtx d, const int64_t* __restrict__ chunk_start, float* __restrict__ partial) {
+  const int64_t b = blockIdx.x;
+  const int mat = find_mat(chunk_start, d.n, b);
+  const MatDev& m = d.mats[mat];
+  const int64_t total = (int64_t)m.p * m.q;
+  const int64_t off = (b - chunk_start[mat]) * CHUNK;
+  const void* S = ext_ptr(d, EXT_SRC, mat);
+  float acc = 0.f;
+#pragma unroll
+  for (int rep = 0; rep < CHUNK / 256; ++rep) {
+    const int64_t i = off + rep * 256 + threadIdx.x;
+    if (i < total) {
+      float x;
+      if constexpr (SF32) x = reinterpret_cast<const float*>(S)[i];
+      else x = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(S)[i] << 16);
+      acc = fmaf(x, x, acc);
+    }
+  }
+  __shared__ float red[256];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[b] = red[0];
+}
+// one workgroup per matrix: sum of its partial sums in double, stored behind the r Ritz values
+__global__ __launch_bounds__(256) void k_frob2_sum(DevCtx d, const int64_t* __restrict__ chunk_start, const float* __restrict__ partial) {
+  const MatDev& m = d.mats[blockIdx.x];
+  if (m.ritz < 0) return;
+  __shared__ double red[256];
+  double acc = 0.0;
+  for (int64_t b = chunk_start[blockIdx.x] + threadIdx.x; b < chunk_start[blockIdx.x + 1]; b += 256) acc += (double)partial[b];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) reinterpret_cast<float*>(d.arena + m.ritz)[m.r] = (float)red[0];
+}
+__global__ void k_stable_rank(DevCtx d, float* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d.n) return;
+  const MatDev& m = d.mats[i];
+  const float* rz = reinterpret_cast<const float*>(d.arena + m.ritz);
+  out[i] = rz[m.r] / (rz[0] * rz[0]);
+}
+hipError_t launch_frob2(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float* partial, bool src_f32, hipStream_t s) {
+  if (src_f32) hipLaunchKernelGGL(k_frob2_chunks<true>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, partial);
+  else hipLaunchKernelGGL(k_frob2_chunks<false>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, partial);
+  hipLaunchKernelGGL(k_frob2_sum, dim3(d.n), dim3(256), 0, s, d, chunk_start, partial);
+  return hipGetLastError();
+}
+hipError_t launch_stable_rank(const DevCtx& d, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(k_stable_rank, dim3((d.n + 63) / 64), dim3(64), 0, s, d, out);
   return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ namespace {
     }                                                                                             \
   } while (0)
 
-enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT, OP_EIGH };
+enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT, OP_EIGH, OP_FROB };
 
 struct Op {
   int kind;
@@ -48,6 +48,7 @@ struct Plan {
   int mb = 4;
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
   int r_max = 0;                    // largest rank of any matrix
+  int64_t frob_part = -1;           // per-chunk partial sums of ||Src||_F^2 (Rayleigh-Ritz option)
   int down_pipe = 0;                // pipelined down-projection: rank blocks per wave (1: 128-rank tiles, 2: 256-rank), 0: plain kernel
   int rank_tile = 128;              // rank indices per down-projection tile
   bool g_once = true;               // every matrix has one rank tile of the down-projection: G is read exactly once
@@ -370,6 +371,7 @@ struct ProgramBuilder {
       // the block is orthonormal to 1e-4 already) brings the columns back to working precision without changing
       // their order or, visibly, their directions
       ycur = orth(true, 1 - ycur, 1, false);
+      simple(OP_FROB);            // ||Src||_F^2 for the stable rank (Sec. 5.1)
     }
     // rotation: R = Q_new^T Q_old (and R o R)
     gemm([&](int i, GemmDesc& g) {
@@ -442,6 +444,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   }
   P.chunk_start_h[n] = chunks;
   P.nchunks = chunks;
+  if (hp.rayleigh_ritz) P.frob_part = A.take(sizeof(float) * (size_t)chunks);
   // rank blocks of 32 per down-projection tile: the pipelined kernel (bf16 G) always takes four and
   // leaves the waves of absent blocks idle; the plain kernel is instantiated for 1, 2 and 4
   P.mb = (hp.grad_dtype == LORDO_BF16 || rp_max > 64) ? 4 : (rp_max > 32 ? 2 : 1);
@@ -535,7 +538,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.minv = A.take(rr * 4);
     m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
     m.part = A.take(rr * 4 * P.part_slices);
-    m.ritz = hp.rayleigh_ritz ? A.take((size_t)m.r * 4) : -1;
+    m.ritz = hp.rayleigh_ritz ? A.take((size_t)(m.r + 1) * 4) : -1;
   }
   // projection tile tables
   std::vector<ProjTile> down, up;
@@ -902,6 +905,9 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
       case OP_EIGH: HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, s)); break;
+      case OP_FROB:
+        HIPCHK(launch_frob2(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, c->at<float>(P.frob_part), src_dtype == LORDO_F32, s));
+        break;
       case OP_ROT_PRE:
         HIPCHK(launch_rot_pre(c->dev, c->at<float>(P.u), c->at<float>(P.v), (float)(1.0 / c1), (float)(1.0 / c2), s));
         break;
@@ -1178,6 +1184,13 @@ int lordo_get_mssv(lordo_ctx* c, float* dev_out, void* stream) {
   if (!c || !dev_out) return LORDO_EINVAL;
   if (!c->refreshed) return LORDO_ESTATE;
   HIPCHK(launch_mssv(c->dev, dev_out, reinterpret_cast<hipStream_t>(stream)));
+  return LORDO_OK;
+}
+
+int lordo_get_stable_rank(lordo_ctx* c, float* dev_out, void* stream) {
+  if (!c || !dev_out) return LORDO_EINVAL;
+  if (!c->refreshed || !c->hp.rayleigh_ritz) return LORDO_ESTATE;
+  HIPCHK(launch_stable_rank(c->dev, dev_out, reinterpret_cast<hipStream_t>(stream)));
   return LORDO_OK;
 }
 

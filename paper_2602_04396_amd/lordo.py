@@ -22,6 +22,7 @@ EXPORTS = [
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
     "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv", "lordo_refresh_subspace_local",
     "lordo_export_uplink", "lordo_outer_step_lowrank", "lordo_init_projection", "lordo_sync_payload",
+    "lordo_get_stable_rank",
 ]
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
@@ -83,6 +84,7 @@ def load() -> C.CDLL:
     lib.lordo_get_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_set_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_get_mssv.argtypes = [vp, vp, vp]
+    lib.lordo_get_stable_rank.argtypes = [vp, vp, vp]
     lib.lordo_get_step.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.lordo_set_step.argtypes = [vp, C.c_int64]
     lib.lordo_poll_status.argtypes = [vp, vp]
@@ -259,6 +261,12 @@ class Lordo:
         """Per matrix: mean squared singular value of Q_new^T Q_old of the last refresh (tensor of n floats)."""
         out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.arena.device)
         _check(self.lib.lordo_get_mssv(self.ctx, C.c_void_p(out.data_ptr()), self._stream()))
+        return out
+
+    def stable_rank(self):
+        """Per matrix: ||Src||_F^2 / ||Src||_2^2 of the source of the last refresh (needs rayleigh_ritz)."""
+        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.arena.device)
+        _check(self.lib.lordo_get_stable_rank(self.ctx, C.c_void_p(out.data_ptr()), self._stream()))
         return out
 
     @property

@@ -371,6 +371,7 @@ def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16):
     dists, orths = pair.refresh(Src, Om, bf16=src_bf16)
     print(f"rayleigh-ritz refresh: dist {np.round(dists, 6)} orth {np.round(orths, 7)}", flush=True)
     assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
+    sr_gpu = pair.opt.stable_rank().cpu().numpy().astype(np.float64)
     for i, (p, q, r) in enumerate(shapes):
         A = np.asarray(Src[i], dtype=np.float64)
         Qg = pair.get(i, lordo.STATE_Q)
@@ -383,6 +384,9 @@ def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16):
         assert np.linalg.norm(D - np.diag(d)) <= 1e-5 * np.linalg.norm(D), f"matrix {i}: restricted matrix not diagonal"
         assert np.all(np.diff(d) <= 1e-5 * d[0]), f"matrix {i}: columns not in descending order"
         assert np.max(np.abs(np.sqrt(d) - ritz) / ritz) <= TOL
+        # stable rank of the source (Sec. 5.1) against the definition: the leading Ritz value stands for the
+        # spectral norm, which the spiked recipe separates well
+        assert abs(sr_gpu[i] - orc.stable_rank(A)) <= TOL * orc.stable_rank(A), f"stable rank of matrix {i}"
         # columns whose singular value is separated by 5 % from both neighbours are fixed up to sign; the two
         # bases differ by the subspace error divided by the gap at most (a few times, to be safe)
         nb = np.concatenate([[np.inf], S, [0.0]])
