@@ -817,6 +817,7 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
   float* cs = V + n * ld;                 // c[0..half), s[0..half)
   float* lam = cs + n;                    // n
   __shared__ int rotated;
+  __shared__ int round_rot[3];            // "some pair of round t rotates", t % 3; cleared two rounds ahead
   __shared__ float amax_s;
   const int tid = threadIdx.x, nt = blockDim.x;
   const float* T = reinterpret_cast<const float*>(d.arena + m.gram);
@@ -828,7 +829,7 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
     A[i * ld + j] = v;
     V[i * ld + j] = i == j ? 1.f : 0.f;
   }
-  if (tid == 0) rotated = 0;
+  if (tid == 0) { rotated = 0; round_rot[0] = 0; round_rot[1] = 0; round_rot[2] = 0; }
   __syncthreads();
   if (tid < 64) {                         // largest diagonal entry (one wave)
     float mx = 0.f;
@@ -840,6 +841,14 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
   const float abs_thr = 3e-8f * amax_s;
   const int mm = n - 1;                   // players 0 .. mm-1 rotate, player mm stays
   int* pairs = reinterpret_cast<int*>(lam);   // p | q << 8 of the round's pairs (the eigenvalue array is filled at the end)
+  // pairs of every round (circle method): pair 0 of round t is (t, mm), pair k > 0 is ((t + k) % mm, (t + mm - k) % mm)
+  unsigned short* sched = reinterpret_cast<unsigned short*>(lam + n);
+  for (int idx = tid; idx < mm * half; idx += nt) {
+    const int round = idx / half, k = idx - round * half;
+    const int a = (round + k) % mm, b = k == 0 ? mm : (round + mm - k) % mm;
+    sched[idx] = (unsigned short)((a < b ? a : b) | ((a < b ? b : a) << 8));
+  }
+  __syncthreads();
 
   // work items of the two update phases: (pair k, row or column i), the same for every round.  A wave takes up to
   // four pairs and its lanes the rows (columns) lane and lane + 64: the rotation of a pair is read once per wave
@@ -855,28 +864,36 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
     ii[j] = i;
   }
 
+  int t3 = 0;                             // rounds taken so far, modulo 3
   for (int sweep = 0; sweep < 15; ++sweep) {
     for (int round = 0; round < mm; ++round) {
-      // pair k of this round (circle method): k = 0: (round % mm, mm); k > 0: ((round + k) % mm, (round + mm - k) % mm)
       if (tid < half) {
         const int k = tid;
-        int a = (round + k) % mm, b = k == 0 ? mm : (round + mm - k) % mm;
-        const int pi = a < b ? a : b, qi = a < b ? b : a;
+        const int pr = sched[round * half + k];
+        const int pi = pr & 255, qi = pr >> 8;
         const float app = A[pi * ld + pi], aqq = A[qi * ld + qi], apq = A[pi * ld + qi];
         float c = 1.f, sn = 0.f;
         const float mag = fabsf(apq);
-        if (mag > abs_thr && mag > 1e-7f * sqrtf(fabsf(app * aqq))) {
-          const float tau = (aqq - app) / (2.f * apq);
-          const float t = copysignf(1.f, tau) / (fabsf(tau) + sqrtf(1.f + tau * tau));
-          c = 1.f / sqrtf(1.f + t * t);
+        if (mag > abs_thr && mag > 1e-7f * __builtin_amdgcn_sqrtf(fabsf(app * aqq))) {
+          // hardware reciprocal, root and reciprocal root (1 ulp): c^2 + s^2 = 1 to rounding either way
+          const float tau = (aqq - app) * 0.5f * __builtin_amdgcn_rcpf(apq);
+          const float t = copysignf(1.f, tau) * __builtin_amdgcn_rcpf(fabsf(tau) + __builtin_amdgcn_sqrtf(1.f + tau * tau));
+          c = __builtin_amdgcn_rsqf(1.f + t * t);
           sn = t * c;
           rotated = 1;                    // benign race: every writer stores 1
+          round_rot[t3] = 1;
         }
         cs[k] = c;
         cs[half + k] = sn;
-        pairs[k] = pi | (qi << 8);
+        pairs[k] = pr;
       }
       __syncthreads();
+      // late sweeps skip most rotations: a round without any costs this one barrier.  The flag of the round after the
+      // next is cleared here; its writers are two barriers away.
+      const int some = round_rot[t3];
+      if (tid == 0) round_rot[t3 == 0 ? 2 : t3 - 1] = 0;
+      t3 = t3 == 2 ? 0 : t3 + 1;
+      if (!some) continue;
       // columns p, q of T and U:  x_p' = c x_p - s x_q,  x_q' = s x_p + c x_q.  All operands of a thread's items
       // are read before any is written, so that the LDS reads overlap.
       {
@@ -884,10 +901,10 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
         int op[ITEMS], oq[ITEMS];
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
-          s8[j] = 0.f;
-          if (kk[j] >= 0) {
+          s8[j] = kk[j] >= 0 ? cs[half + kk[j]] : 0.f;
+          if (s8[j] != 0.f) {             // the same for all lanes of a wave
             const int pr = pairs[kk[j]];
-            c8[j] = cs[kk[j]]; s8[j] = cs[half + kk[j]];
+            c8[j] = cs[kk[j]];
             op[j] = ii[j] * ld + (pr & 255); oq[j] = ii[j] * ld + (pr >> 8);
             ap[j] = A[op[j]]; aq[j] = A[oq[j]];
             vp[j] = V[op[j]]; vq[j] = V[oq[j]];
@@ -909,10 +926,10 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
         int op[ITEMS], oq[ITEMS];
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
-          s8[j] = 0.f;
-          if (kk[j] >= 0) {
+          s8[j] = kk[j] >= 0 ? cs[half + kk[j]] : 0.f;
+          if (s8[j] != 0.f) {
             const int pr = pairs[kk[j]];
-            c8[j] = cs[kk[j]]; s8[j] = cs[half + kk[j]];
+            c8[j] = cs[kk[j]];
             op[j] = (pr & 255) * ld + ii[j]; oq[j] = (pr >> 8) * ld + ii[j];
             ap[j] = A[op[j]]; aq[j] = A[oq[j]];
           }
@@ -954,7 +971,7 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
 }
 size_t jacobi_lds_bytes(int rmax) {
   const int n = (rmax + 1) & ~1;
-  return sizeof(float) * ((size_t)2 * n * (n + 1) + 2 * n);
+  return sizeof(float) * ((size_t)2 * n * (n + 1) + 2 * n) + sizeof(unsigned short) * (size_t)(n - 1) * (n / 2);
 }
 hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, hipStream_t s) {
   if (rmax > 128) return hipErrorInvalidValue;
