@@ -192,3 +192,34 @@ def test_many_tiles_fused_adam_sampled_columns():
             assert rel_l2(n_gpu, st.last_N) <= TOL, f"N, step {step}"
             assert rel_l2(dW_gpu, -lr * Q64 @ st.last_N) <= TOL, f"weight change, step {step}"
     opt.poll_status()
+
+
+def test_c2_full_size_rayleigh_ritz_refresh_sampled_matrices():
+    """Refresh with the Rayleigh-Ritz step on the whole c2 set as bench.py --rayleigh-ritz launches it; three matrices
+    (square, wide, tall) are checked against the oracle: subspace, ordered Ritz values, diagonal restricted matrix,
+    stable rank of the source."""
+    import torch
+    import bench
+    from paper_2602_04396_amd import lordo
+    from tests.harness import projector_distance
+    shapes, W, G, Omega, D, grad_dtype = bench.build_workload(torch, lordo, synth, "c2", None, 1)
+    hp = lordo.hparams(power_iters=2, rayleigh_ritz=True)
+    opt = lordo.Lordo(shapes, hp, W, torch)
+    opt.refresh_subspace(opt.ptrs(G[0], grad_dtype), opt.ptrs(Omega, torch.float32, "qr"))
+    opt.poll_status()
+    sr = opt.stable_rank().cpu().numpy().astype(np.float64)
+    for i in (0, 4, 5):
+        p, q, r = shapes[i]
+        A = G[0][i].float().cpu().numpy().astype(np.float64)
+        Om = Omega[i].cpu().numpy().astype(np.float64)
+        Qg = opt.get_state(i, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+        ritz = opt.get_state(i, lordo.STATE_RITZ).cpu().numpy().astype(np.float64)
+        Qo, S = orc.rayleigh_ritz(orc.range_finder(A, Om, 2), A)
+        assert np.linalg.norm(Qg.T @ Qg - np.eye(r)) <= 1e-4
+        assert projector_distance(Qg, Qo) <= 1e-3, f"matrix {i}"
+        assert np.max(np.abs(ritz - S) / S) <= TOL, f"Ritz values of matrix {i}"
+        Dm = Qg.T @ A @ A.T @ Qg
+        d = np.diag(Dm)
+        assert np.linalg.norm(Dm - np.diag(d)) <= 1e-5 * np.linalg.norm(Dm)
+        assert np.all(np.diff(d) <= 1e-5 * d[0])
+        assert abs(sr[i] - orc.stable_rank(A)) <= TOL * orc.stable_rank(A), f"stable rank of matrix {i}"
