@@ -224,6 +224,18 @@ int lordo_get_mssv(lordo_ctx* ctx, float* dev_out, void* stream);
  * LORDO_ESTATE without hp.rayleigh_ritz or before the first refresh. */
 int lordo_get_stable_rank(lordo_ctx* ctx, float* dev_out, void* stream);
 
+/* The r-th spectral gap sigma_r - sigma_{r+1} of a source (Sec. 5.1, Metrics), per matrix, as an estimate:
+ * sigma_r is the smallest Ritz value of the last refresh; sigma_{r+1} is the largest Ritz value of two block power
+ * iterations on the source deflated by the current basis, (I - Q Q^T) Src, i.e. an approximation from below of the
+ * spectral norm of the deflated source -- which equals sigma_{r+1} when Q spans the leading subspace exactly and
+ * exceeds it otherwise (directions the range finder has not resolved stay in the deflated source).
+ * Src, src_dtype, Omega as for lordo_refresh_subspace; pass the source of the last refresh.
+ * dev_out: device array of n floats.  Changes no state that survives a step (Q, moments, weights are left as they
+ * are); uses the scratch of the refresh, including what LORDO_STATE_GLOW / NUPD show.
+ * LORDO_ESTATE without hp.rayleigh_ritz, before the first refresh, or between lordo_refresh_subspace_local and its step. */
+int lordo_spectral_gap(lordo_ctx* ctx, const void* const* Src, int32_t src_dtype, const void* const* Omega,
+                       float* dev_out, void* stream);
+
 /* Measurement aid: with profiling on, every kernel class below is bracketed by a pair of HIP events
  * on the caller's stream (a few microseconds of overhead per launch).  lordo_profile_read
  * synchronises `stream` and returns the summed event time and the number of spans of one class

@@ -261,6 +261,33 @@ def stable_rank(A: np.ndarray) -> float:
     return float(np.sum(A * A) / sigma[0] ** 2)
 
 
+def spectral_gap(A: np.ndarray, r: int) -> float:
+    """The r-th spectral gap sigma_r - sigma_{r+1} (Sec. 5.1, Metrics), singular values from the library SVD
+    (sigma_{r+1} = 0 when the matrix has only r of them)."""
+    sigma = np.linalg.svd(np.asarray(A, dtype=F64), compute_uv=False)
+    return float(sigma[r - 1] - (sigma[r] if r < len(sigma) else 0.0))
+
+
+def next_singular_value_estimate(A: np.ndarray, Q: np.ndarray, Omega: np.ndarray, iters: int = 2) -> float:
+    """Estimate of sigma_{r+1}(A) given a basis Q of the leading r-dimensional left singular subspace: block power
+    iteration (the range finder above) on the deflated matrix (I - Q Q^T) A, then the largest singular value of the
+    matrix restricted to the block found.  Never above the spectral norm of the deflated matrix."""
+    A = np.asarray(A, dtype=F64)
+    Q = np.asarray(Q, dtype=F64)
+
+    def deflate(Y):
+        return Y - Q @ (Q.T @ Y)
+
+    Y = orth(deflate(A @ np.asarray(Omega, dtype=F64)))
+    for _ in range(iters):
+        Z = orth(A.T @ Y)                 # = ((I - Q Q^T) A)^T Y, since Y is orthogonal to Q
+        Y = orth(deflate(A @ Z))
+    # When the deflated matrix has fewer than r nonzero singular values (2r > min(p, q)), the orthonormalisation
+    # completes the block with directions that need not be orthogonal to Q: deflating the block once more keeps
+    # the result below the norm of the deflated matrix (it changes nothing for a block orthogonal to Q).
+    return float(np.linalg.svd(deflate(Y).T @ A, compute_uv=False)[0])
+
+
 def pseudo_gradient(st: MatrixState, W: np.ndarray) -> np.ndarray:
     """Delta^m = x_{t-K_x} - x_t  (App. A.1 sign convention)."""
     return st.anchor - np.asarray(W, dtype=F64)

@@ -42,7 +42,7 @@ struct MatDev {
   int64_t rot, rot2;      // fp32 r x r : R = Q_new^T Q_old and its elementwise square
   int64_t part;           // fp32 split-K partial sums of the r x r products (Gram, R): slices x r x r
   int64_t err;            // fp32 p x q error-feedback residual E (-1 without error feedback)
-  int64_t ritz;           // fp32 r + 1 : Ritz values of the last refresh, then ||Src||_F^2 (-1 without the Rayleigh-Ritz step)
+  int64_t ritz;           // fp32 r + 2 : Ritz values of the last refresh, ||Src||_F^2, estimate of sigma_{r+1} (-1 without the Rayleigh-Ritz step)
 };
 
 // Work item of the projection kernels.
@@ -169,8 +169,8 @@ hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s);
 hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
 hipError_t launch_frob2(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float* partial, bool src_f32, hipStream_t s);
-hipError_t launch_stable_rank(const DevCtx& d, float* out, hipStream_t s);
-hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, hipStream_t s);
+hipError_t launch_stable_rank(const DevCtx& d, float* out, int which, hipStream_t s);
+hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s);
 hipError_t launch_diag_inverses(const DevCtx& d, hipStream_t s);
 hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
 hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);

@@ -638,12 +638,13 @@ __global__ __launch_bounds__(256) void k_frob2_sum(DevCtx d, const int64_t* __re
   }
   if (threadIdx.x == 0) reinterpret_cast<float*>(d.arena + m.ritz)[m.r] = (float)red[0];
 }
-__global__ void k_stable_rank(DevCtx d, float* __restrict__ out) {
+// which = 0: stable rank ||Src||_F^2 / sigma_1^2;  1: spectral gap sigma_r - sigma_{r+1} (estimates of both)
+__global__ void k_stable_rank(DevCtx d, float* __restrict__ out, int which) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= d.n) return;
   const MatDev& m = d.mats[i];
   const float* rz = reinterpret_cast<const float*>(d.arena + m.ritz);
-  out[i] = rz[m.r] / (rz[0] * rz[0]);
+  out[i] = which == 0 ? rz[m.r] / (rz[0] * rz[0]) : rz[m.r - 1] - rz[m.r + 1];
 }
 hipError_t launch_frob2(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float* partial, bool src_f32, hipStream_t s) {
   if (src_f32) hipLaunchKernelGGL(k_frob2_chunks<true>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, partial);
@@ -651,8 +652,8 @@ hipError_t launch_frob2(const DevCtx& d, const int64_t* chunk_start, int64_t nch
   hipLaunchKernelGGL(k_frob2_sum, dim3(d.n), dim3(256), 0, s, d, chunk_start, partial);
   return hipGetLastError();
 }
-hipError_t launch_stable_rank(const DevCtx& d, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(k_stable_rank, dim3((d.n + 63) / 64), dim3(64), 0, s, d, out);
+hipError_t launch_stable_rank(const DevCtx& d, float* out, int which, hipStream_t s) {
+  hipLaunchKernelGGL(k_stable_rank, dim3((d.n + 63) / 64), dim3(64), 0, s, d, out, which);
   return hipGetLastError();
 }
 
@@ -804,7 +805,7 @@ hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
 // its entry of largest magnitude is positive; ritz[k] = sqrt(max(lambda_k, 0)), the Ritz values of Src.
 // Reads the lower triangle of `gram` only.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
+__global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d, int top_value_only) {
   const MatDev m = d.mats[blockIdx.x];
   const int r = m.r;
   if (r > 128 || m.ritz < 0) return;
@@ -952,6 +953,15 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d) {
 
   for (int i = tid; i < n; i += nt) lam[i] = i < r ? A[i * ld + i] : 0.f;
   __syncthreads();
+  if (top_value_only) {                   // spectral-gap estimate: the largest eigenvalue alone, behind ||Src||_F^2
+    if (tid == 0) {
+      float mx = 0.f;
+      for (int i = 0; i < r; ++i) mx = fmaxf(mx, lam[i]);
+      reinterpret_cast<float*>(d.arena + m.ritz)[r + 1] = sqrtf(mx);
+      if (!(mx <= 3.0e38f)) *d.flag = 1;
+    }
+    return;
+  }
   // descending order (ties by index); one thread per eigenvector writes its column
   for (int i = tid; i < r; i += nt) {
     const float li = lam[i];
@@ -973,7 +983,7 @@ size_t jacobi_lds_bytes(int rmax) {
   const int n = (rmax + 1) & ~1;
   return sizeof(float) * ((size_t)2 * n * (n + 1) + 2 * n) + sizeof(unsigned short) * (size_t)(n - 1) * (n / 2);
 }
-hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, hipStream_t s) {
+hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s) {
   if (rmax > 128) return hipErrorInvalidValue;
   const size_t lds = jacobi_lds_bytes(rmax);
   static bool attr_set = false;
@@ -984,7 +994,7 @@ hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, hipStream_t s) {
     attr_set = true;
   }
   const int threads = rmax > 64 ? 1024 : (rmax > 32 ? 512 : 256);
-  hipLaunchKernelGGL(k_jacobi_eigh, dim3(d.n), dim3(threads), lds, s, d);
+  hipLaunchKernelGGL(k_jacobi_eigh, dim3(d.n), dim3(threads), lds, s, d, top_value_only ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -70,6 +70,7 @@ struct Plan {
   std::vector<GemmTile> gtile_h;
   std::vector<Op> ops;              // the refresh
   std::vector<Op> init_ops;         // Q_0 from a caller-supplied block: copy, orthonormalise, pack
+  std::vector<Op> gap_ops;          // estimate of sigma_{r+1} of a source (Rayleigh-Ritz option)
 };
 
 constexpr int MAX_KSPLIT = 16;
@@ -292,6 +293,82 @@ struct ProgramBuilder {
     simple(OP_Q_FROM_Y, ycur);
     simple(OP_PACK);
     P.init_ops.swap(P.ops);
+    P.ops.swap(saved);
+  }
+
+  // Estimate of sigma_{r+1} of the source for the r-th spectral gap (Sec. 5.1, Metrics): block power iteration on the
+  // source deflated by the current basis, (I - Q Q^T) Src, then the largest Ritz value of the block.
+  void build_gap(int iters) {
+    std::vector<Op> saved;
+    saved.swap(P.ops);
+    auto deflate = [&](int ycur) {      // Y <- Y - Q (Q^T Y); the r x r product goes through the buffer of the Cholesky factor
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_arena(m.q32); g.sAm = 1; g.sAk = m.r;
+        g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.lfac); g.ldc = m.r;
+        g.M = m.r; g.N = m.r; g.K = m.p;
+        return true;
+      }, false, true);
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_arena(m.q32); g.sAm = m.r; g.sAk = 1;
+        g.B = ref_arena(m.lfac); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.y[ycur]); g.ldc = m.r;
+        g.M = m.p; g.N = m.r; g.K = m.r;
+        g.alpha = -1.f; g.beta = 1.f;
+        return true;
+      });
+    };
+    auto z_product = [&](int ycur) {    // Z = Src^T Y
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2; g.prec = 1;
+        g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.zw[0]); g.ldc = m.r;
+        g.M = m.q; g.N = m.r; g.K = m.p;
+        return true;
+      });
+      P.ops.back().fast = 1;
+      P.ops.back().iarg = ycur;
+    };
+    auto y_product = [&](int ext_or_z) {   // Y = Src B, B = Omega (-1) or the block in zw[ext_or_z]
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2; g.prec = 1;
+        g.B = ext_or_z < 0 ? ref_ext(EXT_OMEGA) : ref_arena(m.zw[ext_or_z]); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.y[0]); g.ldc = m.r;
+        g.M = m.p; g.N = m.r; g.K = m.q;
+        return true;
+      });
+      P.ops.back().fast = 2;
+      P.ops.back().iarg = ext_or_z;
+    };
+    y_product(-1);
+    deflate(0);
+    int ycur = orth(true, 0, 1);
+    for (int it = 0; it < iters; ++it) {
+      z_product(ycur);                  // Src^T (I - Q Q^T) Y = Src^T Y for a block orthogonal to Q
+      const int zcur = orth(false, 0, 1);
+      y_product(zcur);
+      deflate(0);
+      ycur = orth(true, 0, it + 1 < iters ? 1 : 2);
+    }
+    // with 2r > min(p, q) the deflated source has fewer than r directions and the orthonormalisation completes the
+    // block arbitrarily: deflated once more, the block keeps the estimate below the norm of the deflated source
+    deflate(ycur);
+    z_product(ycur);
+    gemm([&](int i, GemmDesc& g) {
+      const MatDev& m = P.mat[i];
+      g.A = ref_arena(m.zw[0]); g.sAm = 1; g.sAk = m.r;
+      g.B = ref_arena(m.zw[0]); g.sBk = m.r; g.sBn = 1;
+      g.C = ref_arena(m.gram); g.ldc = m.r;
+      g.M = m.r; g.N = m.r; g.K = m.q;
+      return true;
+    }, false, true, true);
+    simple(OP_EIGH, 1);                 // largest eigenvalue only
+    simple(OP_PACK);                    // the Z products borrowed the operand planes of Q
+    P.gap_ops.swap(P.ops);
     P.ops.swap(saved);
   }
 
@@ -538,7 +615,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.minv = A.take(rr * 4);
     m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
     m.part = A.take(rr * 4 * P.part_slices);
-    m.ritz = hp.rayleigh_ritz ? A.take((size_t)(m.r + 1) * 4) : -1;
+    m.ritz = hp.rayleigh_ritz ? A.take((size_t)(m.r + 2) * 4) : -1;
   }
   // projection tile tables
   std::vector<ProjTile> down, up;
@@ -594,6 +671,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // refresh program
   ProgramBuilder pb(P, n);
   pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes, hp.rayleigh_ritz != 0);
+  if (hp.rayleigh_ritz) pb.build_gap(2);
   pb.build_init(hp.orth_passes == 0 ? 2 : hp.orth_passes);
   P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
   P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());
@@ -904,7 +982,7 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
-      case OP_EIGH: HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, s)); break;
+      case OP_EIGH: HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, op.iarg != 0, s)); break;
       case OP_FROB:
         HIPCHK(launch_frob2(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, c->at<float>(P.frob_part), src_dtype == LORDO_F32, s));
         break;
@@ -923,16 +1001,9 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
   return LORDO_OK;
 }
 
-int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, void* stream) {
-  if (!c || !Src || !Omega) return LORDO_EINVAL;
-  if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
-  if (c->grad_folded) return LORDO_ESTATE;          // the error buffer holds a folded gradient: a local step must consume it first
-  if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;   // the buffer is in coordinates of the current Q
-  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
-  if (rc != LORDO_OK) return rc;
-  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
-  if (rc != LORDO_OK) return rc;
+// Which of the projection-type kernels can take the products of a program whose source is Src.
+struct SrcPaths { bool proj_kernels, stream_kernel, proj_tr; };
+static int source_paths(lordo_ctx* c, const void* const* Src, int32_t src_dtype, hipStream_t s, SrcPaths& out) {
   // a bf16 source with the alignment the pipelined down-projection kernel reads gradients with lets that
   // kernel take the products of the power iteration that have its shape
   // (an fp32 source too: that kernel then stages it as bf16 hi + lo planes, as it does the error-feedback sum)
@@ -941,7 +1012,7 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   for (int i = 0; i < c->n && proj_kernels; ++i)
     if ((c->plan.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & pair_mask) != 0) proj_kernels = false;
   if (proj_kernels && src_dtype == LORDO_BF16) {
-    rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+    int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
     if (rc != LORDO_OK) return rc;
   }
   // the products contracted over the columns stream a bf16 source straight into matrix-core fragment order
@@ -955,7 +1026,44 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
   bool proj_tr = proj_kernels && src_dtype == LORDO_BF16;
   for (int i = 0; i < c->n && proj_tr; ++i)
     if ((c->plan.mat[i].q & 7) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & 15) != 0) proj_tr = false;
-  return run_refresh(c, src_dtype, s, false, 0.0, proj_kernels, stream_kernel, proj_tr);
+  out = SrcPaths{proj_kernels, stream_kernel, proj_tr};
+  return LORDO_OK;
+}
+
+int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, void* stream) {
+  if (!c || !Src || !Omega) return LORDO_EINVAL;
+  if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
+  if (c->grad_folded) return LORDO_ESTATE;          // the error buffer holds a folded gradient: a local step must consume it first
+  if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;   // the buffer is in coordinates of the current Q
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
+  if (rc != LORDO_OK) return rc;
+  SrcPaths sp;
+  rc = source_paths(c, Src, src_dtype, s, sp);
+  if (rc != LORDO_OK) return rc;
+  return run_refresh(c, src_dtype, s, false, 0.0, sp.proj_kernels, sp.stream_kernel, sp.proj_tr);
+}
+
+int lordo_spectral_gap(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, float* dev_out, void* stream) {
+  if (!c || !Src || !Omega || !dev_out) return LORDO_EINVAL;
+  if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
+  if (!c->hp.rayleigh_ritz || !c->refreshed || c->grad_folded) return LORDO_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
+  if (rc != LORDO_OK) return rc;
+  SrcPaths sp;
+  rc = source_paths(c, Src, src_dtype, s, sp);
+  if (rc != LORDO_OK) return rc;
+  c->prof.begin(LORDO_K_REFRESH, s);
+  rc = run_ops(c, c->plan.gap_ops, src_dtype, s, false, 1.0, 1.0, sp.proj_kernels, sp.stream_kernel, sp.proj_tr);
+  if (rc != LORDO_OK) return rc;
+  HIPCHK(launch_stable_rank(c->dev, dev_out, 1, s));
+  c->prof.end(LORDO_K_REFRESH, s);
+  return LORDO_OK;
 }
 
 int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {
@@ -1190,7 +1298,7 @@ int lordo_get_mssv(lordo_ctx* c, float* dev_out, void* stream) {
 int lordo_get_stable_rank(lordo_ctx* c, float* dev_out, void* stream) {
   if (!c || !dev_out) return LORDO_EINVAL;
   if (!c->refreshed || !c->hp.rayleigh_ritz) return LORDO_ESTATE;
-  HIPCHK(launch_stable_rank(c->dev, dev_out, reinterpret_cast<hipStream_t>(stream)));
+  HIPCHK(launch_stable_rank(c->dev, dev_out, 0, reinterpret_cast<hipStream_t>(stream)));
   return LORDO_OK;
 }
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
     "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv", "lordo_refresh_subspace_local",
     "lordo_export_uplink", "lordo_outer_step_lowrank", "lordo_init_projection", "lordo_sync_payload",
-    "lordo_get_stable_rank",
+    "lordo_get_stable_rank", "lordo_spectral_gap",
 ]
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
@@ -85,6 +85,7 @@ def load() -> C.CDLL:
     lib.lordo_set_state.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
     lib.lordo_get_mssv.argtypes = [vp, vp, vp]
     lib.lordo_get_stable_rank.argtypes = [vp, vp, vp]
+    lib.lordo_spectral_gap.argtypes = [vp, vpp, C.c_int32, vpp, vp, vp]
     lib.lordo_get_step.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.lordo_set_step.argtypes = [vp, C.c_int64]
     lib.lordo_poll_status.argtypes = [vp, vp]
@@ -198,6 +199,18 @@ class Lordo:
         if dt not in (self.torch.bfloat16, self.torch.float32):
             raise ValueError("refresh source must be bf16 or fp32")
         _check(self.lib.lordo_refresh_subspace(self.ctx, _ptr_array(Src), code, _ptr_array(Omega), self._stream()))
+
+    def spectral_gap(self, Src, Omega):
+        """Per matrix: estimate of sigma_r - sigma_{r+1} of Src (the source of the last refresh; needs rayleigh_ritz)."""
+        dt = (Src.tensors if isinstance(Src, PtrList) else Src)[0].dtype
+        if dt not in (self.torch.bfloat16, self.torch.float32):
+            raise ValueError("source must be bf16 or fp32")
+        self._check_tensors(Src, dt, "pq")
+        self._check_tensors(Omega, self.torch.float32, "qr")
+        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.arena.device)
+        _check(self.lib.lordo_spectral_gap(self.ctx, _ptr_array(Src), BF16 if dt == self.torch.bfloat16 else F32,
+                                           _ptr_array(Omega), C.c_void_p(out.data_ptr()), self._stream()))
+        return out
 
     def refresh_subspace_local(self, G, Omega, grad_scale=1.0):
         """Alg. 2 refresh from grad_scale * G + E; the next call must be local_step with the same G."""

@@ -400,6 +400,32 @@ def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16):
     for i in range(len(shapes)):
         assert rel_l2(pair.get(i, lordo.STATE_U), pair.st[i].u) <= TOL
         assert rel_l2(pair.get(i, lordo.STATE_V), pair.st[i].v) <= TOL
+    # r-th spectral gap (Sec. 5.1): sigma_r from the Ritz values, sigma_{r+1} from the deflated block iteration;
+    # the oracle runs the same iteration with the library's basis, and the definition bounds the estimate
+    Om2 = [synth.omega(np.random.default_rng(synth.seed_for(37, 950 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+    Q_before = [pair.opt.get_state(i, lordo.STATE_Q) for i in range(len(shapes))]
+    gap = pair.opt.spectral_gap(pair.to_dev(Src, src_bf16), pair.to_dev(Om2, False)).cpu().numpy().astype(np.float64)
+    pair.opt.poll_status()
+    for i, (p, q, r) in enumerate(shapes):
+        A = np.asarray(Src[i], dtype=np.float64)
+        Qg = pair.get(i, lordo.STATE_Q)
+        assert torch.equal(pair.opt.get_state(i, lordo.STATE_Q), Q_before[i])          # the basis is left alone
+        ritz = pair.opt.get_state(i, lordo.STATE_RITZ).cpu().numpy().astype(np.float64)
+        est_gpu = ritz[-1] - gap[i]
+        est_orc = orc.next_singular_value_estimate(A, Qg, np.asarray(Om2[i], dtype=np.float64), 2)
+        sigma = np.linalg.svd(A, compute_uv=False)
+        deflated = np.linalg.svd(A - Qg @ (Qg.T @ A), compute_uv=False)[0]
+        if 2 * r > min(p, q):
+            # fewer than r directions are left after the deflation: the block is completed arbitrarily (differently
+            # on the two sides) and the estimate is a bound only
+            assert est_gpu <= deflated * (1 + TOL) and est_orc <= deflated * (1 + 1e-9)
+            continue
+        assert abs(est_gpu - est_orc) <= TOL * est_orc, f"sigma_(r+1) estimate of matrix {i}: {est_gpu} vs {est_orc}"
+        # what the estimate approaches is the norm of the deflated source, which is sigma_(r+1) for the exact leading
+        # subspace and above it for the range finder's (whose trailing directions lie in the noise bulk here)
+        assert sigma[r] * (1 - 1e-6) <= deflated and 0.85 * deflated <= est_gpu <= deflated * (1 + TOL), \
+            f"matrix {i}: estimate {est_gpu}, deflated norm {deflated}, sigma_(r+1) {sigma[r]}"
+        assert abs(gap[i] - (ritz[-1] - est_orc)) <= TOL * ritz[-1]
     for t in range(2, 4):
         pair.local_step([g.draw(t) for g in gens], lr=1e-3)
     pair.compare_local(TOL)

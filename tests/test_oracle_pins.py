@@ -429,6 +429,38 @@ def test_stable_rank_closed_forms():
     assert 1.0 <= orc.stable_rank(low) <= 3.0 + 1e-12
 
 
+def test_spectral_gap_closed_forms_and_its_estimate():
+    """sigma_r - sigma_{r+1} (Sec. 5.1) on matrices with known singular values; the deflated block iteration reaches
+    sigma_{r+1} when it is separated from the rest, and stays below the norm of the deflated matrix always."""
+    rng = rng_of(44)
+    assert abs(orc.spectral_gap(np.diag([5.0, 3.0, 1.0]), 1) - 2.0) < 1e-12
+    assert abs(orc.spectral_gap(np.diag([5.0, 3.0, 1.0]), 2) - 2.0) < 1e-12
+    assert abs(orc.spectral_gap(np.diag([5.0, 3.0, 1.0]), 3) - 1.0) < 1e-12          # no sigma_4
+    p, q, r = 40, 31, 4
+    sv = np.concatenate([[9.0, 8.0, 7.0, 6.0, 4.0], 0.3 * rng.random(q - 5)])
+    U, V = synth.orthonormal(rng, p, p)[:, :q], synth.orthonormal(rng, q, q)
+    A = (U * sv) @ V.T
+    assert abs(orc.spectral_gap(A, r) - 2.0) < 1e-10
+    est = orc.next_singular_value_estimate(A, U[:, :r], rng.standard_normal((q, r)), iters=8)
+    assert abs(est - 4.0) < 1e-9
+    # a basis that misses part of the leading subspace: the estimate sees what is left of it (here sigma_1 = 9)
+    est_wrong = orc.next_singular_value_estimate(A, U[:, 1:r + 1], rng.standard_normal((q, r)), iters=8)
+    assert abs(est_wrong - 9.0) < 1e-9
+    # no separation (Gaussian matrix), few iterations: a lower bound, and not a poor one
+    G = rng.standard_normal((60, 50))
+    Ug, sg, _ = np.linalg.svd(G, full_matrices=False)
+    e2 = orc.next_singular_value_estimate(G, Ug[:, :6], rng.standard_normal((50, 6)), iters=2)
+    assert 0.85 * sg[6] < e2 <= sg[6] * (1 + 1e-12)
+    # 2r > min(p, q): the deflated matrix has fewer than r directions; the estimate must stay below its norm
+    # (the completion of the block by the orthonormalisation is not orthogonal to the basis)
+    A2 = (synth.orthonormal(rng, 30, 30)[:, :20] * np.concatenate([np.linspace(9, 5, 12), 0.4 * rng.random(8)])) \
+        @ synth.orthonormal(rng, 20, 20).T
+    Q2 = orc.range_finder(A2, rng.standard_normal((20, 12)), 1)
+    norm_deflated = np.linalg.svd(A2 - Q2 @ (Q2.T @ A2), compute_uv=False)[0]
+    e3 = orc.next_singular_value_estimate(A2, Q2, rng.standard_normal((20, 12)), iters=2)
+    assert 0.5 * norm_deflated < e3 <= norm_deflated * (1 + 1e-12)
+
+
 def test_range_finder_rank_deficient_source_still_reconstructs():
     """rank(A) < r: the basis is completed arbitrarily; only Q^T Q = I and Q Q^T A = A are fixed."""
     rng = rng_of(16)
