@@ -83,3 +83,65 @@ def test_random_shapes_and_options(case):
     assert max(orths) <= TOL_ORTH and max(dists) <= TOL_SUBSPACE, f"orth {orths} dist {dists}"
     pair.local_step([g.draw(5) for g in gens], lr=1e-3, bf16=bf16)
     pair.compare_local(TOL)
+
+
+def draw_rr_case(case):
+    rng = np.random.default_rng(5000 + case)
+    n = int(rng.integers(1, 5))
+    align = int(rng.integers(0, 3))
+    shapes = []
+    for _ in range(n):
+        p = int(rng.integers(8, 500))
+        q = int(rng.integers(8, 600))
+        r = int(rng.integers(1, max(2, min(p, q, 256) // 2 + 1)))          # ranks up to 128, odd ones and 1 included
+        if align >= 1:
+            q = max(4, q // 4 * 4)
+        if align == 2:
+            q = max(32, q // 32 * 32)
+            r = max(4, r // 4 * 4)
+        shapes.append((p, q, min(r, 128)))
+    return shapes, bool(rng.integers(0, 2)), int(rng.integers(0, 3))
+
+
+@pytest.mark.parametrize("case", list(range(10)))
+def test_random_shapes_rayleigh_ritz_refresh(case):
+    """Refresh with the Rayleigh-Ritz step (Sec. 2: singular vectors in order) and the two spectrum metrics of
+    Sec. 5.1 on randomly drawn shape sets: subspace, ordered Ritz values, diagonal restricted matrix, stable rank,
+    bound on the sigma_(r+1) estimate; then a step."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    shapes, bf16, q_it = draw_rr_case(case)
+    print(f"rr case {case}: {shapes} bf16={bf16} q_it={q_it}", flush=True)
+    ohp = orc.Hyper(power_iters=q_it, rayleigh_ritz=True)
+    ghp = lordo.hparams(power_iters=q_it, rayleigh_ritz=True, grad_dtype=lordo.BF16 if bf16 else lordo.F32)
+    W0 = [synth.weights(np.random.default_rng(synth.seed_for(70, 100 * case + i)), p, q) for i, (p, q, r) in enumerate(shapes)]
+    Q0 = [synth.orthonormal(np.random.default_rng(synth.seed_for(71, 100 * case + i)), p, r).astype(np.float32)
+          for i, (p, q, r) in enumerate(shapes)]
+    pair = Pair(torch, shapes, W0, ohp, ghp, Q0)
+    gens = [synth.SpikedGradient(p, q, min(4, p, q), synth.seed_for(72, 100 * case + i), bf16=bf16) for i, (p, q, r) in enumerate(shapes)]
+    pair.local_step([g.draw(0) for g in gens], lr=1e-3, bf16=bf16, first_step_patch=True)
+    Src = [g.draw(100) for g in gens]
+    Om = [synth.omega(np.random.default_rng(synth.seed_for(73, 100 * case + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+    dists, orths = pair.refresh(Src, Om, bf16=bf16)
+    assert max(orths) <= TOL_ORTH and max(dists) <= TOL_SUBSPACE, f"orth {orths} dist {dists}"
+    sr = pair.opt.stable_rank().cpu().numpy().astype(np.float64)
+    gap = pair.opt.spectral_gap(pair.to_dev(Src, bf16), pair.to_dev(Om, False)).cpu().numpy().astype(np.float64)
+    pair.opt.poll_status()
+    for i, (p, q, r) in enumerate(shapes):
+        A = np.asarray(Src[i], dtype=np.float64)
+        Qg = pair.get(i, lordo.STATE_Q)
+        ritz = pair.opt.get_state(i, lordo.STATE_RITZ).cpu().numpy().astype(np.float64)
+        _, S = orc.rayleigh_ritz(orc.range_finder(A, np.asarray(Om[i], dtype=np.float64), q_it), A)
+        assert np.all(np.diff(ritz) <= 0) and np.max(np.abs(ritz - S) / S) <= TOL, f"Ritz values of matrix {i}"
+        D = Qg.T @ A @ A.T @ Qg
+        d = np.diag(D)
+        assert np.linalg.norm(D - np.diag(d)) <= 1e-5 * np.linalg.norm(D), f"matrix {i}"
+        assert np.all(np.diff(d) <= 1e-5 * d[0]), f"matrix {i}"
+        # the leading Ritz value stands for the spectral norm: as good as the range finder's first direction
+        sr_from_ritz = float(np.sum(A * A) / S[0] ** 2)
+        assert abs(sr[i] - sr_from_ritz) <= TOL * sr_from_ritz, f"stable rank of matrix {i}"
+        assert sr[i] >= orc.stable_rank(A) * (1 - TOL)
+        deflated = np.linalg.svd(A - Qg @ (Qg.T @ A), compute_uv=False)[0]
+        assert ritz[-1] - gap[i] <= deflated * (1 + TOL) + 1e-6 * ritz[0], f"sigma_(r+1) estimate of matrix {i}"
+    pair.local_step([g.draw(5) for g in gens], lr=1e-3, bf16=bf16)
+    pair.compare_local(TOL)
