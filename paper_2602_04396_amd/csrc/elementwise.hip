@@ -908,7 +908,7 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d, int top_value_on
             c8[j] = cs[kk[j]];
             op[j] = ii[j] * ld + (pr & 255); oq[j] = ii[j] * ld + (pr >> 8);
             ap[j] = A[op[j]]; aq[j] = A[oq[j]];
-            vp[j] = V[op[j]]; vq[j] = V[oq[j]];
+            if (!top_value_only) { vp[j] = V[op[j]]; vq[j] = V[oq[j]]; }      // eigenvalues alone need no vectors
           }
         }
 #pragma unroll
@@ -916,8 +916,10 @@ __global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d, int top_value_on
           if (s8[j] != 0.f) {
             A[op[j]] = c8[j] * ap[j] - s8[j] * aq[j];
             A[oq[j]] = s8[j] * ap[j] + c8[j] * aq[j];
-            V[op[j]] = c8[j] * vp[j] - s8[j] * vq[j];
-            V[oq[j]] = s8[j] * vp[j] + c8[j] * vq[j];
+            if (!top_value_only) {
+              V[op[j]] = c8[j] * vp[j] - s8[j] * vq[j];
+              V[oq[j]] = s8[j] * vp[j] + c8[j] * vq[j];
+            }
           }
       }
       __syncthreads();
