@@ -332,6 +332,16 @@ def main():
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, args.rank, dom, args.update)}
 
+    if args.rayleigh_ritz and not args.no_events and not use_ef:
+        # the spectrum metrics (Sec. 5.1) on their own: the gap program is a second pass of the size of a refresh
+        opt.spectral_gap(Gp[0], Op)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(3):
+            opt.spectral_gap(Gp[0], Op)
+        torch.cuda.synchronize()
+        kernels["spectral_gap"] = {"avg_ms": 1e3 * (time.perf_counter() - t2) / 3, "launches": 3}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, shapes, outer_every, refresh_every, d["power_iters"])

@@ -73,6 +73,16 @@ def test_strerror_and_null_handling(lib):
     assert lib.lordo_local_step(None, None, None, 1e-3, 1.0, None) == lordo.EINVAL
     assert lib.lordo_outer_step(None, None, None, None) == lordo.EINVAL
     assert lib.lordo_poll_status(None, None) == lordo.EINVAL
+    assert lib.lordo_refresh_subspace(None, None, lordo.BF16, None, None) == lordo.EINVAL
+    assert lib.lordo_refresh_subspace_local(None, None, 1.0, None, None) == lordo.EINVAL
+    assert lib.lordo_init_projection(None, None, None) == lordo.EINVAL
+    assert lib.lordo_export_uplink(None, None, None) == lordo.EINVAL
+    assert lib.lordo_outer_step_lowrank(None, None, None, None) == lordo.EINVAL
+    assert lib.lordo_sync_payload(None, None, None, None) == lordo.EINVAL
+    assert lib.lordo_get_mssv(None, None, None) == lordo.EINVAL
+    assert lib.lordo_get_stable_rank(None, None, None) == lordo.EINVAL
+    assert lib.lordo_spectral_gap(None, None, lordo.BF16, None, None, None) == lordo.EINVAL
+    assert lib.lordo_get_state(None, 0, 0, None, None) == lordo.EINVAL
 
 
 def test_init_without_gpu_fails_loudly(lib):
