@@ -434,6 +434,37 @@ def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16):
     assert e.value.code == lordo.EINVAL
 
 
+def test_local_variant_with_rayleigh_ritz(torch):
+    """Alg. 2 refresh (source = this step's gradient plus the error buffer, fp32 in the arena) ending with the
+    Rayleigh-Ritz step: the new basis diagonalises the restricted source, in descending order, and its Ritz values
+    and stable rank are those of G + E; the step on the same gradient follows."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128)]
+    ohp = orc.Hyper(error_feedback=True, qhm_mode="low", omega=0.9, power_iters=1, rayleigh_ritz=True)
+    ghp = lordo.hparams(error_feedback=True, qhm_mode=1, omega=0.9, power_iters=1, rayleigh_ritz=True)
+    pair = Pair(torch, shapes, _weights(shapes, 38), ohp, ghp)
+    gens = _spiked(shapes, 38, 8)
+    Om = [synth.omega(np.random.default_rng(synth.seed_for(38, 900 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+    pair.local_step([g.draw(0) for g in gens], lr=1e-3, first_step_patch=True)
+    G = [g.draw(1) for g in gens]
+    sources = [orc.local_variant_source(pair.st[i], np.asarray(G[i], dtype=np.float64), 0.8) for i in range(len(shapes))]
+    dists, orths = pair.refresh_local(G, Om, grad_scale=0.8)
+    assert max(dists) <= TOL_SUBSPACE and max(orths) <= TOL_ORTH
+    sr = pair.opt.stable_rank().cpu().numpy().astype(np.float64)
+    for i, (p, q, r) in enumerate(shapes):
+        A = sources[i]
+        Qg = pair.get(i, lordo.STATE_Q)
+        ritz = pair.opt.get_state(i, lordo.STATE_RITZ).cpu().numpy().astype(np.float64)
+        _, S = orc.rayleigh_ritz(orc.range_finder(A, np.asarray(Om[i], dtype=np.float64), 1), A)
+        assert np.max(np.abs(ritz - S) / S) <= TOL, f"Ritz values of matrix {i}"
+        D = Qg.T @ A @ A.T @ Qg
+        d = np.diag(D)
+        assert np.linalg.norm(D - np.diag(d)) <= 1e-5 * np.linalg.norm(D) and np.all(np.diff(d) <= 1e-5 * d[0])
+        assert abs(sr[i] - np.sum(A * A) / S[0] ** 2) <= TOL * sr[i]
+    pair.local_step(G, lr=1e-3, grad_scale=0.8)
+    pair.compare_local(TOL)
+
+
 def test_refresh_before_first_step_and_exact_reconstruction(torch):
     """rank(Src) = r exactly: the refreshed Q must reproduce Src (Q Q^T Src = Src); t = 0: no rotation."""
     from paper_2602_04396_amd import lordo
