@@ -42,7 +42,8 @@ struct MatDev {
   int64_t rot, rot2;      // fp32 r x r : R = Q_new^T Q_old and its elementwise square
   int64_t part;           // fp32 split-K partial sums of the r x r products (Gram, R): slices x r x r
   int64_t err;            // fp32 p x q error-feedback residual E (-1 without error feedback)
-  int64_t ritz;           // fp32 r + 2 : Ritz values of the last refresh, ||Src||_F^2, estimate of sigma_{r+1} (-1 without the Rayleigh-Ritz step)
+  int64_t ritz;           // fp32 r + 3 : Ritz values of the last refresh, ||Src||_F^2, estimate of sigma_{r+1}, shift of the
+                          // last factorisation of a Ritz matrix (-1 without the Rayleigh-Ritz step)
 };
 
 // Work item of the projection kernels.
@@ -165,7 +166,7 @@ hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int6
 hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
 hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s);
 // refresh helpers (grouped over all matrices)
-hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s);
+hipError_t launch_gram_shift(const DevCtx& d, float coef, bool store, hipStream_t s);
 hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
 hipError_t launch_frob2(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float* partial, bool src_f32, hipStream_t s);

@@ -8,7 +8,7 @@
 //   k_pack_q / k_pack_y / k_pack_block / k_split_planes   fp32 -> bf16 hi/lo operand planes in matrix-core order
 //   k_glow_to_z, k_lr_to_plain, k_plain_to_lr, k_lr_exchange   between the operand layout of the low-rank state and plain buffers
 //   k_gram_shift, k_potf2, k_diag_inverses   CholeskyQR: diagonal shift, Cholesky of a diagonal block and its inverse
-//   k_jacobi_eigh     eigen-decomposition of the r x r Ritz matrix (Rayleigh-Ritz step: basis ordered as in Sec. 2's SVD projection)
+//   k_jacobi_svd      singular vectors of the Cholesky factor of the r x r Ritz matrix (Rayleigh-Ritz step: basis ordered as in Sec. 2's SVD projection)
 //   k_frob2_chunks / k_frob2_sum / k_stable_rank   squared Frobenius norm of the refresh source and its stable rank (Sec. 5.1)
 //   k_rot_pre / k_rot_post, k_mssv   elementwise parts of the moment rotation (Alg. 1 rotation lines); similarity diagnostic (Sec. 5.1)
 #include "common.h"
@@ -556,7 +556,8 @@ hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t
 // CholeskyQR helpers
 // ---------------------------------------------------------------------------------------
 // S_ii += coef * trace(S): keeps the first factorisation positive definite in fp32.
-__global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef) {
+// store: also keep the shift behind the Ritz values (the Rayleigh-Ritz step subtracts it from the eigenvalues).
+__global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef, int store) {
   const MatDev& m = d.mats[blockIdx.x];
   float* S = reinterpret_cast<float*>(d.arena + m.gram);
   __shared__ float red[256];
@@ -570,6 +571,7 @@ __global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef) {
   }
   float shift = coef * red[0];
   for (int i = threadIdx.x; i < m.r; i += 256) S[(int64_t)i * m.r + i] += shift;
+  if (store && m.ritz >= 0 && threadIdx.x == 0) reinterpret_cast<float*>(d.arena + m.ritz)[m.r + 2] = shift;
 }
 // Mean squared singular value of R = Q_new^T Q_old of the last refresh (Sec. 5.1, Metrics):
 // (1/r) sum_i sigma_i^2 = ||R||_F^2 / r, from the elementwise square the rotation already keeps.
@@ -657,8 +659,8 @@ hipError_t launch_stable_rank(const DevCtx& d, float* out, int which, hipStream_
   return hipGetLastError();
 }
 
-hipError_t launch_gram_shift(const DevCtx& d, float coef, hipStream_t s) {
-  hipLaunchKernelGGL(k_gram_shift, dim3(d.n), dim3(256), 0, s, d, coef);
+hipError_t launch_gram_shift(const DevCtx& d, float coef, bool store, hipStream_t s) {
+  hipLaunchKernelGGL(k_gram_shift, dim3(d.n), dim3(256), 0, s, d, coef, store ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -793,210 +795,173 @@ hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
 
 // ---------------------------------------------------------------------------------------
 // Rayleigh-Ritz step of the refresh (Sec. 2 ComputeProjection wants Q = the first r columns of U, largest
-// singular value first): eigen-decomposition T = U diag(lambda) U^T of the r x r matrix T = (Q^T Src)(Q^T Src)^T,
-// r <= 128, one workgroup per matrix, T and U in LDS (odd row pitch).  Cyclic two-sided Jacobi with the
-// round-robin order: a sweep is n-1 rounds of n/2 disjoint plane rotations (n = r rounded up to even; the
-// added index has a zero row and column and is never rotated).  A round has three phases separated by
-// barriers: the n/2 rotations (c, s) that annihilate T[p][q]; columns p, q of T and of U combined; rows p, q
-// of T combined.  A rotation is skipped where |T[p][q]| is below 1e-7 sqrt(T[p][p] T[q][q]) or below
-// 3e-8 of the largest diagonal entry (the entries of T carry that much rounding already); the iteration
-// ends with the first sweep that rotates nothing, after at most 15 sweeps.
-// Output: column k of `lfac` (r x r row-major) = eigenvector of the k-th largest eigenvalue, signed so that
-// its entry of largest magnitude is positive; ritz[k] = sqrt(max(lambda_k, 0)), the Ritz values of Src.
-// Reads the lower triangle of `gram` only.
+// singular value first): eigenvectors of the r x r matrix T = (Q^T Src)(Q^T Src)^T, r <= 128, from its Cholesky
+// factor: T + shift I = L L^T (the factorisation of the orthonormalisation, with its diagonal shift), and the left
+// singular vectors of L are the eigenvectors of T, its singular values s_i give the eigenvalues s_i^2 - shift.
+// One-sided Jacobi on the columns of X = L (one workgroup per matrix, X alone in LDS, odd row pitch): a plane
+// rotation of columns p, q makes them orthogonal; a sweep is n-1 rounds of n/2 disjoint pairs in round-robin
+// order (n = r rounded up to even; the added column is zero and never rotated); at convergence X = U diag(s).
+// Sixteen lanes share a pair: each keeps eight rows of both columns in registers, the three inner products are
+// summed over the sixteen lanes by a butterfly of lane exchanges (both partners of an exchange add the same two
+// numbers, so all lanes hold the same bits and take the same decision), the columns are rotated in registers and written back:
+// one read and one write of X per round, one barrier per round.  A pair is left alone when
+// |x_p . x_q| <= 3e-7 |x_p| |x_q|; the iteration ends with the first sweep that rotates nothing (at most 20).
+// Working on the factor instead of T keeps the small singular values accurate relative to themselves (the
+// factor has the square root of T's condition number).
+// Output: column k of `rot` (r x r row-major) = singular vector of the k-th largest singular value, signed so
+// that its entry of largest magnitude is positive; ritz[k] = sqrt(max(s_k^2 - shift, 0)), the Ritz values of Src.
+// top_value_only: nothing but the largest Ritz value, to ritz[r + 1] (spectral-gap estimate).
+// Reads the lower triangle of `lfac` and the shift the factorisation stored at ritz[r + 2].
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_jacobi_eigh(DevCtx d, int top_value_only) {
+// Sum over the sixteen lanes of a DPP row, the same bits in every lane: four exchange steps (lanes 1 and 2 apart
+// inside a quad, then the mirror image inside eight and inside sixteen lanes, which pairs quads and halves whose
+// lanes already agree); both partners of an exchange add the same two numbers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float sum16(float v) {
+  v += dpp_get<0xB1>(v);      // quad_perm [1, 0, 3, 2]
+  v += dpp_get<0x4E>(v);      // quad_perm [2, 3, 0, 1]
+  v += dpp_get<0x141>(v);     // row_half_mirror
+  v += dpp_get<0x140>(v);     // row_mirror
+  return v;
+}
+
+__global__ __launch_bounds__(1024) void k_jacobi_svd(DevCtx d, int top_value_only) {
   const MatDev m = d.mats[blockIdx.x];
   const int r = m.r;
   if (r > 128 || m.ritz < 0) return;
   const int n = (r + 1) & ~1;
   const int ld = n + 1;
   const int half = n / 2;
+  const int mm = n - 1;                   // players 0 .. mm-1 rotate, player mm stays
   extern __shared__ float jsm[];
-  float* A = jsm;
-  float* V = A + n * ld;
-  float* cs = V + n * ld;                 // c[0..half), s[0..half)
-  float* lam = cs + n;                    // n
+  float* X = jsm;                         // n x ld
+  float* nrm2 = X + n * ld;               // n
+  unsigned short* sched = reinterpret_cast<unsigned short*>(nrm2 + n);    // mm x half pairs, p | q << 8
   __shared__ int rotated;
-  __shared__ int round_rot[3];            // "some pair of round t rotates", t % 3; cleared two rounds ahead
-  __shared__ float amax_s;
   const int tid = threadIdx.x, nt = blockDim.x;
-  const float* T = reinterpret_cast<const float*>(d.arena + m.gram);
+  const float* L = reinterpret_cast<const float*>(d.arena + m.lfac);
+  float* rz = reinterpret_cast<float*>(d.arena + m.ritz);
 
   for (int idx = tid; idx < n * n; idx += nt) {
     const int i = idx / n, j = idx - i * n;
-    float v = 0.f;
-    if (i < r && j < r) v = i >= j ? T[(int64_t)i * r + j] : T[(int64_t)j * r + i];
-    A[i * ld + j] = v;
-    V[i * ld + j] = i == j ? 1.f : 0.f;
+    X[i * ld + j] = (i < r && j <= i) ? L[(int64_t)i * r + j] : 0.f;
   }
-  if (tid == 0) { rotated = 0; round_rot[0] = 0; round_rot[1] = 0; round_rot[2] = 0; }
-  __syncthreads();
-  if (tid < 64) {                         // largest diagonal entry (one wave)
-    float mx = 0.f;
-    for (int i = tid; i < r; i += 64) mx = fmaxf(mx, fabsf(A[i * ld + i]));
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    if (tid == 0) amax_s = mx;
-  }
-  __syncthreads();
-  const float abs_thr = 3e-8f * amax_s;
-  const int mm = n - 1;                   // players 0 .. mm-1 rotate, player mm stays
-  int* pairs = reinterpret_cast<int*>(lam);   // p | q << 8 of the round's pairs (the eigenvalue array is filled at the end)
   // pairs of every round (circle method): pair 0 of round t is (t, mm), pair k > 0 is ((t + k) % mm, (t + mm - k) % mm)
-  unsigned short* sched = reinterpret_cast<unsigned short*>(lam + n);
   for (int idx = tid; idx < mm * half; idx += nt) {
     const int round = idx / half, k = idx - round * half;
     const int a = (round + k) % mm, b = k == 0 ? mm : (round + mm - k) % mm;
     sched[idx] = (unsigned short)((a < b ? a : b) | ((a < b ? b : a) << 8));
   }
+  if (tid == 0) rotated = 0;
   __syncthreads();
 
-  // work items of the two update phases: (pair k, row or column i), the same for every round.  A wave takes up to
-  // four pairs and its lanes the rows (columns) lane and lane + 64: the rotation of a pair is read once per wave
-  // and phase, and the lanes of an access fall on consecutive rows (columns).
-  constexpr int ITEMS = 8;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-  const int kpw = (half + (nt >> 6) - 1) / (nt >> 6);      // pairs per wave, at most 4
-  int kk[ITEMS], ii[ITEMS];
-#pragma unroll
-  for (int j = 0; j < ITEMS; ++j) {
-    const int a = j >> 1, k = wave * kpw + a, i = lane + 64 * (j & 1);
-    kk[j] = (a < kpw && k < half && i < n) ? k : -1;
-    ii[j] = i;
-  }
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int slot = wave * 4 + (lane >> 4);           // pair handled by this group of sixteen lanes
+  const int slots = (nt >> 6) * 4;
+  const int gl = lane & 15;
+  constexpr int ROWS = 8;                            // 16 lanes x 8 rows = 128 >= n
 
-  int t3 = 0;                             // rounds taken so far, modulo 3
-  for (int sweep = 0; sweep < 15; ++sweep) {
+  for (int sweep = 0; sweep < 20; ++sweep) {
     for (int round = 0; round < mm; ++round) {
-      if (tid < half) {
-        const int k = tid;
+      for (int k = slot; k < half; k += slots) {
         const int pr = sched[round * half + k];
         const int pi = pr & 255, qi = pr >> 8;
-        const float app = A[pi * ld + pi], aqq = A[qi * ld + qi], apq = A[pi * ld + qi];
-        float c = 1.f, sn = 0.f;
-        const float mag = fabsf(apq);
-        if (mag > abs_thr && mag > 1e-7f * __builtin_amdgcn_sqrtf(fabsf(app * aqq))) {
-          // hardware reciprocal, root and reciprocal root (1 ulp): c^2 + s^2 = 1 to rounding either way
-          const float tau = (aqq - app) * 0.5f * __builtin_amdgcn_rcpf(apq);
-          const float t = copysignf(1.f, tau) * __builtin_amdgcn_rcpf(fabsf(tau) + __builtin_amdgcn_sqrtf(1.f + tau * tau));
-          c = __builtin_amdgcn_rsqf(1.f + t * t);
-          sn = t * c;
-          rotated = 1;                    // benign race: every writer stores 1
-          round_rot[t3] = 1;
-        }
-        cs[k] = c;
-        cs[half + k] = sn;
-        pairs[k] = pr;
-      }
-      __syncthreads();
-      // late sweeps skip most rotations: a round without any costs this one barrier.  The flag of the round after the
-      // next is cleared here; its writers are two barriers away.
-      const int some = round_rot[t3];
-      if (tid == 0) round_rot[t3 == 0 ? 2 : t3 - 1] = 0;
-      t3 = t3 == 2 ? 0 : t3 + 1;
-      if (!some) continue;
-      // columns p, q of T and U:  x_p' = c x_p - s x_q,  x_q' = s x_p + c x_q.  All operands of a thread's items
-      // are read before any is written, so that the LDS reads overlap.
-      {
-        float c8[ITEMS], s8[ITEMS], ap[ITEMS], aq[ITEMS], vp[ITEMS], vq[ITEMS];
-        int op[ITEMS], oq[ITEMS];
+        float xp[ROWS], xq[ROWS];
+        float a = 0.f, b = 0.f, c = 0.f;
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-          s8[j] = kk[j] >= 0 ? cs[half + kk[j]] : 0.f;
-          if (s8[j] != 0.f) {             // the same for all lanes of a wave
-            const int pr = pairs[kk[j]];
-            c8[j] = cs[kk[j]];
-            op[j] = ii[j] * ld + (pr & 255); oq[j] = ii[j] * ld + (pr >> 8);
-            ap[j] = A[op[j]]; aq[j] = A[oq[j]];
-            if (!top_value_only) { vp[j] = V[op[j]]; vq[j] = V[oq[j]]; }      // eigenvalues alone need no vectors
-          }
+        for (int j = 0; j < ROWS; ++j) {
+          const int row = gl + 16 * j;
+          xp[j] = row < n ? X[row * ld + pi] : 0.f;
+          xq[j] = row < n ? X[row * ld + qi] : 0.f;
         }
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-          if (s8[j] != 0.f) {
-            A[op[j]] = c8[j] * ap[j] - s8[j] * aq[j];
-            A[oq[j]] = s8[j] * ap[j] + c8[j] * aq[j];
-            if (!top_value_only) {
-              V[op[j]] = c8[j] * vp[j] - s8[j] * vq[j];
-              V[oq[j]] = s8[j] * vp[j] + c8[j] * vq[j];
+        for (int j = 0; j < ROWS; ++j) {
+          a = fmaf(xp[j], xp[j], a);
+          b = fmaf(xq[j], xq[j], b);
+          c = fmaf(xp[j], xq[j], c);
+        }
+        a = sum16(a);
+        b = sum16(b);
+        c = sum16(c);
+        if (fabsf(c) > 3e-7f * __builtin_amdgcn_sqrtf(a * b)) {        // the same in all sixteen lanes
+          const float zeta = (b - a) * 0.5f * __builtin_amdgcn_rcpf(c);
+          const float t = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+          const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
+          const float sn = t * cs;
+#pragma unroll
+          for (int j = 0; j < ROWS; ++j) {
+            const int row = gl + 16 * j;
+            if (row < n) {
+              X[row * ld + pi] = cs * xp[j] - sn * xq[j];
+              X[row * ld + qi] = sn * xp[j] + cs * xq[j];
             }
           }
-      }
-      __syncthreads();
-      // rows p, q of T
-      {
-        float c8[ITEMS], s8[ITEMS], ap[ITEMS], aq[ITEMS];
-        int op[ITEMS], oq[ITEMS];
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-          s8[j] = kk[j] >= 0 ? cs[half + kk[j]] : 0.f;
-          if (s8[j] != 0.f) {
-            const int pr = pairs[kk[j]];
-            c8[j] = cs[kk[j]];
-            op[j] = (pr & 255) * ld + ii[j]; oq[j] = (pr >> 8) * ld + ii[j];
-            ap[j] = A[op[j]]; aq[j] = A[oq[j]];
-          }
+          if (gl == 0) rotated = 1;                  // benign race: every writer stores 1
         }
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-          if (s8[j] != 0.f) {
-            A[op[j]] = c8[j] * ap[j] - s8[j] * aq[j];
-            A[oq[j]] = s8[j] * ap[j] + c8[j] * aq[j];
-          }
       }
-      __syncthreads();
+      __syncthreads();                               // the pairs of the next round take other columns
     }
-    const int any = rotated;              // all rounds of the sweep are behind a barrier
+    const int any = rotated;                         // all rounds of the sweep are behind a barrier
     __syncthreads();
     if (tid == 0) rotated = 0;
     __syncthreads();
     if (!any) break;
   }
 
-  for (int i = tid; i < n; i += nt) lam[i] = i < r ? A[i * ld + i] : 0.f;
+  // squared column norms = squared singular values
+  for (int i = tid; i < n; i += nt) {
+    float acc = 0.f;
+    for (int row = 0; row < n; ++row) acc = fmaf(X[row * ld + i], X[row * ld + i], acc);
+    nrm2[i] = i < r ? acc : -1.f;
+  }
   __syncthreads();
-  if (top_value_only) {                   // spectral-gap estimate: the largest eigenvalue alone, behind ||Src||_F^2
+  const float shift = rz[r + 2];
+  if (top_value_only) {
     if (tid == 0) {
       float mx = 0.f;
-      for (int i = 0; i < r; ++i) mx = fmaxf(mx, lam[i]);
-      reinterpret_cast<float*>(d.arena + m.ritz)[r + 1] = sqrtf(mx);
+      for (int i = 0; i < r; ++i) mx = fmaxf(mx, nrm2[i]);
+      rz[r + 1] = sqrtf(fmaxf(mx - shift, 0.f));
       if (!(mx <= 3.0e38f)) *d.flag = 1;
     }
     return;
   }
-  // descending order (ties by index); one thread per eigenvector writes its column
+  // descending order (ties by index); one thread per singular vector writes its column
   for (int i = tid; i < r; i += nt) {
-    const float li = lam[i];
+    const float li = nrm2[i];
     int rank = 0;
-    for (int j = 0; j < r; ++j) rank += (lam[j] > li || (lam[j] == li && j < i)) ? 1 : 0;
+    for (int j = 0; j < r; ++j) rank += (nrm2[j] > li || (nrm2[j] == li && j < i)) ? 1 : 0;
     float best = 0.f, bestv = 1.f;
     for (int row = 0; row < r; ++row) {
-      const float v = V[row * ld + i];
+      const float v = X[row * ld + i];
       if (fabsf(v) > best) { best = fabsf(v); bestv = v; }
     }
-    const float sg = bestv < 0.f ? -1.f : 1.f;
-    float* U = reinterpret_cast<float*>(d.arena + m.lfac);
-    for (int row = 0; row < r; ++row) U[(int64_t)row * r + rank] = sg * V[row * ld + i];
-    reinterpret_cast<float*>(d.arena + m.ritz)[rank] = sqrtf(fmaxf(li, 0.f));
-    if (!(fabsf(li) <= 3.0e38f)) *d.flag = 1;      // NaN or infinity in the Ritz matrix
+    const float scale = (bestv < 0.f ? -1.f : 1.f) * (li > 0.f ? 1.f / sqrtf(li) : 0.f);
+    float* U = reinterpret_cast<float*>(d.arena + m.rot);
+    for (int row = 0; row < r; ++row) U[(int64_t)row * r + rank] = scale * X[row * ld + i];
+    rz[rank] = sqrtf(fmaxf(li - shift, 0.f));
+    if (!(li <= 3.0e38f)) *d.flag = 1;               // NaN or infinity in the factor
   }
 }
 size_t jacobi_lds_bytes(int rmax) {
   const int n = (rmax + 1) & ~1;
-  return sizeof(float) * ((size_t)2 * n * (n + 1) + 2 * n) + sizeof(unsigned short) * (size_t)(n - 1) * (n / 2);
+  return sizeof(float) * ((size_t)n * (n + 1) + n) + sizeof(unsigned short) * (size_t)(n - 1) * (n / 2);
 }
 hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s) {
   if (rmax > 128) return hipErrorInvalidValue;
   const size_t lds = jacobi_lds_bytes(rmax);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_eigh), hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_svd), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)jacobi_lds_bytes(128));
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int threads = rmax > 64 ? 1024 : (rmax > 32 ? 512 : 256);
-  hipLaunchKernelGGL(k_jacobi_eigh, dim3(d.n), dim3(threads), lds, s, d, top_value_only ? 1 : 0);
+  hipLaunchKernelGGL(k_jacobi_svd, dim3(d.n), dim3(threads), lds, s, d, top_value_only ? 1 : 0);
   return hipGetLastError();
 }
 

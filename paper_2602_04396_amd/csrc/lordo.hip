@@ -194,6 +194,45 @@ struct ProgramBuilder {
     P.ops.push_back(op);
   }
 
+  // Cholesky factor of the Gram matrix of every matrix, block column by block column (NB-wide: diagonal block by
+  // k_potf2, two grouped GEMMs for the panel and the trailing update); the Gram buffer is consumed, the factor
+  // goes to its own buffer, the inverses of the diagonal blocks to theirs.
+  int max_blocks_all() const {
+    int mb = 0;
+    for (int i = 0; i < n; ++i) mb = std::max(mb, (P.mat[i].r + NB - 1) / NB);
+    return mb;
+  }
+  void factor(int max_blocks) {
+    for (int jb = 0; jb < max_blocks; ++jb) {
+      simple(OP_POTF2, jb);
+      // L_21 = S_21 L_11^{-T}
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        int rest = m.r - (jb + 1) * NB;
+        if (rest <= 0) return false;
+        int64_t o = ((int64_t)(jb + 1) * NB * m.r + (int64_t)jb * NB) * 4;
+        g.A = ref_arena(m.gram + o); g.sAm = m.r; g.sAk = 1;
+        g.B = ref_arena(m.dinv + (int64_t)jb * NB * NB * 4); g.sBk = 1; g.sBn = NB;
+        g.C = ref_arena(m.lfac + o); g.ldc = m.r;
+        g.M = rest; g.N = NB; g.K = NB;
+        return true;
+      });
+      // S_22 -= L_21 L_21^T
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        int rest = m.r - (jb + 1) * NB;
+        if (rest <= 0) return false;
+        int64_t o = ((int64_t)(jb + 1) * NB * m.r + (int64_t)jb * NB) * 4;
+        g.A = ref_arena(m.lfac + o); g.sAm = m.r; g.sAk = 1;
+        g.B = ref_arena(m.lfac + o); g.sBk = 1; g.sBn = m.r;
+        g.C = ref_arena(m.gram + ((int64_t)(jb + 1) * NB * m.r + (int64_t)(jb + 1) * NB) * 4); g.ldc = m.r;
+        g.M = rest; g.N = rest; g.K = NB;
+        g.alpha = -1.f; g.beta = 1.f;
+        return true;
+      });
+    }
+  }
+
   // Thin QR of the block held in buffer `cur` of the pair selected by `buf` (rows = p or q),
   // by `passes` rounds of CholeskyQR; returns the buffer index that holds the result.
   int orth(bool y_side, int cur, int passes, bool shifted = true) {
@@ -212,34 +251,7 @@ struct ProgramBuilder {
         return true;
       }, false, true, true);      // the factorisation reads the lower triangle only
       if (pass == 0 && shifted) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
-      for (int jb = 0; jb < max_blocks; ++jb) {
-        simple(OP_POTF2, jb);
-        // L_21 = S_21 L_11^{-T}
-        gemm([&](int i, GemmDesc& g) {
-          const MatDev& m = P.mat[i];
-          int rest = m.r - (jb + 1) * NB;
-          if (rest <= 0) return false;
-          int64_t o = ((int64_t)(jb + 1) * NB * m.r + (int64_t)jb * NB) * 4;
-          g.A = ref_arena(m.gram + o); g.sAm = m.r; g.sAk = 1;
-          g.B = ref_arena(m.dinv + (int64_t)jb * NB * NB * 4); g.sBk = 1; g.sBn = NB;
-          g.C = ref_arena(m.lfac + o); g.ldc = m.r;
-          g.M = rest; g.N = NB; g.K = NB;
-          return true;
-        });
-        // S_22 -= L_21 L_21^T
-        gemm([&](int i, GemmDesc& g) {
-          const MatDev& m = P.mat[i];
-          int rest = m.r - (jb + 1) * NB;
-          if (rest <= 0) return false;
-          int64_t o = ((int64_t)(jb + 1) * NB * m.r + (int64_t)jb * NB) * 4;
-          g.A = ref_arena(m.lfac + o); g.sAm = m.r; g.sAk = 1;
-          g.B = ref_arena(m.lfac + o); g.sBk = 1; g.sBn = m.r;
-          g.C = ref_arena(m.gram + ((int64_t)(jb + 1) * NB * m.r + (int64_t)(jb + 1) * NB) * 4); g.ldc = m.r;
-          g.M = rest; g.N = rest; g.K = NB;
-          g.alpha = -1.f; g.beta = 1.f;
-          return true;
-        });
-      }
+      factor(max_blocks);
       simple(OP_DIAG_INV);
       // M = L^{-1}, row block by row block from the inverses of the diagonal blocks:
       // M[i, <i] = -M_ii (L[i, <i] M[<i, <i]); the Gram buffer, consumed by the factorisation, holds the inner product
@@ -366,7 +378,9 @@ struct ProgramBuilder {
       g.M = m.r; g.N = m.r; g.K = m.q;
       return true;
     }, false, true, true);
-    simple(OP_EIGH, 1);                 // largest eigenvalue only
+    simple(OP_SHIFT, 1, 32.f * 5.9604645e-8f);
+    factor(max_blocks_all());
+    simple(OP_EIGH, 1);                 // largest singular value only
     simple(OP_PACK);                    // the Z products borrowed the operand planes of Q
     P.gap_ops.swap(P.ops);
     P.ops.swap(saved);
@@ -434,19 +448,24 @@ struct ProgramBuilder {
         g.C = ref_arena(m.gram); g.ldc = m.r;
         g.M = m.r; g.N = m.r; g.K = m.q;
         return true;
-      }, false, true, true);      // the eigen-solver reads the lower triangle only
-      simple(OP_EIGH);            // eigenvectors, by descending eigenvalue, into the buffer of the Cholesky factor
+      }, false, true, true);      // the factorisation reads the lower triangle only
+      // T + shift I = L L^T, then the singular vectors of L (= eigenvectors of T) by one-sided Jacobi on its columns
+      simple(OP_SHIFT, 1, 32.f * 5.9604645e-8f);
+      factor(max_blocks_all());
+      // left singular vectors, by descending singular value, into the buffer the rotation matrix R takes later
+      // (not the buffer of the factor's inverse: its upper triangle has to stay zero)
+      simple(OP_EIGH);
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
         g.A = ref_arena(m.y[ycur]); g.sAm = m.r; g.sAk = 1;
-        g.B = ref_arena(m.lfac); g.sBk = m.r; g.sBn = 1;
+        g.B = ref_arena(m.rot); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.y[1 - ycur]); g.ldc = m.r;
         g.M = m.p; g.N = m.r; g.K = m.r;
         return true;
       });
-      // the accumulated plane rotations are orthogonal to about 1e-6 per entry only: one CholeskyQR pass (unshifted:
-      // the block is orthonormal to 1e-4 already) brings the columns back to working precision without changing
-      // their order or, visibly, their directions
+      // the columns found are orthogonal to about 1e-6 per pair only: one CholeskyQR pass (unshifted: the block is
+      // orthonormal to 1e-4 already) brings them back to working precision without changing their order or,
+      // visibly, their directions
       ycur = orth(true, 1 - ycur, 1, false);
       simple(OP_FROB);            // ||Src||_F^2 for the stable rank (Sec. 5.1)
     }
@@ -615,7 +634,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.minv = A.take(rr * 4);
     m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
     m.part = A.take(rr * 4 * P.part_slices);
-    m.ritz = hp.rayleigh_ritz ? A.take((size_t)(m.r + 2) * 4) : -1;
+    m.ritz = hp.rayleigh_ritz ? A.take((size_t)(m.r + 3) * 4) : -1;
   }
   // projection tile tables
   std::vector<ProjTile> down, up;
@@ -979,7 +998,7 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
         HIPCHK(launch_gemm32(c->dev, descs, tiles + op.tile_first, op.ntiles, op.tile, src_dtype == LORDO_BF16, s));
         if (op.split) HIPCHK(launch_gemm_reduce(c->dev, descs + op.desc_first, op.ndescs, s));
         break;
-      case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, s)); break;
+      case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, op.iarg != 0, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
       case OP_EIGH: HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, op.iarg != 0, s)); break;
