@@ -50,7 +50,7 @@ def parse():
     ap.add_argument("--refresh-every", type=int, default=None)
     ap.add_argument("--outer-every", type=int, default=None)
     ap.add_argument("--rayleigh-ritz", action="store_true",
-                    help="end every refresh with the Rayleigh-Ritz step (basis ordered as singular vectors; ranks up to 128)")
+                    help="end every refresh with the Rayleigh-Ritz step (basis ordered as singular vectors; ranks up to 1024)")
     ap.add_argument("--update", default="plain", choices=["plain", "low-qhm", "full-qhm", "ef", "global", "local", "uplink"],
                     help="update case of the local step: plain (default, the headline), low-rank / full-rank QHM (omega 0.9), "
                          "error feedback, global = full-rank QHM + error feedback (the paper's LoRDO-Global), local = low-rank QHM + error "

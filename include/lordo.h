@@ -89,7 +89,8 @@ typedef struct {
   int32_t rayleigh_ritz;         /* 1: every refresh ends with a Rayleigh-Ritz step, so that the columns of Q are the
                                     approximate left singular vectors of the source, largest singular value first, as
                                     the SVD projection of Sec. 2 orders them (0: an unordered orthonormal basis of the
-                                    same subspace).  Needs every rank <= 128 (LORDO_EINVAL otherwise)        */
+                                    same subspace).  Needs every rank <= 1024 (LORDO_EINVAL otherwise); sets of ranks up to 128 take a
+                                    much faster solver                                                  */
   int32_t reserved;              /* must be 0 */
 } lordo_hparams;
 

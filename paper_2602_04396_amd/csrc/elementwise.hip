@@ -813,6 +813,11 @@ hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
 // top_value_only: nothing but the largest Ritz value, to ritz[r + 1] (spectral-gap estimate).
 // Reads the lower triangle of `lfac` and the shift the factorisation stored at ritz[r + 2].
 // ---------------------------------------------------------------------------------------
+__global__ void k_fill_zero_i32(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
 // Sum over the sixteen lanes of a DPP row, the same bits in every lane: four exchange steps (lanes 1 and 2 apart
 // inside a quad, then the mirror image inside eight and inside sixteen lanes, which pairs quads and halves whose
 // lanes already agree); both partners of an exchange add the same two numbers.
@@ -962,6 +967,132 @@ hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hi
   }
   const int threads = rmax > 64 ? 1024 : (rmax > 32 ? 512 : 256);
   hipLaunchKernelGGL(k_jacobi_svd, dim3(d.n), dim3(threads), lds, s, d, top_value_only ? 1 : 0);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// The same one-sided Jacobi for ranks above 128 (up to 1024), where the factor does not fit into LDS: the columns of
+// L live as contiguous rows of an r x r buffer in device memory (the Gram buffer, which the factorisation has consumed),
+// one kernel launch is one round, one wave takes one pair of one matrix (both columns in registers, 16 elements per
+// lane at most), and the barrier between rounds is the kernel boundary.  Convergence is tracked on the device: a
+// rotation in sweep s sets flag[s]; the launches of sweep s + 1 return at once when flag[s] is still clear, so the
+// host enqueues a fixed number of sweeps without reading anything back.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_jsvd_init(DevCtx d) {
+  const MatDev& m = d.mats[blockIdx.y];
+  if (m.ritz < 0) return;
+  const int r = m.r;
+  const float* L = reinterpret_cast<const float*>(d.arena + m.lfac);
+  float* Xt = reinterpret_cast<float*>(d.arena + m.gram);
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < (int64_t)r * r; idx += (int64_t)gridDim.x * 256) {
+    const int c = (int)(idx / r), row = (int)(idx - (int64_t)c * r);
+    Xt[idx] = row >= c ? L[(int64_t)row * r + c] : 0.f;       // column c of L
+  }
+}
+__global__ __launch_bounds__(256) void k_jsvd_round(DevCtx d, int round, int sweep, int* __restrict__ flags) {
+  if (sweep > 0 && flags[sweep - 1] == 0) return;             // the previous sweep rotated nothing: converged
+  const MatDev& m = d.mats[blockIdx.y];
+  if (m.ritz < 0) return;
+  const int r = m.r;
+  const int n = (r + 1) & ~1, half = n / 2, mm = n - 1;
+  const int lane = threadIdx.x & 63;
+  const int k = blockIdx.x * 4 + (threadIdx.x >> 6);          // pair of this wave
+  if (k >= half || round >= mm) return;
+  const int a0 = (round + k) % mm, b0 = k == 0 ? mm : (round + mm - k) % mm;
+  const int pi = a0 < b0 ? a0 : b0, qi = a0 < b0 ? b0 : a0;
+  if (qi >= r) return;                                        // the added zero column of an odd rank
+  float* Xt = reinterpret_cast<float*>(d.arena + m.gram);
+  float* xpp = Xt + (int64_t)pi * r;
+  float* xqq = Xt + (int64_t)qi * r;
+  constexpr int EL = 16;                                      // 64 lanes x 16 = 1024 >= r
+  float xp[EL], xq[EL];
+  float a = 0.f, b = 0.f, c = 0.f;
+#pragma unroll
+  for (int j = 0; j < EL; ++j) {
+    const int e = lane + 64 * j;
+    xp[j] = e < r ? xpp[e] : 0.f;
+    xq[j] = e < r ? xqq[e] : 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < EL; ++j) {
+    a = fmaf(xp[j], xp[j], a);
+    b = fmaf(xq[j], xq[j], b);
+    c = fmaf(xp[j], xq[j], c);
+  }
+  // butterfly over the wave: both partners of every exchange add the same two numbers, all lanes end with the same bits
+  a = sum16(a); b = sum16(b); c = sum16(c);
+  a += __shfl_xor(a, 16); b += __shfl_xor(b, 16); c += __shfl_xor(c, 16);
+  a += __shfl_xor(a, 32); b += __shfl_xor(b, 32); c += __shfl_xor(c, 32);
+  if (!(fabsf(c) > 3e-7f * __builtin_amdgcn_sqrtf(a * b))) return;
+  const float zeta = (b - a) * 0.5f * __builtin_amdgcn_rcpf(c);
+  const float t = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+  const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
+  const float sn = t * cs;
+#pragma unroll
+  for (int j = 0; j < EL; ++j) {
+    const int e = lane + 64 * j;
+    if (e < r) {
+      xpp[e] = cs * xp[j] - sn * xq[j];
+      xqq[e] = sn * xp[j] + cs * xq[j];
+    }
+  }
+  if (lane == 0) flags[sweep] = 1;                            // benign race: every writer stores 1
+}
+// squared column norms, order, signs, output: one workgroup per matrix (as the tail of k_jacobi_svd)
+__global__ __launch_bounds__(256) void k_jsvd_finish(DevCtx d, int top_value_only) {
+  const MatDev& m = d.mats[blockIdx.x];
+  if (m.ritz < 0) return;
+  const int r = m.r;
+  const float* Xt = reinterpret_cast<const float*>(d.arena + m.gram);
+  float* rz = reinterpret_cast<float*>(d.arena + m.ritz);
+  __shared__ float nrm2[1024];
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  for (int cidx = wave; cidx < r; cidx += 4) {                // one wave per column: fixed order of the sum
+    float acc = 0.f;
+    for (int e = lane; e < r; e += 64) acc = fmaf(Xt[(int64_t)cidx * r + e], Xt[(int64_t)cidx * r + e], acc);
+    acc = sum16(acc);
+    acc += __shfl_xor(acc, 16);
+    acc += __shfl_xor(acc, 32);
+    if (lane == 0) nrm2[cidx] = acc;
+  }
+  __syncthreads();
+  const float shift = rz[r + 2];
+  if (top_value_only) {
+    if (tid == 0) {
+      float mx = 0.f;
+      for (int i = 0; i < r; ++i) mx = fmaxf(mx, nrm2[i]);
+      rz[r + 1] = sqrtf(fmaxf(mx - shift, 0.f));
+      if (!(mx <= 3.0e38f)) *d.flag = 1;
+    }
+    return;
+  }
+  float* U = reinterpret_cast<float*>(d.arena + m.rot);
+  for (int i = tid; i < r; i += 256) {
+    const float li = nrm2[i];
+    int rank = 0;
+    for (int j = 0; j < r; ++j) rank += (nrm2[j] > li || (nrm2[j] == li && j < i)) ? 1 : 0;
+    float best = 0.f, bestv = 1.f;
+    for (int row = 0; row < r; ++row) {
+      const float v = Xt[(int64_t)i * r + row];
+      if (fabsf(v) > best) { best = fabsf(v); bestv = v; }
+    }
+    const float scale = (bestv < 0.f ? -1.f : 1.f) * (li > 0.f ? 1.f / sqrtf(li) : 0.f);
+    for (int row = 0; row < r; ++row) U[(int64_t)row * r + rank] = scale * Xt[(int64_t)i * r + row];
+    rz[rank] = sqrtf(fmaxf(li - shift, 0.f));
+    if (!(li <= 3.0e38f)) *d.flag = 1;
+  }
+}
+hipError_t launch_jacobi_rounds(const DevCtx& d, int rmax, bool top_value_only, int* flags, hipStream_t s) {
+  if (rmax > 1024) return hipErrorInvalidValue;
+  constexpr int SWEEPS = 16;                                  // flags holds SWEEPS ints
+  hipLaunchKernelGGL(k_fill_zero_i32, dim3(1), dim3(64), 0, s, flags, SWEEPS);
+  hipLaunchKernelGGL(k_jsvd_init, dim3(64, d.n), dim3(256), 0, s, d);
+  const int n = (rmax + 1) & ~1, half = n / 2;
+  for (int sweep = 0; sweep < SWEEPS; ++sweep)
+    for (int round = 0; round < n - 1; ++round)
+      hipLaunchKernelGGL(k_jsvd_round, dim3((half + 3) / 4, d.n), dim3(256), 0, s, d, round, sweep, flags);
+  hipLaunchKernelGGL(k_jsvd_finish, dim3(d.n), dim3(256), 0, s, d, top_value_only ? 1 : 0);
   return hipGetLastError();
 }
 

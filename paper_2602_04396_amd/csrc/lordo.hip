@@ -49,6 +49,7 @@ struct Plan {
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
   int r_max = 0;                    // largest rank of any matrix
   int64_t frob_part = -1;           // per-chunk partial sums of ||Src||_F^2 (Rayleigh-Ritz option)
+  int64_t jflags = -1;              // per-sweep "something rotated" flags of the multi-launch Jacobi solver
   int down_pipe = 0;                // pipelined down-projection: rank blocks per wave (1: 128-rank tiles, 2: 256-rank), 0: plain kernel
   int rank_tile = 128;              // rank indices per down-projection tile
   bool g_once = true;               // every matrix has one rank tile of the down-projection: G is read exactly once
@@ -508,9 +509,9 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
   if (hp->qhm_mode != 0 && !(hp->omega >= 0.0 && hp->omega <= 1.0)) return LORDO_EINVAL;
   if (hp->power_iters < 0 || hp->power_iters > 8) return LORDO_EINVAL;
   if ((hp->rayleigh_ritz != 0 && hp->rayleigh_ritz != 1) || hp->reserved != 0) return LORDO_EINVAL;
-  if (hp->rayleigh_ritz)          // the r x r eigen-solver keeps its two matrices in the LDS of one compute unit
+  if (hp->rayleigh_ritz)          // a wave of the multi-launch Jacobi solver keeps two columns of r elements in registers
     for (int i = 0; i < n; ++i)
-      if (shapes[i].rank > 128) return LORDO_EINVAL;
+      if (shapes[i].rank > 1024) return LORDO_EINVAL;
   if (hp->orth_passes != 0 && hp->orth_passes != 2 && hp->orth_passes != 3) return LORDO_EINVAL;
   if (hp->grad_dtype != LORDO_BF16 && hp->grad_dtype != LORDO_F32) return LORDO_EINVAL;
   if (!std::isfinite(hp->outer_lr) || !std::isfinite(hp->outer_momentum)) return LORDO_EINVAL;
@@ -540,7 +541,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   }
   P.chunk_start_h[n] = chunks;
   P.nchunks = chunks;
-  if (hp.rayleigh_ritz) P.frob_part = A.take(sizeof(float) * (size_t)chunks);
+  if (hp.rayleigh_ritz) { P.frob_part = A.take(sizeof(float) * (size_t)chunks); P.jflags = A.take(256); }
   // rank blocks of 32 per down-projection tile: the pipelined kernel (bf16 G) always takes four and
   // leaves the waves of absent blocks idle; the plain kernel is instantiated for 1, 2 and 4
   P.mb = (hp.grad_dtype == LORDO_BF16 || rp_max > 64) ? 4 : (rp_max > 32 ? 2 : 1);
@@ -1001,7 +1002,10 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, op.iarg != 0, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
-      case OP_EIGH: HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, op.iarg != 0, s)); break;
+      case OP_EIGH:
+        if (P.r_max <= 128) HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, op.iarg != 0, s));
+        else HIPCHK(launch_jacobi_rounds(c->dev, P.r_max, op.iarg != 0, c->at<int>(P.jflags), s));
+        break;
       case OP_FROB:
         HIPCHK(launch_frob2(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, c->at<float>(P.frob_part), src_dtype == LORDO_F32, s));
         break;

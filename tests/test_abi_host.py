@@ -55,8 +55,8 @@ def test_workspace_bytes_scales_and_validates(lib):
     assert lordo.workspace_bytes(shapes, lordo.hparams(qhm_mode=2, omega=0.9)) > c2   # column sums
     assert lordo.workspace_bytes(shapes, lordo.hparams(uplink_buffer=True)) - c2 >= sum(4 * r * q for p, q, r in shapes)
     assert lordo.workspace_bytes(shapes, lordo.hparams(rayleigh_ritz=True)) - c2 >= sum(4 * r for p, q, r in shapes)   # Ritz values
-    with pytest.raises(lordo.LordoError) as e:                   # the eigen-solver of the Rayleigh-Ritz step takes ranks up to 128
-        lordo.workspace_bytes([(512, 512, 129)], lordo.hparams(rayleigh_ritz=True))
+    with pytest.raises(lordo.LordoError) as e:                   # the solver of the Rayleigh-Ritz step takes ranks up to 1024
+        lordo.workspace_bytes([(2048, 2048, 1025)], lordo.hparams(rayleigh_ritz=True))
     assert e.value.code == lordo.EINVAL
     for bad_hp in (lordo.hparams(qhm_mode=3), lordo.hparams(qhm_mode=2, omega=0.9, uplink_buffer=True), lordo.hparams(qhm_mode=1, omega=1.5), lordo.hparams(beta1=1.0),
                    lordo.hparams(power_iters=9), lordo.hparams(orth_passes=5), lordo.hparams(grad_dtype=7)):

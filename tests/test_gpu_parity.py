@@ -347,14 +347,17 @@ def test_local_variant_refresh_from_gradient_plus_residual(torch, bf16):
     assert e.value.code == lordo.ESTATE
 
 
-@pytest.mark.parametrize("src_bf16", [True, False], ids=["bf16_source", "fp32_source"])
-def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16):
+@pytest.mark.parametrize("src_bf16,ranks", [(True, "to_128"), (False, "to_128"), (True, "above_128")],
+                         ids=["bf16_source", "fp32_source", "ranks_above_128"])
+def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16, ranks):
     """Refresh that ends with the Rayleigh-Ritz step (Sec. 2: Q = the first r columns of U, largest singular
     value first).  Unique quantities are compared with the oracle: the subspace (projector), the Ritz values,
     and -- where a singular value is separated from its neighbours -- the column itself up to its sign.  For
     all columns: Q^T Src Src^T Q must be diagonal with descending entries.  Then moments and steps as usual."""
     from paper_2602_04396_amd import lordo
-    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128), (130, 257, 7), (384, 640, 127)]
+    # ranks up to 128: the solver of the Rayleigh-Ritz step runs in LDS; above: one launch per round in device memory
+    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128), (130, 257, 7), (384, 640, 127)] if ranks == "to_128" \
+        else [(520, 392, 256), (300, 400, 129), (640, 512, 200), (96, 72, 20)]
     ohp = orc.Hyper(power_iters=2, rayleigh_ritz=True)
     ghp = lordo.hparams(power_iters=2, rayleigh_ritz=True)
     pair = Pair(torch, shapes, _weights(shapes, 37), ohp, ghp, _rand_Q(shapes, 37))
@@ -429,8 +432,8 @@ def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16):
     for t in range(2, 4):
         pair.local_step([g.draw(t) for g in gens], lr=1e-3)
     pair.compare_local(TOL)
-    with pytest.raises(lordo.LordoError) as e:                  # the eigen-solver takes ranks up to 128
-        lordo.Lordo([(512, 256, 129)], ghp, [torch.zeros(512, 256, device="cuda")], torch)
+    with pytest.raises(lordo.LordoError) as e:                  # the solver takes ranks up to 1024
+        lordo.workspace_bytes([(2048, 1100, 1025)], ghp)
     assert e.value.code == lordo.EINVAL
 
 
