@@ -971,12 +971,13 @@ hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hi
 }
 
 // ---------------------------------------------------------------------------------------
-// The same one-sided Jacobi for ranks above 128 (up to 1024), where the factor does not fit into LDS: the columns of
-// L live as contiguous rows of an r x r buffer in device memory (the Gram buffer, which the factorisation has consumed),
-// one kernel launch is one round, one wave takes one pair of one matrix (both columns in registers, 16 elements per
-// lane at most), and the barrier between rounds is the kernel boundary.  Convergence is tracked on the device: a
-// rotation in sweep s sets flag[s]; the launches of sweep s + 1 return at once when flag[s] is still clear, so the
-// host enqueues a fixed number of sweeps without reading anything back.
+// The same one-sided Jacobi for ranks above 128 (up to 1024), where the factor does not fit into LDS, in blocked
+// form: the columns of L live as contiguous rows of an r x r buffer in device memory (the Gram buffer, which the
+// factorisation has consumed) and are cut into blocks of BW columns; the round-robin order runs over pairs of blocks,
+// one kernel launch is one outer round, one workgroup takes one pair of blocks of one matrix and sweeps once over all
+// pairs of its 2 BW columns in LDS.  The barrier between outer rounds is the kernel boundary.  Convergence is tracked
+// on the device: the rotations of outer sweep s are counted in flag[s]; the launches of sweep s + 1 return at once when
+// that count is below a small allowance, so the host enqueues a fixed number of sweeps without reading anything back.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_jsvd_init(DevCtx d) {
   const MatDev& m = d.mats[blockIdx.y];
@@ -989,54 +990,90 @@ __global__ __launch_bounds__(256) void k_jsvd_init(DevCtx d) {
     Xt[idx] = row >= c ? L[(int64_t)row * r + c] : 0.f;       // column c of L
   }
 }
-__global__ __launch_bounds__(256) void k_jsvd_round(DevCtx d, int round, int sweep, int* __restrict__ flags) {
-  if (sweep > 0 && flags[sweep - 1] == 0) return;             // the previous sweep rotated nothing: converged
+// One outer round: workgroup (kb, matrix) takes the pair of column blocks (bi, bj) that the round-robin order gives
+// for block-pair slot kb, brings their 2 BW columns into LDS (one column contiguous, so a pair's lanes read
+// consecutive addresses), runs one full cyclic sweep over all pairs of these columns there (2 BW - 1 rounds of BW
+// pairs, 32 lanes per pair, one barrier per round) and writes the columns back.
+// CH: 16-byte chunks per lane and column, i.e. the LDS pitch of a column is 128 CH rows for every matrix of the launch
+// (rows past a matrix's rank are zero); a compile-time count lets all loads of a pair be issued before the first wait.
+template <int BW, int CH>
+__global__ __launch_bounds__(BW * 32) void k_jsvd_block(DevCtx d, int oround, int sweep, int* __restrict__ flags, int allow) {
+  if (sweep > 0 && flags[sweep - 1] <= allow) return;         // the previous sweep rotated (next to) nothing: converged
   const MatDev& m = d.mats[blockIdx.y];
   if (m.ritz < 0) return;
   const int r = m.r;
-  const int n = (r + 1) & ~1, half = n / 2, mm = n - 1;
-  const int lane = threadIdx.x & 63;
-  const int k = blockIdx.x * 4 + (threadIdx.x >> 6);          // pair of this wave
-  if (k >= half || round >= mm) return;
-  const int a0 = (round + k) % mm, b0 = k == 0 ? mm : (round + mm - k) % mm;
-  const int pi = a0 < b0 ? a0 : b0, qi = a0 < b0 ? b0 : a0;
-  if (qi >= r) return;                                        // the added zero column of an odd rank
+  const int nb = (r + BW - 1) / BW, nbe = (nb + 1) & ~1, mmb = nbe - 1;
+  const int kb = blockIdx.x;
+  if (kb >= nbe / 2 || oround >= mmb) return;
+  int bi, bj;
+  {
+    const int a0 = (oround + kb) % mmb, b0 = kb == 0 ? mmb : (oround + mmb - kb) % mmb;
+    bi = a0 < b0 ? a0 : b0; bj = a0 < b0 ? b0 : a0;
+  }
+  if (bi >= nb) return;                                       // (bj may be the added empty block)
+  constexpr int NL = 2 * BW;                                  // local columns
+  constexpr int pitch = 128 * CH;                             // a lane takes four consecutive rows with one 16-byte access
+  extern __shared__ f32x4n jsm16[];                           // 16-byte aligned, also behind the static variable below
+  float* Xl = reinterpret_cast<float*>(jsm16);                // NL x pitch
   float* Xt = reinterpret_cast<float*>(d.arena + m.gram);
-  float* xpp = Xt + (int64_t)pi * r;
-  float* xqq = Xt + (int64_t)qi * r;
-  constexpr int EL = 16;                                      // 64 lanes x 16 = 1024 >= r
-  float xp[EL], xq[EL];
-  float a = 0.f, b = 0.f, c = 0.f;
-#pragma unroll
-  for (int j = 0; j < EL; ++j) {
-    const int e = lane + 64 * j;
-    xp[j] = e < r ? xpp[e] : 0.f;
-    xq[j] = e < r ? xqq[e] : 0.f;
+  const int tid = threadIdx.x, nt = BW * 32;
+  auto gcol = [&](int lc) { return lc < BW ? bi * BW + lc : bj * BW + (lc - BW); };
+  for (int idx = tid; idx < NL * pitch; idx += nt) {
+    const int lc = idx / pitch, row = idx - lc * pitch;
+    const int gc = gcol(lc);
+    Xl[idx] = (gc < r && row < r) ? Xt[(int64_t)gc * r + row] : 0.f;
   }
+  __syncthreads();
+  const int slot = tid >> 5, l32 = tid & 31;                  // local pair slot, lane within the pair
+  int nrot = 0;
+  // rounding of an inner product of r terms grows with sqrt(r): so does the level below which a pair counts as orthogonal
+  const float tol = 3e-7f * fmaxf(1.f, __builtin_amdgcn_sqrtf((float)r * (1.f / 128.f)));
+  __shared__ int wg_rot;
+  if (tid == 0) wg_rot = 0;
+  for (int inner = 0; inner < NL - 1; ++inner) {
+    const int a0 = (inner + slot) % (NL - 1), b0 = slot == 0 ? NL - 1 : (inner + NL - 1 - slot) % (NL - 1);
+    f32x4n* xpp = reinterpret_cast<f32x4n*>(Xl + (a0 < b0 ? a0 : b0) * pitch) + l32;
+    f32x4n* xqq = reinterpret_cast<f32x4n*>(Xl + (a0 < b0 ? b0 : a0) * pitch) + l32;
+    f32x4n xp[CH], xq[CH];
+    float a = 0.f, b = 0.f, c = 0.f;
 #pragma unroll
-  for (int j = 0; j < EL; ++j) {
-    a = fmaf(xp[j], xp[j], a);
-    b = fmaf(xq[j], xq[j], b);
-    c = fmaf(xp[j], xq[j], c);
-  }
-  // butterfly over the wave: both partners of every exchange add the same two numbers, all lanes end with the same bits
-  a = sum16(a); b = sum16(b); c = sum16(c);
-  a += __shfl_xor(a, 16); b += __shfl_xor(b, 16); c += __shfl_xor(c, 16);
-  a += __shfl_xor(a, 32); b += __shfl_xor(b, 32); c += __shfl_xor(c, 32);
-  if (!(fabsf(c) > 3e-7f * __builtin_amdgcn_sqrtf(a * b))) return;
-  const float zeta = (b - a) * 0.5f * __builtin_amdgcn_rcpf(c);
-  const float t = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
-  const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
-  const float sn = t * cs;
-#pragma unroll
-  for (int j = 0; j < EL; ++j) {
-    const int e = lane + 64 * j;
-    if (e < r) {
-      xpp[e] = cs * xp[j] - sn * xq[j];
-      xqq[e] = sn * xp[j] + cs * xq[j];
+    for (int j = 0; j < CH; ++j) {
+      xp[j] = xpp[32 * j];
+      xq[j] = xqq[32 * j];
     }
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        a = fmaf(xp[j][e], xp[j][e], a);
+        b = fmaf(xq[j][e], xq[j][e], b);
+        c = fmaf(xp[j][e], xq[j][e], c);
+      }
+    a = sum16(a); b = sum16(b); c = sum16(c);
+    a += __shfl_xor(a, 16); b += __shfl_xor(b, 16); c += __shfl_xor(c, 16);      // same bits in all 32 lanes
+    if (fabsf(c) > tol * __builtin_amdgcn_sqrtf(a * b)) {
+      const float zeta = (b - a) * 0.5f * __builtin_amdgcn_rcpf(c);
+      const float t = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+      const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
+      const float sn = t * cs;
+#pragma unroll
+      for (int j = 0; j < CH; ++j) {
+        xpp[32 * j] = cs * xp[j] - sn * xq[j];
+        xqq[32 * j] = sn * xp[j] + cs * xq[j];
+      }
+      ++nrot;
+    }
+    __syncthreads();                                          // the pairs of the next round take other columns
   }
-  if (lane == 0) flags[sweep] = 1;                            // benign race: every writer stores 1
+  for (int idx = tid; idx < NL * pitch; idx += nt) {
+    const int lc = idx / pitch, row = idx - lc * pitch;
+    const int gc = gcol(lc);
+    if (gc < r && row < r) Xt[(int64_t)gc * r + row] = Xl[idx];
+  }
+  // rotations of the sweep, counted over all matrices (integer sums: the order of the additions does not matter)
+  if (l32 == 0 && nrot) atomicAdd(&wg_rot, nrot);
+  __syncthreads();
+  if (tid == 0 && wg_rot) atomicAdd(&flags[sweep], wg_rot);
 }
 // squared column norms, order, signs, output: one workgroup per matrix (as the tail of k_jacobi_svd)
 __global__ __launch_bounds__(256) void k_jsvd_finish(DevCtx d, int top_value_only) {
@@ -1083,15 +1120,36 @@ __global__ __launch_bounds__(256) void k_jsvd_finish(DevCtx d, int top_value_onl
     if (!(li <= 3.0e38f)) *d.flag = 1;
   }
 }
-hipError_t launch_jacobi_rounds(const DevCtx& d, int rmax, bool top_value_only, int* flags, hipStream_t s) {
+template <int BW, int CH>
+static hipError_t jsvd_block_sweeps(const DevCtx& d, int rmax, int* flags, int sweeps, int allow, hipStream_t s) {
+  constexpr size_t lds = sizeof(float) * 2 * BW * 128 * CH;
+  static_assert(lds <= 147456, "two blocks of columns must fit into LDS");
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_jsvd_block<BW, CH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (rmax > 128 * CH) return hipErrorInvalidValue;
+  const int nb = (rmax + BW - 1) / BW, nbe = (nb + 1) & ~1;
+  for (int sweep = 0; sweep < sweeps; ++sweep)
+    for (int oround = 0; oround < nbe - 1; ++oround)
+      hipLaunchKernelGGL((k_jsvd_block<BW, CH>), dim3(nbe / 2, d.n), dim3(BW * 32), lds, s, d, oround, sweep, flags, allow);
+  return hipGetLastError();
+}
+hipError_t launch_jacobi_rounds(const DevCtx& d, int rmax, int64_t rank_sq_sum, bool top_value_only, int* flags, hipStream_t s) {
   if (rmax > 1024) return hipErrorInvalidValue;
-  constexpr int SWEEPS = 16;                                  // flags holds SWEEPS ints
-  hipLaunchKernelGGL(k_fill_zero_i32, dim3(1), dim3(64), 0, s, flags, SWEEPS);
+  constexpr int SWEEPS = 14;                                  // flags holds 16 ints
+  hipLaunchKernelGGL(k_fill_zero_i32, dim3(1), dim3(64), 0, s, flags, 16);
   hipLaunchKernelGGL(k_jsvd_init, dim3(64, d.n), dim3(256), 0, s, d);
-  const int n = (rmax + 1) & ~1, half = n / 2;
-  for (int sweep = 0; sweep < SWEEPS; ++sweep)
-    for (int round = 0; round < n - 1; ++round)
-      hipLaunchKernelGGL(k_jsvd_round, dim3((half + 3) / 4, d.n), dim3(256), 0, s, d, round, sweep, flags);
+  // two blocks of columns must fit into LDS: 32 columns each up to rank 512, 16 beyond; column pitch 256, 512 or 1024 rows
+  // a sweep visits about r^2 / 2 pairs per matrix (more: pairs inside a block come up again with every partner block);
+  // it counts as converged when fewer than one in 8192 of them still rotates (by angles of the size of the rounding)
+  const int allow = (int)std::min<int64_t>(rank_sq_sum >> 14, 1 << 30);
+  hipError_t e = rmax <= 256 ? jsvd_block_sweeps<32, 2>(d, rmax, flags, SWEEPS, allow, s)
+               : rmax <= 512 ? jsvd_block_sweeps<32, 4>(d, rmax, flags, SWEEPS, allow, s)
+                             : jsvd_block_sweeps<16, 8>(d, rmax, flags, SWEEPS, allow, s);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_jsvd_finish, dim3(d.n), dim3(256), 0, s, d, top_value_only ? 1 : 0);
   return hipGetLastError();
 }

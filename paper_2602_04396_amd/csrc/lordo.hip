@@ -48,6 +48,7 @@ struct Plan {
   int mb = 4;
   int up_waves = 4;                 // waves per workgroup of the up-projection (4: 64 x 64 wave tiles, 8: 32 x 64)
   int r_max = 0;                    // largest rank of any matrix
+  int64_t rank_sq_sum = 0;          // sum of r^2 over the matrices
   int64_t frob_part = -1;           // per-chunk partial sums of ||Src||_F^2 (Rayleigh-Ritz option)
   int64_t jflags = -1;              // per-sweep "something rotated" flags of the multi-launch Jacobi solver
   int down_pipe = 0;                // pipelined down-projection: rank blocks per wave (1: 128-rank tiles, 2: 256-rank), 0: plain kernel
@@ -535,6 +536,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.pp = (int)pad32(m.p); m.qp = (int)pad32(m.q); m.rp = (int)pad32(m.r);
     rp_max = std::max(rp_max, m.rp);
     P.r_max = std::max(P.r_max, (int)m.r);
+    P.rank_sq_sum += (int64_t)m.r * m.r;
     pp_min = std::min(pp_min, m.pp);
     P.chunk_start_h[i] = chunks;
     chunks += ((int64_t)m.p * m.q + CHUNK - 1) / CHUNK;
@@ -1004,7 +1006,7 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
       case OP_EIGH:
         if (P.r_max <= 128) HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, op.iarg != 0, s));
-        else HIPCHK(launch_jacobi_rounds(c->dev, P.r_max, op.iarg != 0, c->at<int>(P.jflags), s));
+        else HIPCHK(launch_jacobi_rounds(c->dev, P.r_max, P.rank_sq_sum, op.iarg != 0, c->at<int>(P.jflags), s));
         break;
       case OP_FROB:
         HIPCHK(launch_frob2(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, c->at<float>(P.frob_part), src_dtype == LORDO_F32, s));

@@ -347,17 +347,20 @@ def test_local_variant_refresh_from_gradient_plus_residual(torch, bf16):
     assert e.value.code == lordo.ESTATE
 
 
-@pytest.mark.parametrize("src_bf16,ranks", [(True, "to_128"), (False, "to_128"), (True, "above_128")],
-                         ids=["bf16_source", "fp32_source", "ranks_above_128"])
+@pytest.mark.parametrize("src_bf16,ranks", [(True, "to_128"), (False, "to_128"), (True, "to_256"), (True, "to_512"), (True, "to_1024")],
+                         ids=["bf16_source", "fp32_source", "ranks_to_256", "ranks_to_512", "ranks_to_1024"])
 def test_refresh_with_rayleigh_ritz_orders_the_basis(torch, src_bf16, ranks):
     """Refresh that ends with the Rayleigh-Ritz step (Sec. 2: Q = the first r columns of U, largest singular
     value first).  Unique quantities are compared with the oracle: the subspace (projector), the Ritz values,
     and -- where a singular value is separated from its neighbours -- the column itself up to its sign.  For
     all columns: Q^T Src Src^T Q must be diagonal with descending entries.  Then moments and steps as usual."""
     from paper_2602_04396_amd import lordo
-    # ranks up to 128: the solver of the Rayleigh-Ritz step runs in LDS; above: one launch per round in device memory
-    shapes = [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128), (130, 257, 7), (384, 640, 127)] if ranks == "to_128" \
-        else [(520, 392, 256), (300, 400, 129), (640, 512, 200), (96, 72, 20)]
+    # ranks up to 128: the solver of the Rayleigh-Ritz step runs in LDS in one launch; above: the blocked form, whose
+    # three instantiations cover ranks up to 256, 512 and 1024
+    shapes = {"to_128": [(200, 328, 48), (96, 72, 20), (300, 136, 33), (256, 192, 128), (130, 257, 7), (384, 640, 127)],
+              "to_256": [(520, 392, 256), (300, 400, 129), (640, 512, 200), (96, 72, 20)],
+              "to_512": [(700, 616, 300), (96, 72, 20), (900, 520, 257)],
+              "to_1024": [(1200, 808, 600), (300, 136, 33)]}[ranks]
     ohp = orc.Hyper(power_iters=2, rayleigh_ritz=True)
     ghp = lordo.hparams(power_iters=2, rayleigh_ritz=True)
     pair = Pair(torch, shapes, _weights(shapes, 37), ohp, ghp, _rand_Q(shapes, 37))
