@@ -798,13 +798,16 @@ hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
 // singular value first): eigenvectors of the r x r matrix T = (Q^T Src)(Q^T Src)^T, r <= 128, from its Cholesky
 // factor: T + shift I = L L^T (the factorisation of the orthonormalisation, with its diagonal shift), and the left
 // singular vectors of L are the eigenvectors of T, its singular values s_i give the eigenvalues s_i^2 - shift.
-// One-sided Jacobi on the columns of X = L (one workgroup per matrix, X alone in LDS, odd row pitch): a plane
-// rotation of columns p, q makes them orthogonal; a sweep is n-1 rounds of n/2 disjoint pairs in round-robin
-// order (n = r rounded up to even; the added column is zero and never rotated); at convergence X = U diag(s).
-// Sixteen lanes share a pair: each keeps eight rows of both columns in registers, the three inner products are
-// summed over the sixteen lanes by a butterfly of lane exchanges (both partners of an exchange add the same two
-// numbers, so all lanes hold the same bits and take the same decision), the columns are rotated in registers and written back:
-// one read and one write of X per round, one barrier per round.  A pair is left alone when
+// One-sided Jacobi on the columns of X = L, one workgroup per matrix: a plane rotation of two columns makes them
+// orthogonal; at convergence X = U diag(s).  The columns stay in registers for the whole iteration: a group of
+// sixteen lanes holds the two columns at positions 2k and 2k + 1 (eight rows of each per lane; n = r rounded up to
+// even, the added column is zero and never rotated).  The pairs follow the odd-even transposition order: even steps
+// pair positions (2k, 2k + 1) inside a group, odd steps pair (2k + 1, 2k + 2) -- the left column of the next group
+// comes over through LDS and the rotated right column goes back -- and every step ends with the two columns of a
+// pair changing places, so that in n steps every column has met every other exactly once (one sweep).  Half the
+// steps touch no LDS and need no barrier; the other half move one column per group each way.  The three inner
+// products of a pair are summed over its sixteen lanes by a butterfly of lane exchanges (both partners of an exchange
+// add the same two numbers, so all lanes hold the same bits and take the same decision).  A pair is left alone when
 // |x_p . x_q| <= 3e-7 |x_p| |x_q|; the iteration ends with the first sweep that rotates nothing (at most 20).
 // Working on the factor instead of T keeps the small singular values accurate relative to themselves (the
 // factor has the square root of T's condition number).
@@ -833,6 +836,36 @@ __device__ __forceinline__ float sum16(float v) {
   return v;
 }
 
+// Rotation of two columns held in registers (eight rows per lane, sixteen lanes): returns the columns swapped, as the
+// odd-even order wants them (p <- rotated q, q <- rotated p), and whether a rotation was applied.
+__device__ __forceinline__ bool rotate_swap(float (&p)[8], float (&q)[8]) {
+  float a = 0.f, b = 0.f, c = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a = fmaf(p[j], p[j], a);
+    b = fmaf(q[j], q[j], b);
+    c = fmaf(p[j], q[j], c);
+  }
+  a = sum16(a);
+  b = sum16(b);
+  c = sum16(c);
+  float cs = 1.f, sn = 0.f;
+  const bool rot = fabsf(c) > 3e-7f * __builtin_amdgcn_sqrtf(a * b);            // the same in all sixteen lanes
+  if (rot) {
+    const float zeta = (b - a) * 0.5f * __builtin_amdgcn_rcpf(c);
+    const float t = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+    cs = __builtin_amdgcn_rsqf(1.f + t * t);
+    sn = t * cs;
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float pn = cs * p[j] - sn * q[j], qn = sn * p[j] + cs * q[j];      // cs = 1, sn = 0 leave both as they are
+    p[j] = qn;
+    q[j] = pn;
+  }
+  return rot;
+}
+
 __global__ __launch_bounds__(1024) void k_jacobi_svd(DevCtx d, int top_value_only) {
   const MatDev m = d.mats[blockIdx.x];
   const int r = m.r;
@@ -840,120 +873,118 @@ __global__ __launch_bounds__(1024) void k_jacobi_svd(DevCtx d, int top_value_onl
   const int n = (r + 1) & ~1;
   const int ld = n + 1;
   const int half = n / 2;
-  const int mm = n - 1;                   // players 0 .. mm-1 rotate, player mm stays
   extern __shared__ float jsm[];
-  float* X = jsm;                         // n x ld
+  float* X = jsm;                         // n x ld: the columns at the end, for the ordering and the output
   float* nrm2 = X + n * ld;               // n
-  unsigned short* sched = reinterpret_cast<unsigned short*>(nrm2 + n);    // mm x half pairs, p | q << 8
+  float* ex = nrm2 + n;                   // half x EXLD: the column that crosses to the neighbouring group
+  constexpr int EXLD = 129;               // all 128 register rows of a column are exchanged, whatever n is
   __shared__ int rotated;
   const int tid = threadIdx.x, nt = blockDim.x;
   const float* L = reinterpret_cast<const float*>(d.arena + m.lfac);
   float* rz = reinterpret_cast<float*>(d.arena + m.ritz);
 
-  for (int idx = tid; idx < n * n; idx += nt) {
-    const int i = idx / n, j = idx - i * n;
-    X[i * ld + j] = (i < r && j <= i) ? L[(int64_t)i * r + j] : 0.f;
-  }
-  // pairs of every round (circle method): pair 0 of round t is (t, mm), pair k > 0 is ((t + k) % mm, (t + mm - k) % mm)
-  for (int idx = tid; idx < mm * half; idx += nt) {
-    const int round = idx / half, k = idx - round * half;
-    const int a = (round + k) % mm, b = k == 0 ? mm : (round + mm - k) % mm;
-    sched[idx] = (unsigned short)((a < b ? a : b) | ((a < b ? b : a) << 8));
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int k = wave * 4 + (lane >> 4);              // this group of sixteen lanes holds positions 2k and 2k + 1
+  const int gl = lane & 15;
+  const bool act = k < half;
+  constexpr int ROWS = 8;                            // 16 lanes x 8 rows = 128 >= n
+  float pl[ROWS], pr[ROWS];                          // the columns at positions 2k (left) and 2k + 1 (right)
+#pragma unroll
+  for (int j = 0; j < ROWS; ++j) {
+    const int row = gl + 16 * j, c0 = 2 * k, c1 = 2 * k + 1;
+    pl[j] = (act && row < r && c0 <= row) ? L[(int64_t)row * r + c0] : 0.f;      // lower triangle; c0 <= row < r
+    pr[j] = (act && row < r && c1 <= row) ? L[(int64_t)row * r + c1] : 0.f;
   }
   if (tid == 0) rotated = 0;
   __syncthreads();
 
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int slot = wave * 4 + (lane >> 4);           // pair handled by this group of sixteen lanes
-  const int slots = (nt >> 6) * 4;
-  const int gl = lane & 15;
-  constexpr int ROWS = 8;                            // 16 lanes x 8 rows = 128 >= n
-
   for (int sweep = 0; sweep < 20; ++sweep) {
-    for (int round = 0; round < mm; ++round) {
-      for (int k = slot; k < half; k += slots) {
-        const int pr = sched[round * half + k];
-        const int pi = pr & 255, qi = pr >> 8;
-        float xp[ROWS], xq[ROWS];
-        float a = 0.f, b = 0.f, c = 0.f;
+    for (int step = 0; step < n; ++step) {
+      if ((step & 1) == 0) {
+        // positions (2k, 2k + 1): both columns are here
+        if (act && rotate_swap(pl, pr) && gl == 0) rotated = 1;                  // benign race: every writer stores 1
+      } else {
+        // positions (2k + 1, 2k + 2): the left column of the next group comes over, the rotated right column goes back
+        if (act && k >= 1) {
 #pragma unroll
-        for (int j = 0; j < ROWS; ++j) {
-          const int row = gl + 16 * j;
-          xp[j] = row < n ? X[row * ld + pi] : 0.f;
-          xq[j] = row < n ? X[row * ld + qi] : 0.f;
+          for (int j = 0; j < ROWS; ++j) ex[k * EXLD + gl + 16 * j] = pl[j];
         }
+        __syncthreads();
+        if (act && k + 1 < half) {
+          float t[ROWS];
 #pragma unroll
-        for (int j = 0; j < ROWS; ++j) {
-          a = fmaf(xp[j], xp[j], a);
-          b = fmaf(xq[j], xq[j], b);
-          c = fmaf(xp[j], xq[j], c);
+          for (int j = 0; j < ROWS; ++j) t[j] = ex[(k + 1) * EXLD + gl + 16 * j];
+          if (rotate_swap(pr, t) && gl == 0) rotated = 1;
+#pragma unroll
+          for (int j = 0; j < ROWS; ++j) ex[(k + 1) * EXLD + gl + 16 * j] = t[j];
         }
-        a = sum16(a);
-        b = sum16(b);
-        c = sum16(c);
-        if (fabsf(c) > 3e-7f * __builtin_amdgcn_sqrtf(a * b)) {        // the same in all sixteen lanes
-          const float zeta = (b - a) * 0.5f * __builtin_amdgcn_rcpf(c);
-          const float t = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
-          const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
-          const float sn = t * cs;
+        __syncthreads();
+        if (act && k >= 1) {
 #pragma unroll
-          for (int j = 0; j < ROWS; ++j) {
-            const int row = gl + 16 * j;
-            if (row < n) {
-              X[row * ld + pi] = cs * xp[j] - sn * xq[j];
-              X[row * ld + qi] = sn * xp[j] + cs * xq[j];
-            }
-          }
-          if (gl == 0) rotated = 1;                  // benign race: every writer stores 1
+          for (int j = 0; j < ROWS; ++j) pl[j] = ex[k * EXLD + gl + 16 * j];
         }
       }
-      __syncthreads();                               // the pairs of the next round take other columns
     }
-    const int any = rotated;                         // all rounds of the sweep are behind a barrier
+    __syncthreads();                                 // n is even: the last step of a sweep ends with a barrier anyway
+    const int any = rotated;
     __syncthreads();
     if (tid == 0) rotated = 0;
     __syncthreads();
     if (!any) break;
   }
+  if (act) {
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+      const int row = gl + 16 * j;
+      if (row < n) {
+        X[row * ld + 2 * k] = pl[j];
+        X[row * ld + 2 * k + 1] = pr[j];
+      }
+    }
+  }
+  __syncthreads();
 
-  // squared column norms = squared singular values
+  // squared column norms = squared singular values; the columns have travelled, the zero column added for an odd rank
+  // is wherever it ended up and has norm zero (the shift keeps every other norm positive)
   for (int i = tid; i < n; i += nt) {
     float acc = 0.f;
     for (int row = 0; row < n; ++row) acc = fmaf(X[row * ld + i], X[row * ld + i], acc);
-    nrm2[i] = i < r ? acc : -1.f;
+    nrm2[i] = acc;
   }
   __syncthreads();
   const float shift = rz[r + 2];
   if (top_value_only) {
     if (tid == 0) {
       float mx = 0.f;
-      for (int i = 0; i < r; ++i) mx = fmaxf(mx, nrm2[i]);
+      for (int i = 0; i < n; ++i) mx = fmaxf(mx, nrm2[i]);
       rz[r + 1] = sqrtf(fmaxf(mx - shift, 0.f));
       if (!(mx <= 3.0e38f)) *d.flag = 1;
     }
     return;
   }
-  // descending order (ties by index); one thread per singular vector writes its column
-  for (int i = tid; i < r; i += nt) {
+  // descending order (ties by position); one thread per singular vector writes its column
+  for (int i = tid; i < n; i += nt) {
     const float li = nrm2[i];
+    if (!(li <= 3.0e38f)) *d.flag = 1;               // NaN or infinity in the factor
+    if (!(li > 0.f)) continue;                       // the added zero column
     int rank = 0;
-    for (int j = 0; j < r; ++j) rank += (nrm2[j] > li || (nrm2[j] == li && j < i)) ? 1 : 0;
+    for (int j = 0; j < n; ++j) rank += (nrm2[j] > li || (nrm2[j] == li && j < i)) ? 1 : 0;
+    if (rank >= r) continue;
     float best = 0.f, bestv = 1.f;
     for (int row = 0; row < r; ++row) {
       const float v = X[row * ld + i];
       if (fabsf(v) > best) { best = fabsf(v); bestv = v; }
     }
-    const float scale = (bestv < 0.f ? -1.f : 1.f) * (li > 0.f ? 1.f / sqrtf(li) : 0.f);
+    const float scale = (bestv < 0.f ? -1.f : 1.f) / sqrtf(li);
     float* U = reinterpret_cast<float*>(d.arena + m.rot);
     for (int row = 0; row < r; ++row) U[(int64_t)row * r + rank] = scale * X[row * ld + i];
     rz[rank] = sqrtf(fmaxf(li - shift, 0.f));
-    if (!(li <= 3.0e38f)) *d.flag = 1;               // NaN or infinity in the factor
   }
 }
 size_t jacobi_lds_bytes(int rmax) {
   const int n = (rmax + 1) & ~1;
-  return sizeof(float) * ((size_t)n * (n + 1) + n) + sizeof(unsigned short) * (size_t)(n - 1) * (n / 2);
+  return sizeof(float) * ((size_t)n * (n + 1) + n + (size_t)(n / 2) * 129);
 }
 hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s) {
   if (rmax > 128) return hipErrorInvalidValue;
