@@ -723,3 +723,41 @@ def test_state_roundtrip_and_errors(torch):
         opt.get_state(0, lordo.STATE_ERR)
     assert e.value.code == lordo.ESTATE
     opt.poll_status()
+
+
+@pytest.mark.parametrize("rayleigh_ritz,top_rank", [(False, 128), (True, 128), (True, 200)],
+                         ids=["plain_refresh", "rayleigh_ritz", "rayleigh_ritz_blocked_solver"])
+def test_two_contexts_with_the_same_inputs_agree_bit_for_bit(torch, rayleigh_ritz, top_rank):
+    """Workers that see the same averaged source recompute the same projection instead of receiving it (Alg. 1): that
+    needs run-to-run identical results.  Two contexts, identical inputs, steps (split-K down-projection), a refresh
+    (grouped GEMMs with split-K, factorisations, with or without the Rayleigh-Ritz solver), more steps and an outer
+    step: every state tensor must agree bit for bit."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(520, 392, top_rank), (300, 640, 64), (200, 328, 48), (1024, 256, 100)]
+    kw = dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=2, rayleigh_ritz=rayleigh_ritz)
+    gens = _spiked(shapes, 39, 6)
+    W0 = _weights(shapes, 39)
+    Om = [torch.tensor(synth.omega(np.random.default_rng(synth.seed_for(39, 900 + i)), q, r), device="cuda")
+          for i, (p, q, r) in enumerate(shapes)]
+    G = [[torch.tensor(g.draw(t), device="cuda").bfloat16() for g in gens] for t in range(5)]
+    runs = []
+    for _ in range(2):
+        W = [torch.tensor(w, dtype=torch.float32, device="cuda") for w in W0]
+        opt = lordo.Lordo(shapes, lordo.hparams(**kw), W, torch)
+        opt.local_step(W, G[0], 1e-3)
+        opt.local_step(W, G[1], 2e-3)
+        opt.refresh_subspace(G[2], Om)
+        opt.local_step(W, G[3], 1e-3)
+        opt.outer_step(W, None)
+        opt.local_step(W, G[4], 1e-3)
+        opt.poll_status()
+        runs.append((W, opt))
+    (Wa, a), (Wb, b) = runs
+    for i in range(len(shapes)):
+        assert torch.equal(Wa[i], Wb[i]), f"W of matrix {i}"
+        for which in (lordo.STATE_Q, lordo.STATE_U, lordo.STATE_V, lordo.STATE_ANCHOR, lordo.STATE_MOM, lordo.STATE_NUPD):
+            assert torch.equal(a.get_state(i, which), b.get_state(i, which)), f"state {which} of matrix {i}"
+    assert torch.equal(a.mssv(), b.mssv())
+    if rayleigh_ritz:
+        assert torch.equal(a.stable_rank(), b.stable_rank())
+        assert torch.equal(a.spectral_gap(G[2], Om), b.spectral_gap(G[2], Om))
