@@ -674,7 +674,7 @@ __device__ __forceinline__ float lane_value(float x, int lane) {      // value o
 // steps of the factorisation and of the inversion need no barrier and no LDS round trip: a column
 // is broadcast lane by lane through scalar registers (v_readlane) and applied with one FMA per
 // element.  Everything is unrolled, every register index is a constant.
-__global__ __launch_bounds__(64) void k_potf2(DevCtx d, int jb) {
+__global__ __launch_bounds__(256) void k_potf2(DevCtx d, int jb) {
   const MatDev& m = d.mats[blockIdx.x];
   const int o = jb * NB;
   int nbk = m.r - o;
@@ -683,92 +683,96 @@ __global__ __launch_bounds__(64) void k_potf2(DevCtx d, int jb) {
   const float* S = reinterpret_cast<const float*>(d.arena + m.gram);
   float* L = reinterpret_cast<float*>(d.arena + m.lfac);
   float* X = reinterpret_cast<float*>(d.arena + m.dinv) + (int64_t)jb * NB * NB;
+  static_assert(NB == 64, "four waves of sixteen columns each");
   __shared__ float tile[NB][NB + 1];
-  const int lane = threadIdx.x;
+  __shared__ __align__(16) float lrow[NB][NB];       // the factor, rows 16-byte aligned: operand of the inversion
+  __shared__ __align__(16) float ccol[2][NB];        // column k of the factor with entries <= k zeroed (multipliers of step k)
+  __shared__ float crow[2][NB];                      // column k of the factor (every row's own factor)
+  __shared__ float red[4];
+  __shared__ int bad_s;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   // rows are read coalesced and handed to their lanes through LDS; identity outside the block
-  for (int rr = 0; rr < NB; ++rr) {
+  for (int rr = w; rr < NB; rr += 4) {
     float val;
     if (rr < nbk && lane < nbk) val = lane <= rr ? S[(int64_t)(o + rr) * m.r + (o + lane)] : 0.f;
     else val = rr == lane ? 1.f : 0.f;
     tile[rr][lane] = val;
   }
+  if (tid == 0) bad_s = 0;
   __syncthreads();
-  float a[NB];
+  // lane = row, wave w holds columns 16 w .. 16 w + 15 of it
+  float a[16];
 #pragma unroll
-  for (int j = 0; j < NB; ++j) a[j] = tile[lane][j];
+  for (int jc = 0; jc < 16; ++jc) a[jc] = tile[lane][16 * w + jc];
   float dmax = lane < nbk ? tile[lane][lane] : 0.f;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) dmax = fmaxf(dmax, __shfl_xor(dmax, off));
   const float floor_piv = 1e-12f * dmax + 1e-37f;
-  bool bad = false;
-  // right-looking Cholesky: after step k register k holds column k of L
+  // right-looking Cholesky, one barrier per column: the wave that holds column k scales it and leaves it in LDS (two
+  // buffers alternate, so the next column can be written while this one is still being read); every wave then updates
+  // its sixteen columns, a[j] -= L[i][k] L[j][k], with the multipliers L[j][k] read as broadcasts (zero for j <= k, which
+  // leaves the finished columns alone)
 #pragma clang loop unroll(full)
   for (int k = 0; k < NB; ++k) {
-    // an opaque copy of the lane index per step: otherwise all 64 lane masks are computed up front
-    // and, with those of the inversion, crowd the scalar registers out
-    int ln = lane;
-    asm volatile("" : "+v"(ln));
-    float piv = lane_value(a[k], k);
-    if (!(piv > floor_piv)) {
-      bad = true;
-      piv = floor_piv;
+    const int buf = k & 1;
+    if (w == k / 16) {
+      float piv = lane_value(a[k % 16], k);
+      if (!(piv > floor_piv)) {
+        if (lane == 0) bad_s = 1;
+        piv = floor_piv;
+      }
+      const float dd = sqrtf(piv);
+      const float lk = lane == k ? dd : (lane > k ? a[k % 16] / dd : 0.f);
+      a[k % 16] = lk;
+      crow[buf][lane] = lk;
+      ccol[buf][lane] = lane > k ? lk : 0.f;
     }
-    const float dd = sqrtf(piv);
-    const float lk = ln == k ? dd : (ln > k ? a[k] / dd : 0.f);
-    a[k] = lk;
-    // L[i][j] -= L[i][k] L[j][k] in groups of eight columns; the empty asm pins a group's FMAs
-    // right after its broadcasts (otherwise the compiler issues all broadcasts of a step first and
-    // runs out of scalar registers), while the eight pairs inside a group overlap
-#pragma clang loop unroll(full)
-    for (int jc = 0; jc < NB / 8; ++jc) {
-      if (8 * jc + 7 > k) {
-#pragma clang loop unroll(full)
-        for (int e = 0; e < 8; ++e) {
-          const int j = 8 * jc + e;
-          if (j > k) a[j] = fmaf(-lk, lane_value(lk, j), a[j]);
-        }
-        asm volatile("" : "+v"(a[8 * jc]), "+v"(a[8 * jc + 1]), "+v"(a[8 * jc + 2]), "+v"(a[8 * jc + 3]),
-                          "+v"(a[8 * jc + 4]), "+v"(a[8 * jc + 5]), "+v"(a[8 * jc + 6]), "+v"(a[8 * jc + 7]));
+    __syncthreads();
+    if (16 * w + 15 > k) {                           // this wave still has columns to the right of k
+      const float mine = crow[buf][lane];
+      const f32x4n* cp = reinterpret_cast<const f32x4n*>(&ccol[buf][16 * w]);
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const f32x4n cv = cp[g4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) a[4 * g4 + e] = fmaf(-mine, cv[e], a[4 * g4 + e]);
       }
     }
   }
-  // X = L^{-1} by forward substitution: lane j builds column j, x[i] = X[i][j]
-  float x[NB];
+  // the factor to LDS (zeros above the diagonal): for the inversion and for the coalesced store
+#pragma unroll
+  for (int jc = 0; jc < 16; ++jc) {
+    const int j = 16 * w + jc;
+    const float v = j <= lane ? a[jc] : 0.f;
+    lrow[lane][j] = v;
+    tile[lane][j] = v;
+  }
+  __syncthreads();
+  if (w == 0) {
+    // X = L^{-1} by forward substitution: lane j builds column j, x[i] = X[i][j]; row i of L is read as broadcasts
+    float x[NB];
 #pragma clang loop unroll(full)
-  for (int i = 0; i < NB; ++i) {
-    int ln = lane;
-    asm volatile("" : "+v"(ln));
-    // four partial sums: the FMA chain of a row is split so that consecutive pairs overlap
-    float acc[4] = {ln == i ? 1.f : 0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < NB; ++i) {
+      // four partial sums: the FMA chain of a row is split so that consecutive terms overlap
+      float acc[4] = {lane == i ? 1.f : 0.f, 0.f, 0.f, 0.f};
+      const f32x4n* lp = reinterpret_cast<const f32x4n*>(&lrow[i][0]);
 #pragma clang loop unroll(full)
-    for (int mc = 0; mc < NB / 8; ++mc) {
-      if (8 * mc < i) {
+      for (int g4 = 0; g4 < NB / 4; ++g4) {
+        if (4 * g4 < i) {
+          const f32x4n lv = lp[g4];
 #pragma clang loop unroll(full)
-        for (int e = 0; e < 8; ++e) {
-          const int mm = 8 * mc + e;
-          if (mm < i) acc[e & 3] = fmaf(-lane_value(a[mm], i), x[mm], acc[e & 3]);    // L[i][mm] is register mm of lane i
+          for (int e = 0; e < 4; ++e)
+            if (4 * g4 + e < i) acc[e] = fmaf(-lv[e], x[4 * g4 + e], acc[e]);
         }
-        asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
       }
+      x[i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / lrow[i][i];
     }
-    x[i] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / lane_value(a[i], i);
-  }
-  if (bad && lane == 0) *d.flag = 1;
 #pragma unroll
-  for (int i = 0; i < NB; ++i) {
-    int ln = lane;
-    asm volatile("" : "+v"(ln));
-    X[i * NB + lane] = ln <= i ? x[i] : 0.f;
+    for (int i = 0; i < NB; ++i) X[i * NB + lane] = lane <= i ? x[i] : 0.f;
   }
-  __syncthreads();
-#pragma unroll
-  for (int j = 0; j < NB; ++j) {
-    int ln = lane;
-    asm volatile("" : "+v"(ln));
-    tile[lane][j] = j <= ln ? a[j] : 0.f;
-  }
-  __syncthreads();
-  for (int rr = 0; rr < nbk; ++rr)
+  if (tid == 0 && bad_s) *d.flag = 1;
+  for (int rr = w; rr < nbk; rr += 4)
     if (lane < nbk) L[(int64_t)(o + rr) * m.r + (o + lane)] = tile[rr][lane];
 }
 // The inverses of the diagonal blocks, copied to their places on the diagonal of the r x r inverse of the
@@ -789,7 +793,7 @@ hipError_t launch_diag_inverses(const DevCtx& d, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s) {
-  hipLaunchKernelGGL(k_potf2, dim3(d.n), dim3(64), 0, s, d, jb);
+  hipLaunchKernelGGL(k_potf2, dim3(d.n), dim3(256), 0, s, d, jb);
   return hipGetLastError();
 }
 
