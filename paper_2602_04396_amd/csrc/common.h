@@ -171,8 +171,8 @@ hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
 hipError_t launch_frob2(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float* partial, bool src_f32, hipStream_t s);
 hipError_t launch_stable_rank(const DevCtx& d, float* out, int which, hipStream_t s);
-hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s);
-hipError_t launch_jacobi_rounds(const DevCtx& d, int rmax, int64_t rank_sq_sum, bool top_value_only, int* flags, hipStream_t s);
+hipError_t launch_jacobi_svd(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s);
+hipError_t launch_jacobi_svd_blocked(const DevCtx& d, int rmax, int64_t rank_sq_sum, bool top_value_only, int* flags, hipStream_t s);
 hipError_t launch_diag_inverses(const DevCtx& d, hipStream_t s);
 hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
 hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);

@@ -990,7 +990,7 @@ size_t jacobi_lds_bytes(int rmax) {
   const int n = (rmax + 1) & ~1;
   return sizeof(float) * ((size_t)n * (n + 1) + n + (size_t)(n / 2) * 129);
 }
-hipError_t launch_jacobi_eigh(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s) {
+hipError_t launch_jacobi_svd(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s) {
   if (rmax > 128) return hipErrorInvalidValue;
   const size_t lds = jacobi_lds_bytes(rmax);
   static bool attr_set = false;
@@ -1172,7 +1172,7 @@ static hipError_t jsvd_block_sweeps(const DevCtx& d, int rmax, int* flags, int s
       hipLaunchKernelGGL((k_jsvd_block<BW, CH>), dim3(nbe / 2, d.n), dim3(BW * 32), lds, s, d, oround, sweep, flags, allow);
   return hipGetLastError();
 }
-hipError_t launch_jacobi_rounds(const DevCtx& d, int rmax, int64_t rank_sq_sum, bool top_value_only, int* flags, hipStream_t s) {
+hipError_t launch_jacobi_svd_blocked(const DevCtx& d, int rmax, int64_t rank_sq_sum, bool top_value_only, int* flags, hipStream_t s) {
   if (rmax > 1024) return hipErrorInvalidValue;
   constexpr int SWEEPS = 14;                                  // flags holds 16 ints
   hipLaunchKernelGGL(k_fill_zero_i32, dim3(1), dim3(64), 0, s, flags, 16);

@@ -25,7 +25,7 @@ namespace {
     }                                                                                             \
   } while (0)
 
-enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT, OP_EIGH, OP_FROB };
+enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT, OP_JSVD, OP_FROB };
 
 struct Op {
   int kind;
@@ -382,7 +382,7 @@ struct ProgramBuilder {
     }, false, true, true);
     simple(OP_SHIFT, 1, 32.f * 5.9604645e-8f);
     factor(max_blocks_all());
-    simple(OP_EIGH, 1);                 // largest singular value only
+    simple(OP_JSVD, 1);                 // largest singular value only
     simple(OP_PACK);                    // the Z products borrowed the operand planes of Q
     P.gap_ops.swap(P.ops);
     P.ops.swap(saved);
@@ -456,7 +456,7 @@ struct ProgramBuilder {
       factor(max_blocks_all());
       // left singular vectors, by descending singular value, into the buffer the rotation matrix R takes later
       // (not the buffer of the factor's inverse: its upper triangle has to stay zero)
-      simple(OP_EIGH);
+      simple(OP_JSVD);
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
         g.A = ref_arena(m.y[ycur]); g.sAm = m.r; g.sAk = 1;
@@ -1004,9 +1004,9 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, op.iarg != 0, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
-      case OP_EIGH:
-        if (P.r_max <= 128) HIPCHK(launch_jacobi_eigh(c->dev, P.r_max, op.iarg != 0, s));
-        else HIPCHK(launch_jacobi_rounds(c->dev, P.r_max, P.rank_sq_sum, op.iarg != 0, c->at<int>(P.jflags), s));
+      case OP_JSVD:
+        if (P.r_max <= 128) HIPCHK(launch_jacobi_svd(c->dev, P.r_max, op.iarg != 0, s));
+        else HIPCHK(launch_jacobi_svd_blocked(c->dev, P.r_max, P.rank_sq_sum, op.iarg != 0, c->at<int>(P.jflags), s));
         break;
       case OP_FROB:
         HIPCHK(launch_frob2(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, c->at<float>(P.frob_part), src_dtype == LORDO_F32, s));
