@@ -82,7 +82,13 @@ typedef struct {
   double  outer_lr;              /* eta_s; 1.0 with outer_momentum 0 is plain averaging (Alg. 1)        */
   double  outer_momentum;        /* mu; 0 keeps no momentum buffer                                      */
   int32_t power_iters;           /* block power iterations of the range finder, 0..8                    */
-  int32_t orth_passes;           /* CholeskyQR passes per orthonormalisation: 2 (default if 0) or 3     */
+  int32_t orth_passes;           /* orthonormalisation of the refresh: 2 (default if 0): one shifted CholeskyQR pass after
+                                    every product of the power iteration, shifted + plain at the end -- for sources whose
+                                    r leading singular values span less than about three orders of magnitude;
+                                    3: the robust variant, shifted + shifted after every product and shifted, shifted,
+                                    plain at the end (conditioning up to about 1e6; about 1.5 times the refresh time).
+                                    Beyond these limits, and for a source of rank below r, a non-positive pivot is
+                                    latched (LORDO_ENUMERIC) */
   int32_t grad_dtype;            /* LORDO_BF16 or LORDO_F32: element type of every G                    */
   int32_t uplink_buffer;         /* 1: keep the r x q up-link buffer A = sum over the window of eta_t N_t (App. A.5.1);
                                     not with qhm_mode 2, whose update has no low-rank form              */

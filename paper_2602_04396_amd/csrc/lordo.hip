@@ -237,7 +237,9 @@ struct ProgramBuilder {
 
   // Thin QR of the block held in buffer `cur` of the pair selected by `buf` (rows = p or q),
   // by `passes` rounds of CholeskyQR; returns the buffer index that holds the result.
-  int orth(bool y_side, int cur, int passes, bool shifted = true) {
+  // The first `nshift` passes add the diagonal shift to their Gram matrix: such a pass cannot break down and divides the
+  // condition number of the block by about 700; a pass without the shift needs a condition number below about 2000.
+  int orth(bool y_side, int cur, int passes, int nshift = 1) {
     auto buf_of = [&](int i, int which) { return y_side ? P.mat[i].y[which] : P.mat[i].zw[which]; };
     auto rows_of = [&](int i) { return y_side ? P.mat[i].p : P.mat[i].q; };
     int max_blocks = 0;
@@ -252,7 +254,7 @@ struct ProgramBuilder {
         g.M = m.r; g.N = m.r; g.K = rows_of(i);
         return true;
       }, false, true, true);      // the factorisation reads the lower triangle only
-      if (pass == 0 && shifted) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
+      if (pass < nshift) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
       factor(max_blocks);
       simple(OP_DIAG_INV);
       // M = L^{-1}, row block by row block from the inverses of the diagonal blocks:
@@ -303,7 +305,7 @@ struct ProgramBuilder {
     std::vector<Op> saved;
     saved.swap(P.ops);
     simple(OP_Y_FROM_EXT);
-    const int ycur = orth(true, 0, passes);
+    const int ycur = orth(true, 0, passes, passes >= 3 ? 2 : 1);
     simple(OP_Q_FROM_Y, ycur);
     simple(OP_PACK);
     P.init_ops.swap(P.ops);
@@ -312,7 +314,8 @@ struct ProgramBuilder {
 
   // Estimate of sigma_{r+1} of the source for the r-th spectral gap (Sec. 5.1, Metrics): block power iteration on the
   // source deflated by the current basis, (I - Q Q^T) Src, then the largest Ritz value of the block.
-  void build_gap(int iters) {
+  void build_gap(int iters, int passes) {
+    const int inner = passes >= 3 ? 2 : 1;
     std::vector<Op> saved;
     saved.swap(P.ops);
     auto deflate = [&](int ycur) {      // Y <- Y - Q (Q^T Y); the r x r product goes through the buffer of the Cholesky factor
@@ -360,13 +363,13 @@ struct ProgramBuilder {
     };
     y_product(-1);
     deflate(0);
-    int ycur = orth(true, 0, 1);
+    int ycur = orth(true, 0, inner, inner);
     for (int it = 0; it < iters; ++it) {
       z_product(ycur);                  // Src^T (I - Q Q^T) Y = Src^T Y for a block orthogonal to Q
-      const int zcur = orth(false, 0, 1);
+      const int zcur = orth(false, 0, inner, inner);
       y_product(zcur);
       deflate(0);
-      ycur = orth(true, 0, it + 1 < iters ? 1 : 2);
+      ycur = it + 1 < iters ? orth(true, 0, inner, inner) : orth(true, 0, inner + 1, inner);
     }
     // with 2r > min(p, q) the deflated source has fewer than r directions and the orthonormalisation completes the
     // block arbitrarily: deflated once more, the block keeps the estimate below the norm of the deflated source
@@ -388,7 +391,10 @@ struct ProgramBuilder {
     P.ops.swap(saved);
   }
 
+  // passes = 3 is the robust variant: two shifted passes after every product of the power iteration (the conditioning
+  // of the source then does not compound from product to product) and shifted, shifted, plain at the end.
   void build(int power_iters, int passes, bool rayleigh_ritz) {
+    const int inner = passes >= 3 ? 2 : 1, nshift = passes >= 3 ? 2 : 1;
     // Y = Src Omega
     gemm([&](int i, GemmDesc& g) {
       const MatDev& m = P.mat[i];
@@ -403,7 +409,7 @@ struct ProgramBuilder {
     // Inside the power iteration the blocks only have to stay well conditioned (any basis of the
     // same span serves the next product), so one shifted CholeskyQR pass is enough there; the basis
     // that becomes Q gets the full number of passes.
-    int ycur = orth(true, 0, power_iters > 0 ? 1 : passes);
+    int ycur = power_iters > 0 ? orth(true, 0, inner, inner) : orth(true, 0, passes, nshift);
     for (int it = 0; it < power_iters; ++it) {
       // Z = Src^T Y
       gemm([&](int i, GemmDesc& g) {
@@ -416,7 +422,7 @@ struct ProgramBuilder {
       });
       P.ops.back().fast = 1;
       P.ops.back().iarg = ycur;
-      int zcur = orth(false, 0, 1);
+      int zcur = orth(false, 0, inner, inner);
       // Y = Src Z
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
@@ -428,7 +434,7 @@ struct ProgramBuilder {
       });
       P.ops.back().fast = 2;
       P.ops.back().iarg = zcur;
-      ycur = orth(true, 0, it + 1 < power_iters ? 1 : passes);
+      ycur = it + 1 < power_iters ? orth(true, 0, inner, inner) : orth(true, 0, passes, nshift);
     }
     if (rayleigh_ritz) {
       // Rayleigh-Ritz step (Sec. 2: Q = the first r columns of U, largest singular value first):
@@ -468,7 +474,7 @@ struct ProgramBuilder {
       // the columns found are orthogonal to about 1e-6 per pair only: one CholeskyQR pass (unshifted: the block is
       // orthonormal to 1e-4 already) brings them back to working precision without changing their order or,
       // visibly, their directions
-      ycur = orth(true, 1 - ycur, 1, false);
+      ycur = orth(true, 1 - ycur, 1, 0);
       simple(OP_FROB);            // ||Src||_F^2 for the stable rank (Sec. 5.1)
     }
     // rotation: R = Q_new^T Q_old (and R o R)
@@ -693,7 +699,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // refresh program
   ProgramBuilder pb(P, n);
   pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes, hp.rayleigh_ritz != 0);
-  if (hp.rayleigh_ritz) pb.build_gap(2);
+  if (hp.rayleigh_ritz) pb.build_gap(2, hp.orth_passes == 0 ? 2 : hp.orth_passes);
   pb.build_init(hp.orth_passes == 0 ? 2 : hp.orth_passes);
   P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
   P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());

@@ -487,16 +487,18 @@ def test_refresh_before_first_step_and_exact_reconstruction(torch):
     assert not pair.get(0, lordo.STATE_U).any() and not pair.get(0, lordo.STATE_V).any()
 
 
-def test_refresh_rank_deficient_source_three_passes(torch):
+@pytest.mark.parametrize("rayleigh_ritz", [False, True], ids=["plain", "rayleigh_ritz"])
+def test_refresh_rank_deficient_source_three_passes(torch, rayleigh_ritz):
     """rank(Src) < r: the completion of the basis is arbitrary; only Q^T Q = I and Q Q^T Src = Src
-    are fixed.  Three CholeskyQR passes are requested for this degenerate case."""
+    are fixed.  Three CholeskyQR passes are requested for this degenerate case.  With the Rayleigh-Ritz step the
+    leading Ritz values are the five singular values of the source and the others vanish."""
     from paper_2602_04396_amd import lordo
     p, q, r = 128, 96, 16
     rng = np.random.default_rng(synth.seed_for(22, 0))
     Src = (rng.standard_normal((p, 5)) @ rng.standard_normal((5, q))).astype(np.float32)
     Om = synth.omega(rng, q, r)
     W = [torch.zeros(p, q, device="cuda")]
-    opt = lordo.Lordo([(p, q, r)], lordo.hparams(power_iters=1, orth_passes=3), W, torch)
+    opt = lordo.Lordo([(p, q, r)], lordo.hparams(power_iters=1, orth_passes=3, rayleigh_ritz=rayleigh_ritz), W, torch)
     opt.refresh_subspace([torch.tensor(Src, device="cuda")], [torch.tensor(Om, device="cuda")])
     try:
         opt.poll_status()
@@ -507,6 +509,39 @@ def test_refresh_rank_deficient_source_three_passes(torch):
     S64 = Src.astype(np.float64)
     assert np.isfinite(Qg).all()
     assert rel_l2(Qg @ (Qg.T @ S64), S64) <= 1e-3
+    if rayleigh_ritz:
+        ritz = opt.get_state(0, lordo.STATE_RITZ).cpu().numpy().astype(np.float64)
+        sigma = np.linalg.svd(S64, compute_uv=False)
+        assert np.max(np.abs(ritz[:5] - sigma[:5]) / sigma[:5]) <= 1e-4
+        assert np.all(ritz[5:] <= 2e-3 * sigma[0])          # zero up to the rounding of the squared values
+        assert np.linalg.norm(Qg.T @ Qg - np.eye(r)) <= 1e-3
+
+
+def test_rayleigh_ritz_nearly_rank_deficient_source(torch):
+    """A source of rank five plus noise four orders of magnitude below it: the factor of the Ritz matrix has a
+    condition number of 1e4 and most of its singular values are tiny; the five leading Ritz values must be the five
+    singular values of the source to 1e-4, the others must be of the size of the noise, and the basis orthonormal."""
+    from paper_2602_04396_amd import lordo
+    p, q, r = 256, 192, 24
+    rng = np.random.default_rng(synth.seed_for(23, 0))
+    Src = (rng.standard_normal((p, 5)) @ rng.standard_normal((5, q)) + 1e-3 * rng.standard_normal((p, q))).astype(np.float32)
+    Om = synth.omega(rng, q, r)
+    W = [torch.zeros(p, q, device="cuda")]
+    # the robust variant of the orthonormalisation (orth_passes = 3): with the default the conditioning of this source,
+    # 1e4, compounds over the products of the power iteration and the last, unshifted pass breaks down
+    opt = lordo.Lordo([(p, q, r)], lordo.hparams(power_iters=2, rayleigh_ritz=True, orth_passes=3), W, torch)
+    opt.refresh_subspace([torch.tensor(Src, device="cuda")], [torch.tensor(Om, device="cuda")])
+    opt.poll_status()
+    Qg = opt.get_state(0, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+    ritz = opt.get_state(0, lordo.STATE_RITZ).cpu().numpy().astype(np.float64)
+    S64 = Src.astype(np.float64)
+    sigma = np.linalg.svd(S64, compute_uv=False)
+    _, S = orc.rayleigh_ritz(orc.range_finder(S64, Om.astype(np.float64), 2), S64)
+    assert np.linalg.norm(Qg.T @ Qg - np.eye(r)) <= TOL_ORTH
+    assert np.max(np.abs(ritz[:5] - sigma[:5]) / sigma[:5]) <= TOL
+    assert np.all(np.diff(ritz) <= 0)
+    assert np.max(np.abs(ritz - S)) <= TOL * sigma[0]           # the small ones in absolute terms
+    assert np.all(ritz[5:] <= 2.0 * sigma[5])
 
 
 @pytest.mark.parametrize("mode", ["average", "nesterov", "heavy_ball", "own_delta"])
