@@ -23,7 +23,10 @@
  *   - Return value: LORDO_OK or a negative LORDO_E* code; lordo_strerror gives text.
  *     Argument and state errors are detected before anything is enqueued.  A numerical
  *     breakdown inside a kernel (non-positive Cholesky pivot) is latched in device
- *     memory and reported by lordo_poll_status as LORDO_ENUMERIC.
+ *     memory and reported by lordo_poll_status as LORDO_ENUMERIC.  While it is latched,
+ *     lordo_refresh_subspace*, lordo_init_projection leave the projection and the
+ *     moments as they were (the refresh that broke down included): the optimizer goes
+ *     on in the old subspace until the caller polls, which clears the latch.
  *   - There is no CPU fallback: without a GPU every compute call returns LORDO_EHIP.
  */
 #ifndef LORDO_H

@@ -283,7 +283,10 @@ hipError_t launch_pack_q(const DevCtx& d, int mat_first, int mat_count, hipStrea
   return hipGetLastError();
 }
 
+// Does nothing while a numerical breakdown is latched: a refresh (or an initial projection) whose factorisation met a
+// non-positive pivot leaves the projection as it was.
 __global__ __launch_bounds__(256) void k_q_from_y(DevCtx d, int ybuf) {
+  if (*d.flag != 0) return;
   const MatDev& m = d.mats[blockIdx.y];
   float* q32 = reinterpret_cast<float*>(d.arena + m.q32);
   const float* y = reinterpret_cast<const float*>(d.arena + m.y[ybuf]);
@@ -1233,6 +1236,7 @@ hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float
   return hipGetLastError();
 }
 __global__ __launch_bounds__(256) void k_rot_post(DevCtx d, float* __restrict__ u, float* __restrict__ v, float c1, float c2) {
+  if (*d.flag != 0) return;       // a breakdown is latched: the moments stay in the coordinates of the projection that stays
   const MatDev& m = d.mats[blockIdx.y];
   const float* a1 = reinterpret_cast<const float*>(d.arena + m.zw[0]);
   const float* a2 = reinterpret_cast<const float*>(d.arena + m.zw[1]);

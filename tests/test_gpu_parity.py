@@ -499,11 +499,20 @@ def test_refresh_rank_deficient_source_three_passes(torch, rayleigh_ritz):
     Om = synth.omega(rng, q, r)
     W = [torch.zeros(p, q, device="cuda")]
     opt = lordo.Lordo([(p, q, r)], lordo.hparams(power_iters=1, orth_passes=3, rayleigh_ritz=rayleigh_ritz), W, torch)
+    G0 = torch.tensor(rng.standard_normal((p, q)).astype(np.float32), device="cuda").bfloat16()
+    opt.local_step(W, [G0], 1e-3)          # moments that a rotation would change
+    before = [opt.get_state(0, which) for which in (lordo.STATE_Q, lordo.STATE_U, lordo.STATE_V)]
     opt.refresh_subspace([torch.tensor(Src, device="cuda")], [torch.tensor(Om, device="cuda")])
     try:
         opt.poll_status()
     except lordo.LordoError as e:          # a latched breakdown is an allowed outcome here
         assert e.code == lordo.ENUMERIC
+        # the refresh that broke down left the projection and the moments alone, and the next step works
+        for x, which in zip(before, (lordo.STATE_Q, lordo.STATE_U, lordo.STATE_V)):
+            assert torch.equal(opt.get_state(0, which), x)
+        opt.local_step(W, [G0], 1e-3)
+        opt.poll_status()
+        assert torch.isfinite(W[0]).all()
         return
     Qg = opt.get_state(0, lordo.STATE_Q).cpu().numpy().astype(np.float64)
     S64 = Src.astype(np.float64)
