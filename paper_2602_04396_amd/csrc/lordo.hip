@@ -508,6 +508,8 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
     const lordo_shape& s = shapes[i];
     if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || s.rank > s.rows || s.reserved != 0) return LORDO_EINVAL;
     if (s.rows > (1 << 24) || s.cols > (1 << 24) || s.rank > 4096) return LORDO_EINVAL;
+    // the kernels address a matrix through buffer descriptors with 32-bit byte offsets: p * q * 4 bytes must stay below 4 GiB
+    if (s.rows * s.cols >= (int64_t(1) << 30)) return LORDO_EINVAL;
   }
   if (!(hp->beta1 >= 0 && hp->beta1 < 1) || !(hp->beta2 >= 0 && hp->beta2 < 1) || !(hp->eps >= 0)) return LORDO_EINVAL;
   if (hp->qhm_mode < 0 || hp->qhm_mode > 2 || (hp->error_feedback != 0 && hp->error_feedback != 1)) return LORDO_EINVAL;

@@ -46,7 +46,7 @@ def test_workspace_bytes_scales_and_validates(lib):
     assert lower < c2 < 8 * lower
     with_mom = lordo.workspace_bytes(shapes, lordo.hparams(outer_momentum=0.9))
     assert with_mom - c2 >= sum(4 * p * q for p, q, r in shapes)
-    for bad in ([(8, 8, 9)], [(0, 8, 1)], [(8, 8, 0)]):
+    for bad in ([(8, 8, 9)], [(0, 8, 1)], [(8, 8, 0)], [(32768, 32768, 64)]):     # the last: p * q * 4 bytes reach 4 GiB
         with pytest.raises(lordo.LordoError) as e:
             lordo.workspace_bytes(bad, hp)
         assert e.value.code == lordo.EINVAL
