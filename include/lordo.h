@@ -66,7 +66,7 @@ extern "C" {
 typedef struct lordo_ctx lordo_ctx;
 
 /* One weight matrix: rows p, cols q, rank r; requires 1 <= r <= p (left projection), r <= 4096,
- * p, q <= 2^24 and p * q < 2^30 (a matrix is addressed with 32-bit byte offsets). */
+ * p, q <= 2^20 and p * q < 2^30 (a matrix is addressed with 32-bit byte offsets). */
 typedef struct {
   int64_t rows;
   int64_t cols;

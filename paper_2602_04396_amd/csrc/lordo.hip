@@ -507,7 +507,8 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
   for (int i = 0; i < n; ++i) {
     const lordo_shape& s = shapes[i];
     if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || s.rank > s.rows || s.reserved != 0) return LORDO_EINVAL;
-    if (s.rows > (1 << 24) || s.cols > (1 << 24) || s.rank > 4096) return LORDO_EINVAL;
+    // (tile coordinates of the grouped GEMM are 16-bit: at most 32767 tiles of 64 rows)
+    if (s.rows > (1 << 20) || s.cols > (1 << 20) || s.rank > 4096) return LORDO_EINVAL;
     // the kernels address a matrix through buffer descriptors with 32-bit byte offsets: p * q * 4 bytes must stay below 4 GiB
     if (s.rows * s.cols >= (int64_t(1) << 30)) return LORDO_EINVAL;
   }
