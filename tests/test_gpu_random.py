@@ -145,3 +145,34 @@ def test_random_shapes_rayleigh_ritz_refresh(case):
         assert ritz[-1] - gap[i] <= deflated * (1 + TOL) + 1e-6 * ritz[0], f"sigma_(r+1) estimate of matrix {i}"
     pair.local_step([g.draw(5) for g in gens], lr=1e-3, bf16=bf16)
     pair.compare_local(TOL)
+
+
+@pytest.mark.parametrize("shapes", [[(70000, 24, 8)], [(24, 70000, 8)], [(40000, 40, 33), (33, 50001, 33)]],
+                         ids=["tall", "wide", "both_with_r_equal_to_the_short_side"])
+def test_extreme_aspect_ratios(shapes):
+    """Index arithmetic far from the square shapes of the benchmark: tens of thousands of rows or columns against a
+    few dozen of the other, through steps, a refresh, a step and the outer step."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    for bf16 in (True, False):
+        kw = dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=1)
+        ohp, ghp = orc.Hyper(**kw), lordo.hparams(grad_dtype=lordo.BF16 if bf16 else lordo.F32, **kw)
+        W0 = [synth.weights(np.random.default_rng(synth.seed_for(80, i)), p, q) for i, (p, q, r) in enumerate(shapes)]
+        Q0 = [synth.orthonormal(np.random.default_rng(synth.seed_for(81, i)), p, r).astype(np.float32) for i, (p, q, r) in enumerate(shapes)]
+        pair = Pair(torch, shapes, W0, ohp, ghp, Q0)
+        gens = [synth.SpikedGradient(p, q, min(4, p, q), synth.seed_for(82, i), bf16=bf16) for i, (p, q, r) in enumerate(shapes)]
+        for t in range(2):
+            pair.local_step([g.draw(t) for g in gens], lr=1e-3, bf16=bf16, first_step_patch=(t == 0))
+        pair.compare_local(TOL)
+        Src = [g.draw(100) for g in gens]
+        Om = [synth.omega(np.random.default_rng(synth.seed_for(83, i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+        dists, orths = pair.refresh(Src, Om, bf16=bf16)
+        assert max(orths) <= TOL_ORTH and max(dists) <= TOL_SUBSPACE, f"orth {orths} dist {dists}"
+        pair.local_step([g.draw(5) for g in gens], lr=1e-3, bf16=bf16)
+        pair.compare_local(TOL)
+        pair.opt.outer_step(pair.W_gpu, None)
+        pair.opt.poll_status()
+        for i in range(len(shapes)):
+            Wn = orc.outer_step(pair.st[i], orc.pseudo_gradient(pair.st[i], pair.W_orc[i]), ohp)
+            got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
+            assert rel_l2(got - pair.W0[i], Wn - pair.W0[i]) <= TOL
