@@ -223,3 +223,46 @@ def test_c2_full_size_rayleigh_ritz_refresh_sampled_matrices():
         assert np.linalg.norm(Dm - np.diag(d)) <= 1e-5 * np.linalg.norm(Dm)
         assert np.all(np.diff(d) <= 1e-5 * d[0])
         assert abs(sr[i] - orc.stable_rank(A)) <= TOL * orc.stable_rank(A), f"stable rank of matrix {i}"
+
+
+def test_one_matrix_just_under_the_size_limit_sampled_columns():
+    """A 32000 x 33000 matrix: p * q * 4 bytes = 3.93 GiB, just under the 4 GiB that the 32-bit byte offsets of the
+    kernels can address.  Refresh, two steps and an outer step; sampled columns (first, last, around the 2^15 column and
+    random ones) against the oracle, the last rows of the matrix finite, anchor equal to the weights."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    p, q, r = 32000, 33000, 64
+    assert p * q < 2 ** 30
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    W = [torch.randn(p, q, generator=gen, device="cuda") * 0.02]
+    G = [[(torch.randn(p, q, generator=gen, device="cuda") * 1e-3).bfloat16()] for _ in range(2)]
+    Om = [torch.randn(q, r, generator=gen, device="cuda")]
+    hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=1)
+    opt = lordo.Lordo([(p, q, r)], hp, W, torch)
+    opt.refresh_subspace(G[0], Om)
+    opt.poll_status()
+    Q = opt.get_state(0, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(Q.T @ Q - np.eye(r)) <= 1e-4
+    cols = np.unique(np.concatenate([[0, 1, q - 1, q - 2, 127, 128, 16384, 32767, 32768],
+                                     np.random.default_rng(1).integers(0, q, 12)]))
+    st = orc.init_state(W[0][:, cols].cpu().numpy().astype(np.float64), r, Q)
+    Wc = st.anchor.copy()
+    ohp = orc.Hyper()
+    for step in range(2):
+        before = W[0][:, cols].cpu().numpy().astype(np.float64)
+        opt.local_step(W, G[step], 1e-3)
+        torch.cuda.synchronize()
+        Gc = G[step][0][:, cols].float().cpu().numpy().astype(np.float64)
+        Wc = orc.local_step(st, Wc, Gc, 1e-3, ohp)
+        got = {name: opt.get_state(0, which).cpu().numpy().astype(np.float64)[:, cols]
+               for name, which in (("g", lordo.STATE_GLOW), ("u", lordo.STATE_U), ("v", lordo.STATE_V), ("N", lordo.STATE_NUPD))}
+        assert rel_l2(got["g"], st.last_g) <= TOL and rel_l2(got["u"], st.u) <= TOL and rel_l2(got["v"], st.v) <= TOL
+        dW = W[0][:, cols].cpu().numpy().astype(np.float64) - before
+        assert rel_l2(dW, -1e-3 * Q @ got["N"]) <= TOL
+        if step:                      # (the first update from zero moments is the sign of g: see the c2 test above)
+            assert rel_l2(got["N"], st.last_N) <= TOL
+    assert torch.isfinite(W[0][[p - 1, p - 2, p - 129]]).all()
+    opt.outer_step(W, None)
+    opt.poll_status()
+    assert torch.equal(opt.get_state(0, lordo.STATE_ANCHOR), W[0])
