@@ -805,3 +805,41 @@ def test_two_contexts_with_the_same_inputs_agree_bit_for_bit(torch, rayleigh_rit
     if rayleigh_ritz:
         assert torch.equal(a.stable_rank(), b.stable_rank())
         assert torch.equal(a.spectral_gap(G[2], Om), b.spectral_gap(G[2], Om))
+
+
+def test_calls_follow_the_callers_stream(torch):
+    """Every call only enqueues on the stream it is given: the same sequence on a side stream, with its inputs
+    produced on that stream right before each call and no synchronisation in between, gives the same bits as on the
+    default stream."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(520, 392, 128), (300, 640, 64), (200, 328, 48)]
+    kw = dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=1)
+    W0 = [torch.tensor(w, dtype=torch.float32, device="cuda") for w in _weights(shapes, 40)]
+    base = [torch.tensor(g.draw(0), device="cuda") for g in _spiked(shapes, 40, 6)]
+    Om = [torch.tensor(synth.omega(np.random.default_rng(synth.seed_for(40, 900 + i)), q, r), device="cuda")
+          for i, (p, q, r) in enumerate(shapes)]
+    torch.cuda.synchronize()
+
+    def run():
+        W = [w.clone() for w in W0]
+        opt = lordo.Lordo(shapes, lordo.hparams(**kw), W, torch)
+        for t in range(4):
+            G = [(b * (1.0 + 0.25 * t)).bfloat16() for b in base]       # produced on the current stream, consumed at once
+            if t == 2:
+                opt.refresh_subspace(G, Om)
+            opt.local_step(W, G, 1e-3)
+        opt.outer_step(W, None)
+        return W, opt
+
+    Wa, a = run()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        Wb, b = run()
+    side.synchronize()
+    torch.cuda.synchronize()
+    a.poll_status()
+    b.poll_status()
+    for i in range(len(shapes)):
+        assert torch.equal(Wa[i], Wb[i])
+        for which in (lordo.STATE_Q, lordo.STATE_U, lordo.STATE_V, lordo.STATE_MOM):
+            assert torch.equal(a.get_state(i, which), b.get_state(i, which))
