@@ -1,5 +1,5 @@
 // Elementwise, packing and small dense kernels of the LoRDO library (gfx950).
-//   k_adam            fused low-rank Adam update on the flat low-rank arena (Sec. 2; Alg. 1 moment lines), with the
+//   k_adam4 / k_adam  fused low-rank Adam update on the flat low-rank arena (Sec. 2; Alg. 1 moment lines), with the
 //                     low-rank QHM bracket, the column sums of the full-rank QHM scale (Sec. 3.2), the planes of g
 //                     for the error-feedback residual and the up-link buffer (App. A.5.1) as options
 //   k_pq<MODE>        p x q family: outer step (Alg. 1 OuterOpt; App. A.2, D.4), pseudo-gradient anchor - W
@@ -134,6 +134,59 @@ __global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, fl
   }
 }
 
+// The same update with four elements per thread (all cases but the column sums of the full-rank QHM scale): every
+// load and store instruction of a wave then covers one dense kilobyte (16 bytes per lane, consecutive lanes
+// consecutive addresses) instead of every other 16 bytes of two.
+__global__ __launch_bounds__(256) void k_adam4(const float* __restrict__ glow, float* __restrict__ u,
+                                               float* __restrict__ v, uint16_t* __restrict__ n_hi,
+                                               uint16_t* __restrict__ n_lo, int64_t nquads, AdamArgs a) {
+  const int64_t qidx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (qidx >= nquads) return;
+  const int64_t base = a.first + qidx * 4;
+  f32x4n g = __builtin_nontemporal_load(reinterpret_cast<const f32x4n*>(glow + base));
+  int nsplit = a.grp_nsplit[0];
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (base >= a.grp_start[i]) nsplit = a.grp_nsplit[i];
+  for (int sidx = 1; sidx < nsplit; ++sidx)               // deterministic split-K reduction, fixed order
+    g += __builtin_nontemporal_load(reinterpret_cast<const f32x4n*>(glow + sidx * a.split_stride + base));
+  f32x4n uu = ld_stream(u + base), vv = ld_stream(v + base);
+  uint32_t hi[4], lo[4];
+  f32x4n nv;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float un = fmaf(a.b1, uu[e], a.omb1 * g[e]);
+    const float vn = fmaf(a.b2, vv[e], a.omb2 * (g[e] * g[e]));
+    uu[e] = un;
+    vv[e] = vn;
+    const float den = sqrtf(vn * a.inv_c2) + a.eps;
+    const float nn = fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;      // the bracket of k_adam, same order
+    split_bf(nn, hi[e], lo[e]);
+    nv[e] = nn;
+  }
+  if (a.acc) {
+    f32x4n c0 = ld_stream(a.acc + base);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c0[e] = fmaf(a.lr, nv[e], c0[e]);
+    st_stream(a.acc + base, c0);
+  }
+  st_stream(u + base, uu);
+  st_stream(v + base, vv);
+  u32x2n ph, pl;
+  ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16);
+  pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
+  *reinterpret_cast<u32x2n*>(n_hi + base) = ph;
+  *reinterpret_cast<u32x2n*>(n_lo + base) = pl;
+  if (a.g_hi) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split_bf(g[e], hi[e], lo[e]);
+    ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16);
+    pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
+    *reinterpret_cast<u32x2n*>(a.g_hi + base) = ph;
+    *reinterpret_cast<u32x2n*>(a.g_lo + base) = pl;
+  }
+}
+
 // fp32 array in operand layout -> bf16 hi / lo planes (the low-rank pseudo-gradient as B operand of the up-projection)
 __global__ __launch_bounds__(256) void k_split_planes(const float* __restrict__ src, uint16_t* __restrict__ p_hi,
                                                       uint16_t* __restrict__ p_lo, int64_t ngroups) {
@@ -164,7 +217,7 @@ hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, ui
   if (ngroups <= 0) return hipSuccess;
   unsigned blocks = (unsigned)((ngroups + 255) / 256);
   if (a.colpart) hipLaunchKernelGGL(k_adam<true>, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
-  else hipLaunchKernelGGL(k_adam<false>, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
+  else hipLaunchKernelGGL(k_adam4, dim3(2 * blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, 2 * ngroups, a);
   return hipGetLastError();
 }
 
