@@ -1069,7 +1069,7 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 
   // fragment slot (64 x 16 bytes) of chunk buffer s: ((s*2 + kind)*4 + blk)*4 + ks*2 + plane,
   // kind 0 = Q rows, 1 = N columns; the epilogue staging blocks reuse the same memory
-  constexpr int TP = 36;
+  constexpr int TP = 68;                                   // pitch of the 32 x 64 staging tile of a wave
   constexpr int SLOTS = 2 * 2 * 4 * 4;
   __shared__ u32x4 frag[SLOTS * 64];                       // 64 KiB
   static_assert(sizeof(u32x4) * SLOTS * 64 >= sizeof(float) * NW * 32 * TP, "staging blocks must fit");
@@ -1102,7 +1102,8 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     }
   };
 
-  // W tile in row order: lane = (rr, c4): row rr + 8j of a block, columns 4*c4 .. 4*c4+3
+  // W tile in row order: lane = (rr, c16): row rr + 4j of a row block, columns 4*c16 .. 4*c16+3 of the wave's two
+  // column blocks, so that one access of the wave covers four rows of 256 contiguous bytes
   const uint32_t row_bytes = (uint32_t)q * 4u;
   const void* target = ua.target_err == 1 ? static_cast<const void*>(d.arena + m.err)
                        : ua.target_err == 2 ? static_cast<const void*>(d.arena + m.mom) : ext_ptr(d, EXT_W, t.mat);
@@ -1111,52 +1112,40 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   const rsrc_t ranchor = make_rsrc(d.arena + m.anchor, (uint32_t)p * row_bytes);
   const rsrc_t rmom = make_rsrc(d.arena + (OUTER && ua.has_mom ? m.mom : m.anchor), (uint32_t)p * row_bytes);
   const rsrc_t rw = OUTER ? ranchor : rw_out;
-  const int rr = lane >> 3, c4 = lane & 7;
-  uint32_t voff[2];
-#pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    int col = 32 * (nb0 + b) + 4 * c4;
-    voff[b] = col < q ? (uint32_t)rr * row_bytes + (uint32_t)c4 * 16u : OOB;
-  }
-  // a group of eight rows that starts at or past the last row gets the size of the resource as its
+  const int rr = lane >> 4, c16 = lane & 15;
+  const int bsel = c16 >> 3;                                 // which of the two column blocks the lane's columns lie in
+  const int lcol = 32 * nb0 + 4 * c16;                       // first of the lane's four columns
+  const uint32_t voff = lcol < q ? (uint32_t)rr * row_bytes + (uint32_t)c16 * 16u : OOB;
+  // a group of four rows that starts at or past the last row gets the size of the resource as its
   // scalar offset, which puts every lane of the access out of range
-  auto w_soff = [&](int a, int b, int j) -> uint32_t {
-    const int row = 32 * (mb0 + a) + 8 * j;
-    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u : (uint32_t)p * row_bytes;
+  auto w_soff = [&](int a, int j) -> uint32_t {
+    const int row = 32 * (mb0 + a) + 4 * j;
+    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * nb0) * 4u : (uint32_t)p * row_bytes;
   };
 
   issue_chunk(0, 0);
-  u32x4 wv[AM][2][4];
+  u32x4 wv[AM][8];
 #pragma unroll
   for (int a = 0; a < AM; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) wv[a][b][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff[b], w_soff(a, b, j), STREAM);
+    for (int j = 0; j < 8; ++j) wv[a][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, w_soff(a, j), STREAM);
   // gradient term (WITH_G): four consecutive columns per lane, same rows as the W accesses; a bf16 G tile is
   // requested here, with the W tile, so that it arrives during the contraction
   const uint32_t ges = ua.g_is_f32 ? 4u : 2u;
   const uint32_t grow_bytes = (uint32_t)q * ges;
   const rsrc_t rg = WITH_G ? make_rsrc(ext_ptr(d, EXT_G, t.mat), (uint32_t)p * grow_bytes) : rw;
-  auto g_soff = [&](int a, int b, int j) -> uint32_t {
-    const int row = 32 * (mb0 + a) + 8 * j;
-    return row < p ? (uint32_t)row * grow_bytes + (uint32_t)(32 * (nb0 + b)) * ges : (uint32_t)p * grow_bytes;
+  auto g_soff = [&](int a, int j) -> uint32_t {
+    const int row = 32 * (mb0 + a) + 4 * j;
+    return row < p ? (uint32_t)row * grow_bytes + (uint32_t)(32 * nb0) * ges : (uint32_t)p * grow_bytes;
   };
-  uint32_t gvoff[2];
-#pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    int col = 32 * (nb0 + b) + 4 * c4;
-    gvoff[b] = col < q ? (uint32_t)rr * grow_bytes + (uint32_t)c4 * 4u * ges : OOB;
-  }
-  u32x2 gpre[WITH_G ? AM : 1][2][4];
+  const uint32_t gvoff = lcol < q ? (uint32_t)rr * grow_bytes + (uint32_t)c16 * 4u * ges : OOB;
+  u32x2 gpre[WITH_G ? AM : 1][8];
   if constexpr (WITH_G) {
     if (!ua.g_is_f32) {
 #pragma unroll
       for (int a = 0; a < AM; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) gpre[a][b][j] = __builtin_amdgcn_raw_buffer_load_b64(rg, gvoff[b], g_soff(a, b, j), STREAM);
+        for (int j = 0; j < 8; ++j) gpre[a][j] = __builtin_amdgcn_raw_buffer_load_b64(rg, gvoff, g_soff(a, j), STREAM);
     }
   }
   ISSUE_FENCE();
@@ -1201,95 +1190,92 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   __syncthreads();                // all waves are done reading fragments: reuse the memory for staging
 
   if (mb0 >= mblocks || nb0 >= nblocks) return;
-  f32x4 cscale[2] = {{1.f, 1.f, 1.f, 1.f}, {1.f, 1.f, 1.f, 1.f}};
+  f32x4 cscale = {1.f, 1.f, 1.f, 1.f};
   if constexpr (WITH_G) {
-    if (ua.colscale) {
+    if (ua.colscale && nb0 + bsel < nblocks) {
       const GAS float* cp = TO_GLOBAL(const float, ua.colpart) + m.lr_off / 32;
       const int rblocks = m.rp / 32;
       const float pad = (float)(m.rp - m.r) * ua.eps;          // padded rank indices hold v = 0: eps each
       const float inv_r = 1.f / (float)m.r;
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      for (int rb = 0; rb < rblocks; ++rb)                      // fixed order
+        sum += *reinterpret_cast<const GAS f32x4*>(cp + ((int64_t)(nb0 + bsel) * rblocks + rb) * 32 + 4 * (c16 & 7));
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        if (nb0 + b >= nblocks) continue;
-        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-        for (int rb = 0; rb < rblocks; ++rb)                    // fixed order
-          sum += *reinterpret_cast<const GAS f32x4*>(cp + ((int64_t)(nb0 + b) * rblocks + rb) * 32 + 4 * c4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) cscale[b][e] = 1.f / ((sum[e] - pad) * inv_r);
-      }
+      for (int e = 0; e < 4; ++e) cscale[e] = 1.f / ((sum[e] - pad) * inv_r);
     }
   }
-  auto g_term = [&](int a, int b, int j) -> f32x4 {
+  auto g_term = [&](int a, int j) -> f32x4 {
     f32x4 gv;
     if (ua.g_is_f32) {
-      u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rg, gvoff[b], g_soff(a, b, j), STREAM);
+      u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rg, gvoff, g_soff(a, j), STREAM);
       gv.x = __uint_as_float(w.x); gv.y = __uint_as_float(w.y); gv.z = __uint_as_float(w.z); gv.w = __uint_as_float(w.w);
     } else {
-      const u32x2 w = gpre[WITH_G ? a : 0][b][j];
+      const u32x2 w = gpre[WITH_G ? a : 0][j];
       gv.x = __uint_as_float(w.x << 16); gv.y = __uint_as_float(w.x & 0xffff0000u);
       gv.z = __uint_as_float(w.y << 16); gv.w = __uint_as_float(w.y & 0xffff0000u);
     }
-    return gv * cscale[b] * ua.coef_g;
+    return gv * cscale * ua.coef_g;
   };
-  // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e
+  // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e of its block; both
+  // column blocks of a row block go into one 32 x 64 staging tile
   float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
 #pragma unroll
-  for (int a = 0; a < AM; ++a)
+  for (int a = 0; a < AM; ++a) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
         f32x4 x;
         x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
-        *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 8 * vq + 4 * (lane >> 5)) = x;
+        *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 32 * b + 8 * vq + 4 * (lane >> 5)) = x;
       }
-      // LDS operations of one wave complete in order: the reads below see the writes above
-      f32x4 gt[4];
-      if constexpr (WITH_G) {
+    // LDS operations of one wave complete in order: the reads below see the writes above
+    f32x4 gt[8];
+    if constexpr (WITH_G) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) gt[j] = g_term(a, b, j);
-      }
-      u32x4 mv[4];
-      if constexpr (OUTER) {
-        if (ua.has_mom) {
+      for (int j = 0; j < 8; ++j) gt[j] = g_term(a, j);
+    }
+    u32x4 mv[8];
+    if constexpr (OUTER) {
+      if (ua.has_mom) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) mv[j] = __builtin_amdgcn_raw_buffer_load_b128(rmom, voff[b], w_soff(a, b, j), STREAM);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 8 * j) * TP + 4 * c4);
-        u32x4 o;
-        o.x = __float_as_uint(fmaf(-lr, x.x, __uint_as_float(wv[a][b][j].x)));
-        o.y = __float_as_uint(fmaf(-lr, x.y, __uint_as_float(wv[a][b][j].y)));
-        o.z = __float_as_uint(fmaf(-lr, x.z, __uint_as_float(wv[a][b][j].z)));
-        o.w = __float_as_uint(fmaf(-lr, x.w, __uint_as_float(wv[a][b][j].w)));
-        if constexpr (WITH_G) {
-          o.x = __float_as_uint(__uint_as_float(o.x) + gt[j].x); o.y = __float_as_uint(__uint_as_float(o.y) + gt[j].y);
-          o.z = __float_as_uint(__uint_as_float(o.z) + gt[j].z); o.w = __float_as_uint(__uint_as_float(o.w) + gt[j].w);
-        }
-        if constexpr (OUTER) {
-          f32x4 step = x;                                    // Delta
-          if (ua.has_mom) {
-            const f32x4 bo = {__uint_as_float(mv[j].x), __uint_as_float(mv[j].y), __uint_as_float(mv[j].z), __uint_as_float(mv[j].w)};
-            f32x4 bn;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              bn[e] = fmaf(ua.mu, bo[e], x[e]);
-              step[e] = ua.nesterov ? fmaf(ua.mu, bn[e], x[e]) : bn[e];
-            }
-            u32x4 bs = {__float_as_uint(bn.x), __float_as_uint(bn.y), __float_as_uint(bn.z), __float_as_uint(bn.w)};
-            __builtin_amdgcn_raw_buffer_store_b128(bs, rmom, voff[b], w_soff(a, b, j), STREAM);
-          }
-          o.x = __float_as_uint(fmaf(-lr, step.x, __uint_as_float(wv[a][b][j].x)));
-          o.y = __float_as_uint(fmaf(-lr, step.y, __uint_as_float(wv[a][b][j].y)));
-          o.z = __float_as_uint(fmaf(-lr, step.z, __uint_as_float(wv[a][b][j].z)));
-          o.w = __float_as_uint(fmaf(-lr, step.w, __uint_as_float(wv[a][b][j].w)));
-          __builtin_amdgcn_raw_buffer_store_b128(o, ranchor, voff[b], w_soff(a, b, j), STREAM);
-        }
-        __builtin_amdgcn_raw_buffer_store_b128(o, rw_out, voff[b], w_soff(a, b, j), STREAM);
+        for (int j = 0; j < 8; ++j) mv[j] = __builtin_amdgcn_raw_buffer_load_b128(rmom, voff, w_soff(a, j), STREAM);
       }
     }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 4 * j) * TP + 4 * c16);
+      u32x4 o;
+      o.x = __float_as_uint(fmaf(-lr, x.x, __uint_as_float(wv[a][j].x)));
+      o.y = __float_as_uint(fmaf(-lr, x.y, __uint_as_float(wv[a][j].y)));
+      o.z = __float_as_uint(fmaf(-lr, x.z, __uint_as_float(wv[a][j].z)));
+      o.w = __float_as_uint(fmaf(-lr, x.w, __uint_as_float(wv[a][j].w)));
+      if constexpr (WITH_G) {
+        o.x = __float_as_uint(__uint_as_float(o.x) + gt[j].x); o.y = __float_as_uint(__uint_as_float(o.y) + gt[j].y);
+        o.z = __float_as_uint(__uint_as_float(o.z) + gt[j].z); o.w = __float_as_uint(__uint_as_float(o.w) + gt[j].w);
+      }
+      if constexpr (OUTER) {
+        f32x4 step = x;                                    // Delta
+        if (ua.has_mom) {
+          const f32x4 bo = {__uint_as_float(mv[j].x), __uint_as_float(mv[j].y), __uint_as_float(mv[j].z), __uint_as_float(mv[j].w)};
+          f32x4 bn;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            bn[e] = fmaf(ua.mu, bo[e], x[e]);
+            step[e] = ua.nesterov ? fmaf(ua.mu, bn[e], x[e]) : bn[e];
+          }
+          u32x4 bs = {__float_as_uint(bn.x), __float_as_uint(bn.y), __float_as_uint(bn.z), __float_as_uint(bn.w)};
+          __builtin_amdgcn_raw_buffer_store_b128(bs, rmom, voff, w_soff(a, j), STREAM);
+        }
+        o.x = __float_as_uint(fmaf(-lr, step.x, __uint_as_float(wv[a][j].x)));
+        o.y = __float_as_uint(fmaf(-lr, step.y, __uint_as_float(wv[a][j].y)));
+        o.z = __float_as_uint(fmaf(-lr, step.z, __uint_as_float(wv[a][j].z)));
+        o.w = __float_as_uint(fmaf(-lr, step.w, __uint_as_float(wv[a][j].w)));
+        __builtin_amdgcn_raw_buffer_store_b128(o, ranchor, voff, w_soff(a, j), STREAM);
+      }
+      __builtin_amdgcn_raw_buffer_store_b128(o, rw_out, voff, w_soff(a, j), STREAM);
+    }
+  }
 }
 
 // Epilogue of the Y = Src B kernels: the 2 x 2 accumulator blocks of a wave (register 4*vq+e of lane l: row l%32
