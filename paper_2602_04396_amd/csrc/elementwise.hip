@@ -1,5 +1,5 @@
 // Elementwise, packing and small dense kernels of the LoRDO library (gfx950).
-//   k_adam4 / k_adam  fused low-rank Adam update on the flat low-rank arena (Sec. 2; Alg. 1 moment lines), with the
+//   k_adam4           fused low-rank Adam update on the flat low-rank arena (Sec. 2; Alg. 1 moment lines), with the
 //                     low-rank QHM bracket, the column sums of the full-rank QHM scale (Sec. 3.2), the planes of g
 //                     for the error-feedback residual and the up-link buffer (App. A.5.1) as options
 //   k_pq<MODE>        p x q family: outer step (Alg. 1 OuterOpt; App. A.2, D.4), pseudo-gradient anchor - W
@@ -31,7 +31,7 @@ __device__ __forceinline__ void split_bf(float x, uint32_t& hi, uint32_t& lo) {
 }
 
 // ---------------------------------------------------------------------------------------
-// fused low-rank Adam: one thread per 8 consecutive elements of the flat arena
+// fused low-rank Adam: one thread per 4 consecutive elements of the flat arena
 // ---------------------------------------------------------------------------------------
 typedef float f32x4n __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2n __attribute__((ext_vector_type(2)));
@@ -44,105 +44,23 @@ __device__ __forceinline__ f32x4n ld_stream(const float* p) { return __builtin_n
 __device__ __forceinline__ void st_stream(float* p, f32x4n x) { __builtin_nontemporal_store(x, reinterpret_cast<f32x4n*>(p)); }
 // COLSUM: also leave, per column and block of 32 rank indices, the sum of the denominators
 // sqrt(v_hat) + eps (the column scale of the full-rank quasi-hyperbolic update, Sec. 3.2, is their
-// mean over the rank).  Four threads of a workgroup hold the four octets of such a block: their
+// mean over the rank).  Eight threads of a workgroup hold the four octets of such a block: their
 // sums meet in LDS and are added in fixed order.  Padded rank indices contribute eps each; the
 // consumer subtracts that.
+// Four elements per thread: every load and store instruction of a wave covers one dense kilobyte (16 bytes per lane,
+// consecutive lanes consecutive addresses).  With eight elements per thread, as two 16-byte accesses per lane and array,
+// a wave instruction touched every other 16 bytes of two kilobytes and the pass took 15 % longer.
 template <bool COLSUM>
-__global__ __launch_bounds__(256) void k_adam(const float* __restrict__ glow, float* __restrict__ u,
-                                              float* __restrict__ v, uint16_t* __restrict__ n_hi,
-                                              uint16_t* __restrict__ n_lo, int64_t ngroups, AdamArgs a) {
-  __shared__ float part[COLSUM ? 256 : 1];
-  int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const bool live = gidx < ngroups;
-  if (!COLSUM && !live) return;
-  int64_t base = a.first + gidx * 8;
-  float dsum = 0.f;
-  if (live) {
-    float g[8], uu[8], vv[8];
-    {
-      const f32x4n* gp = reinterpret_cast<const f32x4n*>(glow + base);
-      f32x4n a0 = __builtin_nontemporal_load(gp), a1 = __builtin_nontemporal_load(gp + 1);
-      g[0] = a0.x; g[1] = a0.y; g[2] = a0.z; g[3] = a0.w; g[4] = a1.x; g[5] = a1.y; g[6] = a1.z; g[7] = a1.w;
-      int nsplit = a.grp_nsplit[0];
-#pragma unroll
-      for (int i = 1; i < 4; ++i)
-        if (base >= a.grp_start[i]) nsplit = a.grp_nsplit[i];
-      for (int sidx = 1; sidx < nsplit; ++sidx) {         // deterministic split-K reduction, fixed order
-        const f32x4n* sp = reinterpret_cast<const f32x4n*>(glow + sidx * a.split_stride + base);
-        f32x4n b0 = __builtin_nontemporal_load(sp), b1 = __builtin_nontemporal_load(sp + 1);
-        g[0] += b0.x; g[1] += b0.y; g[2] += b0.z; g[3] += b0.w; g[4] += b1.x; g[5] += b1.y; g[6] += b1.z; g[7] += b1.w;
-      }
-      f32x4n u0 = ld_stream(u + base), u1 = ld_stream(u + base + 4);
-      uu[0] = u0.x; uu[1] = u0.y; uu[2] = u0.z; uu[3] = u0.w; uu[4] = u1.x; uu[5] = u1.y; uu[6] = u1.z; uu[7] = u1.w;
-      f32x4n v0 = ld_stream(v + base), v1 = ld_stream(v + base + 4);
-      vv[0] = v0.x; vv[1] = v0.y; vv[2] = v0.z; vv[3] = v0.w; vv[4] = v1.x; vv[5] = v1.y; vv[6] = v1.z; vv[7] = v1.w;
-    }
-    uint32_t hi[8], lo[8];
-    float nv[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float un = fmaf(a.b1, uu[e], a.omb1 * g[e]);
-      float vn = fmaf(a.b2, vv[e], a.omb2 * (g[e] * g[e]));
-      uu[e] = un;
-      vv[e] = vn;
-      const float den = sqrtf(vn * a.inv_c2) + a.eps;
-      dsum += den;
-      // Alg. 1 update bracket: u_hat / den, or (omega u_hat + (1 - omega) g) / den for the low-rank
-      // quasi-hyperbolic case; with qw = 1, qg = 0 the value is bit-identical to u_hat / den
-      float nn = fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;
-      split_bf(nn, hi[e], lo[e]);
-      nv[e] = nn;
-    }
-    if (a.acc) {               // App. A.5.1: sum over the window of eta_t times the low-rank update
-      f32x4n c0 = ld_stream(a.acc + base), c1 = ld_stream(a.acc + base + 4);
-      c0.x = fmaf(a.lr, nv[0], c0.x); c0.y = fmaf(a.lr, nv[1], c0.y); c0.z = fmaf(a.lr, nv[2], c0.z); c0.w = fmaf(a.lr, nv[3], c0.w);
-      c1.x = fmaf(a.lr, nv[4], c1.x); c1.y = fmaf(a.lr, nv[5], c1.y); c1.z = fmaf(a.lr, nv[6], c1.z); c1.w = fmaf(a.lr, nv[7], c1.w);
-      st_stream(a.acc + base, c0);
-      st_stream(a.acc + base + 4, c1);
-    }
-    st_stream(u + base, f32x4n{uu[0], uu[1], uu[2], uu[3]});
-    st_stream(u + base + 4, f32x4n{uu[4], uu[5], uu[6], uu[7]});
-    st_stream(v + base, f32x4n{vv[0], vv[1], vv[2], vv[3]});
-    st_stream(v + base + 4, f32x4n{vv[4], vv[5], vv[6], vv[7]});
-    u32x4n ph, pl;
-    ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
-    pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
-    *reinterpret_cast<u32x4n*>(n_hi + base) = ph;
-    *reinterpret_cast<u32x4n*>(n_lo + base) = pl;
-    if (a.g_hi) {            // error feedback: the summed g as operand planes of the residual update E = A - Q g
-#pragma unroll
-      for (int e = 0; e < 8; ++e) split_bf(g[e], hi[e], lo[e]);
-      ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
-      pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
-      *reinterpret_cast<u32x4n*>(a.g_hi + base) = ph;
-      *reinterpret_cast<u32x4n*>(a.g_lo + base) = pl;
-    }
-  }
-  if constexpr (COLSUM) {
-    // group index = (column block * (rp/8) + octet) * 32 + column; a.first/8 and the group count of every
-    // matrix are multiples of 128, so threadIdx % 128 = (octet % 4) * 32 + column
-    part[threadIdx.x] = dsum;
-    __syncthreads();
-    if (live && (threadIdx.x & 96) == 0) {
-      const int t0 = threadIdx.x;
-      const float sum = ((part[t0] + part[t0 + 32]) + part[t0 + 64]) + part[t0 + 96];
-      // this thread holds octet 4*rb of rank block rb: its group index is (cb*(rp/8) + 4*rb)*32 + column,
-      // and the sum goes to (cb*(rp/32) + rb)*32 + column
-      const int64_t grp = base >> 3;
-      a.colpart[((grp & ~int64_t(31)) >> 2) + (grp & 31)] = sum;
-    }
-  }
-}
-
-// The same update with four elements per thread (all cases but the column sums of the full-rank QHM scale): every
-// load and store instruction of a wave then covers one dense kilobyte (16 bytes per lane, consecutive lanes
-// consecutive addresses) instead of every other 16 bytes of two.
 __global__ __launch_bounds__(256) void k_adam4(const float* __restrict__ glow, float* __restrict__ u,
                                                float* __restrict__ v, uint16_t* __restrict__ n_hi,
                                                uint16_t* __restrict__ n_lo, int64_t nquads, AdamArgs a) {
+  __shared__ float part[COLSUM ? 256 : 1];
   const int64_t qidx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (qidx >= nquads) return;
+  const bool live = qidx < nquads;
+  if (!COLSUM && !live) return;
   const int64_t base = a.first + qidx * 4;
+  float dsum = 0.f;
+  if (live) {
   f32x4n g = __builtin_nontemporal_load(reinterpret_cast<const f32x4n*>(glow + base));
   int nsplit = a.grp_nsplit[0];
 #pragma unroll
@@ -160,7 +78,10 @@ __global__ __launch_bounds__(256) void k_adam4(const float* __restrict__ glow, f
     uu[e] = un;
     vv[e] = vn;
     const float den = sqrtf(vn * a.inv_c2) + a.eps;
-    const float nn = fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;      // the bracket of k_adam, same order
+    dsum += den;
+    // Alg. 1 update bracket: u_hat / den, or (omega u_hat + (1 - omega) g) / den for the low-rank
+    // quasi-hyperbolic case; with qw = 1, qg = 0 the value is bit-identical to u_hat / den
+    const float nn = fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;
     split_bf(nn, hi[e], lo[e]);
     nv[e] = nn;
   }
@@ -184,6 +105,23 @@ __global__ __launch_bounds__(256) void k_adam4(const float* __restrict__ glow, f
     pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
     *reinterpret_cast<u32x2n*>(a.g_hi + base) = ph;
     *reinterpret_cast<u32x2n*>(a.g_lo + base) = pl;
+  }
+  }
+  if constexpr (COLSUM) {
+    // Full-rank QHM scale (Sec. 3.2): per column and block of 32 rank indices, the sum of sqrt(v_hat) + eps.  A group
+    // of eight elements has index (column block * (rp/8) + octet) * 32 + column and is held by two threads; a.first/8
+    // and the group count of every matrix are multiples of 128, so threadIdx = ((octet % 4) * 32 + column) * 2 + half.
+    part[threadIdx.x] = dsum;
+    __syncthreads();
+    if (live && threadIdx.x < 64 && (threadIdx.x & 1) == 0) {
+      const int t0 = threadIdx.x;                    // octet % 4 = 0, half = 0 of its column
+      float sum = 0.f;
+#pragma unroll
+      for (int o = 0; o < 4; ++o) sum += part[t0 + 64 * o] + part[t0 + 64 * o + 1];      // fixed order
+      // this thread's group is (cb*(rp/8) + 4*rb)*32 + column; the sum goes to (cb*(rp/32) + rb)*32 + column
+      const int64_t grp = base >> 3;
+      a.colpart[((grp & ~int64_t(31)) >> 2) + (grp & 31)] = sum;
+    }
   }
 }
 
@@ -216,8 +154,8 @@ hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, ui
   int64_t ngroups = (nelem - a.first) / 8;            // a.first and nelem are multiples of 8
   if (ngroups <= 0) return hipSuccess;
   unsigned blocks = (unsigned)((ngroups + 255) / 256);
-  if (a.colpart) hipLaunchKernelGGL(k_adam<true>, dim3(blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, ngroups, a);
-  else hipLaunchKernelGGL(k_adam4, dim3(2 * blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, 2 * ngroups, a);
+  if (a.colpart) hipLaunchKernelGGL(k_adam4<true>, dim3(2 * blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, 2 * ngroups, a);
+  else hipLaunchKernelGGL(k_adam4<false>, dim3(2 * blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, 2 * ngroups, a);
   return hipGetLastError();
 }
 
