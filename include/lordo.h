@@ -65,13 +65,24 @@ extern "C" {
 
 typedef struct lordo_ctx lordo_ctx;
 
-/* One weight matrix: rows p, cols q, rank r; requires 1 <= r <= p (left projection), r <= 4096,
- * p, q <= 2^20 and p * q < 2^30 (a matrix is addressed with 32-bit byte offsets). */
+/* One weight matrix: rows p, cols q, rank r; requires r <= 4096, p, q <= 2^20 and p * q < 2^30 (a matrix is
+ * addressed with 32-bit byte offsets).
+ *   side 0  projection on the left, as the paper writes it (Sec. 2: Q is p x r, the moments r x q); 1 <= r <= p.
+ *   side 1  projection on the right, the choice that keeps Q and the moments small for a tall matrix (p > q):
+ *           g = (s G) Q_R with Q_R q x r, moments p x r, W <- W - eta N Q_R^T, and the refresh takes the right
+ *           singular subspace of its source.  This is Sec. 2 applied to the transpose of the matrix, and the library
+ *           runs it as exactly that on the caller's row-major p x q arrays (W, G, Src, Delta keep their layout):
+ *           every low-rank array of such a matrix is the one of the TRANSPOSED problem, i.e. Q is q x r, the r x q
+ *           states (u, v, g, N) are r x p, Omega is p x r and the block of lordo_init_projection q x r.
+ *           1 <= r <= q.  Built for the update cases "No QHM" and "Low-Rank QHM" without error feedback and without
+ *           the up-link buffer (LORDO_EINVAL otherwise); its two products of the local step and the products of a
+ *           refresh with the source run in the library's generic grouped GEMM, also for the left-projected matrices
+ *           of the same context in the refresh. */
 typedef struct {
   int64_t rows;
   int64_t cols;
   int32_t rank;
-  int32_t reserved;   /* must be 0 */
+  int32_t side;
 } lordo_shape;
 
 /* Hyper-parameters (Alg. 1 "Require").  Scalars are double so that 1-beta and

@@ -158,6 +158,34 @@ def local_step(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyp
 
 
 # ----------------------------------------------------------------------------
+# projection on the right (Sec. 2 with the roles of rows and columns exchanged)
+# ----------------------------------------------------------------------------
+def local_step_right(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyper,
+                     grad_scale: float = 1.0) -> np.ndarray:
+    """One local step with the projection on the right, written out on the p x q arrays:
+    g = G_hat Q (p x r), Adam moments on g, W <- W - lr N Q^T, with Q of size q x r.  This is Sec. 2's update
+    of the transposed matrix; `st` is the state of that transposed problem (Q: q x r; u, v, last_g, last_N: r x p,
+    i.e. the transposes of the p x r arrays of this function).  Cases "No QHM" and "Low-Rank QHM" only."""
+    assert not hp.error_feedback and hp.qhm_mode != "full" and not hp.uplink_buffer
+    W = np.asarray(W, dtype=F64)
+    G_hat = grad_scale * np.asarray(G, dtype=F64)
+    st.t += 1
+    g = G_hat @ st.Q                                   # p x r
+    u, v = update_moments(st.u.T, st.v.T, g, hp.beta1, hp.beta2)
+    N = low_rank_direction(u, v, g, st.t, hp)          # p x r
+    st.u, st.v = u.T, v.T
+    st.last_g, st.last_N = g.T, N.T
+    return W - lr * (N @ st.Q.T)
+
+
+def refresh_subspace_right(st: MatrixState, A_src: np.ndarray, Omega: np.ndarray, hp: Hyper,
+                           Q_forced: np.ndarray | None = None) -> np.ndarray:
+    """Refresh for the projection on the right: the right singular subspace of the source is the left one of its
+    transpose, so this is ComputeProjection (Sec. 2) on A_src^T, Omega of size p x r, and the same rotation."""
+    return refresh_subspace(st, np.asarray(A_src, dtype=F64).T, Omega, hp, Q_forced)
+
+
+# ----------------------------------------------------------------------------
 # subspace refresh (Sec. 2 "ComputeProjection"; Alg. 1 sync branch)
 # ----------------------------------------------------------------------------
 def svd_projection(A: np.ndarray, r: int) -> np.ndarray:

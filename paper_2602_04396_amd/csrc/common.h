@@ -28,6 +28,8 @@ enum ExtTable : int32_t {       // per-call tables of caller pointers, one entry
 // Per-matrix record in device memory.  Offsets are in BYTES from the arena base unless noted.
 struct MatDev {
   int32_t p, q, r, pp, qp, rp;
+  int32_t tr, pad_;       // tr = 1: projection on the right (Sec. 2 projects the rows; the short side is the usual choice for tall matrices):
+                          // p, q are the dimensions of the TRANSPOSE of the caller's row-major matrix, on which the method runs unchanged
   int64_t q32;            // fp32 p x r plain projection
   int64_t qa_hi, qa_lo;   // bf16 BL(m = row of W, k = rank)      : A operand of the up-projection
   int64_t qt_hi, qt_lo;   // bf16 BL(m = rank, k = row of W)      : A operand of the down-projection
@@ -126,7 +128,7 @@ hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bo
                           const uint16_t* b_lo, const UpArgs& ua, hipStream_t s);
 // gemm32.hip
 hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int tile, int src_is_bf16,
-                         hipStream_t s);
+                         hipStream_t s, float alpha_mul = 1.f);   // alpha_mul scales every product of the launch (per-call coefficients)
 hipError_t launch_gemm_reduce(const DevCtx& d, const GemmDesc* descs, int ndescs, hipStream_t s);
 // elementwise.hip
 // Elements at flat position >= grp_start[i] are the sum of grp_nsplit[i] split-K slices of g.
@@ -188,5 +190,7 @@ hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, con
                               float* dst, int nsplit, int64_t stride, hipStream_t s);
 hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s);
 hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hipStream_t s);
+// right-projected matrices only: plain rows x r block in zw[0] -> slice 0 of the blocked array g (to_lr), or the planes of N -> zw[1]
+hipError_t launch_tr_exchange(const DevCtx& d, bool to_lr, float* glow, const uint16_t* n_hi, const uint16_t* n_lo, hipStream_t s);
 
 }  // namespace lordo

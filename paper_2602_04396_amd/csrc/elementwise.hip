@@ -6,7 +6,7 @@
 //                     (App. A.1), anchor copy, and the part of the outer step that does not depend on Delta
 //   k_fold_grad       E <- E + s G, the projection source of the local variant (Alg. 2)
 //   k_pack_q / k_pack_y / k_pack_block / k_split_planes   fp32 -> bf16 hi/lo operand planes in matrix-core order
-//   k_glow_to_z, k_lr_to_plain, k_plain_to_lr, k_lr_exchange   between the operand layout of the low-rank state and plain buffers
+//   k_glow_to_z, k_lr_to_plain, k_plain_to_lr, k_lr_exchange, k_tr_exchange   between the operand layout of the low-rank state and plain buffers
 //   k_gram_shift, k_potf2, k_diag_inverses   CholeskyQR: diagonal shift, Cholesky of a diagonal block and its inverse
 //   k_jacobi_svd      singular vectors of the Cholesky factor of the r x r Ritz matrix (Rayleigh-Ritz step: basis ordered as in Sec. 2's SVD projection)
 //   k_frob2_chunks / k_frob2_sum / k_stable_rank   squared Frobenius norm of the refresh source and its stable rank (Sec. 5.1)
@@ -1318,6 +1318,28 @@ __global__ __launch_bounds__(256) void k_lr_exchange(DevCtx d, float* lr_arr) {
 hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hipStream_t s) {
   if (to_plain) hipLaunchKernelGGL(k_lr_exchange<true>, dim3(64, d.n), dim3(256), 0, s, d, lr_arr);
   else hipLaunchKernelGGL(k_lr_exchange<false>, dim3(64, d.n), dim3(256), 0, s, d, lr_arr);
+  return hipGetLastError();
+}
+
+// Right-projected matrices (m.tr): the generic GEMM leaves g as the plain q x r block zw[0] and reads N as the plain
+// block zw[1]; the Adam kernel works on the blocked arrays.  TO_LR: slice 0 of g <- zw[0]; else zw[1] <- N (hi + lo).
+template <bool TO_LR>
+__global__ __launch_bounds__(256) void k_tr_exchange(DevCtx d, float* glow, const uint16_t* n_hi, const uint16_t* n_lo) {
+  const int mat = blockIdx.y;
+  const MatDev& m = d.mats[mat];
+  if (!m.tr) return;
+  float* plain = reinterpret_cast<float*>(d.arena + (TO_LR ? m.zw[0] : m.zw[1]));
+  const int64_t total = (int64_t)m.r * m.q;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t j = t / m.r, i = t % m.r;                      // column j of the low-rank state, rank index i
+    const int64_t at = m.lr_off + bl_index(j, i, m.rp);
+    if (TO_LR) glow[at] = plain[t];
+    else plain[t] = bf2f(n_hi[at]) + bf2f(n_lo[at]);
+  }
+}
+hipError_t launch_tr_exchange(const DevCtx& d, bool to_lr, float* glow, const uint16_t* n_hi, const uint16_t* n_lo, hipStream_t s) {
+  if (to_lr) hipLaunchKernelGGL(k_tr_exchange<true>, dim3(64, d.n), dim3(256), 0, s, d, glow, n_hi, n_lo);
+  else hipLaunchKernelGGL(k_tr_exchange<false>, dim3(64, d.n), dim3(256), 0, s, d, glow, n_hi, n_lo);
   return hipGetLastError();
 }
 

@@ -321,7 +321,7 @@ __device__ __forceinline__ void gemm_loop_bf(f32x16 (&acc)[WB][WB], const Operan
 // is fetched into registers while the matrix cores work on the one in LDS.
 template <int WB>
 __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __restrict__ descs,
-                                                const GemmTile* __restrict__ tiles, int src_is_bf16) {
+                                                const GemmTile* __restrict__ tiles, int src_is_bf16, float alpha_mul) {
   constexpr int TM = 64 * WB, TN = 64 * WB;
   constexpr int PITCH = TM + 4;
   constexpr int NV = TM * TK / 4 / 256;
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
           Pp[(int64_t)row * N + col] = acc[a][b][v];
         } else if (row < M) {
           int64_t o = (int64_t)row * g.ldc + col;
-          float val = g.alpha * acc[a][b][v];
+          float val = g.alpha * alpha_mul * acc[a][b][v];
           if (g.beta != 0.f) val = fmaf(g.beta, C[o], val);
           C[o] = val;
           if (C2) C2[o] = val * val;
@@ -428,10 +428,10 @@ hipError_t launch_gemm_reduce(const DevCtx& d, const GemmDesc* descs, int ndescs
 }
 
 hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int tile, int src_is_bf16,
-                         hipStream_t s) {
+                         hipStream_t s, float alpha_mul) {
   if (ntiles <= 0) return hipSuccess;
-  if (tile == 128) hipLaunchKernelGGL((k_gemm32<2>), dim3(ntiles), dim3(256), 0, s, d, descs, tiles, src_is_bf16);
-  else hipLaunchKernelGGL((k_gemm32<1>), dim3(ntiles), dim3(256), 0, s, d, descs, tiles, src_is_bf16);
+  if (tile == 128) hipLaunchKernelGGL((k_gemm32<2>), dim3(ntiles), dim3(256), 0, s, d, descs, tiles, src_is_bf16, alpha_mul);
+  else hipLaunchKernelGGL((k_gemm32<1>), dim3(ntiles), dim3(256), 0, s, d, descs, tiles, src_is_bf16, alpha_mul);
   return hipGetLastError();
 }
 

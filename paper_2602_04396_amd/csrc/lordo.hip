@@ -73,6 +73,8 @@ struct Plan {
   std::vector<Op> ops;              // the refresh
   std::vector<Op> init_ops;         // Q_0 from a caller-supplied block: copy, orthonormalise, pack
   std::vector<Op> gap_ops;          // estimate of sigma_{r+1} of a source (Rayleigh-Ritz option)
+  bool any_tr = false;              // some matrix is projected on the right
+  std::vector<Op> tr_down_ops, tr_up_ops;   // their two products of the local step, by the generic GEMM
 };
 
 constexpr int MAX_KSPLIT = 16;
@@ -186,6 +188,14 @@ struct ProgramBuilder {
     op.ndescs = (int)P.desc_h.size() - op.desc_first;
     op.ntiles = (int)P.gtile_h.size() - op.tile_first;
     P.ops.push_back(op);
+  }
+  // A operand = the source (transposed: its transpose).  The source of a right-projected matrix is the caller's
+  // row-major array read as its transpose: element (i, j) of the p x q matrix at j * p + i.
+  static void src_operand(GemmDesc& g, const MatDev& m, bool transposed) {
+    g.A = ref_ext(EXT_SRC); g.a_bf16 = 2; g.prec = 1;
+    const int64_t s_row = m.tr ? 1 : m.q, s_col = m.tr ? m.p : 1;
+    g.sAm = transposed ? s_col : s_row;
+    g.sAk = transposed ? s_row : s_col;
   }
   void simple(int kind, int iarg = 0, float farg = 0.f, bool rot_only = false) {
     Op op;
@@ -340,7 +350,7 @@ struct ProgramBuilder {
     auto z_product = [&](int ycur) {    // Z = Src^T Y
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2; g.prec = 1;
+        src_operand(g, m, true);
         g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.zw[0]); g.ldc = m.r;
         g.M = m.q; g.N = m.r; g.K = m.p;
@@ -352,7 +362,7 @@ struct ProgramBuilder {
     auto y_product = [&](int ext_or_z) {   // Y = Src B, B = Omega (-1) or the block in zw[ext_or_z]
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2; g.prec = 1;
+        src_operand(g, m, false);
         g.B = ext_or_z < 0 ? ref_ext(EXT_OMEGA) : ref_arena(m.zw[ext_or_z]); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.y[0]); g.ldc = m.r;
         g.M = m.p; g.N = m.r; g.K = m.q;
@@ -393,12 +403,42 @@ struct ProgramBuilder {
 
   // passes = 3 is the robust variant: two shifted passes after every product of the power iteration (the conditioning
   // of the source then does not compound from product to product) and shifted, shifted, plain at the end.
+  // Local step of the right-projected matrices (Sec. 2 with the roles of rows and columns exchanged), on the caller's
+  // row-major arrays: g^T = (s G) Q into zw[0], and W <- W - eta N^T Q^T with N^T read from zw[1]; the scale s and
+  // the step size multiply the launch (they change per call).
+  void build_tr_step(bool g_bf16) {
+    std::vector<Op> keep;
+    keep.swap(P.ops);
+    gemm([&](int i, GemmDesc& g) {
+      const MatDev& m = P.mat[i];
+      if (!m.tr) return false;
+      g.A = ref_ext(EXT_G); g.sAm = m.p; g.sAk = 1; g.a_bf16 = g_bf16 ? 1 : 0;
+      g.B = ref_arena(m.q32); g.sBk = m.r; g.sBn = 1;
+      g.C = ref_arena(m.zw[0]); g.ldc = m.r;
+      g.M = m.q; g.N = m.r; g.K = m.p;
+      return true;
+    });
+    P.tr_down_ops.swap(P.ops);
+    gemm([&](int i, GemmDesc& g) {
+      const MatDev& m = P.mat[i];
+      if (!m.tr) return false;
+      g.A = ref_arena(m.zw[1]); g.sAm = m.r; g.sAk = 1;
+      g.B = ref_arena(m.q32); g.sBk = 1; g.sBn = m.r;
+      g.C = ref_ext(EXT_W); g.ldc = m.p;
+      g.M = m.q; g.N = m.p; g.K = m.r;
+      g.alpha = -1.f; g.beta = 1.f;
+      return true;
+    });
+    P.tr_up_ops.swap(P.ops);
+    keep.swap(P.ops);
+  }
+
   void build(int power_iters, int passes, bool rayleigh_ritz) {
     const int inner = passes >= 3 ? 2 : 1, nshift = passes >= 3 ? 2 : 1;
     // Y = Src Omega
     gemm([&](int i, GemmDesc& g) {
       const MatDev& m = P.mat[i];
-      g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2; g.prec = 1;
+      src_operand(g, m, false);
       g.B = ref_ext(EXT_OMEGA); g.sBk = m.r; g.sBn = 1;
       g.C = ref_arena(m.y[0]); g.ldc = m.r;
       g.M = m.p; g.N = m.r; g.K = m.q;
@@ -414,7 +454,7 @@ struct ProgramBuilder {
       // Z = Src^T Y
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2; g.prec = 1;
+        src_operand(g, m, true);
         g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.zw[0]); g.ldc = m.r;
         g.M = m.q; g.N = m.r; g.K = m.p;
@@ -426,7 +466,7 @@ struct ProgramBuilder {
       // Y = Src Z
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        g.A = ref_ext(EXT_SRC); g.sAm = m.q; g.sAk = 1; g.a_bf16 = 2; g.prec = 1;
+        src_operand(g, m, false);
         g.B = ref_arena(m.zw[zcur]); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.y[0]); g.ldc = m.r;
         g.M = m.p; g.N = m.r; g.K = m.q;
@@ -441,7 +481,7 @@ struct ProgramBuilder {
       // Z = Src^T Y (= B^T, B the source restricted to the subspace), T = Z^T Z = B B^T, T = U diag U^T, Y <- Y U
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        g.A = ref_ext(EXT_SRC); g.sAm = 1; g.sAk = m.q; g.a_bf16 = 2; g.prec = 1;
+        src_operand(g, m, true);
         g.B = ref_arena(m.y[ycur]); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.zw[0]); g.ldc = m.r;
         g.M = m.q; g.N = m.r; g.K = m.p;
@@ -504,9 +544,15 @@ struct ProgramBuilder {
 
 int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
   if (!shapes || !hp || n <= 0) return LORDO_EINVAL;
+  if (hp->qhm_mode < 0 || hp->qhm_mode > 2 || (hp->error_feedback != 0 && hp->error_feedback != 1)) return LORDO_EINVAL;
+  if (hp->uplink_buffer != 0 && hp->uplink_buffer != 1) return LORDO_EINVAL;
   for (int i = 0; i < n; ++i) {
     const lordo_shape& s = shapes[i];
-    if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || s.rank > s.rows || s.reserved != 0) return LORDO_EINVAL;
+    if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || (s.side != 0 && s.side != 1)) return LORDO_EINVAL;
+    if (s.rank > (s.side ? s.cols : s.rows)) return LORDO_EINVAL;
+    // projection on the right: the plain and the low-rank QHM update only (the other update cases fuse their
+    // gradient terms into the kernels of the left projection)
+    if (s.side && (hp->error_feedback || hp->qhm_mode == 2 || hp->uplink_buffer)) return LORDO_EINVAL;
     // (tile coordinates of the grouped GEMM are 16-bit: at most 32767 tiles of 64 rows)
     if (s.rows > (1 << 20) || s.cols > (1 << 20) || s.rank > 4096) return LORDO_EINVAL;
     // the kernels address a matrix through buffer descriptors with 32-bit byte offsets: p * q * 4 bytes must stay below 4 GiB
@@ -541,12 +587,14 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   const bool has_mom = hp.outer_momentum != 0.0;
   for (int i = 0; i < n; ++i) {
     MatDev& m = P.mat[i];
-    m.p = (int)shapes[i].rows; m.q = (int)shapes[i].cols; m.r = shapes[i].rank;
+    m.tr = shapes[i].side;
+    m.p = (int)(m.tr ? shapes[i].cols : shapes[i].rows); m.q = (int)(m.tr ? shapes[i].rows : shapes[i].cols); m.r = shapes[i].rank;
+    if (m.tr) P.any_tr = true;
     m.pp = (int)pad32(m.p); m.qp = (int)pad32(m.q); m.rp = (int)pad32(m.r);
     rp_max = std::max(rp_max, m.rp);
     P.r_max = std::max(P.r_max, (int)m.r);
     P.rank_sq_sum += (int64_t)m.r * m.r;
-    pp_min = std::min(pp_min, m.pp);
+    if (!m.tr) pp_min = std::min(pp_min, m.pp);
     P.chunk_start_h[i] = chunks;
     chunks += ((int64_t)m.p * m.q + CHUNK - 1) / CHUNK;
   }
@@ -570,10 +618,10 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the Adam kernel.  Factors are powers of two up to 8.
   int64_t tiles0 = 0;
   for (int i = 0; i < n; ++i)
-    tiles0 += (int64_t)((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + P.rank_tile - 1) / P.rank_tile);
+    if (!P.mat[i].tr) tiles0 += (int64_t)((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + P.rank_tile - 1) / P.rank_tile);
   P.splits.assign(n, 1);
   P.nsplit = 1;
-  if (tiles0 < 1536) {
+  if (tiles0 > 0 && tiles0 < 1536) {
     // slices of about the shortest matrix's height; halved while the launch would still have fewer
     // than about 1.5 workgroups per compute unit (a single tall matrix, for instance)
     int chunk = std::max(256, pp_min);
@@ -582,6 +630,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
       bool can_grow = false;
       P.nsplit = 1;
       for (int i = 0; i < n; ++i) {
+        if (P.mat[i].tr) continue;       // right-projected matrices take the generic GEMM: one slice
         int want = (P.mat[i].pp + chunk - 1) / chunk;
         int f = 1;
         while (f * 2 <= want && f < 8) f *= 2;
@@ -618,7 +667,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the launch has several rounds of workgroups and the epilogue of one overlaps the main loop of
   // another; a launch that needs split-K is a single round of workgroups in lock step, where the
   // stand-alone kernel is as fast and leaves the down-projection shorter.
-  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0 && !hp.uplink_buffer && !hp.error_feedback;
+  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0 && !hp.uplink_buffer && !hp.error_feedback && !P.any_tr;
   P.adam_first = fuse_adam ? lr : 0;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);
@@ -652,6 +701,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   std::vector<ProjTile> down, up;
   for (int i = 0; i < n; ++i) {
     const MatDev& m = P.mat[i];
+    if (m.tr) continue;               // no tiles of the projection kernels
     const int f = P.splits[i];
     const int klen = ((m.pp + f - 1) / f + 31) / 32 * 32;
     for (int n0 = 0; n0 < m.qp; n0 += down_bn)
@@ -688,7 +738,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     P.y_fast_shapes = true;
     for (int i : order) {
       const MatDev& m = P.mat[i];
-      if ((m.q & 31) != 0 || (m.r & 3) != 0) P.y_fast_shapes = false;
+      if ((m.q & 31) != 0 || (m.r & 3) != 0 || m.tr) P.y_fast_shapes = false;
       for (int m0 = 0; m0 < m.pp; m0 += 128)
         for (int n0 = 0; n0 < m.rp; n0 += 128) {
           ProjTile t{};
@@ -704,6 +754,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes, hp.rayleigh_ritz != 0);
   if (hp.rayleigh_ritz) pb.build_gap(2, hp.orth_passes == 0 ? 2 : hp.orth_passes);
   pb.build_init(hp.orth_passes == 0 ? 2 : hp.orth_passes);
+  if (P.any_tr) pb.build_tr_step(hp.grad_dtype == LORDO_BF16);
   P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
   P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());
   P.bytes = A.cur;
@@ -840,8 +891,8 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
   INITCHK(hipStreamSynchronize(s));
   INITCHK(hipMemcpy(c->at<void>(P.mats), P.mat.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
   INITCHK(hipMemcpy(c->at<void>(P.chunk_start), P.chunk_start_h.data(), sizeof(int64_t) * (n + 1), hipMemcpyHostToDevice));
-  INITCHK(hipMemcpy(c->at<void>(P.down_tiles), P.down_h.data(), sizeof(ProjTile) * P.down_h.size(), hipMemcpyHostToDevice));
-  INITCHK(hipMemcpy(c->at<void>(P.up_tiles), P.up_h.data(), sizeof(ProjTile) * P.up_h.size(), hipMemcpyHostToDevice));
+  if (!P.down_h.empty()) INITCHK(hipMemcpy(c->at<void>(P.down_tiles), P.down_h.data(), sizeof(ProjTile) * P.down_h.size(), hipMemcpyHostToDevice));
+  if (!P.up_h.empty()) INITCHK(hipMemcpy(c->at<void>(P.up_tiles), P.up_h.data(), sizeof(ProjTile) * P.up_h.size(), hipMemcpyHostToDevice));
   INITCHK(hipMemcpy(c->at<void>(P.ytiles), P.ytile_h.data(), sizeof(ProjTile) * P.ytile_h.size(), hipMemcpyHostToDevice));
   if (!P.desc_h.empty())
     INITCHK(hipMemcpy(c->at<void>(P.descs), P.desc_h.data(), sizeof(GemmDesc) * P.desc_h.size(), hipMemcpyHostToDevice));
@@ -901,11 +952,11 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   a.lr = (float)lr;
   const bool g_f32 = c->hp.grad_dtype == LORDO_F32;
   bool g_vec = true;            // 4-byte accesses to a bf16 G need an even q and 4-byte aligned pointers
-  for (int i = 0; i < c->n; ++i)
-    if ((P.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 3) != 0) { g_vec = false; break; }
+  for (int i = 0; i < c->n; ++i)      // (right-projected matrices do not pass through the projection kernels)
+    if (!P.mat[i].tr && ((P.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 3) != 0)) { g_vec = false; break; }
   bool w_vec = true;            // 16-byte accesses to W need q % 4 == 0 and 16-byte aligned pointers
   for (int i = 0; i < c->n; ++i)
-    if ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
+    if (!P.mat[i].tr && ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0)) { w_vec = false; break; }
   if (qhm_full || ef) {         // the gradient-term epilogue reads four columns of G per lane
     if (!w_vec) return LORDO_EINVAL;
     for (int i = 0; i < c->n; ++i)
@@ -918,9 +969,15 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   c->prof.begin(LORDO_K_DOWN, s);
   bool g_tr = true;             // 16-byte global-to-LDS loads of G need q % 8 == 0 and 16-byte aligned pointers
   for (int i = 0; i < c->n && g_tr; ++i)
-    if ((P.mat[i].q & 7) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 15) != 0) g_tr = false;
-  HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, g_tr, P.g_once, c->at<float>(P.glow),
-                          P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
+    if (!P.mat[i].tr && ((P.mat[i].q & 7) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 15) != 0)) g_tr = false;
+  if (!P.down_h.empty())
+    HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, g_tr, P.g_once, c->at<float>(P.glow),
+                            P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
+  if (P.any_tr) {               // g^T = (s G) Q by the generic GEMM, then into the blocked array the Adam kernel reads
+    for (const Op& op : P.tr_down_ops)
+      HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, (float)grad_scale));
+    HIPCHK(launch_tr_exchange(c->dev, true, c->at<float>(P.glow), nullptr, nullptr, s));
+  }
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
   if (P.adam_first < P.lr_total)
@@ -944,8 +1001,14 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   } else {
     ua.coef_acc = (float)-lr; ua.coef_g = 0.f; ua.colscale = 0; ua.colpart = nullptr;
   }
-  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
-                        c->at<uint16_t>(P.n_lo), ua, s));
+  if (!P.up_h.empty())
+    HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
+                          c->at<uint16_t>(P.n_lo), ua, s));
+  if (P.any_tr) {               // W <- W - eta N^T Q^T on the caller's rows
+    HIPCHK(launch_tr_exchange(c->dev, false, nullptr, c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), s));
+    for (const Op& op : P.tr_up_ops)
+      HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, (float)lr));
+  }
   c->prof.end(LORDO_K_UP, s);
   c->t = t;
   c->grad_folded = false;
@@ -1041,7 +1104,7 @@ static int source_paths(lordo_ctx* c, const void* const* Src, int32_t src_dtype,
   // a bf16 source with the alignment the pipelined down-projection kernel reads gradients with lets that
   // kernel take the products of the power iteration that have its shape
   // (an fp32 source too: that kernel then stages it as bf16 hi + lo planes, as it does the error-feedback sum)
-  bool proj_kernels = c->plan.down_pipe != 0;
+  bool proj_kernels = c->plan.down_pipe != 0 && !c->plan.any_tr;      // a right-projected matrix: the generic products for all
   const uintptr_t pair_mask = src_dtype == LORDO_BF16 ? 3 : 7;       // two adjacent columns with one access
   for (int i = 0; i < c->n && proj_kernels; ++i)
     if ((c->plan.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & pair_mask) != 0) proj_kernels = false;

@@ -28,7 +28,7 @@ K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
 
 class Shape(C.Structure):
-    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("rank", C.c_int32), ("reserved", C.c_int32)]
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("rank", C.c_int32), ("side", C.c_int32)]
 
 
 class HParams(C.Structure):
@@ -127,8 +127,8 @@ def _ptr_array(tensors):
 
 def _shape_array(shapes):
     arr = (Shape * len(shapes))()
-    for i, (p, q, r) in enumerate(shapes):
-        arr[i] = Shape(p, q, r, 0)
+    for i, sh in enumerate(shapes):      # (p, q, r) or (p, q, r, side); side 1 = projection on the right
+        arr[i] = Shape(sh[0], sh[1], sh[2], sh[3] if len(sh) > 3 else 0)
     return arr
 
 
@@ -172,8 +172,11 @@ class Lordo:
             return
         if len(ts) != self.n:
             raise ValueError("one tensor per matrix expected")
-        for t, (p, q, r) in zip(ts, self.shapes):
-            want = {"pq": (p, q), "qr": (q, r), "rq": (r, q), "pr": (p, r)}[kind]
+        for t, sh in zip(ts, self.shapes):
+            p, q, r = sh[:3]
+            # low-rank arrays of a right-projected matrix are those of the transposed problem
+            tp, tq = (q, p) if len(sh) > 3 and sh[3] else (p, q)
+            want = {"pq": (p, q), "qr": (tq, r), "rq": (r, tq), "pr": (tp, r)}[kind]
             if tuple(t.shape) != want or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
                 raise ValueError(f"expected contiguous CUDA {dtype} tensor of shape {want}, got {t.dtype} {tuple(t.shape)}")
 
@@ -256,8 +259,10 @@ class Lordo:
 
     # -- state ------------------------------------------------------------------------------------
     def _state_shape(self, mat, which):
-        p, q, r = self.shapes[mat]
-        return {STATE_Q: (p, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q), STATE_ERR: (p, q), STATE_RITZ: (r,)}.get(which, (r, q))
+        sh = self.shapes[mat]
+        p, q, r = sh[:3]
+        tp, tq = (q, p) if len(sh) > 3 and sh[3] else (p, q)
+        return {STATE_Q: (tp, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q), STATE_ERR: (p, q), STATE_RITZ: (r,)}.get(which, (r, tq))
 
     def get_state(self, mat, which):
         out = self.torch.empty(self._state_shape(mat, which), dtype=self.torch.float32, device=self.arena.device)

@@ -47,9 +47,13 @@ class Pair:
         self.W0 = [w.copy() for w in self.W_orc]
         self.opt = lordo.Lordo(shapes, gpu_hp, self.W_gpu, torch)
         self.st = []
-        for i, (p, q, r) in enumerate(shapes):
+        # a shape may carry a fourth entry, side: 1 = projection on the right; the oracle state of such a matrix is
+        # the state of the transposed problem (as the library's low-rank arrays are)
+        self.side = [int(sh[3]) if len(sh) > 3 else 0 for sh in shapes]
+        for i, sh in enumerate(shapes):
+            r = sh[2]
             q0 = None if Q0 is None else Q0[i]
-            self.st.append(orc.init_state(self.W_orc[i], r, q0))
+            self.st.append(orc.init_state(self.W_orc[i].T if self.side[i] else self.W_orc[i], r, q0))
             if q0 is not None:
                 self.opt.set_state(i, lordo.STATE_Q, torch.tensor(q0, dtype=torch.float32, device=self.dev).contiguous())
                 # the oracle continues from the fp32 value the library was given
@@ -75,8 +79,8 @@ class Pair:
         self.torch.cuda.synchronize()
         patched = 0
         for i in range(len(self.shapes)):
-            self.W_orc[i] = orc.local_step(self.st[i], self.W_orc[i], np.asarray(G[i], dtype=np.float64), lr, self.ohp,
-                                           grad_scale)
+            step = orc.local_step_right if self.side[i] else orc.local_step
+            self.W_orc[i] = step(self.st[i], self.W_orc[i], np.asarray(G[i], dtype=np.float64), lr, self.ohp, grad_scale)
             if first_step_patch:
                 patched += self._patch_sign_ambiguous(i, lr)
         return patched
@@ -96,7 +100,8 @@ class Pair:
         N_new = st.last_N.copy()
         N_new[amb] = N_gpu[amb]
         weight = self.ohp.omega if self.ohp.qhm_mode == "full" else 1.0      # share of Q N in the update
-        self.W_orc[i] = self.W_orc[i] + lr * weight * st.Q @ (st.last_N - N_new)
+        fix = lr * weight * st.Q @ (st.last_N - N_new)
+        self.W_orc[i] = self.W_orc[i] + (fix.T if self.side[i] else fix)
         if self.ohp.uplink_buffer:
             st.A = st.A + lr * (N_new - st.last_N)
         st.last_N = N_new
@@ -138,11 +143,12 @@ class Pair:
         self.opt.refresh_subspace(Sd, Od)
         self.opt.poll_status()
         dists, orths = [], []
-        for i, (p, q, r) in enumerate(self.shapes):
+        for i, sh in enumerate(self.shapes):
+            r = sh[2]
             Qg = self.get(i, L.STATE_Q)
             orths.append(float(np.linalg.norm(Qg.T @ Qg - np.eye(r))))
-            Qo = orc.range_finder(np.asarray(Src[i], dtype=np.float64), np.asarray(Omega[i], dtype=np.float64),
-                                  self.ohp.power_iters)
+            src = np.asarray(Src[i], dtype=np.float64)
+            Qo = orc.range_finder(src.T if self.side[i] else src, np.asarray(Omega[i], dtype=np.float64), self.ohp.power_iters)
             dists.append(projector_distance(Qg, Qo))
             orc.refresh_subspace(self.st[i], None, None, self.ohp, Q_forced=Qg)
         return dists, orths

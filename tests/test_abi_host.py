@@ -65,6 +65,24 @@ def test_workspace_bytes_scales_and_validates(lib):
         assert e.value.code == lordo.EINVAL
 
 
+def test_right_projection_validation(lib):
+    hp = lordo.hparams()
+    tall = lordo.workspace_bytes([(3072, 768, 128, 1)], hp)       # projection on the short side: Q 768 x 128, moments 128 x 3072
+    assert 0 < tall
+    with pytest.raises(lordo.LordoError) as e:                     # rank is bounded by the projected side: the columns
+        lordo.workspace_bytes([(64, 32, 33, 1)], hp)
+    assert e.value.code == lordo.EINVAL
+    assert lordo.workspace_bytes([(32, 64, 33, 1)], hp) > 0        # ... and not by the rows
+    with pytest.raises(lordo.LordoError):
+        lordo.workspace_bytes([(64, 32, 8, 2)], hp)
+    # built for the plain and the low-rank QHM update
+    assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(qhm_mode=1, omega=0.9)) > 0
+    for bad in (lordo.hparams(error_feedback=True), lordo.hparams(qhm_mode=2, omega=0.9), lordo.hparams(uplink_buffer=True)):
+        with pytest.raises(lordo.LordoError) as e:
+            lordo.workspace_bytes([(64, 32, 8, 1)], bad)
+        assert e.value.code == lordo.EINVAL
+
+
 def test_strerror_and_null_handling(lib):
     assert lib.lordo_strerror(0) == b"ok"
     for code in (-1, -2, -3, -4, -5):

@@ -663,3 +663,50 @@ def test_comm_ratios_golden():
     assert abs(lowrank - val) / val < tol
     val, tol = quoted["vs_fullrank_ddp"]
     assert abs(fullrank - val) / val < tol
+
+
+# ---------------------------------------------------------------------------------------------
+# projection on the right (Sec. 2 applied to the transposed matrix)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("qhm", ["none", "low"])
+def test_right_projection_is_the_method_on_the_transpose(qhm):
+    """The explicit right-side formulas (g = G Q, W -= lr N Q^T) against the left-side functions run on
+    W^T, G^T: two code paths, one result, over steps and a refresh."""
+    rng = np.random.default_rng(77)
+    p, q, r = 23, 11, 4
+    hp = orc.Hyper(qhm_mode=qhm, omega=0.7 if qhm == "low" else 1.0, power_iters=1)
+    W = rng.standard_normal((p, q))
+    Q0 = np.linalg.qr(rng.standard_normal((q, r)))[0]
+    a, b = orc.init_state(W.T, r, Q0), orc.init_state(W.T, r, Q0)
+    Wa, Wb = W.copy(), W.T.copy()
+    for t in range(3):
+        G = rng.standard_normal((p, q))
+        Wa = orc.local_step_right(a, Wa, G, 1e-2, hp, grad_scale=0.5)
+        Wb = orc.local_step(b, Wb, G.T, 1e-2, hp, grad_scale=0.5)
+        np.testing.assert_allclose(Wa, Wb.T, rtol=0, atol=1e-14)
+        np.testing.assert_allclose(a.last_N, b.last_N, rtol=0, atol=1e-13)
+    Src, Om = rng.standard_normal((p, q)), rng.standard_normal((p, r))
+    Qa = orc.refresh_subspace_right(a, Src, Om, hp)
+    Qb = orc.refresh_subspace(b, Src.T, Om, hp)
+    np.testing.assert_allclose(Qa, Qb, rtol=0, atol=1e-14)
+    # the new basis spans the top right singular vectors' neighbourhood: Src Q Q^T keeps more of Src than any r coordinates
+    assert Qa.shape == (q, r) and np.allclose(Qa.T @ Qa, np.eye(r), atol=1e-12)
+    np.testing.assert_allclose(a.u, b.u, rtol=0, atol=1e-14)
+
+
+def test_right_projection_full_rank_identity_is_adam():
+    """r = q and Q = I: the right-projected step is Adam on the full gradient; first step in closed form
+    (bias-corrected moments equal g and g^2, so N = g / (|g| + eps))."""
+    rng = np.random.default_rng(78)
+    p, q = 9, 5
+    hp = orc.Hyper()
+    W, G = rng.standard_normal((p, q)), rng.standard_normal((p, q))
+    st = orc.init_state(W.T, q, np.eye(q))
+    W1 = orc.local_step_right(st, W, G, 1e-3, hp)
+    np.testing.assert_allclose(W1, W - 1e-3 * G / (np.abs(G) + hp.eps), rtol=1e-12, atol=1e-15)
+    # a gradient orthogonal to the columns of Q projects to rounding noise (which eps = 1e-8 in the denominator
+    # turns into at most 1e-8 per element of N): W stays where it is
+    Q = np.linalg.qr(rng.standard_normal((q, 2)))[0]
+    st = orc.init_state(W.T, 2, Q)
+    G_perp = rng.standard_normal((p, q)) @ (np.eye(q) - Q @ Q.T)
+    np.testing.assert_allclose(orc.local_step_right(st, W, G_perp, 1e-3, hp), W, rtol=0, atol=1e-9)
