@@ -55,6 +55,9 @@ def parse():
                     help="update case of the local step: plain (default, the headline), low-rank / full-rank QHM (omega 0.9), "
                          "error feedback, global = full-rank QHM + error feedback (the paper's LoRDO-Global), local = low-rank QHM + error "
                          "feedback with the refresh of Alg. 2, uplink = plain with the r x q up-link buffer and the outer step fed from it")
+    ap.add_argument("--short-side", action="store_true",
+                    help="project every matrix with more rows than columns on the right (shape field side = 1); "
+                         "update cases plain and low-qhm")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 1 GiB device copies (known traffic) to scale the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
@@ -265,7 +268,17 @@ def main():
                        grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
                        qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef, uplink_buffer=uplink,
                        rayleigh_ritz=args.rayleigh_ritz)
-    opt = lordo.Lordo(shapes, hp, W, torch)
+    if args.short_side:
+        if args.update not in ("plain", "low-qhm"):
+            sys.exit("--short-side: the projection on the right is built for --update plain and low-qhm")
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(synth.seed_for(int(cfg[1:]), 997))
+        lib_shapes = [(p, q, r, 1) if p > q else (p, q, r) for p, q, r in shapes]
+        Omega = [torch.randn(p if p > q else q, r, generator=gen, device="cuda") for p, q, r in shapes]
+        shapes = [(q, p, r) if p > q else (p, q, r) for p, q, r in shapes]      # the transposed problems, for the work counts
+    else:
+        lib_shapes = shapes
+    opt = lordo.Lordo(lib_shapes, hp, W, torch)
     Wp = opt.ptrs(W)
     Gp = [opt.ptrs(g, grad_dtype) for g in G]
     Dp = opt.ptrs(D)
@@ -344,7 +357,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, shapes, outer_every, refresh_every, d["power_iters"])
+        cpu = None if args.short_side else cpu_baseline(cfg, shapes, outer_every, refresh_every, d["power_iters"])
 
     out = {
         "metric": "full-model low-rank optimizer step ms",
@@ -356,7 +369,7 @@ def main():
                    "matrices": len(shapes), "params": sum(p * q for p, q, r in shapes),
                    "refresh_every": refresh_every, "outer_every": outer_every, "power_iters": d["power_iters"],
                    "grad_sets": n_sets, "outer": "nesterov lr 0.7 momentum 0.9 on a generated averaged pseudo-gradient",
-                   "update": args.update, "rayleigh_ritz": bool(args.rayleigh_ritz)},
+                   "update": args.update, "rayleigh_ritz": bool(args.rayleigh_ritz), "short_side": bool(args.short_side)},
         "roofline": roofline,
         "kernels": kernels,
         "cpu_baseline": cpu,

@@ -190,7 +190,7 @@ hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, con
                               float* dst, int nsplit, int64_t stride, hipStream_t s);
 hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s);
 hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hipStream_t s);
-// right-projected matrices only: plain rows x r block in zw[0] -> slice 0 of the blocked array g (to_lr), or the planes of N -> zw[1]
-hipError_t launch_tr_exchange(const DevCtx& d, bool to_lr, float* glow, const uint16_t* n_hi, const uint16_t* n_lo, hipStream_t s);
+// right-projected matrices only: slice 0 of the blocked array g <- scale * (plain rows x r block in zw[0])
+hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, hipStream_t s);
 
 }  // namespace lordo

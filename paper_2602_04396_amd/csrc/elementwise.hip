@@ -1321,25 +1321,22 @@ hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hip
   return hipGetLastError();
 }
 
-// Right-projected matrices (m.tr): the generic GEMM leaves g as the plain q x r block zw[0] and reads N as the plain
-// block zw[1]; the Adam kernel works on the blocked arrays.  TO_LR: slice 0 of g <- zw[0]; else zw[1] <- N (hi + lo).
-template <bool TO_LR>
-__global__ __launch_bounds__(256) void k_tr_exchange(DevCtx d, float* glow, const uint16_t* n_hi, const uint16_t* n_lo) {
+// Right-projected matrices (m.tr): their down-projection leaves g^T as the plain q x r block zw[0] (q = rows of the caller's
+// matrix); the Adam kernel reads slice 0 of the blocked array g.  `scale` is the caller's gradient scale where the product
+// was formed from the raw gradient.
+__global__ __launch_bounds__(256) void k_tr_exchange(DevCtx d, float* glow, float scale) {
   const int mat = blockIdx.y;
   const MatDev& m = d.mats[mat];
   if (!m.tr) return;
-  float* plain = reinterpret_cast<float*>(d.arena + (TO_LR ? m.zw[0] : m.zw[1]));
+  const float* plain = reinterpret_cast<const float*>(d.arena + m.zw[0]);
   const int64_t total = (int64_t)m.r * m.q;
   for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
     const int64_t j = t / m.r, i = t % m.r;                      // column j of the low-rank state, rank index i
-    const int64_t at = m.lr_off + bl_index(j, i, m.rp);
-    if (TO_LR) glow[at] = plain[t];
-    else plain[t] = bf2f(n_hi[at]) + bf2f(n_lo[at]);
+    glow[m.lr_off + bl_index(j, i, m.rp)] = scale * plain[t];
   }
 }
-hipError_t launch_tr_exchange(const DevCtx& d, bool to_lr, float* glow, const uint16_t* n_hi, const uint16_t* n_lo, hipStream_t s) {
-  if (to_lr) hipLaunchKernelGGL(k_tr_exchange<true>, dim3(64, d.n), dim3(256), 0, s, d, glow, n_hi, n_lo);
-  else hipLaunchKernelGGL(k_tr_exchange<false>, dim3(64, d.n), dim3(256), 0, s, d, glow, n_hi, n_lo);
+hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, hipStream_t s) {
+  hipLaunchKernelGGL(k_tr_exchange, dim3(64, d.n), dim3(256), 0, s, d, glow, scale);
   return hipGetLastError();
 }
 

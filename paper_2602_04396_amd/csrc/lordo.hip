@@ -74,7 +74,14 @@ struct Plan {
   std::vector<Op> init_ops;         // Q_0 from a caller-supplied block: copy, orthonormalise, pack
   std::vector<Op> gap_ops;          // estimate of sigma_{r+1} of a source (Rayleigh-Ritz option)
   bool any_tr = false;              // some matrix is projected on the right
-  std::vector<Op> tr_down_ops, tr_up_ops;   // their two products of the local step, by the generic GEMM
+  std::vector<Op> tr_down_ops;      // their product g^T = G Q by the generic GEMM (fp32 gradients, shapes the streaming kernel does not take)
+  // Right-projected matrices in the kernels of the left projection: the products of the step are those of the caller's
+  // p x q matrix with the operand planes in exchanged roles (see build_plan), described by two shadow tables of MatDev.
+  std::vector<MatDev> mat_up, mat_stb;
+  int64_t mats_up = -1, mats_stb = -1, up_tr_tiles = -1, ytile_tr = -1;
+  std::vector<ProjTile> up_tr_h, ytile_tr_h;
+  int64_t tr_plane_gap = 0;         // bytes from a hi plane of such a matrix to its lo plane (the same for all of them)
+  bool tr_stream_shapes = false;    // every right-projected matrix has cols % 32 == 0 and r % 4 == 0
 };
 
 constexpr int MAX_KSPLIT = 16;
@@ -403,9 +410,9 @@ struct ProgramBuilder {
 
   // passes = 3 is the robust variant: two shifted passes after every product of the power iteration (the conditioning
   // of the source then does not compound from product to product) and shifted, shifted, plain at the end.
-  // Local step of the right-projected matrices (Sec. 2 with the roles of rows and columns exchanged), on the caller's
-  // row-major arrays: g^T = (s G) Q into zw[0], and W <- W - eta N^T Q^T with N^T read from zw[1]; the scale s and
-  // the step size multiply the launch (they change per call).
+  // Down-projection of the right-projected matrices (Sec. 2 with the roles of rows and columns exchanged) on the
+  // caller's row-major arrays by the generic GEMM: g^T = (s G) Q into zw[0]; the scale s multiplies the launch (it
+  // changes per call).  Taken for fp32 gradients and for shapes or pointers the streaming kernel does not read.
   void build_tr_step(bool g_bf16) {
     std::vector<Op> keep;
     keep.swap(P.ops);
@@ -419,17 +426,6 @@ struct ProgramBuilder {
       return true;
     });
     P.tr_down_ops.swap(P.ops);
-    gemm([&](int i, GemmDesc& g) {
-      const MatDev& m = P.mat[i];
-      if (!m.tr) return false;
-      g.A = ref_arena(m.zw[1]); g.sAm = m.r; g.sAk = 1;
-      g.B = ref_arena(m.q32); g.sBk = 1; g.sBn = m.r;
-      g.C = ref_ext(EXT_W); g.ldc = m.p;
-      g.M = m.q; g.N = m.p; g.K = m.r;
-      g.alpha = -1.f; g.beta = 1.f;
-      return true;
-    });
-    P.tr_up_ops.swap(P.ops);
     keep.swap(P.ops);
   }
 
@@ -683,8 +679,10 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     size_t pr = (size_t)m.p * m.r, pq = (size_t)m.p * m.q, qr = (size_t)m.q * m.r, rr = (size_t)m.r * m.r;
     size_t planes = (size_t)m.pp * m.rp * 2;
     m.q32 = A.take(pr * 4);
-    m.qa_hi = A.take(planes); m.qa_lo = A.take(planes);
-    m.qt_hi = A.take(planes); m.qt_lo = A.take(planes);
+    if (!m.tr) {
+      m.qa_hi = A.take(planes); m.qa_lo = A.take(planes);
+      m.qt_hi = A.take(planes); m.qt_lo = A.take(planes);
+    }
     m.anchor = A.take(pq * 4);
     m.mom = has_mom ? A.take(pq * 4) : -1;
     m.err = hp.error_feedback ? A.take(pq * 4) : -1;
@@ -696,6 +694,60 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     m.rot = A.take(rr * 4); m.rot2 = A.take(rr * 4);
     m.part = A.take(rr * 4 * P.part_slices);
     m.ritz = hp.rayleigh_ritz ? A.take((size_t)(m.r + 3) * 4) : -1;
+  }
+  if (P.any_tr) {
+    // operand planes of the right-projected matrices: all hi planes of a kind, then all lo planes in the same order,
+    // so that one pair of base pointers (hi, hi + gap) serves every such matrix in a launch
+    for (int kind = 0; kind < 4; ++kind)          // qa hi, qa lo, qt hi, qt lo
+      for (int i = 0; i < n; ++i) {
+        MatDev& m = P.mat[i];
+        if (!m.tr) continue;
+        const int64_t at = A.take((size_t)m.pp * m.rp * 2);
+        (kind == 0 ? m.qa_hi : kind == 1 ? m.qa_lo : kind == 2 ? m.qt_hi : m.qt_lo) = at;
+      }
+    for (int i = 0; i < n; ++i)
+      if (P.mat[i].tr) { P.tr_plane_gap = P.mat[i].qa_lo - P.mat[i].qa_hi; break; }
+    // Shadow records: the caller's matrix W (rows x cols) as a left-projected problem.
+    //   up-projection  W -= eta N^T Q^T: its A planes (row of W, rank) are the planes of N (column of the low-rank
+    //     state = row of W, rank), its B planes (column of W, rank) the up-projection planes of Q (row of Q = column of W);
+    //   streaming product  g^T = G Q: its B planes (rank, column of W) are the down-projection planes of Q (rank, row of Q),
+    //     its result goes to zw[0] as the plain rows x r block.
+    // The kernels add lr_off (in 2-byte elements) to the plane base pointers they are given: with the arena base as hi
+    // pointer and arena + gap as lo pointer, lr_off = (offset of the hi plane) / 2 selects the planes of Q.
+    P.mat_up = P.mat;
+    P.mat_stb = P.mat;
+    P.tr_stream_shapes = hp.grad_dtype == LORDO_BF16;
+    for (int i = 0; i < n; ++i) {
+      const MatDev& m = P.mat[i];
+      if (!m.tr) continue;
+      MatDev sdw = m;
+      sdw.tr = 0;
+      sdw.p = m.q; sdw.q = m.p; sdw.pp = m.qp; sdw.qp = m.pp;
+      MatDev up = sdw, stb = sdw;
+      up.qa_hi = P.n_hi + 2 * m.lr_off; up.qa_lo = P.n_lo + 2 * m.lr_off;
+      up.lr_off = m.qa_hi / 2;
+      stb.lr_off = m.qt_hi / 2;
+      stb.y[0] = m.zw[0];
+      P.mat_up[i] = up;
+      P.mat_stb[i] = stb;
+      if ((sdw.q & 31) != 0 || (sdw.r & 3) != 0) P.tr_stream_shapes = false;
+      constexpr int SB = 8 * 128;
+      for (int ms = 0; ms < sdw.pp; ms += SB)
+        for (int ns = 0; ns < sdw.qp; ns += SB)
+          for (int m0 = ms; m0 < std::min(ms + SB, (int)sdw.pp); m0 += 128)
+            for (int n0 = ns; n0 < std::min(ns + SB, (int)sdw.qp); n0 += 128) {
+              ProjTile t{};
+              t.mat = i; t.m0 = m0; t.n0 = n0;
+              P.up_tr_h.push_back(t);
+            }
+      for (int m0 = 0; m0 < sdw.pp; m0 += 128)
+        for (int n0 = 0; n0 < sdw.rp; n0 += 128) {
+          ProjTile t{};
+          t.mat = i; t.m0 = m0; t.n0 = n0;
+          P.ytile_tr_h.push_back(t);
+        }
+    }
+    P.up_tr_h = xcd_order(P.up_tr_h);
   }
   // projection tile tables
   std::vector<ProjTile> down, up;
@@ -730,6 +782,12 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.up_h = xcd_order(up);
   P.down_tiles = A.take(sizeof(ProjTile) * P.down_h.size());
   P.up_tiles = A.take(sizeof(ProjTile) * P.up_h.size());
+  if (P.any_tr) {     // tables, like the two above: behind the state that lordo_init clears after the tables are uploaded
+    P.mats_up = A.take(sizeof(MatDev) * n);
+    P.mats_stb = A.take(sizeof(MatDev) * n);
+    P.up_tr_tiles = A.take(sizeof(ProjTile) * P.up_tr_h.size());
+    P.ytile_tr = A.take(sizeof(ProjTile) * P.ytile_tr_h.size());
+  }
   {   // products Y = Src B of the refresh: tiles of 128 rows x 128 rank indices, matrices with a long contraction first
     std::vector<ProjTile> yt;
     std::vector<int> order(n);
@@ -890,6 +948,12 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
   } while (0)
   INITCHK(hipStreamSynchronize(s));
   INITCHK(hipMemcpy(c->at<void>(P.mats), P.mat.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
+  if (P.any_tr) {
+    INITCHK(hipMemcpy(c->at<void>(P.mats_up), P.mat_up.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
+    INITCHK(hipMemcpy(c->at<void>(P.mats_stb), P.mat_stb.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
+    INITCHK(hipMemcpy(c->at<void>(P.up_tr_tiles), P.up_tr_h.data(), sizeof(ProjTile) * P.up_tr_h.size(), hipMemcpyHostToDevice));
+    INITCHK(hipMemcpy(c->at<void>(P.ytile_tr), P.ytile_tr_h.data(), sizeof(ProjTile) * P.ytile_tr_h.size(), hipMemcpyHostToDevice));
+  }
   INITCHK(hipMemcpy(c->at<void>(P.chunk_start), P.chunk_start_h.data(), sizeof(int64_t) * (n + 1), hipMemcpyHostToDevice));
   if (!P.down_h.empty()) INITCHK(hipMemcpy(c->at<void>(P.down_tiles), P.down_h.data(), sizeof(ProjTile) * P.down_h.size(), hipMemcpyHostToDevice));
   if (!P.up_h.empty()) INITCHK(hipMemcpy(c->at<void>(P.up_tiles), P.up_h.data(), sizeof(ProjTile) * P.up_h.size(), hipMemcpyHostToDevice));
@@ -973,10 +1037,22 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (!P.down_h.empty())
     HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, g_tr, P.g_once, c->at<float>(P.glow),
                             P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
-  if (P.any_tr) {               // g^T = (s G) Q by the generic GEMM, then into the blocked array the Adam kernel reads
-    for (const Op& op : P.tr_down_ops)
-      HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, (float)grad_scale));
-    HIPCHK(launch_tr_exchange(c->dev, true, c->at<float>(P.glow), nullptr, nullptr, s));
+  if (P.any_tr) {               // g^T = (s G) Q into the plain block zw[0], then into the blocked array the Adam kernel reads
+    bool stream = P.tr_stream_shapes;
+    for (int i = 0; i < c->n && stream; ++i)
+      if (P.mat[i].tr && (reinterpret_cast<uintptr_t>(G[i]) & 15) != 0) stream = false;
+    uint16_t* planes_hi = reinterpret_cast<uint16_t*>(c->dev.arena);
+    uint16_t* planes_lo = reinterpret_cast<uint16_t*>(c->dev.arena + P.tr_plane_gap);
+    if (stream) {               // the kernel of the refresh products Y = Src B, with G as source and the planes of Q as B
+      DevCtx dv = c->dev;
+      dv.mats = c->at<MatDev>(P.mats_stb);
+      dv.slot[EXT_SRC] = dv.slot[EXT_G];
+      HIPCHK(launch_src_times_block(dv, c->at<ProjTile>(P.ytile_tr), (int)P.ytile_tr_h.size(), planes_hi, planes_lo, s));
+    } else {
+      for (const Op& op : P.tr_down_ops)
+        HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, (float)grad_scale));
+    }
+    HIPCHK(launch_tr_exchange(c->dev, c->at<float>(P.glow), stream ? (float)grad_scale : 1.f, s));
   }
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
@@ -1004,10 +1080,14 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (!P.up_h.empty())
     HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
                           c->at<uint16_t>(P.n_lo), ua, s));
-  if (P.any_tr) {               // W <- W - eta N^T Q^T on the caller's rows
-    HIPCHK(launch_tr_exchange(c->dev, false, nullptr, c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), s));
-    for (const Op& op : P.tr_up_ops)
-      HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, (float)lr));
+  if (P.any_tr) {               // W <- W - eta N^T Q^T: the up-projection kernel on the shadow records (planes of N as A, of Q as B)
+    bool w_vec_tr = true;
+    for (int i = 0; i < c->n && w_vec_tr; ++i)
+      if (P.mat[i].tr && ((P.mat[i].p & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0)) w_vec_tr = false;
+    DevCtx du = c->dev;
+    du.mats = c->at<MatDev>(P.mats_up);
+    HIPCHK(launch_proj_up(du, c->at<ProjTile>(P.up_tr_tiles), (int)P.up_tr_h.size(), w_vec_tr, reinterpret_cast<uint16_t*>(c->dev.arena),
+                          reinterpret_cast<uint16_t*>(c->dev.arena + P.tr_plane_gap), ua, s));
   }
   c->prof.end(LORDO_K_UP, s);
   c->t = t;

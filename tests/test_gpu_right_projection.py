@@ -21,6 +21,7 @@ def lowrank_dims(sh):
 SHAPE_SETS = {
     "mixed": [(300, 96, 24, 1), (128, 256, 32, 0), (517, 130, 33, 1)],            # ragged, odd rank, both sides in one context
     "right_only": [(1024, 256, 64, 1), (768, 128, 128, 1)],                       # tall matrices, rank = short side included
+    "aligned_mixed": [(520, 128, 36, 1), (256, 384, 64, 0), (3072, 768, 128, 1)], # shapes the streaming kernel takes, beside a left-projected one
 }
 
 
