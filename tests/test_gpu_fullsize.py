@@ -266,3 +266,74 @@ def test_one_matrix_just_under_the_size_limit_sampled_columns():
     opt.outer_step(W, None)
     opt.poll_status()
     assert torch.equal(opt.get_state(0, lordo.STATE_ANCHOR), W[0])
+
+
+def test_c2_full_size_short_side_sampled_rows():
+    """Workload c2 with its tall matrices projected on the right, in the launch configuration `bench.py --short-side`
+    times: for such a matrix every formula acts row by row (g_i = G_i Q, W_i -= lr N_i Q^T), so the oracle follows
+    sampled rows of full-size matrices with the library's basis; a left-projected matrix of the same context rides along."""
+    import torch
+    import bench
+    from paper_2602_04396_amd import lordo
+    shapes, W, G, _, D, grad_dtype = bench.build_workload(torch, lordo, synth, "c2", None, 3)
+    lib_shapes = [(p, q, r, 1) if p > q else (p, q, r) for p, q, r in shapes]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.seed_for(2, 4343))
+    Omega = [torch.randn(p if p > q else q, r, generator=gen, device="cuda") for p, q, r in shapes]
+    hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=2)
+    W0 = [w.clone() for w in W]
+    opt = lordo.Lordo(lib_shapes, hp, W, torch)
+    Wp = opt.ptrs(W)
+    Gp = [opt.ptrs(g, grad_dtype) for g in G]
+    opt.refresh_subspace(Gp[0], opt.ptrs(Omega, torch.float32, "qr"))
+    opt.poll_status()
+    ohp = orc.Hyper()
+    rng = np.random.default_rng(synth.seed_for(2, 4344))
+    tall = [i for i, (p, q, r) in enumerate(shapes) if p > q]
+    assert len(tall) == 12
+    picked = [tall[0], tall[5], tall[-1], 4]                   # three right-projected matrices and a left-projected one
+    sample = {}
+    for i in picked:
+        p, q, r = shapes[i]
+        right = i in tall
+        Q = opt.get_state(i, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+        assert Q.shape == ((q, r) if right else (p, r)) and np.linalg.norm(Q.T @ Q - np.eye(r)) <= 1e-4
+        m = p if right else q                                   # the index the formulas act along independently
+        idx = np.unique(np.concatenate([[0, m - 1, 127, 128, 255, 256], rng.integers(0, m, 10)]))
+        Wsub = W0[i][idx, :] if right else W0[i][:, idx]
+        Wsub = Wsub.cpu().numpy().astype(np.float64)
+        st = orc.init_state(Wsub.T if right else Wsub, r, Q)
+        sample[i] = dict(Q=Q, idx=idx, st=st, W=Wsub.copy(), right=right)
+
+    def sub(t, i):
+        sm = sample[i]
+        return (t[sm["idx"], :] if sm["right"] else t[:, sm["idx"]]).float().cpu().numpy().astype(np.float64)
+
+    for step, lr in enumerate([1e-3, 2e-3]):
+        W_before = {i: sub(W[i], i) for i in picked}
+        opt.local_step(Wp, Gp[1 + step], lr)
+        torch.cuda.synchronize()
+        for i in picked:
+            sm = sample[i]
+            st, Q = sm["st"], sm["Q"]
+            fn = orc.local_step_right if sm["right"] else orc.local_step
+            sm["W"] = fn(st, sm["W"], sub(G[1 + step][i], i), lr, ohp)
+            cols = sm["idx"]                                    # columns of the r x (.) state arrays
+            get = lambda which: opt.get_state(i, which).cpu().numpy().astype(np.float64)[:, cols]
+            assert rel_l2(get(lordo.STATE_GLOW), st.last_g) <= TOL, f"g, matrix {i}, step {step}"
+            assert rel_l2(get(lordo.STATE_U), st.u) <= TOL and rel_l2(get(lordo.STATE_V), st.v) <= TOL, f"moments, matrix {i}, step {step}"
+            n_gpu = get(lordo.STATE_NUPD)
+            dW_gpu = sub(W[i], i) - W_before[i]
+            up = (lambda N: -lr * N.T @ Q.T) if sm["right"] else (lambda N: -lr * Q @ N)
+            if step == 0:       # N is the sign of g: compare away from |g| ~ 0, and the weight change with the library's own N
+                amb = np.abs(st.last_g) < 1e-4 * np.sqrt(np.mean(st.last_g ** 2))
+                assert np.all(np.abs(n_gpu) <= 1 + 1e-6)
+                assert rel_l2(np.where(amb, 0, n_gpu), np.where(amb, 0, st.last_N)) <= TOL, f"N, matrix {i}, step 0"
+                assert rel_l2(dW_gpu, up(n_gpu)) <= TOL, f"weight change, matrix {i}, step 0"
+            else:
+                assert rel_l2(n_gpu, st.last_N) <= TOL, f"N, matrix {i}, step {step}"
+                assert rel_l2(dW_gpu, up(st.last_N)) <= TOL, f"weight change, matrix {i}, step {step}"
+    opt.outer_step(Wp, opt.ptrs(D))
+    torch.cuda.synchronize()
+    for i in picked:
+        assert torch.equal(opt.get_state(i, lordo.STATE_ANCHOR), W[i]) and torch.isfinite(W[i]).all()
