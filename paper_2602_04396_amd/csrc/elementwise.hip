@@ -1329,10 +1329,14 @@ __global__ __launch_bounds__(256) void k_tr_exchange(DevCtx d, float* glow, floa
   const MatDev& m = d.mats[mat];
   if (!m.tr) return;
   const float* plain = reinterpret_cast<const float*>(d.arena + m.zw[0]);
-  const int64_t total = (int64_t)m.r * m.q;
-  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
-    const int64_t j = t / m.r, i = t % m.r;                      // column j of the low-rank state, rank index i
-    glow[m.lr_off + bl_index(j, i, m.rp)] = scale * plain[t];
+  // in the order of the blocked array (contiguous writes; the reads are 32-byte pieces of rows that neighbouring threads
+  // complete); padded columns and ranks are written as zeros
+  const int64_t total = (int64_t)m.qp * m.rp;
+  const int64_t per_jb = (int64_t)m.rp * 32;
+  for (int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x; o < total; o += (int64_t)gridDim.x * 256) {
+    const int64_t jb = o / per_jb, rem = o % per_jb;
+    const int64_t j = jb * 32 + ((rem >> 3) & 31), i = (rem >> 8) * 8 + (rem & 7);      // column j of the low-rank state, rank index i
+    glow[m.lr_off + o] = (j < m.q && i < m.r) ? scale * plain[j * m.r + i] : 0.f;
   }
 }
 hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, hipStream_t s) {
