@@ -269,8 +269,8 @@ def main():
                        qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef, uplink_buffer=uplink,
                        rayleigh_ritz=args.rayleigh_ritz)
     if args.short_side:
-        if args.update not in ("plain", "low-qhm"):
-            sys.exit("--short-side: the projection on the right is built for --update plain and low-qhm")
+        if args.update not in ("plain", "low-qhm", "uplink"):
+            sys.exit("--short-side: the projection on the right is built for --update plain, low-qhm and uplink")
         gen = torch.Generator(device="cuda")
         gen.manual_seed(synth.seed_for(int(cfg[1:]), 997))
         lib_shapes = [(p, q, r, 1) if p > q else (p, q, r) for p, q, r in shapes]
@@ -287,6 +287,7 @@ def main():
     if uplink:    # stand-in for the mean of the workers' buffers: eta * H times a unit-scale low-rank update
         gen = torch.Generator(device="cuda")
         gen.manual_seed(synth.seed_for(int(cfg[1:]), 998))
+        # (`shapes` holds the transposed problems of right-projected matrices: their buffers are r x rows)
         Ap = opt.ptrs([(1e-3 * max(outer_every, 1)) * torch.randn(r, q, generator=gen, device="cuda") for p, q, r in shapes],
                       torch.float32, "rq")
     lr = 1e-3

@@ -166,7 +166,7 @@ def local_step_right(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, h
     g = G_hat Q (p x r), Adam moments on g, W <- W - lr N Q^T, with Q of size q x r.  This is Sec. 2's update
     of the transposed matrix; `st` is the state of that transposed problem (Q: q x r; u, v, last_g, last_N: r x p,
     i.e. the transposes of the p x r arrays of this function).  Cases "No QHM" and "Low-Rank QHM" only."""
-    assert not hp.error_feedback and hp.qhm_mode != "full" and not hp.uplink_buffer
+    assert not hp.error_feedback and hp.qhm_mode != "full"
     W = np.asarray(W, dtype=F64)
     G_hat = grad_scale * np.asarray(G, dtype=F64)
     st.t += 1
@@ -175,6 +175,8 @@ def local_step_right(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, h
     N = low_rank_direction(u, v, g, st.t, hp)          # p x r
     st.u, st.v = u.T, v.T
     st.last_g, st.last_N = g.T, N.T
+    if hp.uplink_buffer:                               # App. A.5.1, in the layout of the transposed problem (r x p)
+        st.A = st.A + lr * N.T
     return W - lr * (N @ st.Q.T)
 
 

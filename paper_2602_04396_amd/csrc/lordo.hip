@@ -548,7 +548,7 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
     if (s.rank > (s.side ? s.cols : s.rows)) return LORDO_EINVAL;
     // projection on the right: the plain and the low-rank QHM update only (the other update cases fuse their
     // gradient terms into the kernels of the left projection)
-    if (s.side && (hp->error_feedback || hp->qhm_mode == 2 || hp->uplink_buffer)) return LORDO_EINVAL;
+    if (s.side && (hp->error_feedback || hp->qhm_mode == 2)) return LORDO_EINVAL;
     // (tile coordinates of the grouped GEMM are 16-bit: at most 32767 tiles of 64 rows)
     if (s.rows > (1 << 20) || s.cols > (1 << 20) || s.rank > 4096) return LORDO_EINVAL;
     // the kernels address a matrix through buffer descriptors with 32-bit byte offsets: p * q * 4 bytes must stay below 4 GiB
@@ -1346,9 +1346,23 @@ int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* Av
     rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(AvgAcc)), s);
     if (rc != LORDO_OK) return rc;
   }
-  bool w_vec = true;
+  bool w_vec = true;            // rows of W of a multiple of 4 floats (a right-projected matrix: its p is the row length)
   for (int i = 0; i < c->n; ++i)
-    if ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
+    if (((P.mat[i].tr ? P.mat[i].p : P.mat[i].q) & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0) { w_vec = false; break; }
+  // Delta = Q A through the up-projection kernel: the left-projected matrices, then the right-projected ones on their
+  // shadow records (planes of A in the place of N as A operand, planes of Q as B operand)
+  auto up_all = [&](const UpArgs& ua) -> hipError_t {
+    hipError_t e = hipSuccess;
+    if (!P.up_h.empty())
+      e = launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi), c->at<uint16_t>(P.n_lo), ua, s);
+    if (e == hipSuccess && P.any_tr) {
+      DevCtx du = c->dev;
+      du.mats = c->at<MatDev>(P.mats_up);
+      e = launch_proj_up(du, c->at<ProjTile>(P.up_tr_tiles), (int)P.up_tr_h.size(), w_vec, reinterpret_cast<uint16_t*>(c->dev.arena),
+                         reinterpret_cast<uint16_t*>(c->dev.arena + P.tr_plane_gap), ua, s);
+    }
+    return e;
+  };
   OuterArgs a;
   a.lr = (float)c->hp.outer_lr;
   a.mu = (float)c->hp.outer_momentum;
@@ -1369,8 +1383,7 @@ int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* Av
     // anchor and the momentum and writes W, the anchor and the momentum
     ua.outer = 1; ua.nesterov = a.nesterov; ua.has_mom = a.has_mom; ua.mu = a.mu;
     ua.coef_acc = (float)-c->hp.outer_lr;
-    HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), true, c->at<uint16_t>(P.n_hi),
-                          c->at<uint16_t>(P.n_lo), ua, s));
+    HIPCHK(up_all(ua));
     HIPCHK(launch_fill_zero(c->at<void>(P.acc), sizeof(float) * P.lr_total, s));
     c->prof.end(LORDO_K_OUTER, s);
     c->window_steps = 0;
@@ -1381,13 +1394,11 @@ int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* Av
   // kernel into W and into b, then anchor <- W
   HIPCHK(launch_outer_base(c->dev, chunks, P.nchunks, a, s));
   ua.coef_acc = (float)(-c->hp.outer_lr * ((a.has_mom && a.nesterov) ? 1.0 + c->hp.outer_momentum : 1.0));
-  HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
-                        c->at<uint16_t>(P.n_lo), ua, s));
+  HIPCHK(up_all(ua));
   if (a.has_mom) {
     ua.target_err = 2;
     ua.coef_acc = 1.f;
-    HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
-                          c->at<uint16_t>(P.n_lo), ua, s));
+    HIPCHK(up_all(ua));
   }
   HIPCHK(launch_anchor_from_w(c->dev, chunks, P.nchunks, s));
   HIPCHK(launch_fill_zero(c->at<void>(P.acc), sizeof(float) * P.lr_total, s));

@@ -92,3 +92,35 @@ def test_right_projection_rayleigh_ritz_and_metrics():
     np.testing.assert_allclose(np.sqrt(np.diag(gram)), ritz, rtol=1e-4, atol=1e-6 * ritz[0])
     sr = float(pair.opt.stable_rank().cpu().numpy()[0])
     assert abs(sr - orc.stable_rank(A)) <= 1e-4 * orc.stable_rank(A)
+
+
+@pytest.mark.parametrize("mom", [0.0, 0.9])
+@pytest.mark.parametrize("name", ["mixed", "aligned_mixed"])
+def test_right_projection_uplink_buffer_and_lowrank_outer_step(name, mom):
+    """Up-link buffer (App. A.5.1) with right-projected matrices: A accumulates lr * N in the layout of the transposed
+    problem (r x rows), and the outer step forms Delta = (Q A)^T in the up-projection kernel on the caller's rows."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    shapes = SHAPE_SETS[name]
+    common = dict(uplink_buffer=True, outer_lr=0.7, outer_momentum=mom, outer_nesterov=True, power_iters=1)
+    ohp = orc.Hyper(**common)
+    ghp = lordo.hparams(grad_dtype=lordo.BF16, **common)
+    W0 = [synth.weights(np.random.default_rng(synth.seed_for(87, i)), sh[0], sh[1]) for i, sh in enumerate(shapes)]
+    Q0 = [synth.orthonormal(np.random.default_rng(synth.seed_for(88, i)), lowrank_dims(sh)[0], sh[2]).astype(np.float32)
+          for i, sh in enumerate(shapes)]
+    pair = Pair(torch, shapes, W0, ohp, ghp, Q0)
+    gens = [synth.SpikedGradient(sh[0], sh[1], 4, synth.seed_for(89, i), bf16=True) for i, sh in enumerate(shapes)]
+    for window in range(2):
+        for t in range(3):
+            pair.local_step([g.draw(10 * window + t) for g in gens], lr=1e-3 * (1 + t), bf16=True, first_step_patch=(window == 0 and t == 0))
+        pair.compare_local(TOL)                          # includes the buffer A
+        out = [torch.empty(sh[2], lowrank_dims(sh)[1], dtype=torch.float32, device="cuda") for sh in shapes]
+        pair.opt.export_uplink(out)
+        avg = [0.5 * o.cpu().numpy() for o in out]       # stand-in for the mean over workers
+        pair.opt.outer_step_lowrank(pair.W_gpu, pair.to_dev(avg, False))
+        for i in range(len(shapes)):
+            Wt = orc.outer_step_lowrank(pair.st[i], np.asarray(avg[i], dtype=np.float64), ohp)
+            pair.W_orc[i] = Wt.T.copy() if pair.side[i] else Wt
+            got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
+            assert rel_l2(got - pair.W0[i], pair.W_orc[i] - pair.W0[i]) <= TOL, f"window {window}, matrix {i}"
+            assert np.array_equal(pair.get(i, lordo.STATE_ANCHOR), got.astype(np.float32).astype(np.float64))
