@@ -92,6 +92,18 @@ def test_right_projection_rayleigh_ritz_and_metrics():
     np.testing.assert_allclose(np.sqrt(np.diag(gram)), ritz, rtol=1e-4, atol=1e-6 * ritz[0])
     sr = float(pair.opt.stable_rank().cpu().numpy()[0])
     assert abs(sr - orc.stable_rank(A)) <= 1e-4 * orc.stable_rank(A)
+    # spectral gap (Sec. 5.1): the estimate of sigma_(r+1) against the oracle's iteration on the transposed source with
+    # the library's basis, and against the exact norm of the deflated source; the basis is left alone
+    Om2 = synth.omega(np.random.default_rng(synth.seed_for(86, 1)), p, r)
+    Q_before = pair.opt.get_state(0, lordo.STATE_Q)
+    gap = float(pair.opt.spectral_gap(pair.to_dev(Src, False), pair.to_dev([Om2], False)).cpu().numpy()[0])
+    pair.opt.poll_status()
+    assert torch.equal(pair.opt.get_state(0, lordo.STATE_Q), Q_before)
+    est_gpu = ritz[-1] - gap
+    est_orc = orc.next_singular_value_estimate(A.T, Qg, np.asarray(Om2, dtype=np.float64), 2)
+    deflated = np.linalg.svd(A.T - Qg @ (Qg.T @ A.T), compute_uv=False)[0]
+    assert abs(est_gpu - est_orc) <= 1e-4 * est_orc
+    assert 0.85 * deflated <= est_gpu <= (1 + 1e-4) * deflated
 
 
 @pytest.mark.parametrize("mom", [0.0, 0.9])
