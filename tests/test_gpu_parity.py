@@ -769,9 +769,9 @@ def test_state_roundtrip_and_errors(torch):
     opt.poll_status()
 
 
-@pytest.mark.parametrize("rayleigh_ritz,top_rank", [(False, 128), (True, 128), (True, 200)],
-                         ids=["plain_refresh", "rayleigh_ritz", "rayleigh_ritz_blocked_solver"])
-def test_two_contexts_with_the_same_inputs_agree_bit_for_bit(torch, rayleigh_ritz, top_rank):
+@pytest.mark.parametrize("rayleigh_ritz,top_rank,short_side", [(False, 128, False), (True, 128, False), (True, 200, False), (True, 128, True)],
+                         ids=["plain_refresh", "rayleigh_ritz", "rayleigh_ritz_blocked_solver", "tall_matrix_projected_on_the_right"])
+def test_two_contexts_with_the_same_inputs_agree_bit_for_bit(torch, rayleigh_ritz, top_rank, short_side):
     """Workers that see the same averaged source recompute the same projection instead of receiving it (Alg. 1): that
     needs run-to-run identical results.  Two contexts, identical inputs, steps (split-K down-projection), a refresh
     (grouped GEMMs with split-K, factorisations, with or without the Rayleigh-Ritz solver), more steps and an outer
@@ -783,6 +783,9 @@ def test_two_contexts_with_the_same_inputs_agree_bit_for_bit(torch, rayleigh_rit
     W0 = _weights(shapes, 39)
     Om = [torch.tensor(synth.omega(np.random.default_rng(synth.seed_for(39, 900 + i)), q, r), device="cuda")
           for i, (p, q, r) in enumerate(shapes)]
+    if short_side:          # the tall matrix projected on its columns: generic products in the refresh, shadow launches in the step
+        Om[3] = torch.tensor(synth.omega(np.random.default_rng(synth.seed_for(39, 903)), 1024, 100), device="cuda")
+        shapes = shapes[:3] + [(1024, 256, 100, 1)]
     G = [[torch.tensor(g.draw(t), device="cuda").bfloat16() for g in gens] for t in range(5)]
     runs = []
     for _ in range(2):
