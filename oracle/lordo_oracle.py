@@ -165,12 +165,15 @@ def local_step_right(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, h
     """One local step with the projection on the right, written out on the p x q arrays:
     g = G_hat Q (p x r), Adam moments on g, W <- W - lr N Q^T, with Q of size q x r.  This is Sec. 2's update
     of the transposed matrix; `st` is the state of that transposed problem (Q: q x r; u, v, last_g, last_N: r x p,
-    i.e. the transposes of the p x r arrays of this function).  Cases "No QHM" and "Low-Rank QHM" only."""
-    assert not hp.error_feedback and hp.qhm_mode != "full"
+    i.e. the transposes of the p x r arrays of this function; E: q x p).  Cases "No QHM" and "Low-Rank QHM" only."""
+    assert hp.qhm_mode != "full"
     W = np.asarray(W, dtype=F64)
     G_hat = grad_scale * np.asarray(G, dtype=F64)
     st.t += 1
-    g = G_hat @ st.Q                                   # p x r
+    A = G_hat + st.E.T if hp.error_feedback else G_hat  # st.E is kept in the layout of the transposed problem (q x p)
+    g = A @ st.Q                                       # p x r
+    if hp.error_feedback:
+        st.E = (A - g @ st.Q.T).T                      # E_t = G + E_{t-1} - g Q^T
     u, v = update_moments(st.u.T, st.v.T, g, hp.beta1, hp.beta2)
     N = low_rank_direction(u, v, g, st.t, hp)          # p x r
     st.u, st.v = u.T, v.T

@@ -166,7 +166,7 @@ hipError_t launch_outer_base(const DevCtx& d, const int64_t* chunk_start, int64_
 hipError_t launch_split_planes(const float* src, uint16_t* p_hi, uint16_t* p_lo, int64_t nelem, hipStream_t s);
 hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
 hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
-hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s);
+hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s, bool only_tr = false);
 // refresh helpers (grouped over all matrices)
 hipError_t launch_gram_shift(const DevCtx& d, float coef, bool store, hipStream_t s);
 hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);

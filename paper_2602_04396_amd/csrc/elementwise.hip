@@ -503,10 +503,11 @@ hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int
 // E <- E + scale * G for every matrix (Alg. 2: the projection of the local variant is computed from
 // the gradient plus the error buffer; the sum is formed in place in the buffer).
 template <bool GF32>
-__global__ __launch_bounds__(256) void k_fold_grad(DevCtx d, const int64_t* __restrict__ chunk_start, float scale) {
+__global__ __launch_bounds__(256) void k_fold_grad(DevCtx d, const int64_t* __restrict__ chunk_start, float scale, int only_tr) {
   const int64_t b = blockIdx.x;
   const int mat = find_mat(chunk_start, d.n, b);
   const MatDev& m = d.mats[mat];
+  if (only_tr && !m.tr) return;       // the local step folds for the right-projected matrices only (the others add E in their kernel)
   const int64_t total = (int64_t)m.p * m.q;
   const int64_t off = (b - chunk_start[mat]) * CHUNK;
   float* E = reinterpret_cast<float*>(d.arena + m.err);
@@ -540,9 +541,9 @@ __global__ __launch_bounds__(256) void k_fold_grad(DevCtx d, const int64_t* __re
     }
   }
 }
-hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s) {
-  if (g_is_f32) hipLaunchKernelGGL(k_fold_grad<true>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, scale);
-  else hipLaunchKernelGGL(k_fold_grad<false>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, scale);
+hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s, bool only_tr) {
+  if (g_is_f32) hipLaunchKernelGGL(k_fold_grad<true>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, scale, only_tr ? 1 : 0);
+  else hipLaunchKernelGGL(k_fold_grad<false>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, scale, only_tr ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -77,8 +77,9 @@ struct Plan {
   std::vector<Op> tr_down_ops;      // their product g^T = G Q by the generic GEMM (fp32 gradients, shapes the streaming kernel does not take)
   // Right-projected matrices in the kernels of the left projection: the products of the step are those of the caller's
   // p x q matrix with the operand planes in exchanged roles (see build_plan), described by two shadow tables of MatDev.
-  std::vector<MatDev> mat_up, mat_stb;
-  int64_t mats_up = -1, mats_stb = -1, up_tr_tiles = -1, ytile_tr = -1;
+  std::vector<MatDev> mat_up, mat_stb, mat_up_ef;    // mat_up_ef: the planes of g in the place of N (error-feedback residual)
+  std::vector<Op> tr_down_ef_ops;                    // g^T = (s G + E) Q from the folded residual, by the generic GEMM
+  int64_t mats_up = -1, mats_stb = -1, mats_up_ef = -1, up_tr_tiles = -1, ytile_tr = -1;
   std::vector<ProjTile> up_tr_h, ytile_tr_h;
   int64_t tr_plane_gap = 0;         // bytes from a hi plane of such a matrix to its lo plane (the same for all of them)
   bool tr_stream_shapes = false;    // every right-projected matrix has cols % 32 == 0 and r % 4 == 0
@@ -413,7 +414,7 @@ struct ProgramBuilder {
   // Down-projection of the right-projected matrices (Sec. 2 with the roles of rows and columns exchanged) on the
   // caller's row-major arrays by the generic GEMM: g^T = (s G) Q into zw[0]; the scale s multiplies the launch (it
   // changes per call).  Taken for fp32 gradients and for shapes or pointers the streaming kernel does not read.
-  void build_tr_step(bool g_bf16) {
+  void build_tr_step(bool g_bf16, bool ef) {
     std::vector<Op> keep;
     keep.swap(P.ops);
     gemm([&](int i, GemmDesc& g) {
@@ -426,6 +427,18 @@ struct ProgramBuilder {
       return true;
     });
     P.tr_down_ops.swap(P.ops);
+    if (ef) {           // source: the residual after E <- s G + E (fp32, in the arena, the caller's layout)
+      gemm([&](int i, GemmDesc& g) {
+        const MatDev& m = P.mat[i];
+        if (!m.tr) return false;
+        g.A = ref_arena(m.err); g.sAm = m.p; g.sAk = 1;
+        g.B = ref_arena(m.q32); g.sBk = m.r; g.sBn = 1;
+        g.C = ref_arena(m.zw[0]); g.ldc = m.r;
+        g.M = m.q; g.N = m.r; g.K = m.p;
+        return true;
+      });
+      P.tr_down_ef_ops.swap(P.ops);
+    }
     keep.swap(P.ops);
   }
 
@@ -546,9 +559,9 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
     const lordo_shape& s = shapes[i];
     if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || (s.side != 0 && s.side != 1)) return LORDO_EINVAL;
     if (s.rank > (s.side ? s.cols : s.rows)) return LORDO_EINVAL;
-    // projection on the right: the plain and the low-rank QHM update only (the other update cases fuse their
-    // gradient terms into the kernels of the left projection)
-    if (s.side && (hp->error_feedback || hp->qhm_mode == 2)) return LORDO_EINVAL;
+    // projection on the right: not the full-rank QHM update (its column scale, fused into the up-projection kernel's
+    // epilogue, would have to become a row scale)
+    if (s.side && hp->qhm_mode == 2) return LORDO_EINVAL;
     // (tile coordinates of the grouped GEMM are 16-bit: at most 32767 tiles of 64 rows)
     if (s.rows > (1 << 20) || s.cols > (1 << 20) || s.rank > 4096) return LORDO_EINVAL;
     // the kernels address a matrix through buffer descriptors with 32-bit byte offsets: p * q * 4 bytes must stay below 4 GiB
@@ -716,6 +729,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     // pointer and arena + gap as lo pointer, lr_off = (offset of the hi plane) / 2 selects the planes of Q.
     P.mat_up = P.mat;
     P.mat_stb = P.mat;
+    P.mat_up_ef = P.mat;
     P.tr_stream_shapes = hp.grad_dtype == LORDO_BF16;
     for (int i = 0; i < n; ++i) {
       const MatDev& m = P.mat[i];
@@ -730,6 +744,10 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
       stb.y[0] = m.zw[0];
       P.mat_up[i] = up;
       P.mat_stb[i] = stb;
+      if (hp.error_feedback) {
+        up.qa_hi = P.g_hi + 2 * m.lr_off; up.qa_lo = P.g_lo + 2 * m.lr_off;
+        P.mat_up_ef[i] = up;
+      }
       if ((sdw.q & 31) != 0 || (sdw.r & 3) != 0) P.tr_stream_shapes = false;
       constexpr int SB = 8 * 128;
       for (int ms = 0; ms < sdw.pp; ms += SB)
@@ -785,6 +803,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   if (P.any_tr) {     // tables, like the two above: behind the state that lordo_init clears after the tables are uploaded
     P.mats_up = A.take(sizeof(MatDev) * n);
     P.mats_stb = A.take(sizeof(MatDev) * n);
+    P.mats_up_ef = A.take(sizeof(MatDev) * n);
     P.up_tr_tiles = A.take(sizeof(ProjTile) * P.up_tr_h.size());
     P.ytile_tr = A.take(sizeof(ProjTile) * P.ytile_tr_h.size());
   }
@@ -812,7 +831,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes, hp.rayleigh_ritz != 0);
   if (hp.rayleigh_ritz) pb.build_gap(2, hp.orth_passes == 0 ? 2 : hp.orth_passes);
   pb.build_init(hp.orth_passes == 0 ? 2 : hp.orth_passes);
-  if (P.any_tr) pb.build_tr_step(hp.grad_dtype == LORDO_BF16);
+  if (P.any_tr) pb.build_tr_step(hp.grad_dtype == LORDO_BF16, hp.error_feedback != 0);
   P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
   P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());
   P.bytes = A.cur;
@@ -951,6 +970,7 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
   if (P.any_tr) {
     INITCHK(hipMemcpy(c->at<void>(P.mats_up), P.mat_up.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
     INITCHK(hipMemcpy(c->at<void>(P.mats_stb), P.mat_stb.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
+    INITCHK(hipMemcpy(c->at<void>(P.mats_up_ef), P.mat_up_ef.data(), sizeof(MatDev) * n, hipMemcpyHostToDevice));
     INITCHK(hipMemcpy(c->at<void>(P.up_tr_tiles), P.up_tr_h.data(), sizeof(ProjTile) * P.up_tr_h.size(), hipMemcpyHostToDevice));
     INITCHK(hipMemcpy(c->at<void>(P.ytile_tr), P.ytile_tr_h.data(), sizeof(ProjTile) * P.ytile_tr_h.size(), hipMemcpyHostToDevice));
   }
@@ -1024,6 +1044,8 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (qhm_full || ef) {         // the gradient-term epilogue reads four columns of G per lane
     if (!w_vec) return LORDO_EINVAL;
     for (int i = 0; i < c->n; ++i)
+      if (P.mat[i].tr && ((P.mat[i].p & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0)) return LORDO_EINVAL;
+    for (int i = 0; i < c->n; ++i)
       if ((reinterpret_cast<uintptr_t>(G[i]) & (g_f32 ? 15 : 7)) != 0) return LORDO_EINVAL;
   }
   DownFuse fuse;
@@ -1038,7 +1060,13 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
     HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, g_tr, P.g_once, c->at<float>(P.glow),
                             P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
   if (P.any_tr) {               // g^T = (s G) Q into the plain block zw[0], then into the blocked array the Adam kernel reads
-    bool stream = P.tr_stream_shapes;
+    bool stream = P.tr_stream_shapes && !ef;
+    if (ef) {                   // A = s G + E is formed in the residual buffer first (unless a refresh of the local variant has done it)
+      if (!folded)
+        HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)grad_scale, g_f32, s, true));
+      for (const Op& op : P.tr_down_ef_ops)
+        HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, 1.f));
+    }
     for (int i = 0; i < c->n && stream; ++i)
       if (P.mat[i].tr && (reinterpret_cast<uintptr_t>(G[i]) & 15) != 0) stream = false;
     uint16_t* planes_hi = reinterpret_cast<uint16_t*>(c->dev.arena);
@@ -1048,7 +1076,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
       dv.mats = c->at<MatDev>(P.mats_stb);
       dv.slot[EXT_SRC] = dv.slot[EXT_G];
       HIPCHK(launch_src_times_block(dv, c->at<ProjTile>(P.ytile_tr), (int)P.ytile_tr_h.size(), planes_hi, planes_lo, s));
-    } else {
+    } else if (!ef) {
       for (const Op& op : P.tr_down_ops)
         HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, (float)grad_scale));
     }
@@ -1066,8 +1094,17 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   ua.eps = (float)c->hp.eps;
   if (ef) {                     // E <- grad_scale*G + E - Q g (Alg. 1 error-feedback lines); reads the E the down-projection used
     ua.coef_acc = -1.f; ua.coef_g = (float)proj_scale; ua.target_err = 1; ua.colscale = 0; ua.colpart = nullptr;
-    HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.g_hi),
-                          c->at<uint16_t>(P.g_lo), ua, s));
+    if (!P.up_h.empty())
+      HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.g_hi),
+                            c->at<uint16_t>(P.g_lo), ua, s));
+    if (P.any_tr) {             // right-projected matrices: E already holds s G + E; E <- E - g^T Q^T on the shadow records (planes of g as A)
+      UpArgs ue = ua;
+      ue.coef_g = 0.f;
+      DevCtx du = c->dev;
+      du.mats = c->at<MatDev>(P.mats_up_ef);
+      HIPCHK(launch_proj_up(du, c->at<ProjTile>(P.up_tr_tiles), (int)P.up_tr_h.size(), true, reinterpret_cast<uint16_t*>(c->dev.arena),
+                            reinterpret_cast<uint16_t*>(c->dev.arena + P.tr_plane_gap), ue, s));
+    }
   }
   ua.target_err = 0;
   if (qhm_full) {               // W <- W - eta [ (1-omega) G_hat diag(1/s) + omega Q N ]  (Alg. 1 "Full-Rank QHM")
@@ -1247,6 +1284,7 @@ int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad
   if (!c || !G || !Omega || !std::isfinite(grad_scale)) return LORDO_EINVAL;
   if (!c->hp.error_feedback || c->grad_folded) return LORDO_ESTATE;
   if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;
+  if (c->plan.any_tr) return LORDO_EINVAL;             // the local variant is built for left-projected matrices
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   Plan& P = c->plan;
   int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);

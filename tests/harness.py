@@ -126,7 +126,8 @@ class Pair:
                 # of A, however small E itself is.  So E is held to tol relative to ||A||, and
                 # ||A||^2 = ||g||^2 + ||E||^2 for orthonormal Q.
                 scale = np.sqrt(np.sum(st.last_g * st.last_g) + np.sum(st.E * st.E))
-                errs["E"] = float(np.linalg.norm(self.get(i, L.STATE_ERR) - st.E) / max(scale, 1e-300))
+                E_gpu = self.get(i, L.STATE_ERR)             # the caller's layout; the oracle state of a right-projected matrix holds E^T
+                errs["E"] = float(np.linalg.norm((E_gpu.T if self.side[i] else E_gpu) - st.E) / max(scale, 1e-300))
             if self.ohp.uplink_buffer:
                 errs["A"] = rel_l2(self.get(i, L.STATE_UPLINK), st.A)
             for k, e in errs.items():

@@ -78,7 +78,8 @@ def test_right_projection_validation(lib):
     # built for the plain and the low-rank QHM update
     assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(qhm_mode=1, omega=0.9)) > 0
     assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(uplink_buffer=True)) > 0
-    for bad in (lordo.hparams(error_feedback=True), lordo.hparams(qhm_mode=2, omega=0.9)):
+    assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(error_feedback=True)) > 0
+    for bad in (lordo.hparams(qhm_mode=2, omega=0.9), lordo.hparams(qhm_mode=2, omega=0.9, error_feedback=True)):
         with pytest.raises(lordo.LordoError) as e:
             lordo.workspace_bytes([(64, 32, 8, 1)], bad)
         assert e.value.code == lordo.EINVAL

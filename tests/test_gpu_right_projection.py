@@ -26,15 +26,20 @@ SHAPE_SETS = {
 
 
 @pytest.mark.parametrize("bf16", [True, False], ids=["bf16", "fp32"])
-@pytest.mark.parametrize("qhm", ["none", "low"])
+@pytest.mark.parametrize("qhm", ["none", "low", "low_ef"])
 @pytest.mark.parametrize("name", list(SHAPE_SETS))
 def test_right_projection_steps_refresh_outer(name, qhm, bf16):
     import torch
     from paper_2602_04396_amd import lordo
     shapes = SHAPE_SETS[name]
+    ef = qhm == "low_ef"                 # error feedback (Alg. 1): the residual of a right-projected matrix, E <- s G + E - g Q^T
+    if ef:
+        qhm = "low"
+        if name == "mixed":
+            pytest.skip("the residual update of the up-projection kernel needs rows of W of a multiple of 4 floats")
     n = len(shapes)
     omega = 0.8 if qhm == "low" else 1.0
-    common = dict(omega=omega, outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=1)
+    common = dict(omega=omega, outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=1, error_feedback=ef)
     ohp = orc.Hyper(qhm_mode=qhm, **common)
     ghp = lordo.hparams(qhm_mode={"none": 0, "low": 1}[qhm], grad_dtype=lordo.BF16 if bf16 else lordo.F32, **common)
     W0 = [synth.weights(np.random.default_rng(synth.seed_for(80, i)), sh[0], sh[1]) for i, sh in enumerate(shapes)]

@@ -668,13 +668,15 @@ def test_comm_ratios_golden():
 # ---------------------------------------------------------------------------------------------
 # projection on the right (Sec. 2 applied to the transposed matrix)
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("qhm", ["none", "low"])
+@pytest.mark.parametrize("qhm", ["none", "low", "low_ef"])
 def test_right_projection_is_the_method_on_the_transpose(qhm):
     """The explicit right-side formulas (g = G Q, W -= lr N Q^T) against the left-side functions run on
     W^T, G^T: two code paths, one result, over steps and a refresh."""
     rng = np.random.default_rng(77)
     p, q, r = 23, 11, 4
-    hp = orc.Hyper(qhm_mode=qhm, omega=0.7 if qhm == "low" else 1.0, power_iters=1)
+    ef = qhm == "low_ef"
+    qhm = "low" if ef else qhm
+    hp = orc.Hyper(qhm_mode=qhm, omega=0.7 if qhm == "low" else 1.0, power_iters=1, error_feedback=ef)
     W = rng.standard_normal((p, q))
     Q0 = np.linalg.qr(rng.standard_normal((q, r)))[0]
     a, b = orc.init_state(W.T, r, Q0), orc.init_state(W.T, r, Q0)
@@ -685,6 +687,9 @@ def test_right_projection_is_the_method_on_the_transpose(qhm):
         Wb = orc.local_step(b, Wb, G.T, 1e-2, hp, grad_scale=0.5)
         np.testing.assert_allclose(Wa, Wb.T, rtol=0, atol=1e-14)
         np.testing.assert_allclose(a.last_N, b.last_N, rtol=0, atol=1e-13)
+        if ef:          # the residual is orthogonal to the basis on the right, and the books balance (sum of gradients = projected part + E)
+            np.testing.assert_allclose(a.E, b.E, rtol=0, atol=1e-14)
+            assert np.linalg.norm(a.E.T @ a.Q) <= 1e-12
     Src, Om = rng.standard_normal((p, q)), rng.standard_normal((p, r))
     Qa = orc.refresh_subspace_right(a, Src, Om, hp)
     Qb = orc.refresh_subspace(b, Src.T, Om, hp)
