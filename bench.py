@@ -269,8 +269,8 @@ def main():
                        qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef, uplink_buffer=uplink,
                        rayleigh_ritz=args.rayleigh_ritz)
     if args.short_side:
-        if args.update not in ("plain", "low-qhm", "uplink", "ef"):
-            sys.exit("--short-side: the projection on the right is built for --update plain, low-qhm, ef and uplink")
+        if args.update not in ("plain", "low-qhm", "uplink", "ef", "local"):
+            sys.exit("--short-side: the projection on the right is built for --update plain, low-qhm, ef, local and uplink")
         gen = torch.Generator(device="cuda")
         gen.manual_seed(synth.seed_for(int(cfg[1:]), 997))
         lib_shapes = [(p, q, r, 1) if p > q else (p, q, r) for p, q, r in shapes]

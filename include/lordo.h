@@ -75,8 +75,8 @@ typedef struct lordo_ctx lordo_ctx;
  *           every low-rank array of such a matrix is the one of the TRANSPOSED problem, i.e. Q is q x r, the r x q
  *           states (u, v, g, N) are r x p, Omega is p x r and the block of lordo_init_projection q x r.
  *           1 <= r <= q.  Built for the update cases "No QHM" and "Low-Rank QHM", with or without error feedback
- *           (then: columns a multiple of 4, 16-byte aligned W) and the up-link buffer; not for "Full-Rank QHM" and not
- *           for lordo_refresh_subspace_local (LORDO_EINVAL); its two products of the local step and the products of a
+ *           (then: columns a multiple of 4, 16-byte aligned W) and the up-link buffer; not for "Full-Rank QHM"
+ *           (LORDO_EINVAL); its two products of the local step and the products of a
  *           refresh with the source run in the library's generic grouped GEMM, also for the left-projected matrices
  *           of the same context in the refresh. */
 typedef struct {

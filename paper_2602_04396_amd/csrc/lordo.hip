@@ -1284,7 +1284,6 @@ int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad
   if (!c || !G || !Omega || !std::isfinite(grad_scale)) return LORDO_EINVAL;
   if (!c->hp.error_feedback || c->grad_folded) return LORDO_ESTATE;
   if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;
-  if (c->plan.any_tr) return LORDO_EINVAL;             // the local variant is built for left-projected matrices
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   Plan& P = c->plan;
   int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
@@ -1297,7 +1296,7 @@ int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad
   if (rc != LORDO_OK) return rc;
   c->grad_folded = true;
   c->folded_g.assign(G, G + c->n);
-  bool proj_kernels = P.down_pipe != 0;                // the residual is 256-byte aligned; pairs of columns need an even q
+  bool proj_kernels = P.down_pipe != 0 && !P.any_tr;   // the residual is 256-byte aligned; pairs of columns need an even q
   for (int i = 0; i < c->n && proj_kernels; ++i)
     if ((P.mat[i].q & 1) != 0) proj_kernels = false;
   return run_refresh(c, LORDO_F32, s, true, grad_scale, proj_kernels, false);

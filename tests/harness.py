@@ -164,10 +164,12 @@ class Pair:
         self.opt.refresh_subspace_local(self._held_G, Od, grad_scale)
         self.opt.poll_status()
         dists, orths = [], []
-        for i, (p, q, r) in enumerate(self.shapes):
+        for i, sh in enumerate(self.shapes):
+            r = sh[2]
             Qg = self.get(i, L.STATE_Q)
             orths.append(float(np.linalg.norm(Qg.T @ Qg - np.eye(r))))
-            src = orc.local_variant_source(self.st[i], np.asarray(G[i], dtype=np.float64), grad_scale)
+            Gi = np.asarray(G[i], dtype=np.float64)
+            src = orc.local_variant_source(self.st[i], Gi.T if self.side[i] else Gi, grad_scale)     # in the layout of the oracle state
             Qo = orc.range_finder(src, np.asarray(Omega[i], dtype=np.float64), self.ohp.power_iters)
             dists.append(projector_distance(Qg, Qo))
             orc.refresh_subspace(self.st[i], None, None, self.ohp, Q_forced=Qg)

@@ -141,3 +141,31 @@ def test_right_projection_uplink_buffer_and_lowrank_outer_step(name, mom):
             got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
             assert rel_l2(got - pair.W0[i], pair.W_orc[i] - pair.W0[i]) <= TOL, f"window {window}, matrix {i}"
             assert np.array_equal(pair.get(i, lordo.STATE_ANCHOR), got.astype(np.float32).astype(np.float64))
+
+
+@pytest.mark.parametrize("name", ["right_only", "aligned_mixed"])
+def test_right_projection_local_variant(name):
+    """Alg. 2 with right-projected matrices: identity columns as Q_0, projection from s G + E of the step's own gradient,
+    low-rank QHM with error feedback; two refreshes with steps between."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    shapes = SHAPE_SETS[name]
+    common = dict(omega=0.8, error_feedback=True, power_iters=1)
+    ohp = orc.Hyper(qhm_mode="low", **common)
+    ghp = lordo.hparams(qhm_mode=1, grad_dtype=lordo.BF16, **common)
+    W0 = [synth.weights(np.random.default_rng(synth.seed_for(90, i)), sh[0], sh[1]) for i, sh in enumerate(shapes)]
+    pair = Pair(torch, shapes, W0, ohp, ghp)
+    gens = [synth.SpikedGradient(sh[0], sh[1], 4, synth.seed_for(91, i), bf16=True) for i, sh in enumerate(shapes)]
+    t = 0
+    for window in range(2):
+        G = [g.draw(t) for g in gens]
+        Om = [synth.omega(np.random.default_rng(synth.seed_for(92, 10 * window + i)), lowrank_dims(sh)[1], sh[2]) for i, sh in enumerate(shapes)]
+        dists, orths = pair.refresh_local(G, Om, grad_scale=0.9, bf16=True)
+        assert max(orths) <= TOL_ORTH and max(dists) <= TOL_SUBSPACE, f"window {window}: orth {orths} dist {dists}"
+        pair.local_step(G, lr=1e-3, grad_scale=0.9, bf16=True, first_step_patch=(window == 0))
+        pair.compare_local(TOL)
+        t += 1
+        for _ in range(2):
+            pair.local_step([g.draw(t) for g in gens], lr=1e-3, grad_scale=0.9, bf16=True)
+            t += 1
+        pair.compare_local(TOL)
