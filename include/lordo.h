@@ -114,6 +114,11 @@ typedef struct {
                                     same subspace).  Needs every rank <= 1024 (LORDO_EINVAL otherwise); sets of ranks up to 128 take a
                                     much faster solver                                                  */
   int32_t reserved;              /* must be 0 */
+  uint64_t seed;                 /* seed of the library's own Gaussian generator, used where the caller passes no
+                                    random block: lordo_init_projection(Block = NULL) (Alg. 1 "Require": random Q_0) and
+                                    lordo_refresh_subspace*(Omega = NULL).  Counter-based (Philox-4x32-10 + Box-Muller):
+                                    element e of the block of matrix i in the k-th such call of the context is a function
+                                    of (seed, i, k, e) alone, so two contexts initialised alike draw the same blocks */
 } lordo_hparams;
 
 /* Bytes of arena lordo_init needs for these shapes and hyper-parameters (host call). */
@@ -131,7 +136,8 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
 /* Random initial projection of the global variant (Alg. 1 "Require": Q_0 random, against the identity
  * columns of Alg. 2 that lordo_init leaves): Q_0 = orthonormal basis of the caller's block, by the same
  * CholeskyQR as the refresh (columns signed so that the triangular factor has a positive diagonal).
- *   Block  host array of n device pointers, p x r fp32 each (e.g. Gaussian), read only, full column rank.
+ *   Block  host array of n device pointers, p x r fp32 each (e.g. Gaussian), read only, full column rank;
+ *          NULL: the library draws Gaussian blocks from hp.seed.
  * Valid only before the first local step (LORDO_ESTATE afterwards: changing the basis of running moments
  * is what lordo_refresh_subspace does). */
 int lordo_init_projection(lordo_ctx* ctx, const void* const* Block, void* stream);
@@ -157,8 +163,10 @@ int lordo_local_step(lordo_ctx* ctx, void* const* W, const void* const* G,
  *  signed so that the triangular factor has a positive diagonal; then, if t > 0, Alg. 1 rotation:
  *  R = Q_new^T Q;  u <- R u;  v <- c2 | (R o R)(v/c2 - (u/c1)^2) + (R u/c1)^2 |;  finally Q <- Q_new).
  *   Src        host array of n device pointers, p x q each, element type src_dtype
- *              (a gradient, or an averaged pseudo-gradient); read only.  Every entry non-NULL.
- *   Omega      host array of n device pointers, q x r fp32 Gaussian start blocks, read only.
+ *              (a gradient, or an averaged pseudo-gradient); read only.  A NULL entry leaves that matrix
+ *              out: its Q, u, v (and its value in lordo_get_mssv) stay as they are.
+ *   Omega      host array of n device pointers, q x r fp32 Gaussian start blocks, read only (entries of
+ *              matrices that are left out may be NULL); NULL: the library draws the blocks from hp.seed.
  * The storage behind LORDO_STATE_GLOW and LORDO_STATE_NUPD serves as scratch: both hold the values of the
  * last local step only until the next refresh.  With hp.uplink_buffer the call returns LORDO_ESTATE while
  * the buffer is non-empty (see lordo_export_uplink). */
@@ -175,7 +183,7 @@ int lordo_refresh_subspace(lordo_ctx* ctx, const void* const* Src, int32_t src_d
  * lordo_refresh_subspace*, and get/set of LORDO_STATE_ERR, return LORDO_ESTATE; so does a local step
  * with other gradient pointers.
  *   G      host array of n device pointers, p x q of hp.grad_dtype, read only.
- *   Omega  host array of n device pointers, q x r fp32 Gaussian start blocks, read only. */
+ *   Omega  host array of n device pointers, q x r fp32 Gaussian start blocks, read only; NULL: drawn from hp.seed. */
 int lordo_refresh_subspace_local(lordo_ctx* ctx, const void* const* G, double grad_scale,
                                  const void* const* Omega, void* stream);
 
@@ -186,7 +194,8 @@ int lordo_export_pseudograd(lordo_ctx* ctx, const void* const* W, void* const* D
  * or, if AvgDelta == NULL, this worker's own anchor - W:
  *   mu == 0:  W <- anchor - eta_s D
  *   mu != 0:  b <- mu b + D;  W <- anchor - eta_s (D + mu b) (Nesterov) or anchor - eta_s b (heavy ball)
- * then anchor <- W.  W is written (and read only when AvgDelta == NULL). */
+ * then anchor <- W.  W is written (and read only when AvgDelta == NULL).  With AvgDelta == NULL the call needs at
+ * least one local step since the last outer step (LORDO_ESTATE otherwise: there is no pseudo-gradient yet). */
 int lordo_outer_step(lordo_ctx* ctx, void* const* W, const void* const* AvgDelta, void* stream);
 
 /* Up-link time buffer (App. A.5.1, "Worker Communication"; memory-overhead table): with

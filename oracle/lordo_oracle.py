@@ -4,7 +4,10 @@ TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
 HIP library must compute; it is imported by tests/, by the smoke check and by
 the benchmark's cpu_baseline leg and by nothing else.  It shares no code with
 the HIP path and never sees a value produced by it, except where a test hands
-it a basis on purpose (teacher forcing of the sign/rotation-ambiguous basis).
+it a basis on purpose (teacher forcing of the sign/rotation-ambiguous basis)
+and, in the tests' first-step handling, the sign of an update whose argument is
+zero to working precision (tests/harness.py checks that value against the
+closed form before it is taken).
 
 Every function is the paper's formula written out with numpy in float64, one
 statement per line of the formula, no blocking, fusion or reordering.  Library
@@ -211,6 +214,50 @@ def initial_projection(block: np.ndarray) -> np.ndarray:
     """Q_0 of the global variant (Alg. 1, Require: a random initial projection): the orthonormal
     basis of a random p x r block, made unique by the positive diagonal of its triangular factor."""
     return orth(np.asarray(block, dtype=F64))
+
+
+# ----------------------------------------------------------------------------
+# random blocks the method draws (Alg. 1, Require: "random initial projection"; the Gaussian start of the
+# range finder): a counter-based generator, so that a second implementation can draw the identical block
+# ----------------------------------------------------------------------------
+def philox4x32_10(counter: np.ndarray, key: np.ndarray) -> np.ndarray:
+    """Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
+    SC 2011).  counter: (..., 4) uint32, key: (..., 2) uint32 -> (..., 4) uint32.  One round: with
+    (hi0, lo0) = 0xD2511F53 * c0 and (hi1, lo1) = 0xCD9E8D57 * c2 as 64-bit products,
+    c <- (hi1 ^ c1 ^ k0, lo1, hi0 ^ c3 ^ k1, lo0); the key is bumped by (0x9E3779B9, 0xBB67AE85) between rounds."""
+    c = [np.asarray(counter, dtype=np.uint64)[..., i] for i in range(4)]
+    k = [np.asarray(key, dtype=np.uint64)[..., i] for i in range(2)]
+    mask = np.uint64(0xFFFFFFFF)
+    for _ in range(10):
+        prod0 = np.uint64(0xD2511F53) * c[0]
+        prod1 = np.uint64(0xCD9E8D57) * c[2]
+        hi0, lo0 = prod0 >> np.uint64(32), prod0 & mask
+        hi1, lo1 = prod1 >> np.uint64(32), prod1 & mask
+        c = [hi1 ^ c[1] ^ k[0], lo1, hi0 ^ c[3] ^ k[1], lo0]
+        k = [(k[0] + np.uint64(0x9E3779B9)) & mask, (k[1] + np.uint64(0xBB67AE85)) & mask]
+    return np.stack(c, axis=-1).astype(np.uint32)
+
+
+def gaussian_block(seed: int, matrix: int, draw: int, rows: int, cols: int) -> np.ndarray:
+    """rows x cols block of standard normals: element e (row-major) is output e % 4 of
+    Philox-4x32-10(counter = (e // 4 low word, e // 4 high word, matrix, draw), key = (seed low, seed high)),
+    the four outputs turned into normals in pairs by Box-Muller: u = ((x >> 8) + 1/2) 2^-24 lies in (0, 1);
+    (z0, z1) = sqrt(-2 ln u0) (cos 2 pi u1, sin 2 pi u1) from outputs 0 and 1, (z2, z3) likewise from 2 and 3."""
+    total = rows * cols
+    nquads = (total + 3) // 4
+    quad = np.arange(nquads, dtype=np.uint64)
+    counter = np.stack([quad & np.uint64(0xFFFFFFFF), quad >> np.uint64(32),
+                        np.full(nquads, matrix, dtype=np.uint64), np.full(nquads, draw, dtype=np.uint64)], axis=-1)
+    key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint64)
+    x = philox4x32_10(counter, np.broadcast_to(key, (nquads, 2)))
+    u = ((x >> np.uint32(8)).astype(F64) + 0.5) * 2.0 ** -24
+    z = np.empty((nquads, 4), dtype=F64)
+    for h in range(2):
+        rad = np.sqrt(-2.0 * np.log(u[:, 2 * h]))
+        ang = 2.0 * np.pi * u[:, 2 * h + 1]
+        z[:, 2 * h] = rad * np.cos(ang)
+        z[:, 2 * h + 1] = rad * np.sin(ang)
+    return z.reshape(-1)[:total].reshape(rows, cols)
 
 
 def range_finder(A: np.ndarray, Omega: np.ndarray, power_iters: int) -> np.ndarray:

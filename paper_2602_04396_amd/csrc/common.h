@@ -94,10 +94,17 @@ struct DevCtx {
   int32_t n;
   int32_t* flag;          // numerical breakdown latch
   int32_t slot[EXT_COUNT];  // table (absolute index) each kind uses in this launch
+  int32_t skip_null;        // 1: the source table of this refresh has NULL entries; those matrices are left as they are
 };
 
 __device__ __forceinline__ void* ext_ptr(const DevCtx& d, int table, int mat) {
   return d.ext[(int64_t)d.slot[table] * d.n + mat];
+}
+
+// A refresh may leave matrices out (NULL entry in the caller's source table): every kernel of the refresh program
+// returns at once for such a matrix, so its projection, moments and scratch are not touched.  Uniform per workgroup.
+__device__ __forceinline__ bool mat_skipped(const DevCtx& d, int mat) {
+  return d.skip_null != 0 && ext_ptr(d, EXT_SRC, mat) == nullptr;
 }
 
 constexpr int CHUNK = 2048;       // elements per workgroup of the p x q elementwise kernels
@@ -192,5 +199,7 @@ hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const flo
 hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hipStream_t s);
 // right-projected matrices only: slice 0 of the blocked array g <- scale * (plain rows x r block in zw[0])
 hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, hipStream_t s);
+// Gaussian block of every matrix from the counter-based generator: which = 0 into y[0] (p x r), 1 into zw[3] (q x r)
+hipError_t launch_gauss_block(const DevCtx& d, int which, uint64_t seed, uint32_t draw, hipStream_t s);
 
 }  // namespace lordo

@@ -81,7 +81,9 @@ __global__ __launch_bounds__(256) void k_adam4(const float* __restrict__ glow, f
     dsum += den;
     // Alg. 1 update bracket: u_hat / den, or (omega u_hat + (1 - omega) g) / den for the low-rank
     // quasi-hyperbolic case; with qw = 1, qg = 0 the value is bit-identical to u_hat / den
-    const float nn = fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;
+    // den == 0 needs eps == 0 and a second moment of exactly zero, i.e. every gradient so far was zero there (always
+    // true in the zero padding of the arena): the update is then zero, not 0 / 0
+    const float nn = den == 0.f ? 0.f : fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;
     split_bf(nn, hi[e], lo[e]);
     nv[e] = nn;
   }
@@ -227,6 +229,7 @@ hipError_t launch_identity_q(const DevCtx& d, hipStream_t s) {
 // One thread writes one 8-element group of the up-projection planes and one of the
 // down-projection planes (both have pp*rp/8 groups).
 __global__ __launch_bounds__(256) void k_pack_q(DevCtx d, int mat_first) {
+  if (mat_skipped(d, mat_first + blockIdx.y)) return;
   const MatDev& m = d.mats[mat_first + blockIdx.y];
   const float* q32 = reinterpret_cast<const float*>(d.arena + m.q32);
   uint16_t* qa_hi = reinterpret_cast<uint16_t*>(d.arena + m.qa_hi);
@@ -277,7 +280,7 @@ hipError_t launch_pack_q(const DevCtx& d, int mat_first, int mat_count, hipStrea
 // Does nothing while a numerical breakdown is latched: a refresh (or an initial projection) whose factorisation met a
 // non-positive pivot leaves the projection as it was.
 __global__ __launch_bounds__(256) void k_q_from_y(DevCtx d, int ybuf) {
-  if (*d.flag != 0) return;
+  if (*d.flag != 0 || mat_skipped(d, blockIdx.y)) return;
   const MatDev& m = d.mats[blockIdx.y];
   float* q32 = reinterpret_cast<float*>(d.arena + m.q32);
   const float* y = reinterpret_cast<const float*>(d.arena + m.y[ybuf]);
@@ -288,6 +291,7 @@ __global__ __launch_bounds__(256) void k_q_from_y(DevCtx d, int ybuf) {
 // shape of g = Q^T G with Y in the place of Q): Y (plain p x r, buffer ybuf) -> the down-projection operand
 // planes.  The planes hold Q between refreshes; the refresh repacks them from the new Q when it ends.
 __global__ __launch_bounds__(256) void k_pack_y(DevCtx d, int ybuf) {
+  if (mat_skipped(d, blockIdx.y)) return;
   const MatDev& m = d.mats[blockIdx.y];
   const float* y = reinterpret_cast<const float*>(d.arena + m.y[ybuf]);
   uint16_t* qt_hi = reinterpret_cast<uint16_t*>(d.arena + m.qt_hi);
@@ -316,6 +320,7 @@ hipError_t launch_pack_y(const DevCtx& d, int ybuf, hipStream_t s) {
 // The result of that product, left by the down-projection kernel in the layout of g (split-K slices
 // included), as the plain q x r block Z: Z[j][i] = sum over slices of g(i, j), slices added in order.
 __global__ __launch_bounds__(256) void k_glow_to_z(DevCtx d, const float* __restrict__ glow, int zbuf, AdamArgs a) {
+  if (mat_skipped(d, blockIdx.y)) return;
   const MatDev& m = d.mats[blockIdx.y];
   float* z = reinterpret_cast<float*>(d.arena + m.zw[zbuf]);
   int nsplit = a.grp_nsplit[0];
@@ -339,6 +344,7 @@ hipError_t launch_glow_to_z(const DevCtx& d, const float* glow, int zbuf, const 
 // orthonormalised Z in buffer zbuf) as bf16 hi / lo planes in operand layout (m = rank, k = column j),
 // at this matrix's place in the flat plane arrays.
 __global__ __launch_bounds__(256) void k_pack_block(DevCtx d, int zbuf, uint16_t* __restrict__ p_hi, uint16_t* __restrict__ p_lo) {
+  if (mat_skipped(d, blockIdx.y)) return;
   const MatDev& m = d.mats[blockIdx.y];
   const float* z = zbuf < 0 ? reinterpret_cast<const float*>(ext_ptr(d, EXT_OMEGA, blockIdx.y))
                             : reinterpret_cast<const float*>(d.arena + m.zw[zbuf]);
@@ -553,6 +559,7 @@ hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t
 // S_ii += coef * trace(S): keeps the first factorisation positive definite in fp32.
 // store: also keep the shift behind the Ritz values (the Rayleigh-Ritz step subtracts it from the eigenvalues).
 __global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef, int store) {
+  if (mat_skipped(d, blockIdx.x)) return;
   const MatDev& m = d.mats[blockIdx.x];
   float* S = reinterpret_cast<float*>(d.arena + m.gram);
   __shared__ float red[256];
@@ -596,6 +603,7 @@ template <bool SF32>
 __global__ __launch_bounds__(256) void k_frob2_chunks(DevCtx d, const int64_t* __restrict__ chunk_start, float* __restrict__ partial) {
   const int64_t b = blockIdx.x;
   const int mat = find_mat(chunk_start, d.n, b);
+  if (mat_skipped(d, mat)) return;
   const MatDev& m = d.mats[mat];
   const int64_t total = (int64_t)m.p * m.q;
   const int64_t off = (b - chunk_start[mat]) * CHUNK;
@@ -623,7 +631,7 @@ __global__ __launch_bounds__(256) void k_frob2_chunks(DevCtx d, const int64_t* _
 // one workgroup per matrix: sum of its partial sums in double, stored behind the r Ritz values
 __global__ __launch_bounds__(256) void k_frob2_sum(DevCtx d, const int64_t* __restrict__ chunk_start, const float* __restrict__ partial) {
   const MatDev& m = d.mats[blockIdx.x];
-  if (m.ritz < 0) return;
+  if (m.ritz < 0 || mat_skipped(d, blockIdx.x)) return;
   __shared__ double red[256];
   double acc = 0.0;
   for (int64_t b = chunk_start[blockIdx.x] + threadIdx.x; b < chunk_start[blockIdx.x + 1]; b += 256) acc += (double)partial[b];
@@ -670,6 +678,7 @@ __device__ __forceinline__ float lane_value(float x, int lane) {      // value o
 // is broadcast lane by lane through scalar registers (v_readlane) and applied with one FMA per
 // element.  Everything is unrolled, every register index is a constant.
 __global__ __launch_bounds__(256) void k_potf2(DevCtx d, int jb) {
+  if (mat_skipped(d, blockIdx.x)) return;
   const MatDev& m = d.mats[blockIdx.x];
   const int o = jb * NB;
   int nbk = m.r - o;
@@ -773,6 +782,7 @@ __global__ __launch_bounds__(256) void k_potf2(DevCtx d, int jb) {
 // The inverses of the diagonal blocks, copied to their places on the diagonal of the r x r inverse of the
 // whole factor (the rows below are then built from them by products).
 __global__ __launch_bounds__(256) void k_diag_inverses(DevCtx d) {
+  if (mat_skipped(d, blockIdx.x)) return;
   const MatDev& m = d.mats[blockIdx.x];
   const float* X = reinterpret_cast<const float*>(d.arena + m.dinv);
   float* M = reinterpret_cast<float*>(d.arena + m.minv);
@@ -868,7 +878,7 @@ __device__ __forceinline__ bool rotate_swap(float (&p)[8], float (&q)[8]) {
 __global__ __launch_bounds__(1024) void k_jacobi_svd(DevCtx d, int top_value_only) {
   const MatDev m = d.mats[blockIdx.x];
   const int r = m.r;
-  if (r > 128 || m.ritz < 0) return;
+  if (r > 128 || m.ritz < 0 || mat_skipped(d, blockIdx.x)) return;
   const int n = (r + 1) & ~1;
   const int ld = n + 1;
   const int half = n / 2;
@@ -1011,7 +1021,7 @@ hipError_t launch_jacobi_svd(const DevCtx& d, int rmax, bool top_value_only, hip
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_jsvd_init(DevCtx d) {
   const MatDev& m = d.mats[blockIdx.y];
-  if (m.ritz < 0) return;
+  if (m.ritz < 0 || mat_skipped(d, blockIdx.y)) return;
   const int r = m.r;
   const float* L = reinterpret_cast<const float*>(d.arena + m.lfac);
   float* Xt = reinterpret_cast<float*>(d.arena + m.gram);
@@ -1030,7 +1040,7 @@ template <int BW, int CH>
 __global__ __launch_bounds__(BW * 32) void k_jsvd_block(DevCtx d, int oround, int sweep, int* __restrict__ flags, int allow) {
   if (sweep > 0 && flags[sweep - 1] <= allow) return;         // the previous sweep rotated (next to) nothing: converged
   const MatDev& m = d.mats[blockIdx.y];
-  if (m.ritz < 0) return;
+  if (m.ritz < 0 || mat_skipped(d, blockIdx.y)) return;
   const int r = m.r;
   const int nb = (r + BW - 1) / BW, nbe = (nb + 1) & ~1, mmb = nbe - 1;
   const int kb = blockIdx.x;
@@ -1108,7 +1118,7 @@ __global__ __launch_bounds__(BW * 32) void k_jsvd_block(DevCtx d, int oround, in
 // squared column norms, order, signs, output: one workgroup per matrix (as the tail of k_jacobi_svd)
 __global__ __launch_bounds__(256) void k_jsvd_finish(DevCtx d, int top_value_only) {
   const MatDev& m = d.mats[blockIdx.x];
-  if (m.ritz < 0) return;
+  if (m.ritz < 0 || mat_skipped(d, blockIdx.x)) return;
   const int r = m.r;
   const float* Xt = reinterpret_cast<const float*>(d.arena + m.gram);
   float* rz = reinterpret_cast<float*>(d.arena + m.ritz);
@@ -1196,6 +1206,7 @@ hipError_t launch_jacobi_svd_blocked(const DevCtx& d, int rmax, int64_t rank_sq_
 // k_rot_post keeps the flat numbering: its writes go to the blocked arrays, contiguous over threads.
 __global__ __launch_bounds__(256) void k_rot_pre(DevCtx d, const float* __restrict__ u, const float* __restrict__ v,
                                                  float inv_c1, float inv_c2) {
+  if (mat_skipped(d, blockIdx.y)) return;
   const MatDev& m = d.mats[blockIdx.y];
   float* uh = reinterpret_cast<float*>(d.arena + m.zw[2]);
   float* var = reinterpret_cast<float*>(d.arena + m.zw[3]);
@@ -1228,7 +1239,7 @@ hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float
   return hipGetLastError();
 }
 __global__ __launch_bounds__(256) void k_rot_post(DevCtx d, float* __restrict__ u, float* __restrict__ v, float c1, float c2) {
-  if (*d.flag != 0) return;       // a breakdown is latched: the moments stay in the coordinates of the projection that stays
+  if (*d.flag != 0 || mat_skipped(d, blockIdx.y)) return;       // a breakdown is latched: the moments stay in the coordinates of the projection that stays
   const MatDev& m = d.mats[blockIdx.y];
   const float* a1 = reinterpret_cast<const float*>(d.arena + m.zw[0]);
   const float* a2 = reinterpret_cast<const float*>(d.arena + m.zw[1]);
@@ -1340,6 +1351,55 @@ __global__ __launch_bounds__(256) void k_tr_exchange(DevCtx d, float* glow, floa
     glow[m.lr_off + o] = (j < m.q && i < m.r) ? scale * plain[j * m.r + i] : 0.f;
   }
 }
+// ---------------------------------------------------------------------------------------
+// Gaussian start blocks drawn on the device (Alg. 1 Require: a random initial projection; the start block of the
+// range finder when the caller supplies none).  Counter-based: element e (row-major index in the block) of matrix
+// `mat` in draw number `draw` of a context seeded with `seed` is output e % 4 of
+//   Philox-4x32-10(counter = (e / 4 low, e / 4 high, mat, draw), key = (seed low, seed high))      (Salmon et al., SC 2011)
+// turned into standard normals two at a time by the Box-Muller transform: u = (x >> 8 + 0.5) 2^-24 in (0, 1),
+// (z0, z1) = sqrt(-2 ln u0) (cos 2 pi u1, sin 2 pi u1) from outputs (0, 1), (z2, z3) likewise from outputs (2, 3).
+// A float64 reference of the same generator reproduces the block to fp32 rounding of ln / cos / sin.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c[0]), lo0 = 0xD2511F53u * c[0];
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c[2]), lo1 = 0xCD9E8D57u * c[2];
+    const uint32_t n0 = hi1 ^ c[1] ^ k0, n2 = hi0 ^ c[3] ^ k1;
+    c[0] = n0; c[1] = lo1; c[2] = n2; c[3] = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+}
+// which = 0: buffer 0 of the Y pair (p x r: the block of an initial projection); 1: zw[3] (q x r: a start block Omega)
+__global__ __launch_bounds__(256) void k_gauss_block(DevCtx d, int which, uint64_t seed, uint32_t draw) {
+  const int mat = blockIdx.y;
+  if (mat_skipped(d, mat)) return;
+  const MatDev& m = d.mats[mat];
+  float* dst = reinterpret_cast<float*>(d.arena + (which == 0 ? m.y[0] : m.zw[3]));
+  const int64_t total = (int64_t)(which == 0 ? m.p : m.q) * m.r;
+  const int64_t nquads = (total + 3) / 4;
+  for (int64_t qd = (int64_t)blockIdx.x * 256 + threadIdx.x; qd < nquads; qd += (int64_t)gridDim.x * 256) {
+    uint32_t c[4] = {(uint32_t)qd, (uint32_t)((uint64_t)qd >> 32), (uint32_t)mat, draw};
+    philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
+    float z[4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const float u0 = ((float)(c[2 * h] >> 8) + 0.5f) * 5.9604644775390625e-8f;
+      const float u1 = ((float)(c[2 * h + 1] >> 8) + 0.5f) * 5.9604644775390625e-8f;
+      const float rad = sqrtf(-2.f * logf(u0));
+      const float ang = 6.283185307179586f * u1;
+      z[2 * h] = rad * cosf(ang);
+      z[2 * h + 1] = rad * sinf(ang);
+    }
+    for (int e = 0; e < 4 && qd * 4 + e < total; ++e) dst[qd * 4 + e] = z[e];
+  }
+}
+hipError_t launch_gauss_block(const DevCtx& d, int which, uint64_t seed, uint32_t draw, hipStream_t s) {
+  hipLaunchKernelGGL(k_gauss_block, dim3(128, d.n), dim3(256), 0, s, d, which, seed, draw);
+  return hipGetLastError();
+}
+
 hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, hipStream_t s) {
   hipLaunchKernelGGL(k_tr_exchange, dim3(64, d.n), dim3(256), 0, s, d, glow, scale);
   return hipGetLastError();

@@ -327,6 +327,7 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
   constexpr int NV = TM * TK / 4 / 256;
   const GemmTile t = tiles[blockIdx.x];
   const GemmDesc g = descs[t.desc];
+  if (mat_skipped(d, g.mat)) return;
   const int M = g.M, N = g.N;
   const int kbeg = g.ksplit > 1 ? t.ks * g.klen : 0;
   int K = g.ksplit > 1 ? (kbeg + g.klen < g.K ? kbeg + g.klen : g.K) : g.K;           // end of this slice
@@ -406,7 +407,7 @@ __global__ __launch_bounds__(256) void k_gemm32(DevCtx d, const GemmDesc* __rest
 // Sum of the split-K slices in slice order (deterministic), then alpha, beta and the optional square.
 __global__ __launch_bounds__(256) void k_gemm_reduce(DevCtx d, const GemmDesc* __restrict__ descs) {
   const GemmDesc g = descs[blockIdx.y];
-  if (g.ksplit <= 1) return;
+  if (g.ksplit <= 1 || mat_skipped(d, g.mat)) return;
   const float* Pp = reinterpret_cast<const float*>(resolve(d, g.P, g.mat));
   float* C = reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C, g.mat)));
   float* C2 = g.C2.off >= 0 ? reinterpret_cast<float*>(const_cast<char*>(resolve(d, g.C2, g.mat))) : nullptr;

@@ -845,6 +845,9 @@ struct Profiler {
   bool on = false;
   std::vector<hipEvent_t> pool;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> spans[NUM_KCLASS];
+  bool open[NUM_KCLASS] = {};         // begin() recorded, end() not yet
+  double sum_ms[NUM_KCLASS] = {};     // spans already read: their events went back to the pool
+  int64_t count[NUM_KCLASS] = {};
   hipEvent_t get() {
     if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
     hipEvent_t e = nullptr;
@@ -857,15 +860,28 @@ struct Profiler {
     if (!a || !b) return;
     (void)hipEventRecord(a, s);
     spans[k].push_back({a, b});
+    open[k] = true;
   }
   void end(int k, hipStream_t s) {
-    if (!on || spans[k].empty()) return;
+    if (!on || !open[k]) return;
     (void)hipEventRecord(spans[k].back().second, s);
+    open[k] = false;
+  }
+  // a call that fails between begin() and end() drops its span: the closing event was never recorded
+  void abandon(int k) {
+    if (!open[k]) return;
+    pool.push_back(spans[k].back().first);
+    pool.push_back(spans[k].back().second);
+    spans[k].pop_back();
+    open[k] = false;
   }
   void clear() {
-    for (auto& v : spans) {
-      for (auto& pr : v) { pool.push_back(pr.first); pool.push_back(pr.second); }
-      v.clear();
+    for (int k = 0; k < NUM_KCLASS; ++k) {
+      for (auto& pr : spans[k]) { pool.push_back(pr.first); pool.push_back(pr.second); }
+      spans[k].clear();
+      open[k] = false;
+      sum_ms[k] = 0.0;
+      count[k] = 0;
     }
   }
   ~Profiler() {
@@ -886,6 +902,8 @@ struct lordo_ctx {
   // come with the same gradient pointers and takes its projected matrix from the buffer alone
   bool grad_folded = false;
   int64_t window_steps = 0;      // local steps since the last outer step: what the up-link buffer holds
+  uint32_t draws = 0;            // Gaussian blocks drawn from the internal generator so far (the `draw` word of its counter)
+  bool gauss_init = false;       // lordo_init_projection without a block: the program's first op draws it
   std::vector<const void*> folded_g;
   int device = 0;
   // cached caller pointer tables: EXT_SLOTS per kind, replaced round-robin
@@ -895,10 +913,14 @@ struct lordo_ctx {
   template <class T>
   T* at(int64_t off) const { return reinterpret_cast<T*>(dev.arena + off); }
 
-  int set_ext(int table, void* const* host, hipStream_t s) {
-    if (!host) return LORDO_EINVAL;
+  static bool has_null(const void* const* host, int n) {
     for (int i = 0; i < n; ++i)
-      if (!host[i]) return LORDO_EINVAL;
+      if (!host[i]) return true;
+    return false;
+  }
+  int set_ext(int table, void* const* host, hipStream_t s, bool allow_null = false) {
+    if (!host) return LORDO_EINVAL;
+    if (!allow_null && has_null(host, n)) return LORDO_EINVAL;
     for (int k = 0; k < EXT_SLOTS; ++k) {
       const std::vector<void*>& sh = shadow[table][k];
       if (!sh.empty() && std::memcmp(sh.data(), host, sizeof(void*) * n) == 0) {
@@ -1004,10 +1026,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (!c || !W || !G || !std::isfinite(lr) || !std::isfinite(grad_scale)) return LORDO_EINVAL;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   Plan& P = c->plan;
-  int rc = c->set_ext(EXT_W, W, s);
-  if (rc != LORDO_OK) return rc;
-  rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
-  if (rc != LORDO_OK) return rc;
+  if (lordo_ctx::has_null(reinterpret_cast<const void* const*>(W), c->n) || lordo_ctx::has_null(G, c->n)) return LORDO_EINVAL;
   // after lordo_refresh_subspace_local the error buffer already holds grad_scale * G + E of this step
   const bool folded = c->grad_folded;
   if (folded && std::memcmp(c->folded_g.data(), G, sizeof(void*) * c->n) != 0) return LORDO_ESTATE;
@@ -1048,6 +1067,11 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
     for (int i = 0; i < c->n; ++i)
       if ((reinterpret_cast<uintptr_t>(G[i]) & (g_f32 ? 15 : 7)) != 0) return LORDO_EINVAL;
   }
+  // every argument and state check has passed: from here on kernels are enqueued
+  int rc = c->set_ext(EXT_W, W, s);
+  if (rc != LORDO_OK) return rc;
+  rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
+  if (rc != LORDO_OK) return rc;
   DownFuse fuse;
   fuse.u = c->at<float>(P.u); fuse.v = c->at<float>(P.v);
   fuse.n_hi = c->at<uint16_t>(P.n_hi); fuse.n_lo = c->at<uint16_t>(P.n_lo);
@@ -1148,10 +1172,11 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
     c2 = 1.0 - std::pow(c->hp.beta2, (double)c->t);
   }
   c->prof.begin(LORDO_K_REFRESH, s);
-  if (fold)
-    HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)fold_scale, c->hp.grad_dtype == LORDO_F32, s));
-  int rc = run_ops(c, P.ops, src_dtype, s, rotate, c1, c2, proj_kernels, stream_kernel, proj_tr);
-  if (rc != LORDO_OK) return rc;
+  int rc = LORDO_OK;
+  if (fold && launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)fold_scale, c->hp.grad_dtype == LORDO_F32, s) != hipSuccess)
+    rc = LORDO_EHIP;
+  if (rc == LORDO_OK) rc = run_ops(c, P.ops, src_dtype, s, rotate, c1, c2, proj_kernels, stream_kernel, proj_tr);
+  if (rc != LORDO_OK) { c->prof.abandon(LORDO_K_REFRESH); return rc; }
   c->prof.end(LORDO_K_REFRESH, s);
   c->refreshed = true;
   return LORDO_OK;
@@ -1208,7 +1233,10 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
         break;
       case OP_Q_FROM_Y: HIPCHK(launch_q_from_y(c->dev, op.iarg, s)); break;
       case OP_PACK: HIPCHK(launch_pack_q(c->dev, 0, c->n, s)); break;
-      case OP_Y_FROM_EXT: HIPCHK(launch_y_from_ext(c->dev, s)); break;
+      case OP_Y_FROM_EXT:
+        if (c->gauss_init) HIPCHK(launch_gauss_block(c->dev, 0, c->hp.seed, c->draws, s));
+        else HIPCHK(launch_y_from_ext(c->dev, s));
+        break;
       default: return LORDO_ESTATE;
     }
   }
@@ -1226,7 +1254,7 @@ static int source_paths(lordo_ctx* c, const void* const* Src, int32_t src_dtype,
   for (int i = 0; i < c->n && proj_kernels; ++i)
     if ((c->plan.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(Src[i]) & pair_mask) != 0) proj_kernels = false;
   if (proj_kernels && src_dtype == LORDO_BF16) {
-    int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+    int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s, true);
     if (rc != LORDO_OK) return rc;
   }
   // the products contracted over the columns stream a bf16 source straight into matrix-core fragment order
@@ -1244,20 +1272,39 @@ static int source_paths(lordo_ctx* c, const void* const* Src, int32_t src_dtype,
   return LORDO_OK;
 }
 
+// Start blocks of the range finder: the caller's table, or (Omega == NULL) blocks drawn by the library's generator
+// into the fourth q x r scratch block of every matrix, which nothing touches before the first product has read it.
+static int select_omega(lordo_ctx* c, const void* const* Omega, hipStream_t s) {
+  if (Omega) return c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s, c->dev.skip_null != 0);
+  HIPCHK(launch_gauss_block(c->dev, 1, c->hp.seed, c->draws, s));
+  ++c->draws;
+  std::vector<void*> own(c->n);
+  for (int i = 0; i < c->n; ++i) own[i] = c->dev.arena + c->plan.mat[i].zw[3];
+  return c->set_ext(EXT_OMEGA, own.data(), s);
+}
+
 int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, void* stream) {
-  if (!c || !Src || !Omega) return LORDO_EINVAL;
+  if (!c || !Src) return LORDO_EINVAL;
   if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
+  for (int i = 0; i < c->n; ++i)
+    if (Omega && Src[i] && !Omega[i]) return LORDO_EINVAL;      // (a matrix that is left out needs no start block)
   if (c->grad_folded) return LORDO_ESTATE;          // the error buffer holds a folded gradient: a local step must consume it first
   if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;   // the buffer is in coordinates of the current Q
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s);
+  // a NULL source leaves that matrix out: its projection, moments and similarity value stay as they are
+  int live = 0;
+  for (int i = 0; i < c->n; ++i) live += Src[i] != nullptr;
+  if (live == 0) return LORDO_OK;
+  const bool some_null = live < c->n;
+  int rc = c->set_ext(EXT_SRC, const_cast<void* const*>(reinterpret_cast<const void* const*>(Src)), s, true);
   if (rc != LORDO_OK) return rc;
-  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
-  if (rc != LORDO_OK) return rc;
-  SrcPaths sp;
-  rc = source_paths(c, Src, src_dtype, s, sp);
-  if (rc != LORDO_OK) return rc;
-  return run_refresh(c, src_dtype, s, false, 0.0, sp.proj_kernels, sp.stream_kernel, sp.proj_tr);
+  c->dev.skip_null = some_null ? 1 : 0;             // (before the start blocks are drawn: none for a matrix left out)
+  rc = select_omega(c, Omega, s);
+  SrcPaths sp{};
+  if (rc == LORDO_OK) rc = source_paths(c, Src, src_dtype, s, sp);
+  if (rc == LORDO_OK) rc = run_refresh(c, src_dtype, s, false, 0.0, sp.proj_kernels, sp.stream_kernel, sp.proj_tr);
+  c->dev.skip_null = 0;
+  return rc;
 }
 
 int lordo_spectral_gap(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, float* dev_out, void* stream) {
@@ -1274,41 +1321,52 @@ int lordo_spectral_gap(lordo_ctx* c, const void* const* Src, int32_t src_dtype, 
   if (rc != LORDO_OK) return rc;
   c->prof.begin(LORDO_K_REFRESH, s);
   rc = run_ops(c, c->plan.gap_ops, src_dtype, s, false, 1.0, 1.0, sp.proj_kernels, sp.stream_kernel, sp.proj_tr);
-  if (rc != LORDO_OK) return rc;
-  HIPCHK(launch_stable_rank(c->dev, dev_out, 1, s));
+  if (rc == LORDO_OK && launch_stable_rank(c->dev, dev_out, 1, s) != hipSuccess) rc = LORDO_EHIP;
+  if (rc != LORDO_OK) { c->prof.abandon(LORDO_K_REFRESH); return rc; }
   c->prof.end(LORDO_K_REFRESH, s);
   return LORDO_OK;
 }
 
 int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {
-  if (!c || !G || !Omega || !std::isfinite(grad_scale)) return LORDO_EINVAL;
+  if (!c || !G || !std::isfinite(grad_scale)) return LORDO_EINVAL;
+  if (lordo_ctx::has_null(G, c->n) || (Omega && lordo_ctx::has_null(Omega, c->n))) return LORDO_EINVAL;
   if (!c->hp.error_feedback || c->grad_folded) return LORDO_ESTATE;
   if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   Plan& P = c->plan;
   int rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
   if (rc != LORDO_OK) return rc;
-  rc = c->set_ext(EXT_OMEGA, const_cast<void* const*>(reinterpret_cast<const void* const*>(Omega)), s);
+  rc = select_omega(c, Omega, s);
   if (rc != LORDO_OK) return rc;
   std::vector<void*> src(c->n);
   for (int i = 0; i < c->n; ++i) src[i] = c->dev.arena + P.mat[i].err;
   rc = c->set_ext(EXT_SRC, src.data(), s);
   if (rc != LORDO_OK) return rc;
-  c->grad_folded = true;
-  c->folded_g.assign(G, G + c->n);
   bool proj_kernels = P.down_pipe != 0 && !P.any_tr;   // the residual is 256-byte aligned; pairs of columns need an even q
   for (int i = 0; i < c->n && proj_kernels; ++i)
     if ((P.mat[i].q & 1) != 0) proj_kernels = false;
-  return run_refresh(c, LORDO_F32, s, true, grad_scale, proj_kernels, false);
+  rc = run_refresh(c, LORDO_F32, s, true, grad_scale, proj_kernels, false);
+  if (rc != LORDO_OK) return rc;
+  // only a refresh that was enqueued in full commits the context to the step that consumes the folded buffer
+  c->grad_folded = true;
+  c->folded_g.assign(G, G + c->n);
+  return LORDO_OK;
 }
 
 int lordo_init_projection(lordo_ctx* c, const void* const* Block, void* stream) {
-  if (!c || !Block) return LORDO_EINVAL;
+  if (!c) return LORDO_EINVAL;
+  if (Block && lordo_ctx::has_null(Block, c->n)) return LORDO_EINVAL;
   if (c->t != 0 || c->grad_folded) return LORDO_ESTATE;      // the moments would have to be rotated: that is what a refresh does
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  int rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(Block)), s);
-  if (rc != LORDO_OK) return rc;
-  return run_ops(c, c->plan.init_ops, LORDO_F32, s, false, 1.0, 1.0, false, false);
+  if (Block) {
+    int rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(Block)), s);
+    if (rc != LORDO_OK) return rc;
+  }
+  c->gauss_init = Block == nullptr;              // no block: the program's first op draws a Gaussian one from hp.seed
+  const int rc = run_ops(c, c->plan.init_ops, LORDO_F32, s, false, 1.0, 1.0, false, false);
+  if (c->gauss_init) ++c->draws;
+  c->gauss_init = false;
+  return rc;
 }
 
 int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* DeltaOut, void* stream) {
@@ -1326,6 +1384,9 @@ int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* Del
 
 int lordo_outer_step(lordo_ctx* c, void* const* W, const void* const* AvgDelta, void* stream) {
   if (!c || !W) return LORDO_EINVAL;
+  if (lordo_ctx::has_null(reinterpret_cast<const void* const*>(W), c->n) || (AvgDelta && lordo_ctx::has_null(AvgDelta, c->n))) return LORDO_EINVAL;
+  // this worker's own pseudo-gradient exists only after local steps: none since the last outer step is a caller error
+  if (!AvgDelta && c->window_steps == 0) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int rc = c->set_ext(EXT_W, W, s);
   if (rc != LORDO_OK) return rc;
@@ -1564,14 +1625,21 @@ int lordo_profile_read(lordo_ctx* c, int32_t kernel_class, double* total_ms, int
   if (!c || !total_ms || !launches || kernel_class < 0 || kernel_class >= NUM_KCLASS) return LORDO_EINVAL;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   HIPCHK(hipStreamSynchronize(s));
-  double sum = 0.0;
-  for (auto& pr : c->prof.spans[kernel_class]) {
+  Profiler& pf = c->prof;
+  pf.abandon(kernel_class);                       // (only a failed call leaves a span open)
+  // completed spans are folded into the running sums and their events reused, so a long profiled run holds a
+  // bounded number of events
+  for (auto& pr : pf.spans[kernel_class]) {
     float ms = 0.f;
     HIPCHK(hipEventElapsedTime(&ms, pr.first, pr.second));
-    sum += ms;
+    pf.sum_ms[kernel_class] += ms;
+    ++pf.count[kernel_class];
+    pf.pool.push_back(pr.first);
+    pf.pool.push_back(pr.second);
   }
-  *total_ms = sum;
-  *launches = (int64_t)c->prof.spans[kernel_class].size();
+  pf.spans[kernel_class].clear();
+  *total_ms = pf.sum_ms[kernel_class];
+  *launches = pf.count[kernel_class];
   return LORDO_OK;
 }
 

@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256) void k_proj_down(DevCtx d, const ProjTile* __r
   constexpr int BK = 32 * KG;                                 // rows of G per pipeline stage
   constexpr int KGRPS = 4 * KG;                               // 8-row groups per stage
   const ProjTile t = tiles[blockIdx.x];
-  if (t.mat < 0) return;
+  if (t.mat < 0 || mat_skipped(d, t.mat)) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
   const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
@@ -367,7 +367,8 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
     const float vn = fmaf(f.b2, vv[e], f.omb2 * (g[e] * g[e]));
     uu[e] = un;
     vv[e] = vn;
-    const float nn = (un * f.inv_c1) / (sqrtf(vn * f.inv_c2) + f.eps);
+    const float den = sqrtf(vn * f.inv_c2) + f.eps;
+    const float nn = den == 0.f ? 0.f : (un * f.inv_c1) / den;       // eps == 0 and no gradient yet (e.g. the padding): zero, not 0 / 0
     hi[e] = f2bf_rne(nn);
     lo[e] = f2bf_rne(nn - __uint_as_float(hi[e] << 16));
   }
@@ -402,7 +403,7 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   constexpr int BK = 32;
   constexpr int NW = 8;
   const ProjTile t = tiles[blockIdx.x];
-  if (t.mat < 0) return;
+  if (t.mat < 0 || mat_skipped(d, t.mat)) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
   const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
@@ -668,7 +669,7 @@ __global__ __launch_bounds__(512) void k_proj_down_tr(DevCtx d, const ProjTile* 
   constexpr int SSLOTS = GSLOTS + ASLOTS;
   constexpr int NDMA = 2 + 2 * RB;                             // loads per wave and stage
   const ProjTile t = tiles[blockIdx.x];
-  if (t.mat < 0) return;
+  if (t.mat < 0 || mat_skipped(d, t.mat)) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qt_hi = TO_GLOBAL(const u32x4, d.arena + m.qt_hi);
   const GAS u32x4* qt_lo = TO_GLOBAL(const u32x4, d.arena + m.qt_lo);
@@ -918,7 +919,7 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __restrict__ tiles,
                                                  const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr, int to_mom) {
   const ProjTile t = tiles[blockIdx.x];
-  if (t.mat < 0) return;
+  if (t.mat < 0 || mat_skipped(d, t.mat)) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qa_hi = TO_GLOBAL(const u32x4, d.arena + m.qa_hi);
   const GAS u32x4* qa_lo = TO_GLOBAL(const u32x4, d.arena + m.qa_lo);
@@ -1060,7 +1061,7 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   constexpr int AM = NW == 4 ? 2 : 1;                      // row blocks per wave
   constexpr int WM = 4 / AM;                               // wave rows
   const ProjTile t = tiles[blockIdx.x];
-  if (t.mat < 0) return;
+  if (t.mat < 0 || mat_skipped(d, t.mat)) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* qa_hi = TO_GLOBAL(const u32x4, d.arena + m.qa_hi);
   const GAS u32x4* qa_lo = TO_GLOBAL(const u32x4, d.arena + m.qa_lo);
@@ -1335,7 +1336,7 @@ __device__ __forceinline__ void store_y_tile(const DevCtx& d, const MatDev& m, c
 __global__ __launch_bounds__(256) void k_src_times_block(DevCtx d, const ProjTile* __restrict__ tiles,
                                                          const uint16_t* __restrict__ b_hi, const uint16_t* __restrict__ b_lo) {
   const ProjTile t = tiles[blockIdx.x];
-  if (t.mat < 0) return;
+  if (t.mat < 0 || mat_skipped(d, t.mat)) return;
   const MatDev m = d.mats[t.mat];
   const GAS u32x4* bh = TO_GLOBAL(const u32x4, b_hi + m.lr_off);
   const GAS u32x4* bl = TO_GLOBAL(const u32x4, b_lo + m.lr_off);

@@ -41,15 +41,16 @@ class HParams(C.Structure):
         ("power_iters", C.c_int32), ("orth_passes", C.c_int32),
         ("grad_dtype", C.c_int32), ("uplink_buffer", C.c_int32),
         ("rayleigh_ritz", C.c_int32), ("reserved", C.c_int32),
+        ("seed", C.c_uint64),
     ]
 
 
 def hparams(beta1=0.9, beta2=0.999, eps=1e-8, bias_correction=True, outer_lr=1.0, outer_momentum=0.0,
             outer_nesterov=False, power_iters=2, orth_passes=2, grad_dtype=BF16, qhm_mode=0, omega=1.0,
-            error_feedback=False, uplink_buffer=False, rayleigh_ritz=False) -> HParams:
+            error_feedback=False, uplink_buffer=False, rayleigh_ritz=False, seed=0) -> HParams:
     return HParams(beta1, beta2, eps, int(bias_correction), qhm_mode, omega, int(error_feedback),
                    int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, int(uplink_buffer),
-                   int(rayleigh_ritz), 0)
+                   int(rayleigh_ritz), 0, int(seed))
 
 
 class LordoError(RuntimeError):
@@ -121,7 +122,7 @@ def _ptr_array(tensors):
         return tensors.arr
     arr = (C.c_void_p * len(tensors))()
     for i, t in enumerate(tensors):
-        arr[i] = t.data_ptr()
+        arr[i] = None if t is None else t.data_ptr()
     return arr
 
 
@@ -167,12 +168,14 @@ class Lordo:
         self._check_tensors(tensors, dtype or self.torch.float32, kind)
         return PtrList(list(tensors), _ptr_array(tensors))
 
-    def _check_tensors(self, ts, dtype, kind):
+    def _check_tensors(self, ts, dtype, kind, allow_none=False):
         if isinstance(ts, PtrList):
             return
         if len(ts) != self.n:
             raise ValueError("one tensor per matrix expected")
         for t, sh in zip(ts, self.shapes):
+            if t is None and allow_none:
+                continue
             p, q, r = sh[:3]
             # low-rank arrays of a right-projected matrix are those of the transposed problem
             tp, tq = (q, p) if len(sh) > 3 and sh[3] else (p, q)
@@ -189,19 +192,30 @@ class Lordo:
         self._check_tensors(G, self._grad_dtype(), "pq")
         _check(self.lib.lordo_local_step(self.ctx, _ptr_array(W), _ptr_array(G), float(lr), float(grad_scale), self._stream()))
 
-    def init_projection(self, block):
-        """Q_0 = orthonormal basis of the p x r blocks given (Alg. 1: random initial projection)."""
+    def init_projection(self, block=None):
+        """Q_0 = orthonormal basis of the p x r blocks given (Alg. 1: random initial projection); None: blocks
+        drawn by the library from hp.seed."""
+        if block is None:
+            _check(self.lib.lordo_init_projection(self.ctx, None, self._stream()))
+            return
         self._check_tensors(block, self.torch.float32, "pr")
         _check(self.lib.lordo_init_projection(self.ctx, _ptr_array(block), self._stream()))
 
-    def refresh_subspace(self, Src, Omega):
-        dt = (Src.tensors if isinstance(Src, PtrList) else Src)[0].dtype
-        self._check_tensors(Src, dt, "pq")
-        self._check_tensors(Omega, self.torch.float32, "qr")
-        code = BF16 if dt == self.torch.bfloat16 else F32
+    def refresh_subspace(self, Src, Omega=None):
+        """Src: one tensor per matrix (None entries leave that matrix out); Omega None: start blocks from hp.seed."""
+        src_list = Src.tensors if isinstance(Src, PtrList) else Src
+        live = [t for t in src_list if t is not None]
+        if not live:
+            return
+        dt = live[0].dtype
         if dt not in (self.torch.bfloat16, self.torch.float32):
             raise ValueError("refresh source must be bf16 or fp32")
-        _check(self.lib.lordo_refresh_subspace(self.ctx, _ptr_array(Src), code, _ptr_array(Omega), self._stream()))
+        self._check_tensors(Src, dt, "pq", allow_none=True)
+        if Omega is not None:
+            self._check_tensors(Omega, self.torch.float32, "qr", allow_none=True)
+        code = BF16 if dt == self.torch.bfloat16 else F32
+        _check(self.lib.lordo_refresh_subspace(self.ctx, _ptr_array(Src), code, None if Omega is None else _ptr_array(Omega),
+                                               self._stream()))
 
     def spectral_gap(self, Src, Omega):
         """Per matrix: estimate of sigma_r - sigma_{r+1} of Src (the source of the last refresh; needs rayleigh_ritz)."""
@@ -218,8 +232,10 @@ class Lordo:
     def refresh_subspace_local(self, G, Omega, grad_scale=1.0):
         """Alg. 2 refresh from grad_scale * G + E; the next call must be local_step with the same G."""
         self._check_tensors(G, self._grad_dtype(), "pq")
-        self._check_tensors(Omega, self.torch.float32, "qr")
-        _check(self.lib.lordo_refresh_subspace_local(self.ctx, _ptr_array(G), float(grad_scale), _ptr_array(Omega), self._stream()))
+        if Omega is not None:
+            self._check_tensors(Omega, self.torch.float32, "qr")
+        _check(self.lib.lordo_refresh_subspace_local(self.ctx, _ptr_array(G), float(grad_scale),
+                                                     None if Omega is None else _ptr_array(Omega), self._stream()))
 
     def export_pseudograd(self, W, out):
         self._check_tensors(W, self.torch.float32, "pq")

@@ -715,3 +715,40 @@ def test_right_projection_full_rank_identity_is_adam():
     st = orc.init_state(W.T, 2, Q)
     G_perp = rng.standard_normal((p, q)) @ (np.eye(q) - Q @ Q.T)
     np.testing.assert_allclose(orc.local_step_right(st, W, G_perp, 1e-3, hp), W, rtol=0, atol=1e-9)
+
+
+# ---------------------------------------------------------------------------
+# the generator of the blocks the method draws itself (Alg. 1 Require: random initial projection)
+# ---------------------------------------------------------------------------
+def test_philox_matches_the_published_known_answers():
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 3
+    for words in rows:
+        w = [int(x, 16) for x in words]
+        out = orc.philox4x32_10(np.array([w[0:4]], dtype=np.uint32), np.array([w[4:6]], dtype=np.uint32))[0]
+        assert [int(x) for x in out] == w[6:10]
+
+
+def test_gaussian_block_is_box_muller_of_the_philox_words_and_standard_normal():
+    seed, mat, draw = 0x1234567812345678, 3, 2
+    Z = orc.gaussian_block(seed, mat, draw, 5, 3)               # 15 elements: a ragged last quad
+    # element 6 = output 2 of quad 1, element 7 = output 3: one Box-Muller pair, here through the complex exponential
+    x = orc.philox4x32_10(np.array([[1, 0, mat, draw]], dtype=np.uint32),
+                          np.array([[seed & 0xFFFFFFFF, seed >> 32]], dtype=np.uint32))[0]
+    u0, u1 = ((int(x[2]) >> 8) + 0.5) / 2 ** 24, ((int(x[3]) >> 8) + 0.5) / 2 ** 24
+    z = np.sqrt(-2 * np.log(u0)) * np.exp(2j * np.pi * u1)
+    assert abs(Z.reshape(-1)[6] - z.real) < 1e-14 and abs(Z.reshape(-1)[7] - z.imag) < 1e-14
+    # a prefix property: the block of a larger shape starts with the same numbers (element index is the counter)
+    assert np.array_equal(orc.gaussian_block(seed, mat, draw, 1, 15).reshape(-1), Z.reshape(-1))
+    # other matrix, other draw, other seed: other numbers
+    for other in (orc.gaussian_block(seed, mat + 1, draw, 5, 3), orc.gaussian_block(seed, mat, draw + 1, 5, 3),
+                  orc.gaussian_block(seed + 1, mat, draw, 5, 3)):
+        assert np.min(np.abs(other - Z)) > 0
+    big = orc.gaussian_block(99, 0, 0, 2000, 256)
+    n = big.size
+    assert abs(big.mean()) < 4 / np.sqrt(n) and abs(big.var() - 1) < 4 * np.sqrt(2 / n)
+    assert abs(np.mean(big ** 4) - 3) < 4 * np.sqrt(96 / n) and np.abs(big).max() < 6.2
+    # columns are uncorrelated: the Gram matrix of the block is n_rows * I up to sampling noise
+    Gm = big.T @ big / 2000
+    assert np.linalg.norm(Gm - np.eye(256), 2) < 2.5 * (np.sqrt(256 / 2000) * 2 + 256 / 2000)
