@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the LoRDO hot path on one MI355X.
 
-A "step" is one local step over every matrix of the workload (down-projection, fused low-rank
-Adam, up-projection with the weight update), plus, at the workload's cadence, the outer step on
-a generated averaged pseudo-gradient (every `outer_every` steps) and the subspace refresh with
-moment rotation (every `refresh_every` steps).  With the default K = 200 steps on workload c2 the
-timed region holds exactly one refresh and six outer steps.  Inputs are synthetic, seeded and
-resident in HBM before the timed region starts.
+Default workload: c4, the ~7B-shaped set (224 matrices, r = 512), the largest one that is a whole model.  A "step"
+is one local step over every matrix (down-projection, fused low-rank Adam, up-projection with the weight update);
+workloads with a cadence (c2: refresh every 200, outer step every 32 steps) also run the outer step on a generated
+averaged pseudo-gradient and the subspace refresh with moment rotation inside the timed region at that cadence.
+c4 times them apart from the local step: whatever --steps is, one outer step and one refresh are event-timed after
+the loop, so `kernels` always holds down, adam, up, outer and refresh.  Inputs are synthetic, seeded and resident
+in HBM before the timed region starts.
 
-Prints ONE JSON line: the whole-path time per step, the roofline of the dominant kernel (event-
-timed through the library's profiling hooks on the stream the kernels run on) and the float64
-oracle timed on the host cores on a bounded sample of the same workload.
+Prints ONE JSON line: the time per step, the time of one refresh and of one outer step, the roofline of the
+dominant kernel of the local step (event-timed through the library's profiling hooks on the stream the kernels run
+on), the per-class times of the other workloads (c2, c3, the rank sweep on the 8192 x 28672 matrix with one and two
+power iterations) and the float64 oracle timed on the host cores with one thread and with all of them.
 """
 from __future__ import annotations
 
@@ -40,13 +42,15 @@ WORKLOAD_TEXT = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c4")
     ap.add_argument("--rank", type=int, default=None)
     ap.add_argument("--grad-sets", type=int, default=None, help="distinct gradient sets cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="skip the event-timed second pass")
+    ap.add_argument("--no-extra", dest="extra", action="store_false",
+                    help="skip the per-class times of the other workloads (c2, c3, rank sweep on c5)")
     ap.add_argument("--refresh-every", type=int, default=None)
     ap.add_argument("--outer-every", type=int, default=None)
     ap.add_argument("--rayleigh-ritz", action="store_true",
@@ -162,160 +166,154 @@ def run_steps(opt, Wp, Gp, Dp, Op, steps, outer_every, refresh_every, lr, start=
             opt.refresh_subspace(g, Op)
 
 
-def cpu_baseline(cfg, shapes, outer_every, refresh_every, power_iters):
-    """Time the float64 oracle on the host on a bounded sample: local steps on the leading matrices
-    (one transformer layer's worth per distinct shape), one refresh and one outer step on the same
-    sample; scale by element counts to the whole set and amortise at the workload's cadence."""
+def _oracle_sample(cfg, shapes, power_iters, sample, n_local, thread_settings):
+    """Wall-clock of the float64 oracle on the matrices `sample`: for every entry of `thread_settings` (BLAS pool
+    limited to that many threads; None: as many as it takes by itself) a dict matrix index -> (local step, refresh,
+    outer step) seconds.  The inputs of a matrix are generated once and serve every setting."""
     import numpy as np
     from oracle import lordo_oracle as orc
     from paper_2602_04396_amd import synth
+    from threadpoolctl import threadpool_limits
+    d = synth.CONFIG_DEFAULTS[cfg]
+    hp = orc.Hyper(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=power_iters)
+    out = [dict() for _ in thread_settings]
+    for i in sample:
+        p, q, r = shapes[i]
+        rng = np.random.default_rng(synth.seed_for(int(cfg[1:]), 300 + i))
+        W0 = synth.weights(rng, p, q).astype(np.float64)
+        Q0 = synth.orthonormal(rng, p, r)
+        gen = synth.SpikedGradient(p, q, d["n_spike"], synth.seed_for(int(cfg[1:]), i), noise=d["noise"])
+        grads = [gen.draw(t).astype(np.float64) for t in range(n_local)]
+        om = synth.omega(np.random.default_rng(synth.seed_for(int(cfg[1:]), 400 + i)), q, r).astype(np.float64)
+        for k, threads in enumerate(thread_settings):
+            W = W0.copy()
+            st = orc.init_state(W, r, Q0)
+            with threadpool_limits(limits=threads):
+                t0 = time.perf_counter()
+                for t in range(n_local):
+                    W = orc.local_step(st, W, grads[t], 1e-3, hp)
+                t1 = time.perf_counter()
+                orc.refresh_subspace(st, grads[-1], om, hp)
+                t2 = time.perf_counter()
+                W = orc.outer_step(st, orc.pseudo_gradient(st, W), hp)
+                t3 = time.perf_counter()
+            out[k][i] = ((t1 - t0) / n_local, t2 - t1, t3 - t2)
+    return out
+
+
+def cpu_baseline(cfg, shapes, outer_every, refresh_every, power_iters):
+    """The float64 oracle, as it stands, timed on the host cores: once with one thread and once with every core
+    the BLAS pool takes.  Small sets (c1, c2) are timed in full; for the larger ones the oracle runs one matrix
+    per distinct shape at full size and its time is multiplied by the number of matrices of that shape
+    ("extrapolated").  The value is per step: the local step plus, where the workload has a cadence, the refresh
+    and the outer step amortised over it; the three parts are also given on their own."""
     try:
         from threadpoolctl import threadpool_info
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    d = synth.CONFIG_DEFAULTS[cfg]
-    # sample: one matrix per distinct shape, then further matrices in layer order until the
-    # local-step work of the sample reaches a fixed float64 flop budget (or the set is exhausted)
-    n_local = 2
-    budget = 1.0e11
-    seen, sample = set(), []
-    for i, s in enumerate(shapes):
-        if s not in seen:
-            seen.add(s)
-            sample.append(i)
-    flops = sum(4 * r * p * q for p, q, r in (shapes[i] for i in sample)) * n_local
-    for i, s in enumerate(shapes):
-        if flops >= budget:
-            break
-        if i not in sample:
-            sample.append(i)
-            flops += 4 * s[2] * s[0] * s[1] * n_local
-    sample.sort()
-    hp = orc.Hyper(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=power_iters)
-    states, Ws, gens = [], [], []
-    for i in sample:
-        p, q, r = shapes[i]
-        rng = np.random.default_rng(synth.seed_for(int(cfg[1:]), 300 + i))
-        W0 = synth.weights(rng, p, q).astype(np.float64)
-        states.append(orc.init_state(W0, r, synth.orthonormal(rng, p, r)))
-        Ws.append(W0)
-        gens.append(synth.SpikedGradient(p, q, d["n_spike"], synth.seed_for(int(cfg[1:]), i), noise=d["noise"]))
-    grads = [[g.draw(t).astype(np.float64) for g in gens] for t in range(2)]
-    omegas = [synth.omega(np.random.default_rng(synth.seed_for(int(cfg[1:]), 400 + i)), shapes[i][1], shapes[i][2]).astype(np.float64)
-              for i in sample]
-    # weights of the sample in the whole set: by shape count
+    full = cfg in ("c1", "c2")
     counts = {}
-    for s in shapes:
-        counts[s] = counts.get(s, 0) + 1
-    in_sample = {}
-    for i in sample:
-        in_sample[shapes[i]] = in_sample.get(shapes[i], 0) + 1
-    t_local = t_refresh = t_outer = 0.0
-    for k, i in enumerate(sample):
-        w = counts[shapes[i]] / in_sample[shapes[i]]
-        t0 = time.perf_counter()
-        for t in range(n_local):
-            Ws[k] = orc.local_step(states[k], Ws[k], grads[t][k], 1e-3, hp)
-        t1 = time.perf_counter()
-        orc.refresh_subspace(states[k], grads[1][k], omegas[k], hp)
-        t2 = time.perf_counter()
-        D = orc.pseudo_gradient(states[k], Ws[k])
-        Ws[k] = orc.outer_step(states[k], D, hp)
-        t3 = time.perf_counter()
-        t_local += w * (t1 - t0) / n_local
-        t_refresh += w * (t2 - t1)
-        t_outer += w * (t3 - t2)
-    ms = 1e3 * (t_local + (t_refresh / refresh_every if refresh_every else 0.0) + (t_outer / outer_every if outer_every else 0.0))
+    for sh in shapes:
+        counts[sh] = counts.get(sh, 0) + 1
+    if full:
+        sample = list(range(len(shapes)))
+        weight = {i: 1.0 for i in sample}
+    else:
+        seen, sample = set(), []
+        for i, sh in enumerate(shapes):
+            if sh not in seen:
+                seen.add(sh)
+                sample.append(i)
+        weight = {i: float(counts[shapes[i]]) for i in sample}
+    n_local = 2 if full else 1
+
+    def total(per):
+        t_local = sum(weight[i] * per[i][0] for i in sample)
+        t_refresh = sum(weight[i] * per[i][1] for i in sample)
+        t_outer = sum(weight[i] * per[i][2] for i in sample)
+        ms = 1e3 * (t_local + (t_refresh / refresh_every if refresh_every else 0.0) + (t_outer / outer_every if outer_every else 0.0))
+        return {"value": ms, "local_step_ms": 1e3 * t_local, "refresh_ms": 1e3 * t_refresh, "outer_step_ms": 1e3 * t_outer}
+
+    per_all, per_one = _oracle_sample(cfg, shapes, power_iters, sample, n_local, [None, 1])
+    multi, single = total(per_all), total(per_one)
+    label = ("full set" if full else "extrapolated (one matrix per distinct shape x counts)")
     return {
-        "value": ms, "unit": "ms/step", "cores": int(cores), "kind": "oracle",
-        "sample": (f"{len(sample)} of {len(shapes)} matrices (every distinct shape present), "
-                   f"{n_local} local steps + 1 refresh + 1 outer step each, scaled by shape counts to the full set; "
-                   f"local {1e3 * t_local:.1f} ms, refresh {1e3 * t_refresh:.1f} ms, outer {1e3 * t_outer:.1f} ms"),
+        "value": multi["value"], "unit": "ms/step", "cores": int(cores), "kind": "oracle",
+        "sample": (f"{label}: {len(sample)} of {len(shapes)} matrices at full size, {n_local} local step(s) + 1 refresh + 1 outer step "
+                   f"each; value = local step" + (" + refresh / refresh_every" if refresh_every else "")
+                   + (" + outer step / outer_every" if outer_every else "") + " (ms); the three parts are given separately"),
+        "threads_all": dict(multi, cores=int(cores)),
+        "threads_1": dict(single, cores=1),
     }
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import torch
-    from paper_2602_04396_amd import lordo, synth
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.calibrate_copy:
-        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")        # 1 GiB, far beyond every cache
-        b = torch.empty_like(a)
-        for _ in range(5):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibration": "5 device copies of 1 GiB: 1048576 KiB read and 1048576 KiB written each"}))
-        return
-    lordo.load()
-    cfg = args.config.lower()
-    d = synth.CONFIG_DEFAULTS[cfg]
-    outer_every = d["outer_every"] if args.outer_every is None else args.outer_every
-    refresh_every = d["refresh_every"] if args.refresh_every is None else args.refresh_every
-    n_sets = args.grad_sets or (4 if cfg in ("c1", "c2") else 2)
-    shapes, W, G, Omega, D, grad_dtype = build_workload(torch, lordo, synth, cfg, args.rank, n_sets)
-    qhm_mode = {"plain": 0, "ef": 0, "low-qhm": 1, "full-qhm": 2, "global": 2, "local": 1, "uplink": 0}[args.update]
-    uplink = args.update == "uplink"
-    if uplink and outer_every and refresh_every:       # the buffer is tied to Q: refresh only right after an outer step
-        refresh_every = max(outer_every, refresh_every // outer_every * outer_every)
-    use_ef = args.update in ("ef", "global", "local")
-    local_variant = args.update == "local"
-    hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=d["power_iters"],
-                       grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
-                       qhm_mode=qhm_mode, omega=0.9 if qhm_mode else 1.0, error_feedback=use_ef, uplink_buffer=uplink,
-                       rayleigh_ritz=args.rayleigh_ritz)
-    if args.short_side:
-        if args.update not in ("plain", "low-qhm", "uplink", "ef", "local"):
-            sys.exit("--short-side: the projection on the right is built for --update plain, low-qhm, ef, local and uplink")
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(synth.seed_for(int(cfg[1:]), 997))
-        lib_shapes = [(p, q, r, 1) if p > q else (p, q, r) for p, q, r in shapes]
-        Omega = [torch.randn(p if p > q else q, r, generator=gen, device="cuda") for p, q, r in shapes]
-        shapes = [(q, p, r) if p > q else (p, q, r) for p, q, r in shapes]      # the transposed problems, for the work counts
-    else:
-        lib_shapes = shapes
-    opt = lordo.Lordo(lib_shapes, hp, W, torch)
-    Wp = opt.ptrs(W)
-    Gp = [opt.ptrs(g, grad_dtype) for g in G]
-    Dp = opt.ptrs(D)
-    Op = opt.ptrs(Omega, torch.float32, "qr")
-    Ap = None
-    if uplink:    # stand-in for the mean of the workers' buffers: eta * H times a unit-scale low-rank update
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(synth.seed_for(int(cfg[1:]), 998))
-        # (`shapes` holds the transposed problems of right-projected matrices: their buffers are r x rows)
-        Ap = opt.ptrs([(1e-3 * max(outer_every, 1)) * torch.randn(r, q, generator=gen, device="cuda") for p, q, r in shapes],
-                      torch.float32, "rq")
-    lr = 1e-3
-    # a first projection from the first gradient set, as a training run would have
-    opt.refresh_subspace(Gp[0], Op)
-    opt.poll_status()
+class Workload:
+    """One workload resident in HBM, its library context, and the pointer tables of every call."""
 
-    run_steps(opt, Wp, Gp, Dp, Op, args.warmup, outer_every, refresh_every, lr, start=0, local_variant=local_variant, Ap=Ap)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(opt, Wp, Gp, Dp, Op, args.steps, outer_every, refresh_every, lr, start=0, local_variant=local_variant, Ap=Ap)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = 1e3 * (t1 - t0) / args.steps
-    opt.poll_status()
+    def __init__(self, torch, lordo, synth, cfg, rank, n_sets, args, power_iters=None, base=None):
+        self.torch, self.lordo, self.cfg, self.rank = torch, lordo, cfg, rank
+        d = synth.CONFIG_DEFAULTS[cfg]
+        self.defaults = d
+        self.power_iters = d["power_iters"] if power_iters is None else power_iters
+        if base is None:
+            base = build_workload(torch, lordo, synth, cfg, rank, n_sets)
+        shapes, W, G, Omega, D, grad_dtype = base
+        self.base = base
+        self.grad_dtype = grad_dtype
+        self.qhm_mode = {"plain": 0, "ef": 0, "low-qhm": 1, "full-qhm": 2, "global": 2, "local": 1, "uplink": 0}[args.update]
+        self.uplink = args.update == "uplink"
+        self.use_ef = args.update in ("ef", "global", "local")
+        self.local_variant = args.update == "local"
+        hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=self.power_iters,
+                           grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
+                           qhm_mode=self.qhm_mode, omega=0.9 if self.qhm_mode else 1.0, error_feedback=self.use_ef,
+                           uplink_buffer=self.uplink, rayleigh_ritz=args.rayleigh_ritz)
+        if args.short_side:
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(synth.seed_for(int(cfg[1:]), 997))
+            lib_shapes = [(p, q, r, 1) if p > q else (p, q, r) for p, q, r in shapes]
+            Omega = [torch.randn(p if p > q else q, r, generator=gen, device="cuda") for p, q, r in shapes]
+            shapes = [(q, p, r) if p > q else (p, q, r) for p, q, r in shapes]      # the transposed problems, for the work counts
+        else:
+            lib_shapes = shapes
+        self.shapes = shapes
+        self.opt = opt = lordo.Lordo(lib_shapes, hp, W, torch)
+        self.Wp = opt.ptrs(W)
+        self.Gp = [opt.ptrs(g, grad_dtype) for g in G]
+        self.Dp = opt.ptrs(D)
+        self.Op = opt.ptrs(Omega, torch.float32, "qr")
+        self.Ap = None
+        if self.uplink:    # stand-in for the mean of the workers' buffers: eta * H times a unit-scale low-rank update
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(synth.seed_for(int(cfg[1:]), 998))
+            # (`shapes` holds the transposed problems of right-projected matrices: their buffers are r x rows)
+            self.Ap = opt.ptrs([(1e-3 * max(d["outer_every"], 1)) * torch.randn(r, q, generator=gen, device="cuda") for p, q, r in shapes],
+                               torch.float32, "rq")
+        # a first projection from the first gradient set, as a training run would have
+        opt.refresh_subspace(self.Gp[0], self.Op)
+        opt.poll_status()
 
-    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2, ef=use_ef, qhm_full=qhm_mode == 2)
-    kernels = {}
-    roofline = None
-    if not args.no_events:
+    def steps(self, n, outer_every, refresh_every, lr=1e-3):
+        run_steps(self.opt, self.Wp, self.Gp, self.Dp, self.Op, n, outer_every, refresh_every, lr, start=0,
+                  local_variant=self.local_variant, Ap=self.Ap)
+
+    def outer_once(self):
+        self.opt.outer_step_lowrank(self.Wp, self.Ap) if self.uplink else self.opt.outer_step(self.Wp, self.Dp)
+
+    def refresh_once(self):
+        self.opt.refresh_subspace(self.Gp[0], self.Op)
+
+    def profiled(self, n, outer_every, refresh_every, work):
+        """`n` steps at the given cadence with every kernel class bracketed by HIP events on the launch stream, then
+        -- whatever the cadence and n -- one outer step and one refresh, so that both always have a time of their own."""
+        lordo, opt = self.lordo, self.opt
         opt.profile_enable(True)
-        run_steps(opt, Wp, Gp, Dp, Op, args.steps, outer_every, refresh_every, lr, start=0, local_variant=local_variant, Ap=Ap)
-        if not outer_every:          # workloads that time the outer step and the refresh on their own
-            opt.outer_step_lowrank(Wp, Ap) if uplink else opt.outer_step(Wp, Dp)
-        if not refresh_every:
-            opt.refresh_subspace(Gp[0], Op)
-        torch.cuda.synchronize()
-        total_by = {}
+        self.steps(n, outer_every, refresh_every)
+        self.outer_once()
+        self.refresh_once()
+        self.torch.cuda.synchronize()
+        kernels, total_by = {}, {}
         for name, kc in (("down", lordo.K_DOWN), ("adam", lordo.K_ADAM), ("up", lordo.K_UP), ("outer", lordo.K_OUTER),
                          ("refresh", lordo.K_REFRESH)):
             ms, cnt = opt.profile_read(kc)
@@ -328,37 +326,161 @@ def main():
                 if work[name]["flops"]:
                     entry["TFLOPps"] = work[name]["flops"] / (avg * 1e-3) / 1e12
             if name == "refresh":
-                entry["TFLOPps"] = refresh_flops(shapes, d["power_iters"]) / (avg * 1e-3) / 1e12
+                entry["TFLOPps"] = refresh_flops(self.shapes, self.power_iters) / (avg * 1e-3) / 1e12
             kernels[name] = entry
             total_by[name] = ms
         opt.profile_enable(False)
-        dom = max((k for k in total_by if k in work), key=lambda k: total_by[k])
-        w = work[dom]
-        avg_s = kernels[dom]["avg_ms"] * 1e-3
-        t_hbm = w["bytes"] / (HBM_PEAK_GBS * 1e9)
-        t_mfma = w["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-        if t_mfma > t_hbm:
-            ach = w["flops"] / avg_s / 1e12
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(cfg, args.rank, dom, args.update)}
-        else:
-            ach = w["bytes"] / avg_s / 1e9
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, args.rank, dom, args.update)}
+        opt.poll_status()
+        return kernels, total_by
 
-    if args.rayleigh_ritz and not args.no_events and not use_ef:
+    def close(self):
+        self.opt.close()
+
+
+def roofline_of(kernels, total_by, work, cfg, rank, update):
+    """Roofline entry of the kernel class that takes most of the local step."""
+    dom = max((k for k in total_by if k in ("down", "adam", "up")), key=lambda k: total_by[k])
+    w = work[dom]
+    avg_s = kernels[dom]["avg_ms"] * 1e-3
+    t_hbm = w["bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_mfma = w["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_mfma > t_hbm:
+        ach = w["flops"] / avg_s / 1e12
+        return {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(cfg, rank, dom, update)}
+    ach = w["bytes"] / avg_s / 1e9
+    return {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, rank, dom, update)}
+
+
+def class_ms(kernels):
+    return {k: round(v["avg_ms"], 5) for k, v in kernels.items()}
+
+
+def extra_configs(torch, lordo, synth, args, skip_cfg):
+    """Per-class times of the other workloads of the table, so that one run covers it: c2, c3 and the rank sweep on
+    the single largest matrix (c5) with one and two power iterations in the refresh.  Kernel-class averages only."""
+    import gc
+    out = []
+    for cfg, steps in (("c2", 50), ("c3", 10), ("c4", 6)):
+        if cfg == skip_cfg:
+            continue
+        wl = Workload(torch, lordo, synth, cfg, None, 4 if cfg == "c2" else 2, args)
+        wl.steps(3, 0, 0)
+        work = algorithmic_work(wl.shapes, 2)
+        kernels, _ = wl.profiled(steps, 0, 0, work)
+        out.append({"workload": cfg, "rank": wl.shapes[0][2], "power_iters": wl.power_iters, "ms": class_ms(kernels),
+                    "GBps": {k: round(v["GBps"]) for k, v in kernels.items() if "GBps" in v},
+                    "TFLOPps": {k: round(v["TFLOPps"], 1) for k, v in kernels.items() if "TFLOPps" in v}})
+        wl.close()
+        del wl
+        gc.collect()
+        torch.cuda.empty_cache()
+    if skip_cfg != "c5":
+        base = None
+        for rank in (64, 128, 256, 512, 1024):
+            if base is None:
+                base = build_workload(torch, lordo, synth, "c5", rank, 2)
+            shapes = synth.config_shapes("c5", rank)
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(synth.seed_for(5, 999))
+            Omega = [torch.randn(q, r, generator=gen, device="cuda") for p, q, r in shapes]
+            this = (shapes, base[1], base[2], Omega, base[4], base[5])
+            entry = {"workload": "c5", "rank": rank}
+            for q_it in (1, 2):
+                wl = Workload(torch, lordo, synth, "c5", rank, 2, args, power_iters=q_it, base=this)
+                wl.steps(3, 0, 0)
+                work = algorithmic_work(wl.shapes, 2)
+                kernels, _ = wl.profiled(10 if q_it == 1 else 0, 0, 0, work)
+                if q_it == 1:
+                    entry["ms"] = class_ms({k: v for k, v in kernels.items() if k != "refresh"})
+                    entry["GBps"] = {k: round(v["GBps"]) for k, v in kernels.items() if "GBps" in v}
+                    entry["TFLOPps"] = {k: round(v["TFLOPps"], 1) for k, v in kernels.items() if "TFLOPps" in v and k != "refresh"}
+                entry[f"refresh_ms_q{q_it}"] = round(kernels["refresh"]["avg_ms"], 4)
+                wl.close()
+                del wl
+                gc.collect()
+            out.append(entry)
+            del Omega, this
+            torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import gc
+    import torch
+    from paper_2602_04396_amd import lordo, synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")        # 1 GiB, far beyond every cache
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 10
+        print(json.dumps({"calibration": "device copies of 1 GiB: 1048576 KiB read and 1048576 KiB written each",
+                          "copy_GBps": 2 * (1 << 30) / dt / 1e9}))
+        return
+    lordo.load()
+    cfg = args.config.lower()
+    d = synth.CONFIG_DEFAULTS[cfg]
+    outer_every = d["outer_every"] if args.outer_every is None else args.outer_every
+    refresh_every = d["refresh_every"] if args.refresh_every is None else args.refresh_every
+    n_sets = args.grad_sets or (4 if cfg in ("c1", "c2") else 2)
+    if args.short_side and args.update not in ("plain", "low-qhm", "uplink", "ef", "local"):
+        sys.exit("--short-side: the projection on the right is built for --update plain, low-qhm, ef, local and uplink")
+    wl = Workload(torch, lordo, synth, cfg, args.rank, n_sets, args)
+    if wl.uplink and outer_every and refresh_every:       # the buffer is tied to Q: refresh only right after an outer step
+        refresh_every = max(outer_every, refresh_every // outer_every * outer_every)
+    shapes, grad_dtype = wl.shapes, wl.grad_dtype
+
+    wl.steps(args.warmup, outer_every, refresh_every)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    wl.steps(args.steps, outer_every, refresh_every)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+    wl.opt.poll_status()
+
+    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2, ef=wl.use_ef, qhm_full=wl.qhm_mode == 2)
+    kernels = {}
+    roofline = None
+    if not args.no_events:
+        kernels, total_by = wl.profiled(args.steps, outer_every, refresh_every, work)
+        roofline = roofline_of(kernels, total_by, work, cfg, args.rank, args.update)
+
+    if args.rayleigh_ritz and not args.no_events and not wl.use_ef:
         # the spectrum metrics (Sec. 5.1) on their own: the gap program is a second pass of the size of a refresh
-        opt.spectral_gap(Gp[0], Op)
+        wl.opt.spectral_gap(wl.Gp[0], wl.Op)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         for _ in range(3):
-            opt.spectral_gap(Gp[0], Op)
+            wl.opt.spectral_gap(wl.Gp[0], wl.Op)
         torch.cuda.synchronize()
         kernels["spectral_gap"] = {"avg_ms": 1e3 * (time.perf_counter() - t2) / 3, "launches": 3}
+    power_iters = wl.power_iters
+    wl.close()
+    del wl
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    extra = None
+    if args.extra and not args.no_events:
+        extra = {"configs": extra_configs(torch, lordo, synth, args, cfg),
+                 "note": "HIP-event averages per kernel class and call (ms); down/up TFLOP/s on 2pqr flops, GB/s on algorithmic bytes"}
 
     cpu = None
-    if not args.no_cpu_baseline:
-        cpu = None if args.short_side else cpu_baseline(cfg, shapes, outer_every, refresh_every, d["power_iters"])
+    if not args.no_cpu_baseline and not args.short_side:
+        cpu = cpu_baseline(cfg, shapes, outer_every, refresh_every, power_iters)
 
     out = {
         "metric": "full-model low-rank optimizer step ms",
@@ -368,11 +490,17 @@ def main():
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[cfg] + (f", rank override {args.rank}" if args.rank else ""),
                    "matrices": len(shapes), "params": sum(p * q for p, q, r in shapes),
-                   "refresh_every": refresh_every, "outer_every": outer_every, "power_iters": d["power_iters"],
+                   "timed_region": ("local steps only; one refresh and one outer step are event-timed on their own after it"
+                                    if not (refresh_every or outer_every) else
+                                    f"local steps with a refresh every {refresh_every} and an outer step every {outer_every} steps"),
+                   "refresh_every": refresh_every, "outer_every": outer_every, "power_iters": power_iters,
                    "grad_sets": n_sets, "outer": "nesterov lr 0.7 momentum 0.9 on a generated averaged pseudo-gradient",
                    "update": args.update, "rayleigh_ritz": bool(args.rayleigh_ritz), "short_side": bool(args.short_side)},
+        "ms_per_refresh": kernels.get("refresh", {}).get("avg_ms"),
+        "ms_per_outer": kernels.get("outer", {}).get("avg_ms"),
         "roofline": roofline,
         "kernels": kernels,
+        "extra": extra,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

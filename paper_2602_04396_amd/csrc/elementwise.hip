@@ -575,6 +575,42 @@ __global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef, int st
   for (int i = threadIdx.x; i < m.r; i += 256) S[(int64_t)i * m.r + i] += shift;
   if (store && m.ritz >= 0 && threadIdx.x == 0) reinterpret_cast<float*>(d.arena + m.ritz)[m.r + 2] = shift;
 }
+// Diagonal of the Gram matrix S = X^T X of a tall block X (rows x r, row-major), summed in double from the fp32
+// entries: S_kk = sum_i X_ik^2.  The grouped GEMM forms S from three-term bf16 operands; on the diagonal the product
+// of the two middle terms is a square, always positive and about 2^-18 of the entry, and in a long contraction it
+// falls below half an ulp of the running sum and is rounded away step after step: the diagonal came out 2e-6 to
+// 3e-6 too small at p >= 4096 and the columns of the orthonormalised block that much too long -- 7e-5 in
+// || Q^T Q - I ||_F at r = 512.  The diagonal carries the column norms, so it alone is recomputed exactly.
+// One workgroup per (64 columns, matrix): 4 row lanes x 64 columns, fixed-order reduction.
+// which: 0, 1 = buffers of the Y pair (rows = p); 2, 3 = zw[0], zw[1] (rows = q).
+__global__ __launch_bounds__(256) void k_gram_diag(DevCtx d, int which) {
+  const int mat = blockIdx.y;
+  if (mat_skipped(d, mat)) return;
+  const MatDev& m = d.mats[mat];
+  const int k = blockIdx.x * 64 + (threadIdx.x & 63);
+  if (blockIdx.x * 64 >= m.r) return;
+  const float* X = reinterpret_cast<const float*>(d.arena + (which < 2 ? m.y[which] : m.zw[which - 2]));
+  const int rows = which < 2 ? m.p : m.q;
+  const int lane_row = threadIdx.x >> 6;
+  double acc = 0.0;
+  if (k < m.r)
+    for (int i = lane_row; i < rows; i += 4) {
+      const double x = (double)X[(int64_t)i * m.r + k];
+      acc = fma(x, x, acc);
+    }
+  __shared__ double part[4][64];
+  part[lane_row][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (lane_row == 0 && k < m.r) {
+    const int c = threadIdx.x & 63;
+    reinterpret_cast<float*>(d.arena + m.gram)[(int64_t)k * m.r + k] = (float)((part[0][c] + part[1][c]) + (part[2][c] + part[3][c]));
+  }
+}
+hipError_t launch_gram_diag(const DevCtx& d, int which, int rmax, hipStream_t s) {
+  hipLaunchKernelGGL(k_gram_diag, dim3((rmax + 63) / 64, d.n), dim3(256), 0, s, d, which);
+  return hipGetLastError();
+}
+
 // Mean squared singular value of R = Q_new^T Q_old of the last refresh (Sec. 5.1, Metrics):
 // (1/r) sum_i sigma_i^2 = ||R||_F^2 / r, from the elementwise square the rotation already keeps.
 __global__ __launch_bounds__(256) void k_mssv(DevCtx d, float* __restrict__ out) {

@@ -145,7 +145,7 @@ __device__ __forceinline__ void gemm_loop(f32x16 (&acc)[WB][WB], const Operand<T
 // ---------------------------------------------------------------------------------------
 // Split-bf16 variant of the K loop for the range-finder products (Alg. 2 sketch and power
 // iteration).  Operands go to LDS as bf16 planes in matrix-core fragment order -- a bf16 source is
-// exact, an fp32 operand becomes hi + mid + lo (2^-24 relative, as exact as fp32) -- and the
+// exact, an fp32 operand becomes hi + mid + lo, each rounded to nearest (2^-26 relative, as exact as fp32) -- and the
 // products run on v_mfma_f32_32x32x16_bf16: three passes for a bf16 source, six for an fp32 one
 // (all products of terms down to 2^-24).  Two terms (2^-16) are not enough: the trailing directions
 // of the range finder's block sit in the noise of the source, where gaps between singular values are
@@ -202,17 +202,29 @@ struct OperandBF {
       }
     }
   }
-  // Two fp32 values -> three packed bf16 pairs whose sum is the values to 2^-24: hi is the truncated
-  // upper half, mid the truncated upper half of the (exactly representable) remainder, lo the
-  // truncated rest -- about five vector operations per element.
+  // Two fp32 values -> three packed bf16 pairs whose sum is the values to 2^-26: hi is the value rounded to nearest,
+  // mid the (exactly representable) remainder rounded to nearest, lo the rounded rest; the conversion is the
+  // hardware's packed round-to-nearest-even instruction, about five vector operations per element.
+  // Rounding to nearest, not truncation: truncated terms all carry the sign of the value, so on the diagonal of a
+  // Gram matrix X^T X every cross product hi * lo is positive; those below half an ulp of the running sum are
+  // rounded away one k-step after the other, and the diagonal came out too small by up to 2e-5 relative (growing
+  // with the length of the contraction), i.e. the columns of the orthonormalised block too long by 1e-5.  With
+  // terms of random sign the same loss has zero mean.
+  static __device__ __forceinline__ uint32_t pack_rne(float x0, float x1) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {x0, x1};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  }
   static __device__ __forceinline__ void split3(uint32_t x0, uint32_t x1, uint32_t (&t)[3]) {
-    t[0] = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
-    const float r0 = __uint_as_float(x0) - __uint_as_float(x0 & 0xffff0000u);
-    const float r1 = __uint_as_float(x1) - __uint_as_float(x1 & 0xffff0000u);
-    t[1] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
-    const float s0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xffff0000u);
-    const float s1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
-    t[2] = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
+    const float f0 = __uint_as_float(x0), f1 = __uint_as_float(x1);
+    t[0] = pack_rne(f0, f1);
+    const float r0 = f0 - __uint_as_float(t[0] << 16);
+    const float r1 = f1 - __uint_as_float(t[0] & 0xffff0000u);
+    t[1] = pack_rne(r0, r1);
+    const float s0 = r0 - __uint_as_float(t[1] << 16);
+    const float s1 = r1 - __uint_as_float(t[1] & 0xffff0000u);
+    t[2] = pack_rne(s0, s1);
   }
   // P: the operand's planes (one for an exact bf16 operand, three for an fp32 one), PLANE elements apart
   template <bool BF16>

@@ -25,7 +25,7 @@ namespace {
     }                                                                                             \
   } while (0)
 
-enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT, OP_JSVD, OP_FROB };
+enum OpKind : int { OP_GEMM, OP_SHIFT, OP_POTF2, OP_DIAG_INV, OP_ROT_PRE, OP_ROT_POST, OP_Q_FROM_Y, OP_PACK, OP_Y_FROM_EXT, OP_JSVD, OP_FROB, OP_GRAM_DIAG };
 
 struct Op {
   int kind;
@@ -272,6 +272,7 @@ struct ProgramBuilder {
         g.M = m.r; g.N = m.r; g.K = rows_of(i);
         return true;
       }, false, true, true);      // the factorisation reads the lower triangle only
+      simple(OP_GRAM_DIAG, (y_side ? 0 : 2) + cur);      // the diagonal (the column norms) exactly
       if (pass < nshift) simple(OP_SHIFT, 0, 32.f * 5.9604645e-8f);
       factor(max_blocks);
       simple(OP_DIAG_INV);
@@ -1216,6 +1217,7 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
         if (op.split) HIPCHK(launch_gemm_reduce(c->dev, descs + op.desc_first, op.ndescs, s));
         break;
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, op.iarg != 0, s)); break;
+      case OP_GRAM_DIAG: HIPCHK(launch_gram_diag(c->dev, op.iarg, P.r_max, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
       case OP_JSVD:
