@@ -177,7 +177,7 @@ hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t
 // refresh helpers (grouped over all matrices)
 hipError_t launch_gram_shift(const DevCtx& d, float coef, bool store, hipStream_t s);
 // exact diagonal of the Gram matrix of block `which` (0, 1: Y pair; 2, 3: zw[0], zw[1]) written over the one the GEMM left
-hipError_t launch_gram_diag(const DevCtx& d, int which, int rmax, hipStream_t s);
+hipError_t launch_gram_diag(const DevCtx& d, int which, int rmax, int part_slices, hipStream_t s);
 hipError_t launch_mssv(const DevCtx& d, float* out, hipStream_t s);
 hipError_t launch_potf2(const DevCtx& d, int jb, hipStream_t s);
 hipError_t launch_frob2(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float* partial, bool src_f32, hipStream_t s);

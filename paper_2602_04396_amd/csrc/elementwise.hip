@@ -581,33 +581,66 @@ __global__ __launch_bounds__(256) void k_gram_shift(DevCtx d, float coef, int st
 // falls below half an ulp of the running sum and is rounded away step after step: the diagonal came out 2e-6 to
 // 3e-6 too small at p >= 4096 and the columns of the orthonormalised block that much too long -- 7e-5 in
 // || Q^T Q - I ||_F at r = 512.  The diagonal carries the column norms, so it alone is recomputed exactly.
-// One workgroup per (64 columns, matrix): 4 row lanes x 64 columns, fixed-order reduction.
+// Two stages, both in a fixed order: workgroup (64 columns, row chunk, matrix) sums its rows (4 row lanes x 64
+// columns, eight loads in flight per thread) into the split-K partial-sum buffer of the matrix, which the Gram
+// product has just released; one thread per column then adds the chunks and writes the diagonal entry.
 // which: 0, 1 = buffers of the Y pair (rows = p); 2, 3 = zw[0], zw[1] (rows = q).
-__global__ __launch_bounds__(256) void k_gram_diag(DevCtx d, int which) {
-  const int mat = blockIdx.y;
+constexpr int GD_CHUNKS = 64;
+__device__ __forceinline__ int gram_diag_chunks(const MatDev& m, int part_slices) {
+  const int cap = (m.r * part_slices) / 2;              // doubles per column that fit into part_slices * r * r floats
+  return cap < 1 ? 1 : (cap < GD_CHUNKS ? cap : GD_CHUNKS);
+}
+__global__ __launch_bounds__(256) void k_gram_diag_part(DevCtx d, int which, int part_slices) {
+  const int mat = blockIdx.z;
   if (mat_skipped(d, mat)) return;
   const MatDev& m = d.mats[mat];
+  if ((int)blockIdx.x * 64 >= m.r) return;
+  const int nch = gram_diag_chunks(m, part_slices);
+  if ((int)blockIdx.y >= nch) return;
   const int k = blockIdx.x * 64 + (threadIdx.x & 63);
-  if (blockIdx.x * 64 >= m.r) return;
   const float* X = reinterpret_cast<const float*>(d.arena + (which < 2 ? m.y[which] : m.zw[which - 2]));
   const int rows = which < 2 ? m.p : m.q;
+  const int per = ((rows + nch - 1) / nch + 3) & ~3;
+  const int r0 = blockIdx.y * per, r1 = r0 + per < rows ? r0 + per : rows;
   const int lane_row = threadIdx.x >> 6;
   double acc = 0.0;
-  if (k < m.r)
-    for (int i = lane_row; i < rows; i += 4) {
+  if (k < m.r) {
+    int i = r0 + lane_row;
+    for (; i + 28 < r1; i += 32) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = X[(int64_t)(i + 4 * e) * m.r + k];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc = fma((double)x[e], (double)x[e], acc);
+    }
+    for (; i < r1; i += 4) {
       const double x = (double)X[(int64_t)i * m.r + k];
       acc = fma(x, x, acc);
     }
+  }
   __shared__ double part[4][64];
   part[lane_row][threadIdx.x & 63] = acc;
   __syncthreads();
   if (lane_row == 0 && k < m.r) {
     const int c = threadIdx.x & 63;
-    reinterpret_cast<float*>(d.arena + m.gram)[(int64_t)k * m.r + k] = (float)((part[0][c] + part[1][c]) + (part[2][c] + part[3][c]));
+    reinterpret_cast<double*>(d.arena + m.part)[(int64_t)blockIdx.y * m.r + k] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
   }
 }
-hipError_t launch_gram_diag(const DevCtx& d, int which, int rmax, hipStream_t s) {
-  hipLaunchKernelGGL(k_gram_diag, dim3((rmax + 63) / 64, d.n), dim3(256), 0, s, d, which);
+__global__ __launch_bounds__(64) void k_gram_diag_sum(DevCtx d, int part_slices) {
+  const int mat = blockIdx.y;
+  if (mat_skipped(d, mat)) return;
+  const MatDev& m = d.mats[mat];
+  const int k = blockIdx.x * 64 + threadIdx.x;
+  if (k >= m.r) return;
+  const int nch = gram_diag_chunks(m, part_slices);
+  const double* part = reinterpret_cast<const double*>(d.arena + m.part);
+  double acc = 0.0;
+  for (int c = 0; c < nch; ++c) acc += part[(int64_t)c * m.r + k];
+  reinterpret_cast<float*>(d.arena + m.gram)[(int64_t)k * m.r + k] = (float)acc;
+}
+hipError_t launch_gram_diag(const DevCtx& d, int which, int rmax, int part_slices, hipStream_t s) {
+  hipLaunchKernelGGL(k_gram_diag_part, dim3((rmax + 63) / 64, GD_CHUNKS, d.n), dim3(256), 0, s, d, which, part_slices);
+  hipLaunchKernelGGL(k_gram_diag_sum, dim3((rmax + 63) / 64, d.n), dim3(64), 0, s, d, part_slices);
   return hipGetLastError();
 }
 

@@ -1217,7 +1217,7 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
         if (op.split) HIPCHK(launch_gemm_reduce(c->dev, descs + op.desc_first, op.ndescs, s));
         break;
       case OP_SHIFT: HIPCHK(launch_gram_shift(c->dev, op.farg, op.iarg != 0, s)); break;
-      case OP_GRAM_DIAG: HIPCHK(launch_gram_diag(c->dev, op.iarg, P.r_max, s)); break;
+      case OP_GRAM_DIAG: HIPCHK(launch_gram_diag(c->dev, op.iarg, P.r_max, P.part_slices, s)); break;
       case OP_POTF2: HIPCHK(launch_potf2(c->dev, op.iarg, s)); break;
       case OP_DIAG_INV: HIPCHK(launch_diag_inverses(c->dev, s)); break;
       case OP_JSVD:
