@@ -133,6 +133,23 @@ int lordo_workspace_bytes(const lordo_shape* shapes, int32_t n, const lordo_hpar
 int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp,
                void* arena, size_t arena_bytes, void* const* W, void* stream);
 
+/* lordo_init for callers that cannot allocate device memory at all (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same context, but its workspace -- projection, moments, anchor, momentum and
+ * all scratch that lordo_init places in the caller's arena -- lives in a fixed array inside the library,
+ * LORDO_STATIC_WORKSPACE_BYTES per GPU, held from the first such call on a GPU until the process ends.  No device
+ * memory is allocated or freed, here or in any later call on the context.
+ *   shapes, n, hp, W, stream   as for lordo_init.
+ * Returns LORDO_ENOMEM (with the sizes on stderr) when lordo_workspace_bytes(shapes, n, hp) exceeds
+ * LORDO_STATIC_WORKSPACE_BYTES, and LORDO_ESTATE while another context created by this call is alive on the current
+ * GPU: every such context of a GPU uses the same array, so only one may exist at a time (lordo_destroy releases it);
+ * the array keeps the previous context's contents, which this call overwrites or clears as lordo_init does with an
+ * uninitialised arena.  Calls on the one live context follow the stream-ordering rule above; issued from two host
+ * threads or two streams without ordering they race on the array like any two calls on one context.
+ * Every other entry point takes the context as if it came from lordo_init. */
+#define LORDO_STATIC_WORKSPACE_BYTES (64u << 20)
+int lordo_init_static(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp,
+                      void* const* W, void* stream);
+
 /* Random initial projection of the global variant (Alg. 1 "Require": Q_0 random, against the identity
  * columns of Alg. 2 that lordo_init leaves): Q_0 = orthonormal basis of the caller's block, by the same
  * CholeskyQR as the refresh (columns signed so that the triangular factor has a positive diagonal).

@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 using namespace lordo;
@@ -907,6 +908,7 @@ struct lordo_ctx {
   bool gauss_init = false;       // lordo_init_projection without a block: the program's first op draws it
   std::vector<const void*> folded_g;
   int device = 0;
+  int static_device = -1;        // >= 0: the context lives in the library's static workspace of that device (lordo_init_static)
   // cached caller pointer tables: EXT_SLOTS per kind, replaced round-robin
   std::vector<void*> shadow[EXT_COUNT][EXT_SLOTS];
   int next_slot[EXT_COUNT] = {0, 0, 0, 0, 0, 0};
@@ -951,8 +953,22 @@ int lordo_workspace_bytes(const lordo_shape* shapes, int32_t n, const lordo_hpar
   return LORDO_OK;
 }
 
-int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp, void* arena,
-               size_t arena_bytes, void* const* W, void* stream) {
+}  // extern "C"
+
+// Workspace for callers that cannot allocate device memory (see lordo_init_static): a fixed array in the code object,
+// one copy per GPU the library runs on, held until the process ends.  In host code this name is only a handle of the
+// symbol: the device address of each GPU's copy is looked up once per device (hipGetSymbolAddress) and only that
+// address is ever handed to kernels, fills and copies.
+static __device__ __align__(256) unsigned char scratch[LORDO_STATIC_WORKSPACE_BYTES];
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[MAX_DEVICES] = {};       // device address of this GPU's copy of `scratch`
+bool g_static_busy[MAX_DEVICES] = {};       // a context created by lordo_init_static on this GPU is alive
+}  // namespace
+
+static int init_context(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp, void* arena,
+                        size_t arena_bytes, void* const* W, void* stream) {
   if (!out) return LORDO_EINVAL;
   *out = nullptr;
   int rc = validate(shapes, n, hp);
@@ -1020,6 +1036,47 @@ int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lord
   INITCHK(hipStreamSynchronize(s));
 #undef INITCHK
   *out = c;
+  return LORDO_OK;
+}
+
+extern "C" {
+
+int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp, void* arena,
+               size_t arena_bytes, void* const* W, void* stream) {
+  return init_context(out, shapes, n, hp, arena, arena_bytes, W, stream);
+}
+
+int lordo_init_static(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp, void* const* W, void* stream) {
+  if (!out) return LORDO_EINVAL;
+  *out = nullptr;
+  int rc = validate(shapes, n, hp);
+  if (rc != LORDO_OK) return rc;
+  {
+    Plan P;
+    build_plan(shapes, n, *hp, P);
+    if (P.bytes > (size_t)LORDO_STATIC_WORKSPACE_BYTES) {
+      fprintf(stderr, "lordo_init_static: these shapes need %zu bytes of workspace, the static workspace holds %zu\n", P.bytes,
+              (size_t)LORDO_STATIC_WORKSPACE_BYTES);
+      return LORDO_ENOMEM;
+    }
+  }
+  int dev = 0;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return LORDO_EINVAL;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static_busy[dev]) return LORDO_ESTATE;         // one context at a time per GPU: a second one would share the array
+  if (!g_static_ptr[dev]) {                            // once per device, with that device current
+    void* ptr = nullptr;
+    HIPCHK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255) != 0) return LORDO_EHIP;
+    g_static_ptr[dev] = ptr;
+  }
+  // the array keeps what the last context left in it: init_context overwrites every table and clears the flag, the
+  // pointer tables, the state and the scratch regions, exactly as it does for a caller's uninitialised arena
+  rc = init_context(out, shapes, n, hp, g_static_ptr[dev], LORDO_STATIC_WORKSPACE_BYTES, W, stream);
+  if (rc != LORDO_OK) return rc;
+  (*out)->static_device = dev;
+  g_static_busy[dev] = true;
   return LORDO_OK;
 }
 
@@ -1657,6 +1714,12 @@ const char* lordo_strerror(int code) {
   }
 }
 
-void lordo_destroy(lordo_ctx* c) { delete c; }
+void lordo_destroy(lordo_ctx* c) {
+  if (c && c->static_device >= 0) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    g_static_busy[c->static_device] = false;
+  }
+  delete c;
+}
 
 }  // extern "C"

@@ -22,8 +22,9 @@ EXPORTS = [
     "lordo_get_step", "lordo_set_step", "lordo_poll_status", "lordo_strerror", "lordo_destroy",
     "lordo_profile_enable", "lordo_profile_read", "lordo_get_mssv", "lordo_refresh_subspace_local",
     "lordo_export_uplink", "lordo_outer_step_lowrank", "lordo_init_projection", "lordo_sync_payload",
-    "lordo_get_stable_rank", "lordo_spectral_gap",
+    "lordo_get_stable_rank", "lordo_spectral_gap", "lordo_init_static",
 ]
+STATIC_WORKSPACE_BYTES = 64 << 20
 K_DOWN, K_ADAM, K_UP, K_OUTER, K_EXPORT, K_REFRESH = range(6)
 
 
@@ -73,6 +74,7 @@ def load() -> C.CDLL:
     vp, vpp = C.c_void_p, C.POINTER(C.c_void_p)
     lib.lordo_workspace_bytes.argtypes = [C.POINTER(Shape), C.c_int32, C.POINTER(HParams), C.POINTER(C.c_size_t)]
     lib.lordo_init.argtypes = [C.POINTER(vp), C.POINTER(Shape), C.c_int32, C.POINTER(HParams), vp, C.c_size_t, vpp, vp]
+    lib.lordo_init_static.argtypes = [C.POINTER(vp), C.POINTER(Shape), C.c_int32, C.POINTER(HParams), vpp, vp]
     lib.lordo_local_step.argtypes = [vp, vpp, vpp, C.c_double, C.c_double, vp]
     lib.lordo_refresh_subspace.argtypes = [vp, vpp, C.c_int32, vpp, vp]
     lib.lordo_refresh_subspace_local.argtypes = [vp, vpp, C.c_double, vpp, vp]
@@ -143,19 +145,25 @@ class Lordo:
     """One optimizer context over a list of (p, q, r) matrices.  `W` and every other
     argument is a list of torch CUDA tensors, contiguous, in the order of `shapes`."""
 
-    def __init__(self, shapes, hp: HParams, W, torch):
+    def __init__(self, shapes, hp: HParams, W, torch, static_workspace=False):
         self.lib = load()
         self.torch = torch
         self.shapes = [tuple(s) for s in shapes]
         self.hp = hp
         self.n = len(shapes)
         self._check_tensors(W, torch.float32, "pq")
+        self.device = W[0].device
+        self.ctx = C.c_void_p()
+        if static_workspace:         # lordo_init_static: the workspace is the library's own fixed array, nothing is allocated
+            self.arena = None
+            _check(self.lib.lordo_init_static(C.byref(self.ctx), _shape_array(self.shapes), self.n, C.byref(hp),
+                                              _ptr_array(W), self._stream()))
+            return
         nbytes = workspace_bytes(self.shapes, hp)
         self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=W[0].device)
         base = self.arena.data_ptr()
         self.arena_ptr = (base + 255) // 256 * 256
         self.arena_bytes = nbytes
-        self.ctx = C.c_void_p()
         _check(self.lib.lordo_init(C.byref(self.ctx), _shape_array(self.shapes), self.n, C.byref(hp),
                                    C.c_void_p(self.arena_ptr), nbytes, _ptr_array(W), self._stream()))
 
@@ -224,7 +232,7 @@ class Lordo:
             raise ValueError("source must be bf16 or fp32")
         self._check_tensors(Src, dt, "pq")
         self._check_tensors(Omega, self.torch.float32, "qr")
-        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.arena.device)
+        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.device)
         _check(self.lib.lordo_spectral_gap(self.ctx, _ptr_array(Src), BF16 if dt == self.torch.bfloat16 else F32,
                                            _ptr_array(Omega), C.c_void_p(out.data_ptr()), self._stream()))
         return out
@@ -267,6 +275,8 @@ class Lordo:
     def sync_payload(self):
         """(payload, moments_count): the contiguous fp32 region [u | v | A] of the workspace as a tensor view
         (Alg. 1 synchronisation; App. A.5.1) and the number of leading elements that are moments."""
+        if self.arena is None:
+            raise ValueError("the payload view needs a torch-owned arena (context created with static_workspace)")
         ptr, count, moments = C.c_void_p(), C.c_size_t(), C.c_size_t()
         _check(self.lib.lordo_sync_payload(self.ctx, C.byref(ptr), C.byref(count), C.byref(moments)))
         off = ptr.value - self.arena.data_ptr()
@@ -281,7 +291,7 @@ class Lordo:
         return {STATE_Q: (tp, r), STATE_ANCHOR: (p, q), STATE_MOM: (p, q), STATE_ERR: (p, q), STATE_RITZ: (r,)}.get(which, (r, tq))
 
     def get_state(self, mat, which):
-        out = self.torch.empty(self._state_shape(mat, which), dtype=self.torch.float32, device=self.arena.device)
+        out = self.torch.empty(self._state_shape(mat, which), dtype=self.torch.float32, device=self.device)
         _check(self.lib.lordo_get_state(self.ctx, mat, which, C.c_void_p(out.data_ptr()), self._stream()))
         return out
 
@@ -293,13 +303,13 @@ class Lordo:
 
     def mssv(self):
         """Per matrix: mean squared singular value of Q_new^T Q_old of the last refresh (tensor of n floats)."""
-        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.arena.device)
+        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.device)
         _check(self.lib.lordo_get_mssv(self.ctx, C.c_void_p(out.data_ptr()), self._stream()))
         return out
 
     def stable_rank(self):
         """Per matrix: ||Src||_F^2 / ||Src||_2^2 of the source of the last refresh (needs rayleigh_ritz)."""
-        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.arena.device)
+        out = self.torch.empty(len(self.shapes), dtype=self.torch.float32, device=self.device)
         _check(self.lib.lordo_get_stable_rank(self.ctx, C.c_void_p(out.data_ptr()), self._stream()))
         return out
 
