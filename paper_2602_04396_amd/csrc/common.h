@@ -133,6 +133,9 @@ struct UpArgs {
 };
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* b_hi,
                           const uint16_t* b_lo, const UpArgs& ua, hipStream_t s);
+// plain update with 256 x 128 tiles (ranks from 256 up, 16-byte row accesses); `tiles` hold m0 in steps of 256
+hipError_t launch_proj_up_wide(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* b_hi, const uint16_t* b_lo,
+                               const UpArgs& ua, hipStream_t s);
 // gemm32.hip
 hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile* tiles, int ntiles, int tile, int src_is_bf16,
                          hipStream_t s, float alpha_mul = 1.f);   // alpha_mul scales every product of the launch (per-call coefficients)

@@ -67,6 +67,8 @@ struct Plan {
   std::vector<MatDev> mat;
   std::vector<int64_t> chunk_start_h;
   std::vector<ProjTile> down_h, up_h, ytile_h;       // ytile: 128 rows x 128 ranks tiles of the products Y = Src B
+  std::vector<ProjTile> up_wide_h;                   // 256 x 128 tiles of the plain update (every left-projected rank >= 256)
+  int64_t up_wide_tiles = -1;
   int64_t ytiles = 0;
   bool y_fast_shapes = false;       // every matrix has q % 32 == 0 and r % 4 == 0
   std::vector<GemmDesc> desc_h;
@@ -802,6 +804,29 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   P.up_h = xcd_order(up);
   P.down_tiles = A.take(sizeof(ProjTile) * P.down_h.size());
   P.up_tiles = A.take(sizeof(ProjTile) * P.up_h.size());
+  {   // ranks from 256 up: the plain update runs on 256 x 128 tiles (fewer operand bytes per output through LDS and L2)
+    bool wide = !up.empty();
+    for (int i = 0; i < n; ++i)
+      if (!P.mat[i].tr && P.mat[i].rp < 256) wide = false;
+    if (wide) {
+      std::vector<ProjTile> uw;
+      constexpr int SBM = 8 * 256, SBN = 8 * 128;     // super-blocks of 8 x 8 tiles: what one XCD runs at a time
+      for (int i = 0; i < n; ++i) {
+        const MatDev& m = P.mat[i];
+        if (m.tr) continue;
+        for (int ms = 0; ms < m.pp; ms += SBM)
+          for (int ns = 0; ns < m.qp; ns += SBN)
+            for (int m0 = ms; m0 < std::min(ms + SBM, m.pp); m0 += 256)
+              for (int n0 = ns; n0 < std::min(ns + SBN, m.qp); n0 += 128) {
+                ProjTile t{};
+                t.mat = i; t.m0 = m0; t.n0 = n0;
+                uw.push_back(t);
+              }
+      }
+      P.up_wide_h = xcd_order(uw);
+      P.up_wide_tiles = A.take(sizeof(ProjTile) * P.up_wide_h.size());
+    }
+  }
   if (P.any_tr) {     // tables, like the two above: behind the state that lordo_init clears after the tables are uploaded
     P.mats_up = A.take(sizeof(MatDev) * n);
     P.mats_stb = A.take(sizeof(MatDev) * n);
@@ -1016,6 +1041,8 @@ static int init_context(lordo_ctx** out, const lordo_shape* shapes, int32_t n, c
   INITCHK(hipMemcpy(c->at<void>(P.chunk_start), P.chunk_start_h.data(), sizeof(int64_t) * (n + 1), hipMemcpyHostToDevice));
   if (!P.down_h.empty()) INITCHK(hipMemcpy(c->at<void>(P.down_tiles), P.down_h.data(), sizeof(ProjTile) * P.down_h.size(), hipMemcpyHostToDevice));
   if (!P.up_h.empty()) INITCHK(hipMemcpy(c->at<void>(P.up_tiles), P.up_h.data(), sizeof(ProjTile) * P.up_h.size(), hipMemcpyHostToDevice));
+  if (!P.up_wide_h.empty())
+    INITCHK(hipMemcpy(c->at<void>(P.up_wide_tiles), P.up_wide_h.data(), sizeof(ProjTile) * P.up_wide_h.size(), hipMemcpyHostToDevice));
   INITCHK(hipMemcpy(c->at<void>(P.ytiles), P.ytile_h.data(), sizeof(ProjTile) * P.ytile_h.size(), hipMemcpyHostToDevice));
   if (!P.desc_h.empty())
     INITCHK(hipMemcpy(c->at<void>(P.descs), P.desc_h.data(), sizeof(GemmDesc) * P.desc_h.size(), hipMemcpyHostToDevice));
@@ -1196,7 +1223,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   } else {
     ua.coef_acc = (float)-lr; ua.coef_g = 0.f; ua.colscale = 0; ua.colpart = nullptr;
   }
-  if (!P.up_h.empty())
+  if (!P.up_wide_h.empty() && w_vec && !qhm_full)
+    HIPCHK(launch_proj_up_wide(c->dev, c->at<ProjTile>(P.up_wide_tiles), (int)P.up_wide_h.size(), c->at<uint16_t>(P.n_hi),
+                               c->at<uint16_t>(P.n_lo), ua, s));
+  else if (!P.up_h.empty())
     HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.n_hi),
                           c->at<uint16_t>(P.n_lo), ua, s));
   if (P.any_tr) {               // W <- W - eta N^T Q^T: the up-projection kernel on the shadow records (planes of N as A, of Q as B)

@@ -1279,6 +1279,185 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Up-projection for ranks from 256 up (plain update, q % 4 == 0, W 16-byte aligned): workgroup tile 256 rows x 128
+// columns of W, 4 waves in a 2 x 2 grid, wave tile 128 x 64 = 4 x 2 accumulator blocks.  With the 128 x 128 tile
+// above every wave reads 16 KiB of fragments from LDS per 24 MFMAs, which keeps LDS as busy as the matrix cores, and
+// the workgroup pulls 1 byte of operand planes through L2 per output element and k-step; here a wave reads 12 KiB per
+// 24 MFMAs and the tile pulls 0.75 bytes.  The operand fragments of one k-step of 16 (24 KiB: eight row blocks of Q,
+// four column blocks of N, two planes each) arrive by global-to-LDS loads through a ring of three buffers, two
+// k-steps in flight, with explicit waits as in the pipelined down-projection; 72 KiB of LDS and 128 accumulator
+// registers admit two workgroups per compute unit, so that the epilogue of one (read, update, write of its W tile)
+// runs under the contraction of the other.  The registers leave no room for the whole W tile: the first row block
+// is requested before the contraction, the others when it ends.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* __restrict__ tiles,
+                                                      const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, UpArgs ua) {
+  const float lr = -ua.coef_acc;
+  const ProjTile t = tiles[blockIdx.x];
+  if (t.mat < 0) return;
+  const MatDev m = d.mats[t.mat];
+  const GAS u32x4* qa_hi = TO_GLOBAL(const u32x4, d.arena + m.qa_hi);
+  const GAS u32x4* qa_lo = TO_GLOBAL(const u32x4, d.arena + m.qa_lo);
+  const GAS u32x4* nh = TO_GLOBAL(const u32x4, n_hi + m.lr_off);
+  const GAS u32x4* nl = TO_GLOBAL(const u32x4, n_lo + m.lr_off);
+
+  // fragment slot (64 x 16 bytes) of ring buffer s: s*24 + [Q: blk*2 + plane | 16 + blk*2 + plane : N]
+  constexpr int TP = 68;                                   // pitch of the 32 x 64 staging tile of a wave
+  constexpr int SLOTS = 24;
+  constexpr int NS = 3;
+  extern __shared__ u32x4 lds_dyn[];                       // 3 x 24 KiB
+  u32x4* frag = lds_dyn;
+  static_assert(sizeof(u32x4) * NS * SLOTS * 64 >= sizeof(float) * 4 * 32 * TP, "staging blocks must fit");
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave & 1, wn = wave >> 1;
+  const int mblocks = m.pp / 32, nblocks = m.qp / 32;
+  const int mb0 = t.m0 / 32 + 4 * wm, nb0 = t.n0 / 32 + 2 * wn;    // this wave's first row / column block
+  const int p = m.p, q = m.q;
+  const int64_t rgroups = m.rp / 8;
+  const int nchunks = m.rp / 16;
+
+  // feeding role: wave w brings in row blocks 2w, 2w + 1 of Q and column block w of N, both planes: six loads per k-step
+  const GAS u32x4* fsrc[6];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int mbf = t.m0 / 32 + 2 * wave + j < mblocks ? t.m0 / 32 + 2 * wave + j : mblocks - 1;
+    fsrc[2 * j] = qa_hi + (int64_t)mbf * rgroups * 32 + lane;
+    fsrc[2 * j + 1] = qa_lo + (int64_t)mbf * rgroups * 32 + lane;
+  }
+  {
+    const int nbf = t.n0 / 32 + wave < nblocks ? t.n0 / 32 + wave : nblocks - 1;
+    fsrc[4] = nh + (int64_t)nbf * rgroups * 32 + lane;
+    fsrc[5] = nl + (int64_t)nbf * rgroups * 32 + lane;
+  }
+  auto issue_chunk = [&](int c, int s) {
+    c = c < nchunks ? c : nchunks - 1;                     // past the end the last k-step is loaded again: same count every iteration
+    u32x4* base = frag + s * SLOTS * 64;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int pl = 0; pl < 2; ++pl) dma16_async(fsrc[2 * j + pl] + (int64_t)c * 64, base + ((2 * wave + j) * 2 + pl) * 64);
+#pragma unroll
+    for (int pl = 0; pl < 2; ++pl) dma16_async(fsrc[4 + pl] + (int64_t)c * 64, base + (16 + wave * 2 + pl) * 64);
+  };
+
+  // W tile in row order: lane = (rr, c16): row rr + 4j of a row block, columns 4*c16 .. 4*c16+3 of the wave's two
+  // column blocks, so that one access of the wave covers four rows of 256 contiguous bytes
+  const uint32_t row_bytes = (uint32_t)q * 4u;
+  const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
+  const int rr = lane >> 4, c16 = lane & 15;
+  const int lcol = 32 * nb0 + 4 * c16;                       // first of the lane's four columns
+  const uint32_t voff = lcol < q ? (uint32_t)rr * row_bytes + (uint32_t)c16 * 16u : OOB;
+  auto w_soff = [&](int a, int j) -> uint32_t {
+    const int row = 32 * (mb0 + a) + 4 * j;
+    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * nb0) * 4u : (uint32_t)p * row_bytes;
+  };
+
+  issue_chunk(0, 0);
+  issue_chunk(1, 1);
+  u32x4 wv0[8], wv1[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) wv0[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, w_soff(0, j), STREAM);
+  ISSUE_FENCE();
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  // the first wait also has to cover the eight W loads issued after the two k-steps: vector-memory operations
+  // complete in order, so "at most 6 + 8 outstanding" means k-step 0 has landed
+  asm volatile("s_waitcnt vmcnt(14) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  int sbuf = 0;
+  for (int c = 0; c < nchunks; ++c) {
+    if (c > 0) WAIT_VM_BARRIER(6);                           // only k-step c+1 may be outstanding; all waves are done with c-1
+    issue_chunk(c + 2, sbuf == 0 ? 2 : sbuf - 1);          // into the buffer of k-step c-1
+    ISSUE_FENCE();
+    const u32x4* fb = frag + sbuf * SLOTS * 64;
+    sbuf = sbuf == 2 ? 0 : sbuf + 1;
+    u32x4 qh[4], ql[4], xh[2], xl[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      xh[b] = fb[(16 + (2 * wn + b) * 2 + 0) * 64 + lane];
+      xl[b] = fb[(16 + (2 * wn + b) * 2 + 1) * 64 + lane];
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      qh[a] = fb[((4 * wm + a) * 2 + 0) * 64 + lane];
+      ql[a] = fb[((4 * wm + a) * 2 + 1) * 64 + lane];
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {      // transposed block: N fragment first
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xh[b]), as_bf(qh[a]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xl[b]), as_bf(qh[a]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xh[b]), as_bf(ql[a]), acc[a][b], 0, 0, 0);
+      }
+  }
+  WAIT_VM_BARRIER(0);             // the repeated loads of the last k-step have landed, all waves are done reading fragments
+
+  if (mb0 >= mblocks || nb0 >= nblocks) return;
+  float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
+  auto combine = [&](int a, const u32x4 (&wv)[8]) {
+    // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e of its block
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        f32x4 x;
+        x.x = acc[a][b][4 * vq]; x.y = acc[a][b][4 * vq + 1]; x.z = acc[a][b][4 * vq + 2]; x.w = acc[a][b][4 * vq + 3];
+        *reinterpret_cast<f32x4*>(T + (lane & 31) * TP + 32 * b + 8 * vq + 4 * (lane >> 5)) = x;
+      }
+    // LDS operations of one wave complete in order: the reads below see the writes above
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 4 * j) * TP + 4 * c16);
+      u32x4 o;
+      o.x = __float_as_uint(fmaf(-lr, x.x, __uint_as_float(wv[j].x)));
+      o.y = __float_as_uint(fmaf(-lr, x.y, __uint_as_float(wv[j].y)));
+      o.z = __float_as_uint(fmaf(-lr, x.z, __uint_as_float(wv[j].z)));
+      o.w = __float_as_uint(fmaf(-lr, x.w, __uint_as_float(wv[j].w)));
+      __builtin_amdgcn_raw_buffer_store_b128(o, rw, voff, w_soff(a, j), STREAM);
+    }
+  };
+  auto fetch = [&](int a, u32x4 (&wv)[8]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) wv[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, w_soff(a, j), STREAM);
+  };
+  // the fragment registers are free now: two further row blocks are requested at once, the last one as soon as
+  // the first has been combined, so that only one memory latency is left exposed per tile
+  u32x4 wv2[8];
+  fetch(1, wv1);
+  fetch(2, wv2);
+  ISSUE_FENCE();
+  combine(0, wv0);
+  fetch(3, wv0);
+  ISSUE_FENCE();
+  combine(1, wv1);
+  combine(2, wv2);
+  combine(3, wv0);
+}
+
+hipError_t launch_proj_up_wide(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* b_hi, const uint16_t* b_lo,
+                               const UpArgs& ua, hipStream_t s) {
+  if (ntiles <= 0) return hipSuccess;
+  constexpr int LDS_BYTES = 3 * 24 * 1024;
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_up_wide), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(k_proj_up_wide, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo, ua);
+  return hipGetLastError();
+}
+
 // Epilogue of the Y = Src B kernels: the 2 x 2 accumulator blocks of a wave (register 4*vq+e of lane l: row l%32
 // of the row block, rank 8*vq + 4*(l/32) + e of the rank block) go through a per-wave LDS tile into row order
 // and out to buffer 0 of the Y pair with 16-byte stores along the rows.

@@ -149,6 +149,19 @@ def test_empty_and_invalid_sets(torch):
     assert e.value.code == lordo.EINVAL
 
 
+def test_local_steps_ranks_from_256_up_ragged_edges(torch):
+    """Every rank >= 256: the plain update runs on 256 x 128 tiles.  Rows that are no multiple of 256 (or of 32),
+    columns that are no multiple of 128, a rank that is no multiple of 32, one matrix smaller than a tile."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(520, 392, 256), (300, 260, 257), (257, 132, 256), (1100, 644, 320), (256, 128, 256)]
+    pair = Pair(torch, shapes, _weights(shapes, 16), orc.Hyper(), lordo.hparams(), _rand_Q(shapes, 16))
+    gens = _spiked(shapes, 16, 8)
+    for t in range(3):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3 * (1 + t), first_step_patch=(t == 0))
+        worst = pair.compare_local(TOL)
+    print("ranks >= 256:", worst, flush=True)
+
+
 def test_local_steps_identity_init_and_grad_scale(torch):
     """Q_0 = first r columns of I (the library's own initial state), grad_scale != 1."""
     from paper_2602_04396_amd import lordo
