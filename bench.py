@@ -62,6 +62,8 @@ def parse():
     ap.add_argument("--short-side", action="store_true",
                     help="project every matrix with more rows than columns on the right (shape field side = 1); "
                          "update cases plain and low-qhm")
+    ap.add_argument("--param-dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage type of the weights (bf16: updates formed in fp32 and rounded once; update cases plain, low-qhm, ef, local)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 1 GiB device copies (known traffic) to scale the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
@@ -70,10 +72,10 @@ def parse():
 KERNEL_OF_CLASS = {"down": "k_proj_down", "adam": "k_adam", "up": "k_proj_up", "outer": "k_pq<0>"}
 
 
-def measured_traffic(cfg, rank, kernel_class, update="plain"):
+def measured_traffic(cfg, rank, kernel_class, update="plain", param_dtype="f32"):
     """HBM bytes per launch of a kernel class from the committed rocprofv3 counter summary of this
     workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy), or None if there is none."""
-    if rank is not None or update != "plain":
+    if rank is not None or update != "plain" or param_dtype != "f32":
         return None
     path = os.path.join(ROOT, "profiles", f"{cfg}_hbm_traffic_pmc.txt")
     prefix = KERNEL_OF_CLASS.get(kernel_class)
@@ -95,7 +97,7 @@ def measured_traffic(cfg, rank, kernel_class, update="plain"):
     return best[1] if best else None
 
 
-def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False):
+def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False, w_bytes=4):
     """Algorithmic bytes and flops per step of each kernel class (unpadded sizes).  With error feedback
     the down-projection also reads the residual E, Adam also writes g as operand planes and the "up"
     class holds a second launch (E <- G + E - Q g: E read and written, G read); the full-rank QHM
@@ -104,7 +106,7 @@ def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False):
     spr = sum(p * r for p, q, r in shapes)
     srq = sum(r * q for p, q, r in shapes)
     flops = sum(2 * p * q * r for p, q, r in shapes)
-    up_bytes = 8 * spq + 4 * spr + 4 * srq + (grad_bytes * spq if qhm_full else 0)
+    up_bytes = 2 * w_bytes * spq + 4 * spr + 4 * srq + (grad_bytes * spq if qhm_full else 0)
     up_flops = flops
     if ef:
         up_bytes += 8 * spq + grad_bytes * spq + 4 * spr + 4 * srq
@@ -113,7 +115,7 @@ def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False):
         "down": dict(bytes=grad_bytes * spq + 4 * spr + 4 * srq + (4 * spq if ef else 0), flops=flops),
         "adam": dict(bytes=(28 if ef else 24) * srq, flops=0),
         "up": dict(bytes=up_bytes, flops=up_flops),
-        "outer": dict(bytes=24 * spq, flops=0),
+        "outer": dict(bytes=(20 + w_bytes) * spq, flops=0),
     }
 
 
@@ -131,13 +133,13 @@ def refresh_flops(shapes, q_it, rotate=True):
     return total
 
 
-def build_workload(torch, lordo, synth, cfg, rank, n_sets):
+def build_workload(torch, lordo, synth, cfg, rank, n_sets, w_dtype=None):
     shapes = synth.config_shapes(cfg, rank)
     d = synth.CONFIG_DEFAULTS[cfg]
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.seed_for(int(cfg[1:]), 999))
-    W = [(0.02 * torch.randn(p, q, generator=gen, device=dev)).contiguous() for p, q, r in shapes]
+    W = [(0.02 * torch.randn(p, q, generator=gen, device=dev)).to(w_dtype or torch.float32).contiguous() for p, q, r in shapes]
     grad_dtype = torch.float32 if cfg == "c1" else torch.bfloat16
     draws = [synth.device_spiked_gradient(torch, p, q, d["n_spike"], synth.seed_for(int(cfg[1:]), i), noise=d["noise"],
                                           dtype=grad_dtype, device=dev) for i, (p, q, r) in enumerate(shapes)]
@@ -256,8 +258,9 @@ class Workload:
         d = synth.CONFIG_DEFAULTS[cfg]
         self.defaults = d
         self.power_iters = d["power_iters"] if power_iters is None else power_iters
+        w_bf16 = getattr(args, "param_dtype", "f32") == "bf16"
         if base is None:
-            base = build_workload(torch, lordo, synth, cfg, rank, n_sets)
+            base = build_workload(torch, lordo, synth, cfg, rank, n_sets, torch.bfloat16 if w_bf16 else None)
         shapes, W, G, Omega, D, grad_dtype = base
         self.base = base
         self.grad_dtype = grad_dtype
@@ -268,7 +271,8 @@ class Workload:
         hp = lordo.hparams(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=self.power_iters,
                            grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
                            qhm_mode=self.qhm_mode, omega=0.9 if self.qhm_mode else 1.0, error_feedback=self.use_ef,
-                           uplink_buffer=self.uplink, rayleigh_ritz=args.rayleigh_ritz)
+                           uplink_buffer=self.uplink, rayleigh_ritz=args.rayleigh_ritz,
+                           param_dtype=lordo.BF16 if w_bf16 else lordo.F32)
         if args.short_side:
             gen = torch.Generator(device="cuda")
             gen.manual_seed(synth.seed_for(int(cfg[1:]), 997))
@@ -337,7 +341,7 @@ class Workload:
         self.opt.close()
 
 
-def roofline_of(kernels, total_by, work, cfg, rank, update):
+def roofline_of(kernels, total_by, work, cfg, rank, update, param_dtype="f32"):
     """Roofline entry of the kernel class that takes most of the local step."""
     dom = max((k for k in total_by if k in ("down", "adam", "up")), key=lambda k: total_by[k])
     w = work[dom]
@@ -347,10 +351,10 @@ def roofline_of(kernels, total_by, work, cfg, rank, update):
     if t_mfma > t_hbm:
         ach = w["flops"] / avg_s / 1e12
         return {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(cfg, rank, dom, update)}
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(cfg, rank, dom, update, param_dtype)}
     ach = w["bytes"] / avg_s / 1e9
     return {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, rank, dom, update)}
+            "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(cfg, rank, dom, update, param_dtype)}
 
 
 def class_ms(kernels):
@@ -367,7 +371,7 @@ def extra_configs(torch, lordo, synth, args, skip_cfg):
             continue
         wl = Workload(torch, lordo, synth, cfg, None, 4 if cfg == "c2" else 2, args)
         wl.steps(3, 0, 0)
-        work = algorithmic_work(wl.shapes, 2)
+        work = algorithmic_work(wl.shapes, 2, w_bytes=2 if args.param_dtype == "bf16" else 4)
         kernels, _ = wl.profiled(steps, 0, 0, work)
         out.append({"workload": cfg, "rank": wl.shapes[0][2], "power_iters": wl.power_iters, "ms": class_ms(kernels),
                     "GBps": {k: round(v["GBps"]) for k, v in kernels.items() if "GBps" in v},
@@ -380,7 +384,7 @@ def extra_configs(torch, lordo, synth, args, skip_cfg):
         base = None
         for rank in (64, 128, 256, 512, 1024):
             if base is None:
-                base = build_workload(torch, lordo, synth, "c5", rank, 2)
+                base = build_workload(torch, lordo, synth, "c5", rank, 2, torch.bfloat16 if args.param_dtype == "bf16" else None)
             shapes = synth.config_shapes("c5", rank)
             gen = torch.Generator(device="cuda")
             gen.manual_seed(synth.seed_for(5, 999))
@@ -390,7 +394,7 @@ def extra_configs(torch, lordo, synth, args, skip_cfg):
             for q_it in (1, 2):
                 wl = Workload(torch, lordo, synth, "c5", rank, 2, args, power_iters=q_it, base=this)
                 wl.steps(3, 0, 0)
-                work = algorithmic_work(wl.shapes, 2)
+                work = algorithmic_work(wl.shapes, 2, w_bytes=2 if args.param_dtype == "bf16" else 4)
                 kernels, _ = wl.profiled(10 if q_it == 1 else 0, 0, 0, work)
                 if q_it == 1:
                     entry["ms"] = class_ms({k: v for k, v in kernels.items() if k != "refresh"})
@@ -451,12 +455,13 @@ def main():
     ms_per_step = 1e3 * (t1 - t0) / args.steps
     wl.opt.poll_status()
 
-    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2, ef=wl.use_ef, qhm_full=wl.qhm_mode == 2)
+    w_bytes = 2 if args.param_dtype == "bf16" else 4
+    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2, ef=wl.use_ef, qhm_full=wl.qhm_mode == 2, w_bytes=w_bytes)
     kernels = {}
     roofline = None
     if not args.no_events:
         kernels, total_by = wl.profiled(args.steps, outer_every, refresh_every, work)
-        roofline = roofline_of(kernels, total_by, work, cfg, args.rank, args.update)
+        roofline = roofline_of(kernels, total_by, work, cfg, args.rank, args.update, args.param_dtype)
 
     if args.rayleigh_ritz and not args.no_events and not wl.use_ef:
         # the spectrum metrics (Sec. 5.1) on their own: the gap program is a second pass of the size of a refresh
@@ -495,7 +500,8 @@ def main():
                                     f"local steps with a refresh every {refresh_every} and an outer step every {outer_every} steps"),
                    "refresh_every": refresh_every, "outer_every": outer_every, "power_iters": power_iters,
                    "grad_sets": n_sets, "outer": "nesterov lr 0.7 momentum 0.9 on a generated averaged pseudo-gradient",
-                   "update": args.update, "rayleigh_ritz": bool(args.rayleigh_ritz), "short_side": bool(args.short_side)},
+                   "update": args.update, "rayleigh_ritz": bool(args.rayleigh_ritz), "short_side": bool(args.short_side),
+                   "param_dtype": args.param_dtype},
         "ms_per_refresh": kernels.get("refresh", {}).get("avg_ms"),
         "ms_per_outer": kernels.get("outer", {}).get("avg_ms"),
         "roofline": roofline,

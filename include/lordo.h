@@ -113,7 +113,11 @@ typedef struct {
                                     the SVD projection of Sec. 2 orders them (0: an unordered orthonormal basis of the
                                     same subspace).  Needs every rank <= 1024 (LORDO_EINVAL otherwise); sets of ranks up to 128 take a
                                     much faster solver                                                  */
-  int32_t reserved;              /* must be 0 */
+  int32_t param_dtype;           /* element type of every W: LORDO_F32 (0, the default) or LORDO_BF16 -- bf16 STORAGE of the
+                                    weights: every update is formed in fp32 from the stored value and rounded to nearest-even
+                                    once when it is written back; the anchor and the outer momentum stay fp32 (the anchor
+                                    holds the stored, i.e. rounded, model).  Built for qhm_mode 0 and 1, with or without
+                                    error feedback; not with qhm_mode 2 or uplink_buffer (LORDO_EINVAL) */
   uint64_t seed;                 /* seed of the library's own Gaussian generator, used where the caller passes no
                                     random block: lordo_init_projection(Block = NULL) (Alg. 1 "Require": random Q_0) and
                                     lordo_refresh_subspace*(Omega = NULL).  Counter-based (Philox-4x32-10 + Box-Muller):
@@ -127,7 +131,7 @@ int lordo_workspace_bytes(const lordo_shape* shapes, int32_t n, const lordo_hpar
 /* Create a context (the north-star call "lordo_init": matrix shapes, rank, hyper-parameters).
  *   arena        device, caller-allocated, 256-byte aligned, >= lordo_workspace_bytes; the library
  *                keeps Q, u, v, the anchor, the outer momentum and all scratch in it until destroy.
- *   W            host array of n device pointers to fp32 p x q weights; read once: anchor <- W.
+ *   W            host array of n device pointers to p x q weights of hp.param_dtype; read once: anchor <- W.
  * State after init: Q = first r columns of the identity (Alg. 2 "Require"), u = v = 0,
  * b = 0, t = 0 (Alg. 1 "Require").  Synchronises `stream` before returning. */
 int lordo_init(lordo_ctx** out, const lordo_shape* shapes, int32_t n, const lordo_hparams* hp,
@@ -166,7 +170,7 @@ int lordo_init_projection(lordo_ctx* ctx, const void* const* Block, void* stream
  *   qhm_mode 0:  N = u^ / den;                             W <- W - lr * Q N
  *   qhm_mode 1:  N = (omega u^ + (1-omega) g) / den;       W <- W - lr * Q N
  *   qhm_mode 2:  N = u^ / den;  s_j = mean_i den_ij;       W <- W - lr * ((1-omega) grad_scale G diag(1/s) + omega Q N)
- *   W   host array of n device pointers, fp32 p x q, updated in place.
+ *   W   host array of n device pointers, p x q of hp.param_dtype, updated in place.
  *   G   host array of n device pointers, p x q of hp.grad_dtype, read only.
  *   grad_scale  scalar the caller's gradient clipping produced (1 = none).
  * qhm_mode 2 and error feedback need q % 4 == 0 for every matrix, W aligned to 16 bytes and G to
@@ -204,7 +208,7 @@ int lordo_refresh_subspace(lordo_ctx* ctx, const void* const* Src, int32_t src_d
 int lordo_refresh_subspace_local(lordo_ctx* ctx, const void* const* G, double grad_scale,
                                  const void* const* Omega, void* stream);
 
-/* This worker's pseudo-gradient (App. A.1): DeltaOut_i <- anchor_i - W_i, fp32 p x q. */
+/* This worker's pseudo-gradient (App. A.1): DeltaOut_i <- anchor_i - W_i, fp32 p x q (W of hp.param_dtype). */
 int lordo_export_pseudograd(lordo_ctx* ctx, const void* const* W, void* const* DeltaOut, void* stream);
 
 /* Outer step (Alg. 1 OuterOpt; App. A.2): with D = AvgDelta_i (the cross-worker mean, fp32 p x q)

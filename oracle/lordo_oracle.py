@@ -161,6 +161,38 @@ def local_step(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyp
 
 
 # ----------------------------------------------------------------------------
+# weights kept in bf16 (storage option; the paper does not state the precision of its runs, Sec. 5.1)
+# ----------------------------------------------------------------------------
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 value (8 significant bits, the exponent range of float32), ties to even, of float64
+    numbers, rounded ONCE from float64: x = f * 2^e with 1 <= |f| < 2 is moved to the nearest multiple of
+    2^(e-7).  (Values below the smallest normal float32, 2^-126, do not occur in this use and are not handled.)"""
+    x = np.asarray(x, dtype=F64)
+    out = np.zeros_like(x)
+    nz = x != 0
+    e = np.floor(np.log2(np.abs(x[nz])))
+    quantum = 2.0 ** (e - 7.0)
+    out[nz] = np.rint(x[nz] / quantum) * quantum        # numpy's rint rounds halves to even
+    return out
+
+
+def local_step_bf16_weights(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyper,
+                            grad_scale: float = 1.0) -> np.ndarray:
+    """The local step of Alg. 1 for weights that are STORED in bf16: the update is applied to the stored value in
+    full precision and the result is rounded to bf16 once.  (Reading: the paper is silent on storage precision;
+    moments, projection and every intermediate stay as they are, only x is kept in the short format.)"""
+    return round_to_bf16(local_step(st, W, G, lr, hp, grad_scale))
+
+
+def outer_step_bf16_weights(st: MatrixState, avg_delta: np.ndarray, hp: Hyper) -> np.ndarray:
+    """Outer step for bf16-stored weights: OuterOpt in full precision from the anchor, the new model rounded once;
+    the anchor of the next window is the model as stored."""
+    W_new = round_to_bf16(outer_step(st, avg_delta, hp))
+    st.anchor = W_new.copy()
+    return W_new
+
+
+# ----------------------------------------------------------------------------
 # projection on the right (Sec. 2 with the roles of rows and columns exchanged)
 # ----------------------------------------------------------------------------
 def local_step_right(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyper,

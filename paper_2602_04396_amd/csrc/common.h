@@ -130,6 +130,7 @@ struct UpArgs {
   // anchor instead of W and also writes the anchor and the momentum b
   int32_t outer, nesterov, has_mom;
   float mu;
+  int32_t w_bf16;         // the caller's W is bf16 storage (target W only; the plain update)
 };
 hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bool vec, const uint16_t* b_hi,
                           const uint16_t* b_lo, const UpArgs& ua, hipStream_t s);
@@ -170,12 +171,12 @@ hipError_t launch_identity_q(const DevCtx& d, hipStream_t s);
 hipError_t launch_fill_zero(void* dst, int64_t bytes, hipStream_t s);
 hipError_t launch_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
 // p x q elementwise family: chunk_start (device) has n+1 entries, prefix sums of per-matrix chunk counts
-struct OuterArgs { float lr, mu; int32_t nesterov, has_mom, own_delta; };
+struct OuterArgs { float lr, mu; int32_t nesterov, has_mom, own_delta, w_bf16; };
 hipError_t launch_outer(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s);
 hipError_t launch_outer_base(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s);
 hipError_t launch_split_planes(const float* src, uint16_t* p_hi, uint16_t* p_lo, int64_t nelem, hipStream_t s);
-hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
-hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s);
+hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, bool w_bf16, hipStream_t s);
+hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, bool w_bf16, hipStream_t s);
 hipError_t launch_fold_grad(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, float scale, bool g_is_f32, hipStream_t s, bool only_tr = false);
 // refresh helpers (grouped over all matrices)
 hipError_t launch_gram_shift(const DevCtx& d, float coef, bool store, hipStream_t s);

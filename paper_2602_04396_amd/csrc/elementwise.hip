@@ -399,19 +399,69 @@ __device__ __forceinline__ int find_mat(const int64_t* chunk_start, int n, int64
   return lo;
 }
 
-template <int MODE>   // 0 outer step, 1 export delta, 2 anchor <- W, 3 part of the outer step that does not depend on Delta
+// Four consecutive weights at W + i0: fp32, or bf16 storage (values widened exactly on the way in, rounded to
+// nearest-even once on the way out; the value an outer step leaves in the anchor is the rounded one, i.e. the stored model).
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float f32x2n __attribute__((ext_vector_type(2)));
+  const f32x2n v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+template <bool WBF>
+__device__ __forceinline__ void load_w4(const void* W, int64_t i0, float (&w)[4]) {
+  if constexpr (WBF) {
+    const u32x2n t = __builtin_nontemporal_load(reinterpret_cast<const u32x2n*>(reinterpret_cast<const uint16_t*>(W) + i0));
+    w[0] = __uint_as_float(t.x << 16); w[1] = __uint_as_float(t.x & 0xffff0000u);
+    w[2] = __uint_as_float(t.y << 16); w[3] = __uint_as_float(t.y & 0xffff0000u);
+  } else {
+    const f32x4n t = ld_stream(reinterpret_cast<const float*>(W) + i0);
+    w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+  }
+}
+// returns the values as stored (rounded for bf16 weights); `cached`: an ordinary store (the consumer reads it right away)
+template <bool WBF>
+__device__ __forceinline__ f32x4n store_w4(void* W, int64_t i0, f32x4n x, bool cached) {
+  if constexpr (WBF) {
+    const u32x2n t = {pack2_bf16(x.x, x.y), pack2_bf16(x.z, x.w)};
+    u32x2n* dst = reinterpret_cast<u32x2n*>(reinterpret_cast<uint16_t*>(W) + i0);
+    if (cached) *dst = t; else __builtin_nontemporal_store(t, dst);
+    return f32x4n{__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xffff0000u), __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xffff0000u)};
+  } else {
+    float* dst = reinterpret_cast<float*>(W) + i0;
+    if (cached) *reinterpret_cast<f32x4n*>(dst) = x; else st_stream(dst, x);
+    return x;
+  }
+}
+template <bool WBF>
+__device__ __forceinline__ float load_w1(const void* W, int64_t i) {
+  if constexpr (WBF) return bf2f(reinterpret_cast<const uint16_t*>(W)[i]);
+  else return reinterpret_cast<const float*>(W)[i];
+}
+template <bool WBF>
+__device__ __forceinline__ float store_w1(void* W, int64_t i, float x) {
+  if constexpr (WBF) {
+    const uint32_t h = f2bf(x);
+    reinterpret_cast<uint16_t*>(W)[i] = (uint16_t)h;
+    return bf2f(h);
+  } else {
+    reinterpret_cast<float*>(W)[i] = x;
+    return x;
+  }
+}
+
+template <int MODE, bool WBF>   // 0 outer step, 1 export delta, 2 anchor <- W, 3 part of the outer step that does not depend on Delta; WBF: bf16 weights
 __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict__ chunk_start, OuterArgs a) {
   int64_t b = blockIdx.x;
   int mat = find_mat(chunk_start, d.n, b);
   const MatDev& m = d.mats[mat];
   int64_t total = (int64_t)m.p * m.q;
   int64_t off = (b - chunk_start[mat]) * CHUNK;
-  float* W = reinterpret_cast<float*>(ext_ptr(d, EXT_W, mat));
+  void* W = ext_ptr(d, EXT_W, mat);
   float* anchor = reinterpret_cast<float*>(d.arena + m.anchor);
   float* mom = a.has_mom ? reinterpret_cast<float*>(d.arena + m.mom) : nullptr;
   const float* din = (MODE == 0 && !a.own_delta) ? reinterpret_cast<const float*>(ext_ptr(d, EXT_DIN, mat)) : nullptr;
   float* dout = MODE == 1 ? reinterpret_cast<float*>(ext_ptr(d, EXT_DOUT, mat)) : nullptr;
-  bool vec = (total % 4 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
+  bool vec = (total % 4 == 0) && ((reinterpret_cast<uintptr_t>(W) & (WBF ? 7 : 15)) == 0) &&
              (din == nullptr || (reinterpret_cast<uintptr_t>(din) & 15) == 0) &&
              (dout == nullptr || (reinterpret_cast<uintptr_t>(dout) & 15) == 0);
 #pragma unroll
@@ -422,13 +472,13 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
     int cnt = total - i0 < 4 ? (int)(total - i0) : 4;
     if (vec) {       // every array here is touched once per call and is far larger than the caches: streaming accesses
       f32x4n t;
-      if ((MODE != 0 && MODE != 3) || (MODE == 0 && a.own_delta)) { t = ld_stream(W + i0); w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w; }
+      if ((MODE != 0 && MODE != 3) || (MODE == 0 && a.own_delta)) load_w4<WBF>(W, i0, w);
       if (MODE != 2) { t = ld_stream(anchor + i0); an[0] = t.x; an[1] = t.y; an[2] = t.z; an[3] = t.w; }
       if (din) { t = ld_stream(din + i0); dl[0] = t.x; dl[1] = t.y; dl[2] = t.z; dl[3] = t.w; }
       if ((MODE == 0 || MODE == 3) && mom) { t = ld_stream(mom + i0); bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w; }
     } else {
       for (int e = 0; e < cnt; ++e) {
-        if ((MODE != 0 && MODE != 3) || (MODE == 0 && a.own_delta)) w[e] = W[i0 + e];
+        if ((MODE != 0 && MODE != 3) || (MODE == 0 && a.own_delta)) w[e] = load_w1<WBF>(W, i0 + e);
         if (MODE != 2) an[e] = anchor[i0 + e];
         if (din) dl[e] = din[i0 + e];
         if ((MODE == 0 || MODE == 3) && mom) bb[e] = mom[i0 + e];
@@ -465,44 +515,48 @@ __global__ __launch_bounds__(256) void k_pq(DevCtx d, const int64_t* __restrict_
     if (vec) {
       f32x4n t0 = {o0[0], o0[1], o0[2], o0[3]};
       if (MODE == 0) {
-        st_stream(W + i0, t0);
-        st_stream(anchor + i0, t0);
+        const f32x4n kept = store_w4<WBF>(W, i0, t0, false);
+        st_stream(anchor + i0, kept);                          // the anchor is the model as it is stored
         if (mom) st_stream(mom + i0, f32x4n{o1[0], o1[1], o1[2], o1[3]});
       } else if (MODE == 1) {
         st_stream(dout + i0, t0);
       } else if (MODE == 2) {
         st_stream(anchor + i0, t0);
       } else {             // the up-projection kernel reads both again right away: cacheable stores
-        *reinterpret_cast<f32x4n*>(W + i0) = t0;
+        store_w4<WBF>(W, i0, t0, true);
         if (mom) *reinterpret_cast<f32x4n*>(mom + i0) = f32x4n{o1[0], o1[1], o1[2], o1[3]};
       }
     } else {
       for (int e = 0; e < cnt; ++e) {
-        if (MODE == 0) { W[i0 + e] = o0[e]; anchor[i0 + e] = o0[e]; if (mom) mom[i0 + e] = o1[e]; }
+        if (MODE == 0) { anchor[i0 + e] = store_w1<WBF>(W, i0 + e, o0[e]); if (mom) mom[i0 + e] = o1[e]; }
         else if (MODE == 1) dout[i0 + e] = o0[e];
         else if (MODE == 2) anchor[i0 + e] = o0[e];
-        else { W[i0 + e] = o0[e]; if (mom) mom[i0 + e] = o1[e]; }
+        else { store_w1<WBF>(W, i0 + e, o0[e]); if (mom) mom[i0 + e] = o1[e]; }
       }
     }
   }
 }
 
 hipError_t launch_outer(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(k_pq<0>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  if (a.w_bf16) hipLaunchKernelGGL((k_pq<0, true>), dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  else hipLaunchKernelGGL((k_pq<0, false>), dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
   return hipGetLastError();
 }
 hipError_t launch_outer_base(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, const OuterArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(k_pq<3>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  if (a.w_bf16) return hipErrorInvalidValue;       // (the outer step from the up-link buffers is built for fp32 weights)
+  hipLaunchKernelGGL((k_pq<3, false>), dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
   return hipGetLastError();
 }
-hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s) {
+hipError_t launch_export_delta(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, bool w_bf16, hipStream_t s) {
   OuterArgs a{};
-  hipLaunchKernelGGL(k_pq<1>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  if (w_bf16) hipLaunchKernelGGL((k_pq<1, true>), dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  else hipLaunchKernelGGL((k_pq<1, false>), dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
   return hipGetLastError();
 }
-hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, hipStream_t s) {
+hipError_t launch_anchor_from_w(const DevCtx& d, const int64_t* chunk_start, int64_t nchunks, bool w_bf16, hipStream_t s) {
   OuterArgs a{};
-  hipLaunchKernelGGL(k_pq<2>, dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  if (w_bf16) hipLaunchKernelGGL((k_pq<2, true>), dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
+  else hipLaunchKernelGGL((k_pq<2, false>), dim3((unsigned)nchunks), dim3(256), 0, s, d, chunk_start, a);
   return hipGetLastError();
 }
 

@@ -577,7 +577,11 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
   if ((hp->uplink_buffer != 0 && hp->uplink_buffer != 1) || (hp->uplink_buffer && hp->qhm_mode == 2)) return LORDO_EINVAL;
   if (hp->qhm_mode != 0 && !(hp->omega >= 0.0 && hp->omega <= 1.0)) return LORDO_EINVAL;
   if (hp->power_iters < 0 || hp->power_iters > 8) return LORDO_EINVAL;
-  if ((hp->rayleigh_ritz != 0 && hp->rayleigh_ritz != 1) || hp->reserved != 0) return LORDO_EINVAL;
+  if (hp->rayleigh_ritz != 0 && hp->rayleigh_ritz != 1) return LORDO_EINVAL;
+  if (hp->param_dtype != LORDO_F32 && hp->param_dtype != LORDO_BF16) return LORDO_EINVAL;
+  // bf16 weights: built for the plain and the low-rank QHM update (with or without error feedback); the gradient-term
+  // epilogue of the full-rank QHM update and the fused outer step from the up-link buffers write fp32 weights only
+  if (hp->param_dtype == LORDO_BF16 && (hp->qhm_mode == 2 || hp->uplink_buffer)) return LORDO_EINVAL;
   if (hp->rayleigh_ritz)          // a wave of the multi-launch Jacobi solver keeps two columns of r elements in registers
     for (int i = 0; i < n; ++i)
       if (shapes[i].rank > 1024) return LORDO_EINVAL;
@@ -1059,7 +1063,7 @@ static int init_context(lordo_ctx** out, const lordo_shape* shapes, int32_t n, c
     int r2 = c->set_ext(EXT_W, W, s);
     if (r2 != LORDO_OK) return fail(r2);
   }
-  INITCHK(launch_anchor_from_w(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, s));
+  INITCHK(launch_anchor_from_w(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, hp->param_dtype == LORDO_BF16, s));
   INITCHK(hipStreamSynchronize(s));
 #undef INITCHK
   *out = c;
@@ -1142,13 +1146,15 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   bool g_vec = true;            // 4-byte accesses to a bf16 G need an even q and 4-byte aligned pointers
   for (int i = 0; i < c->n; ++i)      // (right-projected matrices do not pass through the projection kernels)
     if (!P.mat[i].tr && ((P.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 3) != 0)) { g_vec = false; break; }
-  bool w_vec = true;            // 16-byte accesses to W need q % 4 == 0 and 16-byte aligned pointers
+  const bool w_bf16 = c->hp.param_dtype == LORDO_BF16;
+  const uintptr_t w_mask = w_bf16 ? 7 : 15;     // four weights with one access: 16 bytes of fp32, 8 bytes of bf16
+  bool w_vec = true;            // four-column accesses to W need q % 4 == 0 and pointers aligned to them
   for (int i = 0; i < c->n; ++i)
-    if (!P.mat[i].tr && ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0)) { w_vec = false; break; }
+    if (!P.mat[i].tr && ((P.mat[i].q & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & w_mask) != 0)) { w_vec = false; break; }
   if (qhm_full || ef) {         // the gradient-term epilogue reads four columns of G per lane
     if (!w_vec) return LORDO_EINVAL;
     for (int i = 0; i < c->n; ++i)
-      if (P.mat[i].tr && ((P.mat[i].p & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0)) return LORDO_EINVAL;
+      if (P.mat[i].tr && ((P.mat[i].p & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & w_mask) != 0)) return LORDO_EINVAL;
     for (int i = 0; i < c->n; ++i)
       if ((reinterpret_cast<uintptr_t>(G[i]) & (g_f32 ? 15 : 7)) != 0) return LORDO_EINVAL;
   }
@@ -1201,6 +1207,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   UpArgs ua{};
   ua.g_is_f32 = g_f32 ? 1 : 0;
   ua.eps = (float)c->hp.eps;
+  ua.w_bf16 = w_bf16 ? 1 : 0;
   if (ef) {                     // E <- grad_scale*G + E - Q g (Alg. 1 error-feedback lines); reads the E the down-projection used
     ua.coef_acc = -1.f; ua.coef_g = (float)proj_scale; ua.target_err = 1; ua.colscale = 0; ua.colpart = nullptr;
     if (!P.up_h.empty())
@@ -1232,7 +1239,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (P.any_tr) {               // W <- W - eta N^T Q^T: the up-projection kernel on the shadow records (planes of N as A, of Q as B)
     bool w_vec_tr = true;
     for (int i = 0; i < c->n && w_vec_tr; ++i)
-      if (P.mat[i].tr && ((P.mat[i].p & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & 15) != 0)) w_vec_tr = false;
+      if (P.mat[i].tr && ((P.mat[i].p & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & w_mask) != 0)) w_vec_tr = false;
     DevCtx du = c->dev;
     du.mats = c->at<MatDev>(P.mats_up);
     HIPCHK(launch_proj_up(du, c->at<ProjTile>(P.up_tr_tiles), (int)P.up_tr_h.size(), w_vec_tr, reinterpret_cast<uint16_t*>(c->dev.arena),
@@ -1466,7 +1473,7 @@ int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* Del
   rc = c->set_ext(EXT_DOUT, DeltaOut, s);
   if (rc != LORDO_OK) return rc;
   c->prof.begin(LORDO_K_EXPORT, s);
-  HIPCHK(launch_export_delta(c->dev, c->at<int64_t>(c->plan.chunk_start), c->plan.nchunks, s));
+  HIPCHK(launch_export_delta(c->dev, c->at<int64_t>(c->plan.chunk_start), c->plan.nchunks, c->hp.param_dtype == LORDO_BF16, s));
   c->prof.end(LORDO_K_EXPORT, s);
   return LORDO_OK;
 }
@@ -1485,6 +1492,7 @@ int lordo_outer_step(lordo_ctx* c, void* const* W, const void* const* AvgDelta, 
   a.nesterov = c->hp.outer_nesterov ? 1 : 0;
   a.has_mom = c->hp.outer_momentum != 0.0 ? 1 : 0;
   a.own_delta = AvgDelta ? 0 : 1;
+  a.w_bf16 = c->hp.param_dtype == LORDO_BF16 ? 1 : 0;
   if (AvgDelta) {
     rc = c->set_ext(EXT_DIN, const_cast<void* const*>(reinterpret_cast<const void* const*>(AvgDelta)), s);
     if (rc != LORDO_OK) return rc;
@@ -1556,6 +1564,7 @@ int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* Av
   a.nesterov = c->hp.outer_nesterov ? 1 : 0;
   a.has_mom = c->hp.outer_momentum != 0.0 ? 1 : 0;
   a.own_delta = 0;
+  a.w_bf16 = 0;               // (the up-link buffer is refused with bf16 weights)
   const int64_t* chunks = c->at<int64_t>(P.chunk_start);
   c->prof.begin(LORDO_K_OUTER, s);
   // the averaged buffer replaces this worker's own (which the step clears anyway); its bf16 hi / lo planes
@@ -1587,7 +1596,7 @@ int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* Av
     ua.coef_acc = 1.f;
     HIPCHK(up_all(ua));
   }
-  HIPCHK(launch_anchor_from_w(c->dev, chunks, P.nchunks, s));
+  HIPCHK(launch_anchor_from_w(c->dev, chunks, P.nchunks, false, s));
   HIPCHK(launch_fill_zero(c->at<void>(P.acc), sizeof(float) * P.lr_total, s));
   c->prof.end(LORDO_K_OUTER, s);
   c->window_steps = 0;

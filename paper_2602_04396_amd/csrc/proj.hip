@@ -908,6 +908,37 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
   return hipGetLastError();
 }
 
+// Element type of the caller's weights: fp32, or bf16 storage (the update is formed in fp32 from the stored value and
+// rounded to nearest-even once when it is written back).  Four consecutive columns of a row per lane.
+template <bool WBF> struct WAcc;
+template <> struct WAcc<false> {
+  static constexpr uint32_t ES = 4;
+  typedef u32x4 raw_t;
+  static __device__ __forceinline__ raw_t load(rsrc_t r, uint32_t voff, uint32_t soff) { return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, STREAM); }
+  static __device__ __forceinline__ f32x4 unpack(raw_t w) {
+    return f32x4{__uint_as_float(w.x), __uint_as_float(w.y), __uint_as_float(w.z), __uint_as_float(w.w)};
+  }
+  static __device__ __forceinline__ void store(f32x4 x, rsrc_t r, uint32_t voff, uint32_t soff) {
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4{__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)}, r, voff, soff, STREAM);
+  }
+};
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {       // the hardware's packed round-to-nearest-even conversion
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+template <> struct WAcc<true> {
+  static constexpr uint32_t ES = 2;
+  typedef u32x2 raw_t;
+  static __device__ __forceinline__ raw_t load(rsrc_t r, uint32_t voff, uint32_t soff) { return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, STREAM); }
+  static __device__ __forceinline__ f32x4 unpack(raw_t w) {
+    return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u)};
+  }
+  static __device__ __forceinline__ void store(f32x4 x, rsrc_t r, uint32_t voff, uint32_t soff) {
+    __builtin_amdgcn_raw_buffer_store_b64(u32x2{pack_bf16_rne(x.x, x.y), pack_bf16_rne(x.z, x.w)}, r, voff, soff, STREAM);
+  }
+};
+
 // ---------------------------------------------------------------------------------------
 // Up-projection with the weight update fused, fallback for any q and any alignment of W (the main
 // path below needs q % 4 == 0 and 16-byte aligned W).  Workgroup tile 128 x 128 of W, 4 waves in a
@@ -916,8 +947,10 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
 // the W tile is fetched through a buffer resource, one dword per access, before the contraction so
 // that its latency hides behind it.
 // ---------------------------------------------------------------------------------------
+template <bool WBF>       // WBF: the caller's W is bf16 (never together with to_mom: the momentum is fp32)
 __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __restrict__ tiles,
                                                  const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, float lr, int to_mom) {
+  constexpr uint32_t ES = WBF ? 2u : 4u;
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0 || mat_skipped(d, t.mat)) return;
   const MatDev m = d.mats[t.mat];
@@ -939,17 +972,17 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
   // outside the buffer (reads give 0, writes are dropped).  Register v of block (a, b) is row
   // 8*(v/4) + 4*(lane/32) + v%4, column lane%32: the lane supplies its part of the offset, the
   // block / register part is scalar, and a row at or past p gets the size of the resource.
-  const uint32_t row_bytes = (uint32_t)q * 4u;
+  const uint32_t row_bytes = (uint32_t)q * ES;
   const rsrc_t rw = make_rsrc(to_mom ? static_cast<void*>(d.arena + m.mom) : ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
   uint32_t voff[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     int col = 32 * (nb0 + b) + (lane & 31);
-    voff[b] = col < q ? (uint32_t)(4 * (lane >> 5)) * row_bytes + (uint32_t)(lane & 31) * 4u : OOB;
+    voff[b] = col < q ? (uint32_t)(4 * (lane >> 5)) * row_bytes + (uint32_t)(lane & 31) * ES : OOB;
   }
   auto w_soff = [&](int a, int b, int v) -> uint32_t {
     const int row = 32 * (mb0 + a) + 8 * (v >> 2) + (v & 3);
-    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * (nb0 + b)) * 4u : (uint32_t)p * row_bytes;
+    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * (nb0 + b)) * ES : (uint32_t)p * row_bytes;
   };
   float wv[2][2][16];
 #pragma unroll
@@ -957,8 +990,10 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], w_soff(a, b, v), STREAM));
+      for (int v = 0; v < 16; ++v) {
+        if constexpr (WBF) wv[a][b][v] = __uint_as_float((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rw, voff[b], w_soff(a, b, v), STREAM) << 16);
+        else wv[a][b][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, voff[b], w_soff(a, b, v), STREAM));
+      }
   ISSUE_FENCE();
 
   f32x16 acc[2][2];
@@ -1020,9 +1055,11 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 #pragma unroll
     for (int v = 0; v < 16; ++v)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(fmaf(-lr, acc[a][b][v], wv[a][b][v])), rw, voff[b],
-                                              w_soff(a, b, v), STREAM);
+      for (int b = 0; b < 2; ++b) {
+        const float val = fmaf(-lr, acc[a][b][v], wv[a][b][v]);
+        if constexpr (WBF) __builtin_amdgcn_raw_buffer_store_b16((short)f2bf_rne(val), rw, voff[b], w_soff(a, b, v), STREAM);
+        else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), rw, voff[b], w_soff(a, b, v), STREAM);
+      }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1052,11 +1089,15 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 //   Delta = Q B stays in the accumulators, the tile that is read is the anchor, and the epilogue does
 //   b <- mu b + Delta;  x <- anchor - eta_s (Delta + mu b) (Nesterov), anchor - eta_s b (heavy ball) or anchor - eta_s Delta
 //   (no momentum);  W <- x, anchor <- x.
-template <int NW, int EPI>         // NW waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64); EPI 0 plain, 1 gradient term, 2 outer step
+template <int NW, int EPI, bool WBF>   // NW waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64); EPI 0 plain, 1 gradient term, 2 outer step;
+                                       // WBF: the caller's W is bf16 (plain update only)
 __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
                                                          const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, UpArgs ua) {
   constexpr bool WITH_G = EPI == 1;
   constexpr bool OUTER = EPI == 2;
+  static_assert(!WBF || EPI == 0, "bf16 weights: plain update only");
+  typedef WAcc<WBF> WA;
+  constexpr uint32_t WES = WA::ES;
   const float lr = -ua.coef_acc;
   constexpr int AM = NW == 4 ? 2 : 1;                      // row blocks per wave
   constexpr int WM = 4 / AM;                               // wave rows
@@ -1105,7 +1146,7 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 
   // W tile in row order: lane = (rr, c16): row rr + 4j of a row block, columns 4*c16 .. 4*c16+3 of the wave's two
   // column blocks, so that one access of the wave covers four rows of 256 contiguous bytes
-  const uint32_t row_bytes = (uint32_t)q * 4u;
+  const uint32_t row_bytes = (uint32_t)q * WES;
   const void* target = ua.target_err == 1 ? static_cast<const void*>(d.arena + m.err)
                        : ua.target_err == 2 ? static_cast<const void*>(d.arena + m.mom) : ext_ptr(d, EXT_W, t.mat);
   const rsrc_t rw_out = make_rsrc(target, (uint32_t)p * row_bytes);
@@ -1116,20 +1157,20 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   const int rr = lane >> 4, c16 = lane & 15;
   const int bsel = c16 >> 3;                                 // which of the two column blocks the lane's columns lie in
   const int lcol = 32 * nb0 + 4 * c16;                       // first of the lane's four columns
-  const uint32_t voff = lcol < q ? (uint32_t)rr * row_bytes + (uint32_t)c16 * 16u : OOB;
+  const uint32_t voff = lcol < q ? (uint32_t)rr * row_bytes + (uint32_t)c16 * (4u * WES) : OOB;
   // a group of four rows that starts at or past the last row gets the size of the resource as its
   // scalar offset, which puts every lane of the access out of range
   auto w_soff = [&](int a, int j) -> uint32_t {
     const int row = 32 * (mb0 + a) + 4 * j;
-    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * nb0) * 4u : (uint32_t)p * row_bytes;
+    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * nb0) * WES : (uint32_t)p * row_bytes;
   };
 
   issue_chunk(0, 0);
-  u32x4 wv[AM][8];
+  typename WA::raw_t wv[AM][8];
 #pragma unroll
   for (int a = 0; a < AM; ++a)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) wv[a][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, w_soff(a, j), STREAM);
+    for (int j = 0; j < 8; ++j) wv[a][j] = WA::load(rw, voff, w_soff(a, j));
   // gradient term (WITH_G): four consecutive columns per lane, same rows as the W accesses; a bf16 G tile is
   // requested here, with the W tile, so that it arrives during the contraction
   const uint32_t ges = ua.g_is_f32 ? 4u : 2u;
@@ -1246,11 +1287,16 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 4 * j) * TP + 4 * c16);
+      const f32x4 wf = WA::unpack(wv[a][j]);
+      if constexpr (WBF) {
+        WA::store(f32x4{fmaf(-lr, x.x, wf.x), fmaf(-lr, x.y, wf.y), fmaf(-lr, x.z, wf.z), fmaf(-lr, x.w, wf.w)}, rw_out, voff, w_soff(a, j));
+        continue;
+      }
       u32x4 o;
-      o.x = __float_as_uint(fmaf(-lr, x.x, __uint_as_float(wv[a][j].x)));
-      o.y = __float_as_uint(fmaf(-lr, x.y, __uint_as_float(wv[a][j].y)));
-      o.z = __float_as_uint(fmaf(-lr, x.z, __uint_as_float(wv[a][j].z)));
-      o.w = __float_as_uint(fmaf(-lr, x.w, __uint_as_float(wv[a][j].w)));
+      o.x = __float_as_uint(fmaf(-lr, x.x, wf.x));
+      o.y = __float_as_uint(fmaf(-lr, x.y, wf.y));
+      o.z = __float_as_uint(fmaf(-lr, x.z, wf.z));
+      o.w = __float_as_uint(fmaf(-lr, x.w, wf.w));
       if constexpr (WITH_G) {
         o.x = __float_as_uint(__uint_as_float(o.x) + gt[j].x); o.y = __float_as_uint(__uint_as_float(o.y) + gt[j].y);
         o.z = __float_as_uint(__uint_as_float(o.z) + gt[j].z); o.w = __float_as_uint(__uint_as_float(o.w) + gt[j].w);
@@ -1268,10 +1314,10 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
           u32x4 bs = {__float_as_uint(bn.x), __float_as_uint(bn.y), __float_as_uint(bn.z), __float_as_uint(bn.w)};
           __builtin_amdgcn_raw_buffer_store_b128(bs, rmom, voff, w_soff(a, j), STREAM);
         }
-        o.x = __float_as_uint(fmaf(-lr, step.x, __uint_as_float(wv[a][j].x)));
-        o.y = __float_as_uint(fmaf(-lr, step.y, __uint_as_float(wv[a][j].y)));
-        o.z = __float_as_uint(fmaf(-lr, step.z, __uint_as_float(wv[a][j].z)));
-        o.w = __float_as_uint(fmaf(-lr, step.w, __uint_as_float(wv[a][j].w)));
+        o.x = __float_as_uint(fmaf(-lr, step.x, wf.x));
+        o.y = __float_as_uint(fmaf(-lr, step.y, wf.y));
+        o.z = __float_as_uint(fmaf(-lr, step.z, wf.z));
+        o.w = __float_as_uint(fmaf(-lr, step.w, wf.w));
         __builtin_amdgcn_raw_buffer_store_b128(o, ranchor, voff, w_soff(a, j), STREAM);
       }
       __builtin_amdgcn_raw_buffer_store_b128(o, rw_out, voff, w_soff(a, j), STREAM);
@@ -1291,8 +1337,11 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 // runs under the contraction of the other.  The registers leave no room for the whole W tile: the first row block
 // is requested before the contraction, the others when it ends.
 // ---------------------------------------------------------------------------------------
+template <bool WBF>
 __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* __restrict__ tiles,
                                                       const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, UpArgs ua) {
+  typedef WAcc<WBF> WA;
+  constexpr uint32_t WES = WA::ES;
   const float lr = -ua.coef_acc;
   const ProjTile t = tiles[blockIdx.x];
   if (t.mat < 0) return;
@@ -1345,21 +1394,21 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
 
   // W tile in row order: lane = (rr, c16): row rr + 4j of a row block, columns 4*c16 .. 4*c16+3 of the wave's two
   // column blocks, so that one access of the wave covers four rows of 256 contiguous bytes
-  const uint32_t row_bytes = (uint32_t)q * 4u;
+  const uint32_t row_bytes = (uint32_t)q * WES;
   const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
   const int rr = lane >> 4, c16 = lane & 15;
   const int lcol = 32 * nb0 + 4 * c16;                       // first of the lane's four columns
-  const uint32_t voff = lcol < q ? (uint32_t)rr * row_bytes + (uint32_t)c16 * 16u : OOB;
+  const uint32_t voff = lcol < q ? (uint32_t)rr * row_bytes + (uint32_t)c16 * (4u * WES) : OOB;
   auto w_soff = [&](int a, int j) -> uint32_t {
     const int row = 32 * (mb0 + a) + 4 * j;
-    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * nb0) * 4u : (uint32_t)p * row_bytes;
+    return row < p ? (uint32_t)row * row_bytes + (uint32_t)(32 * nb0) * WES : (uint32_t)p * row_bytes;
   };
 
   issue_chunk(0, 0);
   issue_chunk(1, 1);
-  u32x4 wv0[8], wv1[8];
+  typename WA::raw_t wv0[8], wv1[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) wv0[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, w_soff(0, j), STREAM);
+  for (int j = 0; j < 8; ++j) wv0[j] = WA::load(rw, voff, w_soff(0, j));
   ISSUE_FENCE();
 
   f32x16 acc[4][2];
@@ -1404,7 +1453,7 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
 
   if (mb0 >= mblocks || nb0 >= nblocks) return;
   float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
-  auto combine = [&](int a, const u32x4 (&wv)[8]) {
+  auto combine = [&](int a, const typename WA::raw_t (&wv)[8]) {
     // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e of its block
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -1418,21 +1467,17 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 4 * j) * TP + 4 * c16);
-      u32x4 o;
-      o.x = __float_as_uint(fmaf(-lr, x.x, __uint_as_float(wv[j].x)));
-      o.y = __float_as_uint(fmaf(-lr, x.y, __uint_as_float(wv[j].y)));
-      o.z = __float_as_uint(fmaf(-lr, x.z, __uint_as_float(wv[j].z)));
-      o.w = __float_as_uint(fmaf(-lr, x.w, __uint_as_float(wv[j].w)));
-      __builtin_amdgcn_raw_buffer_store_b128(o, rw, voff, w_soff(a, j), STREAM);
+      const f32x4 wf = WA::unpack(wv[j]);
+      WA::store(f32x4{fmaf(-lr, x.x, wf.x), fmaf(-lr, x.y, wf.y), fmaf(-lr, x.z, wf.z), fmaf(-lr, x.w, wf.w)}, rw, voff, w_soff(a, j));
     }
   };
-  auto fetch = [&](int a, u32x4 (&wv)[8]) {
+  auto fetch = [&](int a, typename WA::raw_t (&wv)[8]) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) wv[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, w_soff(a, j), STREAM);
+    for (int j = 0; j < 8; ++j) wv[j] = WA::load(rw, voff, w_soff(a, j));
   };
   // the fragment registers are free now: two further row blocks are requested at once, the last one as soon as
   // the first has been combined, so that only one memory latency is left exposed per tile
-  u32x4 wv2[8];
+  typename WA::raw_t wv2[8];
   fetch(1, wv1);
   fetch(2, wv2);
   ISSUE_FENCE();
@@ -1450,11 +1495,13 @@ hipError_t launch_proj_up_wide(const DevCtx& d, const ProjTile* tiles, int ntile
   constexpr int LDS_BYTES = 3 * 24 * 1024;
   static bool raised = false;
   if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_up_wide), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_up_wide<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_up_wide<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return e;
     raised = true;
   }
-  hipLaunchKernelGGL(k_proj_up_wide, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo, ua);
+  if (ua.w_bf16) hipLaunchKernelGGL(k_proj_up_wide<true>, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo, ua);
+  else hipLaunchKernelGGL(k_proj_up_wide<false>, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo, ua);
   return hipGetLastError();
 }
 
@@ -1615,16 +1662,19 @@ hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bo
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
   const bool with_g = ua.coef_g != 0.f || ua.target_err == 1;
+  const bool w_bf16 = ua.w_bf16 != 0 && ua.target_err == 0;     // (the residual and the momentum are fp32 whatever the weights are)
   if (ua.outer) {
-    if (!vec) return hipErrorInvalidValue;       // the outer-step epilogue exists for 16-byte row accesses only
-    hipLaunchKernelGGL((k_proj_up_dma<4, 2>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    if (!vec || w_bf16) return hipErrorInvalidValue;       // the outer-step epilogue exists for 16-byte row accesses of fp32 weights only
+    hipLaunchKernelGGL((k_proj_up_dma<4, 2, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else if (with_g) {
-    if (!vec) return hipErrorInvalidValue;       // the gradient-term epilogue exists for 16-byte row accesses only
-    hipLaunchKernelGGL((k_proj_up_dma<4, 1>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    if (!vec || w_bf16) return hipErrorInvalidValue;       // the gradient-term epilogue exists for 16-byte row accesses of fp32 targets only
+    hipLaunchKernelGGL((k_proj_up_dma<4, 1, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else if (vec) {
-    hipLaunchKernelGGL((k_proj_up_dma<4, 0>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    if (w_bf16) hipLaunchKernelGGL((k_proj_up_dma<4, 0, true>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    else hipLaunchKernelGGL((k_proj_up_dma<4, 0, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else {
-    hipLaunchKernelGGL(k_proj_up, grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc, ua.target_err == 2 ? 1 : 0);
+    if (w_bf16) hipLaunchKernelGGL(k_proj_up<true>, grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc, 0);
+    else hipLaunchKernelGGL(k_proj_up<false>, grid, block, 0, s, d, tiles, b_hi, b_lo, -ua.coef_acc, ua.target_err == 2 ? 1 : 0);
   }
   return hipGetLastError();
 }

@@ -41,17 +41,17 @@ class HParams(C.Structure):
         ("outer_lr", C.c_double), ("outer_momentum", C.c_double),
         ("power_iters", C.c_int32), ("orth_passes", C.c_int32),
         ("grad_dtype", C.c_int32), ("uplink_buffer", C.c_int32),
-        ("rayleigh_ritz", C.c_int32), ("reserved", C.c_int32),
+        ("rayleigh_ritz", C.c_int32), ("param_dtype", C.c_int32),
         ("seed", C.c_uint64),
     ]
 
 
 def hparams(beta1=0.9, beta2=0.999, eps=1e-8, bias_correction=True, outer_lr=1.0, outer_momentum=0.0,
             outer_nesterov=False, power_iters=2, orth_passes=2, grad_dtype=BF16, qhm_mode=0, omega=1.0,
-            error_feedback=False, uplink_buffer=False, rayleigh_ritz=False, seed=0) -> HParams:
+            error_feedback=False, uplink_buffer=False, rayleigh_ritz=False, seed=0, param_dtype=F32) -> HParams:
     return HParams(beta1, beta2, eps, int(bias_correction), qhm_mode, omega, int(error_feedback),
                    int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, int(uplink_buffer),
-                   int(rayleigh_ritz), 0, int(seed))
+                   int(rayleigh_ritz), int(param_dtype), int(seed))
 
 
 class LordoError(RuntimeError):
@@ -151,7 +151,7 @@ class Lordo:
         self.shapes = [tuple(s) for s in shapes]
         self.hp = hp
         self.n = len(shapes)
-        self._check_tensors(W, torch.float32, "pq")
+        self._check_tensors(W, torch.bfloat16 if hp.param_dtype == BF16 else torch.float32, "pq")
         self.device = W[0].device
         self.ctx = C.c_void_p()
         if static_workspace:         # lordo_init_static: the workspace is the library's own fixed array, nothing is allocated
@@ -191,12 +191,15 @@ class Lordo:
             if tuple(t.shape) != want or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
                 raise ValueError(f"expected contiguous CUDA {dtype} tensor of shape {want}, got {t.dtype} {tuple(t.shape)}")
 
+    def _w_dtype(self):
+        return self.torch.bfloat16 if self.hp.param_dtype == BF16 else self.torch.float32
+
     def _grad_dtype(self):
         return self.torch.bfloat16 if self.hp.grad_dtype == BF16 else self.torch.float32
 
     # -- the four calls -----------------------------------------------------------------------
     def local_step(self, W, G, lr, grad_scale=1.0):
-        self._check_tensors(W, self.torch.float32, "pq")
+        self._check_tensors(W, self._w_dtype(), "pq")
         self._check_tensors(G, self._grad_dtype(), "pq")
         _check(self.lib.lordo_local_step(self.ctx, _ptr_array(W), _ptr_array(G), float(lr), float(grad_scale), self._stream()))
 
@@ -246,12 +249,12 @@ class Lordo:
                                                      None if Omega is None else _ptr_array(Omega), self._stream()))
 
     def export_pseudograd(self, W, out):
-        self._check_tensors(W, self.torch.float32, "pq")
+        self._check_tensors(W, self._w_dtype(), "pq")
         self._check_tensors(out, self.torch.float32, "pq")
         _check(self.lib.lordo_export_pseudograd(self.ctx, _ptr_array(W), _ptr_array(out), self._stream()))
 
     def outer_step(self, W, avg_delta=None):
-        self._check_tensors(W, self.torch.float32, "pq")
+        self._check_tensors(W, self._w_dtype(), "pq")
         if avg_delta is not None:
             self._check_tensors(avg_delta, self.torch.float32, "pq")
             _check(self.lib.lordo_outer_step(self.ctx, _ptr_array(W), _ptr_array(avg_delta), self._stream()))
@@ -265,7 +268,7 @@ class Lordo:
 
     def outer_step_lowrank(self, W, avg_acc=None):
         """Outer step with Delta = Q avg_acc (avg_acc: mean of the workers' exported buffers; None: own buffer)."""
-        self._check_tensors(W, self.torch.float32, "pq")
+        self._check_tensors(W, self._w_dtype(), "pq")
         if avg_acc is not None:
             self._check_tensors(avg_acc, self.torch.float32, "rq")
             _check(self.lib.lordo_outer_step_lowrank(self.ctx, _ptr_array(W), _ptr_array(avg_acc), self._stream()))

@@ -752,3 +752,51 @@ def test_gaussian_block_is_box_muller_of_the_philox_words_and_standard_normal():
     # columns are uncorrelated: the Gram matrix of the block is n_rows * I up to sampling noise
     Gm = big.T @ big / 2000
     assert np.linalg.norm(Gm - np.eye(256), 2) < 2.5 * (np.sqrt(256 / 2000) * 2 + 256 / 2000)
+
+
+# ---------------------------------------------------------------------------
+# bf16 storage of the weights
+# ---------------------------------------------------------------------------
+def test_round_to_bf16_is_round_to_nearest_even_once():
+    """Against an independent route: for float32-representable inputs the bit-level rounding of the input generator
+    (add 0x7FFF + lsb, shift) is the same rounding; plus hand-made ties, the error bound, idempotence, and a
+    double-rounding trap (float64 -> float32 -> bf16 would go the other way)."""
+    rng = rng_of(70)
+    x32 = (rng.standard_normal(20000) * 10.0 ** rng.uniform(-6, 3, 20000)).astype(np.float32)
+    assert np.array_equal(orc.round_to_bf16(x32.astype(np.float64)), synth.bf16_round(x32).astype(np.float64))
+    # ties go to the even neighbour: spacing at 1.0 is 2^-7
+    assert orc.round_to_bf16(np.array([1 + 2.0 ** -8]))[0] == 1.0
+    assert orc.round_to_bf16(np.array([1 + 3 * 2.0 ** -8]))[0] == 1 + 2.0 ** -6
+    assert orc.round_to_bf16(np.array([-(1 + 2.0 ** -8)]))[0] == -1.0
+    assert orc.round_to_bf16(np.array([0.0, 2.0 ** -20, -0.375]))[1] == 2.0 ** -20
+    # just above a tie in float64, but a tie after a first rounding to float32: one rounding decides correctly
+    x = 1 + 2.0 ** -8 + 2.0 ** -40
+    assert np.float32(x) == np.float32(1 + 2.0 ** -8) and orc.round_to_bf16(np.array([x]))[0] == 1 + 2.0 ** -7
+    y = rng.standard_normal(5000) * 10.0 ** rng.uniform(-5, 5, 5000)
+    r = orc.round_to_bf16(y)
+    ulp = 2.0 ** (np.floor(np.log2(np.abs(y))) - 7)
+    assert np.all(np.abs(r - y) <= 0.5 * ulp) and np.array_equal(orc.round_to_bf16(r), r)
+
+
+def test_bf16_weight_steps_are_the_full_precision_steps_rounded_once():
+    """The local and the outer step for bf16-stored weights equal the float64 step from the same stored value, rounded
+    once (Alg. 1 update lines; OuterOpt); the low-rank state does not depend on the weights at all."""
+    rng = rng_of(71)
+    p, q, r = 24, 18, 5
+    W0 = orc.round_to_bf16(0.02 * rng.standard_normal((p, q)))
+    Q = synth.orthonormal(rng, p, r)
+    hp = orc.Hyper(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True)
+    a, b = orc.init_state(W0, r, Q), orc.init_state(W0, r, Q)
+    Wa, Wb = W0.copy(), W0.copy()
+    for t in range(4):
+        G = rng.standard_normal((p, q)) * 1e-2
+        full = orc.local_step(b, Wa, G, 1e-2, hp)                  # from the STORED value of the other chain
+        Wa = orc.local_step_bf16_weights(a, Wa, G, 1e-2, hp)
+        assert np.array_equal(Wa, orc.round_to_bf16(full))
+        assert np.array_equal(a.u, b.u) and np.array_equal(a.v, b.v) and np.array_equal(a.last_N, b.last_N)
+    D = orc.pseudo_gradient(a, Wa)
+    b.anchor, b.b = a.anchor.copy(), a.b.copy()
+    full = orc.outer_step(b, D, hp)
+    Wn = orc.outer_step_bf16_weights(a, D, hp)
+    assert np.array_equal(Wn, orc.round_to_bf16(full)) and np.array_equal(a.anchor, Wn)
+    assert np.array_equal(a.b, b.b)
