@@ -283,7 +283,7 @@ class Workload:
             lib_shapes = shapes
         self.shapes = shapes
         self.opt = opt = lordo.Lordo(lib_shapes, hp, W, torch)
-        self.Wp = opt.ptrs(W)
+        self.Wp = opt.ptrs(W, torch.bfloat16 if w_bf16 else torch.float32)
         self.Gp = [opt.ptrs(g, grad_dtype) for g in G]
         self.Dp = opt.ptrs(D)
         self.Op = opt.ptrs(Omega, torch.float32, "qr")
