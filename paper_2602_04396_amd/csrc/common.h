@@ -204,7 +204,7 @@ hipError_t launch_lr_to_plain(const DevCtx& d, int mat, const float* lr_arr, con
 hipError_t launch_plain_to_lr(const DevCtx& d, int mat, float* lr_arr, const float* src, hipStream_t s);
 hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hipStream_t s);
 // right-projected matrices only: slice 0 of the blocked array g <- scale * (plain rows x r block in zw[0])
-hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, hipStream_t s);
+hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, bool all, hipStream_t s);
 // Gaussian block of every matrix from the counter-based generator: which = 0 into y[0] (p x r), 1 into zw[3] (q x r)
 hipError_t launch_gauss_block(const DevCtx& d, int which, uint64_t seed, uint32_t draw, hipStream_t s);
 

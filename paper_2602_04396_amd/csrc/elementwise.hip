@@ -1459,10 +1459,10 @@ hipError_t launch_lr_exchange(const DevCtx& d, float* lr_arr, bool to_plain, hip
 // Right-projected matrices (m.tr): their down-projection leaves g^T as the plain q x r block zw[0] (q = rows of the caller's
 // matrix); the Adam kernel reads slice 0 of the blocked array g.  `scale` is the caller's gradient scale where the product
 // was formed from the raw gradient.
-__global__ __launch_bounds__(256) void k_tr_exchange(DevCtx d, float* glow, float scale) {
+__global__ __launch_bounds__(256) void k_tr_exchange(DevCtx d, float* glow, float scale, int all) {
   const int mat = blockIdx.y;
   const MatDev& m = d.mats[mat];
-  if (!m.tr) return;
+  if (!m.tr && !all) return;      // all: the product of every matrix was formed as a plain block (fp32 gradients)
   const float* plain = reinterpret_cast<const float*>(d.arena + m.zw[0]);
   // in the order of the blocked array (contiguous writes; the reads are 32-byte pieces of rows that neighbouring threads
   // complete); padded columns and ranks are written as zeros
@@ -1523,8 +1523,8 @@ hipError_t launch_gauss_block(const DevCtx& d, int which, uint64_t seed, uint32_
   return hipGetLastError();
 }
 
-hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, hipStream_t s) {
-  hipLaunchKernelGGL(k_tr_exchange, dim3(64, d.n), dim3(256), 0, s, d, glow, scale);
+hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, bool all, hipStream_t s) {
+  hipLaunchKernelGGL(k_tr_exchange, dim3(64, d.n), dim3(256), 0, s, d, glow, scale, all ? 1 : 0);
   return hipGetLastError();
 }
 

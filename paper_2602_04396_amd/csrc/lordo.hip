@@ -77,6 +77,7 @@ struct Plan {
   std::vector<Op> init_ops;         // Q_0 from a caller-supplied block: copy, orthonormalise, pack
   std::vector<Op> gap_ops;          // estimate of sigma_{r+1} of a source (Rayleigh-Ritz option)
   bool any_tr = false;              // some matrix is projected on the right
+  bool down_generic = false;        // fp32 gradients: the down-projection of EVERY matrix runs in the grouped GEMM (three-term operands)
   std::vector<Op> tr_down_ops;      // their product g^T = G Q by the generic GEMM (fp32 gradients, shapes the streaming kernel does not take)
   // Right-projected matrices in the kernels of the left projection: the products of the step are those of the caller's
   // p x q matrix with the operand planes in exchanged roles (see build_plan), described by two shadow tables of MatDev.
@@ -418,13 +419,22 @@ struct ProgramBuilder {
   // Down-projection of the right-projected matrices (Sec. 2 with the roles of rows and columns exchanged) on the
   // caller's row-major arrays by the generic GEMM: g^T = (s G) Q into zw[0]; the scale s multiplies the launch (it
   // changes per call).  Taken for fp32 gradients and for shapes or pointers the streaming kernel does not read.
-  void build_tr_step(bool g_bf16, bool ef) {
+  void build_tr_step(bool g_bf16, bool ef, bool all_mats) {
+    // g^T (columns of the low-rank state x r, plain, into zw[0]) = (caller's matrix, read in the orientation of the
+    // matrix's problem) x Q.  Right-projected matrix: rows of the caller's array are the columns of the state,
+    // element (row i, column j) at i * m.p + j.  Left-projected matrix (all_mats: fp32 gradients, whose products run
+    // here with three-term operands, as exact as fp32): the columns of the caller's array are the columns of the
+    // state, element (row i, column j) at i * m.q + j, contracted over the rows.
+    auto a_strides = [](GemmDesc& g, const MatDev& m) {
+      if (m.tr) { g.sAm = m.p; g.sAk = 1; }
+      else { g.sAm = 1; g.sAk = m.q; }
+    };
     std::vector<Op> keep;
     keep.swap(P.ops);
     gemm([&](int i, GemmDesc& g) {
       const MatDev& m = P.mat[i];
-      if (!m.tr) return false;
-      g.A = ref_ext(EXT_G); g.sAm = m.p; g.sAk = 1; g.a_bf16 = g_bf16 ? 1 : 0;
+      if (!m.tr && !all_mats) return false;
+      g.A = ref_ext(EXT_G); a_strides(g, m); g.a_bf16 = g_bf16 ? 1 : 0;
       g.B = ref_arena(m.q32); g.sBk = m.r; g.sBn = 1;
       g.C = ref_arena(m.zw[0]); g.ldc = m.r;
       g.M = m.q; g.N = m.r; g.K = m.p;
@@ -434,8 +444,8 @@ struct ProgramBuilder {
     if (ef) {           // source: the residual after E <- s G + E (fp32, in the arena, the caller's layout)
       gemm([&](int i, GemmDesc& g) {
         const MatDev& m = P.mat[i];
-        if (!m.tr) return false;
-        g.A = ref_arena(m.err); g.sAm = m.p; g.sAk = 1;
+        if (!m.tr && !all_mats) return false;
+        g.A = ref_arena(m.err); a_strides(g, m);
         g.B = ref_arena(m.q32); g.sBk = m.r; g.sBn = 1;
         g.C = ref_arena(m.zw[0]); g.ldc = m.r;
         g.M = m.q; g.N = m.r; g.K = m.p;
@@ -620,7 +630,8 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   if (hp.rayleigh_ritz) { P.frob_part = A.take(sizeof(float) * (size_t)chunks); P.jflags = A.take(256); }
   // rank blocks of 32 per down-projection tile: the pipelined kernel (bf16 G) always takes four and
   // leaves the waves of absent blocks idle; the plain kernel is instantiated for 1, 2 and 4
-  P.mb = (hp.grad_dtype == LORDO_BF16 || rp_max > 64) ? 4 : (rp_max > 32 ? 2 : 1);
+  P.down_generic = hp.grad_dtype == LORDO_F32;
+  P.mb = 4;
   // Down-projection launch shape: the pipelined kernel (rank tiles of 128, bf16 G, 256-column
   // tiles) where it applies, else the plain kernel with 128-column tiles.
   P.down_pipe = (P.mb == 4 && hp.grad_dtype == LORDO_BF16) ? (rp_max >= 256 ? 2 : 1) : 0;
@@ -638,7 +649,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     if (!P.mat[i].tr) tiles0 += (int64_t)((P.mat[i].qp + down_bn - 1) / down_bn) * ((P.mat[i].rp + P.rank_tile - 1) / P.rank_tile);
   P.splits.assign(n, 1);
   P.nsplit = 1;
-  if (tiles0 > 0 && tiles0 < 1536) {
+  if (tiles0 > 0 && tiles0 < 1536 && !P.down_generic) {
     // slices of about the shortest matrix's height; halved while the launch would still have fewer
     // than about 1.5 workgroups per compute unit (a single tall matrix, for instance)
     int chunk = std::max(256, pp_min);
@@ -782,7 +793,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     if (m.tr) continue;               // no tiles of the projection kernels
     const int f = P.splits[i];
     const int klen = ((m.pp + f - 1) / f + 31) / 32 * 32;
-    for (int n0 = 0; n0 < m.qp; n0 += down_bn)
+    for (int n0 = 0; n0 < (P.down_generic ? 0 : m.qp); n0 += down_bn)
       for (int m0 = 0; m0 < m.rp; m0 += P.rank_tile)
         for (int sp = 0; sp < f; ++sp) {
           ProjTile t{};
@@ -862,7 +873,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   pb.build(hp.power_iters, hp.orth_passes == 0 ? 2 : hp.orth_passes, hp.rayleigh_ritz != 0);
   if (hp.rayleigh_ritz) pb.build_gap(2, hp.orth_passes == 0 ? 2 : hp.orth_passes);
   pb.build_init(hp.orth_passes == 0 ? 2 : hp.orth_passes);
-  if (P.any_tr) pb.build_tr_step(hp.grad_dtype == LORDO_BF16, hp.error_feedback != 0);
+  if (P.any_tr || P.down_generic) pb.build_tr_step(hp.grad_dtype == LORDO_BF16, hp.error_feedback != 0, P.down_generic);
   P.descs = A.take(sizeof(GemmDesc) * P.desc_h.size());
   P.gtiles = A.take(sizeof(GemmTile) * P.gtile_h.size());
   P.bytes = A.cur;
@@ -1119,7 +1130,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   // after lordo_refresh_subspace_local the error buffer already holds grad_scale * G + E of this step
   const bool folded = c->grad_folded;
   if (folded && std::memcmp(c->folded_g.data(), G, sizeof(void*) * c->n) != 0) return LORDO_ESTATE;
-  const double proj_scale = folded ? 0.0 : grad_scale;
+  // fp32 gradients with error feedback: the sum s G + E of every matrix is formed in the residual buffer before the
+  // product (as it is for right-projected matrices), so the residual update adds no gradient term of its own
+  const bool generic = P.down_generic;
+  const double proj_scale = (folded || (generic && c->hp.error_feedback)) ? 0.0 : grad_scale;
   const int64_t t = c->t + 1;
   double c1 = 1.0, c2 = 1.0;
   if (c->hp.bias_correction) {
@@ -1174,11 +1188,11 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (!P.down_h.empty())
     HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, g_tr, P.g_once, c->at<float>(P.glow),
                             P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
-  if (P.any_tr) {               // g^T = (s G) Q into the plain block zw[0], then into the blocked array the Adam kernel reads
-    bool stream = P.tr_stream_shapes && !ef;
+  if (P.any_tr || generic) {    // g^T = (s G) Q into the plain block zw[0], then into the blocked array the Adam kernel reads
+    bool stream = P.tr_stream_shapes && !ef && !generic;
     if (ef) {                   // A = s G + E is formed in the residual buffer first (unless a refresh of the local variant has done it)
       if (!folded)
-        HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)grad_scale, g_f32, s, true));
+        HIPCHK(launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)grad_scale, g_f32, s, !generic));
       for (const Op& op : P.tr_down_ef_ops)
         HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, 1.f));
     }
@@ -1195,7 +1209,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
       for (const Op& op : P.tr_down_ops)
         HIPCHK(launch_gemm32(c->dev, c->at<GemmDesc>(P.descs), c->at<GemmTile>(P.gtiles) + op.tile_first, op.ntiles, op.tile, 0, s, (float)grad_scale));
     }
-    HIPCHK(launch_tr_exchange(c->dev, c->at<float>(P.glow), stream ? (float)grad_scale : 1.f, s));
+    HIPCHK(launch_tr_exchange(c->dev, c->at<float>(P.glow), stream ? (float)grad_scale : 1.f, generic, s));
   }
   c->prof.end(LORDO_K_DOWN, s);
   c->prof.begin(LORDO_K_ADAM, s);
