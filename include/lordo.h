@@ -74,11 +74,11 @@ typedef struct lordo_ctx lordo_ctx;
  *           runs it as exactly that on the caller's row-major p x q arrays (W, G, Src, Delta keep their layout):
  *           every low-rank array of such a matrix is the one of the TRANSPOSED problem, i.e. Q is q x r, the r x q
  *           states (u, v, g, N) are r x p, Omega is p x r and the block of lordo_init_projection q x r.
- *           1 <= r <= q.  Built for the update cases "No QHM" and "Low-Rank QHM", with or without error feedback
- *           (then: columns a multiple of 4, 16-byte aligned W) and the up-link buffer; not for "Full-Rank QHM"
- *           (LORDO_EINVAL); its two products of the local step and the products of a
- *           refresh with the source run in the library's generic grouped GEMM, also for the left-projected matrices
- *           of the same context in the refresh. */
+ *           1 <= r <= q.  Every update case; in the "Full-Rank QHM" case the scale of the gradient term runs over the
+ *           rows of W, s_i = mean over the rank of sqrt(v^_ik) + eps (the columns of the transposed problem).  With
+ *           error feedback or full-rank QHM: columns a multiple of 4, 16-byte aligned W.  The products of a refresh
+ *           with the source run in the library's generic grouped GEMM, also for the left-projected matrices of the
+ *           same context. */
 typedef struct {
   int64_t rows;
   int64_t cols;

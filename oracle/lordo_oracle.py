@@ -200,8 +200,9 @@ def local_step_right(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, h
     """One local step with the projection on the right, written out on the p x q arrays:
     g = G_hat Q (p x r), Adam moments on g, W <- W - lr N Q^T, with Q of size q x r.  This is Sec. 2's update
     of the transposed matrix; `st` is the state of that transposed problem (Q: q x r; u, v, last_g, last_N: r x p,
-    i.e. the transposes of the p x r arrays of this function; E: q x p).  Cases "No QHM" and "Low-Rank QHM" only."""
-    assert hp.qhm_mode != "full"
+    i.e. the transposes of the p x r arrays of this function; E: q x p).  In the "Full-Rank QHM" case (Sec. 3.2) the
+    scale mu(.) of the gradient term, a mean over the rank index, belongs to the ROWS of W here: one value per row i,
+    s_i = mean_k (sqrt(v_hat_ik) + eps), and the term is diag(1 / s) G_hat."""
     W = np.asarray(W, dtype=F64)
     G_hat = grad_scale * np.asarray(G, dtype=F64)
     st.t += 1
@@ -214,7 +215,12 @@ def local_step_right(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, h
     st.u, st.v = u.T, v.T
     st.last_g, st.last_N = g.T, N.T
     if hp.uplink_buffer:                               # App. A.5.1, in the layout of the transposed problem (r x p)
+        assert hp.qhm_mode != "full", "the full-rank QHM update has no low-rank form (App. A.5.1)"
         st.A = st.A + lr * N.T
+    if hp.qhm_mode == "full":
+        _, c2 = bias_factors(st.t, hp)
+        row_scale = np.mean(np.sqrt(v / c2) + hp.eps, axis=1)      # mu(.) over the rank index: one value per row of W
+        return W - lr * ((1.0 - hp.omega) * (G_hat / row_scale[:, None]) + hp.omega * (N @ st.Q.T))
     return W - lr * (N @ st.Q.T)
 
 

@@ -573,9 +573,6 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
     const lordo_shape& s = shapes[i];
     if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || (s.side != 0 && s.side != 1)) return LORDO_EINVAL;
     if (s.rank > (s.side ? s.cols : s.rows)) return LORDO_EINVAL;
-    // projection on the right: not the full-rank QHM update (its column scale, fused into the up-projection kernel's
-    // epilogue, would have to become a row scale)
-    if (s.side && hp->qhm_mode == 2) return LORDO_EINVAL;
     // (tile coordinates of the grouped GEMM are 16-bit: at most 32767 tiles of 64 rows)
     if (s.rows > (1 << 20) || s.cols > (1 << 20) || s.rank > 4096) return LORDO_EINVAL;
     // the kernels address a matrix through buffer descriptors with 32-bit byte offsets: p * q * 4 bytes must stay below 4 GiB
@@ -759,6 +756,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
       MatDev up = sdw, stb = sdw;
       up.qa_hi = P.n_hi + 2 * m.lr_off; up.qa_lo = P.n_lo + 2 * m.lr_off;
       up.lr_off = m.qa_hi / 2;
+      up.qt_hi = m.lr_off;          // (unused by the up-projection otherwise) the matrix's place in the flat low-rank arrays: row scales of the full-rank QHM term
       stb.lr_off = m.qt_hi / 2;
       stb.y[0] = m.zw[0];
       P.mat_up[i] = up;
@@ -1256,8 +1254,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
       if (P.mat[i].tr && ((P.mat[i].p & 3) != 0 || (reinterpret_cast<uintptr_t>(W[i]) & w_mask) != 0)) w_vec_tr = false;
     DevCtx du = c->dev;
     du.mats = c->at<MatDev>(P.mats_up);
+    UpArgs ut = ua;
+    if (qhm_full) ut.colscale = 2;      // the scale of the gradient term runs over the rows of W: the columns of the low-rank state
     HIPCHK(launch_proj_up(du, c->at<ProjTile>(P.up_tr_tiles), (int)P.up_tr_h.size(), w_vec_tr, reinterpret_cast<uint16_t*>(c->dev.arena),
-                          reinterpret_cast<uint16_t*>(c->dev.arena + P.tr_plane_gap), ua, s));
+                          reinterpret_cast<uint16_t*>(c->dev.arena + P.tr_plane_gap), ut, s));
   }
   c->prof.end(LORDO_K_UP, s);
   c->t = t;

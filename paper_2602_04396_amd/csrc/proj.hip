@@ -1074,7 +1074,7 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
   if (mb0 >= mblocks || nb0 >= nblocks) return;
   f32x4 cscale = {1.f, 1.f, 1.f, 1.f};
   if constexpr (WITH_G) {
-    if (ua.colscale && nb0 + bsel < nblocks) {
+    if (ua.colscale == 1 && nb0 + bsel < nblocks) {
       const GAS float* cp = TO_GLOBAL(const float, ua.colpart) + m.lr_off / 32;
       const int rblocks = m.rp / 32;
       const float pad = (float)(m.rp - m.r) * ua.eps;          // padded rank indices hold v = 0: eps each
@@ -1098,6 +1098,23 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     }
     return gv * cscale * ua.coef_g;
   };
+  // colscale == 2: the scale belongs to the ROWS of this tile -- a right-projected matrix, whose low-rank state has one
+  // column per row of W (Sec. 3.2 on the transposed problem): 1 / mean over the rank of sqrt(v_hat) + eps of that row.
+  // The shadow record of such a matrix keeps the matrix's place in the flat low-rank arrays in `qt_hi`.
+  auto row_scales = [&](int a, float (&rs)[8]) {
+    const GAS float* cp = TO_GLOBAL(const float, ua.colpart) + m.qt_hi / 32;
+    const int rblocks = m.rp / 32;
+    const float pad = (float)(m.rp - m.r) * ua.eps;
+    const float inv_r = 1.f / (float)m.r;
+    const int cb = mb0 + a < mblocks ? mb0 + a : mblocks - 1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float sum = 0.f;
+      for (int rb = 0; rb < rblocks; ++rb) sum += cp[((int64_t)cb * rblocks + rb) * 32 + rr + 4 * j];      // fixed order
+      const float den = (sum - pad) * inv_r;
+      rs[j] = den > 0.f ? 1.f / den : 0.f;                      // (rows of the padding: nothing is stored there)
+    }
+  };
   // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e of its block; both
   // column blocks of a row block go into one 32 x 64 staging tile
   float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
@@ -1116,6 +1133,12 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     if constexpr (WITH_G) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) gt[j] = g_term(a, j);
+      if (ua.colscale == 2) {
+        float rs[8];
+        row_scales(a, rs);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) gt[j] *= rs[j];
+      }
     }
     u32x4 mv[8];
     if constexpr (OUTER) {

@@ -75,14 +75,15 @@ def test_right_projection_validation(lib):
     assert lordo.workspace_bytes([(32, 64, 33, 1)], hp) > 0        # ... and not by the rows
     with pytest.raises(lordo.LordoError):
         lordo.workspace_bytes([(64, 32, 8, 2)], hp)
-    # built for the plain and the low-rank QHM update
+    # every update case, error feedback and the up-link buffer (the last not with full-rank QHM, as on the left)
     assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(qhm_mode=1, omega=0.9)) > 0
     assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(uplink_buffer=True)) > 0
     assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(error_feedback=True)) > 0
-    for bad in (lordo.hparams(qhm_mode=2, omega=0.9), lordo.hparams(qhm_mode=2, omega=0.9, error_feedback=True)):
-        with pytest.raises(lordo.LordoError) as e:
-            lordo.workspace_bytes([(64, 32, 8, 1)], bad)
-        assert e.value.code == lordo.EINVAL
+    assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(qhm_mode=2, omega=0.9)) > 0
+    assert lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(qhm_mode=2, omega=0.9, error_feedback=True)) > 0
+    with pytest.raises(lordo.LordoError) as e:
+        lordo.workspace_bytes([(64, 32, 8, 1)], lordo.hparams(qhm_mode=2, omega=0.9, uplink_buffer=True))
+    assert e.value.code == lordo.EINVAL
 
 
 def test_strerror_and_null_handling(lib):

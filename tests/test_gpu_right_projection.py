@@ -26,27 +26,26 @@ SHAPE_SETS = {
 
 
 @pytest.mark.parametrize("bf16", [True, False], ids=["bf16", "fp32"])
-@pytest.mark.parametrize("qhm", ["none", "low", "low_ef"])
+@pytest.mark.parametrize("qhm", ["none", "low", "low_ef", "full", "full_ef"])
 @pytest.mark.parametrize("name", list(SHAPE_SETS))
 def test_right_projection_steps_refresh_outer(name, qhm, bf16):
     import torch
     from paper_2602_04396_amd import lordo
     shapes = SHAPE_SETS[name]
-    ef = qhm == "low_ef"                 # error feedback (Alg. 1): the residual of a right-projected matrix, E <- s G + E - g Q^T
-    if ef:
-        qhm = "low"
+    ef = qhm.endswith("_ef")             # error feedback (Alg. 1): the residual of a right-projected matrix, E <- s G + E - g Q^T
+    qhm = qhm.split("_")[0]              # full: Sec. 3.2 on the transposed problem, the gradient term scaled per row of W
     n = len(shapes)
-    omega = 0.8 if qhm == "low" else 1.0
+    omega = 0.8 if qhm != "none" else 1.0
     common = dict(omega=omega, outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=1, error_feedback=ef)
     ohp = orc.Hyper(qhm_mode=qhm, **common)
-    ghp = lordo.hparams(qhm_mode={"none": 0, "low": 1}[qhm], grad_dtype=lordo.BF16 if bf16 else lordo.F32, **common)
+    ghp = lordo.hparams(qhm_mode={"none": 0, "low": 1, "full": 2}[qhm], grad_dtype=lordo.BF16 if bf16 else lordo.F32, **common)
     W0 = [synth.weights(np.random.default_rng(synth.seed_for(80, i)), sh[0], sh[1]) for i, sh in enumerate(shapes)]
     Q0 = [synth.orthonormal(np.random.default_rng(synth.seed_for(81, i)), lowrank_dims(sh)[0], sh[2]).astype(np.float32)
           for i, sh in enumerate(shapes)]
     pair = Pair(torch, shapes, W0, ohp, ghp, Q0)
     gens = [synth.SpikedGradient(sh[0], sh[1], 4, synth.seed_for(82, i), bf16=bf16) for i, sh in enumerate(shapes)]
-    if ef and name == "mixed":
-        # the residual update of the up-projection kernel needs rows of W of a multiple of 4 floats: 130 columns are refused
+    if (ef or qhm == "full") and name == "mixed":
+        # the gradient-term epilogue of the up-projection kernel needs rows of W of a multiple of 4 floats: 130 columns are refused
         W_before = [w.clone() for w in pair.W_gpu]
         with pytest.raises(lordo.LordoError) as e:
             pair.opt.local_step(pair.W_gpu, pair.to_dev([g.draw(0) for g in gens], bf16), 1e-3)

@@ -668,15 +668,15 @@ def test_comm_ratios_golden():
 # ---------------------------------------------------------------------------------------------
 # projection on the right (Sec. 2 applied to the transposed matrix)
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("qhm", ["none", "low", "low_ef"])
+@pytest.mark.parametrize("qhm", ["none", "low", "low_ef", "full", "full_ef"])
 def test_right_projection_is_the_method_on_the_transpose(qhm):
-    """The explicit right-side formulas (g = G Q, W -= lr N Q^T) against the left-side functions run on
-    W^T, G^T: two code paths, one result, over steps and a refresh."""
+    """The explicit right-side formulas (g = G Q, W -= lr N Q^T; full-rank QHM: the gradient term scaled per ROW of W)
+    against the left-side functions run on W^T, G^T: two code paths, one result, over steps and a refresh."""
     rng = np.random.default_rng(77)
     p, q, r = 23, 11, 4
-    ef = qhm == "low_ef"
-    qhm = "low" if ef else qhm
-    hp = orc.Hyper(qhm_mode=qhm, omega=0.7 if qhm == "low" else 1.0, power_iters=1, error_feedback=ef)
+    ef = qhm.endswith("_ef")
+    qhm = qhm.split("_")[0]
+    hp = orc.Hyper(qhm_mode=qhm, omega=0.7 if qhm != "none" else 1.0, power_iters=1, error_feedback=ef)
     W = rng.standard_normal((p, q))
     Q0 = np.linalg.qr(rng.standard_normal((q, r)))[0]
     a, b = orc.init_state(W.T, r, Q0), orc.init_state(W.T, r, Q0)
