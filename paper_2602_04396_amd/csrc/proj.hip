@@ -431,50 +431,39 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   const bool fuse = t.fuse != 0 && fa.u != nullptr;            // uniform over the workgroup
   const int64_t rgroups = m.rp / 8;
   const float osc = EF ? 1.f : grad_scale;                     // with error feedback the scale went into the staged sum
+  // accumulator block idx = 4 rb + a: rank block mbg[rb], column block t.n0 / 32 + 4 nh + a
+  auto live = [&](int idx) { return active[idx >> 2] && t.n0 / 32 + 4 * nh + (idx & 3) < m.qp / 32; };
+  // offset of the lane's four consecutive rank indices of that block's column block, rank group 4*mbg + vq
+  auto offset_of = [&](int idx, int vq) {
+    const int nbg = t.n0 / 32 + 4 * nh + (idx & 3);
+    return (((int64_t)nbg * rgroups + 4 * mbg[idx >> 2] + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+  };
+  // fused Adam: the moments of the next block are requested before this one is worked on
+  f32x4 uu[2][4], vv[2][4];
+  auto fetch = [&](int idx, int buf) {
+    if (!live(idx)) return;
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    if (!active[rb]) continue;
-    // offset of the lane's four consecutive rank indices of column block nbg, rank group 4*mbg + vq
-    auto offset_of = [&](int nbg, int vq) {
-      return (((int64_t)nbg * rgroups + 4 * mbg[rb] + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
-    };
-    if (!fuse) {
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int nbg = t.n0 / 32 + 4 * nh + a;
-        if (nbg >= m.qp / 32) continue;
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          f32x4 val;
-          val.x = osc * acc[rb][a][4 * vq];     val.y = osc * acc[rb][a][4 * vq + 1];
-          val.z = osc * acc[rb][a][4 * vq + 2]; val.w = osc * acc[rb][a][4 * vq + 3];
-          *reinterpret_cast<GAS f32x4*>(out + offset_of(nbg, vq)) = val;
-        }
-      }
-      continue;
+    for (int vq = 0; vq < 4; ++vq) {
+      const int64_t at = base + offset_of(idx, vq);
+      uu[buf][vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.u + at));
+      vv[buf][vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
     }
-    // fused Adam: the moments of a whole column block are requested before any of them is used
+  };
+  if (fuse) fetch(0, 0);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int nbg = t.n0 / 32 + 4 * nh + a;
-      if (nbg >= m.qp / 32) continue;
-      f32x4 uu[4], vv[4];
+  for (int idx = 0; idx < 4 * RB; ++idx) {
+    if (fuse && idx + 1 < 4 * RB) fetch(idx + 1, (idx + 1) & 1);
+    ISSUE_FENCE();
+    if (!live(idx)) continue;
+    const int rb = idx >> 2, a = idx & 3;
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int64_t at = base + offset_of(nbg, vq);
-        uu[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.u + at));
-        vv[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
-      }
-      ISSUE_FENCE();
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int64_t o = offset_of(nbg, vq);
-        f32x4 val;
-        val.x = osc * acc[rb][a][4 * vq];     val.y = osc * acc[rb][a][4 * vq + 1];
-        val.z = osc * acc[rb][a][4 * vq + 2]; val.w = osc * acc[rb][a][4 * vq + 3];
-        *reinterpret_cast<GAS f32x4*>(out + o) = val;
-        adam4(fa, base + o, val, uu[vq], vv[vq]);
-      }
+    for (int vq = 0; vq < 4; ++vq) {
+      const int64_t o = offset_of(idx, vq);
+      f32x4 val;
+      val.x = osc * acc[rb][a][4 * vq];     val.y = osc * acc[rb][a][4 * vq + 1];
+      val.z = osc * acc[rb][a][4 * vq + 2]; val.w = osc * acc[rb][a][4 * vq + 3];
+      *reinterpret_cast<GAS f32x4*>(out + o) = val;
+      if (fuse) adam4(fa, base + o, val, uu[idx & 1][vq], vv[idx & 1][vq]);
     }
   }
 }
@@ -642,35 +631,40 @@ __global__ __launch_bounds__(512) void k_proj_down_tr(DevCtx d, const ProjTile* 
   GAS float* out = TO_GLOBAL(float, glow) + (int64_t)t.split * split_stride + base;
   const bool fuse = t.fuse != 0 && fa.u != nullptr;
   const int64_t rgroups = m.rp / 8;
+  // accumulator block idx = 4 rb + a: rank block mbg[rb], column block t.n0 / 32 + 4 nh + a
+  auto live = [&](int idx) { return active[idx >> 2] && t.n0 / 32 + 4 * nh + (idx & 3) < m.qp / 32; };
+  auto offset_of = [&](int idx, int vq) {
+    const int nbg = t.n0 / 32 + 4 * nh + (idx & 3);
+    return (((int64_t)nbg * rgroups + 4 * mbg[idx >> 2] + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
+  };
+  // fused Adam: the moments of the NEXT block are requested before this one is worked on, so that the epilogue of a
+  // tile exposes one memory latency and not one per block (this workgroup has the compute unit to itself: nothing
+  // else runs while it waits)
+  f32x4 uu[2][4], vv[2][4];
+  auto fetch = [&](int idx, int buf) {
+    if (!live(idx)) return;
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    if (!active[rb]) continue;
-    auto offset_of = [&](int nbg, int vq) {
-      return (((int64_t)nbg * rgroups + 4 * mbg[rb] + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
-    };
+    for (int vq = 0; vq < 4; ++vq) {
+      const int64_t at = base + offset_of(idx, vq);
+      uu[buf][vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.u + at));
+      vv[buf][vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
+    }
+  };
+  if (fuse) fetch(0, 0);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int nbg = t.n0 / 32 + 4 * nh + a;
-      if (nbg >= m.qp / 32) continue;
-      f32x4 uu[4], vv[4];
-      if (fuse) {
+  for (int idx = 0; idx < 4 * RB; ++idx) {
+    if (fuse && idx + 1 < 4 * RB) fetch(idx + 1, (idx + 1) & 1);
+    ISSUE_FENCE();
+    if (!live(idx)) continue;
+    const int rb = idx >> 2, a = idx & 3;
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          const int64_t at = base + offset_of(nbg, vq);
-          uu[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.u + at));
-          vv[vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
-        }
-        ISSUE_FENCE();
-      }
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int64_t o = offset_of(nbg, vq);
-        f32x4 val;
-        val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
-        val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
-        *reinterpret_cast<GAS f32x4*>(out + o) = val;
-        if (fuse) adam4(fa, base + o, val, uu[vq], vv[vq]);
-      }
+    for (int vq = 0; vq < 4; ++vq) {
+      const int64_t o = offset_of(idx, vq);
+      f32x4 val;
+      val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
+      val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
+      *reinterpret_cast<GAS f32x4*>(out + o) = val;
+      if (fuse) adam4(fa, base + o, val, uu[idx & 1][vq], vv[idx & 1][vq]);
     }
   }
 }
