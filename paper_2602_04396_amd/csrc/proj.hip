@@ -438,8 +438,25 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
     const int nbg = t.n0 / 32 + 4 * nh + (idx & 3);
     return (((int64_t)nbg * rgroups + 4 * mbg[idx >> 2] + vq) * 32 + (lane & 31)) * 8 + 4 * (lane >> 5);
   };
-  // fused Adam: the moments of the next block are requested before this one is worked on
-  f32x4 uu[2][4], vv[2][4];
+  if (!fuse) {
+#pragma unroll
+    for (int idx = 0; idx < 4 * RB; ++idx) {
+      if (!live(idx)) continue;
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        f32x4 val;
+        val.x = osc * acc[idx >> 2][idx & 3][4 * vq];     val.y = osc * acc[idx >> 2][idx & 3][4 * vq + 1];
+        val.z = osc * acc[idx >> 2][idx & 3][4 * vq + 2]; val.w = osc * acc[idx >> 2][idx & 3][4 * vq + 3];
+        *reinterpret_cast<GAS f32x4*>(out + offset_of(idx, vq)) = val;
+      }
+    }
+    return;
+  }
+  // fused Adam.  With 256-rank tiles (one workgroup per compute unit, nothing else to run while it waits) the moments of
+  // the next block are requested before this one is worked on; the 128-rank tile has no registers to spare for that
+  // without giving up its second workgroup per compute unit
+  constexpr int PF = RB == 2 ? 1 : 0;
+  f32x4 uu[1 + PF][4], vv[1 + PF][4];
   auto fetch = [&](int idx, int buf) {
     if (!live(idx)) return;
 #pragma unroll
@@ -449,10 +466,11 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
       vv[buf][vq] = __builtin_nontemporal_load(TO_GLOBAL(const f32x4, fa.v + at));
     }
   };
-  if (fuse) fetch(0, 0);
+  if (PF) fetch(0, 0);
 #pragma unroll
   for (int idx = 0; idx < 4 * RB; ++idx) {
-    if (fuse && idx + 1 < 4 * RB) fetch(idx + 1, (idx + 1) & 1);
+    if (!PF) fetch(idx, 0);
+    else if (idx + 1 < 4 * RB) fetch(idx + 1, (idx + 1) & 1);
     ISSUE_FENCE();
     if (!live(idx)) continue;
     const int rb = idx >> 2, a = idx & 3;
@@ -463,7 +481,7 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
       val.x = osc * acc[rb][a][4 * vq];     val.y = osc * acc[rb][a][4 * vq + 1];
       val.z = osc * acc[rb][a][4 * vq + 2]; val.w = osc * acc[rb][a][4 * vq + 3];
       *reinterpret_cast<GAS f32x4*>(out + o) = val;
-      if (fuse) adam4(fa, base + o, val, uu[idx & 1][vq], vv[idx & 1][vq]);
+      adam4(fa, base + o, val, uu[idx & PF][vq], vv[idx & PF][vq]);
     }
   }
 }
