@@ -448,8 +448,18 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / 10
-        print(json.dumps({"calibration": "device copies of 1 GiB: 1048576 KiB read and 1048576 KiB written each",
-                          "copy_GBps": 2 * (1 << 30) / dt / 1e9}))
+        # the same memory under a read-modify-write pass (torch's in-place add: 1 GiB read, 1 GiB written), the access
+        # pattern of the weight update and of the outer step
+        for _ in range(5):
+            a.add_(1.0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            a.add_(1.0)
+        torch.cuda.synchronize()
+        dt_rmw = (time.perf_counter() - t0) / 10
+        print(json.dumps({"calibration": "device copies of 1 GiB: 1048576 KiB read and 1048576 KiB written each; then in-place adds over 1 GiB",
+                          "copy_GBps": 2 * (1 << 30) / dt / 1e9, "read_modify_write_GBps": 2 * (1 << 30) / dt_rmw / 1e9}))
         return
     lordo.load()
     cfg = args.config.lower()

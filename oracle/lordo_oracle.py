@@ -31,9 +31,9 @@ Readings of points the paper leaves open (each is stated again at its use):
   * mu(z) of the full-rank QHM term (Sec. 3.2) is the mean over the rank index,
     one scale per column.
 
-Parity pins live in tests/test_oracle_*.py.  Unpinned: nothing in the default
-path; the full-rank QHM form is pinned only by its reductions (omega = 1, and
-r = p with Q = I) -- "parity unpinned" beyond those for that optional variant.
+Parity pins live in tests/test_oracle_*.py.  Unpinned: nothing (the full-rank
+QHM form is pinned by its reductions at omega = 0 and 1 and by the formula of
+Sec. 3.2 written out with plain loops at an interior omega).
 """
 from __future__ import annotations
 

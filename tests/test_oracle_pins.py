@@ -286,6 +286,37 @@ def test_full_rank_qhm_omega_zero_is_column_scaled_sgd():
     assert rel(W1, W0 - 0.1 * G / scale[None, :]) < 1e-13
 
 
+def test_full_rank_qhm_between_the_endpoints_written_out():
+    """Sec. 3.2 at an interior omega, after several steps (so that v_hat is not g*g), written out with plain loops:
+    W_ij <- W_ij - eta [ (1 - omega) G_ij / s_j + omega (Q N)_ij ],  s_j = (1/r) sum_k (sqrt(v_hat_kj) + eps),
+    N = u_hat / (sqrt(v_hat) + eps).  The moments do not depend on omega, so they come from a plain chain run on the
+    same gradients; the update is then also the affine combination of the two endpoint updates."""
+    rng = rng_of(13)
+    p, q, r, eta, om, eps = 8, 6, 3, 0.05, 0.35, 1e-8
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    hp = orc.Hyper(qhm_mode="full", omega=om)
+    st, plain = orc.init_state(W0, r, Q), orc.init_state(W0, r, Q)
+    ends = [orc.init_state(W0, r, Q), orc.init_state(W0, r, Q)]
+    W = W0.copy()
+    for t in range(1, 4):
+        G = rng.standard_normal((p, q))
+        orc.local_step(plain, W0, G, eta, orc.Hyper())
+        W_prev = W.copy()
+        W = orc.local_step(st, W_prev, G, eta, hp)
+        u_hat = plain.u / (1 - 0.9 ** t)
+        v_hat = plain.v / (1 - 0.999 ** t)
+        expect = W_prev.copy()
+        for j in range(q):
+            s_j = sum(np.sqrt(v_hat[k, j]) + eps for k in range(r)) / r
+            for i in range(p):
+                qn = sum(Q[i, k] * u_hat[k, j] / (np.sqrt(v_hat[k, j]) + eps) for k in range(r))
+                expect[i, j] -= eta * ((1 - om) * G[i, j] / s_j + om * qn)
+        assert rel(W, expect) < 1e-13
+        W_end = [orc.local_step(ends[e], W_prev, G, eta, orc.Hyper(qhm_mode="full", omega=float(e))) for e in (0, 1)]
+        assert rel(W, (1 - om) * W_end[0] + om * W_end[1]) < 1e-13
+
+
 def test_low_rank_qhm_stays_in_span_full_rank_qhm_leaves_it():
     """App. A.4: the low-rank QHM update stays in span(Q); the full-rank one does not."""
     rng = rng_of(12)
