@@ -1281,10 +1281,6 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
 
   issue_chunk(0, 0);
   issue_chunk(1, 1);
-  typename WA::raw_t wv0[8], wv1[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) wv0[j] = WA::load(rw, voff, w_soff(0, j));
-  ISSUE_FENCE();
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -1294,35 +1290,49 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  // the first wait also has to cover the eight W loads issued after the two k-steps: vector-memory operations
-  // complete in order, so "at most 6 + 8 outstanding" means k-step 0 has landed
-  asm volatile("s_waitcnt vmcnt(14) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  int sbuf = 0;
-  for (int c = 0; c < nchunks; ++c) {
-    if (c > 0) WAIT_VM_BARRIER(6);                           // only k-step c+1 may be outstanding; all waves are done with c-1
-    issue_chunk(c + 2, sbuf == 0 ? 2 : sbuf - 1);          // into the buffer of k-step c-1
-    ISSUE_FENCE();
-    const u32x4* fb = frag + sbuf * SLOTS * 64;
-    sbuf = sbuf == 2 ? 0 : sbuf + 1;
-    u32x4 qh[4], ql[4], xh[2], xl[2];
+  // Fragments of a k-step in registers: [0..3] Q hi, [4..7] Q lo of the wave's four row blocks, [8..9] N hi, [10..11] N lo
+  // of its two column blocks.  The fragments of k-step c+1 are read from LDS while the matrix cores work on k-step c.
+  auto read_frags = [&](u32x4 (&f)[12], int s) {
+    const u32x4* fb = frag + s * SLOTS * 64;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      xh[b] = fb[(16 + (2 * wn + b) * 2 + 0) * 64 + lane];
-      xl[b] = fb[(16 + (2 * wn + b) * 2 + 1) * 64 + lane];
+      f[8 + b] = fb[(16 + (2 * wn + b) * 2 + 0) * 64 + lane];
+      f[10 + b] = fb[(16 + (2 * wn + b) * 2 + 1) * 64 + lane];
     }
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-      qh[a] = fb[((4 * wm + a) * 2 + 0) * 64 + lane];
-      ql[a] = fb[((4 * wm + a) * 2 + 1) * 64 + lane];
+      f[a] = fb[((4 * wm + a) * 2 + 0) * 64 + lane];
+      f[4 + a] = fb[((4 * wm + a) * 2 + 1) * 64 + lane];
     }
+  };
+  auto multiply = [&](const u32x4 (&f)[12]) {
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b) {      // transposed block: N fragment first
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xh[b]), as_bf(qh[a]), acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xl[b]), as_bf(qh[a]), acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(xh[b]), as_bf(ql[a]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f[8 + b]), as_bf(f[a]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f[10 + b]), as_bf(f[a]), acc[a][b], 0, 0, 0);
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(f[8 + b]), as_bf(f[4 + a]), acc[a][b], 0, 0, 0);
       }
+  };
+  // one k-step: on entry `cur` holds the fragments of k-step c; k-steps c+1 and c+2 are in flight
+  int sbuf = 0;                                              // ring buffer of k-step c
+  auto step = [&](const u32x4 (&cur)[12], u32x4 (&nxt)[12], int c) {
+    WAIT_VM_BARRIER(6);                                      // k-step c+1 has landed; every wave holds k-step c in registers
+    issue_chunk(c + 3, sbuf);                                // into the buffer of k-step c
+    sbuf = sbuf == 2 ? 0 : sbuf + 1;
+    read_frags(nxt, sbuf);
+    ISSUE_FENCE();
+    multiply(cur);
+  };
+  u32x4 fa[12], fb2[12];
+  WAIT_VM_BARRIER(6);                                        // k-step 0 has landed
+  issue_chunk(2, 2);
+  read_frags(fa, 0);
+  ISSUE_FENCE();
+  for (int c = 0; c < nchunks; c += 2) {                     // (the padded rank is a multiple of 32: an even number of k-steps)
+    step(fa, fb2, c);
+    step(fb2, fa, c + 1);
   }
   WAIT_VM_BARRIER(0);             // the repeated loads of the last k-step have landed, all waves are done reading fragments
 
@@ -1352,7 +1362,8 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
   };
   // the fragment registers are free now: two further row blocks are requested at once, the last one as soon as
   // the first has been combined, so that only one memory latency is left exposed per tile
-  typename WA::raw_t wv2[8];
+  typename WA::raw_t wv0[8], wv1[8], wv2[8];
+  fetch(0, wv0);
   fetch(1, wv1);
   fetch(2, wv2);
   ISSUE_FENCE();
