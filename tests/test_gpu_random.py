@@ -85,6 +85,59 @@ def test_random_shapes_and_options(case):
     pair.compare_local(TOL)
 
 
+def draw_high_rank_case(case):
+    rng = np.random.default_rng(9000 + case)
+    n = int(rng.integers(1, 4))
+    align = int(rng.integers(0, 3))
+    shapes = []
+    for _ in range(n):
+        p = int(rng.integers(8, 400))
+        q = int(rng.integers(8, 500))
+        if align >= 1:
+            q = max(4, q // 4 * 4)
+        if align == 2:
+            q = max(32, q // 32 * 32)
+        lim = min(p, q)
+        r = int(rng.integers(max(1, lim // 2), lim + 1))          # from half of the short side up to all of it
+        shapes.append((p, q, r))
+    bf16 = bool(rng.integers(0, 2))
+    qhm = ["none", "low", "full"][int(rng.integers(0, 3))]
+    ef = bool(rng.integers(0, 2))
+    if align == 0 and (qhm == "full" or ef):
+        qhm, ef = ("low" if qhm == "full" else qhm), False
+    return shapes, bf16, qhm, ef
+
+
+@pytest.mark.parametrize("case", list(range(8)))
+def test_random_shapes_ranks_up_to_the_short_side(case):
+    """Ranks between half of min(p, q) and min(p, q) itself (the sweeps above stay below half): local steps from a
+    given orthonormal basis in every update case, then the outer step from the window's own pseudo-gradient.  No
+    refresh here: a start block of r = min(p, q) columns times a noise-dominated source is as ill-conditioned as
+    the source, which is the orthonormalisation's documented limit, not this test's subject."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    shapes, bf16, qhm, ef = draw_high_rank_case(case)
+    omega = 0.8 if qhm != "none" else 1.0
+    common = dict(omega=omega, error_feedback=ef, outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True)
+    ohp = orc.Hyper(qhm_mode=qhm, **common)
+    ghp = lordo.hparams(qhm_mode={"none": 0, "low": 1, "full": 2}[qhm], grad_dtype=lordo.BF16 if bf16 else lordo.F32, **common)
+    print(f"high-rank case {case}: {shapes} bf16={bf16} qhm={qhm} ef={ef}", flush=True)
+    W0 = [synth.weights(np.random.default_rng(synth.seed_for(64, 100 * case + i)), p, q) for i, (p, q, r) in enumerate(shapes)]
+    Q0 = [synth.orthonormal(np.random.default_rng(synth.seed_for(65, 100 * case + i)), p, r).astype(np.float32)
+          for i, (p, q, r) in enumerate(shapes)]
+    pair = Pair(torch, shapes, W0, ohp, ghp, Q0)
+    gens = [synth.SpikedGradient(p, q, min(4, p, q), synth.seed_for(66, 100 * case + i), bf16=bf16) for i, (p, q, r) in enumerate(shapes)]
+    for t in range(3):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3 * (1 + t), grad_scale=0.9, bf16=bf16, first_step_patch=(t == 0))
+        pair.compare_local(TOL)
+    pair.opt.outer_step(pair.W_gpu, None)
+    for i in range(len(shapes)):
+        pair.W_orc[i] = orc.outer_step(pair.st[i], orc.pseudo_gradient(pair.st[i], pair.W_orc[i]), ohp)
+        got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
+        assert rel_l2(got - pair.W0[i], pair.W_orc[i] - pair.W0[i]) <= TOL, f"outer step, matrix {i}"
+    pair.opt.poll_status()
+
+
 def draw_rr_case(case):
     rng = np.random.default_rng(5000 + case)
     n = int(rng.integers(1, 5))
