@@ -692,7 +692,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the launch has several rounds of workgroups and the epilogue of one overlaps the main loop of
   // another; a launch that needs split-K is a single round of workgroups in lock step, where the
   // stand-alone kernel is as fast and leaves the down-projection shorter.
-  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode == 0 && !hp.uplink_buffer && !hp.error_feedback && !P.any_tr;
+  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode != 2 && !hp.uplink_buffer && !hp.error_feedback && !P.any_tr;
   P.adam_first = fuse_adam ? lr : 0;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);

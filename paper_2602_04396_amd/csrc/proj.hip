@@ -202,6 +202,7 @@ struct FusedAdam {
   uint16_t* n_hi;
   uint16_t* n_lo;
   float b1, omb1, b2, omb2, inv_c1, inv_c2, eps;
+  float qw, qg;               // update bracket (qw u_hat + qg g) / den: 1, 0 for "No QHM"; omega, 1 - omega for low-rank QHM
 };
 
 __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f32x4 uu, f32x4 vv) {
@@ -213,7 +214,8 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
     uu[e] = un;
     vv[e] = vn;
     const float den = sqrtf(vn * f.inv_c2) + f.eps;
-    const float nn = den == 0.f ? 0.f : (un * f.inv_c1) / den;       // eps == 0 and no gradient yet (e.g. the padding): zero, not 0 / 0
+    // with qw = 1, qg = 0 bit-identical to u_hat / den; eps == 0 and no gradient yet (e.g. the padding): zero, not 0 / 0
+    const float nn = den == 0.f ? 0.f : fmaf(f.qg, g[e], f.qw * (un * f.inv_c1)) / den;
     hi[e] = f2bf_rne(nn);
     lo[e] = f2bf_rne(nn - __uint_as_float(hi[e] << 16));
   }
@@ -746,6 +748,7 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
       fa.u = fuse->u; fa.v = fuse->v; fa.n_hi = fuse->n_hi; fa.n_lo = fuse->n_lo;
       fa.b1 = fuse->a.b1; fa.omb1 = fuse->a.omb1; fa.b2 = fuse->a.b2; fa.omb2 = fuse->a.omb2;
       fa.inv_c1 = fuse->a.inv_c1; fa.inv_c2 = fuse->a.inv_c2; fa.eps = fuse->a.eps;
+      fa.qw = fuse->a.qw; fa.qg = fuse->a.qg;
     }
     // 256-rank tiles (ranks from 256 up, where the matrix cores bound the kernel): gradient by global-to-LDS loads,
     // transposed while it is read from LDS -- 8 to 11 % faster there than staging through registers; with 128-rank

@@ -116,14 +116,14 @@ def _first_of_each_shape(shapes):
     return out
 
 
-def _run_model_config(cfg, power_iters):
+def _run_model_config(cfg, power_iters, **update):
     import torch
     import bench
     from paper_2602_04396_amd import lordo
     shapes, W, G, Omega, D, grad_dtype = bench.build_workload(torch, lordo, synth, cfg, None, 2)
     kw = dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=power_iters)
-    hp = lordo.hparams(seed=synth.seed_for(int(cfg[1:]), 77), **kw)
-    ohp = orc.Hyper(**kw)
+    hp = lordo.hparams(seed=synth.seed_for(int(cfg[1:]), 77), **kw, **{k: ({"low": 1}[v] if k == "qhm_mode" else v) for k, v in update.items()})
+    ohp = orc.Hyper(**kw, **update)
     opt = lordo.Lordo(shapes, hp, W, torch)
     Wp = opt.ptrs(W)
     Gp = [opt.ptrs(g, grad_dtype) for g in G]
@@ -154,6 +154,12 @@ def test_c3_full_size_student_t_sampled_columns():
     the fp32 averaged pseudo-gradient with one power iteration, one more step."""
     assert synth.CONFIG_DEFAULTS["c3"]["noise"] == "student"
     _run_model_config("c3", synth.CONFIG_DEFAULTS["c3"]["power_iters"])
+
+
+def test_c3_low_rank_qhm_in_the_fused_epilogue():
+    """The same sequence with the low-rank QHM update (Alg. 1, second update case): at this launch shape its bracket
+    (omega u_hat + (1 - omega) g) / (sqrt(v_hat) + eps) is formed in the epilogue of the down-projection."""
+    _run_model_config("c3", synth.CONFIG_DEFAULTS["c3"]["power_iters"], qhm_mode="low", omega=0.8)
 
 
 def test_c4_full_size_sampled_columns():
