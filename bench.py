@@ -64,6 +64,8 @@ def parse():
                          "update cases plain and low-qhm")
     ap.add_argument("--param-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the weights (bf16: updates formed in fp32 and rounded once; update cases plain, low-qhm, ef, local)")
+    ap.add_argument("--err-dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage type of the error-feedback residual E (update cases ef and global)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 1 GiB device copies (known traffic) to scale the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
@@ -97,7 +99,7 @@ def measured_traffic(cfg, rank, kernel_class, update="plain", param_dtype="f32")
     return best[1] if best else None
 
 
-def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False, w_bytes=4):
+def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False, w_bytes=4, e_bytes=4):
     """Algorithmic bytes and flops per step of each kernel class (unpadded sizes).  With error feedback
     the down-projection also reads the residual E, Adam also writes g as operand planes and the "up"
     class holds a second launch (E <- G + E - Q g: E read and written, G read); the full-rank QHM
@@ -109,10 +111,10 @@ def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False, w_bytes=4):
     up_bytes = 2 * w_bytes * spq + 4 * spr + 4 * srq + (grad_bytes * spq if qhm_full else 0)
     up_flops = flops
     if ef:
-        up_bytes += 8 * spq + grad_bytes * spq + 4 * spr + 4 * srq
+        up_bytes += 2 * e_bytes * spq + grad_bytes * spq + 4 * spr + 4 * srq
         up_flops += flops
     return {
-        "down": dict(bytes=grad_bytes * spq + 4 * spr + 4 * srq + (4 * spq if ef else 0), flops=flops),
+        "down": dict(bytes=grad_bytes * spq + 4 * spr + 4 * srq + (e_bytes * spq if ef else 0), flops=flops),
         "adam": dict(bytes=(28 if ef else 24) * srq, flops=0),
         "up": dict(bytes=up_bytes, flops=up_flops),
         "outer": dict(bytes=(20 + w_bytes) * spq, flops=0),
@@ -272,7 +274,8 @@ class Workload:
                            grad_dtype=lordo.F32 if grad_dtype == torch.float32 else lordo.BF16,
                            qhm_mode=self.qhm_mode, omega=0.9 if self.qhm_mode else 1.0, error_feedback=self.use_ef,
                            uplink_buffer=self.uplink, rayleigh_ritz=args.rayleigh_ritz,
-                           param_dtype=lordo.BF16 if w_bf16 else lordo.F32)
+                           param_dtype=lordo.BF16 if w_bf16 else lordo.F32,
+                           err_dtype=lordo.BF16 if getattr(args, "err_dtype", "f32") == "bf16" and self.use_ef else lordo.F32)
         if args.short_side:
             gen = torch.Generator(device="cuda")
             gen.manual_seed(synth.seed_for(int(cfg[1:]), 997))
@@ -484,7 +487,8 @@ def main():
     wl.opt.poll_status()
 
     w_bytes = 2 if args.param_dtype == "bf16" else 4
-    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2, ef=wl.use_ef, qhm_full=wl.qhm_mode == 2, w_bytes=w_bytes)
+    work = algorithmic_work(shapes, 4 if grad_dtype == torch.float32 else 2, ef=wl.use_ef, qhm_full=wl.qhm_mode == 2, w_bytes=w_bytes,
+                            e_bytes=2 if args.err_dtype == "bf16" else 4)
     kernels = {}
     roofline = None
     if not args.no_events:
@@ -529,7 +533,7 @@ def main():
                    "refresh_every": refresh_every, "outer_every": outer_every, "power_iters": power_iters,
                    "grad_sets": n_sets, "outer": "nesterov lr 0.7 momentum 0.9 on a generated averaged pseudo-gradient",
                    "update": args.update, "rayleigh_ritz": bool(args.rayleigh_ritz), "short_side": bool(args.short_side),
-                   "param_dtype": args.param_dtype},
+                   "param_dtype": args.param_dtype, "err_dtype": args.err_dtype if args.update in ("ef", "global", "local") else None},
         "ms_per_refresh": kernels.get("refresh", {}).get("avg_ms"),
         "ms_per_outer": kernels.get("outer", {}).get("avg_ms"),
         "roofline": roofline,

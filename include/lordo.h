@@ -116,8 +116,14 @@ typedef struct {
   int32_t param_dtype;           /* element type of every W: LORDO_F32 (0, the default) or LORDO_BF16 -- bf16 STORAGE of the
                                     weights: every update is formed in fp32 from the stored value and rounded to nearest-even
                                     once when it is written back; the anchor and the outer momentum stay fp32 (the anchor
-                                    holds the stored, i.e. rounded, model).  Built for qhm_mode 0 and 1, with or without
-                                    error feedback; not with qhm_mode 2 or uplink_buffer (LORDO_EINVAL) */
+                                    holds the stored, i.e. rounded, model).  Every update case, with or without error
+                                    feedback; not with uplink_buffer, whose fused outer step writes fp32 (LORDO_EINVAL) */
+  int32_t err_dtype;             /* storage type of the error-feedback residual E: LORDO_F32 (0, the default) or LORDO_BF16.
+                                    bf16: E <- rne(s G + E - Q g), formed in fp32 from the stored value and rounded once;
+                                    LORDO_STATE_ERR is still read and written as fp32 (converted).  Needs error_feedback,
+                                    bf16 gradients and no right-projected matrix; lordo_refresh_subspace_local (whose
+                                    source s G + E is formed inside the residual buffer) then returns LORDO_EINVAL */
+  int32_t reserved;              /* must be 0                                                           */
   uint64_t seed;                 /* seed of the library's own Gaussian generator, used where the caller passes no
                                     random block: lordo_init_projection(Block = NULL) (Alg. 1 "Require": random Q_0) and
                                     lordo_refresh_subspace*(Omega = NULL).  Counter-based (Philox-4x32-10 + Box-Muller):

@@ -192,6 +192,16 @@ def outer_step_bf16_weights(st: MatrixState, avg_delta: np.ndarray, hp: Hyper) -
     return W_new
 
 
+def local_step_bf16_residual(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyper,
+                             grad_scale: float = 1.0) -> np.ndarray:
+    """The local step of Alg. 1 with error feedback when the residual E is STORED in bf16 (same reading as for the
+    weights): the step runs in full precision from the stored residual -- projection of G_hat + E, new residual
+    G_hat + E - Q g -- and the new residual is rounded to bf16 once.  Nothing else changes."""
+    W_new = local_step(st, W, G, lr, hp, grad_scale)
+    st.E = round_to_bf16(st.E)
+    return W_new
+
+
 # ----------------------------------------------------------------------------
 # projection on the right (Sec. 2 with the roles of rows and columns exchanged)
 # ----------------------------------------------------------------------------

@@ -169,6 +169,8 @@ hipError_t launch_store_ptrs(void** dst, void* const* host_src, int count, hipSt
 hipError_t launch_pack_q(const DevCtx& d, int mat_first, int mat_count, hipStream_t s);
 hipError_t launch_identity_q(const DevCtx& d, hipStream_t s);
 hipError_t launch_fill_zero(void* dst, int64_t bytes, hipStream_t s);
+hipError_t launch_bf16_to_f32(float* dst, const uint16_t* src, int64_t n, hipStream_t s);      // exact widening
+hipError_t launch_f32_to_bf16(uint16_t* dst, const float* src, int64_t n, hipStream_t s);      // round to nearest-even
 hipError_t launch_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
 // p x q elementwise family: chunk_start (device) has n+1 entries, prefix sums of per-matrix chunk counts
 struct OuterArgs { float lr, mu; int32_t nesterov, has_mom, own_delta, w_bf16; };

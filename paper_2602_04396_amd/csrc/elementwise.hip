@@ -209,6 +209,34 @@ hipError_t launch_copy_f32(float* dst, const float* src, int64_t n, hipStream_t 
   return hipGetLastError();
 }
 
+// a bf16-stored state array read and written through the fp32 state interface
+__global__ __launch_bounds__(256) void k_bf16_to_f32(float* dst, const uint16_t* src, int64_t n) {
+  int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+}
+__global__ __launch_bounds__(256) void k_f32_to_bf16(uint16_t* dst, const float* src, int64_t n) {
+  int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    uint32_t hi, lo;
+    split_bf(src[i], hi, lo);          // hi: the nearest-even bf16 of the value
+    dst[i] = (uint16_t)hi;
+  }
+}
+hipError_t launch_bf16_to_f32(float* dst, const uint16_t* src, int64_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(k_bf16_to_f32, dim3((unsigned)blocks), dim3(256), 0, s, dst, src, n);
+  return hipGetLastError();
+}
+hipError_t launch_f32_to_bf16(uint16_t* dst, const float* src, int64_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(k_f32_to_bf16, dim3((unsigned)blocks), dim3(256), 0, s, dst, src, n);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------
 // projection packing
 // ---------------------------------------------------------------------------------------

@@ -586,9 +586,17 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
   if (hp->power_iters < 0 || hp->power_iters > 8) return LORDO_EINVAL;
   if (hp->rayleigh_ritz != 0 && hp->rayleigh_ritz != 1) return LORDO_EINVAL;
   if (hp->param_dtype != LORDO_F32 && hp->param_dtype != LORDO_BF16) return LORDO_EINVAL;
-  // bf16 weights: built for the plain and the low-rank QHM update (with or without error feedback); the gradient-term
-  // epilogue of the full-rank QHM update and the fused outer step from the up-link buffers write fp32 weights only
-  if (hp->param_dtype == LORDO_BF16 && (hp->qhm_mode == 2 || hp->uplink_buffer)) return LORDO_EINVAL;
+  // bf16 weights: every update case; the fused outer step from the up-link buffers writes fp32 weights only
+  if (hp->param_dtype == LORDO_BF16 && hp->uplink_buffer) return LORDO_EINVAL;
+  // bf16 residual: the pipelined down-projection of bf16 gradients widens it on the way in and the residual launch of
+  // the up-projection rounds it once on the way out; the paths that form s G + E inside the buffer (fp32 gradients,
+  // right-projected matrices, the refresh of the local variant) keep an fp32 buffer
+  if ((hp->err_dtype != LORDO_F32 && hp->err_dtype != LORDO_BF16) || hp->reserved != 0) return LORDO_EINVAL;
+  if (hp->err_dtype == LORDO_BF16) {
+    if (!hp->error_feedback || hp->grad_dtype != LORDO_BF16) return LORDO_EINVAL;
+    for (int i = 0; i < n; ++i)
+      if (shapes[i].side) return LORDO_EINVAL;
+  }
   if (hp->rayleigh_ritz)          // a wave of the multi-launch Jacobi solver keeps two columns of r elements in registers
     for (int i = 0; i < n; ++i)
       if (shapes[i].rank > 1024) return LORDO_EINVAL;
@@ -714,7 +722,7 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
     }
     m.anchor = A.take(pq * 4);
     m.mom = has_mom ? A.take(pq * 4) : -1;
-    m.err = hp.error_feedback ? A.take(pq * 4) : -1;
+    m.err = hp.error_feedback ? A.take(pq * (hp.err_dtype == LORDO_BF16 ? 2 : 4)) : -1;
     m.y[0] = A.take(pr * 4); m.y[1] = A.take(pr * 4);
     for (int k = 0; k < 4; ++k) m.zw[k] = A.take(qr * 4);
     m.gram = A.take(rr * 4); m.lfac = A.take(rr * 4);
@@ -1158,7 +1166,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   bool g_vec = true;            // 4-byte accesses to a bf16 G need an even q and 4-byte aligned pointers
   for (int i = 0; i < c->n; ++i)      // (right-projected matrices do not pass through the projection kernels)
     if (!P.mat[i].tr && ((P.mat[i].q & 1) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 3) != 0)) { g_vec = false; break; }
-  const bool w_bf16 = c->hp.param_dtype == LORDO_BF16;
+  const bool w_bf16 = c->hp.param_dtype == LORDO_BF16, e_bf16 = c->hp.err_dtype == LORDO_BF16;
   const uintptr_t w_mask = w_bf16 ? 7 : 15;     // four weights with one access: 16 bytes of fp32, 8 bytes of bf16
   bool w_vec = true;            // four-column accesses to W need q % 4 == 0 and pointers aligned to them
   for (int i = 0; i < c->n; ++i)
@@ -1185,7 +1193,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
     if (!P.mat[i].tr && ((P.mat[i].q & 7) != 0 || (reinterpret_cast<uintptr_t>(G[i]) & 15) != 0)) g_tr = false;
   if (!P.down_h.empty())
     HIPCHK(launch_proj_down(c->dev, c->at<ProjTile>(P.down_tiles), (int)P.down_h.size(), P.mb, P.down_pipe, g_vec, g_tr, P.g_once, c->at<float>(P.glow),
-                            P.lr_total, (float)proj_scale, g_f32, ef ? 1 : 0, &fuse, s));
+                            P.lr_total, (float)proj_scale, g_f32, ef ? (e_bf16 ? 3 : 1) : 0, &fuse, s));
   if (P.any_tr || generic) {    // g^T = (s G) Q into the plain block zw[0], then into the blocked array the Adam kernel reads
     bool stream = P.tr_stream_shapes && !ef && !generic;
     if (ef) {                   // A = s G + E is formed in the residual buffer first (unless a refresh of the local variant has done it)
@@ -1222,6 +1230,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   ua.w_bf16 = w_bf16 ? 1 : 0;
   if (ef) {                     // E <- grad_scale*G + E - Q g (Alg. 1 error-feedback lines); reads the E the down-projection used
     ua.coef_acc = -1.f; ua.coef_g = (float)proj_scale; ua.target_err = 1; ua.colscale = 0; ua.colpart = nullptr;
+    ua.w_bf16 = e_bf16 ? 1 : 0;         // element type of this launch's target: the residual
     if (!P.up_h.empty())
       HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.g_hi),
                             c->at<uint16_t>(P.g_lo), ua, s));
@@ -1235,6 +1244,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
     }
   }
   ua.target_err = 0;
+  ua.w_bf16 = w_bf16 ? 1 : 0;
   if (qhm_full) {               // W <- W - eta [ (1-omega) G_hat diag(1/s) + omega Q N ]  (Alg. 1 "Full-Rank QHM")
     ua.coef_acc = (float)(-lr * c->hp.omega);
     ua.coef_g = (float)(-lr * (1.0 - c->hp.omega) * grad_scale);
@@ -1440,6 +1450,7 @@ int lordo_spectral_gap(lordo_ctx* c, const void* const* Src, int32_t src_dtype, 
 int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {
   if (!c || !G || !std::isfinite(grad_scale)) return LORDO_EINVAL;
   if (lordo_ctx::has_null(G, c->n) || (Omega && lordo_ctx::has_null(Omega, c->n))) return LORDO_EINVAL;
+  if (c->hp.err_dtype == LORDO_BF16) return LORDO_EINVAL;      // the sum s G + E is formed inside the residual buffer: fp32 only
   if (!c->hp.error_feedback || c->grad_folded) return LORDO_ESTATE;
   if (c->hp.uplink_buffer && c->window_steps > 0) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
@@ -1632,7 +1643,8 @@ int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, voi
       break;
     case LORDO_STATE_ERR:
       if (m.err < 0 || c->grad_folded) return LORDO_ESTATE;      // folded: the buffer holds G + E until the next local step
-      HIPCHK(launch_copy_f32(dst, c->at<float>(m.err), (int64_t)m.p * m.q, s));
+      if (c->hp.err_dtype == LORDO_BF16) HIPCHK(launch_bf16_to_f32(dst, c->at<uint16_t>(m.err), (int64_t)m.p * m.q, s));
+      else HIPCHK(launch_copy_f32(dst, c->at<float>(m.err), (int64_t)m.p * m.q, s));
       break;
     case LORDO_STATE_UPLINK:
       if (P.acc < 0) return LORDO_ESTATE;
@@ -1673,7 +1685,8 @@ int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_sr
       break;
     case LORDO_STATE_ERR:
       if (m.err < 0 || c->grad_folded) return LORDO_ESTATE;
-      HIPCHK(launch_copy_f32(c->at<float>(m.err), src, (int64_t)m.p * m.q, s));
+      if (c->hp.err_dtype == LORDO_BF16) HIPCHK(launch_f32_to_bf16(c->at<uint16_t>(m.err), src, (int64_t)m.p * m.q, s));
+      else HIPCHK(launch_copy_f32(c->at<float>(m.err), src, (int64_t)m.p * m.q, s));
       break;
     case LORDO_STATE_UPLINK:
       if (P.acc < 0) return LORDO_ESTATE;

@@ -147,15 +147,17 @@ __device__ __forceinline__ void store_gstage(const GStage<GF32>& st, u32x4* lds_
 }
 
 // grad_scale * G + E of one stage (error feedback, Alg. 1: the projected matrix is the gradient plus the residual)
-template <bool GF32>
-__device__ __forceinline__ void add_residual(GStage<true>& out, const GStage<GF32>& g, const GStage<true>& e, float scale) {
+template <bool GF32, bool EF32>     // EF32: the residual is stored in fp32 (else bf16: widened exactly)
+__device__ __forceinline__ void add_residual(GStage<true>& out, const GStage<GF32>& g, const GStage<EF32>& e, float scale) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    float g0, g1;
+    float g0, g1, e0, e1;
     if constexpr (GF32) { g0 = __uint_as_float(g.x[2 * i]); g1 = __uint_as_float(g.x[2 * i + 1]); }
     else { g0 = __uint_as_float(g.x[i] << 16); g1 = __uint_as_float(g.x[i] & 0xffff0000u); }
-    out.x[2 * i] = __float_as_uint(fmaf(scale, g0, __uint_as_float(e.x[2 * i])));
-    out.x[2 * i + 1] = __float_as_uint(fmaf(scale, g1, __uint_as_float(e.x[2 * i + 1])));
+    if constexpr (EF32) { e0 = __uint_as_float(e.x[2 * i]); e1 = __uint_as_float(e.x[2 * i + 1]); }
+    else { e0 = __uint_as_float(e.x[i] << 16); e1 = __uint_as_float(e.x[i] & 0xffff0000u); }
+    out.x[2 * i] = __float_as_uint(fmaf(scale, g0, e0));
+    out.x[2 * i + 1] = __float_as_uint(fmaf(scale, g1, e1));
   }
 }
 
@@ -242,11 +244,14 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
 // the result is not scaled again.
 // EFM = 2: the projected matrix is an fp32 matrix alone (no G): the fp32 source of a subspace refresh, taken
 // from the caller's source table -- the product Z = Src^T Y of the power iteration has the shape of g = Q^T G.
+// EFM = 3: error feedback with the residual stored in bf16 (widened exactly; the sum is formed in fp32 as before).
 template <int RB, bool VEC, bool GONCE, int EFM>
 __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile* __restrict__ tiles, float* __restrict__ glow,
                                                         int64_t split_stride, float grad_scale, FusedAdam fa) {
   constexpr bool EF = EFM != 0;                                // an fp32 operand is staged: hi and lo planes, three passes
   constexpr bool SRC32 = EFM == 2;                             // ... and it is the whole operand
+  constexpr bool E32 = EFM != 3;                               // storage type of the second operand (residual or source)
+  constexpr uint32_t EES = E32 ? 4u : 2u;
   constexpr int BK = 32;
   constexpr int NW = 8;
   const ProjTile t = tiles[blockIdx.x];
@@ -286,13 +291,13 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   gc.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 2u : OOB;
   const int wslot = ((4 * half + (lane >> 4)) * 4 + kgrp) * 32 + 2 * (lane & 15);
   // residual E: fp32 p x q in the arena, same rows and columns (8-byte accesses need an even q: VEC)
-  const uint32_t erow_bytes = (uint32_t)m.q * 4u;
+  const uint32_t erow_bytes = (uint32_t)m.q * EES;
   const rsrc_t re = SRC32 ? make_rsrc(ext_ptr(d, EXT_SRC, t.mat), (uint32_t)klim * erow_bytes)
                           : (EF ? make_rsrc(d.arena + m.err, (uint32_t)klim * erow_bytes) : rs);
   GCol ge;
   ge.vec = VEC;
-  ge.off0 = col < m.q ? (uint32_t)col * 4u : OOB;
-  ge.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * 4u : OOB;
+  ge.off0 = col < m.q ? (uint32_t)col * EES : OOB;
+  ge.off1 = col + 1 < m.q ? (uint32_t)(col + 1) * EES : OOB;
 
   // Q fragments of a stage: (mblk, kstep) pairs, both planes each; 8*RB pairs, RB per wave
   const int64_t kgroups = m.pp / 8;
@@ -376,7 +381,7 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   // the resource), so the loads of stages past the last one are issued unconditionally: the number of
   // outstanding loads is then the same in every iteration, which the explicit waits rely on.
   GStage<false> st0, st1;
-  GStage<true> se0, se1;                                       // EF: rows of E of the same stages
+  GStage<E32> se0, se1;                                        // EF: rows of E of the same stages
   constexpr int GAUX = GONCE ? STREAM : 0;
   // outstanding loads of one stage: 8 (or 16 two-byte ones) of G, as many again of E
   constexpr int NLOADS = ((SRC32 ? 0 : 1) + (EF ? 1 : 0)) * (VEC ? 8 : 16);
@@ -385,12 +390,12 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
     else if constexpr (NLOADS == 16) WAIT_VM_BARRIER(16);
     else WAIT_VM_BARRIER(32);
   };
-  auto stage_out = [&](const GStage<false>& g, const GStage<true>& e, int sbuf) {
+  auto stage_out = [&](const GStage<false>& g, const GStage<E32>& e, int sbuf) {
     if constexpr (SRC32) {
       store_gstage<true>(e, gfrag + sbuf * GSLOTS, glo + sbuf * GSLOTS, wslot);
     } else if constexpr (EF) {
       GStage<true> sa;
-      add_residual<false>(sa, g, e, grad_scale);
+      add_residual<false, E32>(sa, g, e, grad_scale);
       store_gstage<true>(sa, gfrag + sbuf * GSLOTS, glo + sbuf * GSLOTS, wslot);
     } else {
       store_gstage<false>(g, gfrag + sbuf * GSLOTS, nullptr, wslot);
@@ -398,9 +403,9 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
   };
   issue_a(t.k0, 0);
   if constexpr (!SRC32) load_gstage<false, GAUX>(st0, rs, row_bytes, krow0, klim, gc);                  // stage 0
-  if constexpr (EF) load_gstage<true, GAUX>(se0, re, erow_bytes, krow0, klim, ge);
+  if constexpr (EF) load_gstage<E32, GAUX>(se0, re, erow_bytes, krow0, klim, ge);
   if constexpr (!SRC32) load_gstage<false, GAUX>(st1, rs, row_bytes, krow0 + BK, klim, gc);             // stage 1
-  if constexpr (EF) load_gstage<true, GAUX>(se1, re, erow_bytes, krow0 + BK, klim, ge);
+  if constexpr (EF) load_gstage<E32, GAUX>(se1, re, erow_bytes, krow0 + BK, klim, ge);
   stage_out(st0, se0, 0);
   wait_one_stage();
 
@@ -410,7 +415,7 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
     const int kr = t.k0 + (S) * BK;                                                               \
     if ((S) + 1 < nstages) issue_a(kr + BK, ((S) + 1) & 1);                                       \
     if constexpr (!SRC32) load_gstage<false, GAUX>(LOAD, rs, row_bytes, krow0 + ((S) + 2) * BK, klim, gc); \
-    if constexpr (EF) load_gstage<true, GAUX>(LOADE, re, erow_bytes, krow0 + ((S) + 2) * BK, klim, ge); \
+    if constexpr (EF) load_gstage<E32, GAUX>(LOADE, re, erow_bytes, krow0 + ((S) + 2) * BK, klim, ge); \
     ISSUE_FENCE();                                                                                \
     compute((S) & 1);                                                                             \
     ISSUE_FENCE();                                                                                \
@@ -731,7 +736,8 @@ static hipError_t launch_pipe_vo(bool g_vec, bool g_once, dim3 grid, const DevCt
 static hipError_t launch_pipe_select(int rb, bool g_vec, bool g_once, int ef, dim3 grid, const DevCtx& d, const ProjTile* tiles,
                                      float* glow, int64_t split_stride, float grad_scale, const FusedAdam& fa, hipStream_t s) {
 #define LORDO_PIPE_RB(RBV)                                                                                               \
-  (ef == 2 ? launch_pipe_vo<RBV, 2>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)                \
+  (ef == 3 ? launch_pipe_vo<RBV, 3>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)                \
+   : ef == 2 ? launch_pipe_vo<RBV, 2>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)              \
    : ef == 1 ? launch_pipe_vo<RBV, 1>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s)              \
              : launch_pipe_vo<RBV, 0>(g_vec, g_once, grid, d, tiles, glow, split_stride, grad_scale, fa, s))
   return rb == 2 ? LORDO_PIPE_RB(2) : LORDO_PIPE_RB(1);
@@ -945,12 +951,12 @@ __global__ __launch_bounds__(256) void k_proj_up(DevCtx d, const ProjTile* __res
 //   b <- mu b + Delta;  x <- anchor - eta_s (Delta + mu b) (Nesterov), anchor - eta_s b (heavy ball) or anchor - eta_s Delta
 //   (no momentum);  W <- x, anchor <- x.
 template <int NW, int EPI, bool WBF>   // NW waves per workgroup: 4 (wave tile 64 x 64) or 8 (wave tile 32 x 64); EPI 0 plain, 1 gradient term, 2 outer step;
-                                       // WBF: the caller's W is bf16 (plain update only)
+                                       // WBF: the target (the caller's W, or the residual E) is stored in bf16
 __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTile* __restrict__ tiles,
                                                          const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, UpArgs ua) {
   constexpr bool WITH_G = EPI == 1;
   constexpr bool OUTER = EPI == 2;
-  static_assert(!WBF || EPI == 0, "bf16 weights: plain update only");
+  static_assert(!WBF || EPI != 2, "bf16 targets: plain update and gradient-term epilogue");
   typedef WAcc<WBF> WA;
   constexpr uint32_t WES = WA::ES;
   const float lr = -ua.coef_acc;
@@ -1166,8 +1172,10 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
     for (int j = 0; j < 8; ++j) {
       f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 4 * j) * TP + 4 * c16);
       const f32x4 wf = WA::unpack(wv[a][j]);
-      if constexpr (WBF) {
-        WA::store(f32x4{fmaf(-lr, x.x, wf.x), fmaf(-lr, x.y, wf.y), fmaf(-lr, x.z, wf.z), fmaf(-lr, x.w, wf.w)}, rw_out, voff, w_soff(a, j));
+      if constexpr (WBF) {       // bf16 target: the new value is formed in fp32 and rounded once
+        f32x4 val = {fmaf(-lr, x.x, wf.x), fmaf(-lr, x.y, wf.y), fmaf(-lr, x.z, wf.z), fmaf(-lr, x.w, wf.w)};
+        if constexpr (WITH_G) val += gt[j];
+        WA::store(val, rw_out, voff, w_soff(a, j));
         continue;
       }
       u32x4 o;
@@ -1551,13 +1559,14 @@ hipError_t launch_proj_up(const DevCtx& d, const ProjTile* tiles, int ntiles, bo
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles), block(256);
   const bool with_g = ua.coef_g != 0.f || ua.target_err == 1;
-  const bool w_bf16 = ua.w_bf16 != 0 && ua.target_err == 0;     // (the residual and the momentum are fp32 whatever the weights are)
+  const bool w_bf16 = ua.w_bf16 != 0 && ua.target_err != 2;     // element type of the target as the caller of this launch states it (the momentum is always fp32)
   if (ua.outer) {
     if (!vec || w_bf16) return hipErrorInvalidValue;       // the outer-step epilogue exists for 16-byte row accesses of fp32 weights only
     hipLaunchKernelGGL((k_proj_up_dma<4, 2, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else if (with_g) {
-    if (!vec || w_bf16) return hipErrorInvalidValue;       // the gradient-term epilogue exists for 16-byte row accesses of fp32 targets only
-    hipLaunchKernelGGL((k_proj_up_dma<4, 1, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    if (!vec) return hipErrorInvalidValue;                 // the gradient-term epilogue exists for four-column row accesses only
+    if (w_bf16) hipLaunchKernelGGL((k_proj_up_dma<4, 1, true>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
+    else hipLaunchKernelGGL((k_proj_up_dma<4, 1, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
   } else if (vec) {
     if (w_bf16) hipLaunchKernelGGL((k_proj_up_dma<4, 0, true>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);
     else hipLaunchKernelGGL((k_proj_up_dma<4, 0, false>), grid, block, 0, s, d, tiles, b_hi, b_lo, ua);

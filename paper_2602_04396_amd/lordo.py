@@ -42,16 +42,17 @@ class HParams(C.Structure):
         ("power_iters", C.c_int32), ("orth_passes", C.c_int32),
         ("grad_dtype", C.c_int32), ("uplink_buffer", C.c_int32),
         ("rayleigh_ritz", C.c_int32), ("param_dtype", C.c_int32),
+        ("err_dtype", C.c_int32), ("reserved", C.c_int32),
         ("seed", C.c_uint64),
     ]
 
 
 def hparams(beta1=0.9, beta2=0.999, eps=1e-8, bias_correction=True, outer_lr=1.0, outer_momentum=0.0,
             outer_nesterov=False, power_iters=2, orth_passes=2, grad_dtype=BF16, qhm_mode=0, omega=1.0,
-            error_feedback=False, uplink_buffer=False, rayleigh_ritz=False, seed=0, param_dtype=F32) -> HParams:
+            error_feedback=False, uplink_buffer=False, rayleigh_ritz=False, seed=0, param_dtype=F32, err_dtype=F32) -> HParams:
     return HParams(beta1, beta2, eps, int(bias_correction), qhm_mode, omega, int(error_feedback),
                    int(outer_nesterov), outer_lr, outer_momentum, power_iters, orth_passes, grad_dtype, int(uplink_buffer),
-                   int(rayleigh_ritz), int(param_dtype), int(seed))
+                   int(rayleigh_ritz), int(param_dtype), int(err_dtype), 0, int(seed))
 
 
 class LordoError(RuntimeError):

@@ -29,7 +29,7 @@ def test_exports_every_declared_symbol(lib):
 
 def test_struct_layout_matches_header():
     assert C.sizeof(lordo.Shape) == 24
-    assert C.sizeof(lordo.HParams) == 96 and lordo.HParams.seed.offset == 88
+    assert C.sizeof(lordo.HParams) == 104 and lordo.HParams.seed.offset == 96 and lordo.HParams.err_dtype.offset == 88
     assert lordo.HParams.rayleigh_ritz.offset == 80
     assert lordo.HParams.omega.offset == 32 and lordo.HParams.outer_lr.offset == 48
     assert lordo.HParams.power_iters.offset == 64 and lordo.HParams.grad_dtype.offset == 72

@@ -831,3 +831,28 @@ def test_bf16_weight_steps_are_the_full_precision_steps_rounded_once():
     Wn = orc.outer_step_bf16_weights(a, D, hp)
     assert np.array_equal(Wn, orc.round_to_bf16(full)) and np.array_equal(a.anchor, Wn)
     assert np.array_equal(a.b, b.b)
+
+
+def test_bf16_residual_step_is_the_error_feedback_step_rounded_once():
+    """Alg. 1 error-feedback lines with a bf16-stored residual: from the same stored E the projected matrix, g, the
+    moments and the weights are those of the full-precision step, and the new residual is that step's residual
+    G_hat + E - Q g (written out here) rounded once; it is orthogonal to Q up to that rounding."""
+    rng = rng_of(72)
+    p, q, r = 20, 14, 4
+    Q = synth.orthonormal(rng, p, r)
+    W0 = rng.standard_normal((p, q))
+    hp = orc.Hyper(error_feedback=True, qhm_mode="low", omega=0.8)
+    a, b = orc.init_state(W0, r, Q), orc.init_state(W0, r, Q)
+    Wa = W0.copy()
+    for t in range(4):
+        G = rng.standard_normal((p, q)) * 1e-2
+        b.E = a.E.copy()                                           # the other chain starts from the STORED residual
+        E_before = a.E.copy()
+        Wb = orc.local_step(b, Wa, G, 1e-2, hp, 0.9)
+        Wa = orc.local_step_bf16_residual(a, Wa, G, 1e-2, hp, 0.9)
+        A = 0.9 * G + E_before
+        assert np.array_equal(a.E, orc.round_to_bf16(A - Q @ (Q.T @ A)))
+        assert np.array_equal(a.E, orc.round_to_bf16(b.E)) and np.array_equal(Wa, Wb)
+        assert np.array_equal(a.u, b.u) and np.array_equal(a.v, b.v)
+        assert np.linalg.norm(Q.T @ a.E) <= 2.0 ** -8 * np.linalg.norm(a.E)
+        assert np.array_equal(orc.round_to_bf16(a.E), a.E)
