@@ -385,12 +385,12 @@ def extra_configs(torch, lordo, synth, args, skip_cfg):
     import gc
     out = []
     # (warm-up long enough for the clocks to settle: some tens of milliseconds of steps)
-    for cfg, warm, steps in (("c2", 100, 200), ("c3", 5, 20), ("c4", 3, 6)):
+    for cfg, warm, steps in (("c1", 200, 500), ("c2", 100, 200), ("c3", 5, 20), ("c4", 3, 6)):
         if cfg == skip_cfg:
             continue
         wl = Workload(torch, lordo, synth, cfg, None, 4 if cfg == "c2" else 2, args)
         wl.steps(warm, 0, 0)
-        work = algorithmic_work(wl.shapes, 2, w_bytes=2 if args.param_dtype == "bf16" else 4)
+        work = algorithmic_work(wl.shapes, 4 if cfg == "c1" else 2, w_bytes=2 if args.param_dtype == "bf16" else 4)
         kernels, _ = wl.profiled(steps, 0, 0, work)
         out.append({"workload": cfg, "rank": wl.shapes[0][2], "power_iters": wl.power_iters, "ms": class_ms(kernels),
                     "GBps": {k: round(v["GBps"]) for k, v in kernels.items() if "GBps" in v},

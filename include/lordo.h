@@ -27,6 +27,13 @@
  *     lordo_refresh_subspace*, lordo_init_projection leave the projection and the
  *     moments as they were (the refresh that broke down included): the optimizer goes
  *     on in the old subspace until the caller polls, which clears the latch.
+ *   - Stream capture: the compute calls enqueue kernels only (no allocation, no memset, no
+ *     host synchronisation), so they can be recorded into a HIP graph.  The step count, the
+ *     bias corrections 1 - beta^t derived from it, the learning rate and the gradient scale
+ *     travel as kernel arguments, and the step count advances on the host when a call is
+ *     ISSUED: a recorded lordo_local_step replays with the values of the time it was
+ *     recorded.  Replaying is therefore exact only with bias_correction = 0 and a fixed
+ *     learning rate; otherwise record again (or update the kernel nodes) whenever they change.
  *   - There is no CPU fallback: without a GPU every compute call returns LORDO_EHIP.
  */
 #ifndef LORDO_H
