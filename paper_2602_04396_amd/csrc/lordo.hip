@@ -1231,7 +1231,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   if (ef) {                     // E <- grad_scale*G + E - Q g (Alg. 1 error-feedback lines); reads the E the down-projection used
     ua.coef_acc = -1.f; ua.coef_g = (float)proj_scale; ua.target_err = 1; ua.colscale = 0; ua.colpart = nullptr;
     ua.w_bf16 = e_bf16 ? 1 : 0;         // element type of this launch's target: the residual
-    if (!P.up_h.empty())
+    if (!P.up_wide_h.empty() && w_vec && !g_f32)
+      HIPCHK(launch_proj_up_wide(c->dev, c->at<ProjTile>(P.up_wide_tiles), (int)P.up_wide_h.size(), c->at<uint16_t>(P.g_hi),
+                                 c->at<uint16_t>(P.g_lo), ua, s));
+    else if (!P.up_h.empty())
       HIPCHK(launch_proj_up(c->dev, c->at<ProjTile>(P.up_tiles), (int)P.up_h.size(), w_vec, c->at<uint16_t>(P.g_hi),
                             c->at<uint16_t>(P.g_lo), ua, s));
     if (P.any_tr) {             // right-projected matrices: E already holds s G + E; E <- E - g^T Q^T on the shadow records (planes of g as A)
@@ -1252,7 +1255,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   } else {
     ua.coef_acc = (float)-lr; ua.coef_g = 0.f; ua.colscale = 0; ua.colpart = nullptr;
   }
-  if (!P.up_wide_h.empty() && w_vec && !qhm_full)
+  if (!P.up_wide_h.empty() && w_vec && !(qhm_full && g_f32))   // (the wide kernel's gradient-term epilogue reads bf16 gradients)
     HIPCHK(launch_proj_up_wide(c->dev, c->at<ProjTile>(P.up_wide_tiles), (int)P.up_wide_h.size(), c->at<uint16_t>(P.n_hi),
                                c->at<uint16_t>(P.n_lo), ua, s));
   else if (!P.up_h.empty())

@@ -1223,7 +1223,7 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 // runs under the contraction of the other.  The registers leave no room for the whole W tile: the first row block
 // is requested before the contraction, the others when it ends.
 // ---------------------------------------------------------------------------------------
-template <bool WBF>
+template <bool WBF, bool WITH_G>     // WITH_G: gradient-term epilogue (bf16 G): the full-rank QHM update, or the residual E as target
 __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* __restrict__ tiles,
                                                       const uint16_t* __restrict__ n_hi, const uint16_t* __restrict__ n_lo, UpArgs ua) {
   typedef WAcc<WBF> WA;
@@ -1281,7 +1281,8 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
   // W tile in row order: lane = (rr, c16): row rr + 4j of a row block, columns 4*c16 .. 4*c16+3 of the wave's two
   // column blocks, so that one access of the wave covers four rows of 256 contiguous bytes
   const uint32_t row_bytes = (uint32_t)q * WES;
-  const rsrc_t rw = make_rsrc(ext_ptr(d, EXT_W, t.mat), (uint32_t)p * row_bytes);
+  const void* target = WITH_G && ua.target_err == 1 ? static_cast<const void*>(d.arena + m.err) : ext_ptr(d, EXT_W, t.mat);
+  const rsrc_t rw = make_rsrc(target, (uint32_t)p * row_bytes);
   const int rr = lane >> 4, c16 = lane & 15;
   const int lcol = 32 * nb0 + 4 * c16;                       // first of the lane's four columns
   const uint32_t voff = lcol < q ? (uint32_t)rr * row_bytes + (uint32_t)c16 * (4u * WES) : OOB;
@@ -1349,7 +1350,35 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
 
   if (mb0 >= mblocks || nb0 >= nblocks) return;
   float* T = reinterpret_cast<float*>(frag) + wave * 32 * TP;
-  auto combine = [&](int a, const typename WA::raw_t (&wv)[8]) {
+  // gradient term: coef_g * G * c_j on the lane's four columns, c_j the column scale of the full-rank QHM update
+  // (1 / mean over the rank of sqrt(v_hat) + eps, from the sums the Adam kernel left) or 1
+  const uint32_t grow_bytes = (uint32_t)q * 2u;
+  const rsrc_t rg = WITH_G ? make_rsrc(ext_ptr(d, EXT_G, t.mat), (uint32_t)p * grow_bytes) : rw;
+  const uint32_t gvoff = lcol < q ? (uint32_t)rr * grow_bytes + (uint32_t)c16 * 8u : OOB;
+  auto g_soff = [&](int a, int j) -> uint32_t {
+    const int row = 32 * (mb0 + a) + 4 * j;
+    return row < p ? (uint32_t)row * grow_bytes + (uint32_t)(32 * nb0) * 2u : (uint32_t)p * grow_bytes;
+  };
+  f32x4 cscale = {1.f, 1.f, 1.f, 1.f};
+  if constexpr (WITH_G) {
+    const int bsel = c16 >> 3;
+    if (ua.colscale == 1 && nb0 + bsel < nblocks) {
+      const GAS float* cp = TO_GLOBAL(const float, ua.colpart) + m.lr_off / 32;
+      const int rblocks = m.rp / 32;
+      const float pad = (float)(m.rp - m.r) * ua.eps;          // padded rank indices hold v = 0: eps each
+      const float inv_r = 1.f / (float)m.r;
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      for (int rb = 0; rb < rblocks; ++rb)                      // fixed order
+        sum += *reinterpret_cast<const GAS f32x4*>(cp + ((int64_t)(nb0 + bsel) * rblocks + rb) * 32 + 4 * (c16 & 7));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) cscale[e] = ua.coef_g / ((sum[e] - pad) * inv_r);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) cscale[e] = ua.coef_g;
+    }
+  }
+  struct GRows { u32x2 g[WITH_G ? 8 : 1]; };
+  auto combine = [&](int a, const typename WA::raw_t (&wv)[8], const GRows& gr) {
     // transposed accumulator: register 4*vq+e of lane l is row l%32, column 8*vq + 4*(l/32) + e of its block
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -1364,26 +1393,51 @@ __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* 
     for (int j = 0; j < 8; ++j) {
       const f32x4 x = *reinterpret_cast<const f32x4*>(T + (rr + 4 * j) * TP + 4 * c16);
       const f32x4 wf = WA::unpack(wv[j]);
-      WA::store(f32x4{fmaf(-lr, x.x, wf.x), fmaf(-lr, x.y, wf.y), fmaf(-lr, x.z, wf.z), fmaf(-lr, x.w, wf.w)}, rw, voff, w_soff(a, j));
+      f32x4 val = {fmaf(-lr, x.x, wf.x), fmaf(-lr, x.y, wf.y), fmaf(-lr, x.z, wf.z), fmaf(-lr, x.w, wf.w)};
+      if constexpr (WITH_G) {
+        const u32x2 w = gr.g[j];
+        val.x = fmaf(cscale.x, __uint_as_float(w.x << 16), val.x); val.y = fmaf(cscale.y, __uint_as_float(w.x & 0xffff0000u), val.y);
+        val.z = fmaf(cscale.z, __uint_as_float(w.y << 16), val.z); val.w = fmaf(cscale.w, __uint_as_float(w.y & 0xffff0000u), val.w);
+      }
+      WA::store(val, rw, voff, w_soff(a, j));
     }
   };
-  auto fetch = [&](int a, typename WA::raw_t (&wv)[8]) {
+  auto fetch = [&](int a, typename WA::raw_t (&wv)[8], GRows& gr) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) wv[j] = WA::load(rw, voff, w_soff(a, j));
+    if constexpr (WITH_G) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) gr.g[j] = __builtin_amdgcn_raw_buffer_load_b64(rg, gvoff, g_soff(a, j), STREAM);
+    }
   };
   // the fragment registers are free now: two further row blocks are requested at once, the last one as soon as
   // the first has been combined, so that only one memory latency is left exposed per tile
-  typename WA::raw_t wv0[8], wv1[8], wv2[8];
-  fetch(0, wv0);
-  fetch(1, wv1);
-  fetch(2, wv2);
-  ISSUE_FENCE();
-  combine(0, wv0);
-  fetch(3, wv0);
-  ISSUE_FENCE();
-  combine(1, wv1);
-  combine(2, wv2);
-  combine(3, wv0);
+  // (fp32 target with a gradient tile: 48 registers per row block, two in flight keep the kernel at two waves per SIMD)
+  constexpr bool THREE = !(WITH_G && !WBF);
+  typename WA::raw_t wv0[8], wv1[8], wv2[THREE ? 8 : 1];
+  GRows g0, g1, g2;
+  fetch(0, wv0, g0);
+  fetch(1, wv1, g1);
+  if constexpr (THREE) {
+    fetch(2, wv2, g2);
+    ISSUE_FENCE();
+    combine(0, wv0, g0);
+    fetch(3, wv0, g0);
+    ISSUE_FENCE();
+    combine(1, wv1, g1);
+    combine(2, wv2, g2);
+    combine(3, wv0, g0);
+  } else {
+    ISSUE_FENCE();
+    combine(0, wv0, g0);
+    fetch(2, wv0, g0);
+    ISSUE_FENCE();
+    combine(1, wv1, g1);
+    fetch(3, wv1, g1);
+    ISSUE_FENCE();
+    combine(2, wv0, g0);
+    combine(3, wv1, g1);
+  }
 }
 
 hipError_t launch_proj_up_wide(const DevCtx& d, const ProjTile* tiles, int ntiles, const uint16_t* b_hi, const uint16_t* b_lo,
@@ -1392,13 +1446,21 @@ hipError_t launch_proj_up_wide(const DevCtx& d, const ProjTile* tiles, int ntile
   constexpr int LDS_BYTES = 3 * 24 * 1024;
   static bool raised = false;
   if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_up_wide<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_up_wide<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
+    const void* kernels[4] = {reinterpret_cast<const void*>(k_proj_up_wide<false, false>), reinterpret_cast<const void*>(k_proj_up_wide<true, false>),
+                              reinterpret_cast<const void*>(k_proj_up_wide<false, true>), reinterpret_cast<const void*>(k_proj_up_wide<true, true>)};
+    for (const void* k : kernels) {
+      hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+      if (e != hipSuccess) return e;
+    }
     raised = true;
   }
-  if (ua.w_bf16) hipLaunchKernelGGL(k_proj_up_wide<true>, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo, ua);
-  else hipLaunchKernelGGL(k_proj_up_wide<false>, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo, ua);
+  const bool with_g = ua.coef_g != 0.f || ua.target_err == 1;
+  if (with_g && ua.g_is_f32) return hipErrorInvalidValue;      // the gradient-term epilogue here reads bf16 gradients
+  if (ua.target_err == 2 || ua.outer || ua.colscale == 2) return hipErrorInvalidValue;
+#define LORDO_WIDE(WBFV, GV) hipLaunchKernelGGL((k_proj_up_wide<WBFV, GV>), dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo, ua)
+  if (ua.w_bf16) { if (with_g) LORDO_WIDE(true, true); else LORDO_WIDE(true, false); }
+  else { if (with_g) LORDO_WIDE(false, true); else LORDO_WIDE(false, false); }
+#undef LORDO_WIDE
   return hipGetLastError();
 }
 

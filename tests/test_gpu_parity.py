@@ -162,6 +162,27 @@ def test_local_steps_ranks_from_256_up_ragged_edges(torch):
     print("ranks >= 256:", worst, flush=True)
 
 
+@pytest.mark.parametrize("variant", ["full_qhm", "ef", "global", "global_fp32_grads"])
+def test_local_steps_ranks_from_256_up_gradient_term(torch, variant):
+    """Every rank >= 256 with the epilogues that read a gradient tile on the 256 x 128 tiles: the full-rank QHM update
+    (Sec. 3.2), the residual of the error feedback (Alg. 1), both (LoRDO-Global); with fp32 gradients the 128 x 128
+    kernel takes these launches.  Columns are multiples of 4 (the four-column accesses of these epilogues), otherwise
+    ragged: rows no multiple of 256 or 32, a rank that is no multiple of 32."""
+    from paper_2602_04396_amd import lordo
+    shapes = [(520, 392, 256), (300, 260, 257), (257, 132, 256), (1100, 644, 320), (256, 128, 256)]
+    bf16 = variant != "global_fp32_grads"
+    qhm = "none" if variant == "ef" else "full"
+    ef = variant != "full_qhm"
+    kw = dict(omega=0.8 if qhm == "full" else 1.0, error_feedback=ef)
+    pair = Pair(torch, shapes, _weights(shapes, 18), orc.Hyper(qhm_mode=qhm, **kw),
+                lordo.hparams(qhm_mode=2 if qhm == "full" else 0, grad_dtype=lordo.BF16 if bf16 else lordo.F32, **kw), _rand_Q(shapes, 18))
+    gens = _spiked(shapes, 18, 8, bf16=bf16)
+    for t in range(3):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3 * (1 + t), grad_scale=0.9, bf16=bf16, first_step_patch=(t == 0))
+        worst = pair.compare_local(TOL)
+    print(f"ranks >= 256, {variant}:", worst, flush=True)
+
+
 def test_local_steps_identity_init_and_grad_scale(torch):
     """Q_0 = first r columns of I (the library's own initial state), grad_scale != 1."""
     from paper_2602_04396_amd import lordo
