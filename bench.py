@@ -66,6 +66,9 @@ def parse():
                     help="storage type of the weights (bf16: updates formed in fp32 and rounded once; update cases plain, low-qhm, ef, local)")
     ap.add_argument("--err-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the error-feedback residual E (update cases ef and global)")
+    ap.add_argument("--calibrate-gemm", action="store_true",
+                    help="only time the library's plain bf16 GEMM (torch.matmul / bmm) at the shapes of the c4 projections and at "
+                         "8192^3: what a library contraction reaches on this box with random operands (context for the issued rates)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 1 GiB device copies (known traffic) to scale the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
@@ -440,6 +443,26 @@ def main():
     import torch
     from paper_2602_04396_amd import lordo, synth
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_gemm:
+        def rate(fn, flops, reps):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return flops / ((time.perf_counter() - t0) / reps) / 1e12
+        bf = dict(device="cuda", dtype=torch.bfloat16)
+        out = {"calibration": "library bf16 GEMM (torch.matmul / torch.bmm, fp32 accumulate, bf16 output, standard-normal operands), TFLOP/s"}
+        a, b = torch.randn(8192, 8192, **bf), torch.randn(8192, 8192, **bf)
+        out["square_8192"] = rate(lambda: a @ b, 2 * 8192 ** 3, 10)
+        a, b = torch.randn(128, 4096, 512, **bf), torch.randn(128, 512, 4096, **bf)       # the 128 matrices of 4096 x 4096 of c4
+        out["up_shape_128x(4096x512x4096)"] = rate(lambda: torch.bmm(a, b), 2 * 128 * 4096 * 512 * 4096, 5)
+        a, b = torch.randn(64, 512, 4096, **bf), torch.randn(64, 4096, 11008, **bf)       # the 64 matrices of 4096 x 11008
+        out["down_shape_64x(512x4096x11008)"] = rate(lambda: torch.bmm(a, b), 2 * 64 * 512 * 4096 * 11008, 5)
+        print(json.dumps(out))
+        return
     if args.calibrate_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")        # 1 GiB, far beyond every cache
         b = torch.empty_like(a)
