@@ -546,9 +546,12 @@ def main():
         "metric": "full-model low-rank optimizer step ms",
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 MFMA operands (fp32 state split hi+lo), f32 accumulate and state",
+        "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[cfg] + (f", rank override {args.rank}" if args.rank else ""),
+                   "arithmetic": "bf16 matrix-core products with fp32 accumulation; fp32 operands (Q, N, the moments' inputs) enter as "
+                                 "bf16 hi + lo planes, so that results hold the 1e-4 bound against the float64 oracle; state and weights fp32"
+                                 + (" (weights stored in bf16)" if args.param_dtype == "bf16" else ""),
                    "matrices": len(shapes), "params": sum(p * q for p, q, r in shapes),
                    "timed_region": ("local steps only; one refresh and one outer step are event-timed on their own after it"
                                     if not (refresh_every or outer_every) else
