@@ -700,7 +700,10 @@ void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan&
   // the launch has several rounds of workgroups and the epilogue of one overlaps the main loop of
   // another; a launch that needs split-K is a single round of workgroups in lock step, where the
   // stand-alone kernel is as fast and leaves the down-projection shorter.
-  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && hp.qhm_mode != 2 && !hp.uplink_buffer && !hp.error_feedback && !P.any_tr;
+  // The 256-rank tiles also write what the full-rank QHM update and the error feedback need from that pass (column
+  // sums of the denominators, operand planes of g); the 128-rank kernel has no registers to spare for them.
+  const bool fuse_adam = P.down_pipe && P.nsplit == 1 && !hp.uplink_buffer && !P.any_tr &&
+                         (P.down_pipe == 2 || (hp.qhm_mode != 2 && !hp.error_feedback));
   P.adam_first = fuse_adam ? lr : 0;
   P.glow = A.take(sizeof(float) * lr * P.nsplit);
   P.u = A.take(sizeof(float) * lr);

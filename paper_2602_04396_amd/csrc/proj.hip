@@ -205,10 +205,17 @@ struct FusedAdam {
   uint16_t* n_lo;
   float b1, omb1, b2, omb2, inv_c1, inv_c2, eps;
   float qw, qg;               // update bracket (qw u_hat + qg g) / den: 1, 0 for "No QHM"; omega, 1 - omega for low-rank QHM
+  // 256-rank tiles only (the 128-rank kernel has no registers to spare):
+  uint16_t* g_hi;             // error feedback: the bf16 hi / lo operand planes of g for the residual update (else null)
+  uint16_t* g_lo;
+  float* colpart;             // full-rank QHM: per column and rank block of 32, the sum of sqrt(v_hat) + eps (else null)
 };
 
-__device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f32x4 uu, f32x4 vv) {
+// Returns the sum of the four denominators sqrt(v_hat) + eps (the full-rank QHM scale is their mean over the rank).
+template <bool EXTRA>
+__device__ __forceinline__ float adam4(const FusedAdam& f, int64_t at, f32x4 g, f32x4 uu, f32x4 vv) {
   uint32_t hi[4], lo[4];
+  float dsum = 0.f;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float un = fmaf(f.b1, uu[e], f.omb1 * g[e]);
@@ -216,6 +223,7 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
     uu[e] = un;
     vv[e] = vn;
     const float den = sqrtf(vn * f.inv_c2) + f.eps;
+    dsum += den;
     // with qw = 1, qg = 0 bit-identical to u_hat / den; eps == 0 and no gradient yet (e.g. the padding): zero, not 0 / 0
     const float nn = den == 0.f ? 0.f : fmaf(f.qg, g[e], f.qw * (un * f.inv_c1)) / den;
     hi[e] = f2bf_rne(nn);
@@ -228,6 +236,28 @@ __device__ __forceinline__ void adam4(const FusedAdam& f, int64_t at, f32x4 g, f
   pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
   *TO_GLOBAL(u32x2, f.n_hi + at) = ph;
   *TO_GLOBAL(u32x2, f.n_lo + at) = pl;
+  if constexpr (EXTRA) {
+    if (f.g_hi) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        hi[e] = f2bf_rne(g[e]);
+        lo[e] = f2bf_rne(g[e] - __uint_as_float(hi[e] << 16));
+      }
+      ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16);
+      pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
+      *TO_GLOBAL(u32x2, f.g_hi + at) = ph;
+      *TO_GLOBAL(u32x2, f.g_lo + at) = pl;
+    }
+  }
+  return dsum;
+}
+// Full-rank QHM scale from inside a fused epilogue: `dsum` holds the lane's sixteen denominators of one accumulator
+// block (rank indices 8 vq + 4 (lane / 32) + e of column lane % 32); the other sixteen rank indices of the block sit
+// in lane ^ 32.  Fixed order of additions.
+__device__ __forceinline__ void store_colpart(const FusedAdam& f, const MatDev& m, int nbg, int mbg, int lane, float dsum) {
+  const float other = __shfl_xor(dsum, 32);
+  const float total = (lane < 32) ? dsum + other : other + dsum;
+  if (lane < 32) f.colpart[m.lr_off / 32 + ((int64_t)nbg * (m.rp / 32) + mbg) * 32 + lane] = total;
 }
 
 // 8 waves, 256-column tiles: wave w owns column half w / 4 (four column blocks) and RB rank blocks,
@@ -481,6 +511,7 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
     ISSUE_FENCE();
     if (!live(idx)) continue;
     const int rb = idx >> 2, a = idx & 3;
+    float dsum = 0.f;
 #pragma unroll
     for (int vq = 0; vq < 4; ++vq) {
       const int64_t o = offset_of(idx, vq);
@@ -488,7 +519,10 @@ __global__ __launch_bounds__(512) void k_proj_down_pipe(DevCtx d, const ProjTile
       val.x = osc * acc[rb][a][4 * vq];     val.y = osc * acc[rb][a][4 * vq + 1];
       val.z = osc * acc[rb][a][4 * vq + 2]; val.w = osc * acc[rb][a][4 * vq + 3];
       *reinterpret_cast<GAS f32x4*>(out + o) = val;
-      adam4(fa, base + o, val, uu[idx & PF][vq], vv[idx & PF][vq]);
+      dsum += adam4<RB == 2>(fa, base + o, val, uu[idx & PF][vq], vv[idx & PF][vq]);
+    }
+    if constexpr (RB == 2) {
+      if (fa.colpart) store_colpart(fa, m, t.n0 / 32 + 4 * nh + a, mbg[rb], lane, dsum);
     }
   }
 }
@@ -682,6 +716,7 @@ __global__ __launch_bounds__(512) void k_proj_down_tr(DevCtx d, const ProjTile* 
     ISSUE_FENCE();
     if (!live(idx)) continue;
     const int rb = idx >> 2, a = idx & 3;
+    float dsum = 0.f;
 #pragma unroll
     for (int vq = 0; vq < 4; ++vq) {
       const int64_t o = offset_of(idx, vq);
@@ -689,7 +724,10 @@ __global__ __launch_bounds__(512) void k_proj_down_tr(DevCtx d, const ProjTile* 
       val.x = grad_scale * acc[rb][a][4 * vq];     val.y = grad_scale * acc[rb][a][4 * vq + 1];
       val.z = grad_scale * acc[rb][a][4 * vq + 2]; val.w = grad_scale * acc[rb][a][4 * vq + 3];
       *reinterpret_cast<GAS f32x4*>(out + o) = val;
-      if (fuse) adam4(fa, base + o, val, uu[idx & 1][vq], vv[idx & 1][vq]);
+      if (fuse) dsum += adam4<RB == 2>(fa, base + o, val, uu[idx & 1][vq], vv[idx & 1][vq]);
+    }
+    if constexpr (RB == 2) {
+      if (fuse && fa.colpart) store_colpart(fa, m, t.n0 / 32 + 4 * nh + a, mbg[rb], lane, dsum);
     }
   }
 }
@@ -755,6 +793,7 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
       fa.b1 = fuse->a.b1; fa.omb1 = fuse->a.omb1; fa.b2 = fuse->a.b2; fa.omb2 = fuse->a.omb2;
       fa.inv_c1 = fuse->a.inv_c1; fa.inv_c2 = fuse->a.inv_c2; fa.eps = fuse->a.eps;
       fa.qw = fuse->a.qw; fa.qg = fuse->a.qg;
+      fa.g_hi = fuse->a.g_hi; fa.g_lo = fuse->a.g_lo; fa.colpart = fuse->a.colpart;
     }
     // 256-rank tiles (ranks from 256 up, where the matrix cores bound the kernel): gradient by global-to-LDS loads,
     // transposed while it is read from LDS -- 8 to 11 % faster there than staging through registers; with 128-rank

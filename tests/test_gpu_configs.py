@@ -49,7 +49,7 @@ class Sampled:
             sm = self.s[i]
             st, cols = sm["st"], sm["cols"]
             first = st.t == 0
-            sm["W"] = orc.local_step(st, sm["W"], _f64(G[i][:, cols]), lr, self.ohp)
+            sm["W"] = orc.local_step(st, before[i], _f64(G[i][:, cols]), lr, self.ohp)      # from the weights as the library holds them
             where = f"{tag}, matrix {i} {self.shapes[i]}"
             assert rel_l2(self.cols_of(i, lordo.STATE_GLOW), st.last_g) <= TOL, "g, " + where
             assert rel_l2(self.cols_of(i, lordo.STATE_U), st.u) <= TOL, "u, " + where
@@ -63,10 +63,14 @@ class Sampled:
                 assert amb.sum() <= 1e-3 * amb.size + 3
                 check_first_step_closed_form(n_gpu, self.cols_of(i, lordo.STATE_GLOW), self.ohp, amb)
                 N_new = np.where(amb, n_gpu, st.last_N)
-                sm["W"] = sm["W"] + lr * st.Q @ (st.last_N - N_new)
+                share = self.ohp.omega if self.ohp.qhm_mode == "full" else 1.0           # weight of Q N in the update
+                sm["W"] = sm["W"] + lr * share * st.Q @ (st.last_N - N_new)
                 st.last_N = N_new
             assert rel_l2(n_gpu, st.last_N) <= TOL, "N, " + where
-            assert rel_l2(dW_gpu, -lr * st.Q @ st.last_N) <= TOL, "weight change, " + where
+            assert rel_l2(dW_gpu, sm["W"] - before[i]) <= TOL, "weight change, " + where
+            if self.ohp.error_feedback:     # held relative to the matrix that was projected (||A||^2 = ||g||^2 + ||E||^2)
+                scale = np.sqrt(np.sum(st.last_g ** 2) + np.sum(st.E ** 2))
+                assert np.linalg.norm(self.cols_of(i, lordo.STATE_ERR) - st.E) <= TOL * scale, "E, " + where
 
     def outer_step(self, Wp, Dp, D, tag):
         lordo = self.lordo
@@ -122,7 +126,7 @@ def _run_model_config(cfg, power_iters, **update):
     from paper_2602_04396_amd import lordo
     shapes, W, G, Omega, D, grad_dtype = bench.build_workload(torch, lordo, synth, cfg, None, 2)
     kw = dict(outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True, power_iters=power_iters)
-    hp = lordo.hparams(seed=synth.seed_for(int(cfg[1:]), 77), **kw, **{k: ({"low": 1}[v] if k == "qhm_mode" else v) for k, v in update.items()})
+    hp = lordo.hparams(seed=synth.seed_for(int(cfg[1:]), 77), **kw, **{k: ({"low": 1, "full": 2}[v] if k == "qhm_mode" else v) for k, v in update.items()})
     ohp = orc.Hyper(**kw, **update)
     opt = lordo.Lordo(shapes, hp, W, torch)
     Wp = opt.ptrs(W)
@@ -160,6 +164,12 @@ def test_c3_low_rank_qhm_in_the_fused_epilogue():
     """The same sequence with the low-rank QHM update (Alg. 1, second update case): at this launch shape its bracket
     (omega u_hat + (1 - omega) g) / (sqrt(v_hat) + eps) is formed in the epilogue of the down-projection."""
     _run_model_config("c3", synth.CONFIG_DEFAULTS["c3"]["power_iters"], qhm_mode="low", omega=0.8)
+
+
+def test_c3_lordo_global_in_the_fused_epilogue():
+    """Full-rank QHM with error feedback (Sec. 3.2, Alg. 1: the paper's LoRDO-Global): at this launch shape the column
+    sums of the QHM scale and the operand planes of g for the residual update come out of the down-projection's epilogue."""
+    _run_model_config("c3", synth.CONFIG_DEFAULTS["c3"]["power_iters"], qhm_mode="full", omega=0.8, error_feedback=True)
 
 
 def test_c4_full_size_sampled_columns():

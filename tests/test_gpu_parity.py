@@ -162,14 +162,18 @@ def test_local_steps_ranks_from_256_up_ragged_edges(torch):
     print("ranks >= 256:", worst, flush=True)
 
 
+@pytest.mark.parametrize("shape_set", ["ragged", "one_slice"])
 @pytest.mark.parametrize("variant", ["full_qhm", "ef", "global", "global_fp32_grads"])
-def test_local_steps_ranks_from_256_up_gradient_term(torch, variant):
+def test_local_steps_ranks_from_256_up_gradient_term(torch, variant, shape_set):
     """Every rank >= 256 with the epilogues that read a gradient tile on the 256 x 128 tiles: the full-rank QHM update
     (Sec. 3.2), the residual of the error feedback (Alg. 1), both (LoRDO-Global); with fp32 gradients the 128 x 128
     kernel takes these launches.  Columns are multiples of 4 (the four-column accesses of these epilogues), otherwise
     ragged: rows no multiple of 256 or 32, a rank that is no multiple of 32."""
     from paper_2602_04396_amd import lordo
     shapes = [(520, 392, 256), (300, 260, 257), (257, 132, 256), (1100, 644, 320), (256, 128, 256)]
+    if shape_set == "one_slice":      # no matrix taller than 256 rows: no split-K, so the moment update -- with the column sums of the
+        shapes = [(256, 520, 256), (256, 388, 250), (250, 132, 250)]      # full-rank QHM scale and the operand planes of g -- runs
+                                                                          # in the epilogue of the down-projection
     bf16 = variant != "global_fp32_grads"
     qhm = "none" if variant == "ef" else "full"
     ef = variant != "full_qhm"
@@ -180,7 +184,7 @@ def test_local_steps_ranks_from_256_up_gradient_term(torch, variant):
     for t in range(3):
         pair.local_step([g.draw(t) for g in gens], lr=1e-3 * (1 + t), grad_scale=0.9, bf16=bf16, first_step_patch=(t == 0))
         worst = pair.compare_local(TOL)
-    print(f"ranks >= 256, {variant}:", worst, flush=True)
+    print(f"ranks >= 256, {variant}, {shape_set}:", worst, flush=True)
 
 
 def test_local_steps_identity_init_and_grad_scale(torch):
