@@ -48,6 +48,18 @@ __device__ __forceinline__ uint32_t f2bf_rne(float x) {
 }
 
 
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {       // the hardware's packed round-to-nearest-even conversion
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float f32x2_ __attribute__((ext_vector_type(2)));
+  const f32x2_ v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+// two fp32 values -> packed bf16 hi parts (nearest-even) and packed bf16 parts of what is left: x = hi + lo to 2^-17
+__device__ __forceinline__ void split2_bf(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  hi = pack_bf16_rne(x0, x1);
+  lo = pack_bf16_rne(x0 - __uint_as_float(hi << 16), x1 - __uint_as_float(hi & 0xffff0000u));
+}
+
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Compiler-level fence: keeps the loads issued before it from being sunk to their first use
@@ -132,17 +144,17 @@ __device__ __forceinline__ void store_gstage(const GStage<GF32>& st, u32x4* lds_
     lds_hi[slot] = c0;
     lds_hi[slot + 1] = c1;
   } else {
-    uint32_t h0[8], l0[8], h1[8], l1[8];
+    // column 0 of the lane: floats st.x[0], st.x[2], ...; column 1: st.x[1], st.x[3], ...; rows pair up into packed words
+    uint32_t h0[4], l0[4], h1[4], l1[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float a = __uint_as_float(st.x[2 * i]), b = __uint_as_float(st.x[2 * i + 1]);
-      h0[i] = f2bf_rne(a); l0[i] = f2bf_rne(a - __uint_as_float(h0[i] << 16));
-      h1[i] = f2bf_rne(b); l1[i] = f2bf_rne(b - __uint_as_float(h1[i] << 16));
+    for (int i = 0; i < 4; ++i) {
+      split2_bf(__uint_as_float(st.x[4 * i]), __uint_as_float(st.x[4 * i + 2]), h0[i], l0[i]);
+      split2_bf(__uint_as_float(st.x[4 * i + 1]), __uint_as_float(st.x[4 * i + 3]), h1[i], l1[i]);
     }
-    lds_hi[slot] = mk4(h0[0] | (h0[1] << 16), h0[2] | (h0[3] << 16), h0[4] | (h0[5] << 16), h0[6] | (h0[7] << 16));
-    lds_hi[slot + 1] = mk4(h1[0] | (h1[1] << 16), h1[2] | (h1[3] << 16), h1[4] | (h1[5] << 16), h1[6] | (h1[7] << 16));
-    lds_lo[slot] = mk4(l0[0] | (l0[1] << 16), l0[2] | (l0[3] << 16), l0[4] | (l0[5] << 16), l0[6] | (l0[7] << 16));
-    lds_lo[slot + 1] = mk4(l1[0] | (l1[1] << 16), l1[2] | (l1[3] << 16), l1[4] | (l1[5] << 16), l1[6] | (l1[7] << 16));
+    lds_hi[slot] = mk4(h0[0], h0[1], h0[2], h0[3]);
+    lds_hi[slot + 1] = mk4(h1[0], h1[1], h1[2], h1[3]);
+    lds_lo[slot] = mk4(l0[0], l0[1], l0[2], l0[3]);
+    lds_lo[slot + 1] = mk4(l1[0], l1[1], l1[2], l1[3]);
   }
 }
 
@@ -214,7 +226,7 @@ struct FusedAdam {
 // Returns the sum of the four denominators sqrt(v_hat) + eps (the full-rank QHM scale is their mean over the rank).
 template <bool EXTRA>
 __device__ __forceinline__ float adam4(const FusedAdam& f, int64_t at, f32x4 g, f32x4 uu, f32x4 vv) {
-  uint32_t hi[4], lo[4];
+  float nn[4];
   float dsum = 0.f;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -225,26 +237,21 @@ __device__ __forceinline__ float adam4(const FusedAdam& f, int64_t at, f32x4 g, 
     const float den = sqrtf(vn * f.inv_c2) + f.eps;
     dsum += den;
     // with qw = 1, qg = 0 bit-identical to u_hat / den; eps == 0 and no gradient yet (e.g. the padding): zero, not 0 / 0
-    const float nn = den == 0.f ? 0.f : fmaf(f.qg, g[e], f.qw * (un * f.inv_c1)) / den;
-    hi[e] = f2bf_rne(nn);
-    lo[e] = f2bf_rne(nn - __uint_as_float(hi[e] << 16));
+    nn[e] = den == 0.f ? 0.f : fmaf(f.qg, g[e], f.qw * (un * f.inv_c1)) / den;
   }
   __builtin_nontemporal_store(uu, TO_GLOBAL(f32x4, f.u + at));       // next use is a whole step away
   __builtin_nontemporal_store(vv, TO_GLOBAL(f32x4, f.v + at));
-  u32x2 ph, pl;
-  ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16);
-  pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
+  uint32_t h0, l0, h1, l1;
+  split2_bf(nn[0], nn[1], h0, l0);
+  split2_bf(nn[2], nn[3], h1, l1);
+  u32x2 ph = {h0, h1}, pl = {l0, l1};
   *TO_GLOBAL(u32x2, f.n_hi + at) = ph;
   *TO_GLOBAL(u32x2, f.n_lo + at) = pl;
   if constexpr (EXTRA) {
     if (f.g_hi) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        hi[e] = f2bf_rne(g[e]);
-        lo[e] = f2bf_rne(g[e] - __uint_as_float(hi[e] << 16));
-      }
-      ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16);
-      pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16);
+      split2_bf(g[0], g[1], h0, l0);
+      split2_bf(g[2], g[3], h1, l1);
+      ph = u32x2{h0, h1}; pl = u32x2{l0, l1};
       *TO_GLOBAL(u32x2, f.g_hi + at) = ph;
       *TO_GLOBAL(u32x2, f.g_lo + at) = pl;
     }
@@ -822,11 +829,6 @@ template <> struct WAcc<false> {
     __builtin_amdgcn_raw_buffer_store_b128(u32x4{__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)}, r, voff, soff, STREAM);
   }
 };
-__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {       // the hardware's packed round-to-nearest-even conversion
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 template <> struct WAcc<true> {
   static constexpr uint32_t ES = 2;
   typedef u32x2 raw_t;
