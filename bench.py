@@ -382,6 +382,25 @@ def class_ms(kernels):
     return {k: round(v["avg_ms"], 5) for k, v in kernels.items()}
 
 
+def graph_replay_ms(torch, wl, n):
+    """Milliseconds per local step when the step is recorded once per gradient set into a HIP graph and replayed (the
+    step count and the bias corrections advance on the device, so replays are successive steps)."""
+    graphs = []
+    for Gp in wl.Gp:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            wl.opt.local_step(wl.Wp, Gp, 1e-3)
+        graphs.append(g)
+    for g in graphs:
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    return 1e3 * (time.perf_counter() - t0) / n
+
+
 def extra_configs(torch, lordo, synth, args, skip_cfg):
     """Per-class times of the other workloads of the table, so that one run covers it: c2, c3 and the rank sweep on
     the single largest matrix (c5) with one and two power iterations in the refresh.  Kernel-class averages only."""
@@ -395,7 +414,14 @@ def extra_configs(torch, lordo, synth, args, skip_cfg):
         wl.steps(warm, 0, 0)
         work = algorithmic_work(wl.shapes, 4 if cfg == "c1" else 2, w_bytes=2 if args.param_dtype == "bf16" else 4)
         kernels, _ = wl.profiled(steps, 0, 0, work)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        wl.steps(steps, 0, 0)
+        torch.cuda.synchronize()
+        step_ms = 1e3 * (time.perf_counter() - t0) / steps
         out.append({"workload": cfg, "rank": wl.shapes[0][2], "power_iters": wl.power_iters, "ms": class_ms(kernels),
+                    "step_ms": round(step_ms, 5),
+                    "step_ms_graph_replay": round(graph_replay_ms(torch, wl, steps), 5) if cfg in ("c1", "c2") else None,
                     "GBps": {k: round(v["GBps"]) for k, v in kernels.items() if "GBps" in v},
                     "adam_fused": "fused_into" in kernels.get("adam", {}),
                     "TFLOPps": {k: round(v["TFLOPps"], 1) for k, v in kernels.items() if "TFLOPps" in v}})

@@ -28,12 +28,16 @@
  *     moments as they were (the refresh that broke down included): the optimizer goes
  *     on in the old subspace until the caller polls, which clears the latch.
  *   - Stream capture: the compute calls enqueue kernels only (no allocation, no memset, no
- *     host synchronisation), so they can be recorded into a HIP graph.  The step count, the
- *     bias corrections 1 - beta^t derived from it, the learning rate and the gradient scale
- *     travel as kernel arguments, and the step count advances on the host when a call is
- *     ISSUED: a recorded lordo_local_step replays with the values of the time it was
- *     recorded.  Replaying is therefore exact only with bias_correction = 0 and a fixed
- *     learning rate; otherwise record again (or update the kernel nodes) whenever they change.
+ *     host synchronisation), so they can be recorded into a HIP graph.  The step count and
+ *     the bias corrections 1 - beta^t derived from it live in device memory and are advanced
+ *     by a kernel at the head of every local step, so a recorded lordo_local_step counts its
+ *     REPLAYS: replaying it k times is k local steps (on whatever the gradient buffers hold
+ *     at each replay).  The learning rate and the gradient scale travel as kernel arguments:
+ *     a replay uses the values of the recording.  lordo_get_step returns the number of
+ *     local steps ISSUED through the API (recording counts once, replays do not); after
+ *     replays, tell the context with lordo_set_step before a call that depends on it on the
+ *     host (a refresh skips the moment rotation while that count is 0).  lordo_set_step
+ *     takes effect at the head of the next compute call: do not record that call.
  *   - There is no CPU fallback: without a GPU every compute call returns LORDO_EHIP.
  */
 #ifndef LORDO_H

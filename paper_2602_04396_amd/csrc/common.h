@@ -143,8 +143,19 @@ hipError_t launch_gemm32(const DevCtx& d, const GemmDesc* descs, const GemmTile*
 hipError_t launch_gemm_reduce(const DevCtx& d, const GemmDesc* descs, int ndescs, hipStream_t s);
 // elementwise.hip
 // Elements at flat position >= grp_start[i] are the sum of grp_nsplit[i] split-K slices of g.
+// Step count and the bias corrections 1 - beta^t derived from it (Sec. 2), kept in device memory and advanced by a
+// kernel at the head of every local step: a local step recorded into a HIP graph then counts its REPLAYS, which
+// values passed as kernel arguments could not.
+struct StepDev {
+  int64_t t;
+  float inv_c1, inv_c2;   // 1 / (1 - beta1^t), 1 / (1 - beta2^t); 1 without bias correction
+  float c1, c2;
+};
+hipError_t launch_step(StepDev* sd, double beta1, double beta2, int bias_correction, int64_t set_to, hipStream_t s);
+
 struct AdamArgs {
-  float b1, omb1, b2, omb2, inv_c1, inv_c2, eps;
+  float b1, omb1, b2, omb2, eps;
+  const StepDev* step;    // bias corrections of the current step
   int32_t grp_nsplit[4];
   int64_t grp_start[4];
   int64_t split_stride;
@@ -191,8 +202,8 @@ hipError_t launch_stable_rank(const DevCtx& d, float* out, int which, hipStream_
 hipError_t launch_jacobi_svd(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s);
 hipError_t launch_jacobi_svd_blocked(const DevCtx& d, int rmax, int64_t rank_sq_sum, bool top_value_only, int* flags, hipStream_t s);
 hipError_t launch_diag_inverses(const DevCtx& d, hipStream_t s);
-hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s);
-hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s);
+hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, const StepDev* step, hipStream_t s);
+hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, const StepDev* step, hipStream_t s);
 hipError_t launch_q_from_y(const DevCtx& d, int ybuf, hipStream_t s);
 hipError_t launch_y_from_ext(const DevCtx& d, hipStream_t s);
 hipError_t launch_pack_y(const DevCtx& d, int ybuf, hipStream_t s);

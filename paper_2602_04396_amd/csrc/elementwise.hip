@@ -60,6 +60,7 @@ __global__ __launch_bounds__(256) void k_adam4(const float* __restrict__ glow, f
   if (!COLSUM && !live) return;
   const int64_t base = a.first + qidx * 4;
   float dsum = 0.f;
+  const float inv_c1 = a.step->inv_c1, inv_c2 = a.step->inv_c2;      // uniform: scalar loads
   if (live) {
   f32x4n g = __builtin_nontemporal_load(reinterpret_cast<const f32x4n*>(glow + base));
   int nsplit = a.grp_nsplit[0];
@@ -77,13 +78,13 @@ __global__ __launch_bounds__(256) void k_adam4(const float* __restrict__ glow, f
     const float vn = fmaf(a.b2, vv[e], a.omb2 * (g[e] * g[e]));
     uu[e] = un;
     vv[e] = vn;
-    const float den = sqrtf(vn * a.inv_c2) + a.eps;
+    const float den = sqrtf(vn * inv_c2) + a.eps;
     dsum += den;
     // Alg. 1 update bracket: u_hat / den, or (omega u_hat + (1 - omega) g) / den for the low-rank
     // quasi-hyperbolic case; with qw = 1, qg = 0 the value is bit-identical to u_hat / den
     // den == 0 needs eps == 0 and a second moment of exactly zero, i.e. every gradient so far was zero there (always
     // true in the zero padding of the arena): the update is then zero, not 0 / 0
-    const float nn = den == 0.f ? 0.f : fmaf(a.qg, g[e], a.qw * (un * a.inv_c1)) / den;
+    const float nn = den == 0.f ? 0.f : fmaf(a.qg, g[e], a.qw * (un * inv_c1)) / den;
     split_bf(nn, hi[e], lo[e]);
     nv[e] = nn;
   }
@@ -158,6 +159,26 @@ hipError_t launch_adam(const float* glow, float* u, float* v, uint16_t* n_hi, ui
   unsigned blocks = (unsigned)((ngroups + 255) / 256);
   if (a.colpart) hipLaunchKernelGGL(k_adam4<true>, dim3(2 * blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, 2 * ngroups, a);
   else hipLaunchKernelGGL(k_adam4<false>, dim3(2 * blocks), dim3(256), 0, s, glow, u, v, n_hi, n_lo, 2 * ngroups, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// step counter on the device: t <- t + 1 (set_to < 0) or t <- set_to, and the bias corrections of the new t
+// (Sec. 2: u_hat = u / (1 - beta1^t), v_hat = v / (1 - beta2^t)), formed in double and rounded to fp32 once
+// ---------------------------------------------------------------------------------------
+__global__ void k_step(StepDev* sd, double beta1, double beta2, int bias_correction, int64_t set_to) {
+  const int64_t t = set_to < 0 ? sd->t + 1 : set_to;
+  double c1 = 1.0, c2 = 1.0;
+  if (bias_correction && t > 0) {
+    c1 = 1.0 - pow(beta1, (double)t);
+    c2 = 1.0 - pow(beta2, (double)t);
+  }
+  sd->t = t;
+  sd->c1 = (float)c1; sd->c2 = (float)c2;
+  sd->inv_c1 = (float)(1.0 / c1); sd->inv_c2 = (float)(1.0 / c2);
+}
+hipError_t launch_step(StepDev* sd, double beta1, double beta2, int bias_correction, int64_t set_to, hipStream_t s) {
+  hipLaunchKernelGGL(k_step, dim3(1), dim3(1), 0, s, sd, beta1, beta2, bias_correction, set_to);
   return hipGetLastError();
 }
 
@@ -1356,8 +1377,9 @@ hipError_t launch_jacobi_svd_blocked(const DevCtx& d, int rmax, int64_t rank_sq_
 // side is then read in 32-byte pieces, which costs far less than scattered partial-line writes).
 // k_rot_post keeps the flat numbering: its writes go to the blocked arrays, contiguous over threads.
 __global__ __launch_bounds__(256) void k_rot_pre(DevCtx d, const float* __restrict__ u, const float* __restrict__ v,
-                                                 float inv_c1, float inv_c2) {
+                                                 const StepDev* __restrict__ step) {
   if (mat_skipped(d, blockIdx.y)) return;
+  const float inv_c1 = step->inv_c1, inv_c2 = step->inv_c2;
   const MatDev& m = d.mats[blockIdx.y];
   float* uh = reinterpret_cast<float*>(d.arena + m.zw[2]);
   float* var = reinterpret_cast<float*>(d.arena + m.zw[3]);
@@ -1385,11 +1407,12 @@ __global__ __launch_bounds__(256) void k_rot_pre(DevCtx d, const float* __restri
     }
   }
 }
-hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, float inv_c1, float inv_c2, hipStream_t s) {
-  hipLaunchKernelGGL(k_rot_pre, dim3(256, d.n), dim3(256), 0, s, d, u, v, inv_c1, inv_c2);
+hipError_t launch_rot_pre(const DevCtx& d, const float* u, const float* v, const StepDev* step, hipStream_t s) {
+  hipLaunchKernelGGL(k_rot_pre, dim3(256, d.n), dim3(256), 0, s, d, u, v, step);
   return hipGetLastError();
 }
-__global__ __launch_bounds__(256) void k_rot_post(DevCtx d, float* __restrict__ u, float* __restrict__ v, float c1, float c2) {
+__global__ __launch_bounds__(256) void k_rot_post(DevCtx d, float* __restrict__ u, float* __restrict__ v, const StepDev* __restrict__ step) {
+  const float c1 = step->c1, c2 = step->c2;
   if (*d.flag != 0 || mat_skipped(d, blockIdx.y)) return;       // a breakdown is latched: the moments stay in the coordinates of the projection that stays
   const MatDev& m = d.mats[blockIdx.y];
   const float* a1 = reinterpret_cast<const float*>(d.arena + m.zw[0]);
@@ -1421,8 +1444,8 @@ __global__ __launch_bounds__(256) void k_rot_post(DevCtx d, float* __restrict__ 
     }
   }
 }
-hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, float c1, float c2, hipStream_t s) {
-  hipLaunchKernelGGL(k_rot_post, dim3(256, d.n), dim3(256), 0, s, d, u, v, c1, c2);
+hipError_t launch_rot_post(const DevCtx& d, float* u, float* v, const StepDev* step, hipStream_t s) {
+  hipLaunchKernelGGL(k_rot_post, dim3(256, d.n), dim3(256), 0, s, d, u, v, step);
   return hipGetLastError();
 }
 

@@ -63,7 +63,7 @@ struct Plan {
   int32_t grp_nsplit[4] = {1, 1, 1, 1};
   int64_t grp_start[4] = {0, INT64_MAX, INT64_MAX, INT64_MAX};
   // global regions (byte offsets)
-  int64_t flag, mats, ext, chunk_start, down_tiles, up_tiles, descs, gtiles, glow, u, v, n_hi, n_lo;
+  int64_t flag, step, mats, ext, chunk_start, down_tiles, up_tiles, descs, gtiles, glow, u, v, n_hi, n_lo;
   std::vector<MatDev> mat;
   std::vector<int64_t> chunk_start_h;
   std::vector<ProjTile> down_h, up_h, ytile_h;       // ytile: 128 rows x 128 ranks tiles of the products Y = Src B
@@ -609,6 +609,7 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
 void build_plan(const lordo_shape* shapes, int n, const lordo_hparams& hp, Plan& P) {
   Alloc A;
   P.flag = A.take(256);
+  P.step = A.take(256);
   P.mats = A.take(sizeof(MatDev) * n);
   P.ext = A.take(sizeof(void*) * EXT_COUNT * EXT_SLOTS * n);
   P.chunk_start = A.take(sizeof(int64_t) * (n + 1));
@@ -949,6 +950,13 @@ struct lordo_ctx {
   DevCtx dev{};
   int64_t t = 0;
   bool refreshed = false;        // a subspace refresh has run: R = Q_new^T Q_old of the last one is in the arena
+  bool step_dirty = false;       // the step count on the device has to be set from `t` (after lordo_set_step)
+  int sync_step(hipStream_t s) {
+    if (!step_dirty) return LORDO_OK;
+    if (launch_step(at<StepDev>(plan.step), hp.beta1, hp.beta2, hp.bias_correction, t, s) != hipSuccess) return LORDO_EHIP;
+    step_dirty = false;
+    return LORDO_OK;
+  }
   // lordo_refresh_subspace_local left grad_scale * G + E in the error buffer; the next local step must
   // come with the same gradient pointers and takes its projected matrix from the buffer alone
   bool grad_folded = false;
@@ -1077,6 +1085,8 @@ static int init_context(lordo_ctx** out, const lordo_shape* shapes, int32_t n, c
   INITCHK(launch_fill_zero(c->at<void>(P.flag), 256, s));
   INITCHK(launch_fill_zero(c->at<void>(P.ext), ((sizeof(void*) * EXT_COUNT * EXT_SLOTS * n + 255) & ~size_t(255)), s));
   INITCHK(launch_fill_zero(c->at<void>(P.glow), (int64_t)(P.down_tiles - P.glow), s));
+  INITCHK(launch_step(c->at<StepDev>(P.step), hp->beta1, hp->beta2, hp->bias_correction, 0, s));      // t = 0
+  c->step_dirty = false;
   INITCHK(launch_identity_q(c->dev, s));
   INITCHK(launch_pack_q(c->dev, 0, n, s));
   {
@@ -1144,15 +1154,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   const bool generic = P.down_generic;
   const double proj_scale = (folded || (generic && c->hp.error_feedback)) ? 0.0 : grad_scale;
   const int64_t t = c->t + 1;
-  double c1 = 1.0, c2 = 1.0;
-  if (c->hp.bias_correction) {
-    c1 = 1.0 - std::pow(c->hp.beta1, (double)t);
-    c2 = 1.0 - std::pow(c->hp.beta2, (double)t);
-  }
   AdamArgs a;
   a.b1 = (float)c->hp.beta1; a.omb1 = (float)(1.0 - c->hp.beta1);
   a.b2 = (float)c->hp.beta2; a.omb2 = (float)(1.0 - c->hp.beta2);
-  a.inv_c1 = (float)(1.0 / c1); a.inv_c2 = (float)(1.0 / c2);
+  a.step = c->at<StepDev>(P.step);        // the step count and 1 - beta^t live on the device: advanced below, by a kernel
   a.eps = (float)c->hp.eps;
   for (int i = 0; i < 4; ++i) { a.grp_nsplit[i] = P.grp_nsplit[i]; a.grp_start[i] = P.grp_start[i]; }
   a.split_stride = P.lr_total;
@@ -1182,7 +1187,10 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
       if ((reinterpret_cast<uintptr_t>(G[i]) & (g_f32 ? 15 : 7)) != 0) return LORDO_EINVAL;
   }
   // every argument and state check has passed: from here on kernels are enqueued
-  int rc = c->set_ext(EXT_W, W, s);
+  int rc = c->sync_step(s);
+  if (rc != LORDO_OK) return rc;
+  HIPCHK(launch_step(c->at<StepDev>(P.step), c->hp.beta1, c->hp.beta2, c->hp.bias_correction, -1, s));      // t <- t + 1
+  rc = c->set_ext(EXT_W, W, s);
   if (rc != LORDO_OK) return rc;
   rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
   if (rc != LORDO_OK) return rc;
@@ -1291,13 +1299,10 @@ static int run_refresh(lordo_ctx* c, int32_t src_dtype, hipStream_t s, bool fold
                        bool proj_kernels = false, bool stream_kernel = false, bool proj_tr = false) {
   Plan& P = c->plan;
   const bool rotate = c->t > 0;
-  double c1 = 1.0, c2 = 1.0;
-  if (c->hp.bias_correction && rotate) {
-    c1 = 1.0 - std::pow(c->hp.beta1, (double)c->t);
-    c2 = 1.0 - std::pow(c->hp.beta2, (double)c->t);
-  }
+  const double c1 = 1.0, c2 = 1.0;       // (the rotation passes read the bias corrections of the current step from the device)
+  int rc = c->sync_step(s);
+  if (rc != LORDO_OK) return rc;
   c->prof.begin(LORDO_K_REFRESH, s);
-  int rc = LORDO_OK;
   if (fold && launch_fold_grad(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, (float)fold_scale, c->hp.grad_dtype == LORDO_F32, s) != hipSuccess)
     rc = LORDO_EHIP;
   if (rc == LORDO_OK) rc = run_ops(c, P.ops, src_dtype, s, rotate, c1, c2, proj_kernels, stream_kernel, proj_tr);
@@ -1352,10 +1357,10 @@ static int run_ops(lordo_ctx* c, const std::vector<Op>& ops, int32_t src_dtype, 
         HIPCHK(launch_frob2(c->dev, c->at<int64_t>(P.chunk_start), P.nchunks, c->at<float>(P.frob_part), src_dtype == LORDO_F32, s));
         break;
       case OP_ROT_PRE:
-        HIPCHK(launch_rot_pre(c->dev, c->at<float>(P.u), c->at<float>(P.v), (float)(1.0 / c1), (float)(1.0 / c2), s));
+        HIPCHK(launch_rot_pre(c->dev, c->at<float>(P.u), c->at<float>(P.v), c->at<StepDev>(P.step), s));
         break;
       case OP_ROT_POST:
-        HIPCHK(launch_rot_post(c->dev, c->at<float>(P.u), c->at<float>(P.v), (float)c1, (float)c2, s));
+        HIPCHK(launch_rot_post(c->dev, c->at<float>(P.u), c->at<float>(P.v), c->at<StepDev>(P.step), s));
         break;
       case OP_Q_FROM_Y: HIPCHK(launch_q_from_y(c->dev, op.iarg, s)); break;
       case OP_PACK: HIPCHK(launch_pack_q(c->dev, 0, c->n, s)); break;
@@ -1728,6 +1733,7 @@ int lordo_get_step(lordo_ctx* c, int64_t* t) {
 int lordo_set_step(lordo_ctx* c, int64_t t) {
   if (!c || t < 0) return LORDO_EINVAL;
   c->t = t;
+  c->step_dirty = true;          // the device copy follows at the head of the next call that uses it
   return LORDO_OK;
 }
 

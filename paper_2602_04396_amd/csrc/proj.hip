@@ -215,7 +215,8 @@ struct FusedAdam {
   float* v;
   uint16_t* n_hi;
   uint16_t* n_lo;
-  float b1, omb1, b2, omb2, inv_c1, inv_c2, eps;
+  float b1, omb1, b2, omb2, eps;
+  const StepDev* step;        // bias corrections of the current step (device memory: a replayed graph sees its own step)
   float qw, qg;               // update bracket (qw u_hat + qg g) / den: 1, 0 for "No QHM"; omega, 1 - omega for low-rank QHM
   // 256-rank tiles only (the 128-rank kernel has no registers to spare):
   uint16_t* g_hi;             // error feedback: the bf16 hi / lo operand planes of g for the residual update (else null)
@@ -228,16 +229,17 @@ template <bool EXTRA>
 __device__ __forceinline__ float adam4(const FusedAdam& f, int64_t at, f32x4 g, f32x4 uu, f32x4 vv) {
   float nn[4];
   float dsum = 0.f;
+  const float inv_c1 = f.step->inv_c1, inv_c2 = f.step->inv_c2;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float un = fmaf(f.b1, uu[e], f.omb1 * g[e]);
     const float vn = fmaf(f.b2, vv[e], f.omb2 * (g[e] * g[e]));
     uu[e] = un;
     vv[e] = vn;
-    const float den = sqrtf(vn * f.inv_c2) + f.eps;
+    const float den = sqrtf(vn * inv_c2) + f.eps;
     dsum += den;
     // with qw = 1, qg = 0 bit-identical to u_hat / den; eps == 0 and no gradient yet (e.g. the padding): zero, not 0 / 0
-    nn[e] = den == 0.f ? 0.f : fmaf(f.qg, g[e], f.qw * (un * f.inv_c1)) / den;
+    nn[e] = den == 0.f ? 0.f : fmaf(f.qg, g[e], f.qw * (un * inv_c1)) / den;
   }
   __builtin_nontemporal_store(uu, TO_GLOBAL(f32x4, f.u + at));       // next use is a whole step away
   __builtin_nontemporal_store(vv, TO_GLOBAL(f32x4, f.v + at));
@@ -798,7 +800,7 @@ hipError_t launch_proj_down(const DevCtx& d, const ProjTile* tiles, int ntiles, 
     if (fuse) {
       fa.u = fuse->u; fa.v = fuse->v; fa.n_hi = fuse->n_hi; fa.n_lo = fuse->n_lo;
       fa.b1 = fuse->a.b1; fa.omb1 = fuse->a.omb1; fa.b2 = fuse->a.b2; fa.omb2 = fuse->a.omb2;
-      fa.inv_c1 = fuse->a.inv_c1; fa.inv_c2 = fuse->a.inv_c2; fa.eps = fuse->a.eps;
+      fa.step = fuse->a.step; fa.eps = fuse->a.eps;
       fa.qw = fuse->a.qw; fa.qg = fuse->a.qg;
       fa.g_hi = fuse->a.g_hi; fa.g_lo = fuse->a.g_lo; fa.colpart = fuse->a.colpart;
     }

@@ -190,3 +190,69 @@ def test_eps_zero_with_ragged_ranks_stays_finite_and_matches(torch, variant):
             got = pair.W_gpu[i].cpu().numpy().astype(np.float64)
             assert rel_l2(got - pair.W0[i], Wn - pair.W0[i]) <= TOL
     pair.opt.poll_status()
+
+
+@pytest.mark.parametrize("shape_set", ["split_k", "fused_128_rank_tiles", "fused_256_rank_tiles"])
+def test_recorded_local_step_counts_its_replays(torch, shape_set):
+    """A local step recorded into a HIP graph: the step count and the bias corrections 1 - beta^t (Sec. 2) live in device
+    memory and advance per REPLAY, so replaying the recording k times on new gradients is k local steps.  Two contexts
+    from the same start: one issues the steps one by one, the other replays one recording; weights and state must be
+    equal bit for bit after every replay (eager work and synchronisation between the replays), and the oracle agrees.
+    Then a refresh on the replayed context rotates the moments with the bias corrections of the replayed count."""
+    from paper_2602_04396_amd import lordo
+    shapes = {"split_k": [(256, 384, 64), (130, 260, 128), (520, 392, 96)],
+              "fused_128_rank_tiles": [(256, 520, 192), (250, 388, 120)],          # no matrix taller than 256 rows: no split-K,
+              "fused_256_rank_tiles": [(256, 520, 256), (250, 388, 250)]}[shape_set]  # the moment update is in the epilogue
+    n = len(shapes)
+    W0 = _weights(shapes, 73)
+    Q0 = [synth.orthonormal(np.random.default_rng(synth.seed_for(73, 700 + i)), p, r).astype(np.float32) for i, (p, q, r) in enumerate(shapes)]
+    ohp, ghp = orc.Hyper(), lordo.hparams()
+    eager = Pair(torch, shapes, W0, ohp, ghp, Q0)
+    Wr = [torch.tensor(w, device="cuda") for w in W0]
+    rec = lordo.Lordo(shapes, ghp, Wr, torch)
+    for i in range(n):
+        rec.set_state(i, lordo.STATE_Q, torch.tensor(Q0[i], device="cuda").contiguous())
+    gens = _spiked(shapes, 73, 6)
+    Gbuf = [torch.zeros(p, q, device="cuda", dtype=torch.bfloat16) for p, q, r in shapes]
+    lr = 2e-3
+
+    def load(t):
+        G = [g.draw(t) for g in gens]
+        for buf, g in zip(Gbuf, G):
+            buf.copy_(torch.tensor(g, device="cuda").bfloat16())
+        return G
+
+    # first step issued on both (also lets every kernel of the step set itself up outside the recording)
+    G = load(0)
+    rec.local_step(Wr, Gbuf, lr)
+    eager.local_step(G, lr=lr, first_step_patch=True)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rec.local_step(Wr, Gbuf, lr)             # recorded, not run
+    for t in range(1, 5):
+        G = load(t)
+        graph.replay()
+        eager.local_step(G, lr=lr)
+        torch.cuda.synchronize()
+        for i in range(n):
+            assert torch.equal(Wr[i], eager.W_gpu[i]), f"weights after replay {t}, matrix {i}"
+            for which in (lordo.STATE_U, lordo.STATE_V, lordo.STATE_NUPD):
+                assert torch.equal(rec.get_state(i, which), eager.opt.get_state(i, which)), f"state {which} after replay {t}, matrix {i}"
+    worst = eager.compare_local(TOL)                              # and the eager chain is the oracle's chain
+    print(f"recorded step, {shape_set}: 4 replays bit-equal to 4 issued steps; against the oracle {worst}", flush=True)
+    assert rec.step == 2 and eager.opt.step == 5                 # issued calls: the recording counts once
+    if shape_set == "fused_256_rank_tiles":
+        return                      # (r = p: a square start block, not a case for the range finder)
+    # a refresh after the replays: tell the context how many steps ran, then both rotate alike
+    rec.step = 5
+    Src = [g.draw(50) for g in gens]
+    Om = [synth.omega(np.random.default_rng(synth.seed_for(73, 900 + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
+    Sd = [torch.tensor(a, device="cuda").bfloat16() for a in Src]
+    Od = [torch.tensor(o, device="cuda", dtype=torch.float32) for o in Om]
+    rec.refresh_subspace(Sd, Od)
+    eager.opt.refresh_subspace(Sd, Od)
+    rec.poll_status(); eager.opt.poll_status()
+    for i in range(n):
+        for which in (lordo.STATE_Q, lordo.STATE_U, lordo.STATE_V):
+            assert torch.equal(rec.get_state(i, which), eager.opt.get_state(i, which)), f"state {which} after the refresh, matrix {i}"
