@@ -37,7 +37,9 @@
  *     local steps ISSUED through the API (recording counts once, replays do not); after
  *     replays, tell the context with lordo_set_step before a call that depends on it on the
  *     host (a refresh skips the moment rotation while that count is 0).  lordo_set_step
- *     takes effect at the head of the next compute call: do not record that call.
+ *     takes effect at the head of the next compute call: do not record that call.  The first
+ *     launch of a kernel raises its shared-memory limit with a host-side runtime call, which
+ *     a capturing stream does not allow: issue a call once before recording it.
  *   - There is no CPU fallback: without a GPU every compute call returns LORDO_EHIP.
  */
 #ifndef LORDO_H
