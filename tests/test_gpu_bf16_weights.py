@@ -126,14 +126,16 @@ def test_bf16_weights_local_and_outer_steps(shape_set, variant):
     opt.poll_status()
 
 
-@pytest.mark.parametrize("variant", ["ef", "global", "global_bf16_weights", "lowqhm_ef_wide"])
+@pytest.mark.parametrize("variant", ["ef", "global", "global_bf16_weights", "lowqhm_ef_wide", "global_bf16_weights_one_slice"])
 def test_bf16_residual_local_steps(variant):
     """Error feedback with E stored in bf16 (Alg. 1 error-feedback lines; `local_step_bf16_residual`): plain update,
     the full-rank QHM update (the paper's LoRDO-Global), the same with bf16 weights as well, and ranks >= 256."""
     import torch
     from paper_2602_04396_amd import lordo
     shapes = [(520, 392, 256), (300, 260, 288)] if variant.endswith("wide") else [(256, 384, 64), (130, 260, 128), (520, 392, 96)]
-    w_bf16 = variant == "global_bf16_weights"
+    if variant.endswith("one_slice"):       # no split-K: moment update, column sums and planes of g in the down-projection's epilogue
+        shapes = [(256, 520, 230), (250, 388, 225)]
+    w_bf16 = "bf16_weights" in variant
     qhm = "full" if variant.startswith("global") else ("low" if variant.startswith("lowqhm") else "none")
     kw = dict(error_feedback=True, omega=0.8 if qhm != "none" else 1.0)
     ohp = orc.Hyper(qhm_mode=qhm, **kw)
