@@ -401,6 +401,34 @@ def graph_replay_ms(torch, wl, n):
     return 1e3 * (time.perf_counter() - t0) / n
 
 
+def extra_variants(torch, lordo, synth, args, cfg):
+    """The headline workload under the configuration the paper's experiments use, LoRDO-Global (full-rank QHM with error
+    feedback, Sec. 3.2 and Alg. 1), with fp32 storage and with the weights and the residual stored in bf16: time per
+    local step and per kernel class."""
+    import copy
+    import gc
+    out = []
+    for storage in ("f32", "bf16"):
+        a = copy.copy(args)
+        a.update, a.param_dtype, a.err_dtype, a.rayleigh_ritz, a.short_side = "global", storage, storage, False, False
+        wl = Workload(torch, lordo, synth, cfg, None, 2, a)
+        wl.steps(2, 0, 0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        wl.steps(6, 0, 0)
+        torch.cuda.synchronize()
+        step_ms = 1e3 * (time.perf_counter() - t0) / 6
+        work = algorithmic_work(wl.shapes, 2, ef=True, qhm_full=True, w_bytes=2 if storage == "bf16" else 4, e_bytes=2 if storage == "bf16" else 4)
+        kernels, _ = wl.profiled(4, 0, 0, work)
+        out.append({"workload": cfg, "update": "global (full-rank QHM + error feedback)", "storage_of_W_and_E": storage,
+                    "step_ms": round(step_ms, 4), "ms": class_ms({k: v for k, v in kernels.items() if k in ("down", "adam", "up")})})
+        wl.close()
+        del wl
+        gc.collect()
+        torch.cuda.empty_cache()
+    return out
+
+
 def extra_configs(torch, lordo, synth, args, skip_cfg):
     """Per-class times of the other workloads of the table, so that one run covers it: c2, c3 and the rank sweep on
     the single largest matrix (c5) with one and two power iterations in the refresh.  Kernel-class averages only."""
@@ -562,6 +590,7 @@ def main():
     extra = None
     if args.extra and not args.no_events:
         extra = {"configs": extra_configs(torch, lordo, synth, args, cfg),
+                 "variants": extra_variants(torch, lordo, synth, args, cfg) if args.update == "plain" and not args.short_side else None,
                  "note": "HIP-event averages per kernel class and call (ms); down/up TFLOP/s on 2pqr flops, GB/s on algorithmic bytes"}
 
     cpu = None
