@@ -1255,16 +1255,18 @@ __global__ __launch_bounds__(64 * NW) void k_proj_up_dma(DevCtx d, const ProjTil
 }
 
 // ---------------------------------------------------------------------------------------
-// Up-projection for ranks from 256 up (plain update, q % 4 == 0, W 16-byte aligned): workgroup tile 256 rows x 128
+// Up-projection for ranks from 256 up (q % 4 == 0, target aligned to four of its elements): workgroup tile 256 rows x 128
 // columns of W, 4 waves in a 2 x 2 grid, wave tile 128 x 64 = 4 x 2 accumulator blocks.  With the 128 x 128 tile
-// above every wave reads 16 KiB of fragments from LDS per 24 MFMAs, which keeps LDS as busy as the matrix cores, and
+// above every wave reads 16 KiB of fragments from LDS per 24 MFMAs and
 // the workgroup pulls 1 byte of operand planes through L2 per output element and k-step; here a wave reads 12 KiB per
 // 24 MFMAs and the tile pulls 0.75 bytes.  The operand fragments of one k-step of 16 (24 KiB: eight row blocks of Q,
 // four column blocks of N, two planes each) arrive by global-to-LDS loads through a ring of three buffers, two
 // k-steps in flight, with explicit waits as in the pipelined down-projection; 72 KiB of LDS and 128 accumulator
 // registers admit two workgroups per compute unit, so that the epilogue of one (read, update, write of its W tile)
-// runs under the contraction of the other.  The registers leave no room for the whole W tile: the first row block
-// is requested before the contraction, the others when it ends.
+// runs under the contraction of the other.  Inside a wave the fragments of the next k-step are read from LDS into a
+// second register set while the matrix cores work on the current one; the registers then leave no room for W during
+// the contraction: its row blocks are requested when the contraction ends, three in flight (two when the epilogue
+// also reads a gradient tile: the full-rank QHM update, the residual of the error feedback).
 // ---------------------------------------------------------------------------------------
 template <bool WBF, bool WITH_G>     // WITH_G: gradient-term epilogue (bf16 G): the full-rank QHM update, or the residual E as target
 __global__ __launch_bounds__(256) void k_proj_up_wide(DevCtx d, const ProjTile* __restrict__ tiles,
