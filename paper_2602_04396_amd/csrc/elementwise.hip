@@ -11,6 +11,10 @@
 //   k_jacobi_svd      singular vectors of the Cholesky factor of the r x r Ritz matrix (Rayleigh-Ritz step: basis ordered as in Sec. 2's SVD projection)
 //   k_frob2_chunks / k_frob2_sum / k_stable_rank   squared Frobenius norm of the refresh source and its stable rank (Sec. 5.1)
 //   k_rot_pre / k_rot_post, k_mssv   elementwise parts of the moment rotation (Alg. 1 rotation lines); similarity diagnostic (Sec. 5.1)
+//   k_step            step count and bias corrections 1 - beta^t (Sec. 2) in device memory, advanced once per local step
+//   k_gauss_block     Gaussian start blocks of the range finder and of the random initial projection (Alg. 1 Require)
+//   k_gram_diag_part / k_gram_diag_sum   exact diagonal of the Gram matrices of CholeskyQR
+//   k_bf16_to_f32 / k_f32_to_bf16   a bf16-stored residual through the fp32 state interface
 #include "common.h"
 
 namespace lordo {

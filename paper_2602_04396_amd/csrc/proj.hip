@@ -8,8 +8,9 @@
 //
 // fp32 operands the library owns (Q, N) are kept as two bf16 planes hi + lo (x = hi + lo up to
 // 2^-17 relative), already in the lane order of the MFMA operand fragment, so a fragment is one
-// 16-byte load per lane.  The bf16 gradient is exact; an fp32 gradient is split on the fly.
-//   down:  acc += Qhi^T G + Qlo^T G                      (+ Qhi^T Glo for fp32 G)
+// 16-byte load per lane.  The bf16 gradient is exact; the fp32 sum s G + E of the error feedback is split on the fly
+// (fp32 gradients do not come here: their products run in the grouped GEMM with three-term operands).
+//   down:  acc += Qhi^T G + Qlo^T G                      (+ Qhi^T Alo for a staged fp32 sum A)
 //   up:    acc += Qhi Nhi + Qhi Nlo + Qlo Nhi
 // Accumulation is fp32 in the matrix core.
 //
