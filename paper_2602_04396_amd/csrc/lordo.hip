@@ -414,8 +414,6 @@ struct ProgramBuilder {
     P.ops.swap(saved);
   }
 
-  // passes = 3 is the robust variant: two shifted passes after every product of the power iteration (the conditioning
-  // of the source then does not compound from product to product) and shifted, shifted, plain at the end.
   // Down-projection of the right-projected matrices (Sec. 2 with the roles of rows and columns exchanged) on the
   // caller's row-major arrays by the generic GEMM: g^T = (s G) Q into zw[0]; the scale s multiplies the launch (it
   // changes per call).  Taken for fp32 gradients and for shapes or pointers the streaming kernel does not read.
@@ -456,6 +454,9 @@ struct ProgramBuilder {
     keep.swap(P.ops);
   }
 
+  // The refresh (Sec. 2 ComputeProjection by a randomised range finder, then the rotation of the moments).
+  // passes = 3 is the robust variant: two shifted passes after every product of the power iteration (the conditioning
+  // of the source then does not compound from product to product) and shifted, shifted, plain at the end.
   void build(int power_iters, int passes, bool rayleigh_ritz) {
     const int inner = passes >= 3 ? 2 : 1, nshift = passes >= 3 ? 2 : 1;
     // Y = Src Omega
@@ -567,8 +568,6 @@ struct ProgramBuilder {
 
 int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
   if (!shapes || !hp || n <= 0) return LORDO_EINVAL;
-  if (hp->qhm_mode < 0 || hp->qhm_mode > 2 || (hp->error_feedback != 0 && hp->error_feedback != 1)) return LORDO_EINVAL;
-  if (hp->uplink_buffer != 0 && hp->uplink_buffer != 1) return LORDO_EINVAL;
   for (int i = 0; i < n; ++i) {
     const lordo_shape& s = shapes[i];
     if (s.rows <= 0 || s.cols <= 0 || s.rank <= 0 || (s.side != 0 && s.side != 1)) return LORDO_EINVAL;
@@ -1190,6 +1189,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   int rc = c->sync_step(s);
   if (rc != LORDO_OK) return rc;
   HIPCHK(launch_step(c->at<StepDev>(P.step), c->hp.beta1, c->hp.beta2, c->hp.bias_correction, -1, s));      // t <- t + 1
+  c->step_dirty = true;         // until the whole step is enqueued: a call that fails below leaves the device count to be set back from `t`
   rc = c->set_ext(EXT_W, W, s);
   if (rc != LORDO_OK) return rc;
   rc = c->set_ext(EXT_G, const_cast<void* const*>(reinterpret_cast<const void* const*>(G)), s);
@@ -1285,6 +1285,7 @@ int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double 
   }
   c->prof.end(LORDO_K_UP, s);
   c->t = t;
+  c->step_dirty = false;
   c->grad_folded = false;
   ++c->window_steps;
   return LORDO_OK;
