@@ -4,12 +4,17 @@ g is a nearly cancelled sum, the rounding of the products shows amplified in N (
 full-rank QHM term).  What each group needed:
   * fp32 gradients (cases 150, 154 of the option sweep; Rayleigh-Ritz case 99): the down-projection of fp32 gradients
     now runs with three-term operands, as exact as fp32;
-  * bf16 gradients behind a basis ordered by the Rayleigh-Ritz step (case 27, skipped): g, u, v and the weight change
-    agree to 1e-4, N reaches 1.1e-4.  The rotated second moment, c2 |(R o R)(v_hat - u_hat^2) + (R u_hat)^2|, is a sum
-    of terms of both signs; where it nearly cancels its fp32 value has a large RELATIVE error in that element (the
-    array as a whole stays within 1e-4), and N = u_hat / (sqrt(v_hat) + eps) divides by it.  A third bf16 term of Q in
-    the down-projection was tried and does not change it (1.6e-4): the error is made in the rotation, which would need
-    float64 accumulation to follow the oracle element by element there;
+  * bf16 gradients behind a basis ordered by the Rayleigh-Ritz step, refreshed after exactly ONE step from the zero
+    state (case 27 of that sweep and a 649 x 608 matrix of rank 264 from a sweep of ranks above 128, both skipped):
+    g, u, v and the weight change agree to 1e-4 (u and v after the rotation to 3e-6), N reaches 1.1e-4 and 1.9e-4.
+    After one step v_hat = u_hat^2 identically, so the variance term of the rotated second moment,
+    c2 |(R o R)(v_hat - u_hat^2) + (R u_hat)^2|, is zero in exact arithmetic and in float64; computed from moments
+    STORED in fp32 it is their rounding noise, 1e-7 v_hat with either sign.  Where the rotated first moment is small
+    -- the trailing directions of a basis ordered by singular value are exactly those -- (R u_hat)^2 is no longer
+    large against that noise, the element of v has a large RELATIVE error (the array as a whole stays within 3e-6),
+    and N = u_hat / (sqrt(v_hat) + eps) divides by it.  With two or three steps before the refresh, so that the
+    variance term is a variance, the same two cases give 5e-6 on N (measured).  A third bf16 term of Q in the
+    down-projection does not change the one-step case (1.6e-4): it would take moments stored beyond fp32;
   * one element in 14 696 (case 317 of the option sweep, skipped): bf16 gradients, a 47 x 668 matrix of rank 22.  g, u
     and v agree to 1e-5, and the library's N equals the float64 formula evaluated at the library's own u, v, g to
     3e-6; but one entry of g is about a thousand times smaller than the typical entry at BOTH of the first two steps,
@@ -40,8 +45,9 @@ def test_option_sweep_cases(case):
 
 
 @pytest.mark.parametrize("case", [
-    pytest.param(27, marks=pytest.mark.skip(reason="known miss: N of the step after a Rayleigh-Ritz refresh at 1.1e-4 on one 347 x 252, r = 46 "
-                                                   "matrix (g, u, v, dW within 1e-4): cancellation in the fp32 second-moment rotation, see the module docstring")),
+    pytest.param(27, marks=pytest.mark.skip(reason="known miss: N of the step after a Rayleigh-Ritz refresh that follows ONE step from the zero state at 1.1e-4 on "
+                                                   "one 347 x 252, r = 46 matrix (g, u, v, dW within 1e-4; 5e-6 with two steps before the refresh): the variance term "
+                                                   "of the rotation is rounding noise of the fp32 moments, see the module docstring")),
     99])
 def test_rayleigh_ritz_sweep_cases(case):
     sweep.test_random_shapes_rayleigh_ritz_refresh(case)
@@ -55,3 +61,11 @@ def test_right_projection_sweep_case_193():
         right.test_right_projection_steps_refresh_outer("sweep_193", "none", True)
     finally:
         del right.SHAPE_SETS["sweep_193"]
+
+
+@pytest.mark.skip(reason="known miss: N of the step after a Rayleigh-Ritz refresh that follows ONE step from the zero state at 1.9e-4 (g, u, v, dW within "
+                         "1e-4; 5e-6 with two steps before the refresh): the variance term of the rotation is rounding noise of the fp32 moments, see the "
+                         "module docstring")
+def test_rayleigh_ritz_rank_264_refresh_after_one_step(monkeypatch):
+    monkeypatch.setattr(sweep, "draw_rr_case", lambda case: ([(649, 608, 264)], True, 1))
+    sweep.test_random_shapes_rayleigh_ritz_refresh(6)
