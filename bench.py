@@ -102,6 +102,27 @@ def measured_traffic(cfg, rank, kernel_class, update="plain", param_dtype="f32")
     return best[1] if best else None
 
 
+def measured_mfma_counters(cfg, rank, kernel_class, update="plain", param_dtype="f32"):
+    """Matrix-core busy cycles over elapsed cycles and the clock the chip ran at, for a projection kernel of this
+    workload, from the committed rocprofv3 counter summary (its "derived" lines), or {} if it does not cover the case."""
+    if update != "plain" or param_dtype != "f32" or cfg not in ("c4", "c5"):
+        return {}
+    label = "c4 r=512" if cfg == "c4" else f"c5 r={rank}"
+    path = os.path.join(ROOT, "profiles", "c4_c5_projection_mfma_counters_pmc.txt")
+    prefix = KERNEL_OF_CLASS.get(kernel_class)
+    if prefix is None or not os.path.exists(path):
+        return {}
+    with open(path) as f:
+        for line in f:
+            parts = line.lstrip("# ").strip().split(",")
+            if len(parts) == 6 and parts[0] == label and parts[1].startswith(prefix):
+                try:
+                    return {"mfma_busy_frac_of_elapsed_cycles": float(parts[5]), "clock_GHz": float(parts[4])}
+                except ValueError:
+                    return {}
+    return {}
+
+
 def algorithmic_work(shapes, grad_bytes=2, ef=False, qhm_full=False, w_bytes=4, e_bytes=4):
     """Algorithmic bytes and flops per step of each kernel class (unpadded sizes).  With error feedback
     the down-projection also reads the residual E, Adam also writes g as operand planes and the "up"
@@ -369,6 +390,7 @@ def roofline_of(kernels, total_by, work, cfg, rank, update, param_dtype="f32"):
     passes = {"down": 3 if update in ("ef", "global", "local") else 2, "up": 3}.get(dom, 0)
     issued = {"mfma_passes": passes, "issued_TFLOPps": passes * w["flops"] / avg_s / 1e12,
               "issued_frac_of_mfma_peak": passes * w["flops"] / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS} if passes and w["flops"] else {}
+    issued.update(measured_mfma_counters(cfg, rank, dom, update, param_dtype))
     if t_mfma > t_hbm:
         ach = w["flops"] / avg_s / 1e12
         return dict({"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
