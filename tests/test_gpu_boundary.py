@@ -192,13 +192,16 @@ def test_eps_zero_with_ragged_ranks_stays_finite_and_matches(torch, variant):
     pair.opt.poll_status()
 
 
-@pytest.mark.parametrize("shape_set", ["split_k", "fused_128_rank_tiles", "fused_256_rank_tiles"])
-def test_recorded_local_step_counts_its_replays(torch, shape_set):
+@pytest.mark.parametrize("shape_set,update", [("split_k", "plain"), ("fused_128_rank_tiles", "plain"), ("fused_256_rank_tiles", "plain"),
+                                              ("split_k", "global"), ("fused_256_rank_tiles", "global")])
+def test_recorded_local_step_counts_its_replays(torch, shape_set, update):
     """A local step recorded into a HIP graph: the step count and the bias corrections 1 - beta^t (Sec. 2) live in device
     memory and advance per REPLAY, so replaying the recording k times on new gradients is k local steps.  Two contexts
     from the same start: one issues the steps one by one, the other replays one recording; weights and state must be
     equal bit for bit after every replay (eager work and synchronisation between the replays), and the oracle agrees.
-    Then a refresh on the replayed context rotates the moments with the bias corrections of the replayed count."""
+    Then a refresh on the replayed context rotates the moments with the bias corrections of the replayed count.
+    `global`: the same with error feedback and the full-rank QHM update (the paper's LoRDO-Global), whose step holds the
+    residual launch and the gradient-term epilogue as well; the residual is compared too."""
     from paper_2602_04396_amd import lordo
     shapes = {"split_k": [(256, 384, 64), (130, 260, 128), (520, 392, 96)],
               "fused_128_rank_tiles": [(256, 520, 192), (250, 388, 120)],          # no matrix taller than 256 rows: no split-K,
@@ -206,7 +209,8 @@ def test_recorded_local_step_counts_its_replays(torch, shape_set):
     n = len(shapes)
     W0 = _weights(shapes, 73)
     Q0 = [synth.orthonormal(np.random.default_rng(synth.seed_for(73, 700 + i)), p, r).astype(np.float32) for i, (p, q, r) in enumerate(shapes)]
-    ohp, ghp = orc.Hyper(), lordo.hparams()
+    kw = dict(error_feedback=True, omega=0.8) if update == "global" else {}
+    ohp, ghp = orc.Hyper(qhm_mode="full" if kw else "none", **kw), lordo.hparams(qhm_mode=2 if kw else 0, **kw)
     eager = Pair(torch, shapes, W0, ohp, ghp, Q0)
     Wr = [torch.tensor(w, device="cuda") for w in W0]
     rec = lordo.Lordo(shapes, ghp, Wr, torch)
@@ -237,10 +241,10 @@ def test_recorded_local_step_counts_its_replays(torch, shape_set):
         torch.cuda.synchronize()
         for i in range(n):
             assert torch.equal(Wr[i], eager.W_gpu[i]), f"weights after replay {t}, matrix {i}"
-            for which in (lordo.STATE_U, lordo.STATE_V, lordo.STATE_NUPD):
+            for which in (lordo.STATE_U, lordo.STATE_V, lordo.STATE_NUPD) + ((lordo.STATE_ERR,) if kw else ()):
                 assert torch.equal(rec.get_state(i, which), eager.opt.get_state(i, which)), f"state {which} after replay {t}, matrix {i}"
     worst = eager.compare_local(TOL)                              # and the eager chain is the oracle's chain
-    print(f"recorded step, {shape_set}: 4 replays bit-equal to 4 issued steps; against the oracle {worst}", flush=True)
+    print(f"recorded step, {shape_set} {update}: 4 replays bit-equal to 4 issued steps; against the oracle {worst}", flush=True)
     assert rec.step == 2 and eager.opt.step == 5                 # issued calls: the recording counts once
     if shape_set == "fused_256_rank_tiles":
         return                      # (r = p: a square start block, not a case for the range finder)
