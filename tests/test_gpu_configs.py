@@ -200,3 +200,61 @@ def test_c5_largest_matrix_rank_sweep_ends(rank, power_iters):
     opt.close()
     del opt, W, G, D, Omega
     torch.cuda.empty_cache()
+
+
+def test_c4_lordo_global_with_bf16_storage_sampled_columns():
+    """The paper's LoRDO-Global (full-rank QHM + error feedback; Sec. 3.2, Alg. 1) at the c4 launch shape with the
+    weights and the residual stored in bf16, as `bench.py` times it among its variants: three local steps on sampled
+    columns of one matrix per distinct shape.  Every step starts from the weights and the residual as the library
+    stored them; g, the moments and N within 1e-4, every stored weight and residual element a single rounding of the
+    float64 update (the criteria of tests/test_gpu_bf16_weights.py)."""
+    import torch
+    import bench
+    from paper_2602_04396_amd import lordo
+    from tests.test_gpu_bf16_weights import _check_rounded_once
+    shapes, W, G, Omega, D, grad_dtype = bench.build_workload(torch, lordo, synth, "c4", None, 2, torch.bfloat16)
+    kw = dict(omega=0.8, error_feedback=True)
+    hp = lordo.hparams(seed=synth.seed_for(4, 78), qhm_mode=2, param_dtype=lordo.BF16, err_dtype=lordo.BF16, **kw)
+    ohp = orc.Hyper(qhm_mode="full", **kw)
+    opt = lordo.Lordo(shapes, hp, W, torch)
+    Wp = opt.ptrs(W, torch.bfloat16)
+    Gp = [opt.ptrs(g, grad_dtype) for g in G]
+    opt.init_projection(None)
+    opt.poll_status()
+    picked = _first_of_each_shape(shapes)
+    rng = np.random.default_rng(synth.seed_for(4, 4343))
+    state = {}
+    for i in picked:
+        p, q, r = shapes[i]
+        Q = _f64(opt.get_state(i, lordo.STATE_Q))
+        assert np.linalg.norm(Q.T @ Q - np.eye(r)) <= TOL_ORTH
+        cols = np.unique(np.concatenate([[0, 1, q - 1, 127, 128, 255, 256, 257, q - 257], rng.integers(0, q, 10)]))
+        state[i] = (cols, orc.init_state(_f64(W[i][:, cols]), r, Q))
+    for t, lr in enumerate((1e-3, 2e-3, 1e-3)):
+        before, E_prev = {}, {}
+        for i in picked:
+            cols, st = state[i]
+            before[i] = _f64(W[i][:, cols])
+            E_prev[i] = _f64(opt.get_state(i, lordo.STATE_ERR))[:, cols]
+            assert np.array_equal(orc.round_to_bf16(E_prev[i]), E_prev[i]), "the stored residual is not bf16"
+            st.E = E_prev[i].copy()
+        opt.local_step(Wp, Gp[t % 2], lr)
+        torch.cuda.synchronize()
+        for i in picked:
+            cols, st = state[i]
+            Gc = _f64(G[t % 2][i][:, cols])
+            full_W = orc.local_step(st, before[i], Gc, lr, ohp)          # leaves the unrounded residual in st.E
+            where = f"c4 global bf16 storage, step {t + 1}, matrix {i} {shapes[i]}"
+            get = lambda which: _f64(opt.get_state(i, which))[:, cols]
+            assert rel_l2(get(lordo.STATE_GLOW), st.last_g) <= TOL, "g, " + where
+            assert rel_l2(get(lordo.STATE_U), st.u) <= TOL and rel_l2(get(lordo.STATE_V), st.v) <= TOL, "moments, " + where
+            _check_rounded_once(get(lordo.STATE_ERR), st.E, Gc + E_prev[i], where + " (residual)", max_mismatch=0.1)
+            if t > 0:           # (the first update is the sign of g, decided by rounding where g is zero to working precision)
+                assert rel_l2(get(lordo.STATE_NUPD), st.last_N) <= TOL, "N, " + where
+                _check_rounded_once(_f64(W[i][:, cols]), full_W, full_W - before[i], where + " (weights)", slack_scale=2.0)
+    for i in picked:
+        assert torch.isfinite(W[i].float()).all()
+    opt.poll_status()
+    opt.close()
+    del opt, W, G, D, Omega
+    torch.cuda.empty_cache()
