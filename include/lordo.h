@@ -78,8 +78,11 @@ extern "C" {
 
 typedef struct lordo_ctx lordo_ctx;
 
-/* One weight matrix: rows p, cols q, rank r; requires r <= 4096, p, q <= 2^20 and p * q < 2^30 (a matrix is
- * addressed with 32-bit byte offsets).
+/* One weight matrix: rows p, cols q, rank r; requires r <= 4096, p, q <= 2^20, max(p, q) * r < 2^29 and
+ * max((p + 256) * q, p * (q + 256)) < 2^30: a matrix is addressed with 32-bit byte offsets, so the fp32 array and one
+ * tile beyond it stay below 4 GiB.  A matrix for which that product reaches 2^29 (2 GiB in fp32) must have p and q
+ * multiples of 256 and side 0: the kernels mask what lies outside a ragged matrix with offsets that are out of range
+ * only below 2 GiB.  LORDO_EINVAL otherwise.
  *   side 0  projection on the left, as the paper writes it (Sec. 2: Q is p x r, the moments r x q); 1 <= r <= p.
  *   side 1  projection on the right, the choice that keeps Q and the moments small for a tall matrix (p > q):
  *           g = (s G) Q_R with Q_R q x r, moments p x r, W <- W - eta N Q_R^T, and the refresh takes the right

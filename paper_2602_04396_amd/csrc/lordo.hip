@@ -574,8 +574,17 @@ int validate(const lordo_shape* shapes, int32_t n, const lordo_hparams* hp) {
     if (s.rank > (s.side ? s.cols : s.rows)) return LORDO_EINVAL;
     // (tile coordinates of the grouped GEMM are 16-bit: at most 32767 tiles of 64 rows)
     if (s.rows > (1 << 20) || s.cols > (1 << 20) || s.rank > 4096) return LORDO_EINVAL;
-    // the kernels address a matrix through buffer descriptors with 32-bit byte offsets: p * q * 4 bytes must stay below 4 GiB
-    if (s.rows * s.cols >= (int64_t(1) << 30)) return LORDO_EINVAL;
+    // The kernels address a matrix through buffer descriptors with 32-bit byte offsets: the fp32 array and one tile
+    // (256 rows or columns) beyond it must stay below 4 GiB, so that no sum of offsets wraps.
+    const int64_t with_tile = std::max((s.rows + 256) * s.cols, s.rows * (s.cols + 256));
+    if (with_tile >= (int64_t(1) << 30)) return LORDO_EINVAL;
+    // A lane whose column lies outside the matrix is given the byte offset 2^31, and a row outside it the offset of the
+    // array's end: both are out of the descriptor's range only while the array (with that tile) is below 2 GiB.  From
+    // there on the sides must be multiples of the largest tile, 256, so that no such lane or row exists; the
+    // right-projected path is verified below 2 GiB only.
+    if (with_tile >= (int64_t(1) << 29) && ((s.rows & 255) != 0 || (s.cols & 255) != 0 || s.side != 0)) return LORDO_EINVAL;
+    // the low-rank arrays of the matrix (p x r, r x q in fp32) are addressed the same way and stay below 2 GiB
+    if (std::max(s.rows, s.cols) * (int64_t)s.rank >= (int64_t(1) << 29)) return LORDO_EINVAL;
   }
   if (!(hp->beta1 >= 0 && hp->beta1 < 1) || !(hp->beta2 >= 0 && hp->beta2 < 1) || !(hp->eps >= 0)) return LORDO_EINVAL;
   if (hp->qhm_mode < 0 || hp->qhm_mode > 2 || (hp->error_feedback != 0 && hp->error_feedback != 1)) return LORDO_EINVAL;

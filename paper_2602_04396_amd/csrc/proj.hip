@@ -66,7 +66,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Compiler-level fence: keeps the loads issued before it from being sunk to their first use
 // (prefetches must be in flight while the matrix cores work); it emits no instruction.
 #define ISSUE_FENCE() asm volatile("" ::: "memory")
-constexpr uint32_t OOB = 0x80000000u;        // byte offset beyond any resource (sizes are < 2 GiB)
+// Byte offset given to a lane whose column lies outside the matrix: beyond the range of any resource smaller than 2 GiB.
+// lordo_init admits larger matrices only with sides that are multiples of 256, where no such lane exists.
+constexpr uint32_t OOB = 0x80000000u;
 // Cache policy of the caller's matrices.  G is read once and W is read once and written once per
 // step, hundreds of megabytes each: they are marked non-temporal so that they pass through L2 and
 // the last-level cache as streaming lines and leave both to the operands that are reused (the Q and

@@ -46,10 +46,21 @@ def test_workspace_bytes_scales_and_validates(lib):
     assert lower < c2 < 8 * lower
     with_mom = lordo.workspace_bytes(shapes, lordo.hparams(outer_momentum=0.9))
     assert with_mom - c2 >= sum(4 * p * q for p, q, r in shapes)
-    for bad in ([(8, 8, 9)], [(0, 8, 1)], [(8, 8, 0)], [(32768, 32768, 64)]):     # the last: p * q * 4 bytes reach 4 GiB
+    for bad in ([(8, 8, 9)], [(0, 8, 1)], [(8, 8, 0)],
+                [(32768, 32768, 64)],          # p * q * 4 bytes reach 4 GiB
+                [(32512, 33024, 64)],          # the array fits below 4 GiB, the array plus a tile of 256 rows does not
+                [(32000, 33000, 64)],          # above 2 GiB the sides must be multiples of 256 ...
+                [(33024, 32256, 64, 1)],       # ... and the projection on the left
+                [(23040, 23300, 64)],          # (23040 + 256) * 23300 * 4 bytes reach 2 GiB and 23300 is ragged
+                [(1 << 19, 700, 1100)]):       # a low-rank array p x r of 2 GiB
         with pytest.raises(lordo.LordoError) as e:
             lordo.workspace_bytes(bad, hp)
-        assert e.value.code == lordo.EINVAL
+        assert e.value.code == lordo.EINVAL, bad
+    for good in ([(32256, 33024, 64)],         # 3.97 GiB, aligned
+                 [(22900, 23100, 64)],         # 1.97 GiB, ragged
+                 [(23100, 22900, 64, 1)],
+                 [(1 << 19, 700, 1000)]):
+        assert lordo.workspace_bytes(good, hp) > 0, good
     with_ef = lordo.workspace_bytes(shapes, lordo.hparams(error_feedback=True))
     assert with_ef - c2 >= sum(4 * p * q for p, q, r in shapes)          # the residual E
     assert lordo.workspace_bytes(shapes, lordo.hparams(qhm_mode=2, omega=0.9)) > c2   # column sums

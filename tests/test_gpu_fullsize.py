@@ -226,14 +226,18 @@ def test_c2_full_size_rayleigh_ritz_refresh_sampled_matrices():
         assert abs(sr[i] - orc.stable_rank(A)) <= TOL * orc.stable_rank(A), f"stable rank of matrix {i}"
 
 
-def test_one_matrix_just_under_the_size_limit_sampled_columns():
-    """A 32000 x 33000 matrix: p * q * 4 bytes = 3.93 GiB, just under the 4 GiB that the 32-bit byte offsets of the
-    kernels can address.  Refresh, two steps and an outer step; sampled columns (first, last, around the 2^15 column and
-    random ones) against the oracle, the last rows of the matrix finite, anchor equal to the weights."""
+@pytest.mark.parametrize("p,q", [(32256, 33024), (22900, 23100)], ids=["4GiB_tile_aligned", "2GiB_ragged"])
+def test_one_matrix_just_under_the_size_limits(p, q):
+    """The two size limits of a matrix.  32256 x 33024: p * q * 4 bytes = 3.97 GiB, with one more tile of rows just under the
+    4 GiB that the 32-bit byte offsets of the kernels address; above 2 GiB the sides must be multiples of 256.
+    22900 x 23100: ragged sides, 1.97 GiB, the largest the kernels mask (a lane or row outside the matrix is given an offset
+    that is out of the descriptor's range only below 2 GiB).  Refresh, two steps and an outer step; sampled columns (first,
+    last, around the 2^15 column and random ones) against the oracle; and over the WHOLE matrix the change of every step
+    against -lr Q N formed by the library's fp32 GEMM from the library's Q and N: an element written from the wrong place
+    anywhere in the array would show there.  Anchor equal to the weights at the end."""
     import torch
     from paper_2602_04396_amd import lordo
-    p, q, r = 32000, 33000, 64
-    assert p * q < 2 ** 30
+    r = 64
     gen = torch.Generator(device="cuda")
     gen.manual_seed(7)
     W = [torch.randn(p, q, generator=gen, device="cuda") * 0.02]
@@ -243,15 +247,17 @@ def test_one_matrix_just_under_the_size_limit_sampled_columns():
     opt = lordo.Lordo([(p, q, r)], hp, W, torch)
     opt.refresh_subspace(G[0], Om)
     opt.poll_status()
-    Q = opt.get_state(0, lordo.STATE_Q).cpu().numpy().astype(np.float64)
+    Qd = opt.get_state(0, lordo.STATE_Q)
+    Q = Qd.cpu().numpy().astype(np.float64)
     assert np.linalg.norm(Q.T @ Q - np.eye(r)) <= 1e-4
-    cols = np.unique(np.concatenate([[0, 1, q - 1, q - 2, 127, 128, 16384, 32767, 32768],
+    cols = np.unique(np.concatenate([[0, 1, q - 1, q - 2, 127, 128, 16384, min(32767, q - 3), min(32768, q - 4)],
                                      np.random.default_rng(1).integers(0, q, 12)]))
     st = orc.init_state(W[0][:, cols].cpu().numpy().astype(np.float64), r, Q)
     Wc = st.anchor.copy()
     ohp = orc.Hyper()
     for step in range(2):
-        before = W[0][:, cols].cpu().numpy().astype(np.float64)
+        W_before = W[0].clone()
+        before = W_before[:, cols].cpu().numpy().astype(np.float64)
         opt.local_step(W, G[step], 1e-3)
         torch.cuda.synchronize()
         Gc = G[step][0][:, cols].float().cpu().numpy().astype(np.float64)
@@ -263,10 +269,24 @@ def test_one_matrix_just_under_the_size_limit_sampled_columns():
         assert rel_l2(dW, -1e-3 * Q @ got["N"]) <= TOL
         if step:                      # (the first update from zero moments is the sign of g: see the c2 test above)
             assert rel_l2(got["N"], st.last_N) <= TOL
+        # the whole array: W_before - W = lr Q N everywhere (fp32 on both sides: 1e-3 of the rms covers the rounding of
+        # W itself, 2^-24 |W| against a change of 1e-3 |N|; a misplaced element is off by the size of the change)
+        ref = Qd @ opt.get_state(0, lordo.STATE_NUPD)
+        ref *= 1e-3
+        W_before -= W[0]
+        rms = float(ref.square().mean().sqrt())
+        W_before -= ref
+        worst = float(W_before.abs().max())
+        print(f"{p} x {q} step {step}: largest deviation of the change from lr Q N over the whole array {worst:.3e}, rms of the change {rms:.3e}", flush=True)
+        assert worst <= 2e-2 * rms
+        del ref, W_before
     assert torch.isfinite(W[0][[p - 1, p - 2, p - 129]]).all()
     opt.outer_step(W, None)
     opt.poll_status()
     assert torch.equal(opt.get_state(0, lordo.STATE_ANCHOR), W[0])
+    opt.close()
+    del opt, W, G
+    torch.cuda.empty_cache()
 
 
 def test_c2_full_size_short_side_sampled_rows():
