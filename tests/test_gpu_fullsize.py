@@ -289,6 +289,40 @@ def test_one_matrix_just_under_the_size_limits(p, q):
     torch.cuda.empty_cache()
 
 
+def test_largest_rank_4096():
+    """The largest rank the boundary admits, r = 4096, on an 8192 x 6144 matrix: random initial projection drawn by the
+    library (Alg. 1 Require), two local steps on sampled columns, a refresh from a gradient with one power iteration
+    against the oracle's own range finder (projector distance; moments rotated with the library's basis), one more step."""
+    import torch
+    from paper_2602_04396_amd import lordo
+    from tests.test_gpu_configs import Sampled
+    p, q, r = 8192, 6144, 4096
+    shapes = [(p, q, r)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    W = [(0.02 * torch.randn(p, q, generator=gen, device="cuda")).contiguous()]
+    draw = synth.device_spiked_gradient(torch, p, q, 64, synth.seed_for(9, 1), noise="gauss", dtype=torch.bfloat16, device="cuda")
+    G = [[draw(s)] for s in range(2)]
+    Omega = [torch.randn(q, r, generator=gen, device="cuda")]
+    hp, ohp = lordo.hparams(seed=5, power_iters=1), orc.Hyper(power_iters=1)
+    opt = lordo.Lordo(shapes, hp, W, torch)
+    Wp = opt.ptrs(W)
+    Gp = [opt.ptrs(g, torch.bfloat16) for g in G]
+    Op = opt.ptrs(Omega, torch.float32, "qr")
+    opt.init_projection(None)
+    opt.poll_status()
+    sm = Sampled(torch, lordo, opt, shapes, W, [0], ohp, 123)            # checks the orthonormality of Q_0
+    sm.local_step(Wp, Gp[0], G[0], 1e-3, "r = 4096 step 1")
+    sm.local_step(Wp, Gp[1], G[1], 2e-3, "r = 4096 step 2")
+    sm.refresh(Gp[0], Op, 1, "r = 4096 refresh", {0})
+    sm.local_step(Wp, Gp[1], G[1], 1e-3, "r = 4096 step 3 (after the refresh)")
+    assert torch.isfinite(W[0]).all()
+    opt.poll_status()
+    opt.close()
+    del opt, W, G, Omega
+    torch.cuda.empty_cache()
+
+
 def test_c2_full_size_short_side_sampled_rows():
     """Workload c2 with its tall matrices projected on the right, in the launch configuration `bench.py --short-side`
     times: for such a matrix every formula acts row by row (g_i = G_i Q, W_i -= lr N_i Q^T), so the oracle follows
