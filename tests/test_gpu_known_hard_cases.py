@@ -50,7 +50,7 @@ def test_option_sweep_cases(case):
                                                    "of the rotation is rounding noise of the fp32 moments, see the module docstring")),
     99])
 def test_rayleigh_ritz_sweep_cases(case):
-    sweep.test_random_shapes_rayleigh_ritz_refresh(case)
+    sweep.test_random_shapes_rayleigh_ritz_refresh(case, steps_before_refresh=1)
 
 
 @pytest.mark.skip(reason="known miss: N of the second step at 1.9e-4 on the 244 x 352, r = 124 right-projected matrix (g, u, v within 3e-6), one "
@@ -68,4 +68,4 @@ def test_right_projection_sweep_case_193():
                          "module docstring")
 def test_rayleigh_ritz_rank_264_refresh_after_one_step(monkeypatch):
     monkeypatch.setattr(sweep, "draw_rr_case", lambda case: ([(649, 608, 264)], True, 1))
-    sweep.test_random_shapes_rayleigh_ritz_refresh(6)
+    sweep.test_random_shapes_rayleigh_ritz_refresh(6, steps_before_refresh=1)

@@ -157,10 +157,14 @@ def draw_rr_case(case):
 
 
 @pytest.mark.parametrize("case", list(range(10)))
-def test_random_shapes_rayleigh_ritz_refresh(case):
+def test_random_shapes_rayleigh_ritz_refresh(case, steps_before_refresh=2):
     """Refresh with the Rayleigh-Ritz step (Sec. 2: singular vectors in order) and the two spectrum metrics of
     Sec. 5.1 on randomly drawn shape sets: subspace, ordered Ritz values, diagonal restricted matrix, stable rank,
-    bound on the sigma_(r+1) estimate; then a step."""
+    bound on the sigma_(r+1) estimate; then a step.
+    Two steps come before the refresh: after exactly one step from the zero state v_hat = u_hat^2 identically, the
+    variance term of the rotated second moment is zero in exact arithmetic and rounding noise of the fp32 moments in
+    the library, which the trailing directions of an ordered basis show in N (the one-step form of this test is kept
+    in tests/test_gpu_known_hard_cases.py)."""
     import torch
     from paper_2602_04396_amd import lordo
     shapes, bf16, q_it = draw_rr_case(case)
@@ -172,7 +176,8 @@ def test_random_shapes_rayleigh_ritz_refresh(case):
           for i, (p, q, r) in enumerate(shapes)]
     pair = Pair(torch, shapes, W0, ohp, ghp, Q0)
     gens = [synth.SpikedGradient(p, q, min(4, p, q), synth.seed_for(72, 100 * case + i), bf16=bf16) for i, (p, q, r) in enumerate(shapes)]
-    pair.local_step([g.draw(0) for g in gens], lr=1e-3, bf16=bf16, first_step_patch=True)
+    for t in range(steps_before_refresh):
+        pair.local_step([g.draw(t) for g in gens], lr=1e-3, bf16=bf16, first_step_patch=(t == 0))
     Src = [g.draw(100) for g in gens]
     Om = [synth.omega(np.random.default_rng(synth.seed_for(73, 100 * case + i)), q, r) for i, (p, q, r) in enumerate(shapes)]
     dists, orths = pair.refresh(Src, Om, bf16=bf16)
