@@ -221,4 +221,20 @@ hipError_t launch_tr_exchange(const DevCtx& d, float* glow, float scale, bool al
 // Gaussian block of every matrix from the counter-based generator: which = 0 into y[0] (p x r), 1 into zw[3] (q x r)
 hipError_t launch_gauss_block(const DevCtx& d, int which, uint64_t seed, uint32_t draw, hipStream_t s);
 
+// Dynamic LDS beyond 64 KiB has to be allowed per kernel, and the permission belongs to the device the kernel is loaded
+// on: asked for once per (kernel, device), on the first launch there.
+constexpr int MAX_LDS_DEVICES = 64;
+struct LdsRaised { bool done[MAX_LDS_DEVICES] = {}; };
+inline hipError_t raise_lds(const void* kernel, int bytes, LdsRaised& st) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < MAX_LDS_DEVICES;
+  if (tracked && st.done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  if (tracked) st.done[dev] = true;
+  return hipSuccess;
+}
+
 }  // namespace lordo

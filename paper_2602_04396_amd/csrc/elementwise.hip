@@ -1174,13 +1174,8 @@ size_t jacobi_lds_bytes(int rmax) {
 hipError_t launch_jacobi_svd(const DevCtx& d, int rmax, bool top_value_only, hipStream_t s) {
   if (rmax > 128) return hipErrorInvalidValue;
   const size_t lds = jacobi_lds_bytes(rmax);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_jacobi_svd), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)jacobi_lds_bytes(128));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsRaised raised;
+  if (hipError_t e = raise_lds(reinterpret_cast<const void*>(k_jacobi_svd), (int)jacobi_lds_bytes(128), raised); e != hipSuccess) return e;
   const int threads = rmax > 64 ? 1024 : (rmax > 32 ? 512 : 256);
   hipLaunchKernelGGL(k_jacobi_svd, dim3(d.n), dim3(threads), lds, s, d, top_value_only ? 1 : 0);
   return hipGetLastError();
@@ -1340,12 +1335,8 @@ template <int BW, int CH>
 static hipError_t jsvd_block_sweeps(const DevCtx& d, int rmax, int* flags, int sweeps, int allow, hipStream_t s) {
   constexpr size_t lds = sizeof(float) * 2 * BW * 128 * CH;
   static_assert(lds <= 147456, "two blocks of columns must fit into LDS");
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_jsvd_block<BW, CH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsRaised raised;
+  if (hipError_t e = raise_lds(reinterpret_cast<const void*>(k_jsvd_block<BW, CH>), (int)lds, raised); e != hipSuccess) return e;
   if (rmax > 128 * CH) return hipErrorInvalidValue;
   const int nb = (rmax + BW - 1) / BW, nbe = (nb + 1) & ~1;
   for (int sweep = 0; sweep < sweeps; ++sweep)

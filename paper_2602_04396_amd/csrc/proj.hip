@@ -748,13 +748,8 @@ template <int RB, bool GONCE>
 static hipError_t launch_down_tr(dim3 grid, const DevCtx& d, const ProjTile* tiles, float* glow, int64_t split_stride,
                                  float grad_scale, const FusedAdam& fa, hipStream_t s) {
   constexpr int LDS_BYTES = (RB == 2 ? 3 * 48 : 4 * 32) * 1024;
-  static bool raised = false;
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_down_tr<RB, GONCE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  static LdsRaised raised;
+  if (hipError_t e = raise_lds(reinterpret_cast<const void*>(k_proj_down_tr<RB, GONCE>), LDS_BYTES, raised); e != hipSuccess) return e;
   hipLaunchKernelGGL((k_proj_down_tr<RB, GONCE>), grid, dim3(512), LDS_BYTES, s, d, tiles, glow, split_stride, grad_scale, fa);
   return hipGetLastError();
 }
@@ -765,13 +760,9 @@ template <int RB, bool VEC, bool GONCE, int EF>
 static hipError_t launch_pipe(dim3 grid, const DevCtx& d, const ProjTile* tiles, float* glow, int64_t split_stride,
                               float grad_scale, const FusedAdam& fa, hipStream_t s) {
   constexpr int LDS_BYTES = (RB == 2 ? 98304 : 65536) + (EF != 0 ? 32768 : 0);
-  static bool raised = false;
-  if (LDS_BYTES > 65536 && !raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_proj_down_pipe<RB, VEC, GONCE, EF>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  static LdsRaised raised;
+  if constexpr (LDS_BYTES > 65536)
+    if (hipError_t e = raise_lds(reinterpret_cast<const void*>(k_proj_down_pipe<RB, VEC, GONCE, EF>), LDS_BYTES, raised); e != hipSuccess) return e;
   hipLaunchKernelGGL((k_proj_down_pipe<RB, VEC, GONCE, EF>), grid, dim3(512), LDS_BYTES, s, d, tiles, glow, split_stride, grad_scale, fa);
   return hipGetLastError();
 }
@@ -1492,16 +1483,11 @@ hipError_t launch_proj_up_wide(const DevCtx& d, const ProjTile* tiles, int ntile
                                const UpArgs& ua, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   constexpr int LDS_BYTES = 3 * 24 * 1024;
-  static bool raised = false;
-  if (!raised) {
-    const void* kernels[4] = {reinterpret_cast<const void*>(k_proj_up_wide<false, false>), reinterpret_cast<const void*>(k_proj_up_wide<true, false>),
-                              reinterpret_cast<const void*>(k_proj_up_wide<false, true>), reinterpret_cast<const void*>(k_proj_up_wide<true, true>)};
-    for (const void* k : kernels) {
-      hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-      if (e != hipSuccess) return e;
-    }
-    raised = true;
-  }
+  static LdsRaised raised[4];
+  const void* kernels[4] = {reinterpret_cast<const void*>(k_proj_up_wide<false, false>), reinterpret_cast<const void*>(k_proj_up_wide<true, false>),
+                            reinterpret_cast<const void*>(k_proj_up_wide<false, true>), reinterpret_cast<const void*>(k_proj_up_wide<true, true>)};
+  for (int k = 0; k < 4; ++k)
+    if (hipError_t e = raise_lds(kernels[k], LDS_BYTES, raised[k]); e != hipSuccess) return e;
   const bool with_g = ua.coef_g != 0.f || ua.target_err == 1;
   if (with_g && ua.g_is_f32) return hipErrorInvalidValue;      // the gradient-term epilogue here reads bf16 gradients
   if (ua.target_err == 2 || ua.outer || ua.colscale == 2) return hipErrorInvalidValue;
@@ -1654,12 +1640,8 @@ hipError_t launch_src_times_block(const DevCtx& d, const ProjTile* tiles, int nt
                                   hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   constexpr int LDS_BYTES = 3 * 24 * 1024;
-  static bool raised = false;
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_src_times_block), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  static LdsRaised raised;
+  if (hipError_t e = raise_lds(reinterpret_cast<const void*>(k_src_times_block), LDS_BYTES, raised); e != hipSuccess) return e;
   hipLaunchKernelGGL(k_src_times_block, dim3(ntiles), dim3(256), LDS_BYTES, s, d, tiles, b_hi, b_lo);
   return hipGetLastError();
 }
