@@ -40,6 +40,8 @@
  *     takes effect at the head of the next compute call: do not record that call.  The first
  *     launch of a kernel raises its shared-memory limit with a host-side runtime call, which
  *     a capturing stream does not allow: issue a call once before recording it.
+ *   - A context belongs to the GPU that was current at lordo_init (the arena and the matrices live there): every call
+ *     that enqueues work on it must be made with that GPU current, and returns LORDO_ESTATE otherwise.
  *   - There is no CPU fallback: without a GPU every compute call returns LORDO_EHIP.
  */
 #ifndef LORDO_H

@@ -981,6 +981,13 @@ struct lordo_ctx {
   template <class T>
   T* at(int64_t off) const { return reinterpret_cast<T*>(dev.arena + off); }
 
+  // the arena, the tables in it and the caller's matrices live on the GPU that was current at lordo_init: a call with
+  // another GPU current would launch kernels there on addresses of this one
+  bool on_its_device() const {
+    int cur = -1;
+    return hipGetDevice(&cur) == hipSuccess && cur == device;
+  }
+
   static bool has_null(const void* const* host, int n) {
     for (int i = 0; i < n; ++i)
       if (!host[i]) return true;
@@ -1151,6 +1158,7 @@ int lordo_init_static(lordo_ctx** out, const lordo_shape* shapes, int32_t n, con
 
 int lordo_local_step(lordo_ctx* c, void* const* W, const void* const* G, double lr, double grad_scale, void* stream) {
   if (!c || !W || !G || !std::isfinite(lr) || !std::isfinite(grad_scale)) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   Plan& P = c->plan;
   if (lordo_ctx::has_null(reinterpret_cast<const void* const*>(W), c->n) || lordo_ctx::has_null(G, c->n)) return LORDO_EINVAL;
@@ -1426,6 +1434,7 @@ static int select_omega(lordo_ctx* c, const void* const* Omega, hipStream_t s) {
 
 int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, void* stream) {
   if (!c || !Src) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
   for (int i = 0; i < c->n; ++i)
     if (Omega && Src[i] && !Omega[i]) return LORDO_EINVAL;      // (a matrix that is left out needs no start block)
@@ -1450,6 +1459,7 @@ int lordo_refresh_subspace(lordo_ctx* c, const void* const* Src, int32_t src_dty
 
 int lordo_spectral_gap(lordo_ctx* c, const void* const* Src, int32_t src_dtype, const void* const* Omega, float* dev_out, void* stream) {
   if (!c || !Src || !Omega || !dev_out) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (src_dtype != LORDO_BF16 && src_dtype != LORDO_F32) return LORDO_EINVAL;
   if (!c->hp.rayleigh_ritz || !c->refreshed || c->grad_folded) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
@@ -1470,6 +1480,7 @@ int lordo_spectral_gap(lordo_ctx* c, const void* const* Src, int32_t src_dtype, 
 
 int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad_scale, const void* const* Omega, void* stream) {
   if (!c || !G || !std::isfinite(grad_scale)) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (lordo_ctx::has_null(G, c->n) || (Omega && lordo_ctx::has_null(Omega, c->n))) return LORDO_EINVAL;
   if (c->hp.err_dtype == LORDO_BF16) return LORDO_EINVAL;      // the sum s G + E is formed inside the residual buffer: fp32 only
   if (!c->hp.error_feedback || c->grad_folded) return LORDO_ESTATE;
@@ -1497,6 +1508,7 @@ int lordo_refresh_subspace_local(lordo_ctx* c, const void* const* G, double grad
 
 int lordo_init_projection(lordo_ctx* c, const void* const* Block, void* stream) {
   if (!c) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (Block && lordo_ctx::has_null(Block, c->n)) return LORDO_EINVAL;
   if (c->t != 0 || c->grad_folded) return LORDO_ESTATE;      // the moments would have to be rotated: that is what a refresh does
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
@@ -1513,6 +1525,7 @@ int lordo_init_projection(lordo_ctx* c, const void* const* Block, void* stream) 
 
 int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* DeltaOut, void* stream) {
   if (!c || !W || !DeltaOut) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int rc = c->set_ext(EXT_W, const_cast<void* const*>(reinterpret_cast<const void* const*>(W)), s);
   if (rc != LORDO_OK) return rc;
@@ -1526,6 +1539,7 @@ int lordo_export_pseudograd(lordo_ctx* c, const void* const* W, void* const* Del
 
 int lordo_outer_step(lordo_ctx* c, void* const* W, const void* const* AvgDelta, void* stream) {
   if (!c || !W) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (lordo_ctx::has_null(reinterpret_cast<const void* const*>(W), c->n) || (AvgDelta && lordo_ctx::has_null(AvgDelta, c->n))) return LORDO_EINVAL;
   // this worker's own pseudo-gradient exists only after local steps: none since the last outer step is a caller error
   if (!AvgDelta && c->window_steps == 0) return LORDO_ESTATE;
@@ -1553,6 +1567,7 @@ int lordo_outer_step(lordo_ctx* c, void* const* W, const void* const* AvgDelta, 
 
 int lordo_export_uplink(lordo_ctx* c, void* const* AccOut, void* stream) {
   if (!c || !AccOut) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (!c->hp.uplink_buffer) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int rc = c->set_ext(EXT_DOUT, AccOut, s);
@@ -1578,6 +1593,7 @@ int lordo_sync_payload(lordo_ctx* c, void** dev_ptr, size_t* count, size_t* mome
 
 int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* AvgAcc, void* stream) {
   if (!c || !W) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (!c->hp.uplink_buffer) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   Plan& P = c->plan;
@@ -1651,6 +1667,7 @@ int lordo_outer_step_lowrank(lordo_ctx* c, void* const* W, const void* const* Av
 
 int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, void* stream) {
   if (!c || !dev_dst || mat < 0 || mat >= c->n) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   const MatDev& m = c->plan.mat[mat];
   Plan& P = c->plan;
@@ -1690,6 +1707,7 @@ int lordo_get_state(lordo_ctx* c, int32_t mat, int32_t which, void* dev_dst, voi
 
 int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_src, void* stream) {
   if (!c || !dev_src || mat < 0 || mat >= c->n) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   const MatDev& m = c->plan.mat[mat];
   Plan& P = c->plan;
@@ -1722,6 +1740,7 @@ int lordo_set_state(lordo_ctx* c, int32_t mat, int32_t which, const void* dev_sr
 
 int lordo_get_mssv(lordo_ctx* c, float* dev_out, void* stream) {
   if (!c || !dev_out) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (!c->refreshed) return LORDO_ESTATE;
   HIPCHK(launch_mssv(c->dev, dev_out, reinterpret_cast<hipStream_t>(stream)));
   return LORDO_OK;
@@ -1729,6 +1748,7 @@ int lordo_get_mssv(lordo_ctx* c, float* dev_out, void* stream) {
 
 int lordo_get_stable_rank(lordo_ctx* c, float* dev_out, void* stream) {
   if (!c || !dev_out) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   if (!c->refreshed || !c->hp.rayleigh_ritz) return LORDO_ESTATE;
   HIPCHK(launch_stable_rank(c->dev, dev_out, 0, reinterpret_cast<hipStream_t>(stream)));
   return LORDO_OK;
@@ -1749,6 +1769,7 @@ int lordo_set_step(lordo_ctx* c, int64_t t) {
 
 int lordo_poll_status(lordo_ctx* c, void* stream) {
   if (!c) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   HIPCHK(hipStreamSynchronize(s));
   int32_t flag = 0;
@@ -1770,6 +1791,7 @@ int lordo_profile_enable(lordo_ctx* c, int32_t on) {
 
 int lordo_profile_read(lordo_ctx* c, int32_t kernel_class, double* total_ms, int64_t* launches, void* stream) {
   if (!c || !total_ms || !launches || kernel_class < 0 || kernel_class >= NUM_KCLASS) return LORDO_EINVAL;
+  if (!c->on_its_device()) return LORDO_ESTATE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   HIPCHK(hipStreamSynchronize(s));
   Profiler& pf = c->prof;
