@@ -2,7 +2,8 @@
 bench.py does): c3 (~1B set, 168 matrices, r = 256, Student-t gradients), c4 (~7B set, 224 matrices, r = 512) and
 c5 (one 8192 x 28672 matrix, ranks 64 and 1024).  The float64 oracle follows sampled columns of one matrix per
 distinct shape -- every formula of the local step, of the moment rotation and of the outer step acts column by
-column -- and recomputes the refreshed subspace of those matrices in full with its own range finder."""
+column -- and recomputes the refreshed subspace of those matrices in full with its own range finder.  For the plain
+update the second step is also checked on EVERY element of EVERY matrix against lr Q N from the library's own Q and N."""
 import numpy as np
 import pytest
 
@@ -139,7 +140,41 @@ def _run_model_config(cfg, power_iters, **update):
     picked = distinct + [len(shapes) // 2, len(shapes) - 1]
     sm = Sampled(torch, lordo, opt, shapes, W, picked, ohp, synth.seed_for(int(cfg[1:]), 4242))
     sm.local_step(Wp, Gp[0], G[0], 1e-3, f"{cfg} step 1")
+    # the whole low-rank state after the first step, every matrix: g against Q^T G from the library GEMM (the residual is
+    # zero at this step), and the moments against their closed form from the zero state, u = (1 - beta1) g, v = (1 - beta2) g^2
+    worst_g = 0.0
+    for i in range(len(shapes)):
+        g = opt.get_state(i, lordo.STATE_GLOW)
+        ref = opt.get_state(i, lordo.STATE_Q).T @ G[0][i].float()
+        rms = float(ref.square().mean().sqrt())
+        dev = float((g - ref).abs().max())
+        worst_g = max(worst_g, dev / rms)
+        assert dev <= 1e-3 * rms, f"{cfg} matrix {i} {shapes[i]}: g deviates from Q^T G by {dev:.3e} somewhere (rms {rms:.3e})"
+        u, v = opt.get_state(i, lordo.STATE_U), opt.get_state(i, lordo.STATE_V)
+        assert float((u - (1.0 - ohp.beta1) * g).abs().max()) <= 1e-6 * rms, f"{cfg} matrix {i}: u after the first step"
+        assert float((v - (1.0 - ohp.beta2) * g * g).abs().max()) <= 1e-6 * rms * rms, f"{cfg} matrix {i}: v after the first step"
+    print(f"{cfg}: whole-array check of g, u, v after step 1 over {len(shapes)} matrices, largest deviation of g / its rms {worst_g:.2e}", flush=True)
+    del g, ref, u, v
+    plain = not update
+    W_before = [w.clone() for w in W] if plain else None
     sm.local_step(Wp, Gp[1], G[1], 2e-3, f"{cfg} step 2")
+    if plain:
+        # every element of every matrix: W_before - W = lr Q N, with Q N formed by the library GEMM from the library's own
+        # Q and N (the sampled columns above tie those to the oracle).  A tile written to the wrong place, twice or not at
+        # all, in any of the matrices, is off by the size of the change; fp32 rounding of W is four orders below it.
+        worst = 0.0
+        for i in range(len(shapes)):
+            ref = opt.get_state(i, lordo.STATE_Q) @ opt.get_state(i, lordo.STATE_NUPD)
+            ref *= 2e-3
+            rms = float(ref.square().mean().sqrt())
+            W_before[i] -= W[i]
+            W_before[i] -= ref
+            dev = float(W_before[i].abs().max())
+            worst = max(worst, dev / rms)
+            assert dev <= 2e-2 * rms, f"{cfg} matrix {i} {shapes[i]}: the change deviates from lr Q N by {dev:.3e} somewhere (rms of the change {rms:.3e})"
+            W_before[i] = None
+        print(f"{cfg}: whole-array check of step 2 over {len(shapes)} matrices, largest deviation / rms of the change {worst:.2e}", flush=True)
+        del W_before, ref
     # synchronisation branch of Alg. 1: outer step on the generated averaged pseudo-gradient, new projection from it
     sm.outer_step(Wp, Dp, D, cfg)
     sm.refresh(Dp, Op, power_iters, f"{cfg} refresh from the averaged pseudo-gradient (fp32)", set(distinct))
