@@ -112,6 +112,43 @@ class Sampled:
                 assert rel_l2(self.cols_of(i, lordo.STATE_V), st.v) <= TOL, f"rotated v, {tag}, matrix {i}"
 
 
+def _whole_state_after_first_step(opt, lordo, shapes, G0, ohp, tag):
+    """The whole low-rank state after the first step from the zero state, every matrix: g against Q^T G from the library
+    GEMM (the residual is zero at this step), and the moments against their closed form, u = (1 - beta1) g,
+    v = (1 - beta2) g^2."""
+    worst = 0.0
+    for i in range(len(shapes)):
+        g = opt.get_state(i, lordo.STATE_GLOW)
+        ref = opt.get_state(i, lordo.STATE_Q).T @ G0[i].float()
+        rms = float(ref.square().mean().sqrt())
+        dev = float((g - ref).abs().max())
+        worst = max(worst, dev / rms)
+        assert dev <= 1e-3 * rms, f"{tag} matrix {i} {shapes[i]}: g deviates from Q^T G by {dev:.3e} somewhere (rms {rms:.3e})"
+        u, v = opt.get_state(i, lordo.STATE_U), opt.get_state(i, lordo.STATE_V)
+        assert float((u - (1.0 - ohp.beta1) * g).abs().max()) <= 1e-6 * rms, f"{tag} matrix {i}: u after the first step"
+        assert float((v - (1.0 - ohp.beta2) * g * g).abs().max()) <= 1e-6 * rms * rms, f"{tag} matrix {i}: v after the first step"
+    print(f"{tag}: whole-array check of g, u, v after the first step over {len(shapes)} matrices, largest deviation of g / its rms {worst:.2e}", flush=True)
+
+
+def _whole_weight_change(opt, lordo, shapes, W_before, W, lr, tag):
+    """Every element of every matrix after a step of the plain update: W_before - W = lr Q N, with Q N formed by the library
+    GEMM from the library's own Q and N (the sampled columns tie those to the oracle).  A tile written to the wrong place,
+    twice or not at all, in any of the matrices, is off by the size of the change; fp32 rounding of W is four orders below
+    it.  Consumes W_before."""
+    worst = 0.0
+    for i in range(len(shapes)):
+        ref = opt.get_state(i, lordo.STATE_Q) @ opt.get_state(i, lordo.STATE_NUPD)
+        ref *= lr
+        rms = float(ref.square().mean().sqrt())
+        W_before[i] -= W[i]
+        W_before[i] -= ref
+        dev = float(W_before[i].abs().max())
+        worst = max(worst, dev / rms)
+        assert dev <= 2e-2 * rms, f"{tag} matrix {i} {shapes[i]}: the change deviates from lr Q N by {dev:.3e} somewhere (rms of the change {rms:.3e})"
+        W_before[i] = None
+    print(f"{tag}: whole-array check of the weight change over {len(shapes)} matrices, largest deviation / rms of the change {worst:.2e}", flush=True)
+
+
 def _first_of_each_shape(shapes):
     seen, out = set(), []
     for i, s in enumerate(shapes):
@@ -140,41 +177,12 @@ def _run_model_config(cfg, power_iters, **update):
     picked = distinct + [len(shapes) // 2, len(shapes) - 1]
     sm = Sampled(torch, lordo, opt, shapes, W, picked, ohp, synth.seed_for(int(cfg[1:]), 4242))
     sm.local_step(Wp, Gp[0], G[0], 1e-3, f"{cfg} step 1")
-    # the whole low-rank state after the first step, every matrix: g against Q^T G from the library GEMM (the residual is
-    # zero at this step), and the moments against their closed form from the zero state, u = (1 - beta1) g, v = (1 - beta2) g^2
-    worst_g = 0.0
-    for i in range(len(shapes)):
-        g = opt.get_state(i, lordo.STATE_GLOW)
-        ref = opt.get_state(i, lordo.STATE_Q).T @ G[0][i].float()
-        rms = float(ref.square().mean().sqrt())
-        dev = float((g - ref).abs().max())
-        worst_g = max(worst_g, dev / rms)
-        assert dev <= 1e-3 * rms, f"{cfg} matrix {i} {shapes[i]}: g deviates from Q^T G by {dev:.3e} somewhere (rms {rms:.3e})"
-        u, v = opt.get_state(i, lordo.STATE_U), opt.get_state(i, lordo.STATE_V)
-        assert float((u - (1.0 - ohp.beta1) * g).abs().max()) <= 1e-6 * rms, f"{cfg} matrix {i}: u after the first step"
-        assert float((v - (1.0 - ohp.beta2) * g * g).abs().max()) <= 1e-6 * rms * rms, f"{cfg} matrix {i}: v after the first step"
-    print(f"{cfg}: whole-array check of g, u, v after step 1 over {len(shapes)} matrices, largest deviation of g / its rms {worst_g:.2e}", flush=True)
-    del g, ref, u, v
+    _whole_state_after_first_step(opt, lordo, shapes, G[0], ohp, cfg)
     plain = not update
     W_before = [w.clone() for w in W] if plain else None
     sm.local_step(Wp, Gp[1], G[1], 2e-3, f"{cfg} step 2")
     if plain:
-        # every element of every matrix: W_before - W = lr Q N, with Q N formed by the library GEMM from the library's own
-        # Q and N (the sampled columns above tie those to the oracle).  A tile written to the wrong place, twice or not at
-        # all, in any of the matrices, is off by the size of the change; fp32 rounding of W is four orders below it.
-        worst = 0.0
-        for i in range(len(shapes)):
-            ref = opt.get_state(i, lordo.STATE_Q) @ opt.get_state(i, lordo.STATE_NUPD)
-            ref *= 2e-3
-            rms = float(ref.square().mean().sqrt())
-            W_before[i] -= W[i]
-            W_before[i] -= ref
-            dev = float(W_before[i].abs().max())
-            worst = max(worst, dev / rms)
-            assert dev <= 2e-2 * rms, f"{cfg} matrix {i} {shapes[i]}: the change deviates from lr Q N by {dev:.3e} somewhere (rms of the change {rms:.3e})"
-            W_before[i] = None
-        print(f"{cfg}: whole-array check of step 2 over {len(shapes)} matrices, largest deviation / rms of the change {worst:.2e}", flush=True)
-        del W_before, ref
+        _whole_weight_change(opt, lordo, shapes, W_before, W, 2e-3, cfg)
     # synchronisation branch of Alg. 1: outer step on the generated averaged pseudo-gradient, new projection from it
     sm.outer_step(Wp, Dp, D, cfg)
     sm.refresh(Dp, Op, power_iters, f"{cfg} refresh from the averaged pseudo-gradient (fp32)", set(distinct))
@@ -229,7 +237,10 @@ def test_c5_largest_matrix_rank_sweep_ends(rank, power_iters):
     sm = Sampled(torch, lordo, opt, shapes, W, [0], ohp, synth.seed_for(5, 4242 + rank))
     sm.refresh(Gp[0], Op, power_iters, f"c5 r={rank} q_it={power_iters}", {0})
     sm.local_step(Wp, Gp[1], G[1], 1e-3, f"c5 r={rank} step 1")
+    _whole_state_after_first_step(opt, lordo, shapes, G[1], ohp, f"c5 r={rank}")
+    W_before = [W[0].clone()]
     sm.local_step(Wp, Gp[0], G[0], 2e-3, f"c5 r={rank} step 2")
+    _whole_weight_change(opt, lordo, shapes, W_before, W, 2e-3, f"c5 r={rank}")
     assert torch.isfinite(W[0]).all()
     opt.poll_status()
     opt.close()
