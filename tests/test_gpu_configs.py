@@ -184,7 +184,20 @@ def _run_model_config(cfg, power_iters, **update):
     if plain:
         _whole_weight_change(opt, lordo, shapes, W_before, W, 2e-3, cfg)
     # synchronisation branch of Alg. 1: outer step on the generated averaged pseudo-gradient, new projection from it
+    anchors = [opt.get_state(i, lordo.STATE_ANCHOR) for i in range(len(shapes))]
     sm.outer_step(Wp, Dp, D, cfg)
+    # every element of every matrix: from a zero momentum b' = mu 0 + D and W = anchor - eta_s (D + mu b') (Nesterov), in fp32
+    for i in range(len(shapes)):
+        assert torch.equal(opt.get_state(i, lordo.STATE_MOM), D[i]), f"{cfg} matrix {i}: momentum after the first outer step"
+        ref = anchors[i]
+        ref -= float(ohp.outer_lr * (1.0 + ohp.outer_momentum)) * D[i]
+        dev = float((W[i] - ref).abs().max())
+        scale = float(D[i].abs().max()) * ohp.outer_lr
+        assert dev <= 1e-5 * scale, f"{cfg} matrix {i} {shapes[i]}: outer step off by {dev:.3e} somewhere (largest step {scale:.3e})"
+        assert torch.equal(opt.get_state(i, lordo.STATE_ANCHOR), W[i]), f"{cfg} matrix {i}: anchor after the outer step"
+        anchors[i] = None
+    print(f"{cfg}: whole-array check of the outer step over {len(shapes)} matrices", flush=True)
+    del anchors, ref
     sm.refresh(Dp, Op, power_iters, f"{cfg} refresh from the averaged pseudo-gradient (fp32)", set(distinct))
     sm.local_step(Wp, Gp[0], G[0], 1e-3, f"{cfg} step 3 (after the refresh)")
     for i in picked:
