@@ -199,6 +199,12 @@ def _run_model_config(cfg, power_iters, **update):
     print(f"{cfg}: whole-array check of the outer step over {len(shapes)} matrices", flush=True)
     del anchors, ref
     sm.refresh(Dp, Op, power_iters, f"{cfg} refresh from the averaged pseudo-gradient (fp32)", set(distinct))
+    worst = 0.0
+    for i, (p_, q_, r_) in enumerate(shapes):          # every refreshed basis, not only the sampled matrices
+        Qi = opt.get_state(i, lordo.STATE_Q)
+        worst = max(worst, float(torch.linalg.norm(Qi.T @ Qi - torch.eye(r_, device=Qi.device))))
+    print(f"{cfg}: orthonormality of all {len(shapes)} refreshed bases, largest ||Q^T Q - I||_F {worst:.2e}", flush=True)
+    assert worst <= TOL_ORTH
     sm.local_step(Wp, Gp[0], G[0], 1e-3, f"{cfg} step 3 (after the refresh)")
     for i in picked:
         assert torch.isfinite(W[i]).all()
