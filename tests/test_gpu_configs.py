@@ -149,6 +149,43 @@ def _whole_weight_change(opt, lordo, shapes, W_before, W, lr, tag):
     print(f"{tag}: whole-array check of the weight change over {len(shapes)} matrices, largest deviation / rms of the change {worst:.2e}", flush=True)
 
 
+def _whole_residual(opt, lordo, shapes, G_t, E_prev, tag):
+    """Every element of every residual after a step (Alg. 1 error-feedback lines): E = G + E_prev - Q g, with Q g formed by
+    the library GEMM from the library's own Q and g; E_prev None = the zero residual of the first step."""
+    worst = 0.0
+    for i in range(len(shapes)):
+        ref = G_t[i].float()
+        if E_prev is not None:
+            ref += E_prev[i]
+        scale = float(ref.square().mean().sqrt())
+        ref -= opt.get_state(i, lordo.STATE_Q) @ opt.get_state(i, lordo.STATE_GLOW)
+        dev = float((opt.get_state(i, lordo.STATE_ERR) - ref).abs().max())
+        worst = max(worst, dev / scale)
+        assert dev <= 1e-3 * scale, f"{tag} matrix {i} {shapes[i]}: the residual deviates from G + E - Q g by {dev:.3e} somewhere (rms of G + E {scale:.3e})"
+    print(f"{tag}: whole-array check of the residual over {len(shapes)} matrices, largest deviation / rms of G + E {worst:.2e}", flush=True)
+
+
+def _whole_weight_change_full_qhm(opt, lordo, shapes, W_before, W, G_t, lr, ohp, t, tag):
+    """Every element of every matrix after step t of the full-rank QHM update (Sec. 3.2; Alg. 1 "Full-Rank QHM"):
+    W_before - W = lr [omega Q N + (1 - omega) G diag(1 / s)], s_j = mean over the rank of sqrt(v_hat_kj) + eps, from the
+    library's own Q, N and v.  Consumes W_before."""
+    worst = 0.0
+    c2 = 1.0 - ohp.beta2 ** t if ohp.bias_correction else 1.0
+    for i in range(len(shapes)):
+        s_col = ((opt.get_state(i, lordo.STATE_V) / c2).sqrt() + ohp.eps).mean(dim=0)
+        ref = opt.get_state(i, lordo.STATE_Q) @ opt.get_state(i, lordo.STATE_NUPD)
+        ref *= lr * ohp.omega
+        ref += (lr * (1.0 - ohp.omega)) * (G_t[i].float() / s_col[None, :])
+        rms = float(ref.square().mean().sqrt())
+        W_before[i] -= W[i]
+        W_before[i] -= ref
+        dev = float(W_before[i].abs().max())
+        worst = max(worst, dev / rms)
+        assert dev <= 2e-2 * rms, f"{tag} matrix {i} {shapes[i]}: the change deviates from the full-rank QHM update by {dev:.3e} somewhere (rms {rms:.3e})"
+        W_before[i] = None
+    print(f"{tag}: whole-array check of the full-rank QHM weight change over {len(shapes)} matrices, largest deviation / rms {worst:.2e}", flush=True)
+
+
 def _first_of_each_shape(shapes):
     seen, out = set(), []
     for i, s in enumerate(shapes):
@@ -178,11 +215,20 @@ def _run_model_config(cfg, power_iters, **update):
     sm = Sampled(torch, lordo, opt, shapes, W, picked, ohp, synth.seed_for(int(cfg[1:]), 4242))
     sm.local_step(Wp, Gp[0], G[0], 1e-3, f"{cfg} step 1")
     _whole_state_after_first_step(opt, lordo, shapes, G[0], ohp, cfg)
-    plain = not update
-    W_before = [w.clone() for w in W] if plain else None
+    ef, full = bool(update.get("error_feedback")), update.get("qhm_mode") == "full"
+    plain = not full                   # (the low-rank QHM bracket is inside N: the weight change is lr Q N as well)
+    if ef:
+        _whole_residual(opt, lordo, shapes, G[0], None, f"{cfg} step 1")
+    E_before = [opt.get_state(i, lordo.STATE_ERR) for i in range(len(shapes))] if ef else None
+    W_before = [w.clone() for w in W] if plain or full else None
     sm.local_step(Wp, Gp[1], G[1], 2e-3, f"{cfg} step 2")
     if plain:
         _whole_weight_change(opt, lordo, shapes, W_before, W, 2e-3, cfg)
+    if full:
+        _whole_weight_change_full_qhm(opt, lordo, shapes, W_before, W, G[1], 2e-3, ohp, 2, f"{cfg} step 2")
+    if ef:
+        _whole_residual(opt, lordo, shapes, G[1], E_before, f"{cfg} step 2")
+    del E_before, W_before
     # synchronisation branch of Alg. 1: outer step on the generated averaged pseudo-gradient, new projection from it
     anchors = [opt.get_state(i, lordo.STATE_ANCHOR) for i in range(len(shapes))]
     sm.outer_step(Wp, Dp, D, cfg)
