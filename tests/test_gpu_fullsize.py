@@ -366,8 +366,20 @@ def test_c2_full_size_short_side_sampled_rows():
 
     for step, lr in enumerate([1e-3, 2e-3]):
         W_before = {i: sub(W[i], i) for i in picked}
+        W_all = [w.clone() for w in W]
         opt.local_step(Wp, Gp[1 + step], lr)
         torch.cuda.synchronize()
+        # every element of every matrix: the change is lr Q N (left) or lr N^T Q^T (right) of the library's own Q and N
+        worst = 0.0
+        for i in range(len(shapes)):
+            Qd, Nd = opt.get_state(i, lordo.STATE_Q), opt.get_state(i, lordo.STATE_NUPD)
+            ref = lr * (Nd.T @ Qd.T if i in tall else Qd @ Nd)
+            rms = float(ref.square().mean().sqrt())
+            dev = float((W_all[i] - W[i] - ref).abs().max())
+            worst = max(worst, dev / rms)
+            assert dev <= 2e-2 * rms, f"matrix {i} {lib_shapes[i]}, step {step}: the change deviates from the up-projection of N by {dev:.3e} somewhere (rms {rms:.3e})"
+        print(f"c2 short side, step {step}: whole-array check of the weight change over {len(shapes)} matrices, largest deviation / rms {worst:.2e}", flush=True)
+        del W_all
         for i in picked:
             sm = sample[i]
             st, Q = sm["st"], sm["Q"]
