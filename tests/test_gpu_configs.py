@@ -186,6 +186,28 @@ def _whole_weight_change_full_qhm(opt, lordo, shapes, W_before, W, G_t, lr, ohp,
     print(f"{tag}: whole-array check of the full-rank QHM weight change over {len(shapes)} matrices, largest deviation / rms {worst:.2e}", flush=True)
 
 
+def _whole_rotation(opt, lordo, shapes, old, t, ohp, tag):
+    """Every element of every moment array after a refresh (Alg. 1, rotation of the moments): with R = Q_new^T Q_old from
+    the library's own bases, u = R u_old and v = c2 |(R o R)(v_hat - u_hat^2) + (R u_hat)^2|, evaluated in fp32 by the
+    library GEMM; `old` holds (Q, u, v) of every matrix from before the refresh."""
+    c1 = 1.0 - ohp.beta1 ** t if ohp.bias_correction else 1.0
+    c2 = 1.0 - ohp.beta2 ** t if ohp.bias_correction else 1.0
+    worst = 0.0
+    for i in range(len(shapes)):
+        Q_old, u_old, v_old = old[i]
+        R = opt.get_state(i, lordo.STATE_Q).T @ Q_old
+        u_hat = u_old / c1
+        Ru = R @ u_hat
+        v_ref = c2 * ((R * R) @ (v_old / c2 - u_hat * u_hat) + Ru * Ru).abs()
+        u_ref = R @ u_old
+        du = float((opt.get_state(i, lordo.STATE_U) - u_ref).abs().max()) / float(u_ref.square().mean().sqrt())
+        dv = float((opt.get_state(i, lordo.STATE_V) - v_ref).abs().max()) / float(v_ref.square().mean().sqrt())
+        worst = max(worst, du, dv)
+        assert du <= 1e-3 and dv <= 1e-3, f"{tag} matrix {i} {shapes[i]}: rotated moments deviate by {du:.3e} (u), {dv:.3e} (v) of their rms somewhere"
+        old[i] = None
+    print(f"{tag}: whole-array check of the rotated moments over {len(shapes)} matrices, largest deviation / rms {worst:.2e}", flush=True)
+
+
 def _first_of_each_shape(shapes):
     seen, out = set(), []
     for i, s in enumerate(shapes):
@@ -244,7 +266,10 @@ def _run_model_config(cfg, power_iters, **update):
         anchors[i] = None
     print(f"{cfg}: whole-array check of the outer step over {len(shapes)} matrices", flush=True)
     del anchors, ref
+    old = [(opt.get_state(i, lordo.STATE_Q), opt.get_state(i, lordo.STATE_U), opt.get_state(i, lordo.STATE_V)) for i in range(len(shapes))]
     sm.refresh(Dp, Op, power_iters, f"{cfg} refresh from the averaged pseudo-gradient (fp32)", set(distinct))
+    _whole_rotation(opt, lordo, shapes, old, 2, ohp, cfg)
+    del old
     worst = 0.0
     for i, (p_, q_, r_) in enumerate(shapes):          # every refreshed basis, not only the sampled matrices
         Qi = opt.get_state(i, lordo.STATE_Q)
