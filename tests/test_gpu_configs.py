@@ -208,6 +208,26 @@ def _whole_rotation(opt, lordo, shapes, old, t, ohp, tag):
     print(f"{tag}: whole-array check of the rotated moments over {len(shapes)} matrices, largest deviation / rms {worst:.2e}", flush=True)
 
 
+def _whole_subspace(opt, lordo, shapes, Src, Omega, power_iters, tag):
+    """The refreshed subspace of EVERY matrix against the same range finder (Sec. 2 ComputeProjection as block power
+    iteration) run in fp32 with the library QR and GEMM of torch on the same source and start block: projector distance."""
+    import torch
+    worst = 0.0
+    for i, (p, q, r) in enumerate(shapes):
+        A = Src[i].float()
+        Y = torch.linalg.qr(A @ Omega[i]).Q
+        for _ in range(power_iters):
+            Z = torch.linalg.qr(A.T @ Y).Q
+            Y = torch.linalg.qr(A @ Z).Q
+        Ql = opt.get_state(i, lordo.STATE_Q)
+        # || Y Y^T - Q Q^T ||_F = sqrt(2) || (I - Y Y^T) Q ||_F for two orthonormal bases of equal rank (the form that does
+        # not cancel in fp32)
+        dist = float(2.0 ** 0.5 * torch.linalg.norm(Ql - Y @ (Y.T @ Ql)))
+        worst = max(worst, dist)
+        assert dist <= TOL_SUBSPACE, f"{tag} matrix {i} {shapes[i]}: projector distance {dist:.3e} to the fp32 range finder of torch"
+    print(f"{tag}: subspace of all {len(shapes)} matrices against torch's fp32 range finder, largest projector distance {worst:.2e}", flush=True)
+
+
 def _first_of_each_shape(shapes):
     seen, out = set(), []
     for i, s in enumerate(shapes):
@@ -269,6 +289,7 @@ def _run_model_config(cfg, power_iters, **update):
     old = [(opt.get_state(i, lordo.STATE_Q), opt.get_state(i, lordo.STATE_U), opt.get_state(i, lordo.STATE_V)) for i in range(len(shapes))]
     sm.refresh(Dp, Op, power_iters, f"{cfg} refresh from the averaged pseudo-gradient (fp32)", set(distinct))
     _whole_rotation(opt, lordo, shapes, old, 2, ohp, cfg)
+    _whole_subspace(opt, lordo, shapes, D, Omega, power_iters, cfg)
     del old
     worst = 0.0
     for i, (p_, q_, r_) in enumerate(shapes):          # every refreshed basis, not only the sampled matrices
