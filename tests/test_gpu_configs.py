@@ -395,8 +395,28 @@ def test_c4_lordo_global_with_bf16_storage_sampled_columns():
             E_prev[i] = _f64(opt.get_state(i, lordo.STATE_ERR))[:, cols]
             assert np.array_equal(orc.round_to_bf16(E_prev[i]), E_prev[i]), "the stored residual is not bf16"
             st.E = E_prev[i].copy()
+        W_all = [w.clone() for w in W] if t == 1 else None
         opt.local_step(Wp, Gp[t % 2], lr)
         torch.cuda.synchronize()
+        if t == 1:
+            # every stored weight of every matrix is the fp32 update of the stored value rounded once: within half a bf16
+            # unit of the update formed by the library GEMM from the library's own Q, N and v (plus the fp32 slack of that sum)
+            c2 = 1.0 - ohp.beta2 ** 2
+            worst = 0.0
+            for i in range(len(shapes)):
+                s_col = ((opt.get_state(i, lordo.STATE_V) / c2).sqrt() + ohp.eps).mean(dim=0)
+                upd = opt.get_state(i, lordo.STATE_Q) @ opt.get_state(i, lordo.STATE_NUPD)
+                upd *= lr * ohp.omega
+                upd += (lr * (1.0 - ohp.omega)) * (G[t % 2][i].float() / s_col[None, :])
+                rms = float(upd.square().mean().sqrt())
+                full = W_all[i].float() - upd
+                ulp = torch.exp2(torch.frexp(full).exponent.float() - 8.0)        # spacing of bf16 at |full|
+                over = (W[i].float() - full).abs() - 0.5 * ulp
+                worst = max(worst, float(over.max()) / rms)
+                assert float(over.max()) <= 1e-3 * rms, f"c4 bf16 storage matrix {i} {shapes[i]}: a stored weight is {float(over.max()):.3e} beyond half a unit (rms of the update {rms:.3e})"
+                W_all[i] = None
+            print(f"c4 global bf16 storage: every weight of {len(shapes)} matrices within half a bf16 unit of the fp32 update, largest excess / rms of the update {worst:.2e}", flush=True)
+            del W_all, upd, full, ulp, over
         for i in picked:
             cols, st = state[i]
             Gc = _f64(G[t % 2][i][:, cols])
